@@ -1,0 +1,185 @@
+/*
+ * som.h - C ABI of libsom: batch-mode self-organizing-map training on one AMD MI355X (gfx950).
+ *
+ * The library implements the data-parallel hot path of the batch SOM the paper describes
+ * (section "Self-organizing maps in batch mode"): one training epoch = best-matching-unit
+ * search + batch code-book update, plus cooling schedules and the U-matrix.  The paper's
+ * own entry point is the single function `trainOneEpoch` (section "As an application
+ * programming interface"); the calls below split it into an init call that fixes the map
+ * geometry, one-epoch calls for dense and sparse data, a whole-schedule call, and the
+ * U-matrix.
+ *
+ * Conventions shared by every call
+ *   - Every array pointer is a DEVICE pointer to memory the CALLER owns (for instance a
+ *     torch tensor's data_ptr()); the library borrows it for the duration of the call's
+ *     work on the stream and never frees it.  The library owns only the scratch memory
+ *     inside `som_ctx`, which it allocates with hipMalloc and grows on demand.
+ *   - All work is enqueued on the HIP stream given to som_init (NULL = the default
+ *     stream) and is asynchronous: outputs are valid once that stream has been
+ *     synchronised.  No call synchronises unless its description says so.
+ *   - Node index i = y * cols + x, x = column in 0..cols-1, y = row in 0..rows-1
+ *     (options -x/-y of the paper's command line).  The code book is node-major
+ *     [rows*cols][dim], fp32, as in the paper's API (`float *codebook`).
+ *   - Every call returns a status (SOM_OK = 0).  On SOM_ERR_INVALID_ARG nothing has been
+ *     written or enqueued.  som_last_error gives a human-readable message.
+ *   - A context is used by one host thread at a time.
+ */
+#ifndef SOM_H
+#define SOM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct som_ctx som_ctx;
+
+enum { SOM_OK = 0, SOM_ERR_INVALID_ARG = 1, SOM_ERR_ALLOC = 2, SOM_ERR_DEVICE = 3, SOM_ERR_STATE = 4 };
+enum { SOM_MAP_PLANAR = 0, SOM_MAP_TOROID = 1 };          /* option -m: planar (default) or toroid   */
+enum { SOM_GRID_SQUARE = 0, SOM_GRID_HEXAGONAL = 1 };     /* option -g: square (default) or hexagonal */
+enum { SOM_COOL_LINEAR = 0, SOM_COOL_EXPONENTIAL = 1 };   /* options -t / -T                          */
+
+/* Neighbourhood mass below which a node keeps its weights (see som_train_epoch_dense). */
+#define SOM_EPS_MASS 1e-20
+
+/*
+ * som_init - create a context for a rows x cols map over dim-dimensional data.
+ * (Paper: options -x, -y, -g, -m, -c; "The default is random initialization".)
+ *   out        host pointer that receives the context.
+ *   codebook   device [rows*cols][dim] fp32.  seed == 0: left as the caller filled it
+ *              (option -c, initial code book).  seed != 0: overwritten with uniform [0,1)
+ *              values drawn from a counter-based generator keyed by (seed, element index).
+ *   hip_stream hipStream_t cast to void*, or NULL for the default stream.
+ * Errors: rows, cols or dim < 1, rows*cols > 2^24, unknown enum, NULL pointers ->
+ * SOM_ERR_INVALID_ARG; scratch allocation failure -> SOM_ERR_ALLOC.
+ */
+int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_type,
+             float *codebook, uint64_t seed, void *hip_stream);
+
+/* Release the context and its scratch memory (synchronises the stream first). */
+void som_destroy(som_ctx *ctx);
+
+/* Message of the last failing call on ctx; ctx == NULL: of the last failing som_init. */
+const char *som_last_error(const som_ctx *ctx);
+
+/*
+ * som_train_epoch_dense - one epoch on dense data.
+ * (Paper: BMU equation; batch equation; neighbourhood equation read as
+ *  h = exp(-d^2 / (2 radius^2)) with d the grid distance between two nodes.)
+ *   data      device [n][dim] fp32, row-major (the paper's `float *data`), read only.
+ *   codebook  device [rows*cols][dim] fp32, in: current weights, out: updated weights.
+ *   radius    > 0, neighbourhood radius of this epoch (already cooled).
+ *   scale     learning rate of this epoch, 0 < scale <= 1.  It multiplies numerator and
+ *             denominator of the batch equation alike and therefore has no effect on the
+ *             result; it is validated and otherwise ignored.
+ *   bmus      device [n] int32 out: for each instance the node nearest (Euclidean) to it
+ *             in the INCOMING code book; exact ties go to the lowest node index.
+ * Update: w_i <- sum_j h(bmu_j, i) x_j / sum_j h(bmu_j, i); a node whose denominator is
+ * below SOM_EPS_MASS keeps its weights.  Square grid: unit spacing.  Hexagonal grid: odd
+ * rows shifted right by half a cell, row pitch sqrt(3)/2.  Toroid: distances wrap in both
+ * directions (a hexagonal torus is seamless only for an even number of rows).
+ * Errors: NULL pointer, n < 1, n >= 2^31, radius <= 0 or not finite, scale outside (0,1]
+ * -> SOM_ERR_INVALID_ARG; scratch growth failure -> SOM_ERR_ALLOC; launch failure ->
+ * SOM_ERR_DEVICE.
+ */
+int som_train_epoch_dense(som_ctx *ctx, const float *data, int64_t n, float *codebook,
+                          float radius, float scale, int32_t *bmus);
+
+/*
+ * som_train_epoch_csr - the same epoch on sparse rows in CSR form.
+ * (Paper: sparse kernel; sparse file format with zero-based index:value pairs.)
+ *   indptr    device [n+1] int64, indptr[0] = 0, non-decreasing, indptr[n] = nnz.
+ *   indices   device [nnz] int32, zero-based column indices in 0..dim-1, strictly
+ *             increasing within a row.
+ *   values    device [nnz] fp32.
+ * Unlisted coordinates are zero; an empty row is legal (its BMU is the node of smallest
+ * norm).  The code book stays dense.  CSR structure is NOT validated on the device: rows
+ * that violate the contract give undefined results (indices are still clamped so that no
+ * access leaves the code book).  Other arguments, outputs and errors as for the dense call;
+ * nnz < 0 or nnz >= 2^31 -> SOM_ERR_INVALID_ARG.
+ * The per-node sums of this call are accumulated with fp32 atomic adds, so the last bits
+ * of the new code book may vary from run to run; the BMUs do not.
+ */
+int som_train_epoch_csr(som_ctx *ctx, const int64_t *indptr, const int32_t *indices,
+                        const float *values, int64_t n, int64_t nnz, float *codebook,
+                        float radius, float scale, int32_t *bmus);
+
+/*
+ * som_bmus_dense / som_bmus_csr - BMU search only (BMU equation), code book unchanged:
+ * the mapping of data onto a trained map.  Arguments as in the epoch calls.
+ */
+int som_bmus_dense(som_ctx *ctx, const float *data, int64_t n, const float *codebook, int32_t *bmus);
+int som_bmus_csr(som_ctx *ctx, const int64_t *indptr, const int32_t *indices, const float *values,
+                 int64_t n, int64_t nnz, const float *codebook, int32_t *bmus);
+
+/*
+ * som_update_dense / som_update_csr - the batch update alone (batch equation) for given
+ * BMUs: per-node sums of the instances, neighbourhood smoothing over the map, division.
+ *   bmus  device [n] int32, each in 0..rows*cols-1, read only (values outside that range
+ *         give undefined results but no out-of-bounds access: they are clamped).
+ * Other arguments as in the epoch calls.
+ */
+int som_update_dense(som_ctx *ctx, const float *data, int64_t n, const int32_t *bmus,
+                     float *codebook, float radius, float scale);
+int som_update_csr(som_ctx *ctx, const int64_t *indptr, const int32_t *indices, const float *values,
+                   int64_t n, int64_t nnz, const int32_t *bmus, float *codebook,
+                   float radius, float scale);
+
+/*
+ * som_set_data_dense / som_set_data_csr - register the training set som_train works on.
+ * The pointers are borrowed until the next som_set_data_* or som_destroy; the data must
+ * stay unchanged meanwhile.  Arguments as in the epoch calls.
+ */
+int som_set_data_dense(som_ctx *ctx, const float *data, int64_t n);
+int som_set_data_csr(som_ctx *ctx, const int64_t *indptr, const int32_t *indices,
+                     const float *values, int64_t n, int64_t nnz);
+
+/*
+ * som_train - n_epochs epochs on the registered data with cooled radius and scale, all
+ * enqueued without any host synchronisation; the schedule is evaluated on the device.
+ * (Paper: options -e, -r/-R, -l/-L, -t/-T.)
+ *   Epoch e = 0..n_epochs-1 uses v_e = v0 + (vN - v0) e / (n_epochs-1) (linear) or
+ *   v_e = v0 (vN / v0)^(e / (n_epochs-1)) (exponential); one epoch uses v0.
+ *   radius0 <= 0: default, half the smaller map side (at least 1); radiusN <= 0: 1.
+ *   scale0 <= 0: 1.0; scaleN <= 0: 0.01 (the paper's defaults).
+ *   cooling   SOM_COOL_*, applied to radius and scale alike.
+ *   codebook  device, in/out as in the epoch calls.
+ *   bmus      device [n] int32 out: BMUs found in the LAST epoch (against the code book
+ *             that entered it).
+ * Errors: no data registered -> SOM_ERR_STATE; n_epochs < 1 or bad enum -> SOM_ERR_INVALID_ARG.
+ */
+int som_train(som_ctx *ctx, int n_epochs, float radius0, float radiusN, float scale0,
+              float scaleN, int cooling, float *codebook, int32_t *bmus);
+
+/*
+ * som_cool_schedule - evaluate the cooling schedule of som_train on the device.
+ *   radius_out, scale_out  device [n_epochs] fp64 out (either may be NULL).
+ * Defaults and formulas as in som_train.
+ */
+int som_cool_schedule(som_ctx *ctx, int n_epochs, float radius0, float radiusN, float scale0,
+                      float scaleN, int cooling, double *radius_out, double *scale_out);
+
+/*
+ * som_umatrix - U-matrix of a code book (U-matrix equation): for every node the mean
+ * Euclidean distance between its weight vector and those of its immediate neighbours
+ * (grid distance <= 1: up to 4 on a square grid, up to 6 on a hexagonal one; fewer on the
+ * border of a planar map; a node without neighbours gets 0).
+ *   codebook  device [rows*cols][dim] fp32, read only.
+ *   umatrix   device [rows][cols] fp32 out.
+ */
+int som_umatrix(som_ctx *ctx, const float *codebook, float *umatrix);
+
+/*
+ * som_get_stats - counters of the most recent BMU search on ctx (synchronises the stream).
+ *   rows_refined   instances whose fp32 scores left more than one candidate node and were
+ *                  decided by exact fp64 distances of the candidates;
+ *   rows_rescanned instances that needed an exact fp64 scan of all nodes.
+ * out is a HOST pointer to two int64 values, in that order.
+ */
+int som_get_stats(som_ctx *ctx, int64_t *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SOM_H */

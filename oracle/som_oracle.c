@@ -213,12 +213,36 @@ void oracle_accumulate_csr(const int64_t *indptr, const int32_t *indices, const 
 }
 
 /*
- * New code book from the per-node sums.  `scale` (the learning rate the API
- * carries) multiplies the neighbourhood weight in numerator and denominator
- * alike, exactly as a constant factor on h would in the batch equation, and so
- * cancels.  A node whose unscaled neighbourhood mass D is below eps_mass keeps
- * its weights (no instance influences it).  D_out (may be NULL) receives D.
- * W is read and written in place: node i's new vector depends on S and C only.
+ * New weight vector of one node from the per-node sums.  `scale` (the learning rate the API
+ * carries) multiplies the neighbourhood weight in numerator and denominator alike, exactly
+ * as a constant factor on h would in the batch equation, and so cancels.  A node whose
+ * unscaled neighbourhood mass D is below eps_mass keeps its weights (no instance
+ * influences it).  `w` is node i's own weight vector (in/out).  Returns D.  `num` is scratch
+ * of dim doubles.
+ */
+static double update_node(int i, const double *S, const double *C, float *w, int rows, int cols,
+                          int dim, int map_type, int grid_type, double radius, double scale,
+                          double eps_mass, double *num)
+{
+    int k = rows * cols;
+    double den = 0.0, mass = 0.0;
+    for (int c = 0; c < dim; ++c) num[c] = 0.0;
+    for (int b = 0; b < k; ++b) {
+        if (C[b] == 0.0) continue;          /* contributes exact zeros */
+        double h = oracle_neighbourhood(rows, cols, map_type, grid_type, i, b, radius);
+        const double *s = S + (int64_t)b * dim;
+        mass += h * C[b];
+        den += scale * h * C[b];
+        for (int c = 0; c < dim; ++c) num[c] += scale * h * s[c];
+    }
+    if (mass >= eps_mass)
+        for (int c = 0; c < dim; ++c) w[c] = (float)(num[c] / den);
+    return mass;
+}
+
+/*
+ * New code book for all nodes.  D_out (may be NULL) receives the masses.  W is read and
+ * written in place: node i's new vector depends on S and C only.
  */
 void oracle_update(const double *S, const double *C, float *W, int rows, int cols, int dim,
                    int map_type, int grid_type, double radius, double scale,
@@ -230,23 +254,39 @@ void oracle_update(const double *S, const double *C, float *W, int rows, int col
         double *num = (double *)malloc(sizeof(double) * (size_t)dim);
 #pragma omp for schedule(dynamic, 4)
         for (int i = 0; i < k; ++i) {
-            double den = 0.0, mass = 0.0;
-            for (int c = 0; c < dim; ++c) num[c] = 0.0;
-            for (int b = 0; b < k; ++b) {
-                if (C[b] == 0.0) continue;          /* contributes exact zeros */
-                double h = oracle_neighbourhood(rows, cols, map_type, grid_type, i, b, radius);
-                const double *s = S + (int64_t)b * dim;
-                mass += h * C[b];
-                den += scale * h * C[b];
-                for (int c = 0; c < dim; ++c) num[c] += scale * h * s[c];
-            }
+            double mass = update_node(i, S, C, W + (int64_t)i * dim, rows, cols, dim, map_type,
+                                      grid_type, radius, scale, eps_mass, num);
             if (D_out) D_out[i] = mass;
-            if (mass >= eps_mass) {
-                float *w = W + (int64_t)i * dim;
-                for (int c = 0; c < dim; ++c) w[c] = (float)(num[c] / den);
-            }
         }
         free(num);
+    }
+}
+
+/*
+ * The same for a chosen subset of nodes (sampled checks on maps too large to update whole):
+ * W_out[t] receives the new vector of node nodes[t] (or its old vector from W if its mass is
+ * below eps_mass), D_out[t] its mass.  W itself is not modified.
+ */
+void oracle_update_nodes(const double *S, const double *C, const float *W, int rows, int cols,
+                         int dim, int map_type, int grid_type, double radius, double scale,
+                         double eps_mass, const int32_t *nodes, int n_nodes, float *W_out,
+                         double *D_out)
+{
+#pragma omp parallel
+    {
+        double *num = (double *)malloc(sizeof(double) * (size_t)dim);
+        float *row = (float *)malloc(sizeof(float) * (size_t)dim);
+#pragma omp for schedule(dynamic, 1)
+        for (int t = 0; t < n_nodes; ++t) {
+            int i = nodes[t];
+            memcpy(row, W + (int64_t)i * dim, sizeof(float) * (size_t)dim);
+            double mass = update_node(i, S, C, row, rows, cols, dim, map_type, grid_type, radius,
+                                      scale, eps_mass, num);
+            memcpy(W_out + (int64_t)t * dim, row, sizeof(float) * (size_t)dim);
+            if (D_out) D_out[t] = mass;
+        }
+        free(num);
+        free(row);
     }
 }
 

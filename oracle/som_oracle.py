@@ -51,6 +51,9 @@ def lib():
         L.oracle_update.restype = None
         L.oracle_update.argtypes = [f64p, f64p, f32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                     C.c_double, C.c_double, C.c_double, f64p]
+        L.oracle_update_nodes.restype = None
+        L.oracle_update_nodes.argtypes = [f64p, f64p, f32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                          C.c_double, C.c_double, C.c_double, i32p, C.c_int, f32p, f64p]
         L.oracle_epoch_dense.restype = C.c_int
         L.oracle_epoch_dense.argtypes = [f32p, C.c_int64, C.c_int, f32p, C.c_int, C.c_int, C.c_int,
                                          C.c_int, C.c_double, C.c_double, C.c_double, i32p]
@@ -174,6 +177,23 @@ def update(S, Cn, W, rows: int, cols: int, map_type: int, grid_type: int, radius
                         map_type, grid_type, float(radius), float(scale), float(eps_mass),
                         _p(D, C.c_double))
     return Wn, D
+
+
+def update_nodes(S, Cn, W, rows: int, cols: int, map_type: int, grid_type: int, radius: float, nodes,
+                 scale: float = 1.0, eps_mass: float = EPS_MASS):
+    """New vectors and masses of the listed nodes only: (float32 [len(nodes), dim], float64 [len(nodes)])."""
+    S = np.ascontiguousarray(S, dtype=np.float64)
+    Cn = np.ascontiguousarray(Cn, dtype=np.float64)
+    W = _f32(W)
+    nodes = np.ascontiguousarray(nodes, dtype=np.int32)
+    k, dim = W.shape
+    assert k == rows * cols and S.shape == (k, dim) and Cn.shape == (k,)
+    out = np.empty((nodes.shape[0], dim), dtype=np.float32)
+    D = np.empty(nodes.shape[0], dtype=np.float64)
+    lib().oracle_update_nodes(_p(S, C.c_double), _p(Cn, C.c_double), _p(W, C.c_float), rows, cols, dim,
+                              map_type, grid_type, float(radius), float(scale), float(eps_mass),
+                              _p(nodes, C.c_int32), nodes.shape[0], _p(out, C.c_float), _p(D, C.c_double))
+    return out, D
 
 
 def epoch_dense(X, W, rows, cols, map_type, grid_type, radius, scale=1.0, eps_mass=EPS_MASS):

@@ -1,0 +1,178 @@
+// Sparse best-matching-unit search, fp32 pass (paper: sparse kernel - the code book stays
+// dense while the data are index:value lists; BMU equation).
+//
+// For a CSR row x the scores of all nodes are s_i = |w_i|^2 - 2 sum_nz v * W[i][c].  The code
+// book is first transposed to Wt[dim][kpad] so that one nonzero (c, v) touches one contiguous
+// row of Wt: a workgroup owns an instance, its 256 threads own nodes t, t+256, ... and every
+// nonzero is one coalesced sweep over the node range with v broadcast from LDS.  The scores of
+// an instance never leave registers.
+//
+// As in the dense path the fp32 scores only filter: the workgroup finds the minimum, then the
+// nodes whose score lies within the rounding-error bound of it.  One such node: decided.  Up to
+// kCand: handed to the exact refine pass.  More: the instance is rescanned exactly.
+#include "som_internal.hpp"
+
+#include <math.h>
+
+namespace som {
+
+// ---------------------------------------------------------------- transpose
+__global__ __launch_bounds__(256) void k_transpose(const float *__restrict__ W, int k, int dim, int kpad,
+                                                   float *__restrict__ Wt) {
+  __shared__ float tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;       // 32 x 8
+  const int c0 = blockIdx.x * 32, i0 = blockIdx.y * 32;
+  for (int r = ty; r < 32; r += 8) {
+    const int i = i0 + r, c = c0 + tx;
+    tile[r][tx] = (i < k && c < dim) ? W[(int64_t)i * dim + c] : 0.f;
+  }
+  __syncthreads();
+  for (int r = ty; r < 32; r += 8) {
+    const int c = c0 + r, i = i0 + tx;
+    if (c < dim && i < kpad) Wt[(int64_t)c * kpad + i] = tile[tx][r];
+  }
+}
+
+__device__ __forceinline__ double csr_margin(double len, double xnorm2, double wmax2) {
+  const double u = 5.9604644775390625e-08;   // 2^-24
+  const double xn = sqrt(xnorm2 * (1.0 + 1.2e-7));
+  const double wm = sqrt(wmax2 * (1.0 + 1.2e-7));
+  const double g = len < 1.0 ? 1.0 : len;
+  return 2.125 * u * ((2.0 * g + 2.0) * xn * wm + 2.0 * wm * wm);
+}
+
+template <int ACC>
+__global__ __launch_bounds__(256) void k_bmu_csr(const int64_t *__restrict__ indptr,
+                                                 const int32_t *__restrict__ indices,
+                                                 const float *__restrict__ values, const float *__restrict__ Wt,
+                                                 int kpad, const float *__restrict__ wn32,
+                                                 const float *__restrict__ xn32,
+                                                 const unsigned *__restrict__ wmax_bits, int64_t n, int k, int dim,
+                                                 int32_t *__restrict__ bmus, int32_t *__restrict__ cand_idx,
+                                                 int32_t *__restrict__ cand_n, int32_t *__restrict__ refine_list,
+                                                 int32_t *__restrict__ rescan_list,
+                                                 int32_t *__restrict__ list_counts) {
+  __shared__ int64_t s_off[256];
+  __shared__ float s_val[256];
+  __shared__ float s_min[4];
+  __shared__ int s_cnt;
+  __shared__ int s_list[kCand];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int span = 256 * ACC;                       // nodes covered by one sweep
+  const int nsweep = (k + span - 1) / span;
+  const float wmax2 = __uint_as_float(*wmax_bits);
+
+  for (int64_t j = blockIdx.x; j < n; j += gridDim.x) {
+    const int64_t rs = indptr[j];
+    const int len = (int)(indptr[j + 1] - rs);
+    float sc[ACC];
+    float lmin = INFINITY;
+    float thr = 0.f;
+    // phase 0 finds the minimum score, phase 1 collects the nodes within the margin of it;
+    // with a single sweep the scores of phase 0 are still in registers for phase 1.
+    for (int phase = 0; phase < 2; ++phase) {
+      for (int sw = 0; sw < nsweep; ++sw) {
+        const int node_base = sw * span + tid;
+        if (phase == 0 || nsweep > 1) {
+          float acc[ACC];
+#pragma unroll
+          for (int a = 0; a < ACC; ++a) acc[a] = 0.f;
+          for (int p0 = 0; p0 < len; p0 += 256) {
+            __syncthreads();
+            if (p0 + tid < len) {
+              int c = indices[rs + p0 + tid];
+              c = c < 0 ? 0 : (c >= dim ? dim - 1 : c);
+              s_off[tid] = (int64_t)c * kpad;
+              s_val[tid] = values[rs + p0 + tid];
+            }
+            __syncthreads();
+            const int m = min(256, len - p0);
+            for (int q = 0; q < m; ++q) {
+              const float v = s_val[q];
+              const float *wrow = Wt + s_off[q] + node_base;
+#pragma unroll
+              for (int a = 0; a < ACC; ++a)
+                if (sw * span + a * 256 < kpad) acc[a] = fmaf(v, wrow[a * 256], acc[a]);
+            }
+          }
+#pragma unroll
+          for (int a = 0; a < ACC; ++a) {
+            const int node = node_base + a * 256;
+            sc[a] = node < k ? fmaf(-2.f, acc[a], wn32[node]) : INFINITY;
+          }
+        }
+        if (phase == 0) {
+#pragma unroll
+          for (int a = 0; a < ACC; ++a) lmin = fminf(lmin, sc[a]);
+        } else {
+#pragma unroll
+          for (int a = 0; a < ACC; ++a)
+            if (sc[a] <= thr) {
+              const int pos = atomicAdd(&s_cnt, 1);
+              if (pos < kCand) s_list[pos] = node_base + a * 256;
+            }
+        }
+      }
+      if (phase == 0) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) lmin = fminf(lmin, __shfl_xor(lmin, o, 64));
+        __syncthreads();
+        if (lane == 0) s_min[wave] = lmin;
+        if (tid == 0) s_cnt = 0;
+        __syncthreads();
+        const float smin = fminf(fminf(s_min[0], s_min[1]), fminf(s_min[2], s_min[3]));
+        const double t = (double)smin + csr_margin((double)len, (double)xn32[j], (double)wmax2);
+        // round the threshold up to fp32 so that no score inside the margin is lost
+        thr = (float)t;
+        if ((double)thr < t) thr = nextafterf(thr, INFINITY);
+      }
+    }
+    __syncthreads();
+    if (tid == 0) {
+      const int cnt = s_cnt;
+      if (cnt == 1) {
+        bmus[j] = s_list[0];
+      } else if (cnt >= 2 && cnt <= kCand) {
+        for (int t = 0; t < cnt; ++t) cand_idx[j * kCand + t] = s_list[t];
+        cand_n[j] = cnt;
+        refine_list[atomicAdd(&list_counts[0], 1)] = (int32_t)j;
+      } else {
+        rescan_list[atomicAdd(&list_counts[1], 1)] = (int32_t)j;
+      }
+    }
+    __syncthreads();
+  }
+}
+
+hipError_t launch_transpose_codebook(som_ctx *c, const float *W) {
+  dim3 grid((c->dim + 31) / 32, (c->kpad + 31) / 32);
+  hipLaunchKernelGGL(k_transpose, grid, dim3(256), 0, c->stream, W, c->k, c->dim, c->kpad, c->Wt);
+  return hipGetLastError();
+}
+
+template <int ACC>
+static void launch_bmu_csr_acc(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
+                               int64_t n, int32_t *bmus) {
+  int64_t blocks = (int64_t)c->n_cu * 8;
+  if (blocks > n) blocks = n;
+  hipLaunchKernelGGL(k_bmu_csr<ACC>, dim3((unsigned)blocks), dim3(256), 0, c->stream, indptr, indices, values,
+                     c->Wt, c->kpad, c->wn32, c->xn32, c->wmax_bits, n, c->k, c->dim, bmus, c->cand_idx, c->cand_n,
+                     c->refine_list, c->rescan_list, c->list_counts);
+}
+
+hipError_t launch_bmu_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
+                          int64_t n, int32_t *bmus) {
+  const int need = (c->k + 255) / 256;
+  if (need <= 1) launch_bmu_csr_acc<1>(c, indptr, indices, values, n, bmus);
+  else if (need <= 2) launch_bmu_csr_acc<2>(c, indptr, indices, values, n, bmus);
+  else if (need <= 4) launch_bmu_csr_acc<4>(c, indptr, indices, values, n, bmus);
+  else if (need <= 6) launch_bmu_csr_acc<6>(c, indptr, indices, values, n, bmus);
+  else if (need <= 8) launch_bmu_csr_acc<8>(c, indptr, indices, values, n, bmus);
+  else if (need <= 10) launch_bmu_csr_acc<10>(c, indptr, indices, values, n, bmus);
+  else if (need <= 12) launch_bmu_csr_acc<12>(c, indptr, indices, values, n, bmus);
+  else launch_bmu_csr_acc<16>(c, indptr, indices, values, n, bmus);
+  return hipGetLastError();
+}
+
+}  // namespace som

@@ -1,0 +1,251 @@
+// Exact stage of the best-matching-unit search (paper: BMU equation, d = Euclidean distance).
+//
+// The fp32 pass leaves, per instance, a few candidate nodes with their scores
+// s = |w|^2 - 2 x.w and the smallest score it dropped.  Here:
+//   certify  - bounds the rounding error of those scores; an instance whose best score beats
+//              everything else by more than twice the bound is decided on the spot;
+//   refine   - otherwise the candidates inside the bound are compared by their squared
+//              distances sum_c (x_c - w_c)^2 evaluated in fp64, lowest node index on exact ties;
+//   rescan   - if a dropped score lies inside the bound too, all nodes are compared that way.
+// The instance lists for refine and rescan are built with atomic counters, so their order
+// varies between runs; every instance is decided independently, so the BMUs do not.
+//
+// Error bound of one fp32 score (u = 2^-24, g = roundings a product term can suffer):
+//   |s_fp32 - s| <= u [ (2 g + 2) |x| max|w| + 2 max|w|^2 ]
+// (dot product: g u sum|x_c w_c| <= g u |x||w|, doubled by the factor -2; rounding of the
+// stored |w|^2; rounding of the final multiply-add).  Dense MFMA pass with two-level
+// accumulation: g = block + ceil(dim / block) + 2.  Sparse FMA chain of len terms: g = len.
+#include "som_internal.hpp"
+
+#include <math.h>
+
+namespace som {
+
+__device__ __forceinline__ double score_margin(double g, double xnorm2, double wmax2) {
+  const double u = 5.9604644775390625e-08;   // 2^-24
+  const double xn = sqrt(xnorm2 * (1.0 + 1.2e-7));
+  const double wm = sqrt(wmax2 * (1.0 + 1.2e-7));
+  const double bound = u * ((2.0 * g + 2.0) * xn * wm + 2.0 * wm * wm);
+  return 2.125 * bound;          // both scores of a pair may err, plus slack for higher-order terms
+}
+
+__global__ __launch_bounds__(256) void k_certify(CandView cand, const float *__restrict__ xn32,
+                                                 const unsigned *__restrict__ wmax_bits, double g, int64_t n,
+                                                 int32_t *__restrict__ bmus, int32_t *__restrict__ cand_n,
+                                                 int32_t *__restrict__ refine_list,
+                                                 int32_t *__restrict__ rescan_list,
+                                                 int32_t *__restrict__ list_counts) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  float v[kCand];
+  int id[kCand];
+  float smin = INFINITY;
+#pragma unroll
+  for (int t = 0; t < kCand; ++t) {
+    v[t] = cand.val[j * kCand + t];
+    id[t] = cand.idx[j * kCand + t];
+    if (id[t] >= 0) smin = fminf(smin, v[t]);
+  }
+  const double margin = score_margin(g, (double)xn32[j], (double)__uint_as_float(*wmax_bits));
+  const double thr = (double)smin + margin;
+  int keep[kCand];
+  int cnt = 0;
+#pragma unroll
+  for (int t = 0; t < kCand; ++t)
+    if (id[t] >= 0 && (double)v[t] <= thr) keep[cnt++] = id[t];
+  const bool overflow = (double)cand.over[j] <= thr;
+  if (overflow || cnt == 0) {
+    rescan_list[atomicAdd(&list_counts[1], 1)] = (int32_t)j;
+  } else if (cnt == 1) {
+    bmus[j] = keep[0];
+  } else {
+    for (int t = 0; t < cnt; ++t) cand.idx[j * kCand + t] = keep[t];
+    cand_n[j] = cnt;
+    refine_list[atomicAdd(&list_counts[0], 1)] = (int32_t)j;
+  }
+}
+
+// sum_c (x_c - w_c)^2 in fp64, columns dealt to lanes round-robin, butterfly reduction: the
+// same order for every node, so identical weight vectors give bit-identical results.
+__device__ __forceinline__ double sqdist_dense_wave(const float *__restrict__ x, const float *__restrict__ w,
+                                                    int dim, int lane) {
+  double s = 0.0;
+  for (int c = lane; c < dim; c += kWave) {
+    const double d = (double)x[c] - (double)w[c];
+    s += d * d;
+  }
+  return wave_sum(s);
+}
+
+// The same distance for a sparse row with implicit zeros: |w|^2 + sum_nz ((v - w_c)^2 - w_c^2).
+__device__ __forceinline__ double sqdist_csr_wave(const int32_t *__restrict__ idx, const float *__restrict__ val,
+                                                  int len, const float *__restrict__ w, double wn, int dim,
+                                                  int lane) {
+  double s = 0.0;
+  for (int p = lane; p < len; p += kWave) {
+    int c = idx[p];
+    c = c < 0 ? 0 : (c >= dim ? dim - 1 : c);
+    const double wc = (double)w[c];
+    const double d = (double)val[p] - wc;
+    s += d * d - wc * wc;
+  }
+  return wn + wave_sum(s);
+}
+
+__global__ __launch_bounds__(256) void k_refine_dense(const float *__restrict__ X, const float *__restrict__ W,
+                                                      int dim, const int32_t *__restrict__ cand_idx,
+                                                      const int32_t *__restrict__ cand_n,
+                                                      const int32_t *__restrict__ refine_list,
+                                                      const int32_t *__restrict__ list_counts,
+                                                      int32_t *__restrict__ bmus) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int nwaves = gridDim.x * (blockDim.x / kWave);
+  const int count = list_counts[0];
+  for (int e = wave; e < count; e += nwaves) {
+    const int64_t j = refine_list[e];
+    const int cn = cand_n[j];
+    double best = INFINITY;
+    int arg = 0x7fffffff;
+    for (int t = 0; t < cn; ++t) {
+      const int i = cand_idx[j * kCand + t];
+      const double d2 = sqdist_dense_wave(X + j * dim, W + (int64_t)i * dim, dim, lane);
+      if (d2 < best || (d2 == best && i < arg)) { best = d2; arg = i; }
+    }
+    if (lane == 0) bmus[j] = arg;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_rescan_dense(const float *__restrict__ X, const float *__restrict__ W,
+                                                      int dim, int k, const int32_t *__restrict__ rescan_list,
+                                                      const int32_t *__restrict__ list_counts,
+                                                      int32_t *__restrict__ bmus) {
+  __shared__ double s_best[4];
+  __shared__ int s_arg[4];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const int count = list_counts[1];
+  for (int e = blockIdx.x; e < count; e += gridDim.x) {
+    const int64_t j = rescan_list[e];
+    const float *x = X + j * dim;
+    double best = INFINITY;
+    int arg = 0x7fffffff;
+    for (int i = wave; i < k; i += 4) {           // ascending within a wave: strict < keeps the lowest index
+      const double d2 = sqdist_dense_wave(x, W + (int64_t)i * dim, dim, lane);
+      if (d2 < best) { best = d2; arg = i; }
+    }
+    if (lane == 0) { s_best[wave] = best; s_arg[wave] = arg; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      for (int w = 1; w < 4; ++w)
+        if (s_best[w] < best || (s_best[w] == best && s_arg[w] < arg)) { best = s_best[w]; arg = s_arg[w]; }
+      bmus[j] = arg == 0x7fffffff ? 0 : arg;
+    }
+    __syncthreads();
+  }
+}
+
+__global__ __launch_bounds__(256) void k_refine_csr(const int64_t *__restrict__ indptr,
+                                                    const int32_t *__restrict__ indices,
+                                                    const float *__restrict__ values,
+                                                    const float *__restrict__ W, const double *__restrict__ wn64,
+                                                    int dim, const int32_t *__restrict__ cand_idx,
+                                                    const int32_t *__restrict__ cand_n,
+                                                    const int32_t *__restrict__ refine_list,
+                                                    const int32_t *__restrict__ list_counts,
+                                                    int32_t *__restrict__ bmus) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int nwaves = gridDim.x * (blockDim.x / kWave);
+  const int count = list_counts[0];
+  for (int e = wave; e < count; e += nwaves) {
+    const int64_t j = refine_list[e];
+    const int64_t s = indptr[j];
+    const int len = (int)(indptr[j + 1] - s);
+    const int cn = cand_n[j];
+    double best = INFINITY;
+    int arg = 0x7fffffff;
+    for (int t = 0; t < cn; ++t) {
+      const int i = cand_idx[j * kCand + t];
+      const double d2 = sqdist_csr_wave(indices + s, values + s, len, W + (int64_t)i * dim, wn64[i], dim, lane);
+      if (d2 < best || (d2 == best && i < arg)) { best = d2; arg = i; }
+    }
+    if (lane == 0) bmus[j] = arg;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_rescan_csr(const int64_t *__restrict__ indptr,
+                                                    const int32_t *__restrict__ indices,
+                                                    const float *__restrict__ values,
+                                                    const float *__restrict__ W, const double *__restrict__ wn64,
+                                                    int dim, int k, const int32_t *__restrict__ rescan_list,
+                                                    const int32_t *__restrict__ list_counts,
+                                                    int32_t *__restrict__ bmus) {
+  __shared__ double s_best[4];
+  __shared__ int s_arg[4];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const int count = list_counts[1];
+  for (int e = blockIdx.x; e < count; e += gridDim.x) {
+    const int64_t j = rescan_list[e];
+    const int64_t s = indptr[j];
+    const int len = (int)(indptr[j + 1] - s);
+    double best = INFINITY;
+    int arg = 0x7fffffff;
+    for (int i = wave; i < k; i += 4) {
+      const double d2 = sqdist_csr_wave(indices + s, values + s, len, W + (int64_t)i * dim, wn64[i], dim, lane);
+      if (d2 < best) { best = d2; arg = i; }
+    }
+    if (lane == 0) { s_best[wave] = best; s_arg[wave] = arg; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      for (int w = 1; w < 4; ++w)
+        if (s_best[w] < best || (s_best[w] == best && s_arg[w] < arg)) { best = s_best[w]; arg = s_arg[w]; }
+      bmus[j] = arg == 0x7fffffff ? 0 : arg;
+    }
+    __syncthreads();
+  }
+}
+
+static int persistent_blocks(const som_ctx *c, int64_t upper) {
+  int64_t b = (int64_t)c->n_cu * 8;
+  if (b > upper) b = upper;
+  if (b < 1) b = 1;
+  return (int)b;
+}
+
+hipError_t launch_certify(som_ctx *c, int64_t n, int32_t *bmus) {
+  CandView cand{c->cand_val, c->cand_idx, c->cand_over};
+  const double g = (double)kDenseAccumBlock + (double)((c->dim + kDenseAccumBlock - 1) / kDenseAccumBlock) + 2.0;
+  hipLaunchKernelGGL(k_certify, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, cand, c->xn32,
+                     c->wmax_bits, g, n, bmus, c->cand_n, c->refine_list, c->rescan_list, c->list_counts);
+  return hipGetLastError();
+}
+
+hipError_t launch_refine_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus) {
+  hipLaunchKernelGGL(k_refine_dense, dim3(persistent_blocks(c, 1 << 20)), dim3(256), 0, c->stream, X, W, c->dim,
+                     c->cand_idx, c->cand_n, c->refine_list, c->list_counts, bmus);
+  return hipGetLastError();
+}
+
+hipError_t launch_rescan_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus) {
+  hipLaunchKernelGGL(k_rescan_dense, dim3(persistent_blocks(c, 1 << 20)), dim3(256), 0, c->stream, X, W, c->dim,
+                     c->k, c->rescan_list, c->list_counts, bmus);
+  return hipGetLastError();
+}
+
+hipError_t launch_refine_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
+                             const float *W, int32_t *bmus) {
+  hipLaunchKernelGGL(k_refine_csr, dim3(persistent_blocks(c, 1 << 20)), dim3(256), 0, c->stream, indptr, indices,
+                     values, W, c->wn64, c->dim, c->cand_idx, c->cand_n, c->refine_list, c->list_counts, bmus);
+  return hipGetLastError();
+}
+
+hipError_t launch_rescan_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
+                             const float *W, int32_t *bmus) {
+  hipLaunchKernelGGL(k_rescan_csr, dim3(persistent_blocks(c, 1 << 20)), dim3(256), 0, c->stream, indptr, indices,
+                     values, W, c->wn64, c->dim, c->k, c->rescan_list, c->list_counts, bmus);
+  return hipGetLastError();
+}
+
+}  // namespace som

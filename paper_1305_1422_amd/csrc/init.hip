@@ -1,0 +1,30 @@
+// Random initial code book (paper: option -c, "The default is random initialization").
+// Element e of the code book gets a uniform [0,1) value from a counter-based generator:
+// a 64-bit mix (splitmix64 finaliser) of seed + e * golden-ratio increment, top 24 bits.
+#include "som_internal.hpp"
+
+namespace som {
+
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+__global__ __launch_bounds__(256) void k_fill_uniform(float *__restrict__ W, int64_t count, uint64_t seed) {
+  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; e < count; e += stride) {
+    const uint64_t r = mix64(seed + 0x9E3779B97F4A7C15ull * (uint64_t)(e + 1));
+    W[e] = (float)(r >> 40) * (1.0f / 16777216.0f);
+  }
+}
+
+hipError_t launch_fill_uniform(som_ctx *c, float *W, int64_t count, uint64_t seed) {
+  int64_t blocks = (count + 255) / 256;
+  if (blocks > (int64_t)c->n_cu * 32) blocks = (int64_t)c->n_cu * 32;
+  hipLaunchKernelGGL(k_fill_uniform, dim3((unsigned)blocks), dim3(256), 0, c->stream, W, count, seed);
+  return hipGetLastError();
+}
+
+}  // namespace som

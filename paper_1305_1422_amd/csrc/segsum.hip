@@ -1,0 +1,270 @@
+// Per-node sums of the batch update (paper: batch equation; "Parallelism": the accumulation of
+// local weights used to be the bottleneck when done by one process).
+//
+// The neighbourhood weight of an instance depends on it only through its BMU, so the update
+// needs S_b = sum of the instances whose BMU is b and C_b = their number.  Dense data:
+//   1. C_b by integer atomics, exclusive scan -> segment offsets;
+//   2. stable LSD radix sort of the instance ids by BMU (8-bit digits, ballot-based ranking),
+//      so every segment lists its instances in ascending order;
+//   3. every segment is cut into chunks of kChunkRows instances; one workgroup sums one chunk
+//      (fp64 registers, instances read as whole rows through the permutation);
+//   4. chunks of a node are added in order.
+// No floating-point atomics: the result is bit-reproducible.  Sparse data is scattered with
+// fp32 atomic adds instead (a dense partial row per chunk would not fit anywhere).
+#include "som_internal.hpp"
+
+namespace som {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ int clamp_node(int b, int k) { return b < 0 ? 0 : (b >= k ? k - 1 : b); }
+
+__global__ __launch_bounds__(256) void k_count_bmus(const int32_t *__restrict__ bmus, int64_t n, int k,
+                                                    int32_t *__restrict__ counts) {
+  int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; j < n; j += stride) atomicAdd(&counts[clamp_node(bmus[j], k)], 1);
+}
+
+// Exclusive scan of in[0..len) into out[0..len], out[len] = total.  One workgroup of 1024.
+// `transform` > 0: scan ceil(in / transform) instead of in (chunks per node).
+// in and out may be the same array.
+__global__ __launch_bounds__(1024) void k_scan_exclusive(const int32_t *in, int32_t *out, int len, int transform) {
+  __shared__ int s_wave[16];
+  __shared__ int s_carry;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) s_carry = 0;
+  __syncthreads();
+  for (int base = 0; base < len; base += 1024) {
+    const int i = base + tid;
+    int v = 0;
+    if (i < len) {
+      v = in[i];
+      if (transform > 0) v = (v + transform - 1) / transform;
+    }
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int t = __shfl_up(inc, o, 64);
+      if (lane >= o) inc += t;
+    }
+    if (lane == 63) s_wave[wave] = inc;
+    __syncthreads();
+    int wave_base = 0;
+    for (int w = 0; w < wave; ++w) wave_base += s_wave[w];
+    const int carry = s_carry;
+    if (i < len) out[i] = carry + wave_base + inc - v;
+    __syncthreads();
+    if (tid == 1023) s_carry = carry + wave_base + inc;
+    __syncthreads();
+  }
+  if (tid == 0) out[len] = s_carry;
+}
+
+// ---------------------------------------------------------------- stable radix sort
+__global__ __launch_bounds__(256) void k_radix_hist(const int32_t *__restrict__ keys, int64_t n, int shift,
+                                                    int nblk, int k, int32_t *__restrict__ hist) {
+  __shared__ int s_hist[256];
+  s_hist[threadIdx.x] = 0;
+  __syncthreads();
+  const int64_t base = (int64_t)blockIdx.x * kSortTile;
+  for (int e = threadIdx.x; e < kSortTile; e += 256) {
+    const int64_t j = base + e;
+    if (j < n) atomicAdd(&s_hist[(clamp_node(keys[j], k) >> shift) & 255], 1);
+  }
+  __syncthreads();
+  hist[(int64_t)threadIdx.x * nblk + blockIdx.x] = s_hist[threadIdx.x];
+}
+
+// One wavefront ranks its tile 64 keys at a time, in order: a key's position is the running
+// count of its digit plus the number of lower lanes holding the same digit (eight ballots).
+__global__ __launch_bounds__(64) void k_radix_scatter(const int32_t *__restrict__ keys_in,
+                                                      const int32_t *__restrict__ vals_in,
+                                                      int32_t *__restrict__ keys_out,
+                                                      int32_t *__restrict__ vals_out, int64_t n, int shift,
+                                                      int nblk, int k, const int32_t *__restrict__ hist_scanned) {
+  __shared__ int s_cnt[256];
+  const int lane = threadIdx.x;
+  for (int d = lane; d < 256; d += 64) s_cnt[d] = hist_scanned[(int64_t)d * nblk + blockIdx.x];
+  __syncthreads();
+  const int64_t base = (int64_t)blockIdx.x * kSortTile;
+  for (int step = 0; step < kSortTile / 64; ++step) {
+    const int64_t j = base + step * 64 + lane;
+    const bool valid = j < n;
+    const int key = valid ? clamp_node(keys_in[j], k) : 0;
+    const int val = valid ? (vals_in ? vals_in[j] : (int32_t)j) : 0;
+    const int d = (key >> shift) & 255;
+    unsigned long long same = __ballot(valid);
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      const bool bit = (d >> b) & 1;
+      const unsigned long long bal = __ballot(bit);
+      same &= bit ? bal : ~bal;
+    }
+    const int rank = __popcll(same & ((1ull << lane) - 1ull));
+    const int before = valid ? s_cnt[d] : 0;
+    __syncthreads();
+    if (valid && rank == 0) s_cnt[d] = before + __popcll(same);
+    __syncthreads();
+    if (valid) {
+      keys_out[before + rank] = key;
+      vals_out[before + rank] = val;
+    }
+  }
+}
+
+// ---------------------------------------------------------------- chunks
+__global__ __launch_bounds__(256) void k_fill_chunk_nodes(const int32_t *__restrict__ chunk_off, int k,
+                                                          int32_t *__restrict__ chunk_node) {
+  const int lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int nwaves = gridDim.x * 4;
+  for (int b = wave; b < k; b += nwaves)
+    for (int t = chunk_off[b] + lane; t < chunk_off[b + 1]; t += 64) chunk_node[t] = b;
+}
+
+template <bool kVec4>
+__global__ __launch_bounds__(256) void k_accumulate_dense(const float *__restrict__ X, int dim,
+                                                          const int32_t *__restrict__ perm,
+                                                          const int32_t *__restrict__ seg_off,
+                                                          const int32_t *__restrict__ chunk_off,
+                                                          const int32_t *__restrict__ chunk_node, int k,
+                                                          float *__restrict__ S, float *__restrict__ partial) {
+  __shared__ int s_rows[kChunkRows];
+  const int chunk = blockIdx.x;
+  if (chunk >= chunk_off[k]) return;
+  const int b = chunk_node[chunk];
+  const int first_chunk = chunk_off[b];
+  const int lo = seg_off[b] + (chunk - first_chunk) * kChunkRows;
+  const int hi = min(lo + kChunkRows, seg_off[b + 1]);
+  const int nrows = hi - lo;
+  if (threadIdx.x < nrows) s_rows[threadIdx.x] = perm[lo + threadIdx.x];
+  __syncthreads();
+  const bool single = (chunk_off[b + 1] - first_chunk) == 1;
+  float *dst = single ? S + (int64_t)b * dim : partial + (int64_t)chunk * dim;
+  if (kVec4) {
+    for (int q = threadIdx.x; q < dim / 4; q += blockDim.x) {
+      double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+      for (int r = 0; r < nrows; ++r) {
+        const f32x4 v = *reinterpret_cast<const f32x4 *>(X + (int64_t)s_rows[r] * dim + 4 * q);
+        a0 += (double)v[0]; a1 += (double)v[1]; a2 += (double)v[2]; a3 += (double)v[3];
+      }
+      f32x4 o = {(float)a0, (float)a1, (float)a2, (float)a3};
+      *reinterpret_cast<f32x4 *>(dst + 4 * q) = o;
+    }
+  } else {
+    for (int c = threadIdx.x; c < dim; c += blockDim.x) {
+      double a = 0;
+      for (int r = 0; r < nrows; ++r) a += (double)X[(int64_t)s_rows[r] * dim + c];
+      dst[c] = (float)a;
+    }
+  }
+}
+
+// Empty node: zero row.  One chunk: already written.  Several: add the partial rows in order.
+__global__ __launch_bounds__(256) void k_combine_chunks(const int32_t *__restrict__ chunk_off, int dim,
+                                                        const float *__restrict__ partial, float *__restrict__ S) {
+  const int b = blockIdx.x;
+  const int c0 = chunk_off[b], nc = chunk_off[b + 1] - c0;
+  if (nc == 1) return;
+  float *dst = S + (int64_t)b * dim;
+  for (int c = threadIdx.x; c < dim; c += blockDim.x) {
+    double a = 0;
+    for (int t = 0; t < nc; ++t) a += (double)partial[(int64_t)(c0 + t) * dim + c];
+    dst[c] = (float)a;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_scatter_csr(const int64_t *__restrict__ indptr,
+                                                     const int32_t *__restrict__ indices,
+                                                     const float *__restrict__ values, int64_t n, int dim, int k,
+                                                     const int32_t *__restrict__ bmus, float *__restrict__ S) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  for (int64_t j = wave; j < n; j += nwaves) {
+    float *dst = S + (int64_t)clamp_node(bmus[j], k) * dim;
+    for (int64_t p = indptr[j] + lane; p < indptr[j + 1]; p += 64) {
+      int c = indices[p];
+      c = c < 0 ? 0 : (c >= dim ? dim - 1 : c);
+      unsafeAtomicAdd(dst + c, values[p]);
+    }
+  }
+}
+
+static int radix_passes(int k) {
+  int bits = 1;
+  while ((1ll << bits) < (long long)k) ++bits;
+  return (bits + 7) / 8;
+}
+
+// Counts, segment offsets and the stable permutation of instance ids by BMU.
+// On return c->sort_val[0] holds the permutation.
+hipError_t launch_sort_by_bmu(som_ctx *c, const int32_t *bmus, int64_t n) {
+  hipError_t e = launch_fill_zero_u32(c->stream, c->counts, c->k);
+  if (e != hipSuccess) return e;
+  int64_t cb = (n + 255) / 256;
+  if (cb > (int64_t)c->n_cu * 16) cb = (int64_t)c->n_cu * 16;
+  hipLaunchKernelGGL(k_count_bmus, dim3((unsigned)cb), dim3(256), 0, c->stream, bmus, n, c->k, c->counts);
+  hipLaunchKernelGGL(k_scan_exclusive, dim3(1), dim3(1024), 0, c->stream, c->counts, c->seg_off, c->k, 0);
+
+  const int nblk = (int)((n + kSortTile - 1) / kSortTile);
+  const int passes = radix_passes(c->k);
+  const int32_t *kin = bmus;
+  const int32_t *vin = nullptr;
+  // an even number of hops ends in buffer 0: start in buffer 1 when the pass count is odd
+  int dst = (passes % 2 == 0) ? 1 : 0;
+  for (int p = 0; p < passes; ++p) {
+    hipLaunchKernelGGL(k_radix_hist, dim3(nblk), dim3(256), 0, c->stream, kin, n, 8 * p, nblk, c->k,
+                       c->radix_hist);
+    hipLaunchKernelGGL(k_scan_exclusive, dim3(1), dim3(1024), 0, c->stream, c->radix_hist, c->radix_hist,
+                       256 * nblk, 0);
+    hipLaunchKernelGGL(k_radix_scatter, dim3(nblk), dim3(64), 0, c->stream, kin, vin, c->sort_key[dst],
+                       c->sort_val[dst], n, 8 * p, nblk, c->k, c->radix_hist);
+    kin = c->sort_key[dst];
+    vin = c->sort_val[dst];
+    dst ^= 1;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_accumulate_dense(som_ctx *c, const float *X, int64_t n) {
+  hipLaunchKernelGGL(k_scan_exclusive, dim3(1), dim3(1024), 0, c->stream, c->counts, c->chunk_off, c->k,
+                     kChunkRows);
+  hipLaunchKernelGGL(k_fill_chunk_nodes, dim3(c->n_cu * 2), dim3(256), 0, c->stream, c->chunk_off, c->k,
+                     c->chunk_node);
+  int64_t max_chunks = n / kChunkRows + (n < c->k ? n : c->k);
+  if (max_chunks < 1) max_chunks = 1;
+  const bool vec4 = (c->dim % 4 == 0) && ((uintptr_t)X % 16 == 0);
+  int threads = vec4 ? c->dim / 4 : c->dim;
+  threads = ((threads + 63) / 64) * 64;
+  if (threads > 256) threads = 256;
+  if (threads < 64) threads = 64;
+  if (vec4)
+    hipLaunchKernelGGL(k_accumulate_dense<true>, dim3((unsigned)max_chunks), dim3(threads), 0, c->stream, X,
+                       c->dim, c->sort_val[0], c->seg_off, c->chunk_off, c->chunk_node, c->k, c->S, c->partial);
+  else
+    hipLaunchKernelGGL(k_accumulate_dense<false>, dim3((unsigned)max_chunks), dim3(threads), 0, c->stream, X,
+                       c->dim, c->sort_val[0], c->seg_off, c->chunk_off, c->chunk_node, c->k, c->S, c->partial);
+  hipLaunchKernelGGL(k_combine_chunks, dim3(c->k), dim3(256), 0, c->stream, c->chunk_off, c->dim, c->partial,
+                     c->S);
+  return hipGetLastError();
+}
+
+hipError_t launch_accumulate_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices,
+                                 const float *values, int64_t n, const int32_t *bmus) {
+  hipError_t e = launch_fill_zero_u32(c->stream, c->counts, c->k);
+  if (e != hipSuccess) return e;
+  int64_t cb = (n + 255) / 256;
+  if (cb > (int64_t)c->n_cu * 16) cb = (int64_t)c->n_cu * 16;
+  hipLaunchKernelGGL(k_count_bmus, dim3((unsigned)cb), dim3(256), 0, c->stream, bmus, n, c->k, c->counts);
+  e = launch_fill_zero_u32(c->stream, c->S, (int64_t)c->k * c->dim);
+  if (e != hipSuccess) return e;
+  int64_t sb = (n + 3) / 4;
+  if (sb > (int64_t)c->n_cu * 32) sb = (int64_t)c->n_cu * 32;
+  hipLaunchKernelGGL(k_scatter_csr, dim3((unsigned)sb), dim3(256), 0, c->stream, indptr, indices, values, n,
+                     c->dim, c->k, bmus, c->S);
+  return hipGetLastError();
+}
+
+}  // namespace som

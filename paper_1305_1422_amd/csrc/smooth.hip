@@ -1,0 +1,215 @@
+// Cooling schedules and the neighbourhood part of the batch update (paper: neighbourhood
+// equation, batch equation, options -t/-T, -r/-R, -l/-L, -g, -m; "Parallelism": the influence
+// radius of a best matching node is thresholded).
+//
+// New weights: w_i = N_i / D_i with N_i = sum_b h(b,i) S_b and D_i = sum_b h(b,i) C_b, where
+// h(b,i) = exp(-d^2(b,i) / (2 r^2)) and S_b, C_b are the per-node sums and counts.
+//
+// With q = 4 d^2 = m^2 + 4 a^2 (square) or m^2 + 3 a^2 (hexagonal), a = row distance and
+// m = twice the embedded column distance, the Gaussian factors: h = gx[m] * gy[a].  For a
+// hexagonal grid m depends on the column offset and on the row parities of both nodes only.
+// The sum over the k source nodes is therefore two one-dimensional passes over the map
+// (a (dim+1)-channel image of S and C):
+//   pass x: T_p[yb][xi] = sum_xb gx[m(xi, xb, p, parity(yb))] S[yb][xb]     (p = parity of the
+//           destination row; one image for square grids, two for hexagonal ones)
+//   pass y: N[yi][xi]   = sum_yb gy[a(yi, yb)] T_parity(yi)[yb][xi],  then w = N / D or keep.
+// Cost 2 k (rows + cols) dim instead of 2 k^2 dim flops.  The count channel is done the same
+// way in fp64 by two small kernels.  A node with D < SOM_EPS_MASS keeps its weights.
+//
+// Cooling and the two factor tables are evaluated by a one-workgroup kernel, so a whole
+// training schedule can be enqueued without the host computing anything per epoch.
+#include "som_internal.hpp"
+
+#include <math.h>
+
+namespace som {
+
+__device__ __forceinline__ double cooled(double v0, double vN, int n_epochs, int epoch, int kind) {
+  if (n_epochs <= 1) return v0;
+  const double t = (double)epoch / (double)(n_epochs - 1);
+  return kind == SOM_COOL_EXPONENTIAL ? v0 * pow(vN / v0, t) : v0 + (vN - v0) * t;
+}
+
+__global__ __launch_bounds__(256) void k_epoch_params(EpochParams *__restrict__ params, float *__restrict__ gx,
+                                                      float *__restrict__ gy, int rows, int cols, int hex,
+                                                      int epoch, int n_epochs, double r0, double rN, double s0,
+                                                      double sN, int cooling) {
+  const double radius = cooled(r0, rN, n_epochs, epoch, cooling);
+  const double inv = 1.0 / (8.0 * radius * radius);
+  if (threadIdx.x == 0) {
+    params->radius = radius;
+    params->scale = cooled(s0, sN, n_epochs, epoch, cooling);
+    params->inv8r2 = inv;
+  }
+  for (int m = threadIdx.x; m <= 2 * cols; m += blockDim.x) gx[m] = (float)exp(-(double)m * (double)m * inv);
+  const double ya = hex ? 3.0 : 4.0;
+  for (int a = threadIdx.x; a < rows; a += blockDim.x) gy[a] = (float)exp(-ya * (double)a * (double)a * inv);
+}
+
+__global__ __launch_bounds__(256) void k_cool_schedule(int n_epochs, double r0, double rN, double s0, double sN,
+                                                       int cooling, double *__restrict__ radius_out,
+                                                       double *__restrict__ scale_out) {
+  for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < n_epochs; e += gridDim.x * blockDim.x) {
+    if (radius_out) radius_out[e] = cooled(r0, rN, n_epochs, e, cooling);
+    if (scale_out) scale_out[e] = cooled(s0, sN, n_epochs, e, cooling);
+  }
+}
+
+// twice the embedded column distance between destination column xi (row parity pi) and source
+// column xb (row parity pb)
+__device__ __forceinline__ int col_offset2(int xi, int xb, int pi, int pb, int hex, int toroid, int cols) {
+  int m = 2 * (xi - xb) + (hex ? pi - pb : 0);
+  m = m < 0 ? -m : m;
+  if (toroid && 2 * cols - m < m) m = 2 * cols - m;
+  return m;
+}
+
+__device__ __forceinline__ int row_offset(int yi, int yb, int toroid, int rows) {
+  int a = yi > yb ? yi - yb : yb - yi;
+  if (toroid && rows - a < a) a = rows - a;
+  return a;
+}
+
+// ---------------------------------------------------------------- count channel (fp64)
+__global__ __launch_bounds__(256) void k_count_pass_x(const int32_t *__restrict__ counts,
+                                                      const float *__restrict__ gx, int rows, int cols, int hex,
+                                                      int toroid, double *__restrict__ cntT) {
+  const int k = rows * cols;
+  const int images = hex ? 2 : 1;
+  for (int o = blockIdx.x * blockDim.x + threadIdx.x; o < images * k; o += gridDim.x * blockDim.x) {
+    const int p = o / k, i = o - p * k;
+    const int y = i / cols, xi = i - y * cols;
+    double s = 0.0;
+    for (int xb = 0; xb < cols; ++xb) {
+      const int cb = counts[y * cols + xb];
+      if (cb) s += (double)gx[col_offset2(xi, xb, p, y & 1, hex, toroid, cols)] * (double)cb;
+    }
+    cntT[o] = s;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_count_pass_y(const double *__restrict__ cntT,
+                                                      const float *__restrict__ gy, int rows, int cols, int hex,
+                                                      int toroid, double *__restrict__ massD) {
+  const int k = rows * cols;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < k; i += gridDim.x * blockDim.x) {
+    const int yi = i / cols, x = i - yi * cols;
+    const double *img = cntT + (hex ? (int64_t)(yi & 1) * k : 0);
+    double s = 0.0;
+    for (int yb = 0; yb < rows; ++yb) s += (double)gy[row_offset(yi, yb, toroid, rows)] * img[yb * cols + x];
+    massD[i] = s;
+  }
+}
+
+// ---------------------------------------------------------------- feature channels (fp32)
+constexpr int kSmoothCols = 64;    // feature columns per workgroup (one per lane)
+constexpr int kSmoothOut = 4;      // outputs per thread along the smoothed direction
+
+// pass x.  grid = (ceil(dim/64), rows, images); wavefront w of the workgroup produces the
+// destination columns xi = 4 (w + 4 t) .. + 3.
+template <bool kHex>
+__global__ __launch_bounds__(256) void k_smooth_x(const float *__restrict__ S, float *__restrict__ T,
+                                                  const float *__restrict__ gx, int rows, int cols, int dim,
+                                                  int toroid) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c = blockIdx.x * kSmoothCols + lane;
+  const int y = blockIdx.y;
+  const int p = blockIdx.z;                    // parity of the destination rows this image serves
+  const bool live = c < dim;
+  const float *src = S + (int64_t)y * cols * dim + (live ? c : 0);
+  float *dst = T + ((int64_t)p * rows + y) * (int64_t)cols * dim + c;
+  for (int x0 = wave * kSmoothOut; x0 < cols; x0 += 4 * kSmoothOut) {
+    float acc[kSmoothOut] = {0.f, 0.f, 0.f, 0.f};
+    for (int xb = 0; xb < cols; ++xb) {
+      const float s = live ? src[(int64_t)xb * dim] : 0.f;
+#pragma unroll
+      for (int e = 0; e < kSmoothOut; ++e)
+        acc[e] = fmaf(gx[col_offset2(x0 + e < cols ? x0 + e : cols - 1, xb, p, y & 1, kHex, toroid, cols)], s,
+                      acc[e]);
+    }
+    if (live)
+#pragma unroll
+      for (int e = 0; e < kSmoothOut; ++e)
+        if (x0 + e < cols) dst[(int64_t)(x0 + e) * dim] = acc[e];
+  }
+}
+
+// pass y with the division.  grid = (ceil(dim/64), cols).
+template <bool kHex>
+__global__ __launch_bounds__(256) void k_smooth_y_divide(const float *__restrict__ T, float *__restrict__ W,
+                                                         const float *__restrict__ gy,
+                                                         const double *__restrict__ massD, int rows, int cols,
+                                                         int dim, int toroid) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c = blockIdx.x * kSmoothCols + lane;
+  const int x = blockIdx.y;
+  const bool live = c < dim;
+  const int64_t img = (int64_t)rows * cols * dim;
+  const float *src = T + (int64_t)x * dim + (live ? c : 0);
+  for (int y0 = wave * kSmoothOut; y0 < rows; y0 += 4 * kSmoothOut) {
+    float acc[kSmoothOut] = {0.f, 0.f, 0.f, 0.f};
+    for (int yb = 0; yb < rows; ++yb) {
+      const int64_t off = (int64_t)yb * cols * dim;
+      const float t0 = live ? src[off] : 0.f;                                 // image for even rows
+      const float t1 = kHex ? (live ? src[img + off] : 0.f) : t0;             // image for odd rows
+#pragma unroll
+      for (int e = 0; e < kSmoothOut; ++e) {
+        const int yi = y0 + e;
+        acc[e] = fmaf(gy[row_offset(yi < rows ? yi : rows - 1, yb, toroid, rows)], (kHex && (yi & 1)) ? t1 : t0,
+                      acc[e]);
+      }
+    }
+    if (live)
+#pragma unroll
+      for (int e = 0; e < kSmoothOut; ++e) {
+        const int yi = y0 + e;
+        if (yi < rows) {
+          const int64_t i = (int64_t)yi * cols + x;
+          const double D = massD[i];
+          if (D >= SOM_EPS_MASS) W[i * dim + c] = acc[e] / (float)D;
+        }
+      }
+  }
+}
+
+hipError_t launch_epoch_params(som_ctx *c, int epoch, int n_epochs, double r0, double rN, double s0, double sN,
+                               int cooling) {
+  hipLaunchKernelGGL(k_epoch_params, dim3(1), dim3(256), 0, c->stream, c->params, c->gx, c->gy, c->rows, c->cols,
+                     c->grid_type == SOM_GRID_HEXAGONAL, epoch, n_epochs, r0, rN, s0, sN, cooling);
+  return hipGetLastError();
+}
+
+hipError_t launch_cool_schedule(som_ctx *c, int n_epochs, double r0, double rN, double s0, double sN,
+                                int cooling, double *radius_out, double *scale_out) {
+  hipLaunchKernelGGL(k_cool_schedule, dim3((n_epochs + 255) / 256), dim3(256), 0, c->stream, n_epochs, r0, rN, s0,
+                     sN, cooling, radius_out, scale_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_smooth_and_divide(som_ctx *c, float *W) {
+  const int hex = c->grid_type == SOM_GRID_HEXAGONAL;
+  const int toroid = c->map_type == SOM_MAP_TOROID;
+  const int images = hex ? 2 : 1;
+  int cb = (images * c->k + 255) / 256;
+  hipLaunchKernelGGL(k_count_pass_x, dim3(cb), dim3(256), 0, c->stream, c->counts, c->gx, c->rows, c->cols, hex,
+                     toroid, c->cntT);
+  hipLaunchKernelGGL(k_count_pass_y, dim3((c->k + 255) / 256), dim3(256), 0, c->stream, c->cntT, c->gy, c->rows,
+                     c->cols, hex, toroid, c->massD);
+  const unsigned cblk = (unsigned)((c->dim + kSmoothCols - 1) / kSmoothCols);
+  if (hex) {
+    hipLaunchKernelGGL(k_smooth_x<true>, dim3(cblk, c->rows, 2), dim3(256), 0, c->stream, c->S, c->T, c->gx,
+                       c->rows, c->cols, c->dim, toroid);
+    hipLaunchKernelGGL(k_smooth_y_divide<true>, dim3(cblk, c->cols), dim3(256), 0, c->stream, c->T, W, c->gy,
+                       c->massD, c->rows, c->cols, c->dim, toroid);
+  } else {
+    hipLaunchKernelGGL(k_smooth_x<false>, dim3(cblk, c->rows, 1), dim3(256), 0, c->stream, c->S, c->T, c->gx,
+                       c->rows, c->cols, c->dim, toroid);
+    hipLaunchKernelGGL(k_smooth_y_divide<false>, dim3(cblk, c->cols), dim3(256), 0, c->stream, c->T, W, c->gy,
+                       c->massD, c->rows, c->cols, c->dim, toroid);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace som

@@ -1,0 +1,387 @@
+// C ABI of libsom: argument validation, scratch management and the order in which the kernels
+// of one epoch are enqueued.  See include/som.h for the contract of every entry point.
+//
+// One epoch (paper: "Self-organizing maps in batch mode"; API section, trainOneEpoch):
+//   node norms -> fp32 BMU filter (MFMA, or CSR gather) -> certify / exact refine / exact rescan
+//   -> counts, stable sort by BMU, chunked per-node sums -> neighbourhood smoothing in two
+//   passes with the division fused into the second.
+// Nothing in here synchronises the stream except som_destroy and som_get_stats.
+#include "som_internal.hpp"
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+using namespace som;
+
+static char g_init_error[256] = "";
+
+static int fail(som_ctx *c, int code, const char *fmt, ...) {
+  char *dst = c ? c->err : g_init_error;
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(dst, 256, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+static int dev_fail(som_ctx *c, hipError_t e, const char *what) {
+  return fail(c, SOM_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define SOM_LAUNCH(ctx, expr)                                   \
+  do {                                                          \
+    hipError_t e_ = (expr);                                     \
+    if (e_ != hipSuccess) return dev_fail((ctx), e_, #expr);    \
+  } while (0)
+
+template <typename T>
+static bool dev_alloc(T **p, size_t count) {
+  *p = nullptr;
+  if (count == 0) count = 1;
+  return hipMalloc((void **)p, count * sizeof(T)) == hipSuccess;
+}
+
+template <typename T>
+static void dev_free(T *&p) {
+  if (p) (void)hipFree((void *)p);
+  p = nullptr;
+}
+
+static void free_row_scratch(som_ctx *c) {
+  dev_free(c->xn32); dev_free(c->cand_val); dev_free(c->cand_idx); dev_free(c->cand_over);
+  dev_free(c->cand_n); dev_free(c->refine_list); dev_free(c->rescan_list);
+  dev_free(c->sort_key[0]); dev_free(c->sort_key[1]); dev_free(c->sort_val[0]); dev_free(c->sort_val[1]);
+  dev_free(c->radix_hist); dev_free(c->chunk_node); dev_free(c->partial);
+  c->n_cap = 0;
+}
+
+// Scratch that scales with the number of instances; grown (never shrunk) on demand.
+static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
+  const bool need_partial = dense && c->partial == nullptr;
+  if (n <= c->n_cap && !need_partial) return SOM_OK;
+  if (n > c->n_cap) {
+    (void)hipStreamSynchronize(c->stream);
+    free_row_scratch(c);
+    const size_t N = (size_t)n;
+    const size_t nblk = (N + kSortTile - 1) / kSortTile;
+    bool ok = dev_alloc(&c->xn32, N) && dev_alloc(&c->cand_val, N * kCand) && dev_alloc(&c->cand_idx, N * kCand) &&
+              dev_alloc(&c->cand_over, N) && dev_alloc(&c->cand_n, N) && dev_alloc(&c->refine_list, N) &&
+              dev_alloc(&c->rescan_list, N) && dev_alloc(&c->sort_key[0], N) && dev_alloc(&c->sort_key[1], N) &&
+              dev_alloc(&c->sort_val[0], N) && dev_alloc(&c->sort_val[1], N) &&
+              dev_alloc(&c->radix_hist, 256 * nblk + 1);
+    c->max_chunks = (int64_t)(N / kChunkRows) + c->k;
+    ok = ok && dev_alloc(&c->chunk_node, (size_t)c->max_chunks);
+    if (!ok) {
+      free_row_scratch(c);
+      return fail(c, SOM_ERR_ALLOC, "cannot allocate scratch for %lld instances", (long long)n);
+    }
+    c->n_cap = n;
+  }
+  if (dense && c->partial == nullptr) {
+    if (!dev_alloc(&c->partial, (size_t)c->max_chunks * c->dim))
+      return fail(c, SOM_ERR_ALLOC, "cannot allocate %lld x %d partial sums", (long long)c->max_chunks, c->dim);
+  }
+  return SOM_OK;
+}
+
+static int ensure_transposed(som_ctx *c) {
+  if (c->Wt) return SOM_OK;
+  if (!dev_alloc(&c->Wt, (size_t)c->dim * c->kpad))
+    return fail(c, SOM_ERR_ALLOC, "cannot allocate the transposed code book (%d x %d)", c->dim, c->kpad);
+  SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->Wt, (int64_t)c->dim * c->kpad));
+  return SOM_OK;
+}
+
+static int check_epoch_scalars(som_ctx *c, float radius, float scale) {
+  if (!(radius > 0.f) || !isfinite(radius)) return fail(c, SOM_ERR_INVALID_ARG, "radius must be finite and > 0");
+  if (!(scale > 0.f) || !(scale <= 1.f)) return fail(c, SOM_ERR_INVALID_ARG, "scale must be in (0, 1]");
+  return SOM_OK;
+}
+
+static int check_rows(som_ctx *c, int64_t n) {
+  if (n < 1 || n >= (1ll << 31)) return fail(c, SOM_ERR_INVALID_ARG, "n must be in [1, 2^31)");
+  return SOM_OK;
+}
+
+static int check_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values, int64_t n,
+                     int64_t nnz) {
+  if (!indptr) return fail(c, SOM_ERR_INVALID_ARG, "indptr is NULL");
+  if (nnz < 0 || nnz >= (1ll << 31)) return fail(c, SOM_ERR_INVALID_ARG, "nnz must be in [0, 2^31)");
+  if (nnz > 0 && (!indices || !values)) return fail(c, SOM_ERR_INVALID_ARG, "indices/values are NULL");
+  return check_rows(c, n);
+}
+
+// ---------------------------------------------------------------- stages
+static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *W, int32_t *bmus, bool have_xn) {
+  SOM_LAUNCH(c, launch_row_sqnorms(c, W, c->k, c->dim, c->wn32, nullptr, c->wmax_bits));
+  if (!have_xn) SOM_LAUNCH(c, launch_row_sqnorms(c, X, n, c->dim, c->xn32, nullptr, nullptr));
+  SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 2));
+  SOM_LAUNCH(c, launch_bmu_dense(c, X, n, W));
+  SOM_LAUNCH(c, launch_certify(c, n, bmus));
+  SOM_LAUNCH(c, launch_refine_dense(c, X, W, bmus));
+  SOM_LAUNCH(c, launch_rescan_dense(c, X, W, bmus));
+  return SOM_OK;
+}
+
+static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
+                          int64_t n, const float *W, int32_t *bmus, bool have_xn) {
+  int rc = ensure_transposed(c);
+  if (rc) return rc;
+  SOM_LAUNCH(c, launch_row_sqnorms(c, W, c->k, c->dim, c->wn32, c->wn64, c->wmax_bits));
+  if (!have_xn) SOM_LAUNCH(c, launch_csr_row_sqnorms(c, indptr, values, n, c->xn32));
+  SOM_LAUNCH(c, launch_transpose_codebook(c, W));
+  SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 2));
+  SOM_LAUNCH(c, launch_bmu_csr(c, indptr, indices, values, n, bmus));
+  SOM_LAUNCH(c, launch_refine_csr(c, indptr, indices, values, W, bmus));
+  SOM_LAUNCH(c, launch_rescan_csr(c, indptr, indices, values, W, bmus));
+  return SOM_OK;
+}
+
+static int update_dense(som_ctx *c, const float *X, int64_t n, const int32_t *bmus, float *W) {
+  SOM_LAUNCH(c, launch_sort_by_bmu(c, bmus, n));
+  SOM_LAUNCH(c, launch_accumulate_dense(c, X, n));
+  SOM_LAUNCH(c, launch_smooth_and_divide(c, W));
+  return SOM_OK;
+}
+
+static int update_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values, int64_t n,
+                      const int32_t *bmus, float *W) {
+  SOM_LAUNCH(c, launch_accumulate_csr(c, indptr, indices, values, n, bmus));
+  SOM_LAUNCH(c, launch_smooth_and_divide(c, W));
+  return SOM_OK;
+}
+
+// ---------------------------------------------------------------- entry points
+extern "C" {
+
+int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_type, float *codebook,
+             uint64_t seed, void *hip_stream) {
+  if (!out) return fail(nullptr, SOM_ERR_INVALID_ARG, "out is NULL");
+  *out = nullptr;
+  if (rows < 1 || cols < 1 || dim < 1) return fail(nullptr, SOM_ERR_INVALID_ARG, "rows, cols and dim must be >= 1");
+  if (rows > 65535 || cols > 65535 || (int64_t)rows * cols > (1 << 24))
+    return fail(nullptr, SOM_ERR_INVALID_ARG, "map too large (each side <= 65535, rows*cols <= 2^24)");
+  if ((int64_t)rows * cols * dim >= (1ll << 40)) return fail(nullptr, SOM_ERR_INVALID_ARG, "code book too large");
+  if (map_type != SOM_MAP_PLANAR && map_type != SOM_MAP_TOROID)
+    return fail(nullptr, SOM_ERR_INVALID_ARG, "unknown map_type %d", map_type);
+  if (grid_type != SOM_GRID_SQUARE && grid_type != SOM_GRID_HEXAGONAL)
+    return fail(nullptr, SOM_ERR_INVALID_ARG, "unknown grid_type %d", grid_type);
+  if (!codebook) return fail(nullptr, SOM_ERR_INVALID_ARG, "codebook is NULL");
+
+  som_ctx *c = (som_ctx *)calloc(1, sizeof(som_ctx));
+  if (!c) return fail(nullptr, SOM_ERR_ALLOC, "out of host memory");
+  c->rows = rows; c->cols = cols; c->dim = dim; c->k = rows * cols;
+  c->map_type = map_type; c->grid_type = grid_type;
+  c->stream = (hipStream_t)hip_stream;
+  c->kpad = ((c->k + 255) / 256) * 256;
+
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+    free(c);
+    return fail(nullptr, SOM_ERR_DEVICE, "no HIP device");
+  }
+  c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+
+  const size_t K = (size_t)c->k;
+  const size_t images = grid_type == SOM_GRID_HEXAGONAL ? 2 : 1;
+  bool ok = dev_alloc(&c->wn32, K) && dev_alloc(&c->wn64, K) && dev_alloc(&c->wmax_bits, 1) &&
+            dev_alloc(&c->counts, K + 1) && dev_alloc(&c->seg_off, K + 1) && dev_alloc(&c->chunk_off, K + 1) &&
+            dev_alloc(&c->massD, K) && dev_alloc(&c->cntT, 2 * K) && dev_alloc(&c->gx, 2 * (size_t)cols + 1) &&
+            dev_alloc(&c->gy, (size_t)rows) && dev_alloc(&c->params, 1) && dev_alloc(&c->list_counts, 2) &&
+            dev_alloc(&c->S, K * dim) && dev_alloc(&c->T, images * K * dim);
+  if (!ok) {
+    som_destroy(c);
+    return fail(nullptr, SOM_ERR_ALLOC, "cannot allocate map scratch (%d nodes x %d)", c->k, dim);
+  }
+  hipError_t e = launch_fill_zero_u32(c->stream, c->list_counts, 2);
+  if (e == hipSuccess && seed != 0) e = launch_fill_uniform(c, codebook, (int64_t)c->k * dim, seed);
+  if (e != hipSuccess) {
+    int rc = dev_fail(nullptr, e, "som_init");
+    som_destroy(c);
+    return rc;
+  }
+  *out = c;
+  return SOM_OK;
+}
+
+void som_destroy(som_ctx *c) {
+  if (!c) return;
+  (void)hipStreamSynchronize(c->stream);
+  free_row_scratch(c);
+  dev_free(c->wn32); dev_free(c->wn64); dev_free(c->wmax_bits); dev_free(c->counts); dev_free(c->seg_off);
+  dev_free(c->chunk_off); dev_free(c->massD); dev_free(c->cntT); dev_free(c->gx); dev_free(c->gy);
+  dev_free(c->params); dev_free(c->list_counts); dev_free(c->S); dev_free(c->T); dev_free(c->Wt);
+  free(c);
+}
+
+const char *som_last_error(const som_ctx *c) { return c ? c->err : g_init_error; }
+
+int som_bmus_dense(som_ctx *c, const float *data, int64_t n, const float *codebook, int32_t *bmus) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (!data || !codebook || !bmus) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
+  int rc = check_rows(c, n);
+  if (!rc) rc = ensure_rows(c, n, false);
+  if (rc) return rc;
+  return bmu_search_dense(c, data, n, codebook, bmus, false);
+}
+
+int som_bmus_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values, int64_t n,
+                 int64_t nnz, const float *codebook, int32_t *bmus) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (!codebook || !bmus) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
+  int rc = check_csr(c, indptr, indices, values, n, nnz);
+  if (!rc) rc = ensure_rows(c, n, false);
+  if (rc) return rc;
+  return bmu_search_csr(c, indptr, indices, values, n, codebook, bmus, false);
+}
+
+int som_update_dense(som_ctx *c, const float *data, int64_t n, const int32_t *bmus, float *codebook,
+                     float radius, float scale) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (!data || !codebook || !bmus) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
+  int rc = check_rows(c, n);
+  if (!rc) rc = check_epoch_scalars(c, radius, scale);
+  if (!rc) rc = ensure_rows(c, n, true);
+  if (rc) return rc;
+  SOM_LAUNCH(c, launch_epoch_params(c, 0, 1, radius, radius, scale, scale, SOM_COOL_LINEAR));
+  return update_dense(c, data, n, bmus, codebook);
+}
+
+int som_update_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values, int64_t n,
+                   int64_t nnz, const int32_t *bmus, float *codebook, float radius, float scale) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (!codebook || !bmus) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
+  int rc = check_csr(c, indptr, indices, values, n, nnz);
+  if (!rc) rc = check_epoch_scalars(c, radius, scale);
+  if (!rc) rc = ensure_rows(c, n, false);
+  if (rc) return rc;
+  SOM_LAUNCH(c, launch_epoch_params(c, 0, 1, radius, radius, scale, scale, SOM_COOL_LINEAR));
+  return update_csr(c, indptr, indices, values, n, bmus, codebook);
+}
+
+int som_train_epoch_dense(som_ctx *c, const float *data, int64_t n, float *codebook, float radius, float scale,
+                          int32_t *bmus) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (!data || !codebook || !bmus) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
+  int rc = check_rows(c, n);
+  if (!rc) rc = check_epoch_scalars(c, radius, scale);
+  if (!rc) rc = ensure_rows(c, n, true);
+  if (rc) return rc;
+  SOM_LAUNCH(c, launch_epoch_params(c, 0, 1, radius, radius, scale, scale, SOM_COOL_LINEAR));
+  rc = bmu_search_dense(c, data, n, codebook, bmus, false);
+  if (rc) return rc;
+  return update_dense(c, data, n, bmus, codebook);
+}
+
+int som_train_epoch_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
+                        int64_t n, int64_t nnz, float *codebook, float radius, float scale, int32_t *bmus) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (!codebook || !bmus) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
+  int rc = check_csr(c, indptr, indices, values, n, nnz);
+  if (!rc) rc = check_epoch_scalars(c, radius, scale);
+  if (!rc) rc = ensure_rows(c, n, false);
+  if (rc) return rc;
+  SOM_LAUNCH(c, launch_epoch_params(c, 0, 1, radius, radius, scale, scale, SOM_COOL_LINEAR));
+  rc = bmu_search_csr(c, indptr, indices, values, n, codebook, bmus, false);
+  if (rc) return rc;
+  return update_csr(c, indptr, indices, values, n, bmus, codebook);
+}
+
+int som_set_data_dense(som_ctx *c, const float *data, int64_t n) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (!data) return fail(c, SOM_ERR_INVALID_ARG, "data is NULL");
+  int rc = check_rows(c, n);
+  if (rc) return rc;
+  c->data_kind = 1; c->d_data = data; c->d_n = n; c->d_nnz = 0;
+  c->d_indptr = nullptr; c->d_indices = nullptr; c->d_values = nullptr;
+  return SOM_OK;
+}
+
+int som_set_data_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values, int64_t n,
+                     int64_t nnz) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  int rc = check_csr(c, indptr, indices, values, n, nnz);
+  if (rc) return rc;
+  c->data_kind = 2; c->d_data = nullptr; c->d_n = n; c->d_nnz = nnz;
+  c->d_indptr = indptr; c->d_indices = indices; c->d_values = values;
+  return SOM_OK;
+}
+
+static void schedule_defaults(const som_ctx *c, float &r0, float &rN, float &s0, float &sN) {
+  if (!(r0 > 0.f)) {
+    r0 = 0.5f * (float)(c->rows < c->cols ? c->rows : c->cols);
+    if (r0 < 1.f) r0 = 1.f;
+  }
+  if (!(rN > 0.f)) rN = 1.f;
+  if (!(s0 > 0.f)) s0 = 1.0f;
+  if (!(sN > 0.f)) sN = 0.01f;
+}
+
+int som_train(som_ctx *c, int n_epochs, float radius0, float radiusN, float scale0, float scaleN, int cooling,
+              float *codebook, int32_t *bmus) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (c->data_kind == 0) return fail(c, SOM_ERR_STATE, "no training data registered (som_set_data_*)");
+  if (!codebook || !bmus) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
+  if (n_epochs < 1) return fail(c, SOM_ERR_INVALID_ARG, "n_epochs must be >= 1");
+  if (cooling != SOM_COOL_LINEAR && cooling != SOM_COOL_EXPONENTIAL)
+    return fail(c, SOM_ERR_INVALID_ARG, "unknown cooling %d", cooling);
+  schedule_defaults(c, radius0, radiusN, scale0, scaleN);
+  if (!isfinite(radius0) || !isfinite(radiusN)) return fail(c, SOM_ERR_INVALID_ARG, "radius not finite");
+  if (scale0 > 1.f || scaleN > 1.f) return fail(c, SOM_ERR_INVALID_ARG, "scale must be in (0, 1]");
+  const bool dense = c->data_kind == 1;
+  int rc = ensure_rows(c, c->d_n, dense);
+  if (rc) return rc;
+  if (dense)
+    SOM_LAUNCH(c, launch_row_sqnorms(c, c->d_data, c->d_n, c->dim, c->xn32, nullptr, nullptr));
+  else
+    SOM_LAUNCH(c, launch_csr_row_sqnorms(c, c->d_indptr, c->d_values, c->d_n, c->xn32));
+  for (int e = 0; e < n_epochs; ++e) {
+    SOM_LAUNCH(c, launch_epoch_params(c, e, n_epochs, radius0, radiusN, scale0, scaleN, cooling));
+    if (dense) {
+      rc = bmu_search_dense(c, c->d_data, c->d_n, codebook, bmus, true);
+      if (!rc) rc = update_dense(c, c->d_data, c->d_n, bmus, codebook);
+    } else {
+      rc = bmu_search_csr(c, c->d_indptr, c->d_indices, c->d_values, c->d_n, codebook, bmus, true);
+      if (!rc) rc = update_csr(c, c->d_indptr, c->d_indices, c->d_values, c->d_n, bmus, codebook);
+    }
+    if (rc) return rc;
+  }
+  return SOM_OK;
+}
+
+int som_cool_schedule(som_ctx *c, int n_epochs, float radius0, float radiusN, float scale0, float scaleN,
+                      int cooling, double *radius_out, double *scale_out) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (n_epochs < 1) return fail(c, SOM_ERR_INVALID_ARG, "n_epochs must be >= 1");
+  if (cooling != SOM_COOL_LINEAR && cooling != SOM_COOL_EXPONENTIAL)
+    return fail(c, SOM_ERR_INVALID_ARG, "unknown cooling %d", cooling);
+  schedule_defaults(c, radius0, radiusN, scale0, scaleN);
+  SOM_LAUNCH(c, launch_cool_schedule(c, n_epochs, radius0, radiusN, scale0, scaleN, cooling, radius_out,
+                                     scale_out));
+  return SOM_OK;
+}
+
+int som_umatrix(som_ctx *c, const float *codebook, float *umatrix) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (!codebook || !umatrix) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
+  SOM_LAUNCH(c, launch_umatrix(c, codebook, umatrix));
+  return SOM_OK;
+}
+
+int som_get_stats(som_ctx *c, int64_t *out) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (!out) return fail(c, SOM_ERR_INVALID_ARG, "out is NULL");
+  int32_t h[2] = {0, 0};
+  hipError_t e = hipMemcpyAsync(h, c->list_counts, sizeof(h), hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return dev_fail(c, e, "som_get_stats");
+  out[0] = h[0];
+  out[1] = h[1];
+  return SOM_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,157 @@
+// Internal declarations shared by the translation units of libsom (gfx950 only).
+// Nothing here is part of the C ABI; see include/som.h for that.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "som.h"
+
+namespace som {
+
+// ---------------------------------------------------------------- constants
+constexpr int kWave = 64;                 // CDNA wavefront width
+constexpr int kCand = 4;                  // candidate nodes kept per instance by the fp32 pass
+constexpr int kChunkRows = 32;            // instances summed by one block of the segmented accumulation
+constexpr int kSortTile = 1024;           // keys ranked by one wave of the radix scatter
+constexpr int kDenseAccumBlock = 32;      // k-extent after which the fp32 MFMA accumulator is flushed
+
+// Scores the fp32 pass hands to the exact pass: per instance kCand (value, node) pairs,
+// smallest first where the producer sorts them, plus the smallest value it dropped.
+struct CandView {
+  float *val;      // [n][kCand]
+  int32_t *idx;    // [n][kCand], -1 = empty slot
+  float *over;     // [n] smallest score not kept (+inf if none)
+};
+
+// Epoch parameters produced on the device by the cooling kernel.
+struct EpochParams {
+  double radius;
+  double scale;
+  double inv8r2;   // 1 / (8 radius^2)
+};
+
+}  // namespace som
+
+// ---------------------------------------------------------------- context
+struct som_ctx {
+  int rows, cols, dim, k;
+  int map_type, grid_type;
+  hipStream_t stream;
+  int n_cu;
+
+  // per-map scratch (allocated in som_init)
+  float *wn32;            // [k] squared norms of the code-book rows, fp32
+  double *wn64;           // [k] the same in fp64
+  unsigned *wmax_bits;    // [1] bit pattern of max_i wn32[i] (non-negative floats order like uints)
+  int32_t *counts;        // [k] instances per BMU
+  int32_t *seg_off;       // [k+1] exclusive scan of counts
+  int32_t *chunk_off;     // [k+1] exclusive scan of chunks per node
+  double *massD;          // [k] neighbourhood mass per node
+  double *cntT;           // [2][k] count channel after the pass along x
+  float *gx;              // [2*cols+1] neighbourhood factor along x, index = twice the x offset
+  float *gy;              // [rows] neighbourhood factor along y
+  som::EpochParams *params;   // [1]
+  float *S;               // [k][dim] per-node sums
+  float *T;               // [1 or 2][k][dim] sums after the pass along x
+  float *Wt;              // [dim][kpad] transposed code book (sparse BMU only, lazily allocated)
+  int kpad;
+
+  // per-data scratch (grown on demand to n_cap rows)
+  int64_t n_cap;
+  float *xn32;            // [n] squared norms of the instances
+  float *cand_val;        // [n][kCand]
+  int32_t *cand_idx;      // [n][kCand]
+  float *cand_over;       // [n]
+  int32_t *cand_n;        // [n] number of candidates to evaluate exactly
+  int32_t *refine_list;   // [n]
+  int32_t *rescan_list;   // [n]
+  int32_t *list_counts;   // [2] lengths of refine_list, rescan_list
+  int32_t *sort_key[2];   // [n] each
+  int32_t *sort_val[2];   // [n] each
+  int32_t *radix_hist;    // [256 * sort blocks]
+  int32_t *chunk_node;    // [n/kChunkRows + k]
+  float *partial;         // [n/kChunkRows + k][dim]
+  int64_t max_chunks;
+
+  // registered training set for som_train
+  int data_kind;          // 0 none, 1 dense, 2 csr
+  const float *d_data;
+  const int64_t *d_indptr;
+  const int32_t *d_indices;
+  const float *d_values;
+  int64_t d_n, d_nnz;
+
+  char err[256];
+};
+
+namespace som {
+
+// Every launcher enqueues on ctx->stream and returns hipGetLastError().
+
+// norms.hip
+hipError_t launch_row_sqnorms(som_ctx *c, const float *A, int64_t nrows, int dim, float *out32,
+                              double *out64, unsigned *max_bits);
+hipError_t launch_csr_row_sqnorms(som_ctx *c, const int64_t *indptr, const float *values, int64_t n,
+                                  float *out32);
+
+// bmu_dense.hip
+hipError_t launch_bmu_dense(som_ctx *c, const float *X, int64_t n, const float *W);
+
+// bmu_exact.hip
+hipError_t launch_certify(som_ctx *c, int64_t n, int32_t *bmus);
+hipError_t launch_refine_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
+hipError_t launch_rescan_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
+hipError_t launch_refine_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices,
+                             const float *values, const float *W, int32_t *bmus);
+hipError_t launch_rescan_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices,
+                             const float *values, const float *W, int32_t *bmus);
+
+// bmu_csr.hip
+hipError_t launch_transpose_codebook(som_ctx *c, const float *W);
+hipError_t launch_bmu_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices,
+                          const float *values, int64_t n, int32_t *bmus);
+
+// segsum.hip
+hipError_t launch_sort_by_bmu(som_ctx *c, const int32_t *bmus, int64_t n);   // -> sort_val[0] = row ids
+hipError_t launch_accumulate_dense(som_ctx *c, const float *X, int64_t n);   // -> S, counts
+hipError_t launch_accumulate_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices,
+                                 const float *values, int64_t n, const int32_t *bmus);
+
+// smooth.hip
+hipError_t launch_epoch_params(som_ctx *c, int epoch, int n_epochs, double r0, double rN, double s0,
+                               double sN, int cooling);
+hipError_t launch_cool_schedule(som_ctx *c, int n_epochs, double r0, double rN, double s0, double sN,
+                                int cooling, double *radius_out, double *scale_out);
+hipError_t launch_smooth_and_divide(som_ctx *c, float *W);
+
+// umatrix.hip
+hipError_t launch_umatrix(som_ctx *c, const float *W, float *U);
+
+// init.hip
+hipError_t launch_fill_uniform(som_ctx *c, float *W, int64_t count, uint64_t seed);
+hipError_t launch_fill_zero_u32(hipStream_t s, void *p, int64_t count_u32);
+
+// ---------------------------------------------------------------- device helpers
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+// Grid geometry: q = 4 x squared grid distance between nodes (xi, yi) and (xb, yb).
+// Hexagonal rows of odd y are shifted right by half a cell, row pitch sqrt(3)/2.
+__device__ __forceinline__ long long grid_q(int rows, int cols, int toroid, int hex, int xi, int yi,
+                                            int xb, int yb) {
+  long long a = yi > yb ? yi - yb : yb - yi;
+  long long m = 2ll * (xi - xb) + (hex ? ((yi & 1) - (yb & 1)) : 0);
+  if (m < 0) m = -m;
+  if (toroid) {
+    if (rows - a < a) a = rows - a;
+    if (2ll * cols - m < m) m = 2ll * cols - m;
+  }
+  return m * m + (hex ? 3 : 4) * a * a;
+}
+
+}  // namespace som

@@ -1,0 +1,111 @@
+"""Parity of the sparse (CSR) HIP path against the CPU oracle (gpu tests, through the C ABI)."""
+import numpy as np
+import pytest
+
+from gen import scaled_workload, sparse_zipf_csr
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def densify(csr, dim):
+    indptr, indices, values = csr
+    X = np.zeros((len(indptr) - 1, dim), dtype=np.float32)
+    for j in range(len(indptr) - 1):
+        X[j, indices[indptr[j]:indptr[j + 1]]] = values[indptr[j]:indptr[j + 1]]
+    return X
+
+
+@pytest.mark.parametrize("n,dim,rows,cols,epochs,mean_len", [
+    (2000, 3000, 12, 10, 4, 100.0),     # configuration 4 scaled: one node sweep per instance
+    (600, 900, 24, 22, 2, 30.0),        # 528 nodes: three 256-node slices, the last ragged
+    (300, 500, 1, 3, 2, 8.0),           # tiny map
+])
+def test_scaled_config4(oracle, n, dim, rows, cols, epochs, mean_len):
+    from paper_1305_1422_amd import Som
+    w = scaled_workload(4, n=n, dim=dim, rows=rows, cols=cols, epochs=epochs)
+    csr = sparse_zipf_csr(n, dim, w.data_seed, mean_len=mean_len, max_len=int(4 * mean_len))
+    csr_d = P.csr_to_dev(csr)
+    som = Som(rows, cols, dim, w.map_type, w.grid_type, codebook=torch.from_numpy(w.codebook()))
+    for e in range(epochs):
+        r = oracle.cool(w.radius0, w.radiusN, epochs, e, oracle.LINEAR)
+        P.epoch_parity_csr(oracle, som, csr, csr_d, dim, r, P.MAP[w.map_type], P.GRID[w.grid_type])
+    som.close()
+
+
+def test_many_nodes_take_several_sweeps(oracle):
+    """More nodes than one sweep covers (16 x 256): scores are recomputed per sweep."""
+    from paper_1305_1422_amd import Som
+    rows, cols, dim, n = 70, 64, 300, 150               # 4480 nodes
+    csr = sparse_zipf_csr(n, dim, 21, mean_len=12.0, max_len=40)
+    W = np.random.default_rng(22).random((rows * cols, dim)).astype(np.float32)
+    som = Som(rows, cols, dim, "toroid", "hexagonal", codebook=torch.from_numpy(W))
+    b = som.bmus(P.csr_to_dev(csr)).cpu().numpy()
+    P.check_bmus_csr(oracle, csr, dim, W, b)
+    som.close()
+
+
+def test_sparse_path_equals_dense_path_on_densified_rows(oracle):
+    from paper_1305_1422_amd import Som
+    n, dim, rows, cols = 500, 640, 9, 8
+    csr = sparse_zipf_csr(n, dim, 23, mean_len=25.0, max_len=80)
+    X = densify(csr, dim)
+    W = (np.random.default_rng(24).random((rows * cols, dim)) * 0.2).astype(np.float32)
+    a = Som(rows, cols, dim, "planar", "square", codebook=torch.from_numpy(W))
+    b = Som(rows, cols, dim, "planar", "square", codebook=torch.from_numpy(W))
+    ba = a.train_epoch(P.csr_to_dev(csr), 2.0).cpu().numpy()
+    bb = b.train_epoch(P.to_dev(X), 2.0).cpu().numpy()
+    assert np.array_equal(ba, bb)
+    np.testing.assert_allclose(a.codebook.cpu().numpy(), b.codebook.cpu().numpy(), rtol=1e-5, atol=1e-6)
+    a.close(); b.close()
+
+
+def test_empty_rows_and_duplicate_nodes(oracle):
+    from paper_1305_1422_amd import Som
+    dim, rows, cols = 50, 4, 5
+    rng = np.random.default_rng(25)
+    W = rng.random((rows * cols, dim)).astype(np.float32) + np.float32(0.5)
+    W[11] = W[2] = (W[7] * np.float32(0.01))            # nodes 2 and 11: equal, and the smallest norm
+    indptr = np.array([0, 0, 3, 3, 5], dtype=np.int64)  # rows 0 and 2 are empty
+    indices = np.array([1, 7, 40, 0, 49], dtype=np.int32)
+    values = np.array([0.5, -1.0, 2.0, 3.0, 0.25], dtype=np.float32)
+    csr = (indptr, indices, values)
+    som = Som(rows, cols, dim, codebook=torch.from_numpy(W))
+    b = som.bmus(P.csr_to_dev(csr)).cpu().numpy()
+    want = oracle.bmu_csr(csr, dim, W)
+    assert np.array_equal(b, want) and b[0] == 2 and b[2] == 2
+    som.close()
+
+
+def test_update_csr_given_bmus(oracle):
+    from paper_1305_1422_amd import Som
+    n, dim, rows, cols = 900, 400, 10, 12
+    csr = sparse_zipf_csr(n, dim, 26, mean_len=15.0, max_len=50)
+    rng = np.random.default_rng(27)
+    W = rng.random((rows * cols, dim)).astype(np.float32)
+    bmus = rng.integers(0, rows * cols, size=n).astype(np.int32)
+    bmus[: n // 2] = 17                                   # one heavy node
+    for map_type, grid, radius in [("toroid", "square", 2.5), ("planar", "hexagonal", 0.8)]:
+        som = Som(rows, cols, dim, map_type, grid, codebook=torch.from_numpy(W))
+        som.update(P.csr_to_dev(csr), P.to_dev(bmus), radius)
+        torch.cuda.synchronize()
+        S, C = oracle.accumulate_csr(csr, dim, bmus, rows * cols)
+        P.check_codebook(oracle, S, C, W, som.codebook.cpu().numpy(), rows, cols, P.MAP[map_type], P.GRID[grid], radius)
+        som.close()
+
+
+def test_train_csr_schedule_runs_and_matches_last_epoch(oracle):
+    from paper_1305_1422_amd import Som
+    n, dim, rows, cols, E = 800, 1000, 8, 8, 4
+    csr = sparse_zipf_csr(n, dim, 28, mean_len=40.0, max_len=120)
+    csr_d = P.csr_to_dev(csr)
+    W0 = np.random.default_rng(29).random((rows * cols, dim)).astype(np.float32) * np.float32(0.1)
+    a = Som(rows, cols, dim, codebook=torch.from_numpy(W0))
+    a.train(csr_d, E, 4.0, 1.0, 1.0, 0.01, "linear")
+    b = Som(rows, cols, dim, codebook=torch.from_numpy(W0))
+    for e in range(E):
+        b.train_epoch(csr_d, oracle.cool(4.0, 1.0, E, e, oracle.LINEAR))      # 4, 3, 2, 1: exact in fp32
+    np.testing.assert_allclose(a.codebook.cpu().numpy(), b.codebook.cpu().numpy(), rtol=1e-5, atol=1e-6)
+    a.close(); b.close()

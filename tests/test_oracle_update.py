@@ -236,3 +236,19 @@ def test_whole_epoch_is_bmu_then_update(oracle):
     assert np.array_equal(bmu, oracle.bmu_dense(X, W))        # BMUs refer to the incoming code book
     S, C = oracle.accumulate_dense(X, bmu, rows * cols)
     np.testing.assert_array_equal(Wn, oracle.update(S, C, W, rows, cols, P, HX, 2.0)[0])
+
+
+def test_subset_update_equals_full_update(oracle):
+    rows, cols, dim, n = 6, 5, 4, 90
+    k = rows * cols
+    rng = np.random.default_rng(15)
+    X = rng.random((n, dim)).astype(np.float32)
+    W = rng.random((k, dim)).astype(np.float32)
+    bmu = rng.integers(0, 6, size=n).astype(np.int32)            # far nodes get no mass at r = 0.3
+    S, C = oracle.accumulate_dense(X, bmu, k)
+    full, D = oracle.update(S, C, W, rows, cols, P, HX, 0.3)
+    nodes = np.array([0, 3, 7, 29, 14], dtype=np.int32)
+    sub, Dsub = oracle.update_nodes(S, C, W, rows, cols, P, HX, 0.3, nodes)
+    np.testing.assert_array_equal(sub, full[nodes])
+    np.testing.assert_array_equal(Dsub, D[nodes])
+    assert (D < 1e-20).any() and (D >= 1e-20).any()
