@@ -179,6 +179,24 @@ int som_umatrix(som_ctx *ctx, const float *codebook, float *umatrix);
  */
 int som_get_stats(som_ctx *ctx, int64_t *out);
 
+/*
+ * som_profile_enable / som_profile_read - measurement support (not an operation of the paper).
+ * While enabled, the library brackets the stages of every epoch with HIP events recorded on
+ * the context's stream, so a benchmark can report per-stage device time without a profiler:
+ *   stage 0  dense fp32 BMU pass (one MFMA kernel launch per epoch)
+ *   stage 1  sparse fp32 BMU pass (transpose + CSR kernel)
+ *   stage 2  exact BMU stage (certify, candidate collection, refine, rescan)
+ *   stage 3  per-node sums (sort by BMU, chunk sums / sparse scatter)
+ *   stage 4  neighbourhood smoothing and division
+ * som_profile_read synchronises the stream, adds up the elapsed time of all brackets recorded
+ * since the last read, stores milliseconds in total_ms[0..4] and bracket counts in
+ * launches[0..4] (HOST pointers), and clears the record.  At most 512 brackets per stage are
+ * kept between two reads; further ones are not recorded.
+ */
+#define SOM_PROFILE_STAGES 5
+int som_profile_enable(som_ctx *ctx, int on);
+int som_profile_read(som_ctx *ctx, double *total_ms, int64_t *launches);
+
 #ifdef __cplusplus
 }
 #endif

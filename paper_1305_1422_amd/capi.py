@@ -26,7 +26,9 @@ EXPORTS = [
     "som_update_dense", "som_update_csr",
     "som_set_data_dense", "som_set_data_csr", "som_train",
     "som_cool_schedule", "som_umatrix", "som_get_stats",
+    "som_profile_enable", "som_profile_read",
 ]
+PROFILE_STAGES = ("bmu_dense_fp32", "bmu_csr_fp32", "bmu_exact", "node_sums", "smooth_divide")
 
 
 class SomError(RuntimeError):
@@ -77,6 +79,10 @@ def load():
     L.som_umatrix.argtypes = [vp, vp, vp]
     L.som_get_stats.restype = i32
     L.som_get_stats.argtypes = [vp, C.POINTER(i64)]
+    L.som_profile_enable.restype = i32
+    L.som_profile_enable.argtypes = [vp, i32]
+    L.som_profile_read.restype = i32
+    L.som_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
     _lib = L
     return L
 
@@ -214,3 +220,15 @@ def som_get_stats(ctx):
     out = (C.c_int64 * 2)()
     _check(ctx, load().som_get_stats(ctx, out))
     return int(out[0]), int(out[1])
+
+
+def som_profile_enable(ctx, on: bool) -> None:
+    _check(ctx, load().som_profile_enable(ctx, 1 if on else 0))
+
+
+def som_profile_read(ctx):
+    """{stage name: (total milliseconds, brackets)} since the last read; synchronises the stream."""
+    ms = (C.c_double * len(PROFILE_STAGES))()
+    cnt = (C.c_int64 * len(PROFILE_STAGES))()
+    _check(ctx, load().som_profile_read(ctx, ms, cnt))
+    return {name: (float(ms[i]), int(cnt[i])) for i, name in enumerate(PROFILE_STAGES)}

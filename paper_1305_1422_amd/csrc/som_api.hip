@@ -114,12 +114,31 @@ static int check_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, 
   return check_rows(c, n);
 }
 
+// ---------------------------------------------------------------- per-stage event brackets
+struct StageTimer {
+  som_ctx *c;
+  int stage, slot;
+  StageTimer(som_ctx *ctx, int st) : c(ctx), stage(st), slot(-1) {
+    if (c->prof_on && c->prof_ev[stage] && c->prof_used[stage] < kProfMax) {
+      slot = c->prof_used[stage]++;
+      (void)hipEventRecord(c->prof_ev[stage][2 * slot], c->stream);
+    }
+  }
+  ~StageTimer() {
+    if (slot >= 0) (void)hipEventRecord(c->prof_ev[stage][2 * slot + 1], c->stream);
+  }
+};
+
 // ---------------------------------------------------------------- stages
 static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *W, int32_t *bmus, bool have_xn) {
   SOM_LAUNCH(c, launch_row_sqnorms(c, W, c->k, c->dim, c->wn32, nullptr, c->wmax_bits));
   if (!have_xn) SOM_LAUNCH(c, launch_row_sqnorms(c, X, n, c->dim, c->xn32, nullptr, nullptr));
   SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 2));
-  SOM_LAUNCH(c, launch_bmu_dense(c, X, n, W));
+  {
+    StageTimer t(c, 0);
+    SOM_LAUNCH(c, launch_bmu_dense(c, X, n, W));
+  }
+  StageTimer t(c, 2);
   SOM_LAUNCH(c, launch_certify(c, n, bmus));
   SOM_LAUNCH(c, launch_refine_dense(c, X, W, bmus));
   SOM_LAUNCH(c, launch_rescan_dense(c, X, W, bmus));
@@ -132,24 +151,36 @@ static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indi
   if (rc) return rc;
   SOM_LAUNCH(c, launch_row_sqnorms(c, W, c->k, c->dim, c->wn32, c->wn64, c->wmax_bits));
   if (!have_xn) SOM_LAUNCH(c, launch_csr_row_sqnorms(c, indptr, values, n, c->xn32));
-  SOM_LAUNCH(c, launch_transpose_codebook(c, W));
   SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 2));
-  SOM_LAUNCH(c, launch_bmu_csr(c, indptr, indices, values, n, bmus));
+  {
+    StageTimer t(c, 1);
+    SOM_LAUNCH(c, launch_transpose_codebook(c, W));
+    SOM_LAUNCH(c, launch_bmu_csr(c, indptr, indices, values, n, bmus));
+  }
+  StageTimer t(c, 2);
   SOM_LAUNCH(c, launch_refine_csr(c, indptr, indices, values, W, bmus));
   SOM_LAUNCH(c, launch_rescan_csr(c, indptr, indices, values, W, bmus));
   return SOM_OK;
 }
 
 static int update_dense(som_ctx *c, const float *X, int64_t n, const int32_t *bmus, float *W) {
-  SOM_LAUNCH(c, launch_sort_by_bmu(c, bmus, n));
-  SOM_LAUNCH(c, launch_accumulate_dense(c, X, n));
+  {
+    StageTimer t(c, 3);
+    SOM_LAUNCH(c, launch_sort_by_bmu(c, bmus, n));
+    SOM_LAUNCH(c, launch_accumulate_dense(c, X, n));
+  }
+  StageTimer t(c, 4);
   SOM_LAUNCH(c, launch_smooth_and_divide(c, W));
   return SOM_OK;
 }
 
 static int update_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values, int64_t n,
                       const int32_t *bmus, float *W) {
-  SOM_LAUNCH(c, launch_accumulate_csr(c, indptr, indices, values, n, bmus));
+  {
+    StageTimer t(c, 3);
+    SOM_LAUNCH(c, launch_accumulate_csr(c, indptr, indices, values, n, bmus));
+  }
+  StageTimer t(c, 4);
   SOM_LAUNCH(c, launch_smooth_and_divide(c, W));
   return SOM_OK;
 }
@@ -215,6 +246,11 @@ void som_destroy(som_ctx *c) {
   dev_free(c->wn32); dev_free(c->wn64); dev_free(c->wmax_bits); dev_free(c->counts); dev_free(c->seg_off);
   dev_free(c->chunk_off); dev_free(c->massD); dev_free(c->cntT); dev_free(c->gx); dev_free(c->gy);
   dev_free(c->params); dev_free(c->list_counts); dev_free(c->S); dev_free(c->T); dev_free(c->Wt);
+  for (int s = 0; s < SOM_PROFILE_STAGES; ++s) {
+    if (!c->prof_ev[s]) continue;
+    for (int e = 0; e < 2 * kProfMax; ++e) (void)hipEventDestroy(c->prof_ev[s][e]);
+    free(c->prof_ev[s]);
+  }
   free(c);
 }
 
@@ -381,6 +417,48 @@ int som_get_stats(som_ctx *c, int64_t *out) {
   if (e != hipSuccess) return dev_fail(c, e, "som_get_stats");
   out[0] = h[0];
   out[1] = h[1];
+  return SOM_OK;
+}
+
+int som_profile_enable(som_ctx *c, int on) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (on) {
+    for (int s = 0; s < SOM_PROFILE_STAGES; ++s) {
+      if (c->prof_ev[s]) continue;
+      hipEvent_t *ev = (hipEvent_t *)calloc(2 * kProfMax, sizeof(hipEvent_t));
+      if (!ev) return fail(c, SOM_ERR_ALLOC, "out of host memory");
+      for (int e = 0; e < 2 * kProfMax; ++e) {
+        hipError_t err = hipEventCreate(&ev[e]);
+        if (err != hipSuccess) {
+          for (int d = 0; d < e; ++d) (void)hipEventDestroy(ev[d]);
+          free(ev);
+          return dev_fail(c, err, "hipEventCreate");
+        }
+      }
+      c->prof_ev[s] = ev;
+    }
+  }
+  c->prof_on = on ? 1 : 0;
+  return SOM_OK;
+}
+
+int som_profile_read(som_ctx *c, double *total_ms, int64_t *launches) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (!total_ms || !launches) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
+  hipError_t e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return dev_fail(c, e, "som_profile_read");
+  for (int s = 0; s < SOM_PROFILE_STAGES; ++s) {
+    double sum = 0.0;
+    for (int b = 0; b < c->prof_used[s]; ++b) {
+      float ms = 0.f;
+      e = hipEventElapsedTime(&ms, c->prof_ev[s][2 * b], c->prof_ev[s][2 * b + 1]);
+      if (e != hipSuccess) return dev_fail(c, e, "hipEventElapsedTime");
+      sum += ms;
+    }
+    total_ms[s] = sum;
+    launches[s] = c->prof_used[s];
+    c->prof_used[s] = 0;
+  }
   return SOM_OK;
 }
 

@@ -15,6 +15,7 @@ constexpr int kWave = 64;                 // CDNA wavefront width
 constexpr int kCand = 4;                  // candidate nodes kept per instance by the fp32 pass
 constexpr int kChunkRows = 32;            // instances summed by one block of the segmented accumulation
 constexpr int kSortTile = 1024;           // keys ranked by one wave of the radix scatter
+constexpr int kProfMax = 512;              // event brackets kept per stage between two reads
 constexpr int kDenseAccumBlock = 32;      // k-extent after which the fp32 MFMA accumulator is flushed
 
 // Scores the fp32 pass hands to the exact pass: per instance kCand (value, node) pairs,
@@ -82,6 +83,11 @@ struct som_ctx {
   const int32_t *d_indices;
   const float *d_values;
   int64_t d_n, d_nnz;
+
+  // optional per-stage event brackets (som_profile_enable)
+  int prof_on;
+  int prof_used[SOM_PROFILE_STAGES];
+  hipEvent_t *prof_ev[SOM_PROFILE_STAGES];   // 2 * kProfMax events each, created on first enable
 
   char err[256];
 };
