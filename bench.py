@@ -101,7 +101,7 @@ def main() -> int:
     dt = time.perf_counter() - t0
     prof = capi.som_profile_read(som.ctx)
     capi.som_profile_enable(som.ctx, False)
-    refined, rescanned = som.stats()
+    refined, collected, rescanned = som.stats()
 
     ms_per_step = 1e3 * dt / args.steps
     work = float(w.n) * w.k * w.dim
@@ -137,7 +137,7 @@ def main() -> int:
         "gflops_epoch": 2.0 * work / (dt / args.steps) / 1e9,
         "frac_fp32_mfma_peak_whole_epoch": 2.0 * work / (dt / args.steps) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
         "stage_ms": stage_ms,
-        "last_step_exact_rows": {"refined": refined, "rescanned": rescanned},
+        "last_step_exact_rows": {"refined": refined, "collected": collected, "rescanned": rescanned},
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

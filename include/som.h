@@ -172,10 +172,13 @@ int som_umatrix(som_ctx *ctx, const float *codebook, float *umatrix);
 
 /*
  * som_get_stats - counters of the most recent BMU search on ctx (synchronises the stream).
- *   rows_refined   instances whose fp32 scores left more than one candidate node and were
- *                  decided by exact fp64 distances of the candidates;
+ *   rows_refined   instances whose fp32 scores left two to four candidate nodes, decided by
+ *                  the exact fp64 distances of those candidates;
+ *   rows_collected instances with more candidates than that: a second fp32 sweep listed all
+ *                  nodes under the instance's threshold, then exact distances decided
+ *                  (dense data only);
  *   rows_rescanned instances that needed an exact fp64 scan of all nodes.
- * out is a HOST pointer to two int64 values, in that order.
+ * out is a HOST pointer to three int64 values, in that order.
  */
 int som_get_stats(som_ctx *ctx, int64_t *out);
 

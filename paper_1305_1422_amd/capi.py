@@ -216,10 +216,10 @@ def som_umatrix(ctx, codebook, umatrix) -> None:
 
 
 def som_get_stats(ctx):
-    """(rows_refined, rows_rescanned) of the most recent BMU search; synchronises the stream."""
-    out = (C.c_int64 * 2)()
+    """(rows_refined, rows_collected, rows_rescanned) of the most recent BMU search; synchronises."""
+    out = (C.c_int64 * 3)()
     _check(ctx, load().som_get_stats(ctx, out))
-    return int(out[0]), int(out[1])
+    return int(out[0]), int(out[1]), int(out[2])
 
 
 def som_profile_enable(ctx, on: bool) -> None:

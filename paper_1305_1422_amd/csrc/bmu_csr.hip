@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256) void k_bmu_csr(const int64_t *__restrict__ ind
         cand_n[j] = cnt;
         refine_list[atomicAdd(&list_counts[0], 1)] = (int32_t)j;
       } else {
-        rescan_list[atomicAdd(&list_counts[1], 1)] = (int32_t)j;
+        rescan_list[atomicAdd(&list_counts[2], 1)] = (int32_t)j;
       }
     }
     __syncthreads();

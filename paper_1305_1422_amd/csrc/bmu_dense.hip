@@ -2,23 +2,31 @@
 // between every instance and every node through the linear-algebra form of the Euclidean
 // distance).
 //
-// For instance x and node w the ranking score is s = |w|^2 - 2 x.w (|x|^2 is common to all
-// nodes).  The x.w contraction runs on the fp32 matrix cores (v_mfma_f32_32x32x2_f32); the
-// n x k score matrix is never stored.  The MFMA "M" side carries nodes and the "N" side
-// instances, so each lane owns one instance column of a 32x32 block and 16 of its node rows:
-// the running minimum over nodes needs no cross-lane traffic until the very end.
+// For instance x and node w the ranking score is s = |w'|^2 - 2 x'.w' with x' = x - mu and
+// w' = w - mu (|x'|^2 is common to all nodes; mu is a centring vector that leaves distances
+// unchanged and shrinks the rounding error, see norms.hip).  The x'.w' contraction runs on the
+// fp32 matrix cores (v_mfma_f32_32x32x2_f32); the n x k score matrix is never stored.  The MFMA
+// "M" side carries nodes and the "N" side instances, so each lane owns one instance column of a
+// 32x32 block and 16 of its node rows: the running minimum over nodes needs no cross-lane
+// traffic until the very end.
 //
 // fp32 scores cannot decide the BMU on their own: the rounding error of a long dot product is
-// of the order of the gap between the two best nodes.  The kernel is therefore a filter.  Per
-// instance it emits the kCand smallest scores with their nodes plus the smallest score it
-// dropped; an exact fp64 pass (bmu_exact.hip) decides among the candidates that lie within a
-// proven error bound of the minimum.  To keep that bound small the MFMA accumulator is flushed
-// into a second fp32 accumulator every kFlushK columns (two-level summation).
+// of the order of the gap between the two best nodes.  The kernel is therefore a filter with
+// two modes.
+//   filter:  per instance it emits the kCand smallest scores with their nodes plus the
+//            smallest score it dropped; bmu_exact.hip decides among the candidates that lie
+//            within a proven error bound of the minimum.
+//   collect: for the instances where a dropped score lies inside the bound too, the same
+//            sweep is repeated over just those instances (row indirection) and every node
+//            whose score is below the instance's threshold is appended to a list.
+// To keep the bound small the MFMA accumulator is flushed into a second fp32 accumulator every
+// kDenseAccumBlock columns (two-level summation).
 //
 // Work decomposition: one 256-thread workgroup owns kTI = 128 instances and sweeps all nodes
 // in blocks of kTN = 128; 2 x 2 wavefronts, each a 64 x 64 patch = 2 x 2 MFMA blocks.  Tiles of
 // both operands ([row][k], k contiguous, exactly the layout of X and W in memory) are staged
-// through double-buffered LDS in chunks of kBK = 32 columns, prefetched through registers.
+// through double-buffered LDS in chunks of kBK = 32 columns, prefetched through registers; the
+// centring vector is subtracted on the way.
 #include "som_internal.hpp"
 
 #include <math.h>
@@ -56,11 +64,12 @@ __device__ __forceinline__ bool cand_less(float a, int ai, float b, int bi) {
   return a < b || (a == b && (unsigned)ai < (unsigned)bi);
 }
 
+// Four consecutive columns c..c+3 of one row, zero outside the matrix.
 template <bool kVec4>
-__device__ __forceinline__ f32x4 load_row4(const float *__restrict__ base, int64_t row, int64_t nrows,
-                                           int dim, int c) {
+__device__ __forceinline__ f32x4 load_row4(const float *__restrict__ base, int64_t row, bool row_ok, int dim,
+                                           int c) {
   f32x4 r = {0.f, 0.f, 0.f, 0.f};
-  if (row < nrows) {
+  if (row_ok) {
     const float *p = base + row * dim + c;
     if (kVec4) {
       if (c < dim) r = *reinterpret_cast<const f32x4 *>(p);
@@ -74,10 +83,17 @@ __device__ __forceinline__ f32x4 load_row4(const float *__restrict__ base, int64
   return r;
 }
 
-template <bool kVec4>
+// kCollect == false: instances are rows inst0 .. of X; output = candidate lists (CandView).
+// kCollect == true : instances are X[rows[slot]] for slot < *n_slots; output = every node with
+//                    score <= thr[slot], appended to list[slot][..kListCap) with count cnt[slot].
+template <bool kVec4, bool kCollect>
 __global__ __launch_bounds__(256, 2) void k_bmu_dense(const float *__restrict__ X, const float *__restrict__ W,
+                                                      const float *__restrict__ mu,
                                                       const float *__restrict__ wn, int64_t n, int k, int dim,
-                                                      CandView out) {
+                                                      CandView out, const int32_t *__restrict__ rows,
+                                                      const int32_t *__restrict__ n_slots,
+                                                      const float *__restrict__ thr, int32_t *__restrict__ cnt,
+                                                      int32_t *__restrict__ list) {
   __shared__ __attribute__((aligned(16))) float sW[2][kTN * kLS];
   __shared__ __attribute__((aligned(16))) float sX[2][kTI * kLS];
   __shared__ float sWn[2][kTN];
@@ -90,23 +106,41 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense(const float *__restrict__ 
   const int l32 = lane & 31;
   const int lhi = lane >> 5;
   const int64_t inst0 = (int64_t)blockIdx.x * kTI;
+  const int64_t n_inst = kCollect ? (int64_t)*n_slots : n;
+  if (inst0 >= n_inst) return;       // uniform over the workgroup
 
+  // node blocks swept by this workgroup: all of them, or (collect mode) the blockIdx.y-th share
   const int nK = (dim + kBK - 1) / kBK;
-  const int nNB = (k + kTN - 1) / kTN;
+  const int nNB_all = (k + kTN - 1) / kTN;
+  const int nb_per = kCollect ? (nNB_all + (int)gridDim.y - 1) / (int)gridDim.y : nNB_all;
+  const int nb_first = kCollect ? (int)blockIdx.y * nb_per : 0;
+  const int nNB = min(nb_per, nNB_all - nb_first);
+  if (nNB <= 0) return;              // uniform over the workgroup
   const int total = nK * nNB;
 
   // loader coordinates: 4 float4 per operand per thread and chunk
   const int ld_row = tid >> 3;       // + 32 p
   const int ld_c4 = (tid & 7) * 4;
 
+  int64_t xrow[4];
+  bool xok[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int64_t slot = inst0 + ld_row + 32 * p;
+    xok[p] = slot < n_inst;
+    xrow[p] = kCollect ? (xok[p] ? (int64_t)rows[slot] : 0) : slot;
+  }
+
   f32x4 rw[4], rx[4];
   auto fetch = [&](int t) {
-    const int nb = t / nK, kc = t - nb * nK;
+    const int nb = nb_first + t / nK, kc = t % nK;
     const int c = kc * kBK + ld_c4;
+    const f32x4 m = load_row4<kVec4>(mu, 0, true, dim, c);
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      rw[p] = load_row4<kVec4>(W, (int64_t)nb * kTN + ld_row + 32 * p, k, dim, c);
-      rx[p] = load_row4<kVec4>(X, inst0 + ld_row + 32 * p, n, dim, c);
+      const int64_t node = (int64_t)nb * kTN + ld_row + 32 * p;
+      rw[p] = load_row4<kVec4>(W, node, node < k, dim, c) - m;
+      rx[p] = load_row4<kVec4>(X, xrow[p], xok[p], dim, c) - m;
     }
   };
   auto stage = [&](int t) {
@@ -116,18 +150,22 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense(const float *__restrict__ 
       *reinterpret_cast<f32x4 *>(&sW[buf][(ld_row + 32 * p) * kLS + ld_c4]) = rw[p];
       *reinterpret_cast<f32x4 *>(&sX[buf][(ld_row + 32 * p) * kLS + ld_c4]) = rx[p];
     }
-    const int nb = t / nK;
-    if (t - nb * nK == 0 && tid < kTN) {
+    const int nb = nb_first + t / nK;
+    if (t % nK == 0 && tid < kTN) {
       const int node = nb * kTN + tid;
       sWn[nb & 1][tid] = node < k ? wn[node] : INFINITY;    // padded nodes can never win
     }
   };
 
   Top2 top[2];
+  float lim[2];                       // collect mode: per-instance threshold
+  int64_t slot_of[2];
 #pragma unroll
   for (int ni = 0; ni < 2; ++ni) {
     top[ni].v0 = top[ni].v1 = top[ni].ov = INFINITY;
     top[ni].i0 = top[ni].i1 = -1;
+    slot_of[ni] = inst0 + wi * 64 + ni * 32 + l32;
+    lim[ni] = (kCollect && slot_of[ni] < n_inst) ? thr[slot_of[ni]] : -INFINITY;
   }
 
   f32x16 acc[2][2], tot[2][2];
@@ -146,7 +184,7 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense(const float *__restrict__ 
   const int b_off = (wi * 64 + l32) * kLS + lhi * 4;
 
   for (int t = 0; t < total; ++t) {
-    const int nb = t / nK, kc = t - nb * nK;
+    const int nb = nb_first + t / nK, kc = t % nK;
     if (t + 1 < total) fetch(t + 1);
 
     const float *pw = &sW[t & 1][a_off];
@@ -187,7 +225,15 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense(const float *__restrict__ 
           const int node = nb * kTN + nl;
 #pragma unroll
           for (int ni = 0; ni < 2; ++ni) {
-            top2_push(top[ni], fmaf(-2.f, tot[mi][ni][v], wnv), node);
+            const float s = fmaf(-2.f, tot[mi][ni][v], wnv);
+            if (kCollect) {
+              if (s <= lim[ni]) {
+                const int pos = atomicAdd(&cnt[slot_of[ni]], 1);
+                if (pos < kListCap) list[slot_of[ni] * kListCap + pos] = node;
+              }
+            } else {
+              top2_push(top[ni], s, node);
+            }
             tot[mi][ni][v] = 0.f;
           }
         }
@@ -196,6 +242,7 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense(const float *__restrict__ 
     if (t + 1 < total) stage(t + 1);
     __syncthreads();
   }
+  if (kCollect) return;
 
   // Merge the four partial lists of every instance (two node halves x two lane halves).
   float *mval = &sW[0][0];                                  // [kTI][4][3]
@@ -249,16 +296,38 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense(const float *__restrict__ 
   }
 }
 
+static bool use_vec4(const som_ctx *c, const float *X, const float *W) {
+  return (c->dim % 4 == 0) && (((uintptr_t)X | (uintptr_t)W | (uintptr_t)c->mu) % 16 == 0);
+}
+
 hipError_t launch_bmu_dense(som_ctx *c, const float *X, int64_t n, const float *W) {
   CandView out{c->cand_val, c->cand_idx, c->cand_over};
   const unsigned blocks = (unsigned)((n + kTI - 1) / kTI);
-  const bool vec4 = (c->dim % 4 == 0) && (((uintptr_t)X | (uintptr_t)W) % 16 == 0);
-  if (vec4)
-    hipLaunchKernelGGL(k_bmu_dense<true>, dim3(blocks), dim3(256), 0, c->stream, X, W, c->wn32, n, c->k,
-                       c->dim, out);
+  if (use_vec4(c, X, W))
+    hipLaunchKernelGGL((k_bmu_dense<true, false>), dim3(blocks), dim3(256), 0, c->stream, X, W, c->mu, c->wn32, n,
+                       c->k, c->dim, out, nullptr, nullptr, nullptr, nullptr, nullptr);
   else
-    hipLaunchKernelGGL(k_bmu_dense<false>, dim3(blocks), dim3(256), 0, c->stream, X, W, c->wn32, n, c->k,
-                       c->dim, out);
+    hipLaunchKernelGGL((k_bmu_dense<false, false>), dim3(blocks), dim3(256), 0, c->stream, X, W, c->mu, c->wn32, n,
+                       c->k, c->dim, out, nullptr, nullptr, nullptr, nullptr, nullptr);
+  return hipGetLastError();
+}
+
+// Repeats the sweep for the instances in c->collect_rows (their number is only known on the
+// device: the grid covers the worst case and surplus workgroups leave at once).
+hipError_t launch_bmu_dense_collect(som_ctx *c, const float *X, int64_t n, const float *W) {
+  CandView out{nullptr, nullptr, nullptr};
+  const unsigned blocks = (unsigned)((n + kTI - 1) / kTI);
+  // usually only a few instance tiles are live: share the node blocks out over up to 16 workgroups each
+  const int nNB = (c->k + kTN - 1) / kTN;
+  const unsigned splits = (unsigned)(nNB < 16 ? nNB : 16);
+  if (use_vec4(c, X, W))
+    hipLaunchKernelGGL((k_bmu_dense<true, true>), dim3(blocks, splits), dim3(256), 0, c->stream, X, W, c->mu, c->wn32, n,
+                       c->k, c->dim, out, c->collect_rows, c->list_counts + 1, c->collect_thr, c->collect_cnt,
+                       c->collect_list);
+  else
+    hipLaunchKernelGGL((k_bmu_dense<false, true>), dim3(blocks, splits), dim3(256), 0, c->stream, X, W, c->mu, c->wn32, n,
+                       c->k, c->dim, out, c->collect_rows, c->list_counts + 1, c->collect_thr, c->collect_cnt,
+                       c->collect_list);
   return hipGetLastError();
 }
 

@@ -1,20 +1,27 @@
 // Exact stage of the best-matching-unit search (paper: BMU equation, d = Euclidean distance).
 //
 // The fp32 pass leaves, per instance, a few candidate nodes with their scores
-// s = |w|^2 - 2 x.w and the smallest score it dropped.  Here:
+// s = |w'|^2 - 2 x'.w' (x' = x - mu, w' = w - mu) and the smallest score it dropped.  Here:
 //   certify  - bounds the rounding error of those scores; an instance whose best score beats
 //              everything else by more than twice the bound is decided on the spot;
 //   refine   - otherwise the candidates inside the bound are compared by their squared
-//              distances sum_c (x_c - w_c)^2 evaluated in fp64, lowest node index on exact ties;
-//   rescan   - if a dropped score lies inside the bound too, all nodes are compared that way.
-// The instance lists for refine and rescan are built with atomic counters, so their order
-// varies between runs; every instance is decided independently, so the BMUs do not.
+//              distances sum_c (x_c - w_c)^2 evaluated in fp64 on the original (uncentred)
+//              vectors, lowest node index on exact ties;
+//   collect  - if a dropped score lies inside the bound too, the fp32 sweep is repeated for
+//              that instance and every node under the threshold is listed (bmu_dense.hip),
+//              then the list is compared exactly;
+//   rescan   - if even that list overflows, all nodes are compared exactly.
+// The instance lists are built with atomic counters, so their order varies between runs;
+// every instance is decided independently, so the BMUs do not.
 //
-// Error bound of one fp32 score (u = 2^-24, g = roundings a product term can suffer):
-//   |s_fp32 - s| <= u [ (2 g + 2) |x| max|w| + 2 max|w|^2 ]
-// (dot product: g u sum|x_c w_c| <= g u |x||w|, doubled by the factor -2; rounding of the
-// stored |w|^2; rounding of the final multiply-add).  Dense MFMA pass with two-level
-// accumulation: g = block + ceil(dim / block) + 2.  Sparse FMA chain of len terms: g = len.
+// Error bound of one fp32 score (u = 2^-24, g = roundings a product term can suffer,
+// X = |x'|, Wm = max |w'| over the nodes, both norms taken of the fp32-rounded differences):
+//   |s_fp32 - s_exact| <= u [ (2 g + 2) X Wm + 2 Wm^2 + 2 (X + Wm)^2 ]
+// (dot product: g u sum|x'_c w'_c| <= g u X Wm, doubled by the factor -2; rounding of the stored
+// |w'|^2; rounding of the final multiply-add; and the last term for the rounding of the
+// differences x - mu, w - mu themselves, which moves a squared distance by at most
+// 2 u (X + Wm)^2).  Dense MFMA pass with two-level accumulation: g = block + ceil(dim / block) + 2.
+// Sparse FMA chain of len terms, no centring: g = len and the last term drops out.
 #include "som_internal.hpp"
 
 #include <math.h>
@@ -25,7 +32,7 @@ __device__ __forceinline__ double score_margin(double g, double xnorm2, double w
   const double u = 5.9604644775390625e-08;   // 2^-24
   const double xn = sqrt(xnorm2 * (1.0 + 1.2e-7));
   const double wm = sqrt(wmax2 * (1.0 + 1.2e-7));
-  const double bound = u * ((2.0 * g + 2.0) * xn * wm + 2.0 * wm * wm);
+  const double bound = u * ((2.0 * g + 2.0) * xn * wm + 2.0 * wm * wm + 2.0 * (xn + wm) * (xn + wm));
   return 2.125 * bound;          // both scores of a pair may err, plus slack for higher-order terms
 }
 
@@ -33,7 +40,9 @@ __global__ __launch_bounds__(256) void k_certify(CandView cand, const float *__r
                                                  const unsigned *__restrict__ wmax_bits, double g, int64_t n,
                                                  int32_t *__restrict__ bmus, int32_t *__restrict__ cand_n,
                                                  int32_t *__restrict__ refine_list,
-                                                 int32_t *__restrict__ rescan_list,
+                                                 int32_t *__restrict__ collect_rows,
+                                                 float *__restrict__ collect_thr,
+                                                 int32_t *__restrict__ collect_cnt,
                                                  int32_t *__restrict__ list_counts) {
   const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (j >= n) return;
@@ -55,7 +64,12 @@ __global__ __launch_bounds__(256) void k_certify(CandView cand, const float *__r
     if (id[t] >= 0 && (double)v[t] <= thr) keep[cnt++] = id[t];
   const bool overflow = (double)cand.over[j] <= thr;
   if (overflow || cnt == 0) {
-    rescan_list[atomicAdd(&list_counts[1], 1)] = (int32_t)j;
+    const int slot = atomicAdd(&list_counts[1], 1);
+    collect_rows[slot] = (int32_t)j;
+    float t32 = (float)thr;                     // round the threshold up: no score inside the margin is lost
+    if ((double)t32 < thr) t32 = nextafterf(t32, INFINITY);
+    collect_thr[slot] = cnt == 0 ? INFINITY : t32;
+    collect_cnt[slot] = 0;
   } else if (cnt == 1) {
     bmus[j] = keep[0];
   } else {
@@ -116,6 +130,38 @@ __global__ __launch_bounds__(256) void k_refine_dense(const float *__restrict__ 
   }
 }
 
+// Exact comparison of the collected lists: one wavefront per listed instance.  A list that
+// overflowed its capacity sends the instance on to the full rescan.
+__global__ __launch_bounds__(256) void k_refine_lists_dense(const float *__restrict__ X, const float *__restrict__ W,
+                                                            int dim, const int32_t *__restrict__ collect_rows,
+                                                            const int32_t *__restrict__ collect_cnt,
+                                                            const int32_t *__restrict__ collect_list,
+                                                            int32_t *__restrict__ rescan_list,
+                                                            int32_t *__restrict__ list_counts,
+                                                            int32_t *__restrict__ bmus) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int nwaves = gridDim.x * (blockDim.x / kWave);
+  const int count = list_counts[1];
+  for (int e = wave; e < count; e += nwaves) {
+    const int64_t j = collect_rows[e];
+    const int cn = collect_cnt[e];
+    if (cn > kListCap || cn == 0) {
+      if (lane == 0) rescan_list[atomicAdd(&list_counts[2], 1)] = (int32_t)j;
+      continue;
+    }
+    const int32_t *lst = collect_list + (int64_t)e * kListCap;
+    double best = INFINITY;
+    int arg = 0x7fffffff;
+    for (int t = 0; t < cn; ++t) {
+      const int i = lst[t];
+      const double d2 = sqdist_dense_wave(X + j * dim, W + (int64_t)i * dim, dim, lane);
+      if (d2 < best || (d2 == best && i < arg)) { best = d2; arg = i; }
+    }
+    if (lane == 0) bmus[j] = arg;
+  }
+}
+
 __global__ __launch_bounds__(256) void k_rescan_dense(const float *__restrict__ X, const float *__restrict__ W,
                                                       int dim, int k, const int32_t *__restrict__ rescan_list,
                                                       const int32_t *__restrict__ list_counts,
@@ -124,7 +170,7 @@ __global__ __launch_bounds__(256) void k_rescan_dense(const float *__restrict__ 
   __shared__ int s_arg[4];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
-  const int count = list_counts[1];
+  const int count = list_counts[2];
   for (int e = blockIdx.x; e < count; e += gridDim.x) {
     const int64_t j = rescan_list[e];
     const float *x = X + j * dim;
@@ -185,7 +231,7 @@ __global__ __launch_bounds__(256) void k_rescan_csr(const int64_t *__restrict__ 
   __shared__ int s_arg[4];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
-  const int count = list_counts[1];
+  const int count = list_counts[2];
   for (int e = blockIdx.x; e < count; e += gridDim.x) {
     const int64_t j = rescan_list[e];
     const int64_t s = indptr[j];
@@ -218,7 +264,14 @@ hipError_t launch_certify(som_ctx *c, int64_t n, int32_t *bmus) {
   CandView cand{c->cand_val, c->cand_idx, c->cand_over};
   const double g = (double)kDenseAccumBlock + (double)((c->dim + kDenseAccumBlock - 1) / kDenseAccumBlock) + 2.0;
   hipLaunchKernelGGL(k_certify, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, cand, c->xn32,
-                     c->wmax_bits, g, n, bmus, c->cand_n, c->refine_list, c->rescan_list, c->list_counts);
+                     c->wmax_bits, g, n, bmus, c->cand_n, c->refine_list, c->collect_rows, c->collect_thr,
+                     c->collect_cnt, c->list_counts);
+  return hipGetLastError();
+}
+
+hipError_t launch_refine_lists_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus) {
+  hipLaunchKernelGGL(k_refine_lists_dense, dim3(persistent_blocks(c, 1 << 20)), dim3(256), 0, c->stream, X, W,
+                     c->dim, c->collect_rows, c->collect_cnt, c->collect_list, c->rescan_list, c->list_counts, bmus);
   return hipGetLastError();
 }
 

@@ -1,15 +1,21 @@
-// Squared Euclidean norms of matrix rows (code-book nodes, dense instances, CSR instances).
+// Squared Euclidean norms of matrix rows (code-book nodes, dense instances, CSR instances) and
+// the centring vector of the dense BMU search.
 //
 // The BMU search ranks nodes by |w|^2 - 2 x.w (paper, "Parallelism": the GPU variant
-// evaluates Euclidean distances through linear algebra); |w|^2 is recomputed every epoch,
-// |x|^2 only bounds the rounding error of the fp32 scores.  One wavefront per row, fp64
-// accumulation, so each fp32 result carries a single rounding.
+// evaluates Euclidean distances through linear algebra).  Distances do not change when the
+// same vector mu is subtracted from instances and nodes, but the rounding error of the fp32
+// scores shrinks with |x - mu| |w - mu|, so the dense path works on x - mu and w - mu with mu
+// the mean of a sample of the instances.  Norms are taken of the fp32-rounded differences,
+// exactly as the BMU kernel forms them.  |w - mu|^2 is recomputed every epoch; |x - mu|^2
+// only bounds the rounding error.  One wavefront per row, fp64 accumulation, so each fp32
+// result carries a single rounding.
 #include "som_internal.hpp"
 
 namespace som {
 
 __global__ __launch_bounds__(256) void k_row_sqnorms(const float *__restrict__ A, int64_t nrows, int dim,
-                                                     float *__restrict__ out32, double *__restrict__ out64,
+                                                     const float *__restrict__ mu, float *__restrict__ out32,
+                                                     double *__restrict__ out64,
                                                      unsigned *__restrict__ max_bits) {
   const int lane = threadIdx.x & (kWave - 1);
   const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
@@ -17,9 +23,16 @@ __global__ __launch_bounds__(256) void k_row_sqnorms(const float *__restrict__ A
   for (int64_t r = wave; r < nrows; r += nwaves) {
     const float *a = A + r * dim;
     double s = 0.0;
-    for (int c = lane; c < dim; c += kWave) {
-      double v = (double)a[c];
-      s += v * v;
+    if (mu) {
+      for (int c = lane; c < dim; c += kWave) {
+        const float t = a[c] - mu[c];          // fp32 difference, as staged by the BMU kernel
+        s += (double)t * (double)t;
+      }
+    } else {
+      for (int c = lane; c < dim; c += kWave) {
+        double v = (double)a[c];
+        s += v * v;
+      }
     }
     s = wave_sum(s);
     if (lane == 0) {
@@ -48,6 +61,33 @@ __global__ __launch_bounds__(256) void k_csr_row_sqnorms(const int64_t *__restri
   }
 }
 
+// Column means of a strided sample of the rows, in two steps: kMeanSlabs partial sums per column,
+// then their total.  Any mu is valid for the search (the error bound uses the norms actually
+// obtained), so a sample of up to 8192 rows is enough.  fp64 sums in a fixed order: deterministic.
+constexpr int kMeanSlabs = 64;
+constexpr int kMeanRowsPerSlab = 128;
+
+__global__ __launch_bounds__(64) void k_sample_col_sums(const float *__restrict__ A, int64_t nsample,
+                                                        int64_t stride, int dim, double *__restrict__ partial) {
+  const int c = blockIdx.x * 64 + threadIdx.x;
+  if (c >= dim) return;
+  const int64_t per = (nsample + kMeanSlabs - 1) / kMeanSlabs;
+  const int64_t t0 = blockIdx.y * per;
+  const int64_t t1 = t0 + per < nsample ? t0 + per : nsample;
+  double s = 0.0;
+  for (int64_t t = t0; t < t1; ++t) s += (double)A[t * stride * dim + c];
+  partial[(int64_t)blockIdx.y * dim + c] = s;
+}
+
+__global__ __launch_bounds__(64) void k_finish_col_means(const double *__restrict__ partial, int64_t nsample,
+                                                         int dim, float *__restrict__ mu) {
+  const int c = blockIdx.x * 64 + threadIdx.x;
+  if (c >= dim) return;
+  double s = 0.0;
+  for (int b = 0; b < kMeanSlabs; ++b) s += partial[(int64_t)b * dim + c];
+  mu[c] = (float)(s / (double)nsample);
+}
+
 __global__ void k_zero_u32(unsigned *p, int64_t count) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -70,14 +110,25 @@ hipError_t launch_fill_zero_u32(hipStream_t s, void *p, int64_t count_u32) {
   return hipGetLastError();
 }
 
-hipError_t launch_row_sqnorms(som_ctx *c, const float *A, int64_t nrows, int dim, float *out32,
+hipError_t launch_sample_col_means(som_ctx *c, const float *A, int64_t nrows, int dim, float *mu) {
+  const int64_t cap = (int64_t)kMeanSlabs * kMeanRowsPerSlab;
+  const int64_t nsample = nrows < cap ? nrows : cap;
+  const int64_t stride = nrows / nsample;
+  hipLaunchKernelGGL(k_sample_col_sums, dim3((dim + 63) / 64, kMeanSlabs), dim3(64), 0, c->stream, A, nsample,
+                     stride, dim, c->mu_partial);
+  hipLaunchKernelGGL(k_finish_col_means, dim3((dim + 63) / 64), dim3(64), 0, c->stream, c->mu_partial, nsample,
+                     dim, mu);
+  return hipGetLastError();
+}
+
+hipError_t launch_row_sqnorms(som_ctx *c, const float *A, int64_t nrows, int dim, const float *mu, float *out32,
                               double *out64, unsigned *max_bits) {
   if (max_bits) {
     hipError_t e = launch_fill_zero_u32(c->stream, max_bits, 1);
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(k_row_sqnorms, dim3(grid_for_waves(c, nrows)), dim3(256), 0, c->stream, A, nrows, dim,
-                     out32, out64, max_bits);
+                     mu, out32, out64, max_bits);
   return hipGetLastError();
 }
 

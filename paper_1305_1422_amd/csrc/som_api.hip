@@ -53,6 +53,7 @@ static void dev_free(T *&p) {
 static void free_row_scratch(som_ctx *c) {
   dev_free(c->xn32); dev_free(c->cand_val); dev_free(c->cand_idx); dev_free(c->cand_over);
   dev_free(c->cand_n); dev_free(c->refine_list); dev_free(c->rescan_list);
+  dev_free(c->collect_rows); dev_free(c->collect_thr); dev_free(c->collect_cnt); dev_free(c->collect_list);
   dev_free(c->sort_key[0]); dev_free(c->sort_key[1]); dev_free(c->sort_val[0]); dev_free(c->sort_val[1]);
   dev_free(c->radix_hist); dev_free(c->chunk_node); dev_free(c->partial);
   c->n_cap = 0;
@@ -60,7 +61,7 @@ static void free_row_scratch(som_ctx *c) {
 
 // Scratch that scales with the number of instances; grown (never shrunk) on demand.
 static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
-  const bool need_partial = dense && c->partial == nullptr;
+  const bool need_partial = dense && (c->partial == nullptr || c->collect_list == nullptr);
   if (n <= c->n_cap && !need_partial) return SOM_OK;
   if (n > c->n_cap) {
     (void)hipStreamSynchronize(c->stream);
@@ -69,7 +70,8 @@ static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
     const size_t nblk = (N + kSortTile - 1) / kSortTile;
     bool ok = dev_alloc(&c->xn32, N) && dev_alloc(&c->cand_val, N * kCand) && dev_alloc(&c->cand_idx, N * kCand) &&
               dev_alloc(&c->cand_over, N) && dev_alloc(&c->cand_n, N) && dev_alloc(&c->refine_list, N) &&
-              dev_alloc(&c->rescan_list, N) && dev_alloc(&c->sort_key[0], N) && dev_alloc(&c->sort_key[1], N) &&
+              dev_alloc(&c->rescan_list, N) && dev_alloc(&c->collect_rows, N) && dev_alloc(&c->collect_thr, N) &&
+              dev_alloc(&c->collect_cnt, N) && dev_alloc(&c->sort_key[0], N) && dev_alloc(&c->sort_key[1], N) &&
               dev_alloc(&c->sort_val[0], N) && dev_alloc(&c->sort_val[1], N) &&
               dev_alloc(&c->radix_hist, 256 * nblk + 1);
     c->max_chunks = (int64_t)(N / kChunkRows) + c->k;
@@ -83,6 +85,10 @@ static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
   if (dense && c->partial == nullptr) {
     if (!dev_alloc(&c->partial, (size_t)c->max_chunks * c->dim))
       return fail(c, SOM_ERR_ALLOC, "cannot allocate %lld x %d partial sums", (long long)c->max_chunks, c->dim);
+  }
+  if (dense && c->collect_list == nullptr) {
+    if (!dev_alloc(&c->collect_list, (size_t)c->n_cap * kListCap))
+      return fail(c, SOM_ERR_ALLOC, "cannot allocate candidate lists for %lld instances", (long long)c->n_cap);
   }
   return SOM_OK;
 }
@@ -131,9 +137,12 @@ struct StageTimer {
 
 // ---------------------------------------------------------------- stages
 static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *W, int32_t *bmus, bool have_xn) {
-  SOM_LAUNCH(c, launch_row_sqnorms(c, W, c->k, c->dim, c->wn32, nullptr, c->wmax_bits));
-  if (!have_xn) SOM_LAUNCH(c, launch_row_sqnorms(c, X, n, c->dim, c->xn32, nullptr, nullptr));
-  SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 2));
+  if (!have_xn) {
+    SOM_LAUNCH(c, launch_sample_col_means(c, X, n, c->dim, c->mu));
+    SOM_LAUNCH(c, launch_row_sqnorms(c, X, n, c->dim, c->mu, c->xn32, nullptr, nullptr));
+  }
+  SOM_LAUNCH(c, launch_row_sqnorms(c, W, c->k, c->dim, c->mu, c->wn32, nullptr, c->wmax_bits));
+  SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 3));
   {
     StageTimer t(c, 0);
     SOM_LAUNCH(c, launch_bmu_dense(c, X, n, W));
@@ -141,6 +150,8 @@ static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *
   StageTimer t(c, 2);
   SOM_LAUNCH(c, launch_certify(c, n, bmus));
   SOM_LAUNCH(c, launch_refine_dense(c, X, W, bmus));
+  SOM_LAUNCH(c, launch_bmu_dense_collect(c, X, n, W));
+  SOM_LAUNCH(c, launch_refine_lists_dense(c, X, W, bmus));
   SOM_LAUNCH(c, launch_rescan_dense(c, X, W, bmus));
   return SOM_OK;
 }
@@ -149,9 +160,9 @@ static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indi
                           int64_t n, const float *W, int32_t *bmus, bool have_xn) {
   int rc = ensure_transposed(c);
   if (rc) return rc;
-  SOM_LAUNCH(c, launch_row_sqnorms(c, W, c->k, c->dim, c->wn32, c->wn64, c->wmax_bits));
+  SOM_LAUNCH(c, launch_row_sqnorms(c, W, c->k, c->dim, nullptr, c->wn32, c->wn64, c->wmax_bits));
   if (!have_xn) SOM_LAUNCH(c, launch_csr_row_sqnorms(c, indptr, values, n, c->xn32));
-  SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 2));
+  SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 3));
   {
     StageTimer t(c, 1);
     SOM_LAUNCH(c, launch_transpose_codebook(c, W));
@@ -222,13 +233,14 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
   bool ok = dev_alloc(&c->wn32, K) && dev_alloc(&c->wn64, K) && dev_alloc(&c->wmax_bits, 1) &&
             dev_alloc(&c->counts, K + 1) && dev_alloc(&c->seg_off, K + 1) && dev_alloc(&c->chunk_off, K + 1) &&
             dev_alloc(&c->massD, K) && dev_alloc(&c->cntT, 2 * K) && dev_alloc(&c->gx, 2 * (size_t)cols + 1) &&
-            dev_alloc(&c->gy, (size_t)rows) && dev_alloc(&c->params, 1) && dev_alloc(&c->list_counts, 2) &&
+            dev_alloc(&c->gy, (size_t)rows) && dev_alloc(&c->params, 1) && dev_alloc(&c->list_counts, 4) &&
+            dev_alloc(&c->mu, (size_t)dim) && dev_alloc(&c->mu_partial, (size_t)64 * dim) &&
             dev_alloc(&c->S, K * dim) && dev_alloc(&c->T, images * K * dim);
   if (!ok) {
     som_destroy(c);
     return fail(nullptr, SOM_ERR_ALLOC, "cannot allocate map scratch (%d nodes x %d)", c->k, dim);
   }
-  hipError_t e = launch_fill_zero_u32(c->stream, c->list_counts, 2);
+  hipError_t e = launch_fill_zero_u32(c->stream, c->list_counts, 4);
   if (e == hipSuccess && seed != 0) e = launch_fill_uniform(c, codebook, (int64_t)c->k * dim, seed);
   if (e != hipSuccess) {
     int rc = dev_fail(nullptr, e, "som_init");
@@ -246,6 +258,7 @@ void som_destroy(som_ctx *c) {
   dev_free(c->wn32); dev_free(c->wn64); dev_free(c->wmax_bits); dev_free(c->counts); dev_free(c->seg_off);
   dev_free(c->chunk_off); dev_free(c->massD); dev_free(c->cntT); dev_free(c->gx); dev_free(c->gy);
   dev_free(c->params); dev_free(c->list_counts); dev_free(c->S); dev_free(c->T); dev_free(c->Wt);
+  dev_free(c->mu); dev_free(c->mu_partial);
   for (int s = 0; s < SOM_PROFILE_STAGES; ++s) {
     if (!c->prof_ev[s]) continue;
     for (int e = 0; e < 2 * kProfMax; ++e) (void)hipEventDestroy(c->prof_ev[s][e]);
@@ -260,7 +273,7 @@ int som_bmus_dense(som_ctx *c, const float *data, int64_t n, const float *codebo
   if (!c) return SOM_ERR_INVALID_ARG;
   if (!data || !codebook || !bmus) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
   int rc = check_rows(c, n);
-  if (!rc) rc = ensure_rows(c, n, false);
+  if (!rc) rc = ensure_rows(c, n, true);
   if (rc) return rc;
   return bmu_search_dense(c, data, n, codebook, bmus, false);
 }
@@ -371,9 +384,10 @@ int som_train(som_ctx *c, int n_epochs, float radius0, float radiusN, float scal
   const bool dense = c->data_kind == 1;
   int rc = ensure_rows(c, c->d_n, dense);
   if (rc) return rc;
-  if (dense)
-    SOM_LAUNCH(c, launch_row_sqnorms(c, c->d_data, c->d_n, c->dim, c->xn32, nullptr, nullptr));
-  else
+  if (dense) {
+    SOM_LAUNCH(c, launch_sample_col_means(c, c->d_data, c->d_n, c->dim, c->mu));
+    SOM_LAUNCH(c, launch_row_sqnorms(c, c->d_data, c->d_n, c->dim, c->mu, c->xn32, nullptr, nullptr));
+  } else
     SOM_LAUNCH(c, launch_csr_row_sqnorms(c, c->d_indptr, c->d_values, c->d_n, c->xn32));
   for (int e = 0; e < n_epochs; ++e) {
     SOM_LAUNCH(c, launch_epoch_params(c, e, n_epochs, radius0, radiusN, scale0, scaleN, cooling));
@@ -411,12 +425,13 @@ int som_umatrix(som_ctx *c, const float *codebook, float *umatrix) {
 int som_get_stats(som_ctx *c, int64_t *out) {
   if (!c) return SOM_ERR_INVALID_ARG;
   if (!out) return fail(c, SOM_ERR_INVALID_ARG, "out is NULL");
-  int32_t h[2] = {0, 0};
+  int32_t h[3] = {0, 0, 0};
   hipError_t e = hipMemcpyAsync(h, c->list_counts, sizeof(h), hipMemcpyDeviceToHost, c->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
   if (e != hipSuccess) return dev_fail(c, e, "som_get_stats");
   out[0] = h[0];
   out[1] = h[1];
+  out[2] = h[2];
   return SOM_OK;
 }
 

@@ -13,6 +13,7 @@ namespace som {
 // ---------------------------------------------------------------- constants
 constexpr int kWave = 64;                 // CDNA wavefront width
 constexpr int kCand = 4;                  // candidate nodes kept per instance by the fp32 pass
+constexpr int kListCap = 64;              // nodes a collected candidate list can hold per instance
 constexpr int kChunkRows = 32;            // instances summed by one block of the segmented accumulation
 constexpr int kSortTile = 1024;           // keys ranked by one wave of the radix scatter
 constexpr int kProfMax = 512;              // event brackets kept per stage between two reads
@@ -58,6 +59,8 @@ struct som_ctx {
   float *T;               // [1 or 2][k][dim] sums after the pass along x
   float *Wt;              // [dim][kpad] transposed code book (sparse BMU only, lazily allocated)
   int kpad;
+  float *mu;              // [dim] centring vector of the dense BMU search
+  double *mu_partial;     // [64][dim] partial column sums
 
   // per-data scratch (grown on demand to n_cap rows)
   int64_t n_cap;
@@ -66,9 +69,13 @@ struct som_ctx {
   int32_t *cand_idx;      // [n][kCand]
   float *cand_over;       // [n]
   int32_t *cand_n;        // [n] number of candidates to evaluate exactly
-  int32_t *refine_list;   // [n]
-  int32_t *rescan_list;   // [n]
-  int32_t *list_counts;   // [2] lengths of refine_list, rescan_list
+  int32_t *refine_list;   // [n] instances with 2..kCand candidates
+  int32_t *collect_rows;  // [n] instances whose candidates have to be collected by a second sweep
+  float *collect_thr;     // [n] their score thresholds (indexed by slot in collect_rows)
+  int32_t *collect_cnt;   // [n] nodes found under the threshold
+  int32_t *collect_list;  // [n][kListCap] those nodes (dense path only, lazily allocated)
+  int32_t *rescan_list;   // [n] instances that need an exact scan of all nodes
+  int32_t *list_counts;   // [3] lengths of refine_list, collect_rows, rescan_list
   int32_t *sort_key[2];   // [n] each
   int32_t *sort_val[2];   // [n] each
   int32_t *radix_hist;    // [256 * sort blocks]
@@ -97,17 +104,20 @@ namespace som {
 // Every launcher enqueues on ctx->stream and returns hipGetLastError().
 
 // norms.hip
-hipError_t launch_row_sqnorms(som_ctx *c, const float *A, int64_t nrows, int dim, float *out32,
-                              double *out64, unsigned *max_bits);
+hipError_t launch_sample_col_means(som_ctx *c, const float *A, int64_t nrows, int dim, float *mu);
+hipError_t launch_row_sqnorms(som_ctx *c, const float *A, int64_t nrows, int dim, const float *mu,
+                              float *out32, double *out64, unsigned *max_bits);
 hipError_t launch_csr_row_sqnorms(som_ctx *c, const int64_t *indptr, const float *values, int64_t n,
                                   float *out32);
 
 // bmu_dense.hip
 hipError_t launch_bmu_dense(som_ctx *c, const float *X, int64_t n, const float *W);
+hipError_t launch_bmu_dense_collect(som_ctx *c, const float *X, int64_t n, const float *W);
 
 // bmu_exact.hip
 hipError_t launch_certify(som_ctx *c, int64_t n, int32_t *bmus);
 hipError_t launch_refine_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
+hipError_t launch_refine_lists_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
 hipError_t launch_rescan_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
 hipError_t launch_refine_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices,
                              const float *values, const float *W, int32_t *bmus);
