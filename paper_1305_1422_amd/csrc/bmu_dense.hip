@@ -22,8 +22,11 @@
 // To keep the bound small the MFMA accumulator is flushed into a second fp32 accumulator every
 // kDenseAccumBlock columns (two-level summation).
 //
-// Work decomposition: one 256-thread workgroup owns kTI = 128 instances and sweeps all nodes
-// in blocks of kTN = 128; 2 x 2 wavefronts, each a 64 x 64 patch = 2 x 2 MFMA blocks.  Tiles of
+// Work decomposition: one 256-thread workgroup owns kTI = 128 instances and sweeps one group of
+// node blocks of kTN = 128 nodes each; 2 x 2 wavefronts, each a 64 x 64 patch = 2 x 2 MFMA
+// blocks.  The node groups (grid y) exist for load balance only: with few, long workgroups the
+// last round of workgroups leaves most compute units idle.  Workgroups that run at the same
+// time share a node group, so its weight vectors stay in every L2.  Tiles of
 // both operands ([row][k], k contiguous, exactly the layout of X and W in memory) are staged
 // through double-buffered LDS in chunks of kBK = 32 columns, prefetched through registers; the
 // centring vector is subtracted on the way.
@@ -109,11 +112,11 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense(const float *__restrict__ 
   const int64_t n_inst = kCollect ? (int64_t)*n_slots : n;
   if (inst0 >= n_inst) return;       // uniform over the workgroup
 
-  // node blocks swept by this workgroup: all of them, or (collect mode) the blockIdx.y-th share
+  // node blocks swept by this workgroup: the blockIdx.y-th share of them (node group)
   const int nK = (dim + kBK - 1) / kBK;
   const int nNB_all = (k + kTN - 1) / kTN;
-  const int nb_per = kCollect ? (nNB_all + (int)gridDim.y - 1) / (int)gridDim.y : nNB_all;
-  const int nb_first = kCollect ? (int)blockIdx.y * nb_per : 0;
+  const int nb_per = (nNB_all + (int)gridDim.y - 1) / (int)gridDim.y;
+  const int nb_first = (int)blockIdx.y * nb_per;
   const int nNB = min(nb_per, nNB_all - nb_first);
   if (nNB <= 0) return;              // uniform over the workgroup
   const int total = nK * nNB;
@@ -131,24 +134,26 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense(const float *__restrict__ 
     xrow[p] = kCollect ? (xok[p] ? (int64_t)rows[slot] : 0) : slot;
   }
 
-  f32x4 rw[4], rx[4];
+  // fetch() only issues the global loads; the centring subtraction happens in stage(), after the
+  // MFMA work of the current chunk, so that the load latency stays hidden behind that work.
+  f32x4 rw[4], rx[4], rm;
   auto fetch = [&](int t) {
     const int nb = nb_first + t / nK, kc = t % nK;
     const int c = kc * kBK + ld_c4;
-    const f32x4 m = load_row4<kVec4>(mu, 0, true, dim, c);
+    rm = load_row4<kVec4>(mu, 0, true, dim, c);
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
       const int64_t node = (int64_t)nb * kTN + ld_row + 32 * p;
-      rw[p] = load_row4<kVec4>(W, node, node < k, dim, c) - m;
-      rx[p] = load_row4<kVec4>(X, xrow[p], xok[p], dim, c) - m;
+      rw[p] = load_row4<kVec4>(W, node, node < k, dim, c);
+      rx[p] = load_row4<kVec4>(X, xrow[p], xok[p], dim, c);
     }
   };
   auto stage = [&](int t) {
     const int buf = t & 1;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      *reinterpret_cast<f32x4 *>(&sW[buf][(ld_row + 32 * p) * kLS + ld_c4]) = rw[p];
-      *reinterpret_cast<f32x4 *>(&sX[buf][(ld_row + 32 * p) * kLS + ld_c4]) = rx[p];
+      *reinterpret_cast<f32x4 *>(&sW[buf][(ld_row + 32 * p) * kLS + ld_c4]) = rw[p] - rm;
+      *reinterpret_cast<f32x4 *>(&sX[buf][(ld_row + 32 * p) * kLS + ld_c4]) = rx[p] - rm;
     }
     const int nb = nb_first + t / nK;
     if (t % nK == 0 && tid < kTN) {
@@ -286,7 +291,7 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense(const float *__restrict__ 
         if (c[0]) { v[0] = x; id[0] = xi; }
       }
     }
-    const int64_t j = inst0 + tid;
+    const int64_t j = (int64_t)blockIdx.y * n + inst0 + tid;      // lists are stored [node group][instance]
 #pragma unroll
     for (int t = 0; t < kCand; ++t) {
       out.val[j * kCand + t] = v[t];
@@ -300,15 +305,29 @@ static bool use_vec4(const som_ctx *c, const float *X, const float *W) {
   return (c->dim % 4 == 0) && (((uintptr_t)X | (uintptr_t)W | (uintptr_t)c->mu) % 16 == 0);
 }
 
+// Number of node groups for n instances: enough workgroups for about eight rounds over the chip.
+int bmu_dense_groups(const som_ctx *c, int64_t n) {
+  const int64_t tiles = (n + kTI - 1) / kTI;
+  const int nNB = (c->k + kTN - 1) / kTN;
+  const int64_t slots = 2ll * c->n_cu;
+  int64_t want = (8 * slots + tiles - 1) / tiles;
+  if (want > nNB) want = nNB;
+  if (want > 64) want = 64;
+  if (want < 1) want = 1;
+  const int nb_per = (int)((nNB + want - 1) / want);
+  return (nNB + nb_per - 1) / nb_per;
+}
+
 hipError_t launch_bmu_dense(som_ctx *c, const float *X, int64_t n, const float *W) {
   CandView out{c->cand_val, c->cand_idx, c->cand_over};
   const unsigned blocks = (unsigned)((n + kTI - 1) / kTI);
+  const unsigned groups = (unsigned)bmu_dense_groups(c, n);
   if (use_vec4(c, X, W))
-    hipLaunchKernelGGL((k_bmu_dense<true, false>), dim3(blocks), dim3(256), 0, c->stream, X, W, c->mu, c->wn32, n,
-                       c->k, c->dim, out, nullptr, nullptr, nullptr, nullptr, nullptr);
+    hipLaunchKernelGGL((k_bmu_dense<true, false>), dim3(blocks, groups), dim3(256), 0, c->stream, X, W, c->mu,
+                       c->wn32, n, c->k, c->dim, out, nullptr, nullptr, nullptr, nullptr, nullptr);
   else
-    hipLaunchKernelGGL((k_bmu_dense<false, false>), dim3(blocks), dim3(256), 0, c->stream, X, W, c->mu, c->wn32, n,
-                       c->k, c->dim, out, nullptr, nullptr, nullptr, nullptr, nullptr);
+    hipLaunchKernelGGL((k_bmu_dense<false, false>), dim3(blocks, groups), dim3(256), 0, c->stream, X, W, c->mu,
+                       c->wn32, n, c->k, c->dim, out, nullptr, nullptr, nullptr, nullptr, nullptr);
   return hipGetLastError();
 }
 

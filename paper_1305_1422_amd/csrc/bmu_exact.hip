@@ -36,7 +36,9 @@ __device__ __forceinline__ double score_margin(double g, double xnorm2, double w
   return 2.125 * bound;          // both scores of a pair may err, plus slack for higher-order terms
 }
 
-__global__ __launch_bounds__(256) void k_certify(CandView cand, const float *__restrict__ xn32,
+// `groups` candidate lists per instance (one per node group of the fp32 pass), stored
+// [group][instance][kCand]; the kept candidates are written back into group 0's slots.
+__global__ __launch_bounds__(256) void k_certify(CandView cand, int groups, const float *__restrict__ xn32,
                                                  const unsigned *__restrict__ wmax_bits, double g, int64_t n,
                                                  int32_t *__restrict__ bmus, int32_t *__restrict__ cand_n,
                                                  int32_t *__restrict__ refine_list,
@@ -46,23 +48,30 @@ __global__ __launch_bounds__(256) void k_certify(CandView cand, const float *__r
                                                  int32_t *__restrict__ list_counts) {
   const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (j >= n) return;
-  float v[kCand];
-  int id[kCand];
-  float smin = INFINITY;
+  float smin = INFINITY, omin = INFINITY;
+  for (int q = 0; q < groups; ++q) {
+    const int64_t base = ((int64_t)q * n + j) * kCand;
 #pragma unroll
-  for (int t = 0; t < kCand; ++t) {
-    v[t] = cand.val[j * kCand + t];
-    id[t] = cand.idx[j * kCand + t];
-    if (id[t] >= 0) smin = fminf(smin, v[t]);
+    for (int t = 0; t < kCand; ++t)
+      if (cand.idx[base + t] >= 0) smin = fminf(smin, cand.val[base + t]);
+    omin = fminf(omin, cand.over[(int64_t)q * n + j]);
   }
   const double margin = score_margin(g, (double)xn32[j], (double)__uint_as_float(*wmax_bits));
   const double thr = (double)smin + margin;
   int keep[kCand];
   int cnt = 0;
+  for (int q = 0; q < groups; ++q) {
+    const int64_t base = ((int64_t)q * n + j) * kCand;
 #pragma unroll
-  for (int t = 0; t < kCand; ++t)
-    if (id[t] >= 0 && (double)v[t] <= thr) keep[cnt++] = id[t];
-  const bool overflow = (double)cand.over[j] <= thr;
+    for (int t = 0; t < kCand; ++t) {
+      const int id = cand.idx[base + t];
+      if (id >= 0 && (double)cand.val[base + t] <= thr) {
+        if (cnt < kCand) keep[cnt] = id;
+        ++cnt;
+      }
+    }
+  }
+  const bool overflow = (double)omin <= thr || cnt > kCand;
   if (overflow || cnt == 0) {
     const int slot = atomicAdd(&list_counts[1], 1);
     collect_rows[slot] = (int32_t)j;
@@ -263,8 +272,8 @@ static int persistent_blocks(const som_ctx *c, int64_t upper) {
 hipError_t launch_certify(som_ctx *c, int64_t n, int32_t *bmus) {
   CandView cand{c->cand_val, c->cand_idx, c->cand_over};
   const double g = (double)kDenseAccumBlock + (double)((c->dim + kDenseAccumBlock - 1) / kDenseAccumBlock) + 2.0;
-  hipLaunchKernelGGL(k_certify, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, cand, c->xn32,
-                     c->wmax_bits, g, n, bmus, c->cand_n, c->refine_list, c->collect_rows, c->collect_thr,
+  hipLaunchKernelGGL(k_certify, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, cand,
+                     bmu_dense_groups(c, n), c->xn32, c->wmax_bits, g, n, bmus, c->cand_n, c->refine_list, c->collect_rows, c->collect_thr,
                      c->collect_cnt, c->list_counts);
   return hipGetLastError();
 }

@@ -57,6 +57,7 @@ static void free_row_scratch(som_ctx *c) {
   dev_free(c->sort_key[0]); dev_free(c->sort_key[1]); dev_free(c->sort_val[0]); dev_free(c->sort_val[1]);
   dev_free(c->radix_hist); dev_free(c->chunk_node); dev_free(c->partial);
   c->n_cap = 0;
+  c->cand_cap = 0;
 }
 
 // Scratch that scales with the number of instances; grown (never shrunk) on demand.
@@ -81,6 +82,7 @@ static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
       return fail(c, SOM_ERR_ALLOC, "cannot allocate scratch for %lld instances", (long long)n);
     }
     c->n_cap = n;
+    c->cand_cap = n;
   }
   if (dense && c->partial == nullptr) {
     if (!dev_alloc(&c->partial, (size_t)c->max_chunks * c->dim))
@@ -90,6 +92,20 @@ static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
     if (!dev_alloc(&c->collect_list, (size_t)c->n_cap * kListCap))
       return fail(c, SOM_ERR_ALLOC, "cannot allocate candidate lists for %lld instances", (long long)c->n_cap);
   }
+  return SOM_OK;
+}
+
+// The dense fp32 pass writes one candidate list per node group and instance.
+static int ensure_candidates(som_ctx *c, int64_t n) {
+  const int64_t need = (int64_t)bmu_dense_groups(c, n) * n;
+  if (need <= c->cand_cap) return SOM_OK;
+  (void)hipStreamSynchronize(c->stream);
+  dev_free(c->cand_val); dev_free(c->cand_idx); dev_free(c->cand_over);
+  c->cand_cap = 0;
+  if (!(dev_alloc(&c->cand_val, (size_t)need * kCand) && dev_alloc(&c->cand_idx, (size_t)need * kCand) &&
+        dev_alloc(&c->cand_over, (size_t)need)))
+    return fail(c, SOM_ERR_ALLOC, "cannot allocate candidate lists for %lld slots", (long long)need);
+  c->cand_cap = need;
   return SOM_OK;
 }
 
@@ -137,6 +153,8 @@ struct StageTimer {
 
 // ---------------------------------------------------------------- stages
 static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *W, int32_t *bmus, bool have_xn) {
+  int rc = ensure_candidates(c, n);
+  if (rc) return rc;
   if (!have_xn) {
     SOM_LAUNCH(c, launch_sample_col_means(c, X, n, c->dim, c->mu));
     SOM_LAUNCH(c, launch_row_sqnorms(c, X, n, c->dim, c->mu, c->xn32, nullptr, nullptr));

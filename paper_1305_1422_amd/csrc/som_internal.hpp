@@ -65,9 +65,10 @@ struct som_ctx {
   // per-data scratch (grown on demand to n_cap rows)
   int64_t n_cap;
   float *xn32;            // [n] squared norms of the instances
-  float *cand_val;        // [n][kCand]
-  int32_t *cand_idx;      // [n][kCand]
-  float *cand_over;       // [n]
+  int64_t cand_cap;       // instance slots in the three candidate arrays (node groups x instances)
+  float *cand_val;        // [groups][n][kCand]
+  int32_t *cand_idx;      // [groups][n][kCand]
+  float *cand_over;       // [groups][n]
   int32_t *cand_n;        // [n] number of candidates to evaluate exactly
   int32_t *refine_list;   // [n] instances with 2..kCand candidates
   int32_t *collect_rows;  // [n] instances whose candidates have to be collected by a second sweep
@@ -111,6 +112,7 @@ hipError_t launch_csr_row_sqnorms(som_ctx *c, const int64_t *indptr, const float
                                   float *out32);
 
 // bmu_dense.hip
+int bmu_dense_groups(const som_ctx *c, int64_t n);
 hipError_t launch_bmu_dense(som_ctx *c, const float *X, int64_t n, const float *W);
 hipError_t launch_bmu_dense_collect(som_ctx *c, const float *X, int64_t n, const float *W);
 
