@@ -81,6 +81,11 @@ def main() -> int:
     W0d = torch.from_numpy(W0).to(dev)
     som = Som(w.rows, w.cols, w.dim, w.map_type, w.grid_type, codebook=W0d)
     bmus = torch.empty(w.n, dtype=torch.int32, device=dev)
+    # register the resident training set: its norms are then computed once, not every epoch
+    if w.kind == "dense":
+        capi.som_set_data_dense(som.ctx, Xd)
+    else:
+        capi.som_set_data_csr(som.ctx, *Xd)
     radii = [w.radius0 + (w.radiusN - w.radius0) * e / max(1, w.epochs - 1) for e in range(w.epochs)]
 
     def step(s: int):

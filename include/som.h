@@ -130,6 +130,10 @@ int som_update_csr(som_ctx *ctx, const int64_t *indptr, const int32_t *indices, 
  * som_set_data_dense / som_set_data_csr - register the training set som_train works on.
  * The pointers are borrowed until the next som_set_data_* or som_destroy; the data must
  * stay unchanged meanwhile.  Arguments as in the epoch calls.
+ * Per-instance quantities that depend on the data alone (squared norms, the centring vector
+ * of the dense search) are computed once per registration, on first use.  The epoch and
+ * BMU calls reuse them when they are handed the registered pointer(s) and n; on any other
+ * data they recompute them on every call.
  */
 int som_set_data_dense(som_ctx *ctx, const float *data, int64_t n);
 int som_set_data_csr(som_ctx *ctx, const int64_t *indptr, const int32_t *indices,

@@ -3,9 +3,9 @@
 //
 // The neighbourhood weight of an instance depends on it only through its BMU, so the update
 // needs S_b = sum of the instances whose BMU is b and C_b = their number.  Dense data:
-//   1. C_b by integer atomics, exclusive scan -> segment offsets;
-//   2. stable LSD radix sort of the instance ids by BMU (8-bit digits, ballot-based ranking),
+//   1. stable LSD radix sort of the instance ids by BMU (8-bit digits, ballot-based ranking),
 //      so every segment lists its instances in ascending order;
+//   2. segment offsets by binary search in the sorted keys, C_b = their differences;
 //   3. every segment is cut into chunks of kChunkRows instances; one workgroup sums one chunk
 //      (fp64 registers, instances read as whole rows through the permutation);
 //   4. chunks of a node are added in order.
@@ -19,11 +19,48 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ int clamp_node(int b, int k) { return b < 0 ? 0 : (b >= k ? k - 1 : b); }
 
+// C_b for the sparse path.  Trained maps send most instances to few nodes, so the lanes of a
+// wavefront that hold the same node are merged into one atomic add.
 __global__ __launch_bounds__(256) void k_count_bmus(const int32_t *__restrict__ bmus, int64_t n, int k,
                                                     int32_t *__restrict__ counts) {
-  int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int lane = threadIdx.x & 63;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (; j < n; j += stride) atomicAdd(&counts[clamp_node(bmus[j], k)], 1);
+  const int64_t rounds = (n + stride - 1) / stride;
+  for (int64_t r = 0; r < rounds; ++r) {
+    const int64_t j = r * stride + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    bool pending = j < n;
+    const int b = pending ? clamp_node(bmus[j], k) : 0;
+    unsigned long long todo = __ballot(pending);
+    while (todo) {
+      const int leader = __ffsll((long long)todo) - 1;
+      const int lb = __shfl(b, leader, 64);
+      const unsigned long long same = __ballot(pending && b == lb);
+      if (lane == leader) atomicAdd(&counts[lb], __popcll(same));
+      if (pending && b == lb) pending = false;
+      todo &= ~same;
+    }
+  }
+}
+
+// Segment offsets of the sorted keys: seg_off[b] = first position whose key is >= b.
+__global__ __launch_bounds__(256) void k_segment_bounds(const int32_t *__restrict__ sorted_keys, int64_t n, int k,
+                                                        int32_t *__restrict__ seg_off,
+                                                        int32_t *__restrict__ counts) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= k) return;
+  int bound[2];
+#pragma unroll
+  for (int e = 0; e < 2; ++e) {
+    int64_t lo = 0, hi = n;
+    while (lo < hi) {
+      const int64_t mid = (lo + hi) >> 1;
+      if (sorted_keys[mid] < b + e) lo = mid + 1; else hi = mid;
+    }
+    bound[e] = (int)lo;
+  }
+  seg_off[b] = bound[0];
+  counts[b] = bound[1] - bound[0];
+  if (b == k - 1) seg_off[k] = (int32_t)n;
 }
 
 // Exclusive scan of in[0..len) into out[0..len], out[len] = total.  One workgroup of 1024.
@@ -161,17 +198,24 @@ __global__ __launch_bounds__(256) void k_accumulate_dense(const float *__restric
   }
 }
 
-// Empty node: zero row.  One chunk: already written.  Several: add the partial rows in order.
+// Empty node: zero row.  One chunk: already written.  Several: add the partial rows, eight
+// interleaved running sums (chunk t goes to sum t mod 8) combined pairwise at the end: a fixed
+// order, with eight loads in flight instead of one.
 __global__ __launch_bounds__(256) void k_combine_chunks(const int32_t *__restrict__ chunk_off, int dim,
                                                         const float *__restrict__ partial, float *__restrict__ S) {
   const int b = blockIdx.x;
   const int c0 = chunk_off[b], nc = chunk_off[b + 1] - c0;
   if (nc == 1) return;
   float *dst = S + (int64_t)b * dim;
+  const float *src = partial + (int64_t)c0 * dim;
   for (int c = threadIdx.x; c < dim; c += blockDim.x) {
-    double a = 0;
-    for (int t = 0; t < nc; ++t) a += (double)partial[(int64_t)(c0 + t) * dim + c];
-    dst[c] = (float)a;
+    double a[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    int t = 0;
+    for (; t + 8 <= nc; t += 8)
+#pragma unroll
+      for (int u = 0; u < 8; ++u) a[u] += (double)src[(int64_t)(t + u) * dim + c];
+    for (int u = 0; t < nc; ++t, ++u) a[u] += (double)src[(int64_t)t * dim + c];
+    dst[c] = (float)(((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7])));
   }
 }
 
@@ -198,21 +242,14 @@ static int radix_passes(int k) {
   return (bits + 7) / 8;
 }
 
-// Counts, segment offsets and the stable permutation of instance ids by BMU.
-// On return c->sort_val[0] holds the permutation.
+// Stable permutation of instance ids by BMU, segment offsets and counts.
+// On return c->sort_val[0] holds the permutation (c->sort_key[0] the sorted BMUs).
 hipError_t launch_sort_by_bmu(som_ctx *c, const int32_t *bmus, int64_t n) {
-  hipError_t e = launch_fill_zero_u32(c->stream, c->counts, c->k);
-  if (e != hipSuccess) return e;
-  int64_t cb = (n + 255) / 256;
-  if (cb > (int64_t)c->n_cu * 16) cb = (int64_t)c->n_cu * 16;
-  hipLaunchKernelGGL(k_count_bmus, dim3((unsigned)cb), dim3(256), 0, c->stream, bmus, n, c->k, c->counts);
-  hipLaunchKernelGGL(k_scan_exclusive, dim3(1), dim3(1024), 0, c->stream, c->counts, c->seg_off, c->k, 0);
-
   const int nblk = (int)((n + kSortTile - 1) / kSortTile);
   const int passes = radix_passes(c->k);
   const int32_t *kin = bmus;
   const int32_t *vin = nullptr;
-  // an even number of hops ends in buffer 0: start in buffer 1 when the pass count is odd
+  // an even number of hops ends in buffer 0: start in buffer 1 when the pass count is even
   int dst = (passes % 2 == 0) ? 1 : 0;
   for (int p = 0; p < passes; ++p) {
     hipLaunchKernelGGL(k_radix_hist, dim3(nblk), dim3(256), 0, c->stream, kin, n, 8 * p, nblk, c->k,
@@ -225,6 +262,8 @@ hipError_t launch_sort_by_bmu(som_ctx *c, const int32_t *bmus, int64_t n) {
     vin = c->sort_val[dst];
     dst ^= 1;
   }
+  hipLaunchKernelGGL(k_segment_bounds, dim3((c->k + 255) / 256), dim3(256), 0, c->stream, c->sort_key[0], n, c->k,
+                     c->seg_off, c->counts);
   return hipGetLastError();
 }
 

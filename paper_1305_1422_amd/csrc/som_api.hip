@@ -58,6 +58,7 @@ static void free_row_scratch(som_ctx *c) {
   dev_free(c->radix_hist); dev_free(c->chunk_node); dev_free(c->partial);
   c->n_cap = 0;
   c->cand_cap = 0;
+  c->d_norms_valid = 0;
 }
 
 // Scratch that scales with the number of instances; grown (never shrunk) on demand.
@@ -156,6 +157,7 @@ static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *
   int rc = ensure_candidates(c, n);
   if (rc) return rc;
   if (!have_xn) {
+    c->d_norms_valid = 0;
     SOM_LAUNCH(c, launch_sample_col_means(c, X, n, c->dim, c->mu));
     SOM_LAUNCH(c, launch_row_sqnorms(c, X, n, c->dim, c->mu, c->xn32, nullptr, nullptr));
   }
@@ -179,7 +181,10 @@ static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indi
   int rc = ensure_transposed(c);
   if (rc) return rc;
   SOM_LAUNCH(c, launch_row_sqnorms(c, W, c->k, c->dim, nullptr, c->wn32, c->wn64, c->wmax_bits));
-  if (!have_xn) SOM_LAUNCH(c, launch_csr_row_sqnorms(c, indptr, values, n, c->xn32));
+  if (!have_xn) {
+    c->d_norms_valid = 0;
+    SOM_LAUNCH(c, launch_csr_row_sqnorms(c, indptr, values, n, c->xn32));
+  }
   SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 3));
   {
     StageTimer t(c, 1);
@@ -212,6 +217,29 @@ static int update_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices,
   StageTimer t(c, 4);
   SOM_LAUNCH(c, launch_smooth_and_divide(c, W));
   return SOM_OK;
+}
+
+// Norms (and the centring vector) of the registered training set, computed once.
+static int registered_norms(som_ctx *c) {
+  if (c->d_norms_valid) return SOM_OK;
+  if (c->data_kind == 1) {
+    SOM_LAUNCH(c, launch_sample_col_means(c, c->d_data, c->d_n, c->dim, c->mu));
+    SOM_LAUNCH(c, launch_row_sqnorms(c, c->d_data, c->d_n, c->dim, c->mu, c->xn32, nullptr, nullptr));
+  } else {
+    SOM_LAUNCH(c, launch_csr_row_sqnorms(c, c->d_indptr, c->d_values, c->d_n, c->xn32));
+  }
+  c->d_norms_valid = 1;
+  return SOM_OK;
+}
+
+static bool is_registered_dense(const som_ctx *c, const float *data, int64_t n) {
+  return c->data_kind == 1 && data == c->d_data && n == c->d_n;
+}
+
+static bool is_registered_csr(const som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
+                              int64_t n) {
+  return c->data_kind == 2 && indptr == c->d_indptr && indices == c->d_indices && values == c->d_values &&
+         n == c->d_n;
 }
 
 // ---------------------------------------------------------------- entry points
@@ -292,8 +320,10 @@ int som_bmus_dense(som_ctx *c, const float *data, int64_t n, const float *codebo
   if (!data || !codebook || !bmus) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
   int rc = check_rows(c, n);
   if (!rc) rc = ensure_rows(c, n, true);
+  bool reg = false;
+  if (!rc && is_registered_dense(c, data, n)) { rc = registered_norms(c); reg = true; }
   if (rc) return rc;
-  return bmu_search_dense(c, data, n, codebook, bmus, false);
+  return bmu_search_dense(c, data, n, codebook, bmus, reg);
 }
 
 int som_bmus_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values, int64_t n,
@@ -302,8 +332,10 @@ int som_bmus_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, cons
   if (!codebook || !bmus) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
   int rc = check_csr(c, indptr, indices, values, n, nnz);
   if (!rc) rc = ensure_rows(c, n, false);
+  bool reg = false;
+  if (!rc && is_registered_csr(c, indptr, indices, values, n)) { rc = registered_norms(c); reg = true; }
   if (rc) return rc;
-  return bmu_search_csr(c, indptr, indices, values, n, codebook, bmus, false);
+  return bmu_search_csr(c, indptr, indices, values, n, codebook, bmus, reg);
 }
 
 int som_update_dense(som_ctx *c, const float *data, int64_t n, const int32_t *bmus, float *codebook,
@@ -337,9 +369,11 @@ int som_train_epoch_dense(som_ctx *c, const float *data, int64_t n, float *codeb
   int rc = check_rows(c, n);
   if (!rc) rc = check_epoch_scalars(c, radius, scale);
   if (!rc) rc = ensure_rows(c, n, true);
+  bool reg = false;
+  if (!rc && is_registered_dense(c, data, n)) { rc = registered_norms(c); reg = true; }
   if (rc) return rc;
   SOM_LAUNCH(c, launch_epoch_params(c, 0, 1, radius, radius, scale, scale, SOM_COOL_LINEAR));
-  rc = bmu_search_dense(c, data, n, codebook, bmus, false);
+  rc = bmu_search_dense(c, data, n, codebook, bmus, reg);
   if (rc) return rc;
   return update_dense(c, data, n, bmus, codebook);
 }
@@ -351,9 +385,11 @@ int som_train_epoch_csr(som_ctx *c, const int64_t *indptr, const int32_t *indice
   int rc = check_csr(c, indptr, indices, values, n, nnz);
   if (!rc) rc = check_epoch_scalars(c, radius, scale);
   if (!rc) rc = ensure_rows(c, n, false);
+  bool reg = false;
+  if (!rc && is_registered_csr(c, indptr, indices, values, n)) { rc = registered_norms(c); reg = true; }
   if (rc) return rc;
   SOM_LAUNCH(c, launch_epoch_params(c, 0, 1, radius, radius, scale, scale, SOM_COOL_LINEAR));
-  rc = bmu_search_csr(c, indptr, indices, values, n, codebook, bmus, false);
+  rc = bmu_search_csr(c, indptr, indices, values, n, codebook, bmus, reg);
   if (rc) return rc;
   return update_csr(c, indptr, indices, values, n, bmus, codebook);
 }
@@ -365,6 +401,7 @@ int som_set_data_dense(som_ctx *c, const float *data, int64_t n) {
   if (rc) return rc;
   c->data_kind = 1; c->d_data = data; c->d_n = n; c->d_nnz = 0;
   c->d_indptr = nullptr; c->d_indices = nullptr; c->d_values = nullptr;
+  c->d_norms_valid = 0;
   return SOM_OK;
 }
 
@@ -375,6 +412,7 @@ int som_set_data_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, 
   if (rc) return rc;
   c->data_kind = 2; c->d_data = nullptr; c->d_n = n; c->d_nnz = nnz;
   c->d_indptr = indptr; c->d_indices = indices; c->d_values = values;
+  c->d_norms_valid = 0;
   return SOM_OK;
 }
 
@@ -402,11 +440,8 @@ int som_train(som_ctx *c, int n_epochs, float radius0, float radiusN, float scal
   const bool dense = c->data_kind == 1;
   int rc = ensure_rows(c, c->d_n, dense);
   if (rc) return rc;
-  if (dense) {
-    SOM_LAUNCH(c, launch_sample_col_means(c, c->d_data, c->d_n, c->dim, c->mu));
-    SOM_LAUNCH(c, launch_row_sqnorms(c, c->d_data, c->d_n, c->dim, c->mu, c->xn32, nullptr, nullptr));
-  } else
-    SOM_LAUNCH(c, launch_csr_row_sqnorms(c, c->d_indptr, c->d_values, c->d_n, c->xn32));
+  rc = registered_norms(c);
+  if (rc) return rc;
   for (int e = 0; e < n_epochs; ++e) {
     SOM_LAUNCH(c, launch_epoch_params(c, e, n_epochs, radius0, radiusN, scale0, scaleN, cooling));
     if (dense) {

@@ -15,7 +15,7 @@ constexpr int kWave = 64;                 // CDNA wavefront width
 constexpr int kCand = 4;                  // candidate nodes kept per instance by the fp32 pass
 constexpr int kListCap = 64;              // nodes a collected candidate list can hold per instance
 constexpr int kChunkRows = 32;            // instances summed by one block of the segmented accumulation
-constexpr int kSortTile = 1024;           // keys ranked by one wave of the radix scatter
+constexpr int kSortTile = 4096;           // keys ranked by one wave of the radix scatter
 constexpr int kProfMax = 512;              // event brackets kept per stage between two reads
 constexpr int kDenseAccumBlock = 32;      // k-extent after which the fp32 MFMA accumulator is flushed
 
@@ -91,6 +91,7 @@ struct som_ctx {
   const int32_t *d_indices;
   const float *d_values;
   int64_t d_n, d_nnz;
+  int d_norms_valid;      // xn32 (and mu for dense data) currently describe the registered set
 
   // optional per-stage event brackets (som_profile_enable)
   int prof_on;

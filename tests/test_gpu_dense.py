@@ -224,3 +224,21 @@ def test_argument_errors(oracle):
     with pytest.raises(TypeError):
         som.train_epoch(torch.zeros((4, 3)), 1.0)                # host tensor: refused by the binding
     som.close()
+
+
+def test_registered_data_gives_identical_epochs(oracle):
+    """Epoch calls on the registered training set reuse its cached norms: same BMUs and code book
+    as on unregistered data, also after other data went through the context in between."""
+    from paper_1305_1422_amd import Som, capi
+    w = scaled_workload(2, n=2500, dim=120, rows=9, cols=9)
+    X = P.to_dev(w.data())
+    other = P.to_dev(np.random.default_rng(5).random((700, w.dim)).astype(np.float32) * 7)
+    a = _som(w, w.codebook()); b = _som(w, w.codebook())
+    capi.som_set_data_dense(b.ctx, X)
+    for r in (4.0, 2.0):
+        ba = a.train_epoch(X, r).cpu().numpy()
+        bb = b.train_epoch(X, r).cpu().numpy()
+        assert np.array_equal(ba, bb)
+        assert np.array_equal(a.codebook.cpu().numpy(), b.codebook.cpu().numpy())
+        b.bmus(other)                                  # overwrites the cached norms; must be noticed
+    a.close(); b.close()
