@@ -12,7 +12,7 @@ import os
 from typing import Optional
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libsom.so")
+LIB_PATH = os.environ.get("SOM_LIB_PATH", os.path.join(HERE, "libsom.so"))
 
 SOM_OK, SOM_ERR_INVALID_ARG, SOM_ERR_ALLOC, SOM_ERR_DEVICE, SOM_ERR_STATE = 0, 1, 2, 3, 4
 SOM_MAP_PLANAR, SOM_MAP_TOROID = 0, 1

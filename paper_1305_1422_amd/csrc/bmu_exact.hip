@@ -14,32 +14,35 @@
 // The instance lists are built with atomic counters, so their order varies between runs;
 // every instance is decided independently, so the BMUs do not.
 //
-// Error bound of one fp32 score (u = 2^-24, g = roundings a product term can suffer,
-// X = |x'|, Wm = max |w'| over the nodes, both norms taken of the fp32-rounded differences):
-//   |s_fp32 - s_exact| <= u [ (2 g + 2) X Wm + 2 Wm^2 + 2 (X + Wm)^2 ]
-// (dot product: g u sum|x'_c w'_c| <= g u X Wm, doubled by the factor -2; rounding of the stored
-// |w'|^2; rounding of the final multiply-add; and the last term for the rounding of the
-// differences x - mu, w - mu themselves, which moves a squared distance by at most
-// 2 u (X + Wm)^2).  Dense MFMA pass with two-level accumulation: g = block + ceil(dim / block) + 2.
-// Sparse FMA chain of len terms, no centring: g = len and the last term drops out.
+// Error bound of one dense fp32 score s = c_i - 2 x.w'_i (u = 2^-24, g = roundings a product term
+// can suffer, X = |x|, M = |mu|, Wm = max |w'| over the nodes, w' = fl(w - mu)):
+//   |s_fp32 - s_exact| <= u [ (2 g + 4) X Wm + 4 Wm^2 + 6 M Wm ]
+// made of: the dot product, g u sum|x_c w'_c| <= g u X Wm, doubled by the factor -2; the rounding
+// of the stored c_i, u (Wm^2 + 2 M Wm); the final multiply-add, u (Wm^2 + 2 M Wm + 2 X Wm); and the
+// rounding of w - mu itself, which moves a squared distance by at most 2 u (X + M + Wm) Wm.
+// MFMA pass with two-level accumulation: g = block + ceil(dim / block) + 2.
+// Sparse scores |w|^2 - 2 x.w from an FMA chain of len terms, no centring: g = len,
+//   |s_fp32 - s_exact| <= u [ (2 g + 2) X Wm + 2 Wm^2 ].
 #include "som_internal.hpp"
 
 #include <math.h>
 
 namespace som {
 
-__device__ __forceinline__ double score_margin(double g, double xnorm2, double wmax2) {
+__device__ __forceinline__ double score_margin(double g, double xnorm2, double wmax2, double munorm2) {
   const double u = 5.9604644775390625e-08;   // 2^-24
   const double xn = sqrt(xnorm2 * (1.0 + 1.2e-7));
   const double wm = sqrt(wmax2 * (1.0 + 1.2e-7));
-  const double bound = u * ((2.0 * g + 2.0) * xn * wm + 2.0 * wm * wm + 2.0 * (xn + wm) * (xn + wm));
+  const double mn = sqrt(munorm2 * (1.0 + 1.2e-7));
+  const double bound = u * ((2.0 * g + 4.0) * xn * wm + 4.0 * wm * wm + 6.0 * mn * wm);
   return 2.125 * bound;          // both scores of a pair may err, plus slack for higher-order terms
 }
 
 // `groups` candidate lists per instance (one per node group of the fp32 pass), stored
 // [group][instance][kCand]; the kept candidates are written back into group 0's slots.
 __global__ __launch_bounds__(256) void k_certify(CandView cand, int groups, const float *__restrict__ xn32,
-                                                 const unsigned *__restrict__ wmax_bits, double g, int64_t n,
+                                                 const unsigned *__restrict__ wmax_bits,
+                                                 const float *__restrict__ mu_norm2, double g, int64_t n,
                                                  int32_t *__restrict__ bmus, int32_t *__restrict__ cand_n,
                                                  int32_t *__restrict__ refine_list,
                                                  int32_t *__restrict__ collect_rows,
@@ -56,7 +59,7 @@ __global__ __launch_bounds__(256) void k_certify(CandView cand, int groups, cons
       if (cand.idx[base + t] >= 0) smin = fminf(smin, cand.val[base + t]);
     omin = fminf(omin, cand.over[(int64_t)q * n + j]);
   }
-  const double margin = score_margin(g, (double)xn32[j], (double)__uint_as_float(*wmax_bits));
+  const double margin = score_margin(g, (double)xn32[j], (double)__uint_as_float(*wmax_bits), (double)*mu_norm2);
   const double thr = (double)smin + margin;
   int keep[kCand];
   int cnt = 0;
@@ -273,7 +276,7 @@ hipError_t launch_certify(som_ctx *c, int64_t n, int32_t *bmus) {
   CandView cand{c->cand_val, c->cand_idx, c->cand_over};
   const double g = (double)kDenseAccumBlock + (double)((c->dim + kDenseAccumBlock - 1) / kDenseAccumBlock) + 2.0;
   hipLaunchKernelGGL(k_certify, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, cand,
-                     bmu_dense_groups(c, n), c->xn32, c->wmax_bits, g, n, bmus, c->cand_n, c->refine_list, c->collect_rows, c->collect_thr,
+                     bmu_dense_groups(c, n), c->xn32, c->wmax_bits, c->mu_norm2, g, n, bmus, c->cand_n, c->refine_list, c->collect_rows, c->collect_thr,
                      c->collect_cnt, c->list_counts);
   return hipGetLastError();
 }

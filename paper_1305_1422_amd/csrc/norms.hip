@@ -3,12 +3,13 @@
 //
 // The BMU search ranks nodes by |w|^2 - 2 x.w (paper, "Parallelism": the GPU variant
 // evaluates Euclidean distances through linear algebra).  Distances do not change when the
-// same vector mu is subtracted from instances and nodes, but the rounding error of the fp32
-// scores shrinks with |x - mu| |w - mu|, so the dense path works on x - mu and w - mu with mu
-// the mean of a sample of the instances.  Norms are taken of the fp32-rounded differences,
-// exactly as the BMU kernel forms them.  |w - mu|^2 is recomputed every epoch; |x - mu|^2
-// only bounds the rounding error.  One wavefront per row, fp64 accumulation, so each fp32
-// result carries a single rounding.
+// same vector mu is subtracted from instances and nodes, and
+//     |x - w|^2 - |x - mu|^2 = |w'|^2 + 2 mu.w' - 2 x.w',   w' = w - mu,
+// so the dense path multiplies the raw instances with the CENTRED code book: the rounding
+// error of the fp32 scores then scales with |x| |w - mu| instead of |x| |w|.  mu is the mean
+// of a sample of the instances.  Every epoch k_center_codebook writes w' = fl(w - mu) and the
+// per-node constants c_i = |w'_i|^2 + 2 mu.w'_i (of the rounded w', in fp64, rounded once).
+// |x|^2 and |mu|^2 only bound the rounding error.  One wavefront per row, fp64 accumulation.
 #include "som_internal.hpp"
 
 namespace som {
@@ -40,6 +41,33 @@ __global__ __launch_bounds__(256) void k_row_sqnorms(const float *__restrict__ A
       out32[r] = f;
       if (out64) out64[r] = s;
       if (max_bits) atomicMax(max_bits, __float_as_uint(f));
+    }
+  }
+}
+
+// w' = fl(w - mu), c_i = |w'_i|^2 + 2 mu.w'_i, and the maximum of |w'_i|^2 over the nodes.
+__global__ __launch_bounds__(256) void k_center_codebook(const float *__restrict__ W, int k, int dim,
+                                                         const float *__restrict__ mu, float *__restrict__ Wc,
+                                                         float *__restrict__ cn, unsigned *__restrict__ max_bits) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int nwaves = gridDim.x * (blockDim.x / kWave);
+  for (int i = wave; i < k; i += nwaves) {
+    const float *w = W + (int64_t)i * dim;
+    float *wc = Wc + (int64_t)i * dim;
+    double s2 = 0.0, sm = 0.0;
+    for (int c = lane; c < dim; c += kWave) {
+      const float m = mu[c];
+      const float t = w[c] - m;
+      wc[c] = t;
+      s2 += (double)t * (double)t;
+      sm += (double)m * (double)t;
+    }
+    s2 = wave_sum(s2);
+    sm = wave_sum(sm);
+    if (lane == 0) {
+      cn[i] = (float)(s2 + 2.0 * sm);
+      atomicMax(max_bits, __float_as_uint((float)s2));
     }
   }
 }
@@ -118,6 +146,14 @@ hipError_t launch_sample_col_means(som_ctx *c, const float *A, int64_t nrows, in
                      stride, dim, c->mu_partial);
   hipLaunchKernelGGL(k_finish_col_means, dim3((dim + 63) / 64), dim3(64), 0, c->stream, c->mu_partial, nsample,
                      dim, mu);
+  return hipGetLastError();
+}
+
+hipError_t launch_center_codebook(som_ctx *c, const float *W) {
+  hipError_t e = launch_fill_zero_u32(c->stream, c->wmax_bits, 1);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_center_codebook, dim3(grid_for_waves(c, c->k)), dim3(256), 0, c->stream, W, c->k, c->dim,
+                     c->mu, c->Wc, c->wn32, c->wmax_bits);
   return hipGetLastError();
 }
 

@@ -159,18 +159,19 @@ static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *
   if (!have_xn) {
     c->d_norms_valid = 0;
     SOM_LAUNCH(c, launch_sample_col_means(c, X, n, c->dim, c->mu));
-    SOM_LAUNCH(c, launch_row_sqnorms(c, X, n, c->dim, c->mu, c->xn32, nullptr, nullptr));
+    SOM_LAUNCH(c, launch_row_sqnorms(c, c->mu, 1, c->dim, nullptr, c->mu_norm2, nullptr, nullptr));
+    SOM_LAUNCH(c, launch_row_sqnorms(c, X, n, c->dim, nullptr, c->xn32, nullptr, nullptr));
   }
-  SOM_LAUNCH(c, launch_row_sqnorms(c, W, c->k, c->dim, c->mu, c->wn32, nullptr, c->wmax_bits));
+  SOM_LAUNCH(c, launch_center_codebook(c, W));
   SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 3));
   {
     StageTimer t(c, 0);
-    SOM_LAUNCH(c, launch_bmu_dense(c, X, n, W));
+    SOM_LAUNCH(c, launch_bmu_dense(c, X, n));
   }
   StageTimer t(c, 2);
   SOM_LAUNCH(c, launch_certify(c, n, bmus));
   SOM_LAUNCH(c, launch_refine_dense(c, X, W, bmus));
-  SOM_LAUNCH(c, launch_bmu_dense_collect(c, X, n, W));
+  SOM_LAUNCH(c, launch_bmu_dense_collect(c, X, n));
   SOM_LAUNCH(c, launch_refine_lists_dense(c, X, W, bmus));
   SOM_LAUNCH(c, launch_rescan_dense(c, X, W, bmus));
   return SOM_OK;
@@ -224,7 +225,8 @@ static int registered_norms(som_ctx *c) {
   if (c->d_norms_valid) return SOM_OK;
   if (c->data_kind == 1) {
     SOM_LAUNCH(c, launch_sample_col_means(c, c->d_data, c->d_n, c->dim, c->mu));
-    SOM_LAUNCH(c, launch_row_sqnorms(c, c->d_data, c->d_n, c->dim, c->mu, c->xn32, nullptr, nullptr));
+    SOM_LAUNCH(c, launch_row_sqnorms(c, c->mu, 1, c->dim, nullptr, c->mu_norm2, nullptr, nullptr));
+    SOM_LAUNCH(c, launch_row_sqnorms(c, c->d_data, c->d_n, c->dim, nullptr, c->xn32, nullptr, nullptr));
   } else {
     SOM_LAUNCH(c, launch_csr_row_sqnorms(c, c->d_indptr, c->d_values, c->d_n, c->xn32));
   }
@@ -281,12 +283,14 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
             dev_alloc(&c->massD, K) && dev_alloc(&c->cntT, 2 * K) && dev_alloc(&c->gx, 2 * (size_t)cols + 1) &&
             dev_alloc(&c->gy, (size_t)rows) && dev_alloc(&c->params, 1) && dev_alloc(&c->list_counts, 4) &&
             dev_alloc(&c->mu, (size_t)dim) && dev_alloc(&c->mu_partial, (size_t)64 * dim) &&
+            dev_alloc(&c->Wc, K * dim) && dev_alloc(&c->zero16, 16) && dev_alloc(&c->mu_norm2, 1) &&
             dev_alloc(&c->S, K * dim) && dev_alloc(&c->T, images * K * dim);
   if (!ok) {
     som_destroy(c);
     return fail(nullptr, SOM_ERR_ALLOC, "cannot allocate map scratch (%d nodes x %d)", c->k, dim);
   }
   hipError_t e = launch_fill_zero_u32(c->stream, c->list_counts, 4);
+  if (e == hipSuccess) e = launch_fill_zero_u32(c->stream, c->zero16, 16);
   if (e == hipSuccess && seed != 0) e = launch_fill_uniform(c, codebook, (int64_t)c->k * dim, seed);
   if (e != hipSuccess) {
     int rc = dev_fail(nullptr, e, "som_init");
@@ -304,7 +308,7 @@ void som_destroy(som_ctx *c) {
   dev_free(c->wn32); dev_free(c->wn64); dev_free(c->wmax_bits); dev_free(c->counts); dev_free(c->seg_off);
   dev_free(c->chunk_off); dev_free(c->massD); dev_free(c->cntT); dev_free(c->gx); dev_free(c->gy);
   dev_free(c->params); dev_free(c->list_counts); dev_free(c->S); dev_free(c->T); dev_free(c->Wt);
-  dev_free(c->mu); dev_free(c->mu_partial);
+  dev_free(c->mu); dev_free(c->mu_partial); dev_free(c->Wc); dev_free(c->zero16); dev_free(c->mu_norm2);
   for (int s = 0; s < SOM_PROFILE_STAGES; ++s) {
     if (!c->prof_ev[s]) continue;
     for (int e = 0; e < 2 * kProfMax; ++e) (void)hipEventDestroy(c->prof_ev[s][e]);

@@ -17,7 +17,10 @@ constexpr int kListCap = 64;              // nodes a collected candidate list ca
 constexpr int kChunkRows = 32;            // instances summed by one block of the segmented accumulation
 constexpr int kSortTile = 4096;           // keys ranked by one wave of the radix scatter
 constexpr int kProfMax = 512;              // event brackets kept per stage between two reads
-constexpr int kDenseAccumBlock = 32;      // k-extent after which the fp32 MFMA accumulator is flushed
+#ifndef SOM_FLUSH_BLOCK
+#define SOM_FLUSH_BLOCK 32
+#endif
+constexpr int kDenseAccumBlock = SOM_FLUSH_BLOCK;      // k-extent after which the fp32 MFMA accumulator is flushed
 
 // Scores the fp32 pass hands to the exact pass: per instance kCand (value, node) pairs,
 // smallest first where the producer sorts them, plus the smallest value it dropped.
@@ -59,6 +62,9 @@ struct som_ctx {
   float *T;               // [1 or 2][k][dim] sums after the pass along x
   float *Wt;              // [dim][kpad] transposed code book (sparse BMU only, lazily allocated)
   int kpad;
+  float *Wc;              // [k][dim] centred code book w' = fl(w - mu) of the dense BMU search
+  float *zero16;          // 64 bytes of zeros: source of out-of-range direct-to-LDS loads
+  float *mu_norm2;        // [1] |mu|^2
   float *mu;              // [dim] centring vector of the dense BMU search
   double *mu_partial;     // [64][dim] partial column sums
 
@@ -107,6 +113,7 @@ namespace som {
 
 // norms.hip
 hipError_t launch_sample_col_means(som_ctx *c, const float *A, int64_t nrows, int dim, float *mu);
+hipError_t launch_center_codebook(som_ctx *c, const float *W);   // -> Wc, wn32 (= c_i), wmax_bits
 hipError_t launch_row_sqnorms(som_ctx *c, const float *A, int64_t nrows, int dim, const float *mu,
                               float *out32, double *out64, unsigned *max_bits);
 hipError_t launch_csr_row_sqnorms(som_ctx *c, const int64_t *indptr, const float *values, int64_t n,
@@ -114,8 +121,9 @@ hipError_t launch_csr_row_sqnorms(som_ctx *c, const int64_t *indptr, const float
 
 // bmu_dense.hip
 int bmu_dense_groups(const som_ctx *c, int64_t n);
-hipError_t launch_bmu_dense(som_ctx *c, const float *X, int64_t n, const float *W);
-hipError_t launch_bmu_dense_collect(som_ctx *c, const float *X, int64_t n, const float *W);
+hipError_t launch_bmu_dense(som_ctx *c, const float *X, int64_t n);
+hipError_t launch_bmu_dense_collect(som_ctx *c, const float *X, int64_t n);
+hipError_t launch_bmu_dense_dl(som_ctx *c, const float *X, int64_t n, dim3 grid, bool collect);   // bmu_dense_dl.hip
 
 // bmu_exact.hip
 hipError_t launch_certify(som_ctx *c, int64_t n, int32_t *bmus);
