@@ -55,8 +55,8 @@ __device__ __forceinline__ int mfma_row(int mi, int v, int lhi) { return mi * 32
 // Scores of one node block: push into the running lists (filter mode) or append the nodes under
 // the per-instance threshold to the collected lists (collect mode).  `tot` is cleared.
 template <bool kCollect>
-__device__ __forceinline__ void consume_scores(f32x16 (&tot)[2][2], const float *__restrict__ swn, int node0, int wm,
-                                               int lhi, Top2 (&top)[2], const float (&lim)[2],
+__device__ __forceinline__ void consume_scores(f32x16 (&tot)[2][2], const float *__restrict__ swn, int node0, int k,
+                                               int wm, int lhi, Top2 (&top)[2], const float (&lim)[2],
                                                const int64_t (&slot_of)[2], int32_t *__restrict__ cnt,
                                                int32_t *__restrict__ list) {
 #pragma unroll
@@ -70,7 +70,7 @@ __device__ __forceinline__ void consume_scores(f32x16 (&tot)[2][2], const float 
       for (int ni = 0; ni < 2; ++ni) {
         const float s = fmaf(-2.f, tot[mi][ni][v], wnv);
         if (kCollect) {
-          if (s <= lim[ni]) {
+          if (s <= lim[ni] && node < k) {
             const int pos = atomicAdd(&cnt[slot_of[ni]], 1);
             if (pos < kListCap) list[slot_of[ni] * kListCap + pos] = node;
           }

@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense_dl(const float *__restrict
 #pragma unroll
           for (int v = 0; v < 16; ++v) { tot[mi][ni][v] += acc[mi][ni][v]; acc[mi][ni][v] = 0.f; }
     }
-    if (last_k) consume_scores<kCollect>(tot, sWn[nb & 1], nb * kTN, wm, lhi, top, lim, slot_of, cnt, list);
+    if (last_k) consume_scores<kCollect>(tot, sWn[nb & 1], nb * kTN, k, wm, lhi, top, lim, slot_of, cnt, list);
 
     wait_vector_memory();
     __syncthreads();

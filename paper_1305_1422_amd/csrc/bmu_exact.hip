@@ -42,7 +42,7 @@ __device__ __forceinline__ double score_margin(double g, double xnorm2, double w
 // [group][instance][kCand]; the kept candidates are written back into group 0's slots.
 __global__ __launch_bounds__(256) void k_certify(CandView cand, int groups, const float *__restrict__ xn32,
                                                  const unsigned *__restrict__ wmax_bits,
-                                                 const float *__restrict__ mu_norm2, double g, int64_t n,
+                                                 const float *__restrict__ mu_norm2, double g, int64_t n, int k,
                                                  int32_t *__restrict__ bmus, int32_t *__restrict__ cand_n,
                                                  int32_t *__restrict__ refine_list,
                                                  int32_t *__restrict__ collect_rows,
@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void k_certify(CandView cand, int groups, cons
     const int64_t base = ((int64_t)q * n + j) * kCand;
 #pragma unroll
     for (int t = 0; t < kCand; ++t)
-      if (cand.idx[base + t] >= 0) smin = fminf(smin, cand.val[base + t]);
+      if ((unsigned)cand.idx[base + t] < (unsigned)k) smin = fminf(smin, cand.val[base + t]);
     omin = fminf(omin, cand.over[(int64_t)q * n + j]);
   }
   const double margin = score_margin(g, (double)xn32[j], (double)__uint_as_float(*wmax_bits), (double)*mu_norm2);
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256) void k_certify(CandView cand, int groups, cons
 #pragma unroll
     for (int t = 0; t < kCand; ++t) {
       const int id = cand.idx[base + t];
-      if (id >= 0 && (double)cand.val[base + t] <= thr) {
+      if ((unsigned)id < (unsigned)k && (double)cand.val[base + t] <= thr) {
         if (cnt < kCand) keep[cnt] = id;
         ++cnt;
       }
@@ -145,7 +145,7 @@ __global__ __launch_bounds__(256) void k_refine_dense(const float *__restrict__ 
 // Exact comparison of the collected lists: one wavefront per listed instance.  A list that
 // overflowed its capacity sends the instance on to the full rescan.
 __global__ __launch_bounds__(256) void k_refine_lists_dense(const float *__restrict__ X, const float *__restrict__ W,
-                                                            int dim, const int32_t *__restrict__ collect_rows,
+                                                            int dim, int k, const int32_t *__restrict__ collect_rows,
                                                             const int32_t *__restrict__ collect_cnt,
                                                             const int32_t *__restrict__ collect_list,
                                                             int32_t *__restrict__ rescan_list,
@@ -166,7 +166,7 @@ __global__ __launch_bounds__(256) void k_refine_lists_dense(const float *__restr
     double best = INFINITY;
     int arg = 0x7fffffff;
     for (int t = 0; t < cn; ++t) {
-      const int i = lst[t];
+      const int i = min(max(lst[t], 0), k - 1);        // lists only ever hold valid nodes; never trust memory
       const double d2 = sqdist_dense_wave(X + j * dim, W + (int64_t)i * dim, dim, lane);
       if (d2 < best || (d2 == best && i < arg)) { best = d2; arg = i; }
     }
@@ -276,14 +276,14 @@ hipError_t launch_certify(som_ctx *c, int64_t n, int32_t *bmus) {
   CandView cand{c->cand_val, c->cand_idx, c->cand_over};
   const double g = (double)kDenseAccumBlock + (double)((c->dim + kDenseAccumBlock - 1) / kDenseAccumBlock) + 2.0;
   hipLaunchKernelGGL(k_certify, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, cand,
-                     bmu_dense_groups(c, n), c->xn32, c->wmax_bits, c->mu_norm2, g, n, bmus, c->cand_n, c->refine_list, c->collect_rows, c->collect_thr,
+                     bmu_dense_groups(c, n), c->xn32, c->wmax_bits, c->mu_norm2, g, n, c->k, bmus, c->cand_n, c->refine_list, c->collect_rows, c->collect_thr,
                      c->collect_cnt, c->list_counts);
   return hipGetLastError();
 }
 
 hipError_t launch_refine_lists_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus) {
   hipLaunchKernelGGL(k_refine_lists_dense, dim3(persistent_blocks(c, 1 << 20)), dim3(256), 0, c->stream, X, W,
-                     c->dim, c->collect_rows, c->collect_cnt, c->collect_list, c->rescan_list, c->list_counts, bmus);
+                     c->dim, c->k, c->collect_rows, c->collect_cnt, c->collect_list, c->rescan_list, c->list_counts, bmus);
   return hipGetLastError();
 }
 

@@ -1,0 +1,67 @@
+"""Parity at the full sizes of the stated configurations, in the launch configuration bench.py
+times (registered data, som_train_epoch), on sampled outputs: BMUs of sampled instances against
+the oracle's full search, and sampled nodes of the new code book against the oracle's update
+computed from the GPU's BMU vector.  Properties that hold at any size are checked on everything:
+index range, and code-book rows of nodes below the mass floor unchanged.
+"""
+import numpy as np
+import pytest
+
+from gen import make_workload
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _epochs(oracle, cfg, radii, n_rows=48, n_nodes=32):
+    from paper_1305_1422_amd import Som, capi
+    w = make_workload(cfg)
+    rng = np.random.default_rng(1000 + cfg)
+    X = w.data()
+    mt, gt = P.MAP[w.map_type], P.GRID[w.grid_type]
+    som = Som(w.rows, w.cols, w.dim, w.map_type, w.grid_type, codebook=torch.from_numpy(w.codebook()))
+    if w.kind == "dense":
+        Xd = P.to_dev(X)
+        capi.som_set_data_dense(som.ctx, Xd)
+    else:
+        Xd = P.csr_to_dev(X)
+        capi.som_set_data_csr(som.ctx, *Xd)
+    for radius in radii:
+        W_in = som.codebook.cpu().numpy().copy()
+        b = som.train_epoch(Xd, radius).cpu().numpy()
+        W_out = som.codebook.cpu().numpy()
+        assert b.min() >= 0 and b.max() < w.k
+        rows = np.sort(rng.choice(w.n, size=n_rows, replace=False))
+        if w.kind == "dense":
+            P.check_bmus_dense(oracle, X, W_in, b, rows=rows)
+            S, C = oracle.accumulate_dense(X, b, w.k)
+        else:
+            P.check_bmus_csr(oracle, X, w.dim, W_in, b, rows=rows)
+            S, C = oracle.accumulate_csr(X, w.dim, b, w.k)
+        hit = np.unique(b)
+        nodes = np.unique(np.concatenate([rng.choice(w.k, size=n_nodes, replace=False), hit[:4]]))
+        P.check_codebook(oracle, S, C, W_in, W_out, w.rows, w.cols, mt, gt, radius, nodes=nodes)
+        del S
+    som.close()
+
+
+def test_config2_full_size(oracle):
+    """n=100,000 dim=1,000, 50x50 toroid square: the first epoch (radius 25) and a late one."""
+    _epochs(oracle, 2, [25.0, 3.0])
+
+
+def test_config3_full_size(oracle):
+    """n=50,000 dim=256, 200x200 toroid hexagonal (40,000 nodes)."""
+    _epochs(oracle, 3, [100.0, 2.0], n_rows=32, n_nodes=24)
+
+
+def test_config5_full_size(oracle):
+    """n=1,000,000 dim=128, 100x100 planar hexagonal."""
+    _epochs(oracle, 5, [50.0, 1.0])
+
+
+def test_config4_full_size(oracle):
+    """CSR n=100,000 dim=50,000 (about 1e7 nonzeros), 50x50 planar square."""
+    _epochs(oracle, 4, [25.0], n_rows=24, n_nodes=12)
