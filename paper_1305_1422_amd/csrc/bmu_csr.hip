@@ -1,30 +1,34 @@
 // Sparse best-matching-unit search, fp32 pass (paper: sparse kernel - the code book stays
 // dense while the data are index:value lists; BMU equation).
 //
-// For a CSR row x the scores of all nodes are s_i = |w_i|^2 - 2 sum_nz v * W[i][c].  The code
-// book is first transposed to Wt[dim][kpad] so that one nonzero (c, v) touches one contiguous
-// row of Wt: a workgroup owns an instance, its 256 threads own nodes t, t+256, ... and every
-// nonzero is one coalesced sweep over the node range with v broadcast from LDS.  The scores of
-// an instance never leave registers.
+// As in the dense path the nodes are ranked by s_i = c_i - 2 x.w'_i with w' = w - mu and
+// c_i = |w'_i|^2 + 2 mu.w'_i (identical ranking to |x - w_i|^2, smaller rounding error); x stays
+// sparse, so x.w'_i = sum_nz v * w'_i[c].  mu is the mean of the code-book rows here.  The
+// centred code book is written transposed, Wt[dim][kpad], so that one nonzero (c, v) touches
+// one contiguous row of Wt: a workgroup owns an instance, its 256 threads own nodes t, t+256,
+// ... and every nonzero is one coalesced sweep over the node range with v broadcast from LDS.
+// The scores of an instance never leave registers.
 //
-// As in the dense path the fp32 scores only filter: the workgroup finds the minimum, then the
-// nodes whose score lies within the rounding-error bound of it.  One such node: decided.  Up to
-// kCand: handed to the exact refine pass.  More: the instance is rescanned exactly.
+// The fp32 scores only filter: the workgroup finds the minimum, then the nodes whose score
+// lies within the rounding-error bound of it.  One such node: decided.  Up to kCand: handed to
+// the exact refine pass.  Up to kListCap: stored as a collected list for the exact list pass.
+// More: the instance is rescanned exactly.
 #include "som_internal.hpp"
 
 #include <math.h>
 
 namespace som {
 
-// ---------------------------------------------------------------- transpose
-__global__ __launch_bounds__(256) void k_transpose(const float *__restrict__ W, int k, int dim, int kpad,
-                                                   float *__restrict__ Wt) {
+// ---------------------------------------------------------------- transpose with centring
+__global__ __launch_bounds__(256) void k_transpose_centered(const float *__restrict__ W,
+                                                            const float *__restrict__ mu, int k, int dim, int kpad,
+                                                            float *__restrict__ Wt) {
   __shared__ float tile[32][33];
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;       // 32 x 8
   const int c0 = blockIdx.x * 32, i0 = blockIdx.y * 32;
   for (int r = ty; r < 32; r += 8) {
     const int i = i0 + r, c = c0 + tx;
-    tile[r][tx] = (i < k && c < dim) ? W[(int64_t)i * dim + c] : 0.f;
+    tile[r][tx] = (i < k && c < dim) ? W[(int64_t)i * dim + c] - mu[c] : 0.f;
   }
   __syncthreads();
   for (int r = ty; r < 32; r += 8) {
@@ -33,35 +37,45 @@ __global__ __launch_bounds__(256) void k_transpose(const float *__restrict__ W, 
   }
 }
 
-__device__ __forceinline__ double csr_margin(double len, double xnorm2, double wmax2) {
+// Error bound of one sparse fp32 score (see bmu_exact.hip): FMA chain of len terms, g = len.
+__device__ __forceinline__ double csr_margin(double len, double xnorm2, double wmax2, double munorm2) {
   const double u = 5.9604644775390625e-08;   // 2^-24
   const double xn = sqrt(xnorm2 * (1.0 + 1.2e-7));
   const double wm = sqrt(wmax2 * (1.0 + 1.2e-7));
+  const double mn = sqrt(munorm2 * (1.0 + 1.2e-7));
   const double g = len < 1.0 ? 1.0 : len;
-  return 2.125 * u * ((2.0 * g + 2.0) * xn * wm + 2.0 * wm * wm);
+  return 2.125 * u * ((2.0 * g + 4.0) * xn * wm + 4.0 * wm * wm + 6.0 * mn * wm);
 }
+
+struct CsrBmuOut {
+  int32_t *bmus;
+  int32_t *cand_idx, *cand_n, *refine_list;
+  int32_t *collect_rows, *collect_cnt, *collect_list;
+  int32_t *rescan_list;
+  int32_t *list_counts;
+};
 
 template <int ACC>
 __global__ __launch_bounds__(256) void k_bmu_csr(const int64_t *__restrict__ indptr,
                                                  const int32_t *__restrict__ indices,
                                                  const float *__restrict__ values, const float *__restrict__ Wt,
-                                                 int kpad, const float *__restrict__ wn32,
+                                                 int kpad, const float *__restrict__ cn32,
                                                  const float *__restrict__ xn32,
-                                                 const unsigned *__restrict__ wmax_bits, int64_t n, int k, int dim,
-                                                 int32_t *__restrict__ bmus, int32_t *__restrict__ cand_idx,
-                                                 int32_t *__restrict__ cand_n, int32_t *__restrict__ refine_list,
-                                                 int32_t *__restrict__ rescan_list,
-                                                 int32_t *__restrict__ list_counts) {
+                                                 const unsigned *__restrict__ wmax_bits,
+                                                 const float *__restrict__ mu_norm2, int64_t n, int k, int dim,
+                                                 CsrBmuOut out) {
   __shared__ int64_t s_off[256];
   __shared__ float s_val[256];
   __shared__ float s_min[4];
   __shared__ int s_cnt;
-  __shared__ int s_list[kCand];
+  __shared__ int s_list[kListCap];
+  __shared__ int s_slot;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int span = 256 * ACC;                       // nodes covered by one sweep
   const int nsweep = (k + span - 1) / span;
   const float wmax2 = __uint_as_float(*wmax_bits);
+  const float mu2 = *mu_norm2;
 
   for (int64_t j = blockIdx.x; j < n; j += gridDim.x) {
     const int64_t rs = indptr[j];
@@ -99,7 +113,7 @@ __global__ __launch_bounds__(256) void k_bmu_csr(const int64_t *__restrict__ ind
 #pragma unroll
           for (int a = 0; a < ACC; ++a) {
             const int node = node_base + a * 256;
-            sc[a] = node < k ? fmaf(-2.f, acc[a], wn32[node]) : INFINITY;
+            sc[a] = node < k ? fmaf(-2.f, acc[a], cn32[node]) : INFINITY;
           }
         }
         if (phase == 0) {
@@ -110,7 +124,7 @@ __global__ __launch_bounds__(256) void k_bmu_csr(const int64_t *__restrict__ ind
           for (int a = 0; a < ACC; ++a)
             if (sc[a] <= thr) {
               const int pos = atomicAdd(&s_cnt, 1);
-              if (pos < kCand) s_list[pos] = node_base + a * 256;
+              if (pos < kListCap) s_list[pos] = node_base + a * 256;
             }
         }
       }
@@ -122,24 +136,32 @@ __global__ __launch_bounds__(256) void k_bmu_csr(const int64_t *__restrict__ ind
         if (tid == 0) s_cnt = 0;
         __syncthreads();
         const float smin = fminf(fminf(s_min[0], s_min[1]), fminf(s_min[2], s_min[3]));
-        const double t = (double)smin + csr_margin((double)len, (double)xn32[j], (double)wmax2);
+        const double t = (double)smin + csr_margin((double)len, (double)xn32[j], (double)wmax2, (double)mu2);
         // round the threshold up to fp32 so that no score inside the margin is lost
         thr = (float)t;
         if ((double)thr < t) thr = nextafterf(thr, INFINITY);
       }
     }
     __syncthreads();
-    if (tid == 0) {
-      const int cnt = s_cnt;
-      if (cnt == 1) {
-        bmus[j] = s_list[0];
-      } else if (cnt >= 2 && cnt <= kCand) {
-        for (int t = 0; t < cnt; ++t) cand_idx[j * kCand + t] = s_list[t];
-        cand_n[j] = cnt;
-        refine_list[atomicAdd(&list_counts[0], 1)] = (int32_t)j;
-      } else {
-        rescan_list[atomicAdd(&list_counts[2], 1)] = (int32_t)j;
+    const int cnt = s_cnt;
+    if (cnt == 1) {
+      if (tid == 0) out.bmus[j] = s_list[0];
+    } else if (cnt >= 2 && cnt <= kCand) {
+      if (tid < cnt) out.cand_idx[j * kCand + tid] = s_list[tid];
+      if (tid == 0) {
+        out.cand_n[j] = cnt;
+        out.refine_list[atomicAdd(&out.list_counts[0], 1)] = (int32_t)j;
       }
+    } else if (cnt > kCand && cnt <= kListCap) {
+      if (tid == 0) {
+        s_slot = atomicAdd(&out.list_counts[1], 1);
+        out.collect_rows[s_slot] = (int32_t)j;
+        out.collect_cnt[s_slot] = cnt;
+      }
+      __syncthreads();
+      if (tid < cnt) out.collect_list[(int64_t)s_slot * kListCap + tid] = s_list[tid];
+    } else {
+      if (tid == 0) out.rescan_list[atomicAdd(&out.list_counts[2], 1)] = (int32_t)j;
     }
     __syncthreads();
   }
@@ -147,7 +169,7 @@ __global__ __launch_bounds__(256) void k_bmu_csr(const int64_t *__restrict__ ind
 
 hipError_t launch_transpose_codebook(som_ctx *c, const float *W) {
   dim3 grid((c->dim + 31) / 32, (c->kpad + 31) / 32);
-  hipLaunchKernelGGL(k_transpose, grid, dim3(256), 0, c->stream, W, c->k, c->dim, c->kpad, c->Wt);
+  hipLaunchKernelGGL(k_transpose_centered, grid, dim3(256), 0, c->stream, W, c->mu, c->k, c->dim, c->kpad, c->Wt);
   return hipGetLastError();
 }
 
@@ -156,9 +178,10 @@ static void launch_bmu_csr_acc(som_ctx *c, const int64_t *indptr, const int32_t 
                                int64_t n, int32_t *bmus) {
   int64_t blocks = (int64_t)c->n_cu * 8;
   if (blocks > n) blocks = n;
+  CsrBmuOut out{bmus, c->cand_idx, c->cand_n, c->refine_list, c->collect_rows, c->collect_cnt, c->collect_list,
+                c->rescan_list, c->list_counts};
   hipLaunchKernelGGL(k_bmu_csr<ACC>, dim3((unsigned)blocks), dim3(256), 0, c->stream, indptr, indices, values,
-                     c->Wt, c->kpad, c->wn32, c->xn32, c->wmax_bits, n, c->k, c->dim, bmus, c->cand_idx, c->cand_n,
-                     c->refine_list, c->rescan_list, c->list_counts);
+                     c->Wt, c->kpad, c->wn32, c->xn32, c->wmax_bits, c->mu_norm2, n, c->k, c->dim, out);
 }
 
 hipError_t launch_bmu_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,

@@ -232,6 +232,37 @@ __global__ __launch_bounds__(256) void k_refine_csr(const int64_t *__restrict__ 
   }
 }
 
+__global__ __launch_bounds__(256) void k_refine_lists_csr(const int64_t *__restrict__ indptr,
+                                                          const int32_t *__restrict__ indices,
+                                                          const float *__restrict__ values,
+                                                          const float *__restrict__ W,
+                                                          const double *__restrict__ wn64, int dim, int k,
+                                                          const int32_t *__restrict__ collect_rows,
+                                                          const int32_t *__restrict__ collect_cnt,
+                                                          const int32_t *__restrict__ collect_list,
+                                                          const int32_t *__restrict__ list_counts,
+                                                          int32_t *__restrict__ bmus) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int nwaves = gridDim.x * (blockDim.x / kWave);
+  const int count = list_counts[1];
+  for (int e = wave; e < count; e += nwaves) {
+    const int64_t j = collect_rows[e];
+    const int64_t s = indptr[j];
+    const int len = (int)(indptr[j + 1] - s);
+    const int cn = min(collect_cnt[e], kListCap);
+    const int32_t *lst = collect_list + (int64_t)e * kListCap;
+    double best = INFINITY;
+    int arg = 0x7fffffff;
+    for (int t = 0; t < cn; ++t) {
+      const int i = min(max(lst[t], 0), k - 1);
+      const double d2 = sqdist_csr_wave(indices + s, values + s, len, W + (int64_t)i * dim, wn64[i], dim, lane);
+      if (d2 < best || (d2 == best && i < arg)) { best = d2; arg = i; }
+    }
+    if (lane == 0) bmus[j] = arg == 0x7fffffff ? 0 : arg;
+  }
+}
+
 __global__ __launch_bounds__(256) void k_rescan_csr(const int64_t *__restrict__ indptr,
                                                     const int32_t *__restrict__ indices,
                                                     const float *__restrict__ values,
@@ -303,6 +334,14 @@ hipError_t launch_refine_csr(som_ctx *c, const int64_t *indptr, const int32_t *i
                              const float *W, int32_t *bmus) {
   hipLaunchKernelGGL(k_refine_csr, dim3(persistent_blocks(c, 1 << 20)), dim3(256), 0, c->stream, indptr, indices,
                      values, W, c->wn64, c->dim, c->cand_idx, c->cand_n, c->refine_list, c->list_counts, bmus);
+  return hipGetLastError();
+}
+
+hipError_t launch_refine_lists_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
+                                   const float *W, int32_t *bmus) {
+  hipLaunchKernelGGL(k_refine_lists_csr, dim3(persistent_blocks(c, 1 << 20)), dim3(256), 0, c->stream, indptr,
+                     indices, values, W, c->wn64, c->dim, c->k, c->collect_rows, c->collect_cnt, c->collect_list,
+                     c->list_counts, bmus);
   return hipGetLastError();
 }
 

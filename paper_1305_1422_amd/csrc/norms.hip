@@ -45,29 +45,35 @@ __global__ __launch_bounds__(256) void k_row_sqnorms(const float *__restrict__ A
   }
 }
 
-// w' = fl(w - mu), c_i = |w'_i|^2 + 2 mu.w'_i, and the maximum of |w'_i|^2 over the nodes.
+// w' = fl(w - mu) (stored if Wc is given), c_i = |w'_i|^2 + 2 mu.w'_i, the maximum of |w'_i|^2
+// over the nodes, and optionally |w_i|^2 of the uncentred rows in fp64.
 __global__ __launch_bounds__(256) void k_center_codebook(const float *__restrict__ W, int k, int dim,
                                                          const float *__restrict__ mu, float *__restrict__ Wc,
-                                                         float *__restrict__ cn, unsigned *__restrict__ max_bits) {
+                                                         float *__restrict__ cn, unsigned *__restrict__ max_bits,
+                                                         double *__restrict__ wn64) {
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
   const int nwaves = gridDim.x * (blockDim.x / kWave);
   for (int i = wave; i < k; i += nwaves) {
     const float *w = W + (int64_t)i * dim;
     float *wc = Wc + (int64_t)i * dim;
-    double s2 = 0.0, sm = 0.0;
+    double s2 = 0.0, sm = 0.0, sw = 0.0;
     for (int c = lane; c < dim; c += kWave) {
       const float m = mu[c];
-      const float t = w[c] - m;
-      wc[c] = t;
+      const float x = w[c];
+      const float t = x - m;
+      if (Wc) wc[c] = t;
       s2 += (double)t * (double)t;
       sm += (double)m * (double)t;
+      sw += (double)x * (double)x;
     }
     s2 = wave_sum(s2);
     sm = wave_sum(sm);
+    sw = wave_sum(sw);
     if (lane == 0) {
       cn[i] = (float)(s2 + 2.0 * sm);
       atomicMax(max_bits, __float_as_uint((float)s2));
+      if (wn64) wn64[i] = sw;
     }
   }
 }
@@ -149,11 +155,12 @@ hipError_t launch_sample_col_means(som_ctx *c, const float *A, int64_t nrows, in
   return hipGetLastError();
 }
 
-hipError_t launch_center_codebook(som_ctx *c, const float *W) {
+hipError_t launch_center_codebook(som_ctx *c, const float *W, bool store_centered, bool want_wn64) {
   hipError_t e = launch_fill_zero_u32(c->stream, c->wmax_bits, 1);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_center_codebook, dim3(grid_for_waves(c, c->k)), dim3(256), 0, c->stream, W, c->k, c->dim,
-                     c->mu, c->Wc, c->wn32, c->wmax_bits);
+                     c->mu, store_centered ? c->Wc : nullptr, c->wn32, c->wmax_bits,
+                     want_wn64 ? c->wn64 : nullptr);
   return hipGetLastError();
 }
 

@@ -63,7 +63,7 @@ static void free_row_scratch(som_ctx *c) {
 
 // Scratch that scales with the number of instances; grown (never shrunk) on demand.
 static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
-  const bool need_partial = dense && (c->partial == nullptr || c->collect_list == nullptr);
+  const bool need_partial = (dense && (c->partial == nullptr || c->Wc == nullptr)) || c->collect_list == nullptr;
   if (n <= c->n_cap && !need_partial) return SOM_OK;
   if (n > c->n_cap) {
     (void)hipStreamSynchronize(c->stream);
@@ -89,9 +89,13 @@ static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
     if (!dev_alloc(&c->partial, (size_t)c->max_chunks * c->dim))
       return fail(c, SOM_ERR_ALLOC, "cannot allocate %lld x %d partial sums", (long long)c->max_chunks, c->dim);
   }
-  if (dense && c->collect_list == nullptr) {
+  if (c->collect_list == nullptr) {
     if (!dev_alloc(&c->collect_list, (size_t)c->n_cap * kListCap))
       return fail(c, SOM_ERR_ALLOC, "cannot allocate candidate lists for %lld instances", (long long)c->n_cap);
+  }
+  if (dense && c->Wc == nullptr) {
+    if (!dev_alloc(&c->Wc, (size_t)c->k * c->dim))
+      return fail(c, SOM_ERR_ALLOC, "cannot allocate the centred code book (%d x %d)", c->k, c->dim);
   }
   return SOM_OK;
 }
@@ -162,7 +166,7 @@ static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *
     SOM_LAUNCH(c, launch_row_sqnorms(c, c->mu, 1, c->dim, nullptr, c->mu_norm2, nullptr, nullptr));
     SOM_LAUNCH(c, launch_row_sqnorms(c, X, n, c->dim, nullptr, c->xn32, nullptr, nullptr));
   }
-  SOM_LAUNCH(c, launch_center_codebook(c, W));
+  SOM_LAUNCH(c, launch_center_codebook(c, W, true, false));
   SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 3));
   {
     StageTimer t(c, 0);
@@ -181,11 +185,16 @@ static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indi
                           int64_t n, const float *W, int32_t *bmus, bool have_xn) {
   int rc = ensure_transposed(c);
   if (rc) return rc;
-  SOM_LAUNCH(c, launch_row_sqnorms(c, W, c->k, c->dim, nullptr, c->wn32, c->wn64, c->wmax_bits));
   if (!have_xn) {
     c->d_norms_valid = 0;
     SOM_LAUNCH(c, launch_csr_row_sqnorms(c, indptr, values, n, c->xn32));
   }
+  // centring vector of the sparse search: the mean of the code-book rows (changes every epoch);
+  // it overwrites the one a registered dense training set may have cached
+  if (c->data_kind == 1) c->d_norms_valid = 0;
+  SOM_LAUNCH(c, launch_sample_col_means(c, W, c->k, c->dim, c->mu));
+  SOM_LAUNCH(c, launch_row_sqnorms(c, c->mu, 1, c->dim, nullptr, c->mu_norm2, nullptr, nullptr));
+  SOM_LAUNCH(c, launch_center_codebook(c, W, false, true));
   SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 3));
   {
     StageTimer t(c, 1);
@@ -194,6 +203,7 @@ static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indi
   }
   StageTimer t(c, 2);
   SOM_LAUNCH(c, launch_refine_csr(c, indptr, indices, values, W, bmus));
+  SOM_LAUNCH(c, launch_refine_lists_csr(c, indptr, indices, values, W, bmus));
   SOM_LAUNCH(c, launch_rescan_csr(c, indptr, indices, values, W, bmus));
   return SOM_OK;
 }
@@ -283,7 +293,7 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
             dev_alloc(&c->massD, K) && dev_alloc(&c->cntT, 2 * K) && dev_alloc(&c->gx, 2 * (size_t)cols + 1) &&
             dev_alloc(&c->gy, (size_t)rows) && dev_alloc(&c->params, 1) && dev_alloc(&c->list_counts, 4) &&
             dev_alloc(&c->mu, (size_t)dim) && dev_alloc(&c->mu_partial, (size_t)64 * dim) &&
-            dev_alloc(&c->Wc, K * dim) && dev_alloc(&c->zero16, 16) && dev_alloc(&c->mu_norm2, 1) &&
+            dev_alloc(&c->zero16, 16) && dev_alloc(&c->mu_norm2, 1) &&
             dev_alloc(&c->S, K * dim) && dev_alloc(&c->T, images * K * dim);
   if (!ok) {
     som_destroy(c);

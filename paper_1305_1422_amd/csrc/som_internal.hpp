@@ -62,7 +62,7 @@ struct som_ctx {
   float *T;               // [1 or 2][k][dim] sums after the pass along x
   float *Wt;              // [dim][kpad] transposed code book (sparse BMU only, lazily allocated)
   int kpad;
-  float *Wc;              // [k][dim] centred code book w' = fl(w - mu) of the dense BMU search
+  float *Wc;              // [k][dim] centred code book w' = fl(w - mu) of the dense BMU search (lazily allocated)
   float *zero16;          // 64 bytes of zeros: source of out-of-range direct-to-LDS loads
   float *mu_norm2;        // [1] |mu|^2
   float *mu;              // [dim] centring vector of the dense BMU search
@@ -113,7 +113,7 @@ namespace som {
 
 // norms.hip
 hipError_t launch_sample_col_means(som_ctx *c, const float *A, int64_t nrows, int dim, float *mu);
-hipError_t launch_center_codebook(som_ctx *c, const float *W);   // -> Wc, wn32 (= c_i), wmax_bits
+hipError_t launch_center_codebook(som_ctx *c, const float *W, bool store_centered, bool want_wn64);   // -> Wc, wn32 (= c_i), wmax_bits, wn64
 hipError_t launch_row_sqnorms(som_ctx *c, const float *A, int64_t nrows, int dim, const float *mu,
                               float *out32, double *out64, unsigned *max_bits);
 hipError_t launch_csr_row_sqnorms(som_ctx *c, const int64_t *indptr, const float *values, int64_t n,
@@ -132,6 +132,8 @@ hipError_t launch_refine_lists_dense(som_ctx *c, const float *X, const float *W,
 hipError_t launch_rescan_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
 hipError_t launch_refine_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices,
                              const float *values, const float *W, int32_t *bmus);
+hipError_t launch_refine_lists_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices,
+                                   const float *values, const float *W, int32_t *bmus);
 hipError_t launch_rescan_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices,
                              const float *values, const float *W, int32_t *bmus);
 
