@@ -19,6 +19,8 @@
 
 namespace som {
 
+constexpr int kCsrUnroll = 4;      // nonzeros whose gathers are in flight together
+
 // ---------------------------------------------------------------- transpose with centring
 __global__ __launch_bounds__(256) void k_transpose_centered(const float *__restrict__ W,
                                                             const float *__restrict__ mu, int k, int dim, int kpad,
@@ -102,7 +104,25 @@ __global__ __launch_bounds__(256) void k_bmu_csr(const int64_t *__restrict__ ind
             }
             __syncthreads();
             const int m = min(256, len - p0);
-            for (int q = 0; q < m; ++q) {
+            // four nonzeros per step: all their loads are issued before the first use, so that
+            // enough bytes are in flight to cover the latency of the gathers
+            int q = 0;
+            for (; q + kCsrUnroll <= m; q += kCsrUnroll) {
+              float w[kCsrUnroll][ACC];
+#pragma unroll
+              for (int u = 0; u < kCsrUnroll; ++u) {
+                const float *wrow = Wt + s_off[q + u] + node_base;
+#pragma unroll
+                for (int a = 0; a < ACC; ++a) w[u][a] = (sw * span + a * 256 < kpad) ? wrow[a * 256] : 0.f;
+              }
+#pragma unroll
+              for (int u = 0; u < kCsrUnroll; ++u) {
+                const float v = s_val[q + u];
+#pragma unroll
+                for (int a = 0; a < ACC; ++a) acc[a] = fmaf(v, w[u][a], acc[a]);
+              }
+            }
+            for (; q < m; ++q) {
               const float v = s_val[q];
               const float *wrow = Wt + s_off[q] + node_base;
 #pragma unroll
