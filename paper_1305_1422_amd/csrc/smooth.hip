@@ -188,6 +188,124 @@ hipError_t launch_cool_schedule(som_ctx *c, int n_epochs, double r0, double rN, 
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- feature channels, coefficient matrices
+// Faster variant for maps whose sides are at most kSmoothMatMax: the one-dimensional filters
+// are first written out as dense coefficient matrices, transposed so that the 16 coefficients
+// a wavefront needs for 16 neighbouring outputs and one source are contiguous (one scalar
+// load).  A lane owns one feature column, keeps 16 outputs in registers and streams over the
+// sources: 16 multiply-adds per loaded value, all operands but that value in scalar registers.
+//   GxT[image][source parity][xb][xi]  (xi padded to a multiple of 16 with zeros)
+//   GyT[class][yb][e], destination row yi = classes * e + class  (hex: classes = parities)
+constexpr int kSmoothTile = 16;
+
+__global__ __launch_bounds__(256) void k_smooth_tables(const float *__restrict__ gx, const float *__restrict__ gy,
+                                                       int rows, int cols, int hex, int toroid, int xi_pad,
+                                                       int e_pad, float *__restrict__ GxT, float *__restrict__ GyT) {
+  const int par = hex ? 2 : 1;
+  const int64_t nx = (int64_t)par * par * cols * xi_pad;
+  const int64_t ny = (int64_t)par * rows * e_pad;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < nx + ny; o += stride) {
+    if (o < nx) {
+      const int xi = (int)(o % xi_pad);
+      const int xb = (int)((o / xi_pad) % cols);
+      const int ps = (int)((o / ((int64_t)xi_pad * cols)) % par);
+      const int img = (int)(o / ((int64_t)xi_pad * cols * par));
+      GxT[o] = xi < cols ? gx[col_offset2(xi, xb, img, ps, hex, toroid, cols)] : 0.f;
+    } else {
+      const int64_t q = o - nx;
+      const int e = (int)(q % e_pad);
+      const int yb = (int)((q / e_pad) % rows);
+      const int cls = (int)(q / ((int64_t)e_pad * rows));
+      const int yi = par * e + cls;
+      GyT[q] = yi < rows ? gy[row_offset(yi, yb, toroid, rows)] : 0.f;
+    }
+  }
+}
+
+// pass x.  grid = (ceil(dim/256), rows, images * ceil(cols/16)).
+template <bool kHex>
+__global__ __launch_bounds__(256) void k_smooth_x_mat(const float *__restrict__ S, float *__restrict__ T,
+                                                      const float *__restrict__ GxT, int rows, int cols, int dim,
+                                                      int xi_pad) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c = blockIdx.x * 256 + wave * 64 + lane;
+  const bool live = c < dim;
+  const int y = blockIdx.y;
+  const int ntile = (cols + kSmoothTile - 1) / kSmoothTile;
+  const int img = blockIdx.z / ntile;
+  const int xi0 = (blockIdx.z - img * ntile) * kSmoothTile;
+  const int ps = kHex ? (y & 1) : 0;
+  const float *G = GxT + ((int64_t)(img * (kHex ? 2 : 1) + ps) * cols) * xi_pad + xi0;
+  const float *src = S + (int64_t)y * cols * dim + (live ? c : 0);
+  float acc[kSmoothTile];
+#pragma unroll
+  for (int e = 0; e < kSmoothTile; ++e) acc[e] = 0.f;
+  for (int xb = 0; xb < cols; xb += 4) {
+    float s[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) s[u] = (live && xb + u < cols) ? src[(int64_t)(xb + u) * dim] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float *g = G + (int64_t)min(xb + u, cols - 1) * xi_pad;
+#pragma unroll
+      for (int e = 0; e < kSmoothTile; ++e) acc[e] = fmaf(g[e], s[u], acc[e]);
+    }
+  }
+  if (live) {
+    float *dst = T + ((int64_t)img * rows + y) * (int64_t)cols * dim + c;
+#pragma unroll
+    for (int e = 0; e < kSmoothTile; ++e)
+      if (xi0 + e < cols) dst[(int64_t)(xi0 + e) * dim] = acc[e];
+  }
+}
+
+// pass y with the division.  grid = (ceil(dim/256), cols, classes * ceil(E/16)), E = rows per class.
+template <bool kHex>
+__global__ __launch_bounds__(256) void k_smooth_y_mat(const float *__restrict__ T, float *__restrict__ W,
+                                                      const float *__restrict__ GyT,
+                                                      const double *__restrict__ massD, int rows, int cols, int dim,
+                                                      int e_pad) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c = blockIdx.x * 256 + wave * 64 + lane;
+  const bool live = c < dim;
+  const int x = blockIdx.y;
+  const int classes = kHex ? 2 : 1;
+  const int ntile = e_pad / kSmoothTile;
+  const int cls = blockIdx.z / ntile;
+  const int e0 = (blockIdx.z - cls * ntile) * kSmoothTile;
+  const float *G = GyT + ((int64_t)cls * rows) * e_pad + e0;
+  const float *src = T + (kHex ? (int64_t)cls * rows * cols * dim : 0) + (int64_t)x * dim + (live ? c : 0);
+  const int64_t ystride = (int64_t)cols * dim;
+  float acc[kSmoothTile];
+#pragma unroll
+  for (int e = 0; e < kSmoothTile; ++e) acc[e] = 0.f;
+  for (int yb = 0; yb < rows; yb += 4) {
+    float t[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) t[u] = (live && yb + u < rows) ? src[(int64_t)(yb + u) * ystride] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float *g = G + (int64_t)min(yb + u, rows - 1) * e_pad;
+#pragma unroll
+      for (int e = 0; e < kSmoothTile; ++e) acc[e] = fmaf(g[e], t[u], acc[e]);
+    }
+  }
+  if (live) {
+#pragma unroll
+    for (int e = 0; e < kSmoothTile; ++e) {
+      const int yi = classes * (e0 + e) + cls;
+      if (yi < rows) {
+        const int64_t i = (int64_t)yi * cols + x;
+        const double D = massD[i];
+        if (D >= SOM_EPS_MASS) W[i * dim + c] = acc[e] / (float)D;
+      }
+    }
+  }
+}
+
 hipError_t launch_smooth_and_divide(som_ctx *c, float *W) {
   const int hex = c->grid_type == SOM_GRID_HEXAGONAL;
   const int toroid = c->map_type == SOM_MAP_TOROID;
@@ -197,6 +315,29 @@ hipError_t launch_smooth_and_divide(som_ctx *c, float *W) {
                      toroid, c->cntT);
   hipLaunchKernelGGL(k_count_pass_y, dim3((c->k + 255) / 256), dim3(256), 0, c->stream, c->cntT, c->gy, c->rows,
                      c->cols, hex, toroid, c->massD);
+  if (c->GxT) {           // sides small enough for coefficient matrices
+    const int par = hex ? 2 : 1;
+    const int64_t entries = (int64_t)par * par * c->cols * c->xi_pad + (int64_t)par * c->rows * c->e_pad;
+    int tb = (int)((entries + 255) / 256);
+    if (tb > c->n_cu * 8) tb = c->n_cu * 8;
+    hipLaunchKernelGGL(k_smooth_tables, dim3(tb), dim3(256), 0, c->stream, c->gx, c->gy, c->rows, c->cols, hex, toroid,
+                       c->xi_pad, c->e_pad, c->GxT, c->GyT);
+    const unsigned cb256 = (unsigned)((c->dim + 255) / 256);
+    const unsigned xt = (unsigned)(images * ((c->cols + kSmoothTile - 1) / kSmoothTile));
+    const unsigned yt = (unsigned)(par * (c->e_pad / kSmoothTile));
+    if (hex) {
+      hipLaunchKernelGGL(k_smooth_x_mat<true>, dim3(cb256, c->rows, xt), dim3(256), 0, c->stream, c->S, c->T, c->GxT,
+                         c->rows, c->cols, c->dim, c->xi_pad);
+      hipLaunchKernelGGL(k_smooth_y_mat<true>, dim3(cb256, c->cols, yt), dim3(256), 0, c->stream, c->T, W, c->GyT,
+                         c->massD, c->rows, c->cols, c->dim, c->e_pad);
+    } else {
+      hipLaunchKernelGGL(k_smooth_x_mat<false>, dim3(cb256, c->rows, xt), dim3(256), 0, c->stream, c->S, c->T, c->GxT,
+                         c->rows, c->cols, c->dim, c->xi_pad);
+      hipLaunchKernelGGL(k_smooth_y_mat<false>, dim3(cb256, c->cols, yt), dim3(256), 0, c->stream, c->T, W, c->GyT,
+                         c->massD, c->rows, c->cols, c->dim, c->e_pad);
+    }
+    return hipGetLastError();
+  }
   const unsigned cblk = (unsigned)((c->dim + kSmoothCols - 1) / kSmoothCols);
   if (hex) {
     hipLaunchKernelGGL(k_smooth_x<true>, dim3(cblk, c->rows, 2), dim3(256), 0, c->stream, c->S, c->T, c->gx,

@@ -295,6 +295,12 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
             dev_alloc(&c->mu, (size_t)dim) && dev_alloc(&c->mu_partial, (size_t)64 * dim) &&
             dev_alloc(&c->zero16, 16) && dev_alloc(&c->mu_norm2, 1) &&
             dev_alloc(&c->S, K * dim) && dev_alloc(&c->T, images * K * dim);
+  if (ok && rows <= kSmoothMatMax && cols <= kSmoothMatMax) {
+    const size_t par = grid_type == SOM_GRID_HEXAGONAL ? 2 : 1;
+    c->xi_pad = ((cols + 15) / 16) * 16;
+    c->e_pad = (int)(((((size_t)rows + par - 1) / par) + 15) / 16) * 16;
+    ok = dev_alloc(&c->GxT, par * par * cols * c->xi_pad) && dev_alloc(&c->GyT, par * rows * c->e_pad);
+  }
   if (!ok) {
     som_destroy(c);
     return fail(nullptr, SOM_ERR_ALLOC, "cannot allocate map scratch (%d nodes x %d)", c->k, dim);
@@ -318,6 +324,7 @@ void som_destroy(som_ctx *c) {
   dev_free(c->wn32); dev_free(c->wn64); dev_free(c->wmax_bits); dev_free(c->counts); dev_free(c->seg_off);
   dev_free(c->chunk_off); dev_free(c->massD); dev_free(c->cntT); dev_free(c->gx); dev_free(c->gy);
   dev_free(c->params); dev_free(c->list_counts); dev_free(c->S); dev_free(c->T); dev_free(c->Wt);
+  dev_free(c->GxT); dev_free(c->GyT);
   dev_free(c->mu); dev_free(c->mu_partial); dev_free(c->Wc); dev_free(c->zero16); dev_free(c->mu_norm2);
   for (int s = 0; s < SOM_PROFILE_STAGES; ++s) {
     if (!c->prof_ev[s]) continue;

@@ -16,6 +16,7 @@ constexpr int kCand = 4;                  // candidate nodes kept per instance b
 constexpr int kListCap = 64;              // nodes a collected candidate list can hold per instance
 constexpr int kChunkRows = 32;            // instances summed by one block of the segmented accumulation
 constexpr int kSortTile = 4096;           // keys ranked by one wave of the radix scatter
+constexpr int kSmoothMatMax = 1024;        // largest map side for which the smoothing filters are stored as matrices
 constexpr int kProfMax = 512;              // event brackets kept per stage between two reads
 #ifndef SOM_FLUSH_BLOCK
 #define SOM_FLUSH_BLOCK 32
@@ -57,6 +58,8 @@ struct som_ctx {
   double *cntT;           // [2][k] count channel after the pass along x
   float *gx;              // [2*cols+1] neighbourhood factor along x, index = twice the x offset
   float *gy;              // [rows] neighbourhood factor along y
+  float *GxT, *GyT;       // the two filters as transposed coefficient matrices (maps with sides <= kSmoothMatMax)
+  int xi_pad, e_pad;      // padded output extents of GxT / GyT (multiples of 16)
   som::EpochParams *params;   // [1]
   float *S;               // [k][dim] per-node sums
   float *T;               // [1 or 2][k][dim] sums after the pass along x
