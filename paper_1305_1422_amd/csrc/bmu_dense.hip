@@ -192,12 +192,13 @@ static bool direct_loads_ok(const som_ctx *c, const float *X) {
   return (c->dim % 4 == 0) && (((uintptr_t)X | (uintptr_t)c->Wc) % 16 == 0);
 }
 
-// Number of node groups for n instances: enough workgroups for about eight rounds over the chip.
+// Number of node groups for n instances: enough workgroups for about twelve rounds over the chip
+// (measured: 8 rounds lose 3 % to the ragged last round, more than 16 gain nothing).
 int bmu_dense_groups(const som_ctx *c, int64_t n) {
   const int64_t tiles = (n + kTI - 1) / kTI;
   const int nNB = (c->k + kTN - 1) / kTN;
   const int64_t slots = 2ll * c->n_cu;
-  int64_t want = (8 * slots + tiles - 1) / tiles;
+  int64_t want = (12 * slots + tiles - 1) / tiles;
   if (want > nNB) want = nNB;
   if (want > 64) want = 64;
   if (want < 1) want = 1;
