@@ -45,20 +45,34 @@ __global__ __launch_bounds__(256) void k_row_sqnorms(const float *__restrict__ A
   }
 }
 
+// Sum of three doubles over a 256-thread workgroup, in a fixed order; result valid in thread 0.
+__device__ __forceinline__ void block_sum3(double &a, double &b, double &c, double (*scratch)[3]) {
+  a = wave_sum(a);
+  b = wave_sum(b);
+  c = wave_sum(c);
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  if (lane == 0) { scratch[wave][0] = a; scratch[wave][1] = b; scratch[wave][2] = c; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    a = (scratch[0][0] + scratch[1][0]) + (scratch[2][0] + scratch[3][0]);
+    b = (scratch[0][1] + scratch[1][1]) + (scratch[2][1] + scratch[3][1]);
+    c = (scratch[0][2] + scratch[1][2]) + (scratch[2][2] + scratch[3][2]);
+  }
+  __syncthreads();
+}
+
 // w' = fl(w - mu) (stored if Wc is given), c_i = |w'_i|^2 + 2 mu.w'_i, the maximum of |w'_i|^2
-// over the nodes, and optionally |w_i|^2 of the uncentred rows in fp64.
+// over the nodes, and optionally |w_i|^2 of the uncentred rows in fp64.  One workgroup per node.
 __global__ __launch_bounds__(256) void k_center_codebook(const float *__restrict__ W, int k, int dim,
                                                          const float *__restrict__ mu, float *__restrict__ Wc,
                                                          float *__restrict__ cn, unsigned *__restrict__ max_bits,
                                                          double *__restrict__ wn64) {
-  const int lane = threadIdx.x & (kWave - 1);
-  const int wave = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-  const int nwaves = gridDim.x * (blockDim.x / kWave);
-  for (int i = wave; i < k; i += nwaves) {
+  __shared__ double scratch[4][3];
+  for (int i = blockIdx.x; i < k; i += gridDim.x) {
     const float *w = W + (int64_t)i * dim;
-    float *wc = Wc + (int64_t)i * dim;
+    float *wc = Wc ? Wc + (int64_t)i * dim : nullptr;
     double s2 = 0.0, sm = 0.0, sw = 0.0;
-    for (int c = lane; c < dim; c += kWave) {
+    for (int c = threadIdx.x; c < dim; c += 256) {
       const float m = mu[c];
       const float x = w[c];
       const float t = x - m;
@@ -67,15 +81,22 @@ __global__ __launch_bounds__(256) void k_center_codebook(const float *__restrict
       sm += (double)m * (double)t;
       sw += (double)x * (double)x;
     }
-    s2 = wave_sum(s2);
-    sm = wave_sum(sm);
-    sw = wave_sum(sw);
-    if (lane == 0) {
+    block_sum3(s2, sm, sw, scratch);
+    if (threadIdx.x == 0) {
       cn[i] = (float)(s2 + 2.0 * sm);
       atomicMax(max_bits, __float_as_uint((float)s2));
       if (wn64) wn64[i] = sw;
     }
   }
+}
+
+// |v|^2 of one vector, one workgroup.
+__global__ __launch_bounds__(256) void k_vec_sqnorm(const float *__restrict__ v, int dim, float *__restrict__ out) {
+  __shared__ double scratch[4][3];
+  double s = 0.0, z0 = 0.0, z1 = 0.0;
+  for (int c = threadIdx.x; c < dim; c += 256) s += (double)v[c] * (double)v[c];
+  block_sum3(s, z0, z1, scratch);
+  if (threadIdx.x == 0) *out = (float)s;
 }
 
 __global__ __launch_bounds__(256) void k_csr_row_sqnorms(const int64_t *__restrict__ indptr,
@@ -155,10 +176,15 @@ hipError_t launch_sample_col_means(som_ctx *c, const float *A, int64_t nrows, in
   return hipGetLastError();
 }
 
+hipError_t launch_vec_sqnorm(som_ctx *c, const float *v, int dim, float *out) {
+  hipLaunchKernelGGL(k_vec_sqnorm, dim3(1), dim3(256), 0, c->stream, v, dim, out);
+  return hipGetLastError();
+}
+
 hipError_t launch_center_codebook(som_ctx *c, const float *W, bool store_centered, bool want_wn64) {
   hipError_t e = launch_fill_zero_u32(c->stream, c->wmax_bits, 1);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_center_codebook, dim3(grid_for_waves(c, c->k)), dim3(256), 0, c->stream, W, c->k, c->dim,
+  hipLaunchKernelGGL(k_center_codebook, dim3(c->k < c->n_cu * 32 ? c->k : c->n_cu * 32), dim3(256), 0, c->stream, W, c->k, c->dim,
                      c->mu, store_centered ? c->Wc : nullptr, c->wn32, c->wmax_bits,
                      want_wn64 ? c->wn64 : nullptr);
   return hipGetLastError();

@@ -219,6 +219,15 @@ __global__ __launch_bounds__(256) void k_combine_chunks(const int32_t *__restric
   }
 }
 
+// Clears the rows of S that belong to chosen nodes (the smoothing reads no others).
+__global__ __launch_bounds__(256) void k_zero_chosen_rows(const int32_t *__restrict__ counts, int dim,
+                                                          float *__restrict__ S) {
+  const int b = blockIdx.x;
+  if (counts[b] == 0) return;
+  float *dst = S + (int64_t)b * dim;
+  for (int c = blockIdx.y * 256 + threadIdx.x; c < dim; c += gridDim.y * 256) dst[c] = 0.f;
+}
+
 __global__ __launch_bounds__(256) void k_scatter_csr(const int64_t *__restrict__ indptr,
                                                      const int32_t *__restrict__ indices,
                                                      const float *__restrict__ values, int64_t n, int dim, int k,
@@ -297,8 +306,14 @@ hipError_t launch_accumulate_csr(som_ctx *c, const int64_t *indptr, const int32_
   int64_t cb = (n + 255) / 256;
   if (cb > (int64_t)c->n_cu * 16) cb = (int64_t)c->n_cu * 16;
   hipLaunchKernelGGL(k_count_bmus, dim3((unsigned)cb), dim3(256), 0, c->stream, bmus, n, c->k, c->counts);
-  e = launch_fill_zero_u32(c->stream, c->S, (int64_t)c->k * c->dim);
-  if (e != hipSuccess) return e;
+  if (c->GxT) {          // matrix smoothing only reads the rows of chosen nodes
+    int ysplit = (c->dim + 4095) / 4096;
+    if (ysplit > 64) ysplit = 64;
+    hipLaunchKernelGGL(k_zero_chosen_rows, dim3(c->k, ysplit), dim3(256), 0, c->stream, c->counts, c->dim, c->S);
+  } else {
+    e = launch_fill_zero_u32(c->stream, c->S, (int64_t)c->k * c->dim);
+    if (e != hipSuccess) return e;
+  }
   int64_t sb = (n + 3) / 4;
   if (sb > (int64_t)c->n_cu * 32) sb = (int64_t)c->n_cu * 32;
   hipLaunchKernelGGL(k_scatter_csr, dim3((unsigned)sb), dim3(256), 0, c->stream, indptr, indices, values, n,

@@ -223,32 +223,75 @@ __global__ __launch_bounds__(256) void k_smooth_tables(const float *__restrict__
   }
 }
 
+// Nodes that no instance chose contribute nothing to the sums.  Per map row the columns of the
+// nodes with C > 0 are listed in ascending order (hit_x, hit_n), and the map rows that have any
+// (hit_rows, hit_rows[rows] = their number), so that both passes only touch what counts and the
+// rows of S that belong to empty nodes are never read.  One wavefront per map row.
+__global__ __launch_bounds__(64) void k_hit_lists(const int32_t *__restrict__ counts, int rows, int cols,
+                                                  int32_t *__restrict__ hit_x, int32_t *__restrict__ hit_n) {
+  const int lane = threadIdx.x;
+  for (int y = blockIdx.x; y < rows; y += gridDim.x) {
+    int n = 0;
+    for (int x0 = 0; x0 < cols; x0 += 64) {
+      const int x = x0 + lane;
+      const bool hit = x < cols && counts[y * cols + x] > 0;
+      const unsigned long long m = __ballot(hit);
+      if (hit) hit_x[y * cols + n + __popcll(m & ((1ull << lane) - 1ull))] = x;
+      n += __popcll(m);
+    }
+    if (lane == 0) hit_n[y] = n;
+  }
+}
+
+__global__ __launch_bounds__(64) void k_hit_rows(const int32_t *__restrict__ hit_n, int rows,
+                                                 int32_t *__restrict__ hit_rows) {
+  const int lane = threadIdx.x;
+  int n = 0;
+  for (int y0 = 0; y0 < rows; y0 += 64) {
+    const int y = y0 + lane;
+    const bool hit = y < rows && hit_n[y] > 0;
+    const unsigned long long m = __ballot(hit);
+    if (hit) hit_rows[n + __popcll(m & ((1ull << lane) - 1ull))] = y;
+    n += __popcll(m);
+  }
+  if (lane == 0) hit_rows[rows] = n;
+}
+
 // pass x.  grid = (ceil(dim/256), rows, images * ceil(cols/16)).
 template <bool kHex>
 __global__ __launch_bounds__(256) void k_smooth_x_mat(const float *__restrict__ S, float *__restrict__ T,
-                                                      const float *__restrict__ GxT, int rows, int cols, int dim,
+                                                      const float *__restrict__ GxT,
+                                                      const int32_t *__restrict__ hit_x,
+                                                      const int32_t *__restrict__ hit_n, int rows, int cols, int dim,
                                                       int xi_pad) {
+  const int y = blockIdx.y;
+  const int nh = hit_n[y];
+  if (nh == 0) return;               // pass y skips this map row
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = blockIdx.x * 256 + wave * 64 + lane;
   const bool live = c < dim;
-  const int y = blockIdx.y;
   const int ntile = (cols + kSmoothTile - 1) / kSmoothTile;
   const int img = blockIdx.z / ntile;
   const int xi0 = (blockIdx.z - img * ntile) * kSmoothTile;
   const int ps = kHex ? (y & 1) : 0;
   const float *G = GxT + ((int64_t)(img * (kHex ? 2 : 1) + ps) * cols) * xi_pad + xi0;
   const float *src = S + (int64_t)y * cols * dim + (live ? c : 0);
+  const int32_t *hx = hit_x + (int64_t)y * cols;
   float acc[kSmoothTile];
 #pragma unroll
   for (int e = 0; e < kSmoothTile; ++e) acc[e] = 0.f;
-  for (int xb = 0; xb < cols; xb += 4) {
+  for (int t = 0; t < nh; t += 4) {
+    int xb[4];
     float s[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) s[u] = (live && xb + u < cols) ? src[(int64_t)(xb + u) * dim] : 0.f;
+    for (int u = 0; u < 4; ++u) {
+      xb[u] = hx[min(t + u, nh - 1)];
+      s[u] = (live && t + u < nh) ? src[(int64_t)xb[u] * dim] : 0.f;
+    }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const float *g = G + (int64_t)min(xb + u, cols - 1) * xi_pad;
+      const float *g = G + (int64_t)xb[u] * xi_pad;
 #pragma unroll
       for (int e = 0; e < kSmoothTile; ++e) acc[e] = fmaf(g[e], s[u], acc[e]);
     }
@@ -265,6 +308,7 @@ __global__ __launch_bounds__(256) void k_smooth_x_mat(const float *__restrict__ 
 template <bool kHex>
 __global__ __launch_bounds__(256) void k_smooth_y_mat(const float *__restrict__ T, float *__restrict__ W,
                                                       const float *__restrict__ GyT,
+                                                      const int32_t *__restrict__ hit_rows,
                                                       const double *__restrict__ massD, int rows, int cols, int dim,
                                                       int e_pad) {
   const int lane = threadIdx.x & 63;
@@ -282,13 +326,18 @@ __global__ __launch_bounds__(256) void k_smooth_y_mat(const float *__restrict__ 
   float acc[kSmoothTile];
 #pragma unroll
   for (int e = 0; e < kSmoothTile; ++e) acc[e] = 0.f;
-  for (int yb = 0; yb < rows; yb += 4) {
+  const int nr = hit_rows[rows];       // map rows that hold at least one chosen node
+  for (int r = 0; r < nr; r += 4) {
+    int yb[4];
     float t[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) t[u] = (live && yb + u < rows) ? src[(int64_t)(yb + u) * ystride] : 0.f;
+    for (int u = 0; u < 4; ++u) {
+      yb[u] = hit_rows[min(r + u, nr - 1)];
+      t[u] = (live && r + u < nr) ? src[(int64_t)yb[u] * ystride] : 0.f;
+    }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const float *g = G + (int64_t)min(yb + u, rows - 1) * e_pad;
+      const float *g = G + (int64_t)yb[u] * e_pad;
 #pragma unroll
       for (int e = 0; e < kSmoothTile; ++e) acc[e] = fmaf(g[e], t[u], acc[e]);
     }
@@ -322,19 +371,22 @@ hipError_t launch_smooth_and_divide(som_ctx *c, float *W) {
     if (tb > c->n_cu * 8) tb = c->n_cu * 8;
     hipLaunchKernelGGL(k_smooth_tables, dim3(tb), dim3(256), 0, c->stream, c->gx, c->gy, c->rows, c->cols, hex, toroid,
                        c->xi_pad, c->e_pad, c->GxT, c->GyT);
+    hipLaunchKernelGGL(k_hit_lists, dim3(c->rows < 1024 ? c->rows : 1024), dim3(64), 0, c->stream, c->counts, c->rows,
+                       c->cols, c->hit_x, c->hit_n);
+    hipLaunchKernelGGL(k_hit_rows, dim3(1), dim3(64), 0, c->stream, c->hit_n, c->rows, c->hit_rows);
     const unsigned cb256 = (unsigned)((c->dim + 255) / 256);
     const unsigned xt = (unsigned)(images * ((c->cols + kSmoothTile - 1) / kSmoothTile));
     const unsigned yt = (unsigned)(par * (c->e_pad / kSmoothTile));
     if (hex) {
       hipLaunchKernelGGL(k_smooth_x_mat<true>, dim3(cb256, c->rows, xt), dim3(256), 0, c->stream, c->S, c->T, c->GxT,
-                         c->rows, c->cols, c->dim, c->xi_pad);
+                         c->hit_x, c->hit_n, c->rows, c->cols, c->dim, c->xi_pad);
       hipLaunchKernelGGL(k_smooth_y_mat<true>, dim3(cb256, c->cols, yt), dim3(256), 0, c->stream, c->T, W, c->GyT,
-                         c->massD, c->rows, c->cols, c->dim, c->e_pad);
+                         c->hit_rows, c->massD, c->rows, c->cols, c->dim, c->e_pad);
     } else {
       hipLaunchKernelGGL(k_smooth_x_mat<false>, dim3(cb256, c->rows, xt), dim3(256), 0, c->stream, c->S, c->T, c->GxT,
-                         c->rows, c->cols, c->dim, c->xi_pad);
+                         c->hit_x, c->hit_n, c->rows, c->cols, c->dim, c->xi_pad);
       hipLaunchKernelGGL(k_smooth_y_mat<false>, dim3(cb256, c->cols, yt), dim3(256), 0, c->stream, c->T, W, c->GyT,
-                         c->massD, c->rows, c->cols, c->dim, c->e_pad);
+                         c->hit_rows, c->massD, c->rows, c->cols, c->dim, c->e_pad);
     }
     return hipGetLastError();
   }

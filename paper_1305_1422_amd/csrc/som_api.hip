@@ -163,7 +163,7 @@ static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *
   if (!have_xn) {
     c->d_norms_valid = 0;
     SOM_LAUNCH(c, launch_sample_col_means(c, X, n, c->dim, c->mu));
-    SOM_LAUNCH(c, launch_row_sqnorms(c, c->mu, 1, c->dim, nullptr, c->mu_norm2, nullptr, nullptr));
+    SOM_LAUNCH(c, launch_vec_sqnorm(c, c->mu, c->dim, c->mu_norm2));
     SOM_LAUNCH(c, launch_row_sqnorms(c, X, n, c->dim, nullptr, c->xn32, nullptr, nullptr));
   }
   SOM_LAUNCH(c, launch_center_codebook(c, W, true, false));
@@ -193,7 +193,7 @@ static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indi
   // it overwrites the one a registered dense training set may have cached
   if (c->data_kind == 1) c->d_norms_valid = 0;
   SOM_LAUNCH(c, launch_sample_col_means(c, W, c->k, c->dim, c->mu));
-  SOM_LAUNCH(c, launch_row_sqnorms(c, c->mu, 1, c->dim, nullptr, c->mu_norm2, nullptr, nullptr));
+  SOM_LAUNCH(c, launch_vec_sqnorm(c, c->mu, c->dim, c->mu_norm2));
   SOM_LAUNCH(c, launch_center_codebook(c, W, false, true));
   SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 3));
   {
@@ -235,7 +235,7 @@ static int registered_norms(som_ctx *c) {
   if (c->d_norms_valid) return SOM_OK;
   if (c->data_kind == 1) {
     SOM_LAUNCH(c, launch_sample_col_means(c, c->d_data, c->d_n, c->dim, c->mu));
-    SOM_LAUNCH(c, launch_row_sqnorms(c, c->mu, 1, c->dim, nullptr, c->mu_norm2, nullptr, nullptr));
+    SOM_LAUNCH(c, launch_vec_sqnorm(c, c->mu, c->dim, c->mu_norm2));
     SOM_LAUNCH(c, launch_row_sqnorms(c, c->d_data, c->d_n, c->dim, nullptr, c->xn32, nullptr, nullptr));
   } else {
     SOM_LAUNCH(c, launch_csr_row_sqnorms(c, c->d_indptr, c->d_values, c->d_n, c->xn32));
@@ -299,7 +299,8 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
     const size_t par = grid_type == SOM_GRID_HEXAGONAL ? 2 : 1;
     c->xi_pad = ((cols + 15) / 16) * 16;
     c->e_pad = (int)(((((size_t)rows + par - 1) / par) + 15) / 16) * 16;
-    ok = dev_alloc(&c->GxT, par * par * cols * c->xi_pad) && dev_alloc(&c->GyT, par * rows * c->e_pad);
+    ok = dev_alloc(&c->GxT, par * par * cols * c->xi_pad) && dev_alloc(&c->GyT, par * rows * c->e_pad) &&
+         dev_alloc(&c->hit_x, K) && dev_alloc(&c->hit_n, (size_t)rows) && dev_alloc(&c->hit_rows, (size_t)rows + 1);
   }
   if (!ok) {
     som_destroy(c);
@@ -324,7 +325,7 @@ void som_destroy(som_ctx *c) {
   dev_free(c->wn32); dev_free(c->wn64); dev_free(c->wmax_bits); dev_free(c->counts); dev_free(c->seg_off);
   dev_free(c->chunk_off); dev_free(c->massD); dev_free(c->cntT); dev_free(c->gx); dev_free(c->gy);
   dev_free(c->params); dev_free(c->list_counts); dev_free(c->S); dev_free(c->T); dev_free(c->Wt);
-  dev_free(c->GxT); dev_free(c->GyT);
+  dev_free(c->GxT); dev_free(c->GyT); dev_free(c->hit_x); dev_free(c->hit_n); dev_free(c->hit_rows);
   dev_free(c->mu); dev_free(c->mu_partial); dev_free(c->Wc); dev_free(c->zero16); dev_free(c->mu_norm2);
   for (int s = 0; s < SOM_PROFILE_STAGES; ++s) {
     if (!c->prof_ev[s]) continue;

@@ -60,6 +60,8 @@ struct som_ctx {
   float *gy;              // [rows] neighbourhood factor along y
   float *GxT, *GyT;       // the two filters as transposed coefficient matrices (maps with sides <= kSmoothMatMax)
   int xi_pad, e_pad;      // padded output extents of GxT / GyT (multiples of 16)
+  int32_t *hit_x, *hit_n; // [k] columns of the chosen nodes per map row, [rows] their number
+  int32_t *hit_rows;      // [rows+1] map rows with chosen nodes, last entry = their number
   som::EpochParams *params;   // [1]
   float *S;               // [k][dim] per-node sums
   float *T;               // [1 or 2][k][dim] sums after the pass along x
@@ -116,6 +118,7 @@ namespace som {
 
 // norms.hip
 hipError_t launch_sample_col_means(som_ctx *c, const float *A, int64_t nrows, int dim, float *mu);
+hipError_t launch_vec_sqnorm(som_ctx *c, const float *v, int dim, float *out);
 hipError_t launch_center_codebook(som_ctx *c, const float *W, bool store_centered, bool want_wn64);   // -> Wc, wn32 (= c_i), wmax_bits, wn64
 hipError_t launch_row_sqnorms(som_ctx *c, const float *A, int64_t nrows, int dim, const float *mu,
                               float *out32, double *out64, unsigned *max_bits);
