@@ -39,6 +39,7 @@ enum { SOM_OK = 0, SOM_ERR_INVALID_ARG = 1, SOM_ERR_ALLOC = 2, SOM_ERR_DEVICE = 
 enum { SOM_MAP_PLANAR = 0, SOM_MAP_TOROID = 1 };          /* option -m: planar (default) or toroid   */
 enum { SOM_GRID_SQUARE = 0, SOM_GRID_HEXAGONAL = 1 };     /* option -g: square (default) or hexagonal */
 enum { SOM_COOL_LINEAR = 0, SOM_COOL_EXPONENTIAL = 1 };   /* options -t / -T                          */
+enum { SOM_FILTER_FP32 = 0, SOM_FILTER_SPLIT_F16 = 1 };   /* see som_set_filter                       */
 
 /* Neighbourhood mass below which a node keeps its weights (see som_train_epoch_dense). */
 #define SOM_EPS_MASS 1e-20
@@ -175,6 +176,43 @@ int som_cool_schedule(som_ctx *ctx, int n_epochs, float radius0, float radiusN, 
 int som_umatrix(som_ctx *ctx, const float *codebook, float *umatrix);
 
 /*
+ * som_set_filter - choose the arithmetic of the dense BMU filter pass (paper, "Parallelism":
+ * the GPU variant obtains the distances through linear algebra).  The result of a BMU search
+ * does not depend on it: every filter only shortlists nodes within a proven rounding bound,
+ * and exact fp64 distances decide.
+ *   SOM_FILTER_SPLIT_F16 (default)  every fp32 operand is split into two fp16 numbers and the
+ *                  dot products run as three fp16 matrix instructions with fp32 accumulation:
+ *                  fp32-grade scores at several times the fp32 matrix rate; needs 4 bytes per
+ *                  element of extra device memory for instances and code book.
+ *   SOM_FILTER_FP32  fp32 matrix instructions on the operands as they are.
+ * Errors: unknown value -> SOM_ERR_INVALID_ARG.
+ */
+int som_set_filter(som_ctx *ctx, int filter);
+
+/*
+ * som_debug_scores_dense - test hook (not an operation of the paper): runs the split-fp16
+ * filter on data [n][dim] against codebook and writes EVERY score, not just the candidates:
+ * scores[j * rows*cols + i] = c_i - 2 x_j . w'_i as the filter computed it, w' = fl(w - mu),
+ * c_i = |w'_i|^2 + 2 mu . w'_i; mu_out [dim] receives the centring vector mu that was used.
+ * All pointers are device pointers; scores must hold n * rows*cols floats.  A test compares
+ * the scores with their exact values and the rounding bound the exact stage relies on.
+ * Errors: NULL pointers, n out of range -> SOM_ERR_INVALID_ARG; filter is not
+ * SOM_FILTER_SPLIT_F16 -> SOM_ERR_STATE.
+ */
+int som_debug_scores_dense(som_ctx *ctx, const float *data, int64_t n, const float *codebook, float *scores,
+                           float *mu_out);
+
+/*
+ * som_debug_mfma_f16 - test hook (not an operation of the paper): `count` independent
+ * executions of the 32x32x16 fp16 matrix instruction, D = A B^T + C with A [32][16] and
+ * B [32][16] given as fp16 bit patterns, C and D [32][32] fp32, problem t at offsets 512 t
+ * (A, B) and 1024 t (C, D); device pointers.  Lets a test check the rounding behaviour that
+ * the split-fp16 filter's error bound assumes of the instruction.
+ */
+int som_debug_mfma_f16(const uint16_t *a, const uint16_t *b, const float *c_in, float *d_out, int count,
+                       void *hip_stream);
+
+/*
  * som_get_stats - counters of the most recent BMU search on ctx (synchronises the stream).
  *   rows_refined   instances whose fp32 scores left two to four candidate nodes, decided by
  *                  the exact fp64 distances of those candidates;
@@ -190,17 +228,19 @@ int som_get_stats(som_ctx *ctx, int64_t *out);
  * som_profile_enable / som_profile_read - measurement support (not an operation of the paper).
  * While enabled, the library brackets the stages of every epoch with HIP events recorded on
  * the context's stream, so a benchmark can report per-stage device time without a profiler:
- *   stage 0  dense fp32 BMU pass (one MFMA kernel launch per epoch)
- *   stage 1  sparse fp32 BMU pass (transpose + CSR kernel)
+ *   stage 0  dense BMU filter pass (one MFMA kernel launch per epoch)
+ *   stage 1  sparse BMU filter pass (transpose + CSR kernel)
  *   stage 2  exact BMU stage (certify, candidate collection, refine, rescan)
  *   stage 3  per-node sums (sort by BMU, chunk sums / sparse scatter)
  *   stage 4  neighbourhood smoothing and division
+ *   stage 5  preparation of the dense filter pass (centring vector and norms of unregistered
+ *            data, centred code book, fp16 planes)
  * som_profile_read synchronises the stream, adds up the elapsed time of all brackets recorded
- * since the last read, stores milliseconds in total_ms[0..4] and bracket counts in
- * launches[0..4] (HOST pointers), and clears the record.  At most 512 brackets per stage are
+ * since the last read, stores milliseconds in total_ms[0..5] and bracket counts in
+ * launches[0..5] (HOST pointers), and clears the record.  At most 512 brackets per stage are
  * kept between two reads; further ones are not recorded.
  */
-#define SOM_PROFILE_STAGES 5
+#define SOM_PROFILE_STAGES 6
 int som_profile_enable(som_ctx *ctx, int on);
 int som_profile_read(som_ctx *ctx, double *total_ms, int64_t *launches);
 

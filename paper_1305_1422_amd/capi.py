@@ -18,6 +18,7 @@ SOM_OK, SOM_ERR_INVALID_ARG, SOM_ERR_ALLOC, SOM_ERR_DEVICE, SOM_ERR_STATE = 0, 1
 SOM_MAP_PLANAR, SOM_MAP_TOROID = 0, 1
 SOM_GRID_SQUARE, SOM_GRID_HEXAGONAL = 0, 1
 SOM_COOL_LINEAR, SOM_COOL_EXPONENTIAL = 0, 1
+SOM_FILTER_FP32, SOM_FILTER_SPLIT_F16 = 0, 1
 
 EXPORTS = [
     "som_init", "som_destroy", "som_last_error",
@@ -27,8 +28,9 @@ EXPORTS = [
     "som_set_data_dense", "som_set_data_csr", "som_train",
     "som_cool_schedule", "som_umatrix", "som_get_stats",
     "som_profile_enable", "som_profile_read",
+    "som_set_filter", "som_debug_scores_dense", "som_debug_mfma_f16",
 ]
-PROFILE_STAGES = ("bmu_dense_fp32", "bmu_csr_fp32", "bmu_exact", "node_sums", "smooth_divide")
+PROFILE_STAGES = ("bmu_dense_filter", "bmu_csr_filter", "bmu_exact", "node_sums", "smooth_divide", "prepare_dense")
 
 
 class SomError(RuntimeError):
@@ -83,6 +85,12 @@ def load():
     L.som_profile_enable.argtypes = [vp, i32]
     L.som_profile_read.restype = i32
     L.som_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
+    L.som_set_filter.restype = i32
+    L.som_set_filter.argtypes = [vp, i32]
+    L.som_debug_scores_dense.restype = i32
+    L.som_debug_scores_dense.argtypes = [vp, vp, i64, vp, vp, vp]
+    L.som_debug_mfma_f16.restype = i32
+    L.som_debug_mfma_f16.argtypes = [vp, vp, vp, vp, i32, vp]
     _lib = L
     return L
 
@@ -232,3 +240,27 @@ def som_profile_read(ctx):
     cnt = (C.c_int64 * len(PROFILE_STAGES))()
     _check(ctx, load().som_profile_read(ctx, ms, cnt))
     return {name: (float(ms[i]), int(cnt[i])) for i, name in enumerate(PROFILE_STAGES)}
+
+
+def som_set_filter(ctx, filter: int) -> None:
+    _check(ctx, load().som_set_filter(ctx, filter))
+
+
+def som_debug_scores_dense(ctx, data, codebook, scores, mu_out) -> None:
+    """Test hook: every score of the split-fp16 filter, scores [n][k], and the centring vector used."""
+    import torch
+    _check(ctx, load().som_debug_scores_dense(ctx, _ptr(data, torch.float32, "data"), data.shape[0],
+                                              _ptr(codebook, torch.float32, "codebook"),
+                                              _ptr(scores, torch.float32, "scores"),
+                                              _ptr(mu_out, torch.float32, "mu_out")))
+
+
+def som_debug_mfma_f16(a, b, c_in, d_out) -> None:
+    """Test hook: D = A B^T + C by one 32x32x16 fp16 matrix instruction per problem.
+    a, b: [count][32][16] float16; c_in, d_out: [count][32][32] float32 (device tensors)."""
+    import torch
+    rc = load().som_debug_mfma_f16(_ptr(a, torch.float16, "a"), _ptr(b, torch.float16, "b"),
+                                   _ptr(c_in, torch.float32, "c_in"), _ptr(d_out, torch.float32, "d_out"),
+                                   a.shape[0], C.c_void_p(torch.cuda.current_stream().cuda_stream))
+    if rc != SOM_OK:
+        raise SomError(rc, "som_debug_mfma_f16 failed")

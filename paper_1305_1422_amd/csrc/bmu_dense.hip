@@ -122,6 +122,7 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense(const float *__restrict__ 
     }
   };
 
+  const float kMinusTwo[2] = {-2.f, -2.f};
   Top2 top[2];
   float lim[2];                       // collect mode: per-instance threshold
   int64_t slot_of[2];
@@ -177,13 +178,13 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense(const float *__restrict__ 
 #pragma unroll
           for (int v = 0; v < 16; ++v) { tot[mi][ni][v] += acc[mi][ni][v]; acc[mi][ni][v] = 0.f; }
     }
-    if (last_k) consume_scores<kCollect>(tot, sWn[nb & 1], nb * kTN, k, wm, lhi, top, lim, slot_of, cnt, list);
+    if (last_k) consume_scores<kCollect>(tot, sWn[nb & 1], nb * kTN, k, wm, lhi, kMinusTwo, top, lim, slot_of, cnt, list);
 
     if (t + 1 < total) stage(t + 1);
     __syncthreads();
   }
   if (kCollect) return;
-  merge_and_store(top, &sW[0][0], reinterpret_cast<int *>(&sX[0][0]), tid, wm, wi, l32, lhi, inst0, n, blockIdx.y,
+  merge_and_store<kTI>(top, &sW[0][0], reinterpret_cast<int *>(&sX[0][0]), tid, wm, wi, l32, lhi, inst0, n, blockIdx.y,
                   out);
 }
 

@@ -52,11 +52,13 @@ __device__ __forceinline__ bool cand_less(float a, int ai, float b, int bi) {
 // MFMA 32x32 output element v of a lane: local node row within the 64-node half of a wavefront.
 __device__ __forceinline__ int mfma_row(int mi, int v, int lhi) { return mi * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3); }
 
-// Scores of one node block: push into the running lists (filter mode) or append the nodes under
+// Scores of one node block, s = c_i + factor * dot (factor = -2, times the operand scales where
+// the operands were scaled): push into the running lists (filter mode) or append the nodes under
 // the per-instance threshold to the collected lists (collect mode).  `tot` is cleared.
 template <bool kCollect>
 __device__ __forceinline__ void consume_scores(f32x16 (&tot)[2][2], const float *__restrict__ swn, int node0, int k,
-                                               int wm, int lhi, Top2 (&top)[2], const float (&lim)[2],
+                                               int wm, int lhi, const float (&factor)[2], Top2 (&top)[2],
+                                               const float (&lim)[2],
                                                const int64_t (&slot_of)[2], int32_t *__restrict__ cnt,
                                                int32_t *__restrict__ list) {
 #pragma unroll
@@ -68,7 +70,7 @@ __device__ __forceinline__ void consume_scores(f32x16 (&tot)[2][2], const float 
       const int node = node0 + nl;
 #pragma unroll
       for (int ni = 0; ni < 2; ++ni) {
-        const float s = fmaf(-2.f, tot[mi][ni][v], wnv);
+        const float s = fmaf(factor[ni], tot[mi][ni][v], wnv);
         if (kCollect) {
           if (s <= lim[ni] && node < k) {
             const int pos = atomicAdd(&cnt[slot_of[ni]], 1);
@@ -83,8 +85,9 @@ __device__ __forceinline__ void consume_scores(f32x16 (&tot)[2][2], const float 
 }
 
 // Merge the four partial lists of every instance of the tile (two node halves x two lane halves)
-// into kCand candidates plus the smallest dropped score, and store them.  mval/midx: LDS scratch
-// of kTI*4*3 floats and kTI*4*2 ints that no wavefront reads any more.
+// into kCand candidates plus the smallest dropped score, and store them.  TI = instances per
+// tile; mval/midx: LDS scratch of TI*4*3 floats and TI*4*2 ints that no wavefront reads any more.
+template <int TI>
 __device__ __forceinline__ void merge_and_store(const Top2 (&top)[2], float *mval, int *midx, int tid, int wm, int wi,
                                                 int l32, int lhi, int64_t inst0, int64_t n, int64_t group,
                                                 CandView out) {
@@ -98,7 +101,7 @@ __device__ __forceinline__ void merge_and_store(const Top2 (&top)[2], float *mva
     pi[0] = top[ni].i0; pi[1] = top[ni].i1;
   }
   __syncthreads();
-  if (tid < kTI && inst0 + tid < n) {
+  if (tid < TI && inst0 + tid < n) {
     float v[kCand];
     int id[kCand];
     float ov = INFINITY;

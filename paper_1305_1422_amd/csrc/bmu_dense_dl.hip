@@ -130,6 +130,7 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense_dl(const float *__restrict
   const int a_base = (wm * 64 + l32) * kBK;
   const int b_base = (wi * 64 + l32) * kBK;
 
+  const float kMinusTwo[2] = {-2.f, -2.f};
   Top2 top[2];
   float lim[2];
   int64_t slot_of[2];
@@ -190,13 +191,13 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense_dl(const float *__restrict
 #pragma unroll
           for (int v = 0; v < 16; ++v) { tot[mi][ni][v] += acc[mi][ni][v]; acc[mi][ni][v] = 0.f; }
     }
-    if (last_k) consume_scores<kCollect>(tot, sWn[nb & 1], nb * kTN, k, wm, lhi, top, lim, slot_of, cnt, list);
+    if (last_k) consume_scores<kCollect>(tot, sWn[nb & 1], nb * kTN, k, wm, lhi, kMinusTwo, top, lim, slot_of, cnt, list);
 
     wait_vector_memory();
     __syncthreads();
   }
   if (kCollect) return;
-  merge_and_store(top, &sW[0][0], reinterpret_cast<int *>(&sX[0][0]), tid, wm, wi, l32, lhi, inst0, n, blockIdx.y,
+  merge_and_store<kTI>(top, &sW[0][0], reinterpret_cast<int *>(&sX[0][0]), tid, wm, wi, l32, lhi, inst0, n, blockIdx.y,
                   out);
 }
 

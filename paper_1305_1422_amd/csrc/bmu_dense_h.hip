@@ -1,0 +1,265 @@
+// Dense best-matching-unit search, filter pass on the fp16 matrix cores with split operands
+// (paper: BMU equation; "Parallelism": distances through linear algebra).
+//
+// Same scores as the fp32 pass (bmu_dense_dl.hip): s = c_i - 2 x.w'_i with w' = fl(w - mu), but the
+// dot product is evaluated as three fp16 MFMAs on the hi/lo planes written by split_f16.hip:
+//     x.w' = sx sw (hi_x.hi_w + hi_x.lo_w + lo_x.hi_w) (1 + O(2^-22)),
+// accumulated in fp32 by v_mfma_f32_32x32x16_f16.  On gfx950 that instruction issues in 8 passes
+// for 16 k-values where the fp32 one needs 16 passes for 2: three of them per k-step are 5.3 times
+// the fp32 rate.  The exact stage (bmu_exact.hip) decides as before; only its margin differs.
+//
+// At this rate the operand traffic matters, so the tile is larger than in the fp32 pass: a
+// 512-thread workgroup (8 wavefronts, 2 x 4, each 64 nodes x 64 instances = 2 x 2 MFMA blocks)
+// owns 256 instances and sweeps its group of node blocks of 128.  LDS holds two stages of
+// (128 + 256) rows x 128 bytes = 96 KB, one workgroup per CU, two wavefronts per SIMD.  The 128
+// bytes of a tile row are one chunk of the split layout: 32 hi halves, 32 lo halves.  Tiles are
+// loaded straight into LDS with the XOR swizzle of the fp32 pass (the two passes share the row
+// geometry, so the same swizzle makes the ds_read_b128 operand reads conflict-free): 16-byte
+// slot q of a row holds hi columns 8 q .. 8 q + 7 (q < 4) or lo columns 8 (q - 4) .. (q >= 4),
+// and the MFMA k-step t takes slot 2 t + (lane >> 5) of either plane.
+//
+// The grid is one-dimensional and decoded so that the node groups of one instance tile are
+// workgroups 8 apart: the dispatcher hands those to the same XCD one after the other, they
+// stream the same instance tile at about the same time, and all but the first find it in that
+// XCD's L2.
+#include "bmu_dense_common.hpp"
+
+namespace som {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) void *lptr_h_t;
+
+constexpr int kHTI = 256;                  // instances per tile
+constexpr int kHRow = 32;                  // floats per tile row (= 64 halves = one chunk of 32 columns)
+constexpr int kHFlushChunks = 2;           // chunks (of 32 columns) between accumulator flushes
+constexpr int kHWTile = kTN * kHRow;       // floats
+constexpr int kHXTile = kHTI * kHRow;
+
+__device__ __forceinline__ unsigned lds_address_h(const float *p) { return (unsigned)(size_t)(lptr_h_t)p; }
+
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+// Direct-to-LDS load of 16 bytes per lane (see bmu_dense_dl.hip for why this is inline assembly).
+__device__ __forceinline__ void load16_to_lds_h(const float *g, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_base) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
+__device__ __forceinline__ f16x8 as_halves(f32x4 v) { return __builtin_bit_cast(f16x8, v); }
+
+// kDump: instead of keeping candidates, write every score to dump[slot * k + node] (test hook).
+template <bool kDump>
+__global__ __launch_bounds__(512, 2) void k_bmu_dense_h(const float *__restrict__ Xh, const float *__restrict__ Wh,
+                                                        const float *__restrict__ wc,
+                                                        const float *__restrict__ xscale,
+                                                        const float *__restrict__ wscale,
+                                                        const float *__restrict__ zero16, int64_t n, int k, int nK,
+                                                        int groups, CandView out, float *__restrict__ dump) {
+  __shared__ __attribute__((aligned(16))) float sW[2][kHWTile];
+  __shared__ __attribute__((aligned(16))) float sX[2][kHXTile];
+  __shared__ float sWn[2][kTN];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 2;          // which 64-node half of the tile
+  const int wi = wave & 3;           // which 64-instance quarter of the tile
+  const int l32 = lane & 31;
+  const int lhi = lane >> 5;
+
+  // workgroup -> (instance tile, node group)
+  const int64_t ntiles = (n + kHTI - 1) / kHTI;
+  const int xcd = blockIdx.x & 7;
+  const int64_t slot_id = blockIdx.x >> 3;
+  const int group = (int)(slot_id % groups);
+  const int64_t tile = (slot_id / groups) * 8 + xcd;
+  if (tile >= ntiles) return;        // uniform over the workgroup
+  const int64_t inst0 = tile * kHTI;
+
+  const int nNB_all = (k + kTN - 1) / kTN;
+  const int nb_per = (nNB_all + groups - 1) / groups;
+  const int nb_first = group * nb_per;
+  const int nNB = min(nb_per, nNB_all - nb_first);
+  if (nNB <= 0) return;              // uniform over the workgroup
+  const int total = nK * nNB;
+  const int64_t row_floats = (int64_t)nK * kHRow;
+
+  // ---- loader: one instruction fills 8 tile rows (64 lanes x 16 bytes); wavefront w issues W slots
+  // 2 w, 2 w + 1 and X slots 4 w .. 4 w + 3; lane l sits at row + (l >> 3), slot position l & 7.
+  const int ld_rloc = lane >> 3;
+  const int ld_pos = lane & 7;
+  const float *xp[4];
+  const float *wp[2];
+  int wrow[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = 8 * (4 * wave + i) + ld_rloc;
+    const int q = ld_pos ^ ((row & 7) ^ ((row >> 3) & 1));
+    const int64_t slot = inst0 + row;
+    xp[i] = slot < n ? Xh + slot * row_floats + 4 * q : nullptr;
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    wrow[i] = 8 * (2 * wave + i) + ld_rloc;
+    wp[i] = nullptr;
+  }
+  const int wq = 4 * (ld_pos ^ ((wrow[0] & 7) ^ ((wrow[0] >> 3) & 1)));   // the two rows differ by 8: other swizzle
+  const int wq1 = 4 * (ld_pos ^ ((wrow[1] & 7) ^ ((wrow[1] >> 3) & 1)));
+  const unsigned lds_w = lds_address_h(&sW[0][512 * wave]);     // 2 slots x 256 floats per wavefront
+  const unsigned lds_x = lds_address_h(&sX[0][1024 * wave]);    // 4 slots
+  int ld_nb = nb_first, ld_kc = 0;
+  auto issue_loads = [&](int buf) {
+    if (ld_kc == 0) {                                           // entering a node block
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int64_t node = (int64_t)ld_nb * kTN + wrow[i];
+        wp[i] = node < k ? Wh + node * row_floats + (i == 0 ? wq : wq1) : nullptr;
+      }
+      if (tid < kTN) {
+        const int node = ld_nb * kTN + tid;
+        sWn[ld_nb & 1][tid] = node < k ? wc[node] : INFINITY;    // padded nodes can never win
+      }
+    }
+    const int off = ld_kc * kHRow;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      load16_to_lds_h(wp[i] ? wp[i] + off : zero16, lds_w + buf * (kHWTile * 4) + i * 1024);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      load16_to_lds_h(xp[i] ? xp[i] + off : zero16, lds_x + buf * (kHXTile * 4) + i * 1024);
+    if (++ld_kc == nK) { ld_kc = 0; ++ld_nb; }
+  };
+
+  // ---- reader
+  const int rd_swz = (l32 & 7) ^ ((l32 >> 3) & 1);
+  int rd_off[4];                     // [0], [1]: hi plane of k-steps 0, 1; [2], [3]: lo plane
+#pragma unroll
+  for (int g = 0; g < 4; ++g) rd_off[g] = 4 * ((2 * g + lhi) ^ rd_swz);
+  const int a_base = (wm * 64 + l32) * kHRow;
+  const int b_base = (wi * 64 + l32) * kHRow;
+
+  Top2 top[2];
+  float lim[2] = {0.f, 0.f};
+  int64_t slot_of[2];
+  float factor[2];
+  const float sw = *wscale;
+#pragma unroll
+  for (int ni = 0; ni < 2; ++ni) {
+    top2_init(top[ni]);
+    slot_of[ni] = inst0 + wi * 64 + ni * 32 + l32;
+    factor[ni] = slot_of[ni] < n ? -2.f * xscale[slot_of[ni]] * sw : 0.f;
+  }
+
+  f32x16 acc[2][2], tot[2][2];
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { acc[mi][ni][v] = 0.f; tot[mi][ni][v] = 0.f; }
+
+  issue_loads(0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wavefront's direct-to-LDS loads have landed
+  __syncthreads();
+
+  for (int t = 0; t < total; ++t) {
+    const int nb = nb_first + t / nK, kc = t % nK;
+    if (t + 1 < total) issue_loads((t + 1) & 1);
+
+    const float *pw = &sW[t & 1][a_base];
+    const float *px = &sX[t & 1][b_base];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      f16x8 g1[2], g2[2], h1[2], h2[2];
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        g1[b] = as_halves(*reinterpret_cast<const f32x4 *>(pw + b * 32 * kHRow + rd_off[ks]));
+        g2[b] = as_halves(*reinterpret_cast<const f32x4 *>(pw + b * 32 * kHRow + rd_off[2 + ks]));
+        h1[b] = as_halves(*reinterpret_cast<const f32x4 *>(px + b * 32 * kHRow + rd_off[ks]));
+        h2[b] = as_halves(*reinterpret_cast<const f32x4 *>(px + b * 32 * kHRow + rd_off[2 + ks]));
+      }
+      // the four output blocks take turns, so that an accumulator is reused every fourth MFMA only
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(g2[mi], h1[ni], acc[mi][ni], 0, 0, 0);
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(g1[mi], h2[ni], acc[mi][ni], 0, 0, 0);
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(g1[mi], h1[ni], acc[mi][ni], 0, 0, 0);
+    }
+
+    const bool last_k = (kc == nK - 1);
+    if (last_k || (kc % kHFlushChunks) == kHFlushChunks - 1) {
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) { tot[mi][ni][v] += acc[mi][ni][v]; acc[mi][ni][v] = 0.f; }
+    }
+    if (last_k) {
+      if (kDump) {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int nl = wm * 64 + mfma_row(mi, v, lhi);
+            const int node = nb * kTN + nl;
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+              if (node < k && slot_of[ni] < n) dump[slot_of[ni] * k + node] = fmaf(factor[ni], tot[mi][ni][v], sWn[nb & 1][nl]);
+              tot[mi][ni][v] = 0.f;
+            }
+          }
+      } else {
+        consume_scores<false>(tot, sWn[nb & 1], nb * kTN, k, wm, lhi, factor, top, lim, slot_of, nullptr, nullptr);
+      }
+    }
+
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+  }
+  if (kDump) return;
+  merge_and_store<kHTI>(top, &sW[0][0], reinterpret_cast<int *>(&sX[0][0]), tid, wm, wi, l32, lhi, inst0, n, group,
+                        out);
+}
+
+// Node groups per instance tile: enough workgroups for about ten rounds over the CUs.
+int bmu_dense_h_groups(const som_ctx *c, int64_t n) {
+  const int64_t tiles = (n + kHTI - 1) / kHTI;
+  const int nNB = (c->k + kTN - 1) / kTN;
+  const int64_t slots = c->n_cu;
+  int64_t want = (10 * slots + tiles - 1) / tiles;
+  if (want > nNB) want = nNB;
+  if (want > 64) want = 64;
+  if (want < 1) want = 1;
+  const int nb_per = (int)((nNB + want - 1) / want);
+  return (nNB + nb_per - 1) / nb_per;
+}
+
+hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump) {
+  const int groups = bmu_dense_h_groups(c, n);
+  const int64_t tiles = (n + kHTI - 1) / kHTI;
+  const int64_t blocks = (tiles + 7) / 8 * 8 * groups;
+  const int nK = (c->dim + 31) / 32;
+  CandView out{c->cand_val, c->cand_idx, c->cand_over};
+  const float *Xh = reinterpret_cast<const float *>(c->Xh);
+  const float *Wh = reinterpret_cast<const float *>(c->Wh);
+  if (dump)
+    hipLaunchKernelGGL((k_bmu_dense_h<true>), dim3((unsigned)blocks), dim3(512), 0, c->stream, Xh, Wh, c->wn32, c->xscale,
+                       c->wscale, c->zero16, n, c->k, nK, groups, out, dump);
+  else
+    hipLaunchKernelGGL((k_bmu_dense_h<false>), dim3((unsigned)blocks), dim3(512), 0, c->stream, Xh, Wh, c->wn32, c->xscale,
+                       c->wscale, c->zero16, n, c->k, nK, groups, out, dump);
+  return hipGetLastError();
+}
+
+}  // namespace som

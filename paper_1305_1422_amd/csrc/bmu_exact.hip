@@ -29,20 +29,31 @@
 
 namespace som {
 
-__device__ __forceinline__ double score_margin(double g, double xnorm2, double wmax2, double munorm2) {
+// Coefficients of the bound for one filter variant: |s_filter - s_exact| <=
+//   u [ coef_xw X Wm + coef_floor (xscale_j Wm + wscale X) + 4 Wm^2 + 6 M Wm ].
+struct MarginModel {
+  double coef_xw;
+  double coef_floor;         // 0 for the fp32 pass
+  const float *xscale;       // [n] power-of-two scale of every instance (split-fp16 pass), else null
+  const float *wscale;       // [1] power-of-two scale of the centred code book, else null
+};
+
+__device__ __forceinline__ double score_margin(const MarginModel &mm, int64_t j, double xnorm2, double wmax2,
+                                               double munorm2) {
   const double u = 5.9604644775390625e-08;   // 2^-24
   const double xn = sqrt(xnorm2 * (1.0 + 1.2e-7));
   const double wm = sqrt(wmax2 * (1.0 + 1.2e-7));
   const double mn = sqrt(munorm2 * (1.0 + 1.2e-7));
-  const double bound = u * ((2.0 * g + 4.0) * xn * wm + 4.0 * wm * wm + 6.0 * mn * wm);
-  return 2.125 * bound;          // both scores of a pair may err, plus slack for higher-order terms
+  double bound = mm.coef_xw * xn * wm + 4.0 * wm * wm + 6.0 * mn * wm;
+  if (mm.xscale) bound += mm.coef_floor * ((double)mm.xscale[j] * wm + (double)*mm.wscale * xn);
+  return 2.125 * u * bound;          // both scores of a pair may err, plus slack for higher-order terms
 }
 
 // `groups` candidate lists per instance (one per node group of the fp32 pass), stored
 // [group][instance][kCand]; the kept candidates are written back into group 0's slots.
 __global__ __launch_bounds__(256) void k_certify(CandView cand, int groups, const float *__restrict__ xn32,
                                                  const unsigned *__restrict__ wmax_bits,
-                                                 const float *__restrict__ mu_norm2, double g, int64_t n, int k,
+                                                 const float *__restrict__ mu_norm2, MarginModel mm, int64_t n, int k,
                                                  int32_t *__restrict__ bmus, int32_t *__restrict__ cand_n,
                                                  int32_t *__restrict__ refine_list,
                                                  int32_t *__restrict__ collect_rows,
@@ -59,7 +70,7 @@ __global__ __launch_bounds__(256) void k_certify(CandView cand, int groups, cons
       if ((unsigned)cand.idx[base + t] < (unsigned)k) smin = fminf(smin, cand.val[base + t]);
     omin = fminf(omin, cand.over[(int64_t)q * n + j]);
   }
-  const double margin = score_margin(g, (double)xn32[j], (double)__uint_as_float(*wmax_bits), (double)*mu_norm2);
+  const double margin = score_margin(mm, j, (double)xn32[j], (double)__uint_as_float(*wmax_bits), (double)*mu_norm2);
   const double thr = (double)smin + margin;
   int keep[kCand];
   int cnt = 0;
@@ -303,12 +314,39 @@ static int persistent_blocks(const som_ctx *c, int64_t upper) {
   return (int)b;
 }
 
-hipError_t launch_certify(som_ctx *c, int64_t n, int32_t *bmus) {
+// Roundings a product term can suffer in the fp32 MFMA pass: the accumulator is flushed into a
+// second one every kDenseAccumBlock features.
+static double fp32_pass_roundings(int dim) {
+  return (double)kDenseAccumBlock + (double)((dim + kDenseAccumBlock - 1) / kDenseAccumBlock) + 2.0;
+}
+
+// The same for the split-fp16 pass, in units of u relative to sum |x_c w'_c|.  Measured
+// behaviour of v_mfma_f32_32x32x16_f16 on gfx950 (checked by a test through som_debug_mfma_f16):
+// the 16 products are aligned to the largest of them and truncated 25 bits below its leading bit,
+// their sum joins the accumulator with an error of at most 2 u of the result.  Priced here at
+// 9 u max|product| + 2.5 u (|C| + sum|products|) per instruction: over a flush interval of 64
+// features (12 instructions) that is 2.5 * 12 + 9; every flush adds one rounding.
+static double split_pass_roundings(int dim) {
+  return 2.5 * 12.0 + 9.0 + (double)((dim + 63) / 64) + 1.0;
+}
+
+hipError_t launch_certify(som_ctx *c, int64_t n, int groups, bool split_filter, int32_t *bmus) {
   CandView cand{c->cand_val, c->cand_idx, c->cand_over};
-  const double g = (double)kDenseAccumBlock + (double)((c->dim + kDenseAccumBlock - 1) / kDenseAccumBlock) + 2.0;
-  hipLaunchKernelGGL(k_certify, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, cand,
-                     bmu_dense_groups(c, n), c->xn32, c->wmax_bits, c->mu_norm2, g, n, c->k, bmus, c->cand_n, c->refine_list, c->collect_rows, c->collect_thr,
-                     c->collect_cnt, c->list_counts);
+  MarginModel mm{2.0 * fp32_pass_roundings(c->dim) + 4.0, 0.0, nullptr, nullptr};
+  if (split_filter) {
+    // dot product: accumulation + 3 * 2^-22 of the split (= 12 u) ; both doubled by the factor -2;
+    // + 4 for the stored c_i, the final multiply-add and the rounding of w - mu.  The collect pass
+    // runs on the fp32 kernel with the threshold computed here, so the margin must cover that
+    // pass's own bound as well: never below the fp32 coefficient.
+    const double split = 2.0 * split_pass_roundings(c->dim) + 24.0 + 4.0;
+    if (split > mm.coef_xw) mm.coef_xw = split;
+    mm.coef_floor = sqrt((double)c->dim);        // 2 * 2^-25 per element = u, |v|_1 <= sqrt(dim) |v|_2
+    mm.xscale = c->xscale;
+    mm.wscale = c->wscale;
+  }
+  hipLaunchKernelGGL(k_certify, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, cand, groups, c->xn32,
+                     c->wmax_bits, c->mu_norm2, mm, n, c->k, bmus, c->cand_n, c->refine_list, c->collect_rows,
+                     c->collect_thr, c->collect_cnt, c->list_counts);
   return hipGetLastError();
 }
 

@@ -62,41 +62,76 @@ __device__ __forceinline__ void block_sum3(double &a, double &b, double &c, doub
 }
 
 // w' = fl(w - mu) (stored if Wc is given), c_i = |w'_i|^2 + 2 mu.w'_i, the maximum of |w'_i|^2
-// over the nodes, and optionally |w_i|^2 of the uncentred rows in fp64.  One workgroup per node.
+// over the nodes, and optionally |w_i|^2 of the uncentred rows in fp64.  kTeam threads per node:
+// a wavefront for short rows, the whole workgroup for long ones.  Every writer thread keeps its
+// own running maximum and issues one atomic at the end.
+template <int kTeam>
 __global__ __launch_bounds__(256) void k_center_codebook(const float *__restrict__ W, int k, int dim,
                                                          const float *__restrict__ mu, float *__restrict__ Wc,
                                                          float *__restrict__ cn, unsigned *__restrict__ max_bits,
-                                                         double *__restrict__ wn64) {
+                                                         double *__restrict__ wn64,
+                                                         unsigned *__restrict__ wabs_bits) {
   __shared__ double scratch[4][3];
-  for (int i = blockIdx.x; i < k; i += gridDim.x) {
+  constexpr int kTeams = 256 / kTeam;
+  const int tl = threadIdx.x % kTeam, team = threadIdx.x / kTeam;
+  float vmax = 0.f;
+  float amax = 0.f;                  // largest |w'| element this thread has seen
+  for (int i = blockIdx.x * kTeams + team; i < k; i += gridDim.x * kTeams) {
     const float *w = W + (int64_t)i * dim;
     float *wc = Wc ? Wc + (int64_t)i * dim : nullptr;
     double s2 = 0.0, sm = 0.0, sw = 0.0;
-    for (int c = threadIdx.x; c < dim; c += 256) {
+    for (int c = tl; c < dim; c += kTeam) {
       const float m = mu[c];
       const float x = w[c];
       const float t = x - m;
       if (Wc) wc[c] = t;
+      amax = fmaxf(amax, fabsf(t));
       s2 += (double)t * (double)t;
       sm += (double)m * (double)t;
       sw += (double)x * (double)x;
     }
-    block_sum3(s2, sm, sw, scratch);
-    if (threadIdx.x == 0) {
+    if (kTeam == 256) {
+      block_sum3(s2, sm, sw, scratch);     // i depends on the block only: every thread gets here
+    } else {
+      s2 = wave_sum(s2);
+      sm = wave_sum(sm);
+      sw = wave_sum(sw);
+    }
+    if (tl == 0) {
       cn[i] = (float)(s2 + 2.0 * sm);
-      atomicMax(max_bits, __float_as_uint((float)s2));
+      vmax = fmaxf(vmax, (float)s2);
       if (wn64) wn64[i] = sw;
     }
   }
+  if (tl == 0 && vmax > 0.f) atomicMax(max_bits, __float_as_uint(vmax));
+  if (wabs_bits) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
+    if ((threadIdx.x & 63) == 0 && amax > 0.f) atomicMax(wabs_bits, __float_as_uint(amax));
+  }
 }
 
-// |v|^2 of one vector, one workgroup.
-__global__ __launch_bounds__(256) void k_vec_sqnorm(const float *__restrict__ v, int dim, float *__restrict__ out) {
-  __shared__ double scratch[4][3];
-  double s = 0.0, z0 = 0.0, z1 = 0.0;
-  for (int c = threadIdx.x; c < dim; c += 256) s += (double)v[c] * (double)v[c];
-  block_sum3(s, z0, z1, scratch);
-  if (threadIdx.x == 0) *out = (float)s;
+// |v|^2 of one vector, one workgroup of 1024 threads, fixed summation order.
+__global__ __launch_bounds__(1024) void k_vec_sqnorm(const float *__restrict__ v, int dim, float *__restrict__ out) {
+  __shared__ double part[16];
+  double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+  int c = threadIdx.x;
+  for (; c + 3072 < dim; c += 4096) {
+    const float a = v[c], b = v[c + 1024], d = v[c + 2048], e = v[c + 3072];
+    s0 += (double)a * (double)a;
+    s1 += (double)b * (double)b;
+    s2 += (double)d * (double)d;
+    s3 += (double)e * (double)e;
+  }
+  for (; c < dim; c += 1024) s0 += (double)v[c] * (double)v[c];
+  const double s = wave_sum((s0 + s1) + (s2 + s3));
+  if ((threadIdx.x & (kWave - 1)) == 0) part[threadIdx.x / kWave] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int w = 0; w < 16; ++w) t += part[w];
+    *out = (float)t;
+  }
 }
 
 __global__ __launch_bounds__(256) void k_csr_row_sqnorms(const int64_t *__restrict__ indptr,
@@ -177,16 +212,25 @@ hipError_t launch_sample_col_means(som_ctx *c, const float *A, int64_t nrows, in
 }
 
 hipError_t launch_vec_sqnorm(som_ctx *c, const float *v, int dim, float *out) {
-  hipLaunchKernelGGL(k_vec_sqnorm, dim3(1), dim3(256), 0, c->stream, v, dim, out);
+  hipLaunchKernelGGL(k_vec_sqnorm, dim3(1), dim3(1024), 0, c->stream, v, dim, out);
   return hipGetLastError();
 }
 
 hipError_t launch_center_codebook(som_ctx *c, const float *W, bool store_centered, bool want_wn64) {
-  hipError_t e = launch_fill_zero_u32(c->stream, c->wmax_bits, 1);
+  hipError_t e = launch_fill_zero_u32(c->stream, c->wmax_bits, 2);     // wmax_bits and wabs_bits are neighbours
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_center_codebook, dim3(c->k < c->n_cu * 32 ? c->k : c->n_cu * 32), dim3(256), 0, c->stream, W, c->k, c->dim,
-                     c->mu, store_centered ? c->Wc : nullptr, c->wn32, c->wmax_bits,
-                     want_wn64 ? c->wn64 : nullptr);
+  float *wc = store_centered ? c->Wc : nullptr;
+  unsigned *wabs = store_centered ? c->wmax_bits + 1 : nullptr;
+  double *wn64 = want_wn64 ? c->wn64 : nullptr;
+  const int cap = c->n_cu * 8;
+  if (c->dim <= 2048) {
+    const int need = (c->k + 3) / 4;
+    hipLaunchKernelGGL(k_center_codebook<64>, dim3(need < cap ? need : cap), dim3(256), 0, c->stream, W, c->k, c->dim,
+                       c->mu, wc, c->wn32, c->wmax_bits, wn64, wabs);
+  } else {
+    hipLaunchKernelGGL(k_center_codebook<256>, dim3(c->k < cap ? c->k : cap), dim3(256), 0, c->stream, W, c->k, c->dim,
+                       c->mu, wc, c->wn32, c->wmax_bits, wn64, wabs);
+  }
   return hipGetLastError();
 }
 

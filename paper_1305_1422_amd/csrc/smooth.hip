@@ -197,6 +197,7 @@ hipError_t launch_cool_schedule(som_ctx *c, int n_epochs, double r0, double rN, 
 //   GxT[image][source parity][xb][xi]  (xi padded to a multiple of 16 with zeros)
 //   GyT[class][yb][e], destination row yi = classes * e + class  (hex: classes = parities)
 constexpr int kSmoothTile = 16;
+constexpr int kSmoothUnroll = 8;    // source nodes whose loads are in flight together
 
 __global__ __launch_bounds__(256) void k_smooth_tables(const float *__restrict__ gx, const float *__restrict__ gy,
                                                        int rows, int cols, int hex, int toroid, int xi_pad,
@@ -257,7 +258,23 @@ __global__ __launch_bounds__(64) void k_hit_rows(const int32_t *__restrict__ hit
   if (lane == 0) hit_rows[rows] = n;
 }
 
-// pass x.  grid = (ceil(dim/256), rows, images * ceil(cols/16)).
+// Channel block and output tile of a workgroup.  Plain launch: channel block on grid.x, tile on
+// grid.z.  Folded launch (grid.z == 1, used when there are at least 8 channel blocks): the tiles
+// that read the same sources sit on workgroups 8 apart on grid.x, which the dispatcher hands to the
+// same XCD one after the other, so that all but the first of their reads hit that XCD's L2.
+__device__ __forceinline__ bool smooth_tile_of_block(int ntiles, int cblocks, int &cblk, int &tile) {
+  if (gridDim.z > 1 || ntiles == 1) {
+    cblk = blockIdx.x;
+    tile = blockIdx.z;
+    return true;
+  }
+  const int p = blockIdx.x & 7, r = blockIdx.x >> 3;
+  tile = r % ntiles;
+  cblk = (r / ntiles) * 8 + p;
+  return cblk < cblocks;
+}
+
+// pass x.  grid = (ceil(dim/256), rows, images * ceil(cols/16)), or folded (see above).
 template <bool kHex>
 __global__ __launch_bounds__(256) void k_smooth_x_mat(const float *__restrict__ S, float *__restrict__ T,
                                                       const float *__restrict__ GxT,
@@ -269,11 +286,13 @@ __global__ __launch_bounds__(256) void k_smooth_x_mat(const float *__restrict__ 
   if (nh == 0) return;               // pass y skips this map row
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int c = blockIdx.x * 256 + wave * 64 + lane;
-  const bool live = c < dim;
   const int ntile = (cols + kSmoothTile - 1) / kSmoothTile;
-  const int img = blockIdx.z / ntile;
-  const int xi0 = (blockIdx.z - img * ntile) * kSmoothTile;
+  int cblk, zt;
+  if (!smooth_tile_of_block((kHex ? 2 : 1) * ntile, (dim + 255) / 256, cblk, zt)) return;
+  const int c = cblk * 256 + wave * 64 + lane;
+  const bool live = c < dim;
+  const int img = zt / ntile;
+  const int xi0 = (zt - img * ntile) * kSmoothTile;
   const int ps = kHex ? (y & 1) : 0;
   const float *G = GxT + ((int64_t)(img * (kHex ? 2 : 1) + ps) * cols) * xi_pad + xi0;
   const float *src = S + (int64_t)y * cols * dim + (live ? c : 0);
@@ -281,16 +300,16 @@ __global__ __launch_bounds__(256) void k_smooth_x_mat(const float *__restrict__ 
   float acc[kSmoothTile];
 #pragma unroll
   for (int e = 0; e < kSmoothTile; ++e) acc[e] = 0.f;
-  for (int t = 0; t < nh; t += 4) {
-    int xb[4];
-    float s[4];
+  for (int t = 0; t < nh; t += kSmoothUnroll) {
+    int xb[kSmoothUnroll];
+    float s[kSmoothUnroll];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kSmoothUnroll; ++u) {
       xb[u] = hx[min(t + u, nh - 1)];
       s[u] = (live && t + u < nh) ? src[(int64_t)xb[u] * dim] : 0.f;
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kSmoothUnroll; ++u) {
       const float *g = G + (int64_t)xb[u] * xi_pad;
 #pragma unroll
       for (int e = 0; e < kSmoothTile; ++e) acc[e] = fmaf(g[e], s[u], acc[e]);
@@ -313,13 +332,15 @@ __global__ __launch_bounds__(256) void k_smooth_y_mat(const float *__restrict__ 
                                                       int e_pad) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int c = blockIdx.x * 256 + wave * 64 + lane;
-  const bool live = c < dim;
-  const int x = blockIdx.y;
   const int classes = kHex ? 2 : 1;
   const int ntile = e_pad / kSmoothTile;
-  const int cls = blockIdx.z / ntile;
-  const int e0 = (blockIdx.z - cls * ntile) * kSmoothTile;
+  int cblk, zt;
+  if (!smooth_tile_of_block(classes * ntile, (dim + 255) / 256, cblk, zt)) return;
+  const int c = cblk * 256 + wave * 64 + lane;
+  const bool live = c < dim;
+  const int x = blockIdx.y;
+  const int cls = zt / ntile;
+  const int e0 = (zt - cls * ntile) * kSmoothTile;
   const float *G = GyT + ((int64_t)cls * rows) * e_pad + e0;
   const float *src = T + (kHex ? (int64_t)cls * rows * cols * dim : 0) + (int64_t)x * dim + (live ? c : 0);
   const int64_t ystride = (int64_t)cols * dim;
@@ -327,16 +348,16 @@ __global__ __launch_bounds__(256) void k_smooth_y_mat(const float *__restrict__ 
 #pragma unroll
   for (int e = 0; e < kSmoothTile; ++e) acc[e] = 0.f;
   const int nr = hit_rows[rows];       // map rows that hold at least one chosen node
-  for (int r = 0; r < nr; r += 4) {
-    int yb[4];
-    float t[4];
+  for (int r = 0; r < nr; r += kSmoothUnroll) {
+    int yb[kSmoothUnroll];
+    float t[kSmoothUnroll];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kSmoothUnroll; ++u) {
       yb[u] = hit_rows[min(r + u, nr - 1)];
       t[u] = (live && r + u < nr) ? src[(int64_t)yb[u] * ystride] : 0.f;
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kSmoothUnroll; ++u) {
       const float *g = G + (int64_t)yb[u] * e_pad;
 #pragma unroll
       for (int e = 0; e < kSmoothTile; ++e) acc[e] = fmaf(g[e], t[u], acc[e]);
@@ -377,15 +398,19 @@ hipError_t launch_smooth_and_divide(som_ctx *c, float *W) {
     const unsigned cb256 = (unsigned)((c->dim + 255) / 256);
     const unsigned xt = (unsigned)(images * ((c->cols + kSmoothTile - 1) / kSmoothTile));
     const unsigned yt = (unsigned)(par * (c->e_pad / kSmoothTile));
+    const bool fold = cb256 >= 8;       // enough channel blocks to keep every XCD busy
+    const unsigned cb8 = (cb256 + 7) / 8 * 8;
+    const dim3 gx = fold ? dim3(cb8 * xt, c->rows, 1) : dim3(cb256, c->rows, xt);
+    const dim3 gy = fold ? dim3(cb8 * yt, c->cols, 1) : dim3(cb256, c->cols, yt);
     if (hex) {
-      hipLaunchKernelGGL(k_smooth_x_mat<true>, dim3(cb256, c->rows, xt), dim3(256), 0, c->stream, c->S, c->T, c->GxT,
+      hipLaunchKernelGGL(k_smooth_x_mat<true>, gx, dim3(256), 0, c->stream, c->S, c->T, c->GxT,
                          c->hit_x, c->hit_n, c->rows, c->cols, c->dim, c->xi_pad);
-      hipLaunchKernelGGL(k_smooth_y_mat<true>, dim3(cb256, c->cols, yt), dim3(256), 0, c->stream, c->T, W, c->GyT,
+      hipLaunchKernelGGL(k_smooth_y_mat<true>, gy, dim3(256), 0, c->stream, c->T, W, c->GyT,
                          c->hit_rows, c->massD, c->rows, c->cols, c->dim, c->e_pad);
     } else {
-      hipLaunchKernelGGL(k_smooth_x_mat<false>, dim3(cb256, c->rows, xt), dim3(256), 0, c->stream, c->S, c->T, c->GxT,
+      hipLaunchKernelGGL(k_smooth_x_mat<false>, gx, dim3(256), 0, c->stream, c->S, c->T, c->GxT,
                          c->hit_x, c->hit_n, c->rows, c->cols, c->dim, c->xi_pad);
-      hipLaunchKernelGGL(k_smooth_y_mat<false>, dim3(cb256, c->cols, yt), dim3(256), 0, c->stream, c->T, W, c->GyT,
+      hipLaunchKernelGGL(k_smooth_y_mat<false>, gy, dim3(256), 0, c->stream, c->T, W, c->GyT,
                          c->hit_rows, c->massD, c->rows, c->cols, c->dim, c->e_pad);
     }
     return hipGetLastError();

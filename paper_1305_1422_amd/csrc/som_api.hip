@@ -56,14 +56,18 @@ static void free_row_scratch(som_ctx *c) {
   dev_free(c->collect_rows); dev_free(c->collect_thr); dev_free(c->collect_cnt); dev_free(c->collect_list);
   dev_free(c->sort_key[0]); dev_free(c->sort_key[1]); dev_free(c->sort_val[0]); dev_free(c->sort_val[1]);
   dev_free(c->radix_hist); dev_free(c->chunk_node); dev_free(c->partial);
+  dev_free(c->Xh); dev_free(c->xscale);
   c->n_cap = 0;
   c->cand_cap = 0;
   c->d_norms_valid = 0;
+  c->d_split_valid = 0;
 }
 
 // Scratch that scales with the number of instances; grown (never shrunk) on demand.
 static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
-  const bool need_partial = (dense && (c->partial == nullptr || c->Wc == nullptr)) || c->collect_list == nullptr;
+  const bool split = dense && c->filter == SOM_FILTER_SPLIT_F16;
+  const bool need_partial = (dense && (c->partial == nullptr || c->Wc == nullptr)) || c->collect_list == nullptr ||
+                            (split && (c->Xh == nullptr || c->Wh == nullptr));
   if (n <= c->n_cap && !need_partial) return SOM_OK;
   if (n > c->n_cap) {
     (void)hipStreamSynchronize(c->stream);
@@ -97,12 +101,24 @@ static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
     if (!dev_alloc(&c->Wc, (size_t)c->k * c->dim))
       return fail(c, SOM_ERR_ALLOC, "cannot allocate the centred code book (%d x %d)", c->k, c->dim);
   }
+  if (split) {
+    const size_t row_halves = (size_t)((c->dim + 31) / 32) * 64;
+    if (c->Wh == nullptr && !dev_alloc(&c->Wh, (size_t)c->k * row_halves))
+      return fail(c, SOM_ERR_ALLOC, "cannot allocate the fp16 planes of the code book");
+    if (c->Xh == nullptr) {
+      c->d_split_valid = 0;
+      if (!(dev_alloc(&c->Xh, (size_t)c->n_cap * row_halves) && dev_alloc(&c->xscale, (size_t)c->n_cap)))
+        return fail(c, SOM_ERR_ALLOC, "cannot allocate the fp16 planes of %lld instances", (long long)c->n_cap);
+    }
+  }
   return SOM_OK;
 }
 
 // The dense fp32 pass writes one candidate list per node group and instance.
 static int ensure_candidates(som_ctx *c, int64_t n) {
-  const int64_t need = (int64_t)bmu_dense_groups(c, n) * n;
+  const int groups_h = c->filter == SOM_FILTER_SPLIT_F16 ? bmu_dense_h_groups(c, n) : 1;
+  const int groups_f = bmu_dense_groups(c, n);
+  const int64_t need = (int64_t)(groups_h > groups_f ? groups_h : groups_f) * n;
   if (need <= c->cand_cap) return SOM_OK;
   (void)hipStreamSynchronize(c->stream);
   dev_free(c->cand_val); dev_free(c->cand_idx); dev_free(c->cand_over);
@@ -157,23 +173,41 @@ struct StageTimer {
 };
 
 // ---------------------------------------------------------------- stages
-static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *W, int32_t *bmus, bool have_xn) {
-  int rc = ensure_candidates(c, n);
-  if (rc) return rc;
+// Everything the filter pass needs besides the instances' own norms: centring vector (unless the
+// data are the registered set, whose vector is kept), centred code book and node constants, and
+// for the split-fp16 filter the fp16 planes of both operands.
+static int prepare_dense(som_ctx *c, const float *X, int64_t n, const float *W, bool have_xn) {
+  StageTimer t(c, 5);
+  const bool split = c->filter == SOM_FILTER_SPLIT_F16;
   if (!have_xn) {
     c->d_norms_valid = 0;
+    c->d_split_valid = 0;
     SOM_LAUNCH(c, launch_sample_col_means(c, X, n, c->dim, c->mu));
     SOM_LAUNCH(c, launch_vec_sqnorm(c, c->mu, c->dim, c->mu_norm2));
     SOM_LAUNCH(c, launch_row_sqnorms(c, X, n, c->dim, nullptr, c->xn32, nullptr, nullptr));
   }
+  if (split && !(have_xn && c->d_split_valid)) {
+    SOM_LAUNCH(c, launch_split_rows_f16(c, X, n, nullptr, c->Xh, c->xscale));
+    c->d_split_valid = have_xn ? 1 : 0;
+  }
   SOM_LAUNCH(c, launch_center_codebook(c, W, true, false));
+  if (split) SOM_LAUNCH(c, launch_split_rows_f16(c, c->Wc, c->k, c->wmax_bits + 1, c->Wh, c->wscale));
   SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 3));
+  return SOM_OK;
+}
+
+static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *W, int32_t *bmus, bool have_xn) {
+  int rc = ensure_candidates(c, n);
+  if (!rc) rc = prepare_dense(c, X, n, W, have_xn);
+  if (rc) return rc;
+  const bool split = c->filter == SOM_FILTER_SPLIT_F16;
   {
     StageTimer t(c, 0);
-    SOM_LAUNCH(c, launch_bmu_dense(c, X, n));
+    if (split) SOM_LAUNCH(c, launch_bmu_dense_h(c, n, nullptr));
+    else SOM_LAUNCH(c, launch_bmu_dense(c, X, n));
   }
   StageTimer t(c, 2);
-  SOM_LAUNCH(c, launch_certify(c, n, bmus));
+  SOM_LAUNCH(c, launch_certify(c, n, split ? bmu_dense_h_groups(c, n) : bmu_dense_groups(c, n), split, bmus));
   SOM_LAUNCH(c, launch_refine_dense(c, X, W, bmus));
   SOM_LAUNCH(c, launch_bmu_dense_collect(c, X, n));
   SOM_LAUNCH(c, launch_refine_lists_dense(c, X, W, bmus));
@@ -277,6 +311,7 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
   c->map_type = map_type; c->grid_type = grid_type;
   c->stream = (hipStream_t)hip_stream;
   c->kpad = ((c->k + 255) / 256) * 256;
+  c->filter = SOM_FILTER_SPLIT_F16;
 
   int dev = 0;
   hipDeviceProp_t prop;
@@ -288,12 +323,12 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
 
   const size_t K = (size_t)c->k;
   const size_t images = grid_type == SOM_GRID_HEXAGONAL ? 2 : 1;
-  bool ok = dev_alloc(&c->wn32, K) && dev_alloc(&c->wn64, K) && dev_alloc(&c->wmax_bits, 1) &&
+  bool ok = dev_alloc(&c->wn32, K) && dev_alloc(&c->wn64, K) && dev_alloc(&c->wmax_bits, 2) &&
             dev_alloc(&c->counts, K + 1) && dev_alloc(&c->seg_off, K + 1) && dev_alloc(&c->chunk_off, K + 1) &&
             dev_alloc(&c->massD, K) && dev_alloc(&c->cntT, 2 * K) && dev_alloc(&c->gx, 2 * (size_t)cols + 1) &&
             dev_alloc(&c->gy, (size_t)rows) && dev_alloc(&c->params, 1) && dev_alloc(&c->list_counts, 4) &&
             dev_alloc(&c->mu, (size_t)dim) && dev_alloc(&c->mu_partial, (size_t)64 * dim) &&
-            dev_alloc(&c->zero16, 16) && dev_alloc(&c->mu_norm2, 1) &&
+            dev_alloc(&c->zero16, 16) && dev_alloc(&c->mu_norm2, 1) && dev_alloc(&c->wscale, 1) &&
             dev_alloc(&c->S, K * dim) && dev_alloc(&c->T, images * K * dim);
   if (ok && rows <= kSmoothMatMax && cols <= kSmoothMatMax) {
     const size_t par = grid_type == SOM_GRID_HEXAGONAL ? 2 : 1;
@@ -327,6 +362,7 @@ void som_destroy(som_ctx *c) {
   dev_free(c->params); dev_free(c->list_counts); dev_free(c->S); dev_free(c->T); dev_free(c->Wt);
   dev_free(c->GxT); dev_free(c->GyT); dev_free(c->hit_x); dev_free(c->hit_n); dev_free(c->hit_rows);
   dev_free(c->mu); dev_free(c->mu_partial); dev_free(c->Wc); dev_free(c->zero16); dev_free(c->mu_norm2);
+  dev_free(c->Wh); dev_free(c->wscale);
   for (int s = 0; s < SOM_PROFILE_STAGES; ++s) {
     if (!c->prof_ev[s]) continue;
     for (int e = 0; e < 2 * kProfMax; ++e) (void)hipEventDestroy(c->prof_ev[s][e]);
@@ -424,6 +460,7 @@ int som_set_data_dense(som_ctx *c, const float *data, int64_t n) {
   c->data_kind = 1; c->d_data = data; c->d_n = n; c->d_nnz = 0;
   c->d_indptr = nullptr; c->d_indices = nullptr; c->d_values = nullptr;
   c->d_norms_valid = 0;
+  c->d_split_valid = 0;
   return SOM_OK;
 }
 
@@ -435,6 +472,7 @@ int som_set_data_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, 
   c->data_kind = 2; c->d_data = nullptr; c->d_n = n; c->d_nnz = nnz;
   c->d_indptr = indptr; c->d_indices = indices; c->d_values = values;
   c->d_norms_valid = 0;
+  c->d_split_valid = 0;
   return SOM_OK;
 }
 
@@ -495,6 +533,36 @@ int som_umatrix(som_ctx *c, const float *codebook, float *umatrix) {
   if (!codebook || !umatrix) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
   SOM_LAUNCH(c, launch_umatrix(c, codebook, umatrix));
   return SOM_OK;
+}
+
+int som_set_filter(som_ctx *c, int filter) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (filter != SOM_FILTER_FP32 && filter != SOM_FILTER_SPLIT_F16)
+    return fail(c, SOM_ERR_INVALID_ARG, "unknown filter %d", filter);
+  c->filter = filter;
+  return SOM_OK;
+}
+
+int som_debug_scores_dense(som_ctx *c, const float *data, int64_t n, const float *codebook, float *scores,
+                           float *mu_out) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (!data || !codebook || !scores || !mu_out) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
+  if (c->filter != SOM_FILTER_SPLIT_F16) return fail(c, SOM_ERR_STATE, "only the split-fp16 filter can dump its scores");
+  int rc = check_rows(c, n);
+  if (!rc) rc = ensure_rows(c, n, true);
+  if (!rc) rc = ensure_candidates(c, n);
+  if (!rc) rc = prepare_dense(c, data, n, codebook, false);
+  if (rc) return rc;
+  SOM_LAUNCH(c, launch_bmu_dense_h(c, n, scores));
+  SOM_LAUNCH(c, hipMemcpyAsync(mu_out, c->mu, (size_t)c->dim * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
+  return SOM_OK;
+}
+
+int som_debug_mfma_f16(const uint16_t *a, const uint16_t *b, const float *c_in, float *d_out, int count,
+                       void *hip_stream) {
+  if (!a || !b || !c_in || !d_out || count < 1) return SOM_ERR_INVALID_ARG;
+  return launch_probe_mfma_f16((hipStream_t)hip_stream, a, b, c_in, d_out, count) == hipSuccess ? SOM_OK
+                                                                                                : SOM_ERR_DEVICE;
 }
 
 int som_get_stats(som_ctx *c, int64_t *out) {

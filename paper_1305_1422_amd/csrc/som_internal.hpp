@@ -50,7 +50,7 @@ struct som_ctx {
   // per-map scratch (allocated in som_init)
   float *wn32;            // [k] squared norms of the code-book rows, fp32
   double *wn64;           // [k] the same in fp64
-  unsigned *wmax_bits;    // [1] bit pattern of max_i wn32[i] (non-negative floats order like uints)
+  unsigned *wmax_bits;    // [2] bit patterns of max_i |w'_i|^2 and of the largest |w'| element (non-negative floats order like uints)
   int32_t *counts;        // [k] instances per BMU
   int32_t *seg_off;       // [k+1] exclusive scan of counts
   int32_t *chunk_off;     // [k+1] exclusive scan of chunks per node
@@ -68,6 +68,9 @@ struct som_ctx {
   float *Wt;              // [dim][kpad] transposed code book (sparse BMU only, lazily allocated)
   int kpad;
   float *Wc;              // [k][dim] centred code book w' = fl(w - mu) of the dense BMU search (lazily allocated)
+  _Float16 *Wh;           // [k][ceil(dim/32)][64] centred code book as fp16 hi/lo planes (lazily allocated)
+  float *wscale;          // [1] the power of two the centred code book was divided by
+  int filter;             // SOM_FILTER_*: which matrix format the dense BMU filter runs on
   float *zero16;          // 64 bytes of zeros: source of out-of-range direct-to-LDS loads
   float *mu_norm2;        // [1] |mu|^2
   float *mu;              // [dim] centring vector of the dense BMU search
@@ -76,6 +79,8 @@ struct som_ctx {
   // per-data scratch (grown on demand to n_cap rows)
   int64_t n_cap;
   float *xn32;            // [n] squared norms of the instances
+  _Float16 *Xh;           // [n][ceil(dim/32)][64] dense instances as fp16 hi/lo planes (lazily allocated)
+  float *xscale;          // [n] the power of two each instance was divided by
   int64_t cand_cap;       // instance slots in the three candidate arrays (node groups x instances)
   float *cand_val;        // [groups][n][kCand]
   int32_t *cand_idx;      // [groups][n][kCand]
@@ -103,6 +108,7 @@ struct som_ctx {
   const float *d_values;
   int64_t d_n, d_nnz;
   int d_norms_valid;      // xn32 (and mu for dense data) currently describe the registered set
+  int d_split_valid;      // Xh / xscale currently describe the registered dense set
 
   // optional per-stage event brackets (som_profile_enable)
   int prof_on;
@@ -131,8 +137,16 @@ hipError_t launch_bmu_dense(som_ctx *c, const float *X, int64_t n);
 hipError_t launch_bmu_dense_collect(som_ctx *c, const float *X, int64_t n);
 hipError_t launch_bmu_dense_dl(som_ctx *c, const float *X, int64_t n, dim3 grid, bool collect);   // bmu_dense_dl.hip
 
+// bmu_dense_h.hip, split_f16.hip
+int bmu_dense_h_groups(const som_ctx *c, int64_t n);
+hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump);            // Xh, Wh -> candidates (or all scores)
+hipError_t launch_split_rows_f16(som_ctx *c, const float *A, int64_t nrows, const unsigned *global_max_bits,
+                                 _Float16 *out, float *scale_out);
+hipError_t launch_probe_mfma_f16(hipStream_t stream, const uint16_t *A, const uint16_t *B, const float *C, float *D,
+                                 int count);
+
 // bmu_exact.hip
-hipError_t launch_certify(som_ctx *c, int64_t n, int32_t *bmus);
+hipError_t launch_certify(som_ctx *c, int64_t n, int groups, bool split_filter, int32_t *bmus);
 hipError_t launch_refine_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
 hipError_t launch_refine_lists_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
 hipError_t launch_rescan_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);

@@ -11,6 +11,7 @@ from . import capi
 MAP_TYPES = {"planar": capi.SOM_MAP_PLANAR, "toroid": capi.SOM_MAP_TOROID}
 GRID_TYPES = {"square": capi.SOM_GRID_SQUARE, "hexagonal": capi.SOM_GRID_HEXAGONAL}
 COOLING = {"linear": capi.SOM_COOL_LINEAR, "exponential": capi.SOM_COOL_EXPONENTIAL}
+FILTERS = {"fp32": capi.SOM_FILTER_FP32, "split_f16": capi.SOM_FILTER_SPLIT_F16}
 
 
 def _is_csr(data) -> bool:
@@ -26,8 +27,11 @@ class Som:
     int32 [nnz], values float32 [nnz]).
     """
 
+    default_filter: Optional[str] = None     # None = the library's default; tests switch it
+
     def __init__(self, rows: int, cols: int, dim: int, map_type: str = "planar", grid_type: str = "square",
-                 codebook: Optional[torch.Tensor] = None, seed: int = 0, device: str = "cuda:0"):
+                 codebook: Optional[torch.Tensor] = None, seed: int = 0, device: str = "cuda:0",
+                 filter: Optional[str] = None):
         if not torch.cuda.is_available():
             raise RuntimeError("paper_1305_1422_amd needs a ROCm GPU: there is no CPU fallback")
         self.device = torch.device(device)
@@ -43,6 +47,14 @@ class Som:
             self.stream = torch.cuda.current_stream(self.device)
             self.ctx = capi.som_init(rows, cols, dim, MAP_TYPES[map_type], GRID_TYPES[grid_type], self.codebook,
                                      seed, self.stream.cuda_stream)
+        if filter is None:
+            filter = Som.default_filter
+        if filter is not None:
+            self.set_filter(filter)
+
+    def set_filter(self, filter: str) -> None:
+        """Arithmetic of the dense BMU filter pass: "split_f16" (default) or "fp32"; same results."""
+        capi.som_set_filter(self.ctx, FILTERS[filter])
 
     def close(self) -> None:
         if getattr(self, "ctx", None) is not None:

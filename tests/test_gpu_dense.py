@@ -14,6 +14,16 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 
+@pytest.fixture(autouse=True, params=["split_f16", "fp32"])
+def dense_filter(request):
+    """Every test of this module runs with both arithmetic variants of the dense BMU filter."""
+    from paper_1305_1422_amd import Som
+    old = Som.default_filter
+    Som.default_filter = request.param
+    yield request.param
+    Som.default_filter = old
+
+
 def _som(w, codebook):
     from paper_1305_1422_amd import Som
     return Som(w.rows, w.cols, w.dim, w.map_type, w.grid_type, codebook=torch.from_numpy(codebook))
