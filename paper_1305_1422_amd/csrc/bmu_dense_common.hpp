@@ -61,25 +61,56 @@ __device__ __forceinline__ void consume_scores(f32x16 (&tot)[2][2], const float 
                                                const float (&lim)[2],
                                                const int64_t (&slot_of)[2], int32_t *__restrict__ cnt,
                                                int32_t *__restrict__ list) {
+  if (kCollect) {
 #pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int nl = wm * 64 + mfma_row(mi, v, lhi);
-      const float wnv = swn[nl];
-      const int node = node0 + nl;
+      for (int v = 0; v < 16; ++v) {
+        const int nl = wm * 64 + mfma_row(mi, v, lhi);
+        const float wnv = swn[nl];
+        const int node = node0 + nl;
 #pragma unroll
-      for (int ni = 0; ni < 2; ++ni) {
-        const float s = fmaf(factor[ni], tot[mi][ni][v], wnv);
-        if (kCollect) {
+        for (int ni = 0; ni < 2; ++ni) {
+          const float s = fmaf(factor[ni], tot[mi][ni][v], wnv);
           if (s <= lim[ni] && node < k) {
             const int pos = atomicAdd(&cnt[slot_of[ni]], 1);
             if (pos < kListCap) list[slot_of[ni] * kListCap + pos] = node;
           }
-        } else {
-          top2_push(top[ni], s, node);
+          tot[mi][ni][v] = 0.f;
         }
-        tot[mi][ni][v] = 0.f;
+      }
+    return;
+  }
+  // Filter mode.  After the first node blocks a score rarely beats the second-best of its lane, so
+  // four scores (consecutive nodes) are tested together: if, for no lane of the wavefront, their
+  // minimum is below the lane's second-best, all four only feed the smallest-dropped-score - one
+  // minimum tree and one comparison instead of four list insertions.
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+    for (int v4 = 0; v4 < 16; v4 += 4) {
+      float s[2][4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float wnv = swn[wm * 64 + mfma_row(mi, v4 + e, lhi)];
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+          s[ni][e] = fmaf(factor[ni], tot[mi][ni][v4 + e], wnv);
+          tot[mi][ni][v4 + e] = 0.f;
+        }
+      }
+      const float m0 = fminf(fminf(s[0][0], s[0][1]), fminf(s[0][2], s[0][3]));
+      const float m1 = fminf(fminf(s[1][0], s[1][1]), fminf(s[1][2], s[1][3]));
+      if (__any(m0 < top[0].v1 || m1 < top[1].v1)) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int node = node0 + wm * 64 + mfma_row(mi, v4 + e, lhi);
+          top2_push(top[0], s[0][e], node);
+          top2_push(top[1], s[1][e], node);
+        }
+      } else {
+        top[0].ov = fminf(top[0].ov, m0);
+        top[1].ov = fminf(top[1].ov, m1);
       }
     }
 }

@@ -10,8 +10,11 @@
 //
 // At this rate the operand traffic matters, so the tile is larger than in the fp32 pass: a
 // 512-thread workgroup (8 wavefronts, 2 x 4, each 64 nodes x 64 instances = 2 x 2 MFMA blocks)
-// owns 256 instances and sweeps its group of node blocks of 128.  LDS holds two stages of
-// (128 + 256) rows x 128 bytes = 96 KB, one workgroup per CU, two wavefronts per SIMD.  The 128
+// owns 256 instances and sweeps its group of node blocks of 128.  LDS holds three stages of
+// (128 + 256) rows x 128 bytes = 144 KB, one workgroup per CU, two wavefronts per SIMD: a chunk
+// is multiplied in about half a microsecond, so what a wavefront waits for at the start of a chunk
+// matters: the third stage lets it read the first operands of the next chunk before the barrier
+// (see the pipeline comment in the kernel).  The 128
 // bytes of a tile row are one chunk of the split layout: 32 hi halves, 32 lo halves.  Tiles are
 // loaded straight into LDS with the XOR swizzle of the fp32 pass (the two passes share the row
 // geometry, so the same swizzle makes the ds_read_b128 operand reads conflict-free): 16-byte
@@ -31,17 +34,30 @@ typedef __attribute__((address_space(3))) void *lptr_h_t;
 
 constexpr int kHTI = 256;                  // instances per tile
 constexpr int kHRow = 32;                  // floats per tile row (= 64 halves = one chunk of 32 columns)
-constexpr int kHFlushChunks = 2;           // chunks (of 32 columns) between accumulator flushes
 constexpr int kHWTile = kTN * kHRow;       // floats
 constexpr int kHXTile = kHTI * kHRow;
+constexpr int kHStages = 3;                // LDS stages: loads run two chunks ahead of the MFMAs
 
 __device__ __forceinline__ unsigned lds_address_h(const float *p) { return (unsigned)(size_t)(lptr_h_t)p; }
 
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"
-// Direct-to-LDS load of 16 bytes per lane (see bmu_dense_dl.hip for why this is inline assembly).
-__device__ __forceinline__ void load16_to_lds_h(const float *g, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_base) : "memory", "m0");
+// Direct-to-LDS load of 16 bytes per lane (see bmu_dense_dl.hip for why this is inline assembly),
+// in the addressing form "wavefront-uniform 64-bit base in scalar registers + unsigned 32-bit byte
+// offset per lane": the per-lane offsets are loop constants and the base advances with scalar
+// arithmetic, so a load costs no vector ALU instruction.
+__device__ __forceinline__ void load16_to_lds_h(const void *base, unsigned lane_offset, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(lane_offset), "s"(base), "s"(lds_base)
+               : "memory", "m0");
+}
+// The same for 4 bytes per lane: lane l's word goes to LDS byte address lds_base + 4 l.
+__device__ __forceinline__ void load4_to_lds_h(const void *base, unsigned lane_offset, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1"
+               :
+               : "v"(lane_offset), "s"(base), "s"(lds_base)
+               : "memory", "m0");
 }
 #pragma clang diagnostic pop
 
@@ -53,11 +69,11 @@ __global__ __launch_bounds__(512, 2) void k_bmu_dense_h(const float *__restrict_
                                                         const float *__restrict__ wc,
                                                         const float *__restrict__ xscale,
                                                         const float *__restrict__ wscale,
-                                                        const float *__restrict__ zero16, int64_t n, int k, int nK,
+                                                        int64_t n, int k, int nK,
                                                         int groups, CandView out, float *__restrict__ dump) {
-  __shared__ __attribute__((aligned(16))) float sW[2][kHWTile];
-  __shared__ __attribute__((aligned(16))) float sX[2][kHXTile];
-  __shared__ float sWn[2][kTN];
+  __shared__ __attribute__((aligned(16))) float sW[kHStages][kHWTile];
+  __shared__ __attribute__((aligned(16))) float sX[kHStages][kHXTile];
+  __shared__ float sWn[4][kTN];      // node constants of the node blocks in flight (at most three)
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -82,51 +98,50 @@ __global__ __launch_bounds__(512, 2) void k_bmu_dense_h(const float *__restrict_
   const int nNB = min(nb_per, nNB_all - nb_first);
   if (nNB <= 0) return;              // uniform over the workgroup
   const int total = nK * nNB;
-  const int64_t row_floats = (int64_t)nK * kHRow;
 
   // ---- loader: one instruction fills 8 tile rows (64 lanes x 16 bytes); wavefront w issues W slots
   // 2 w, 2 w + 1 and X slots 4 w .. 4 w + 3; lane l sits at row + (l >> 3), slot position l & 7.
+  // Rows past the end of an operand are redirected to its last row: their products land in output
+  // rows / columns that are never used (padded nodes carry c_i = +inf, padded instances are not stored).
   const int ld_rloc = lane >> 3;
   const int ld_pos = lane & 7;
-  const float *xp[4];
-  const float *wp[2];
+  const unsigned row_bytes = (unsigned)nK * (kHRow * 4);
+  const char *xbase = reinterpret_cast<const char *>(Xh) + inst0 * (int64_t)row_bytes;
+  const int64_t last_inst = n - 1 - inst0;       // >= 0
+  unsigned xoff[4], woff[2], wq[2];
   int wrow[2];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int row = 8 * (4 * wave + i) + ld_rloc;
     const int q = ld_pos ^ ((row & 7) ^ ((row >> 3) & 1));
-    const int64_t slot = inst0 + row;
-    xp[i] = slot < n ? Xh + slot * row_floats + 4 * q : nullptr;
+    xoff[i] = (unsigned)(row < last_inst ? row : (int)last_inst) * row_bytes + 16u * q;
   }
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     wrow[i] = 8 * (2 * wave + i) + ld_rloc;
-    wp[i] = nullptr;
+    wq[i] = 16u * (ld_pos ^ ((wrow[i] & 7) ^ ((wrow[i] >> 3) & 1)));
+    woff[i] = 0;
   }
-  const int wq = 4 * (ld_pos ^ ((wrow[0] & 7) ^ ((wrow[0] >> 3) & 1)));   // the two rows differ by 8: other swizzle
-  const int wq1 = 4 * (ld_pos ^ ((wrow[1] & 7) ^ ((wrow[1] >> 3) & 1)));
   const unsigned lds_w = lds_address_h(&sW[0][512 * wave]);     // 2 slots x 256 floats per wavefront
   const unsigned lds_x = lds_address_h(&sX[0][1024 * wave]);    // 4 slots
+  const unsigned lds_wn = lds_address_h(&sWn[0][0]);
+  const unsigned wn_off = (unsigned)(wave * 64 + lane) * 4u;
   int ld_nb = nb_first, ld_kc = 0;
   auto issue_loads = [&](int buf) {
+    const char *wbase = reinterpret_cast<const char *>(Wh) + (int64_t)ld_nb * kTN * row_bytes;
     if (ld_kc == 0) {                                           // entering a node block
+      const int last_node = k - 1 - ld_nb * kTN;                // >= 0
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int64_t node = (int64_t)ld_nb * kTN + wrow[i];
-        wp[i] = node < k ? Wh + node * row_floats + (i == 0 ? wq : wq1) : nullptr;
-      }
-      if (tid < kTN) {
-        const int node = ld_nb * kTN + tid;
-        sWn[ld_nb & 1][tid] = node < k ? wc[node] : INFINITY;    // padded nodes can never win
-      }
+      for (int i = 0; i < 2; ++i) woff[i] = (unsigned)(wrow[i] < last_node ? wrow[i] : last_node) * row_bytes + wq[i];
+      // node constants of the block: wc is padded to whole blocks with +inf (such nodes can never
+      // win), so the 128 values are loaded like the tiles, as the oldest operation of the batch
+      if (wave < 2) load4_to_lds_h(wc + (int64_t)ld_nb * kTN, wn_off, lds_wn + (ld_nb & 3) * (kTN * 4) + wave * 256);
     }
-    const int off = ld_kc * kHRow;
+    const unsigned off = (unsigned)ld_kc * (kHRow * 4);
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-      load16_to_lds_h(wp[i] ? wp[i] + off : zero16, lds_w + buf * (kHWTile * 4) + i * 1024);
+    for (int i = 0; i < 2; ++i) load16_to_lds_h(wbase + off, woff[i], lds_w + buf * (kHWTile * 4) + i * 1024);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      load16_to_lds_h(xp[i] ? xp[i] + off : zero16, lds_x + buf * (kHXTile * 4) + i * 1024);
+    for (int i = 0; i < 4; ++i) load16_to_lds_h(xbase + off, xoff[i], lds_x + buf * (kHXTile * 4) + i * 1024);
     if (++ld_kc == nK) { ld_kc = 0; ++ld_nb; }
   };
 
@@ -156,54 +171,90 @@ __global__ __launch_bounds__(512, 2) void k_bmu_dense_h(const float *__restrict_
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) { acc[mi][ni][v] = 0.f; tot[mi][ni][v] = 0.f; }
+      for (int v = 0; v < 16; ++v) tot[mi][ni][v] = 0.f;
 
+  // Operands of one k-step (16 features): the hi and lo planes of this wavefront's two 32-node and
+  // two 32-instance row blocks, eight 16-byte LDS reads per lane.
+  struct Operands { f16x8 g1[2], g2[2], h1[2], h2[2]; };
+  auto read_operands = [&](Operands &o, int st, int ks) {
+    const float *pw = &sW[st][a_base];
+    const float *px = &sX[st][b_base];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      o.g1[b] = as_halves(*reinterpret_cast<const f32x4 *>(pw + b * 32 * kHRow + rd_off[ks]));
+      o.g2[b] = as_halves(*reinterpret_cast<const f32x4 *>(pw + b * 32 * kHRow + rd_off[2 + ks]));
+      o.h1[b] = as_halves(*reinterpret_cast<const f32x4 *>(px + b * 32 * kHRow + rd_off[ks]));
+      o.h2[b] = as_halves(*reinterpret_cast<const f32x4 *>(px + b * 32 * kHRow + rd_off[2 + ks]));
+    }
+  };
+  // Twelve MFMAs of one k-step; the four output blocks take turns, so that an accumulator is reused
+  // every fourth instruction only.  The small cross products go first.  `fresh`: the accumulators
+  // start from C = 0 as an operand of the instruction itself, which spares clearing 64 registers.
+  auto multiply = [&](const Operands &o, bool fresh) {
+    if (fresh) {
+      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g2[mi], o.h1[ni], zero, 0, 0, 0);
+    } else {
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g2[mi], o.h1[ni], acc[mi][ni], 0, 0, 0);
+    }
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g1[mi], o.h2[ni], acc[mi][ni], 0, 0, 0);
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g1[mi], o.h1[ni], acc[mi][ni], 0, 0, 0);
+  };
+
+  // Pipeline.  Chunk c is loaded into stage c % 3 during iteration c - 2 and every wavefront waits
+  // for all its loads before the barrier that ends an iteration, so at the start of iteration t the
+  // chunks t and t + 1 are both complete in LDS.  That is what the third stage buys: the operands of
+  // the first k-step of chunk t + 1 are read into registers during iteration t, BEFORE the barrier,
+  // and the MFMAs of iteration t + 1 start right after it instead of waiting for LDS.
   issue_loads(0);
+  if (total > 1) issue_loads(1);
   __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wavefront's direct-to-LDS loads have landed
   __syncthreads();
 
+  // The two wavefronts that share a SIMD (w and w + 4) flush their accumulators in alternate
+  // chunks, so that one's additions overlap the other's MFMAs.  An interval is at most two chunks.
+  const int flush_phase = wave >> 2;
+  bool fresh = true;
+  Operands op0, op1;
+  read_operands(op0, 0, 0);
+  int stage = 0;                                 // t % kHStages
   for (int t = 0; t < total; ++t) {
     const int nb = nb_first + t / nK, kc = t % nK;
-    if (t + 1 < total) issue_loads((t + 1) & 1);
+    const int next_stage = stage == 2 ? 0 : stage + 1;
+    // stage (t + 2) % 3 held chunk t - 1, which every wavefront has left (its prefetched operands
+    // were consumed in iteration t - 1 as well)
+    if (t + 2 < total) issue_loads(stage == 0 ? 2 : stage - 1);
 
-    const float *pw = &sW[t & 1][a_base];
-    const float *px = &sX[t & 1][b_base];
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      f16x8 g1[2], g2[2], h1[2], h2[2];
-#pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        g1[b] = as_halves(*reinterpret_cast<const f32x4 *>(pw + b * 32 * kHRow + rd_off[ks]));
-        g2[b] = as_halves(*reinterpret_cast<const f32x4 *>(pw + b * 32 * kHRow + rd_off[2 + ks]));
-        h1[b] = as_halves(*reinterpret_cast<const f32x4 *>(px + b * 32 * kHRow + rd_off[ks]));
-        h2[b] = as_halves(*reinterpret_cast<const f32x4 *>(px + b * 32 * kHRow + rd_off[2 + ks]));
-      }
-      // the four output blocks take turns, so that an accumulator is reused every fourth MFMA only
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(g2[mi], h1[ni], acc[mi][ni], 0, 0, 0);
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(g1[mi], h2[ni], acc[mi][ni], 0, 0, 0);
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(g1[mi], h1[ni], acc[mi][ni], 0, 0, 0);
-    }
+    read_operands(op1, stage, 1);
+    multiply(op0, fresh);
+    if (t + 1 < total) read_operands(op0, next_stage, 0);
+    multiply(op1, false);
 
     const bool last_k = (kc == nK - 1);
-    if (last_k || (kc % kHFlushChunks) == kHFlushChunks - 1) {
+    fresh = last_k || ((kc + flush_phase) & 1) == 1;
+    if (fresh) {
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) { tot[mi][ni][v] += acc[mi][ni][v]; acc[mi][ni][v] = 0.f; }
+          for (int v = 0; v < 16; ++v) tot[mi][ni][v] += acc[mi][ni][v];
     }
     if (last_k) {
       if (kDump) {
@@ -215,17 +266,18 @@ __global__ __launch_bounds__(512, 2) void k_bmu_dense_h(const float *__restrict_
             const int node = nb * kTN + nl;
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni) {
-              if (node < k && slot_of[ni] < n) dump[slot_of[ni] * k + node] = fmaf(factor[ni], tot[mi][ni][v], sWn[nb & 1][nl]);
+              if (node < k && slot_of[ni] < n) dump[slot_of[ni] * k + node] = fmaf(factor[ni], tot[mi][ni][v], sWn[nb & 3][nl]);
               tot[mi][ni][v] = 0.f;
             }
           }
       } else {
-        consume_scores<false>(tot, sWn[nb & 1], nb * kTN, k, wm, lhi, factor, top, lim, slot_of, nullptr, nullptr);
+        consume_scores<false>(tot, sWn[nb & 3], nb * kTN, k, wm, lhi, factor, top, lim, slot_of, nullptr, nullptr);
       }
     }
 
-    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
     __syncthreads();
+    stage = next_stage;
   }
   if (kDump) return;
   merge_and_store<kHTI>(top, &sW[0][0], reinterpret_cast<int *>(&sX[0][0]), tid, wm, wi, l32, lhi, inst0, n, group,
@@ -255,10 +307,10 @@ hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump) {
   const float *Wh = reinterpret_cast<const float *>(c->Wh);
   if (dump)
     hipLaunchKernelGGL((k_bmu_dense_h<true>), dim3((unsigned)blocks), dim3(512), 0, c->stream, Xh, Wh, c->wn32, c->xscale,
-                       c->wscale, c->zero16, n, c->k, nK, groups, out, dump);
+                       c->wscale, n, c->k, nK, groups, out, dump);
   else
     hipLaunchKernelGGL((k_bmu_dense_h<false>), dim3((unsigned)blocks), dim3(512), 0, c->stream, Xh, Wh, c->wn32, c->xscale,
-                       c->wscale, c->zero16, n, c->k, nK, groups, out, dump);
+                       c->wscale, n, c->k, nK, groups, out, dump);
   return hipGetLastError();
 }
 

@@ -323,7 +323,7 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
 
   const size_t K = (size_t)c->k;
   const size_t images = grid_type == SOM_GRID_HEXAGONAL ? 2 : 1;
-  bool ok = dev_alloc(&c->wn32, K) && dev_alloc(&c->wn64, K) && dev_alloc(&c->wmax_bits, 2) &&
+  bool ok = dev_alloc(&c->wn32, (K + 127) / 128 * 128) && dev_alloc(&c->wn64, K) && dev_alloc(&c->wmax_bits, 2) &&
             dev_alloc(&c->counts, K + 1) && dev_alloc(&c->seg_off, K + 1) && dev_alloc(&c->chunk_off, K + 1) &&
             dev_alloc(&c->massD, K) && dev_alloc(&c->cntT, 2 * K) && dev_alloc(&c->gx, 2 * (size_t)cols + 1) &&
             dev_alloc(&c->gy, (size_t)rows) && dev_alloc(&c->params, 1) && dev_alloc(&c->list_counts, 4) &&
@@ -343,6 +343,12 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
   }
   hipError_t e = launch_fill_zero_u32(c->stream, c->list_counts, 4);
   if (e == hipSuccess) e = launch_fill_zero_u32(c->stream, c->zero16, 16);
+  if (e == hipSuccess && K % 128 != 0) {       // the tail of the node constants past k stays +inf for good
+    float inf[128];
+    for (int i = 0; i < 128; ++i) inf[i] = INFINITY;
+    e = hipMemcpyAsync(c->wn32 + K, inf, (128 - K % 128) * sizeof(float), hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  }
   if (e == hipSuccess && seed != 0) e = launch_fill_uniform(c, codebook, (int64_t)c->k * dim, seed);
   if (e != hipSuccess) {
     int rc = dev_fail(nullptr, e, "som_init");

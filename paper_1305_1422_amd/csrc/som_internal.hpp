@@ -48,7 +48,7 @@ struct som_ctx {
   int n_cu;
 
   // per-map scratch (allocated in som_init)
-  float *wn32;            // [k] squared norms of the code-book rows, fp32
+  float *wn32;            // [k rounded up to 128] node constants c_i of the BMU filters, fp32; +inf past k
   double *wn64;           // [k] the same in fp64
   unsigned *wmax_bits;    // [2] bit patterns of max_i |w'_i|^2 and of the largest |w'| element (non-negative floats order like uints)
   int32_t *counts;        // [k] instances per BMU
