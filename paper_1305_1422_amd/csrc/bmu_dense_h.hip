@@ -8,13 +8,14 @@
 // for 16 k-values where the fp32 one needs 16 passes for 2: three of them per k-step are 5.3 times
 // the fp32 rate.  The exact stage (bmu_exact.hip) decides as before; only its margin differs.
 //
-// At this rate the operand traffic matters, so the tile is larger than in the fp32 pass: a
-// 512-thread workgroup (8 wavefronts, 2 x 4, each 64 nodes x 64 instances = 2 x 2 MFMA blocks)
-// owns 256 instances and sweeps its group of node blocks of 128.  LDS holds three stages of
-// (128 + 256) rows x 128 bytes = 144 KB, one workgroup per CU, two wavefronts per SIMD: a chunk
-// is multiplied in about half a microsecond, so what a wavefront waits for at the start of a chunk
-// matters: the third stage lets it read the first operands of the next chunk before the barrier
-// (see the pipeline comment in the kernel).  The 128
+// Each wavefront owns 64 nodes x 64 instances (2 x 2 MFMA blocks) and sweeps the workgroup's group
+// of node blocks of 128.  Two workgroup shapes are compiled (template parameter WI).  The one in
+// use has 4 wavefronts, 128 instances and two LDS stages of (128 + 128) rows x 128 bytes (64 KB),
+// two workgroups per CU: at this MFMA rate a chunk is multiplied in about half a microsecond, so
+// the gap every barrier leaves in the matrix pipe matters, and a second workgroup with barriers of
+// its own fills it.  The other (8 wavefronts, 256 instances, three stages = 144 KB, one workgroup
+// per CU, first operands of the next chunk read before the barrier) moves a quarter less data
+// through L2 but measured 3-12 % slower on the three dense configurations.  The 128
 // bytes of a tile row are one chunk of the split layout: 32 hi halves, 32 lo halves.  Tiles are
 // loaded straight into LDS with the XOR swizzle of the fp32 pass (the two passes share the row
 // geometry, so the same swizzle makes the ds_read_b128 operand reads conflict-free): 16-byte
@@ -32,11 +33,9 @@ namespace som {
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) void *lptr_h_t;
 
-constexpr int kHTI = 256;                  // instances per tile
 constexpr int kHRow = 32;                  // floats per tile row (= 64 halves = one chunk of 32 columns)
 constexpr int kHWTile = kTN * kHRow;       // floats
-constexpr int kHXTile = kHTI * kHRow;
-constexpr int kHStages = 3;                // LDS stages: loads run two chunks ahead of the MFMAs
+constexpr int kHWI = 2;                    // tile shape in use (see the template parameter WI): measured faster
 
 __device__ __forceinline__ unsigned lds_address_h(const float *p) { return (unsigned)(size_t)(lptr_h_t)p; }
 
@@ -63,14 +62,21 @@ __device__ __forceinline__ void load4_to_lds_h(const void *base, unsigned lane_o
 
 __device__ __forceinline__ f16x8 as_halves(f32x4 v) { return __builtin_bit_cast(f16x8, v); }
 
+// WI: 64-instance columns of wavefronts in a workgroup.  WI = 4: 8 wavefronts, 256 instances, three
+// LDS stages (144 KB), one workgroup per CU.  WI = 2: 4 wavefronts, 128 instances, two LDS stages
+// (64 KB), two workgroups per CU whose barriers are independent.
 // kDump: instead of keeping candidates, write every score to dump[slot * k + node] (test hook).
-template <bool kDump>
-__global__ __launch_bounds__(512, 2) void k_bmu_dense_h(const float *__restrict__ Xh, const float *__restrict__ Wh,
+template <int WI, bool kDump>
+__global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__restrict__ Xh, const float *__restrict__ Wh,
                                                         const float *__restrict__ wc,
                                                         const float *__restrict__ xscale,
                                                         const float *__restrict__ wscale,
                                                         int64_t n, int k, int nK,
                                                         int groups, CandView out, float *__restrict__ dump) {
+  constexpr int kHTI = 64 * WI;              // instances per tile
+  constexpr int kHXTile = kHTI * kHRow;      // floats
+  constexpr int kHStages = WI == 4 ? 3 : 2;
+  constexpr int kWSlots = 16 / (2 * WI);     // W-tile load instructions per wavefront and chunk
   __shared__ __attribute__((aligned(16))) float sW[kHStages][kHWTile];
   __shared__ __attribute__((aligned(16))) float sX[kHStages][kHXTile];
   __shared__ float sWn[4][kTN];      // node constants of the node blocks in flight (at most three)
@@ -78,8 +84,8 @@ __global__ __launch_bounds__(512, 2) void k_bmu_dense_h(const float *__restrict_
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 2;          // which 64-node half of the tile
-  const int wi = wave & 3;           // which 64-instance quarter of the tile
+  const int wm = wave / WI;          // which 64-node half of the tile
+  const int wi = wave % WI;          // which 64-instance column of the tile
   const int l32 = lane & 31;
   const int lhi = lane >> 5;
 
@@ -108,8 +114,8 @@ __global__ __launch_bounds__(512, 2) void k_bmu_dense_h(const float *__restrict_
   const unsigned row_bytes = (unsigned)nK * (kHRow * 4);
   const char *xbase = reinterpret_cast<const char *>(Xh) + inst0 * (int64_t)row_bytes;
   const int64_t last_inst = n - 1 - inst0;       // >= 0
-  unsigned xoff[4], woff[2], wq[2];
-  int wrow[2];
+  unsigned xoff[4], woff[kWSlots], wq[kWSlots];
+  int wrow[kWSlots];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int row = 8 * (4 * wave + i) + ld_rloc;
@@ -117,12 +123,12 @@ __global__ __launch_bounds__(512, 2) void k_bmu_dense_h(const float *__restrict_
     xoff[i] = (unsigned)(row < last_inst ? row : (int)last_inst) * row_bytes + 16u * q;
   }
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    wrow[i] = 8 * (2 * wave + i) + ld_rloc;
+  for (int i = 0; i < kWSlots; ++i) {
+    wrow[i] = 8 * (kWSlots * wave + i) + ld_rloc;
     wq[i] = 16u * (ld_pos ^ ((wrow[i] & 7) ^ ((wrow[i] >> 3) & 1)));
     woff[i] = 0;
   }
-  const unsigned lds_w = lds_address_h(&sW[0][512 * wave]);     // 2 slots x 256 floats per wavefront
+  const unsigned lds_w = lds_address_h(&sW[0][kWSlots * 256 * wave]);   // 256 floats per slot
   const unsigned lds_x = lds_address_h(&sX[0][1024 * wave]);    // 4 slots
   const unsigned lds_wn = lds_address_h(&sWn[0][0]);
   const unsigned wn_off = (unsigned)(wave * 64 + lane) * 4u;
@@ -132,14 +138,14 @@ __global__ __launch_bounds__(512, 2) void k_bmu_dense_h(const float *__restrict_
     if (ld_kc == 0) {                                           // entering a node block
       const int last_node = k - 1 - ld_nb * kTN;                // >= 0
 #pragma unroll
-      for (int i = 0; i < 2; ++i) woff[i] = (unsigned)(wrow[i] < last_node ? wrow[i] : last_node) * row_bytes + wq[i];
+      for (int i = 0; i < kWSlots; ++i) woff[i] = (unsigned)(wrow[i] < last_node ? wrow[i] : last_node) * row_bytes + wq[i];
       // node constants of the block: wc is padded to whole blocks with +inf (such nodes can never
       // win), so the 128 values are loaded like the tiles, as the oldest operation of the batch
       if (wave < 2) load4_to_lds_h(wc + (int64_t)ld_nb * kTN, wn_off, lds_wn + (ld_nb & 3) * (kTN * 4) + wave * 256);
     }
     const unsigned off = (unsigned)ld_kc * (kHRow * 4);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) load16_to_lds_h(wbase + off, woff[i], lds_w + buf * (kHWTile * 4) + i * 1024);
+    for (int i = 0; i < kWSlots; ++i) load16_to_lds_h(wbase + off, woff[i], lds_w + buf * (kHWTile * 4) + i * 1024);
 #pragma unroll
     for (int i = 0; i < 4; ++i) load16_to_lds_h(xbase + off, xoff[i], lds_x + buf * (kHXTile * 4) + i * 1024);
     if (++ld_kc == nK) { ld_kc = 0; ++ld_nb; }
@@ -217,33 +223,42 @@ __global__ __launch_bounds__(512, 2) void k_bmu_dense_h(const float *__restrict_
         acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g1[mi], o.h1[ni], acc[mi][ni], 0, 0, 0);
   };
 
-  // Pipeline.  Chunk c is loaded into stage c % 3 during iteration c - 2 and every wavefront waits
-  // for all its loads before the barrier that ends an iteration, so at the start of iteration t the
-  // chunks t and t + 1 are both complete in LDS.  That is what the third stage buys: the operands of
-  // the first k-step of chunk t + 1 are read into registers during iteration t, BEFORE the barrier,
-  // and the MFMAs of iteration t + 1 start right after it instead of waiting for LDS.
+  // Pipeline with three stages.  Chunk c is loaded into stage c % 3 during iteration c - 2 and every
+  // wavefront waits for all its loads before the barrier that ends an iteration, so at the start of
+  // iteration t the chunks t and t + 1 are both complete in LDS.  That is what the third stage
+  // buys: the operands of the first k-step of chunk t + 1 are read into registers during iteration
+  // t, BEFORE the barrier, and the MFMAs of iteration t + 1 start right after it instead of waiting
+  // for LDS.  With two stages chunk t + 1 is loaded during iteration t and every operand is read
+  // after the barrier; there a second workgroup on the CU fills the gap.
+  constexpr bool kAhead = kHStages == 3;
   issue_loads(0);
-  if (total > 1) issue_loads(1);
+  if (kAhead && total > 1) issue_loads(1);
   __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wavefront's direct-to-LDS loads have landed
   __syncthreads();
 
-  // The two wavefronts that share a SIMD (w and w + 4) flush their accumulators in alternate
-  // chunks, so that one's additions overlap the other's MFMAs.  An interval is at most two chunks.
-  const int flush_phase = wave >> 2;
+  // Wavefronts that share a SIMD flush their accumulators in alternate chunks, so that one's
+  // additions overlap the other's MFMAs: w and w + 4 of a large workgroup, or the wavefronts of two
+  // small workgroups that sit next to each other in the launch order.  An interval is at most two
+  // chunks.
+  const int flush_phase = WI == 4 ? (wave >> 2) : (int)(slot_id & 1);
   bool fresh = true;
   Operands op0, op1;
-  read_operands(op0, 0, 0);
+  if (kAhead) read_operands(op0, 0, 0);
   int stage = 0;                                 // t % kHStages
   for (int t = 0; t < total; ++t) {
     const int nb = nb_first + t / nK, kc = t % nK;
-    const int next_stage = stage == 2 ? 0 : stage + 1;
-    // stage (t + 2) % 3 held chunk t - 1, which every wavefront has left (its prefetched operands
-    // were consumed in iteration t - 1 as well)
-    if (t + 2 < total) issue_loads(stage == 0 ? 2 : stage - 1);
+    const int next_stage = stage == kHStages - 1 ? 0 : stage + 1;
+    // the stage that is loaded now held chunk t - 1, which every wavefront has left
+    if (kAhead) {
+      if (t + 2 < total) issue_loads(stage == 0 ? 2 : stage - 1);
+    } else {
+      if (t + 1 < total) issue_loads(next_stage);
+      read_operands(op0, stage, 0);
+    }
 
     read_operands(op1, stage, 1);
     multiply(op0, fresh);
-    if (t + 1 < total) read_operands(op0, next_stage, 0);
+    if (kAhead && t + 1 < total) read_operands(op0, next_stage, 0);
     multiply(op1, false);
 
     const bool last_k = (kc == nK - 1);
@@ -284,11 +299,11 @@ __global__ __launch_bounds__(512, 2) void k_bmu_dense_h(const float *__restrict_
                         out);
 }
 
-// Node groups per instance tile: enough workgroups for about ten rounds over the CUs.
+// Node groups per instance tile: enough workgroups for about ten rounds over the resident slots.
 int bmu_dense_h_groups(const som_ctx *c, int64_t n) {
-  const int64_t tiles = (n + kHTI - 1) / kHTI;
+  const int64_t tiles = (n + 64 * kHWI - 1) / (64 * kHWI);
   const int nNB = (c->k + kTN - 1) / kTN;
-  const int64_t slots = c->n_cu;
+  const int64_t slots = (int64_t)c->n_cu * (kHWI == 4 ? 1 : 2);
   int64_t want = (10 * slots + tiles - 1) / tiles;
   if (want > nNB) want = nNB;
   if (want > 64) want = 64;
@@ -299,18 +314,18 @@ int bmu_dense_h_groups(const som_ctx *c, int64_t n) {
 
 hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump) {
   const int groups = bmu_dense_h_groups(c, n);
-  const int64_t tiles = (n + kHTI - 1) / kHTI;
+  const int64_t tiles = (n + 64 * kHWI - 1) / (64 * kHWI);
   const int64_t blocks = (tiles + 7) / 8 * 8 * groups;
   const int nK = (c->dim + 31) / 32;
   CandView out{c->cand_val, c->cand_idx, c->cand_over};
   const float *Xh = reinterpret_cast<const float *>(c->Xh);
   const float *Wh = reinterpret_cast<const float *>(c->Wh);
   if (dump)
-    hipLaunchKernelGGL((k_bmu_dense_h<true>), dim3((unsigned)blocks), dim3(512), 0, c->stream, Xh, Wh, c->wn32, c->xscale,
-                       c->wscale, n, c->k, nK, groups, out, dump);
+    hipLaunchKernelGGL((k_bmu_dense_h<kHWI, true>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
+                       c->wn32, c->xscale, c->wscale, n, c->k, nK, groups, out, dump);
   else
-    hipLaunchKernelGGL((k_bmu_dense_h<false>), dim3((unsigned)blocks), dim3(512), 0, c->stream, Xh, Wh, c->wn32, c->xscale,
-                       c->wscale, n, c->k, nK, groups, out, dump);
+    hipLaunchKernelGGL((k_bmu_dense_h<kHWI, false>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
+                       c->wn32, c->xscale, c->wscale, n, c->k, nK, groups, out, dump);
   return hipGetLastError();
 }
 
