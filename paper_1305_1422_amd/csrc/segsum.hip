@@ -100,12 +100,12 @@ __global__ __launch_bounds__(1024) void k_scan_exclusive(const int32_t *in, int3
 
 // ---------------------------------------------------------------- stable radix sort
 __global__ __launch_bounds__(256) void k_radix_hist(const int32_t *__restrict__ keys, int64_t n, int shift,
-                                                    int nblk, int k, int32_t *__restrict__ hist) {
+                                                    int nblk, int tile, int k, int32_t *__restrict__ hist) {
   __shared__ int s_hist[256];
   s_hist[threadIdx.x] = 0;
   __syncthreads();
-  const int64_t base = (int64_t)blockIdx.x * kSortTile;
-  for (int e = threadIdx.x; e < kSortTile; e += 256) {
+  const int64_t base = (int64_t)blockIdx.x * tile;
+  for (int e = threadIdx.x; e < tile; e += 256) {
     const int64_t j = base + e;
     if (j < n) atomicAdd(&s_hist[(clamp_node(keys[j], k) >> shift) & 255], 1);
   }
@@ -119,13 +119,14 @@ __global__ __launch_bounds__(64) void k_radix_scatter(const int32_t *__restrict_
                                                       const int32_t *__restrict__ vals_in,
                                                       int32_t *__restrict__ keys_out,
                                                       int32_t *__restrict__ vals_out, int64_t n, int shift,
-                                                      int nblk, int k, const int32_t *__restrict__ hist_scanned) {
+                                                      int nblk, int tile, int k,
+                                                      const int32_t *__restrict__ hist_scanned) {
   __shared__ int s_cnt[256];
   const int lane = threadIdx.x;
   for (int d = lane; d < 256; d += 64) s_cnt[d] = hist_scanned[(int64_t)d * nblk + blockIdx.x];
   __syncthreads();
-  const int64_t base = (int64_t)blockIdx.x * kSortTile;
-  for (int step = 0; step < kSortTile / 64; ++step) {
+  const int64_t base = (int64_t)blockIdx.x * tile;
+  for (int step = 0; step < tile / 64; ++step) {
     const int64_t j = base + step * 64 + lane;
     const bool valid = j < n;
     const int key = valid ? clamp_node(keys_in[j], k) : 0;
@@ -208,7 +209,8 @@ __global__ __launch_bounds__(256) void k_combine_chunks(const int32_t *__restric
   if (nc == 1) return;
   float *dst = S + (int64_t)b * dim;
   const float *src = partial + (int64_t)c0 * dim;
-  for (int c = threadIdx.x; c < dim; c += blockDim.x) {
+  // grid.y splits the columns: late in training a few dozen nodes hold all the chunks
+  for (int c = blockIdx.y * blockDim.x + threadIdx.x; c < dim; c += gridDim.y * blockDim.x) {
     double a[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     int t = 0;
     for (; t + 8 <= nc; t += 8)
@@ -254,19 +256,24 @@ static int radix_passes(int k) {
 // Stable permutation of instance ids by BMU, segment offsets and counts.
 // On return c->sort_val[0] holds the permutation (c->sort_key[0] the sorted BMUs).
 hipError_t launch_sort_by_bmu(som_ctx *c, const int32_t *bmus, int64_t n) {
-  const int nblk = (int)((n + kSortTile - 1) / kSortTile);
+  // Keys per wavefront of the scatter: small tiles give more parallelism, but the histogram of
+  // 256 counters per tile is scanned by one workgroup, so their number is kept near 256.
+  int64_t tile64 = ((n + 255) / 256 + 63) / 64 * 64;
+  if (tile64 < kSortTile) tile64 = kSortTile;
+  const int tile = (int)tile64;
+  const int nblk = (int)((n + tile - 1) / tile);
   const int passes = radix_passes(c->k);
   const int32_t *kin = bmus;
   const int32_t *vin = nullptr;
   // an even number of hops ends in buffer 0: start in buffer 1 when the pass count is even
   int dst = (passes % 2 == 0) ? 1 : 0;
   for (int p = 0; p < passes; ++p) {
-    hipLaunchKernelGGL(k_radix_hist, dim3(nblk), dim3(256), 0, c->stream, kin, n, 8 * p, nblk, c->k,
+    hipLaunchKernelGGL(k_radix_hist, dim3(nblk), dim3(256), 0, c->stream, kin, n, 8 * p, nblk, tile, c->k,
                        c->radix_hist);
     hipLaunchKernelGGL(k_scan_exclusive, dim3(1), dim3(1024), 0, c->stream, c->radix_hist, c->radix_hist,
                        256 * nblk, 0);
     hipLaunchKernelGGL(k_radix_scatter, dim3(nblk), dim3(64), 0, c->stream, kin, vin, c->sort_key[dst],
-                       c->sort_val[dst], n, 8 * p, nblk, c->k, c->radix_hist);
+                       c->sort_val[dst], n, 8 * p, nblk, tile, c->k, c->radix_hist);
     kin = c->sort_key[dst];
     vin = c->sort_val[dst];
     dst ^= 1;
@@ -294,7 +301,9 @@ hipError_t launch_accumulate_dense(som_ctx *c, const float *X, int64_t n) {
   else
     hipLaunchKernelGGL(k_accumulate_dense<false>, dim3((unsigned)max_chunks), dim3(threads), 0, c->stream, X,
                        c->dim, c->sort_val[0], c->seg_off, c->chunk_off, c->chunk_node, c->k, c->S, c->partial);
-  hipLaunchKernelGGL(k_combine_chunks, dim3(c->k), dim3(256), 0, c->stream, c->chunk_off, c->dim, c->partial,
+  int ysplit = (c->dim + 255) / 256;
+  if (ysplit > 16) ysplit = 16;
+  hipLaunchKernelGGL(k_combine_chunks, dim3(c->k, ysplit), dim3(256), 0, c->stream, c->chunk_off, c->dim, c->partial,
                      c->S);
   return hipGetLastError();
 }

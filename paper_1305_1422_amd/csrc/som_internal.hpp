@@ -15,7 +15,7 @@ constexpr int kWave = 64;                 // CDNA wavefront width
 constexpr int kCand = 4;                  // candidate nodes kept per instance by the fp32 pass
 constexpr int kListCap = 64;              // nodes a collected candidate list can hold per instance
 constexpr int kChunkRows = 32;            // instances summed by one block of the segmented accumulation
-constexpr int kSortTile = 4096;           // keys ranked by one wave of the radix scatter
+constexpr int kSortTile = 1024;           // fewest keys ranked by one wave of the radix scatter
 constexpr int kSmoothMatMax = 1024;        // largest map side for which the smoothing filters are stored as matrices
 constexpr int kProfMax = 512;              // event brackets kept per stage between two reads
 #ifndef SOM_FLUSH_BLOCK
