@@ -58,21 +58,35 @@ __device__ __forceinline__ void load4_to_lds_h(const void *base, unsigned lane_o
                : "v"(lane_offset), "s"(base), "s"(lds_base)
                : "memory", "m0");
 }
+// 16 bytes per lane from a full 64-bit address per lane (rows gathered through an index list).
+__device__ __forceinline__ void load16_to_lds_v(const void *lane_address, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(lane_address), "s"(lds_base) : "memory", "m0");
+}
 #pragma clang diagnostic pop
+
+enum { kHFilter = 0, kHCollect = 1, kHDump = 2 };
 
 __device__ __forceinline__ f16x8 as_halves(f32x4 v) { return __builtin_bit_cast(f16x8, v); }
 
 // WI: 64-instance columns of wavefronts in a workgroup.  WI = 4: 8 wavefronts, 256 instances, three
 // LDS stages (144 KB), one workgroup per CU.  WI = 2: 4 wavefronts, 128 instances, two LDS stages
 // (64 KB), two workgroups per CU whose barriers are independent.
-// kDump: instead of keeping candidates, write every score to dump[slot * k + node] (test hook).
-template <int WI, bool kDump>
+// kMode: kHFilter keeps candidates per instance; kHCollect runs over the instances listed in `rows`
+// (their number is *n_slots) and appends every node whose score is at most thr[slot] to the
+// instance's list; kHDump writes every score to dump[slot * k + node] (test hook).
+template <int WI, int kMode>
 __global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__restrict__ Xh, const float *__restrict__ Wh,
                                                         const float *__restrict__ wc,
                                                         const float *__restrict__ xscale,
                                                         const float *__restrict__ wscale,
                                                         int64_t n, int k, int nK,
-                                                        int groups, CandView out, float *__restrict__ dump) {
+                                                        int groups, CandView out, float *__restrict__ dump,
+                                                        const int32_t *__restrict__ rows,
+                                                        const int32_t *__restrict__ n_slots,
+                                                        const float *__restrict__ thr, int32_t *__restrict__ cnt,
+                                                        int32_t *__restrict__ list) {
+  constexpr bool kCollect = kMode == kHCollect;
+  constexpr bool kDump = kMode == kHDump;
   constexpr int kHTI = 64 * WI;              // instances per tile
   constexpr int kHXTile = kHTI * kHRow;      // floats
   constexpr int kHStages = WI == 4 ? 3 : 2;
@@ -90,7 +104,8 @@ __global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__rest
   const int lhi = lane >> 5;
 
   // workgroup -> (instance tile, node group)
-  const int64_t ntiles = (n + kHTI - 1) / kHTI;
+  const int64_t n_inst = kCollect ? (int64_t)*n_slots : n;      // slots this launch covers
+  const int64_t ntiles = (n_inst + kHTI - 1) / kHTI;
   const int xcd = blockIdx.x & 7;
   const int64_t slot_id = blockIdx.x >> 3;
   const int group = (int)(slot_id % groups);
@@ -113,14 +128,17 @@ __global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__rest
   const int ld_pos = lane & 7;
   const unsigned row_bytes = (unsigned)nK * (kHRow * 4);
   const char *xbase = reinterpret_cast<const char *>(Xh) + inst0 * (int64_t)row_bytes;
-  const int64_t last_inst = n - 1 - inst0;       // >= 0
+  const int64_t last_inst = n_inst - 1 - inst0;  // >= 0
   unsigned xoff[4], woff[kWSlots], wq[kWSlots];
+  const char *xptr[4];                           // collect mode: gathered rows, one address per lane
   int wrow[kWSlots];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int row = 8 * (4 * wave + i) + ld_rloc;
     const int q = ld_pos ^ ((row & 7) ^ ((row >> 3) & 1));
-    xoff[i] = (unsigned)(row < last_inst ? row : (int)last_inst) * row_bytes + 16u * q;
+    const int rclamped = row < last_inst ? row : (int)last_inst;
+    xoff[i] = (unsigned)rclamped * row_bytes + 16u * q;
+    xptr[i] = kCollect ? reinterpret_cast<const char *>(Xh) + (int64_t)rows[inst0 + rclamped] * row_bytes + 16 * q : nullptr;
   }
 #pragma unroll
   for (int i = 0; i < kWSlots; ++i) {
@@ -147,7 +165,10 @@ __global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__rest
 #pragma unroll
     for (int i = 0; i < kWSlots; ++i) load16_to_lds_h(wbase + off, woff[i], lds_w + buf * (kHWTile * 4) + i * 1024);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) load16_to_lds_h(xbase + off, xoff[i], lds_x + buf * (kHXTile * 4) + i * 1024);
+    for (int i = 0; i < 4; ++i) {
+      if (kCollect) load16_to_lds_v(xptr[i] + off, lds_x + buf * (kHXTile * 4) + i * 1024);
+      else load16_to_lds_h(xbase + off, xoff[i], lds_x + buf * (kHXTile * 4) + i * 1024);
+    }
     if (++ld_kc == nK) { ld_kc = 0; ++ld_nb; }
   };
 
@@ -160,7 +181,7 @@ __global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__rest
   const int b_base = (wi * 64 + l32) * kHRow;
 
   Top2 top[2];
-  float lim[2] = {0.f, 0.f};
+  float lim[2];
   int64_t slot_of[2];
   float factor[2];
   const float sw = *wscale;
@@ -168,7 +189,10 @@ __global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__rest
   for (int ni = 0; ni < 2; ++ni) {
     top2_init(top[ni]);
     slot_of[ni] = inst0 + wi * 64 + ni * 32 + l32;
-    factor[ni] = slot_of[ni] < n ? -2.f * xscale[slot_of[ni]] * sw : 0.f;
+    const bool live = slot_of[ni] < n_inst;
+    const int64_t inst = live ? (kCollect ? (int64_t)rows[slot_of[ni]] : slot_of[ni]) : 0;
+    factor[ni] = live ? -2.f * xscale[inst] * sw : 0.f;
+    lim[ni] = (kCollect && live) ? thr[slot_of[ni]] : -INFINITY;
   }
 
   f32x16 acc[2][2], tot[2][2];
@@ -286,7 +310,7 @@ __global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__rest
             }
           }
       } else {
-        consume_scores<false>(tot, sWn[nb & 3], nb * kTN, k, wm, lhi, factor, top, lim, slot_of, nullptr, nullptr);
+        consume_scores<kCollect>(tot, sWn[nb & 3], nb * kTN, k, wm, lhi, factor, top, lim, slot_of, cnt, list);
       }
     }
 
@@ -294,7 +318,7 @@ __global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__rest
     __syncthreads();
     stage = next_stage;
   }
-  if (kDump) return;
+  if (kDump || kCollect) return;
   merge_and_store<kHTI>(top, &sW[0][0], reinterpret_cast<int *>(&sX[0][0]), tid, wm, wi, l32, lhi, inst0, n, group,
                         out);
 }
@@ -321,11 +345,30 @@ hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump) {
   const float *Xh = reinterpret_cast<const float *>(c->Xh);
   const float *Wh = reinterpret_cast<const float *>(c->Wh);
   if (dump)
-    hipLaunchKernelGGL((k_bmu_dense_h<kHWI, true>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
-                       c->wn32, c->xscale, c->wscale, n, c->k, nK, groups, out, dump);
+    hipLaunchKernelGGL((k_bmu_dense_h<kHWI, kHDump>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
+                       c->wn32, c->xscale, c->wscale, n, c->k, nK, groups, out, dump, nullptr, nullptr, nullptr,
+                       nullptr, nullptr);
   else
-    hipLaunchKernelGGL((k_bmu_dense_h<kHWI, false>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
-                       c->wn32, c->xscale, c->wscale, n, c->k, nK, groups, out, dump);
+    hipLaunchKernelGGL((k_bmu_dense_h<kHWI, kHFilter>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
+                       c->wn32, c->xscale, c->wscale, n, c->k, nK, groups, out, dump, nullptr, nullptr, nullptr,
+                       nullptr, nullptr);
+  return hipGetLastError();
+}
+
+// Repeats the sweep for the instances in c->collect_rows (their number is only known on the
+// device: the grid covers the worst case and surplus workgroups leave at once).  Usually only a
+// few instance tiles are live, so the node blocks are shared out over up to 16 workgroups.
+hipError_t launch_bmu_dense_h_collect(som_ctx *c, int64_t n) {
+  const int nNB = (c->k + kTN - 1) / kTN;
+  const int groups = nNB < 16 ? nNB : 16;
+  const int64_t tiles = (n + 64 * kHWI - 1) / (64 * kHWI);
+  const int64_t blocks = (tiles + 7) / 8 * 8 * groups;
+  const int nK = (c->dim + 31) / 32;
+  CandView out{nullptr, nullptr, nullptr};
+  hipLaunchKernelGGL((k_bmu_dense_h<kHWI, kHCollect>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
+                     reinterpret_cast<const float *>(c->Xh), reinterpret_cast<const float *>(c->Wh), c->wn32,
+                     c->xscale, c->wscale, n, c->k, nK, groups, out, nullptr, c->collect_rows, c->list_counts + 1,
+                     c->collect_thr, c->collect_cnt, c->collect_list);
   return hipGetLastError();
 }
 

@@ -103,11 +103,23 @@ __global__ __launch_bounds__(256) void k_center_codebook(const float *__restrict
       if (wn64) wn64[i] = sw;
     }
   }
-  if (tl == 0 && vmax > 0.f) atomicMax(max_bits, __float_as_uint(vmax));
-  if (wabs_bits) {
+  // one pair of atomics per workgroup: thousands of atomics on one address would cost more than
+  // the rest of the kernel
+  __shared__ float smax[2][4];
+  if (tl != 0) vmax = 0.f;
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
-    if ((threadIdx.x & 63) == 0 && amax > 0.f) atomicMax(wabs_bits, __float_as_uint(amax));
+  for (int o = 32; o > 0; o >>= 1) {
+    vmax = fmaxf(vmax, __shfl_xor(vmax, o, 64));
+    amax = fmaxf(amax, __shfl_xor(amax, o, 64));
+  }
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) { smax[0][threadIdx.x >> 6] = vmax; smax[1][threadIdx.x >> 6] = amax; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    vmax = fmaxf(fmaxf(smax[0][0], smax[0][1]), fmaxf(smax[0][2], smax[0][3]));
+    amax = fmaxf(fmaxf(smax[1][0], smax[1][1]), fmaxf(smax[1][2], smax[1][3]));
+    if (vmax > 0.f) atomicMax(max_bits, __float_as_uint(vmax));
+    if (wabs_bits && amax > 0.f) atomicMax(wabs_bits, __float_as_uint(amax));
   }
 }
 
@@ -222,7 +234,7 @@ hipError_t launch_center_codebook(som_ctx *c, const float *W, bool store_centere
   float *wc = store_centered ? c->Wc : nullptr;
   unsigned *wabs = store_centered ? c->wmax_bits + 1 : nullptr;
   double *wn64 = want_wn64 ? c->wn64 : nullptr;
-  const int cap = c->n_cu * 8;
+  const int cap = c->n_cu * 2;
   if (c->dim <= 2048) {
     const int need = (c->k + 3) / 4;
     hipLaunchKernelGGL(k_center_codebook<64>, dim3(need < cap ? need : cap), dim3(256), 0, c->stream, W, c->k, c->dim,

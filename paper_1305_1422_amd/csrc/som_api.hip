@@ -209,7 +209,8 @@ static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *
   StageTimer t(c, 2);
   SOM_LAUNCH(c, launch_certify(c, n, split ? bmu_dense_h_groups(c, n) : bmu_dense_groups(c, n), split, bmus));
   SOM_LAUNCH(c, launch_refine_dense(c, X, W, bmus));
-  SOM_LAUNCH(c, launch_bmu_dense_collect(c, X, n));
+  if (split) SOM_LAUNCH(c, launch_bmu_dense_h_collect(c, n));
+  else SOM_LAUNCH(c, launch_bmu_dense_collect(c, X, n));
   SOM_LAUNCH(c, launch_refine_lists_dense(c, X, W, bmus));
   SOM_LAUNCH(c, launch_rescan_dense(c, X, W, bmus));
   return SOM_OK;

@@ -140,6 +140,7 @@ hipError_t launch_bmu_dense_dl(som_ctx *c, const float *X, int64_t n, dim3 grid,
 // bmu_dense_h.hip, split_f16.hip
 int bmu_dense_h_groups(const som_ctx *c, int64_t n);
 hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump);            // Xh, Wh -> candidates (or all scores)
+hipError_t launch_bmu_dense_h_collect(som_ctx *c, int64_t n);                 // rows of collect_rows -> collect_list
 hipError_t launch_split_rows_f16(som_ctx *c, const float *A, int64_t nrows, const unsigned *global_max_bits,
                                  _Float16 *out, float *scale_out);
 hipError_t launch_probe_mfma_f16(hipStream_t stream, const uint16_t *A, const uint16_t *B, const float *C, float *D,
