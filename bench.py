@@ -25,6 +25,11 @@ METRIC = "epoch throughput (instance*node*dim/s)"
 PEAK_FP32_MFMA_TFLOPS = 157.3
 PEAK_FP16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
+# HBM-side bytes per launch of the dominant kernel (fetched + written), from the two rocprofv3 --pmc
+# runs (FETCH_SIZE, WRITE_SIZE, scaled by the copy calibration) summarised under profiles/;
+# measured once per kernel version, not during this run.  Workloads without a counter run: None.
+MEASURED_TRAFFIC_BYTES = {(2, "split_f16"): 8.980e9 + 0.025e9, (2, "fp32"): 8.49e9 + 0.025e9,
+                          (4, "split_f16"): 63.35e9 + 0.005e9, (4, "fp32"): 63.35e9 + 0.005e9}
 
 
 def cpu_baseline(w, X, W0, seconds_budget: float = 20.0):
@@ -136,12 +141,14 @@ def main() -> int:
         if args.filter == "fp32":
             roofline = {"bound": "mfma", "kernel": "k_bmu_dense_dl<false> (fp32 MFMA BMU filter pass)",
                         "achieved": fp32_equiv, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                        "frac": fp32_equiv / PEAK_FP32_MFMA_TFLOPS, "traffic": None, "avg_launch_ms": dom_ms}
+                        "frac": fp32_equiv / PEAK_FP32_MFMA_TFLOPS,
+                        "traffic": MEASURED_TRAFFIC_BYTES.get((w.config, args.filter)), "avg_launch_ms": dom_ms}
         else:
             # three fp16 matrix products per (instance, node, feature): hi*hi + hi*lo + lo*hi
             roofline = {"bound": "mfma", "kernel": "k_bmu_dense_h<false> (BMU filter pass, 3 fp16 MFMAs on split fp32 operands)",
                         "achieved": 3.0 * fp32_equiv, "peak": PEAK_FP16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                        "frac": 3.0 * fp32_equiv / PEAK_FP16_MFMA_TFLOPS, "traffic": None, "avg_launch_ms": dom_ms,
+                        "frac": 3.0 * fp32_equiv / PEAK_FP16_MFMA_TFLOPS,
+                        "traffic": MEASURED_TRAFFIC_BYTES.get((w.config, args.filter)), "avg_launch_ms": dom_ms,
                         "fp32_equivalent_tflops": fp32_equiv,
                         "fp32_equivalent_vs_fp32_mfma_peak": fp32_equiv / PEAK_FP32_MFMA_TFLOPS}
     else:
@@ -153,7 +160,9 @@ def main() -> int:
         achieved = alg_bytes / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
         roofline = {"bound": "hbm", "kernel": "k_transpose + k_bmu_csr (sparse fp32 BMU pass)",
                     "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
-                    "traffic": None, "avg_launch_ms": dom_ms}
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((w.config, args.filter)), "avg_launch_ms": dom_ms,
+                    "traffic_rate_gbs": (MEASURED_TRAFFIC_BYTES[(w.config, args.filter)] / (dom_ms * 1e-3) / 1e9
+                                         if (w.config, args.filter) in MEASURED_TRAFFIC_BYTES and dom_ms > 0 else None)}
 
     out = {
         "metric": METRIC, "value": value, "unit": "instance*node*dim/s", "n_gpus": 1, "steps": args.steps,

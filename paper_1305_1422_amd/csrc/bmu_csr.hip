@@ -39,6 +39,31 @@ __global__ __launch_bounds__(256) void k_transpose_centered(const float *__restr
   }
 }
 
+// The same transposition for the sliced kernel: entries as int16 multiples of the column's
+// quantisation step, q = round((w - mu_c) / step_c), |q| <= 32767 by the choice of the step.
+__global__ __launch_bounds__(256) void k_transpose_centered_q16(const float *__restrict__ W,
+                                                                const float *__restrict__ mu,
+                                                                const float *__restrict__ qstep, int k, int dim,
+                                                                int kpad, int16_t *__restrict__ Wt) {
+  __shared__ float tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;       // 32 x 8
+  const int c0 = blockIdx.x * 32, i0 = blockIdx.y * 32;
+  for (int r = ty; r < 32; r += 8) {
+    const int i = i0 + r, c = c0 + tx;
+    float q = 0.f;
+    if (i < k && c < dim) {
+      q = rintf((W[(int64_t)i * dim + c] - mu[c]) / qstep[c]);
+      q = fminf(fmaxf(q, -32767.f), 32767.f);
+    }
+    tile[r][tx] = q;
+  }
+  __syncthreads();
+  for (int r = ty; r < 32; r += 8) {
+    const int c = c0 + r, i = i0 + tx;
+    if (c < dim && i < kpad) Wt[(int64_t)c * kpad + i] = (int16_t)tile[tx][r];
+  }
+}
+
 // Error bound of one sparse fp32 score (see bmu_exact.hip): FMA chain of len terms, g = len.
 __device__ __forceinline__ double csr_margin(double len, double xnorm2, double wmax2, double munorm2) {
   const double u = 5.9604644775390625e-08;   // 2^-24
@@ -187,9 +212,215 @@ __global__ __launch_bounds__(256) void k_bmu_csr(const int64_t *__restrict__ ind
   }
 }
 
+// ---------------------------------------------------------------- node slices, one per XCD
+// What bounds the kernel above is the traffic its gathers send past L2: a nonzero touches a whole
+// row of Wt (4 kpad bytes), the popular columns of a Zipf-distributed vocabulary are few, and a 4 MB
+// L2 holds only some hundred rows.  MI355X has eight L2s, one per XCD, and hands workgroup b to
+// XCD b mod 8.  So the nodes are cut into eight slices and workgroup b only ever scores slice
+// b mod 8: an XCD then touches an eighth of every row of Wt, its L2 holds eight times as many
+// columns, and the instances are walked once per slice (their 8 bytes per nonzero are small
+// change next to the 4 kpad / 8 bytes of the gather).
+//
+// A wavefront owns one (instance, slice) pair; lane l owns nodes slice0 + l + 64 a.  The nonzeros of
+// the row are read 64 at a time, one per lane, and handed round with v_readlane: column and value
+// of the current nonzero live in scalar registers, so the gathers are "scalar base + lane offset"
+// loads and the multiply-adds take the value as a scalar operand - no LDS, no workgroup barrier.
+// Wt holds 16-bit integers here (k_transpose_centered_q16): half the bytes per gather, twice the
+// columns per L2; the value of a nonzero is multiplied by its column's step once, and a gathered
+// entry costs one conversion before its multiply-add.  The quantisation moves the dot product of
+// a row by at most 0.51 sum_nz |v_c| step_c; that sum falls out of the products the lanes hold
+// anyway and is stored per instance (row_q) for the margin of k_certify.
+// Output per pair: the two best nodes and the smallest score dropped, in the candidate arrays of
+// the dense path ([slice][instance][kCand]); k_certify merges the eight slices.  In collect mode
+// the wavefront appends every node under the instance's threshold to its list instead.
+__device__ __forceinline__ void wave_argmin(float &v, int &i) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(v, o, 64);
+    const int oi = __shfl_xor(i, o, 64);
+    const bool take = ov < v || (ov == v && (unsigned)oi < (unsigned)i);
+    v = take ? ov : v;
+    i = take ? oi : i;
+  }
+}
+
+template <int ACC, bool kCollect>
+__global__ __launch_bounds__(256) void k_bmu_csr_sliced(const int64_t *__restrict__ indptr,
+                                                        const int32_t *__restrict__ indices,
+                                                        const float *__restrict__ values,
+                                                        const int16_t *__restrict__ Wt, int kpad,
+                                                        const float *__restrict__ qstep,
+                                                        const float *__restrict__ cn32, int64_t n, int k, int dim,
+                                                        CandView out, float *__restrict__ row_q,
+                                                        const int32_t *__restrict__ rows,
+                                                        const int32_t *__restrict__ n_slots,
+                                                        const float *__restrict__ thr, int32_t *__restrict__ cnt,
+                                                        int32_t *__restrict__ list) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int slice = blockIdx.x & 7;
+  const int slice0 = slice * (kpad >> 3);               // kpad is a multiple of 512: ACC * 64 nodes per slice
+  const int64_t pairs = kCollect ? (int64_t)*n_slots : n;
+  const int64_t stride = (int64_t)(gridDim.x >> 3) * 4;
+  float cnode[ACC];
+#pragma unroll
+  for (int a = 0; a < ACC; ++a) {
+    const int node = slice0 + lane + 64 * a;
+    cnode[a] = node < k ? cn32[node] : INFINITY;
+  }
+  for (int64_t p = (int64_t)(blockIdx.x >> 3) * 4 + wave; p < pairs; p += stride) {
+    const int64_t j = kCollect ? (int64_t)rows[p] : p;
+    const int64_t rs = indptr[j];
+    const int len = (int)(indptr[j + 1] - rs);
+    float acc[ACC];
+#pragma unroll
+    for (int a = 0; a < ACC; ++a) acc[a] = 0.f;
+    float vq_abs = 0.f;                                  // this lane's share of sum |v_c| step_c
+    for (int p0 = 0; p0 < len; p0 += 64) {
+      int c = 0;
+      float v = 0.f;
+      if (p0 + lane < len) {
+        c = indices[rs + p0 + lane];
+        c = c < 0 ? 0 : (c >= dim ? dim - 1 : c);
+        v = values[rs + p0 + lane] * qstep[c];
+        vq_abs += fabsf(v);
+      }
+      const int m = min(64, len - p0);
+      int q = 0;
+      // four nonzeros per step: all their gathers are issued before the first use
+      for (; q + kCsrUnroll <= m; q += kCsrUnroll) {
+        int w[kCsrUnroll][ACC];
+        float vs[kCsrUnroll];
+#pragma unroll
+        for (int u = 0; u < kCsrUnroll; ++u) {
+          const int cs = __builtin_amdgcn_readlane(c, q + u);
+          vs[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), q + u));
+          const int16_t *wrow = Wt + (int64_t)cs * kpad + slice0 + lane;
+#pragma unroll
+          for (int a = 0; a < ACC; ++a) w[u][a] = wrow[64 * a];
+        }
+#pragma unroll
+        for (int u = 0; u < kCsrUnroll; ++u)
+#pragma unroll
+          for (int a = 0; a < ACC; ++a) acc[a] = fmaf(vs[u], (float)w[u][a], acc[a]);
+      }
+      for (; q < m; ++q) {
+        const int cs = __builtin_amdgcn_readlane(c, q);
+        const float vq = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), q));
+        const int16_t *wrow = Wt + (int64_t)cs * kpad + slice0 + lane;
+#pragma unroll
+        for (int a = 0; a < ACC; ++a) acc[a] = fmaf(vq, (float)wrow[64 * a], acc[a]);
+      }
+    }
+    float sc[ACC];
+#pragma unroll
+    for (int a = 0; a < ACC; ++a) sc[a] = fmaf(-2.f, acc[a], cnode[a]);      // +inf for nodes past k
+
+    if (kCollect) {
+      const float lim = thr[p];
+#pragma unroll
+      for (int a = 0; a < ACC; ++a) {
+        const int node = slice0 + lane + 64 * a;
+        if (sc[a] <= lim && node < k) {
+          const int pos = atomicAdd(&cnt[p], 1);
+          if (pos < kListCap) list[p * kListCap + pos] = node;
+        }
+      }
+    } else {
+      // two best nodes of the slice and the smallest score after them
+      float best[3];
+      int arg[2];
+#pragma unroll
+      for (int t = 0; t < 3; ++t) {
+        float v = INFINITY;
+        int i = 0x7fffffff;
+#pragma unroll
+        for (int a = 0; a < ACC; ++a) {
+          const int node = slice0 + lane + 64 * a;
+          const bool take = sc[a] < v;                   // nodes ascend with a: strict keeps the lower index
+          v = take ? sc[a] : v;
+          i = take ? node : i;
+        }
+        wave_argmin(v, i);
+        best[t] = v;
+        if (t < 2) {
+          arg[t] = i;
+#pragma unroll
+          for (int a = 0; a < ACC; ++a)
+            if (slice0 + lane + 64 * a == i) sc[a] = INFINITY;
+        }
+      }
+      if (slice == 0) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) vq_abs += __shfl_xor(vq_abs, o, 64);
+        if (lane == 0) row_q[j] = vq_abs;
+      }
+      if (lane == 0) {
+        const int64_t o = (int64_t)slice * n + j;
+        out.val[o * kCand + 0] = best[0];
+        out.idx[o * kCand + 0] = best[0] < INFINITY ? arg[0] : -1;
+        out.val[o * kCand + 1] = best[1];
+        out.idx[o * kCand + 1] = best[1] < INFINITY ? arg[1] : -1;
+#pragma unroll
+        for (int t = 2; t < kCand; ++t) { out.val[o * kCand + t] = INFINITY; out.idx[o * kCand + t] = -1; }
+        out.over[o] = best[2];
+      }
+    }
+  }
+}
+
+constexpr int kCsrSlices = 8;
+constexpr int kCsrSlicedMaxAcc = 16;       // the sliced kernel keeps kpad / 8 / 64 scores per lane
+
+bool bmu_csr_sliced_ok(const som_ctx *c) { return c->kpad / (kCsrSlices * 64) <= kCsrSlicedMaxAcc; }
+
+template <bool kCollect>
+static void launch_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values, int64_t n) {
+  const int acc = c->kpad / (kCsrSlices * 64);
+  int64_t groups = (n + 3) / 4;                                   // workgroups per slice
+  const int64_t cap = (int64_t)c->n_cu;                           // 8 slices x n_cu = 8 workgroups per CU
+  if (groups > cap) groups = cap;
+  const dim3 grid((unsigned)(groups * kCsrSlices));
+  CandView out{c->cand_val, c->cand_idx, c->cand_over};
+#define SOM_SLICED(A)                                                                                              \
+  hipLaunchKernelGGL((k_bmu_csr_sliced<A, kCollect>), grid, dim3(256), 0, c->stream, indptr, indices, values,        \
+                     reinterpret_cast<const int16_t *>(c->Wt), c->kpad, c->qstep, c->wn32, n, c->k, c->dim, out,    \
+                     c->row_q, c->collect_rows, c->list_counts + 1, c->collect_thr, c->collect_cnt, c->collect_list)
+  switch (acc) {
+    case 1: SOM_SLICED(1); break;
+    case 2: SOM_SLICED(2); break;
+    case 3: SOM_SLICED(3); break;
+    case 4: SOM_SLICED(4); break;
+    case 5: SOM_SLICED(5); break;
+    case 6: SOM_SLICED(6); break;
+    case 7: SOM_SLICED(7); break;
+    case 8: SOM_SLICED(8); break;
+    case 9: SOM_SLICED(9); break;
+    case 10: SOM_SLICED(10); break;
+    case 11: SOM_SLICED(11); break;
+    case 12: SOM_SLICED(12); break;
+    case 13: SOM_SLICED(13); break;
+    case 14: SOM_SLICED(14); break;
+    case 15: SOM_SLICED(15); break;
+    default: SOM_SLICED(16); break;
+  }
+#undef SOM_SLICED
+}
+
+hipError_t launch_bmu_csr_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
+                                 int64_t n, bool collect) {
+  if (collect) launch_sliced<true>(c, indptr, indices, values, n);
+  else launch_sliced<false>(c, indptr, indices, values, n);
+  return hipGetLastError();
+}
+
 hipError_t launch_transpose_codebook(som_ctx *c, const float *W) {
   dim3 grid((c->dim + 31) / 32, (c->kpad + 31) / 32);
-  hipLaunchKernelGGL(k_transpose_centered, grid, dim3(256), 0, c->stream, W, c->mu, c->k, c->dim, c->kpad, c->Wt);
+  if (bmu_csr_sliced_ok(c))
+    hipLaunchKernelGGL(k_transpose_centered_q16, grid, dim3(256), 0, c->stream, W, c->mu, c->qstep, c->k, c->dim,
+                       c->kpad, reinterpret_cast<int16_t *>(c->Wt));
+  else
+    hipLaunchKernelGGL(k_transpose_centered, grid, dim3(256), 0, c->stream, W, c->mu, c->k, c->dim, c->kpad, c->Wt);
   return hipGetLastError();
 }
 

@@ -36,6 +36,8 @@ struct MarginModel {
   double coef_floor;         // 0 for the fp32 pass
   const float *xscale;       // [n] power-of-two scale of every instance (split-fp16 pass), else null
   const float *wscale;       // [1] power-of-two scale of the centred code book, else null
+  const int64_t *indptr;     // sparse rows: coef_xw = 2 max(row length, 1) + 6 (one FMA chain over the row)
+  const float *row_q;        // [n] sparse rows scored against the 16-bit code book: sum_nz |v_c| step_c
 };
 
 __device__ __forceinline__ double score_margin(const MarginModel &mm, int64_t j, double xnorm2, double wmax2,
@@ -44,9 +46,19 @@ __device__ __forceinline__ double score_margin(const MarginModel &mm, int64_t j,
   const double xn = sqrt(xnorm2 * (1.0 + 1.2e-7));
   const double wm = sqrt(wmax2 * (1.0 + 1.2e-7));
   const double mn = sqrt(munorm2 * (1.0 + 1.2e-7));
-  double bound = mm.coef_xw * xn * wm + 4.0 * wm * wm + 6.0 * mn * wm;
+  double coef = mm.coef_xw;
+  double absolute = 0.0;
+  if (mm.indptr) {
+    const double len = (double)(mm.indptr[j + 1] - mm.indptr[j]);
+    coef = 2.0 * (len < 1.0 ? 1.0 : len) + 6.0;     // + 2: the product of value and column step is rounded
+    // a quantised entry is within 0.51 steps of w' (0.5 from rounding, the rest from the fp32
+    // division), so the dot product moves by at most 0.51 sum |v_c| step_c (the sum itself carries
+    // fp32 rounding: 1e-5 relative is ample), the score by twice that
+    if (mm.row_q) absolute = 2.0 * 0.51 * (1.0 + 1e-5) * (double)mm.row_q[j];
+  }
+  double bound = coef * xn * wm + 4.0 * wm * wm + 6.0 * mn * wm;
   if (mm.xscale) bound += mm.coef_floor * ((double)mm.xscale[j] * wm + (double)*mm.wscale * xn);
-  return 2.125 * u * bound;          // both scores of a pair may err, plus slack for higher-order terms
+  return 2.125 * (u * bound + absolute);          // both scores of a pair may err, plus slack for higher-order terms
 }
 
 // `groups` candidate lists per instance (one per node group of the fp32 pass), stored
@@ -251,7 +263,8 @@ __global__ __launch_bounds__(256) void k_refine_lists_csr(const int64_t *__restr
                                                           const int32_t *__restrict__ collect_rows,
                                                           const int32_t *__restrict__ collect_cnt,
                                                           const int32_t *__restrict__ collect_list,
-                                                          const int32_t *__restrict__ list_counts,
+                                                          int32_t *__restrict__ rescan_list,
+                                                          int32_t *__restrict__ list_counts,
                                                           int32_t *__restrict__ bmus) {
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
@@ -261,6 +274,10 @@ __global__ __launch_bounds__(256) void k_refine_lists_csr(const int64_t *__restr
     const int64_t j = collect_rows[e];
     const int64_t s = indptr[j];
     const int len = (int)(indptr[j + 1] - s);
+    if (collect_cnt[e] > kListCap || collect_cnt[e] < 1) {      // overflowed (or empty) list: exact scan of all nodes
+      if (lane == 0) rescan_list[atomicAdd(&list_counts[2], 1)] = (int32_t)j;
+      continue;
+    }
     const int cn = min(collect_cnt[e], kListCap);
     const int32_t *lst = collect_list + (int64_t)e * kListCap;
     double best = INFINITY;
@@ -331,10 +348,14 @@ static double split_pass_roundings(int dim) {
   return 2.5 * 12.0 + 9.0 + (double)((dim + 63) / 64) + 2.0;
 }
 
-hipError_t launch_certify(som_ctx *c, int64_t n, int groups, bool split_filter, int32_t *bmus) {
+hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int64_t *indptr, int32_t *bmus) {
   CandView cand{c->cand_val, c->cand_idx, c->cand_over};
-  MarginModel mm{2.0 * fp32_pass_roundings(c->dim) + 4.0, 0.0, nullptr, nullptr};
-  if (split_filter) {
+  MarginModel mm{2.0 * fp32_pass_roundings(c->dim) + 4.0, 0.0, nullptr, nullptr, nullptr, nullptr};
+  if (mode == kCertifyCsr) {
+    mm.indptr = indptr;
+    mm.row_q = c->row_q;
+  }
+  if (mode == kCertifySplit) {
     // dot product: accumulation + 3 * 2^-22 of the split (= 12 u) ; both doubled by the factor -2;
     // + 4 for the stored c_i, the final multiply-add and the rounding of w - mu.  The collect pass
     // runs on the fp32 kernel with the threshold computed here, so the margin must cover that
@@ -380,7 +401,7 @@ hipError_t launch_refine_lists_csr(som_ctx *c, const int64_t *indptr, const int3
                                    const float *W, int32_t *bmus) {
   hipLaunchKernelGGL(k_refine_lists_csr, dim3(persistent_blocks(c, 1 << 20)), dim3(256), 0, c->stream, indptr,
                      indices, values, W, c->wn64, c->dim, c->k, c->collect_rows, c->collect_cnt, c->collect_list,
-                     c->list_counts, bmus);
+                     c->rescan_list, c->list_counts, bmus);
   return hipGetLastError();
 }
 

@@ -80,7 +80,22 @@ __global__ __launch_bounds__(256) void k_center_codebook(const float *__restrict
     const float *w = W + (int64_t)i * dim;
     float *wc = Wc ? Wc + (int64_t)i * dim : nullptr;
     double s2 = 0.0, sm = 0.0, sw = 0.0;
-    for (int c = tl; c < dim; c += kTeam) {
+    int c = tl;
+    for (; c + 3 * kTeam < dim; c += 4 * kTeam) {        // four independent loads in flight per thread
+      float m[4], x[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { m[u] = mu[c + u * kTeam]; x[u] = w[c + u * kTeam]; }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float t = x[u] - m[u];
+        if (Wc) wc[c + u * kTeam] = t;
+        amax = fmaxf(amax, fabsf(t));
+        s2 += (double)t * (double)t;
+        sm += (double)m[u] * (double)t;
+        sw += (double)x[u] * (double)x[u];
+      }
+    }
+    for (; c < dim; c += kTeam) {
       const float m = mu[c];
       const float x = w[c];
       const float t = x - m;
@@ -169,25 +184,62 @@ __global__ __launch_bounds__(256) void k_csr_row_sqnorms(const int64_t *__restri
 constexpr int kMeanSlabs = 64;
 constexpr int kMeanRowsPerSlab = 128;
 
+// With `range` the slab minima and maxima of every column are recorded too ([2][slabs][dim]).
 __global__ __launch_bounds__(64) void k_sample_col_sums(const float *__restrict__ A, int64_t nsample,
-                                                        int64_t stride, int dim, double *__restrict__ partial) {
+                                                        int64_t stride, int dim, double *__restrict__ partial,
+                                                        float *__restrict__ range) {
   const int c = blockIdx.x * 64 + threadIdx.x;
   if (c >= dim) return;
   const int64_t per = (nsample + kMeanSlabs - 1) / kMeanSlabs;
   const int64_t t0 = blockIdx.y * per;
   const int64_t t1 = t0 + per < nsample ? t0 + per : nsample;
   double s = 0.0;
-  for (int64_t t = t0; t < t1; ++t) s += (double)A[t * stride * dim + c];
+  float lo = INFINITY, hi = -INFINITY;
+  for (int64_t t = t0; t < t1; ++t) {
+    const float a = A[t * stride * dim + c];
+    s += (double)a;
+    lo = fminf(lo, a);
+    hi = fmaxf(hi, a);
+  }
   partial[(int64_t)blockIdx.y * dim + c] = s;
+  if (range) {
+    range[(int64_t)blockIdx.y * dim + c] = lo;
+    range[((int64_t)kMeanSlabs + blockIdx.y) * dim + c] = hi;
+  }
 }
 
+// Column means; with `range` (which must then cover ALL rows) also the 16-bit quantisation step of
+// every column of the centred matrix: step_c = max_i |a_ic - mu_c| / 32767 with a little slack, so
+// that a_ic - mu_c, rounded to fp32, divided by the step and rounded to an integer fits an int16;
+// and the largest step (atomic maximum on the bit pattern).
 __global__ __launch_bounds__(64) void k_finish_col_means(const double *__restrict__ partial, int64_t nsample,
-                                                         int dim, float *__restrict__ mu) {
+                                                         int dim, float *__restrict__ mu,
+                                                         const float *__restrict__ range, float *__restrict__ qstep,
+                                                         unsigned *__restrict__ qstep_max_bits) {
   const int c = blockIdx.x * 64 + threadIdx.x;
-  if (c >= dim) return;
-  double s = 0.0;
-  for (int b = 0; b < kMeanSlabs; ++b) s += partial[(int64_t)b * dim + c];
-  mu[c] = (float)(s / (double)nsample);
+  float step = 0.f;
+  if (c < dim) {
+    double s = 0.0;
+    for (int b = 0; b < kMeanSlabs; ++b) s += partial[(int64_t)b * dim + c];
+    const float m = (float)(s / (double)nsample);
+    mu[c] = m;
+    if (range) {
+      float lo = INFINITY, hi = -INFINITY;
+      for (int b = 0; b < kMeanSlabs; ++b) {
+        lo = fminf(lo, range[(int64_t)b * dim + c]);
+        hi = fmaxf(hi, range[((int64_t)kMeanSlabs + b) * dim + c]);
+      }
+      const double amax = fmax((double)hi - (double)m, (double)m - (double)lo);
+      step = amax > 0.0 && amax < 1e300 ? (float)(amax * (1.0 + 1e-6) / 32767.0) : 0.f;
+      if (!(step > 0.f)) step = 1.f;             // constant column (or no rows): every quotient is 0
+      qstep[c] = step;
+    }
+  }
+  if (range) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) step = fmaxf(step, __shfl_xor(step, o, 64));
+    if (threadIdx.x == 0 && step > 0.f) atomicMax(qstep_max_bits, __float_as_uint(step));
+  }
 }
 
 __global__ void k_zero_u32(unsigned *p, int64_t count) {
@@ -217,9 +269,21 @@ hipError_t launch_sample_col_means(som_ctx *c, const float *A, int64_t nrows, in
   const int64_t nsample = nrows < cap ? nrows : cap;
   const int64_t stride = nrows / nsample;
   hipLaunchKernelGGL(k_sample_col_sums, dim3((dim + 63) / 64, kMeanSlabs), dim3(64), 0, c->stream, A, nsample,
-                     stride, dim, c->mu_partial);
+                     stride, dim, c->mu_partial, (float *)nullptr);
   hipLaunchKernelGGL(k_finish_col_means, dim3((dim + 63) / 64), dim3(64), 0, c->stream, c->mu_partial, nsample,
-                     dim, mu);
+                     dim, mu, (const float *)nullptr, (float *)nullptr, (unsigned *)nullptr);
+  return hipGetLastError();
+}
+
+// Means of ALL rows of the code book (at most kMeanSlabs * kMeanRowsPerSlab of them) plus the
+// quantisation steps of its centred columns: c->mu, c->qstep, c->qstep_max_bits.
+hipError_t launch_codebook_means_and_steps(som_ctx *c, const float *W) {
+  hipError_t e = launch_fill_zero_u32(c->stream, c->qstep_max_bits, 1);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_sample_col_sums, dim3((c->dim + 63) / 64, kMeanSlabs), dim3(64), 0, c->stream, W,
+                     (int64_t)c->k, (int64_t)1, c->dim, c->mu_partial, c->col_range);
+  hipLaunchKernelGGL(k_finish_col_means, dim3((c->dim + 63) / 64), dim3(64), 0, c->stream, c->mu_partial,
+                     (int64_t)c->k, c->dim, c->mu, c->col_range, c->qstep, c->qstep_max_bits);
   return hipGetLastError();
 }
 
@@ -240,7 +304,8 @@ hipError_t launch_center_codebook(som_ctx *c, const float *W, bool store_centere
     hipLaunchKernelGGL(k_center_codebook<64>, dim3(need < cap ? need : cap), dim3(256), 0, c->stream, W, c->k, c->dim,
                        c->mu, wc, c->wn32, c->wmax_bits, wn64, wabs);
   } else {
-    hipLaunchKernelGGL(k_center_codebook<256>, dim3(c->k < cap ? c->k : cap), dim3(256), 0, c->stream, W, c->k, c->dim,
+    const int cap_long = c->n_cu * 8;       // long rows: more workgroups in flight, still few atomics
+    hipLaunchKernelGGL(k_center_codebook<256>, dim3(c->k < cap_long ? c->k : cap_long), dim3(256), 0, c->stream, W, c->k, c->dim,
                        c->mu, wc, c->wn32, c->wmax_bits, wn64, wabs);
   }
   return hipGetLastError();

@@ -51,7 +51,7 @@ static void dev_free(T *&p) {
 }
 
 static void free_row_scratch(som_ctx *c) {
-  dev_free(c->xn32); dev_free(c->cand_val); dev_free(c->cand_idx); dev_free(c->cand_over);
+  dev_free(c->xn32); dev_free(c->row_q); dev_free(c->cand_val); dev_free(c->cand_idx); dev_free(c->cand_over);
   dev_free(c->cand_n); dev_free(c->refine_list); dev_free(c->rescan_list);
   dev_free(c->collect_rows); dev_free(c->collect_thr); dev_free(c->collect_cnt); dev_free(c->collect_list);
   dev_free(c->sort_key[0]); dev_free(c->sort_key[1]); dev_free(c->sort_val[0]); dev_free(c->sort_val[1]);
@@ -74,7 +74,7 @@ static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
     free_row_scratch(c);
     const size_t N = (size_t)n;
     const size_t nblk = (N + kSortTile - 1) / kSortTile;
-    bool ok = dev_alloc(&c->xn32, N) && dev_alloc(&c->cand_val, N * kCand) && dev_alloc(&c->cand_idx, N * kCand) &&
+    bool ok = dev_alloc(&c->xn32, N) && dev_alloc(&c->row_q, N) && dev_alloc(&c->cand_val, N * kCand) && dev_alloc(&c->cand_idx, N * kCand) &&
               dev_alloc(&c->cand_over, N) && dev_alloc(&c->cand_n, N) && dev_alloc(&c->refine_list, N) &&
               dev_alloc(&c->rescan_list, N) && dev_alloc(&c->collect_rows, N) && dev_alloc(&c->collect_thr, N) &&
               dev_alloc(&c->collect_cnt, N) && dev_alloc(&c->sort_key[0], N) && dev_alloc(&c->sort_key[1], N) &&
@@ -115,9 +115,9 @@ static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
 }
 
 // The dense fp32 pass writes one candidate list per node group and instance.
-static int ensure_candidates(som_ctx *c, int64_t n) {
-  const int groups_h = c->filter == SOM_FILTER_SPLIT_F16 ? bmu_dense_h_groups(c, n) : 1;
-  const int groups_f = bmu_dense_groups(c, n);
+static int ensure_candidates(som_ctx *c, int64_t n, bool dense) {
+  const int groups_h = dense && c->filter == SOM_FILTER_SPLIT_F16 ? bmu_dense_h_groups(c, n) : 1;
+  const int groups_f = dense ? bmu_dense_groups(c, n) : 8;      // sparse: one list per node slice
   const int64_t need = (int64_t)(groups_h > groups_f ? groups_h : groups_f) * n;
   if (need <= c->cand_cap) return SOM_OK;
   (void)hipStreamSynchronize(c->stream);
@@ -132,9 +132,14 @@ static int ensure_candidates(som_ctx *c, int64_t n) {
 
 static int ensure_transposed(som_ctx *c) {
   if (c->Wt) return SOM_OK;
-  if (!dev_alloc(&c->Wt, (size_t)c->dim * c->kpad))
+  // int16 entries for the sliced kernel, fp32 otherwise
+  const size_t words = bmu_csr_sliced_ok(c) ? ((size_t)c->dim * c->kpad + 1) / 2 : (size_t)c->dim * c->kpad;
+  if (!(dev_alloc(&c->Wt, words) && dev_alloc(&c->col_range, (size_t)2 * 64 * c->dim) &&
+        dev_alloc(&c->qstep, (size_t)c->dim) && dev_alloc(&c->qstep_max_bits, 1))) {
+    dev_free(c->Wt); dev_free(c->col_range); dev_free(c->qstep); dev_free(c->qstep_max_bits);
     return fail(c, SOM_ERR_ALLOC, "cannot allocate the transposed code book (%d x %d)", c->dim, c->kpad);
-  SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->Wt, (int64_t)c->dim * c->kpad));
+  }
+  SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->Wt, (int64_t)words));
   return SOM_OK;
 }
 
@@ -197,7 +202,7 @@ static int prepare_dense(som_ctx *c, const float *X, int64_t n, const float *W, 
 }
 
 static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *W, int32_t *bmus, bool have_xn) {
-  int rc = ensure_candidates(c, n);
+  int rc = ensure_candidates(c, n, true);
   if (!rc) rc = prepare_dense(c, X, n, W, have_xn);
   if (rc) return rc;
   const bool split = c->filter == SOM_FILTER_SPLIT_F16;
@@ -207,7 +212,8 @@ static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *
     else SOM_LAUNCH(c, launch_bmu_dense(c, X, n));
   }
   StageTimer t(c, 2);
-  SOM_LAUNCH(c, launch_certify(c, n, split ? bmu_dense_h_groups(c, n) : bmu_dense_groups(c, n), split, bmus));
+  SOM_LAUNCH(c, launch_certify(c, n, split ? bmu_dense_h_groups(c, n) : bmu_dense_groups(c, n),
+                               split ? kCertifySplit : kCertifyFp32, nullptr, bmus));
   SOM_LAUNCH(c, launch_refine_dense(c, X, W, bmus));
   if (split) SOM_LAUNCH(c, launch_bmu_dense_h_collect(c, n));
   else SOM_LAUNCH(c, launch_bmu_dense_collect(c, X, n));
@@ -219,6 +225,8 @@ static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *
 static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
                           int64_t n, const float *W, int32_t *bmus, bool have_xn) {
   int rc = ensure_transposed(c);
+  const bool sliced = bmu_csr_sliced_ok(c);
+  if (!rc && sliced) rc = ensure_candidates(c, n, false);
   if (rc) return rc;
   if (!have_xn) {
     c->d_norms_valid = 0;
@@ -227,17 +235,21 @@ static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indi
   // centring vector of the sparse search: the mean of the code-book rows (changes every epoch);
   // it overwrites the one a registered dense training set may have cached
   if (c->data_kind == 1) c->d_norms_valid = 0;
-  SOM_LAUNCH(c, launch_sample_col_means(c, W, c->k, c->dim, c->mu));
+  if (sliced) SOM_LAUNCH(c, launch_codebook_means_and_steps(c, W));      // all k <= 8192 rows: exact column ranges
+  else SOM_LAUNCH(c, launch_sample_col_means(c, W, c->k, c->dim, c->mu));
   SOM_LAUNCH(c, launch_vec_sqnorm(c, c->mu, c->dim, c->mu_norm2));
   SOM_LAUNCH(c, launch_center_codebook(c, W, false, true));
   SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 3));
   {
     StageTimer t(c, 1);
     SOM_LAUNCH(c, launch_transpose_codebook(c, W));
-    SOM_LAUNCH(c, launch_bmu_csr(c, indptr, indices, values, n, bmus));
+    if (sliced) SOM_LAUNCH(c, launch_bmu_csr_sliced(c, indptr, indices, values, n, false));
+    else SOM_LAUNCH(c, launch_bmu_csr(c, indptr, indices, values, n, bmus));
   }
   StageTimer t(c, 2);
+  if (sliced) SOM_LAUNCH(c, launch_certify(c, n, 8, kCertifyCsr, indptr, bmus));
   SOM_LAUNCH(c, launch_refine_csr(c, indptr, indices, values, W, bmus));
+  if (sliced) SOM_LAUNCH(c, launch_bmu_csr_sliced(c, indptr, indices, values, n, true));
   SOM_LAUNCH(c, launch_refine_lists_csr(c, indptr, indices, values, W, bmus));
   SOM_LAUNCH(c, launch_rescan_csr(c, indptr, indices, values, W, bmus));
   return SOM_OK;
@@ -311,7 +323,7 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
   c->rows = rows; c->cols = cols; c->dim = dim; c->k = rows * cols;
   c->map_type = map_type; c->grid_type = grid_type;
   c->stream = (hipStream_t)hip_stream;
-  c->kpad = ((c->k + 255) / 256) * 256;
+  c->kpad = ((c->k + 511) / 512) * 512;
   c->filter = SOM_FILTER_SPLIT_F16;
 
   int dev = 0;
@@ -367,6 +379,7 @@ void som_destroy(som_ctx *c) {
   dev_free(c->wn32); dev_free(c->wn64); dev_free(c->wmax_bits); dev_free(c->counts); dev_free(c->seg_off);
   dev_free(c->chunk_off); dev_free(c->massD); dev_free(c->cntT); dev_free(c->gx); dev_free(c->gy);
   dev_free(c->params); dev_free(c->list_counts); dev_free(c->S); dev_free(c->T); dev_free(c->Wt);
+  dev_free(c->col_range); dev_free(c->qstep); dev_free(c->qstep_max_bits);
   dev_free(c->GxT); dev_free(c->GyT); dev_free(c->hit_x); dev_free(c->hit_n); dev_free(c->hit_rows);
   dev_free(c->mu); dev_free(c->mu_partial); dev_free(c->Wc); dev_free(c->zero16); dev_free(c->mu_norm2);
   dev_free(c->Wh); dev_free(c->wscale);
@@ -557,7 +570,7 @@ int som_debug_scores_dense(som_ctx *c, const float *data, int64_t n, const float
   if (c->filter != SOM_FILTER_SPLIT_F16) return fail(c, SOM_ERR_STATE, "only the split-fp16 filter can dump its scores");
   int rc = check_rows(c, n);
   if (!rc) rc = ensure_rows(c, n, true);
-  if (!rc) rc = ensure_candidates(c, n);
+  if (!rc) rc = ensure_candidates(c, n, true);
   if (!rc) rc = prepare_dense(c, data, n, codebook, false);
   if (rc) return rc;
   SOM_LAUNCH(c, launch_bmu_dense_h(c, n, scores));

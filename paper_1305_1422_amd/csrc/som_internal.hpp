@@ -65,8 +65,12 @@ struct som_ctx {
   som::EpochParams *params;   // [1]
   float *S;               // [k][dim] per-node sums
   float *T;               // [1 or 2][k][dim] sums after the pass along x
-  float *Wt;              // [dim][kpad] transposed code book (sparse BMU only, lazily allocated)
+  float *Wt;              // [dim][kpad] centred transposed code book (sparse BMU only, lazily allocated): fp32, or
+                          // int16 multiples of the column steps when the sliced kernel is used
   int kpad;
+  float *col_range;       // [2][64][dim] slab minima and maxima of the code-book columns (with Wt)
+  float *qstep;           // [dim] quantisation step of every column of Wt (with Wt)
+  unsigned *qstep_max_bits;   // [1] bit pattern of the largest step
   float *Wc;              // [k][dim] centred code book w' = fl(w - mu) of the dense BMU search (lazily allocated)
   _Float16 *Wh;           // [k][ceil(dim/32)][64] centred code book as fp16 hi/lo planes (lazily allocated)
   float *wscale;          // [1] the power of two the centred code book was divided by
@@ -79,6 +83,7 @@ struct som_ctx {
   // per-data scratch (grown on demand to n_cap rows)
   int64_t n_cap;
   float *xn32;            // [n] squared norms of the instances
+  float *row_q;           // [n] sparse rows: sum over the nonzeros of |value| x quantisation step of the column
   _Float16 *Xh;           // [n][ceil(dim/32)][64] dense instances as fp16 hi/lo planes (lazily allocated)
   float *xscale;          // [n] the power of two each instance was divided by
   int64_t cand_cap;       // instance slots in the three candidate arrays (node groups x instances)
@@ -124,6 +129,7 @@ namespace som {
 
 // norms.hip
 hipError_t launch_sample_col_means(som_ctx *c, const float *A, int64_t nrows, int dim, float *mu);
+hipError_t launch_codebook_means_and_steps(som_ctx *c, const float *W);      // -> mu, qstep, qstep_max_bits
 hipError_t launch_vec_sqnorm(som_ctx *c, const float *v, int dim, float *out);
 hipError_t launch_center_codebook(som_ctx *c, const float *W, bool store_centered, bool want_wn64);   // -> Wc, wn32 (= c_i), wmax_bits, wn64
 hipError_t launch_row_sqnorms(som_ctx *c, const float *A, int64_t nrows, int dim, const float *mu,
@@ -147,7 +153,8 @@ hipError_t launch_probe_mfma_f16(hipStream_t stream, const uint16_t *A, const ui
                                  int count);
 
 // bmu_exact.hip
-hipError_t launch_certify(som_ctx *c, int64_t n, int groups, bool split_filter, int32_t *bmus);
+enum { kCertifyFp32 = 0, kCertifySplit = 1, kCertifyCsr = 2 };      // whose rounding bound the margin uses
+hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int64_t *indptr, int32_t *bmus);
 hipError_t launch_refine_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
 hipError_t launch_refine_lists_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
 hipError_t launch_rescan_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
@@ -162,6 +169,9 @@ hipError_t launch_rescan_csr(som_ctx *c, const int64_t *indptr, const int32_t *i
 hipError_t launch_transpose_codebook(som_ctx *c, const float *W);
 hipError_t launch_bmu_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices,
                           const float *values, int64_t n, int32_t *bmus);
+bool bmu_csr_sliced_ok(const som_ctx *c);          // map small enough for the one-slice-per-XCD kernel
+hipError_t launch_bmu_csr_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
+                                 int64_t n, bool collect);
 
 // segsum.hip
 hipError_t launch_sort_by_bmu(som_ctx *c, const int32_t *bmus, int64_t n);   // -> sort_val[0] = row ids
