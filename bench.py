@@ -28,8 +28,8 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side bytes per launch of the dominant kernel (fetched + written), from the two rocprofv3 --pmc
 # runs (FETCH_SIZE, WRITE_SIZE, scaled by the copy calibration) summarised under profiles/;
 # measured once per kernel version, not during this run.  Workloads without a counter run: None.
-MEASURED_TRAFFIC_BYTES = {(2, "split_f16"): 8.980e9 + 0.025e9, (2, "fp32"): 8.49e9 + 0.025e9,
-                          (4, "split_f16"): 63.35e9 + 0.005e9, (4, "fp32"): 63.35e9 + 0.005e9}
+MEASURED_TRAFFIC_BYTES = {(2, "split_f16"): 8.997e9 + 0.025e9, (2, "fp32"): 8.49e9 + 0.025e9,
+                          (4, "split_f16"): 14.327e9 + 0.092e9, (4, "fp32"): 14.327e9 + 0.092e9}
 
 
 def cpu_baseline(w, X, W0, seconds_budget: float = 20.0):
@@ -158,7 +158,7 @@ def main() -> int:
         # compulsory bytes: CSR once (8 B per nonzero + 8 B per row), code book once, BMUs out
         alg_bytes = nnz * 8.0 + (w.n + 1) * 8.0 + w.k * w.dim * 4.0 + w.n * 4.0
         achieved = alg_bytes / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
-        roofline = {"bound": "hbm", "kernel": "k_transpose + k_bmu_csr (sparse fp32 BMU pass)",
+        roofline = {"bound": "hbm", "kernel": "k_transpose_centered_q16 + k_bmu_csr_sliced (sparse BMU filter pass)",
                     "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.config, args.filter)), "avg_launch_ms": dom_ms,
                     "traffic_rate_gbs": (MEASURED_TRAFFIC_BYTES[(w.config, args.filter)] / (dom_ms * 1e-3) / 1e9
