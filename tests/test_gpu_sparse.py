@@ -35,10 +35,13 @@ def test_scaled_config4(oracle, n, dim, rows, cols, epochs, mean_len):
     som.close()
 
 
-def test_many_nodes_take_several_sweeps(oracle):
-    """More nodes than one sweep covers (16 x 256): scores are recomputed per sweep."""
+@pytest.mark.parametrize("rows,cols", [(70, 64), (64, 128), (100, 100)])
+def test_many_nodes(oracle, rows, cols):
+    """4,480 and 8,192 nodes: nine and sixteen scores per lane in the kernel that gives every XCD a
+    node slice; 10,000 nodes: past its limit, the kernel with a workgroup per instance and several
+    sweeps over the nodes takes over."""
     from paper_1305_1422_amd import Som
-    rows, cols, dim, n = 70, 64, 300, 150               # 4480 nodes
+    dim, n = 300, 150
     csr = sparse_zipf_csr(n, dim, 21, mean_len=12.0, max_len=40)
     W = np.random.default_rng(22).random((rows * cols, dim)).astype(np.float32)
     som = Som(rows, cols, dim, "toroid", "hexagonal", codebook=torch.from_numpy(W))
