@@ -13,7 +13,7 @@ namespace som {
 // ---------------------------------------------------------------- constants
 constexpr int kWave = 64;                 // CDNA wavefront width
 constexpr int kCand = 4;                  // candidate nodes kept per instance by the fp32 pass
-constexpr int kListCap = 64;              // nodes a collected candidate list can hold per instance
+constexpr int kListCap = 256;             // nodes a collected candidate list can hold per instance
 constexpr int kChunkRows = 32;            // instances summed by one block of the segmented accumulation
 constexpr int kSortTile = 1024;           // fewest keys ranked by one wave of the radix scatter
 constexpr int kSmoothMatMax = 1024;        // largest map side for which the smoothing filters are stored as matrices

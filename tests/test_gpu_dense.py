@@ -94,14 +94,30 @@ def test_identical_codebook_rows_force_full_rescan(oracle):
     """All nodes equal: every score ties, every instance takes the exact rescan, answer node 0."""
     from paper_1305_1422_amd import Som
     rng = np.random.default_rng(8)
-    rows, cols, dim, n = 10, 14, 20, 300
+    rows, cols, dim, n = 20, 14, 20, 300
     W = np.tile(rng.random((1, dim)).astype(np.float32), (rows * cols, 1))
     X = rng.random((n, dim)).astype(np.float32)
     som = Som(rows, cols, dim, codebook=torch.from_numpy(W))
     b = som.bmus(P.to_dev(X)).cpu().numpy()
     assert np.all(b == 0)
     refined, collected, rescanned = som.stats()
-    assert rescanned == n and collected == n and refined == 0       # 140 equal nodes overflow the lists
+    assert rescanned == n and collected == n and refined == 0       # 280 equal nodes overflow the lists of 256
+    som.close()
+
+
+def test_many_identical_codebook_rows_fit_the_collected_lists(oracle):
+    """140 equal nodes among others: every instance's list holds them all, lowest index wins."""
+    from paper_1305_1422_amd import Som
+    rng = np.random.default_rng(9)
+    rows, cols, dim, n = 10, 20, 24, 300
+    W = rng.random((rows * cols, dim)).astype(np.float32) + 3.0      # far from the data
+    W[37:177] = rng.random((1, dim)).astype(np.float32)              # 140 copies of one near vector
+    X = rng.random((n, dim)).astype(np.float32)
+    som = Som(rows, cols, dim, codebook=torch.from_numpy(W))
+    b = som.bmus(P.to_dev(X)).cpu().numpy()
+    assert np.all(b == 37)
+    refined, collected, rescanned = som.stats()
+    assert collected == n and rescanned == 0 and refined == 0
     som.close()
 
 
