@@ -2,6 +2,10 @@
 
 ``python -m paper_1305_1422_amd.build`` or ``build(force=True)``.  hipcc cross-compiles
 without a GPU.  Packed-fp32 instruction selection is switched off for every kernel.
+
+Environment hooks for timing experiments with variant builds: ``SOM_EXTRA_FLAGS`` (extra hipcc
+flags), ``SOM_LIB_OUT`` / ``SOM_OBJ_DIR`` (where the variant library and its objects go), ``HIPCC``.
+The binding loads ``SOM_LIB_PATH`` instead of the in-tree library when that variable is set.
 """
 from __future__ import annotations
 
