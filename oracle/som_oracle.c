@@ -47,6 +47,7 @@
 enum { ORACLE_PLANAR = 0, ORACLE_TOROID = 1 };
 enum { ORACLE_SQUARE = 0, ORACLE_HEXAGONAL = 1 };
 enum { ORACLE_LINEAR = 0, ORACLE_EXPONENTIAL = 1 };
+enum { ORACLE_GAUSSIAN = 0, ORACLE_BUBBLE = 1 };
 
 int oracle_num_threads(void)
 {
@@ -89,6 +90,22 @@ double oracle_neighbourhood(int rows, int cols, int map_type, int grid_type,
                             int i, int b, double radius)
 {
     double q = (double)oracle_grid_q(rows, cols, map_type, grid_type, i, b);
+    return exp(-q / (8.0 * radius * radius));
+}
+
+/*
+ * The other neighbourhoods of the command line (options -n and -p): function 0 = Gaussian,
+ * 1 = bubble (weight 1 inside the current radius, 0 outside); compact != 0 cuts the Gaussian
+ * off beyond the current radius (the bubble has compact support by definition).  "Inside the
+ * radius" means grid distance d <= r, that is q = 4 d^2 <= 4 r^2, compared in double.
+ */
+double oracle_neighbourhood_kind(int rows, int cols, int map_type, int grid_type,
+                                 int i, int b, double radius, int function, int compact)
+{
+    double q = (double)oracle_grid_q(rows, cols, map_type, grid_type, i, b);
+    int inside = q <= 4.0 * radius * radius;
+    if (function == ORACLE_BUBBLE) return inside ? 1.0 : 0.0;
+    if (compact && !inside) return 0.0;
     return exp(-q / (8.0 * radius * radius));
 }
 
@@ -222,14 +239,15 @@ void oracle_accumulate_csr(const int64_t *indptr, const int32_t *indices, const 
  */
 static double update_node(int i, const double *S, const double *C, float *w, int rows, int cols,
                           int dim, int map_type, int grid_type, double radius, double scale,
-                          double eps_mass, double *num)
+                          double eps_mass, double *num, int function, int compact)
 {
     int k = rows * cols;
     double den = 0.0, mass = 0.0;
     for (int c = 0; c < dim; ++c) num[c] = 0.0;
     for (int b = 0; b < k; ++b) {
         if (C[b] == 0.0) continue;          /* contributes exact zeros */
-        double h = oracle_neighbourhood(rows, cols, map_type, grid_type, i, b, radius);
+        double h = oracle_neighbourhood_kind(rows, cols, map_type, grid_type, i, b, radius, function,
+                                             compact);
         const double *s = S + (int64_t)b * dim;
         mass += h * C[b];
         den += scale * h * C[b];
@@ -244,9 +262,9 @@ static double update_node(int i, const double *S, const double *C, float *w, int
  * New code book for all nodes.  D_out (may be NULL) receives the masses.  W is read and
  * written in place: node i's new vector depends on S and C only.
  */
-void oracle_update(const double *S, const double *C, float *W, int rows, int cols, int dim,
-                   int map_type, int grid_type, double radius, double scale,
-                   double eps_mass, double *D_out)
+void oracle_update_kind(const double *S, const double *C, float *W, int rows, int cols, int dim,
+                        int map_type, int grid_type, double radius, double scale,
+                        double eps_mass, double *D_out, int function, int compact)
 {
     int k = rows * cols;
 #pragma omp parallel
@@ -255,11 +273,19 @@ void oracle_update(const double *S, const double *C, float *W, int rows, int col
 #pragma omp for schedule(dynamic, 4)
         for (int i = 0; i < k; ++i) {
             double mass = update_node(i, S, C, W + (int64_t)i * dim, rows, cols, dim, map_type,
-                                      grid_type, radius, scale, eps_mass, num);
+                                      grid_type, radius, scale, eps_mass, num, function, compact);
             if (D_out) D_out[i] = mass;
         }
         free(num);
     }
+}
+
+void oracle_update(const double *S, const double *C, float *W, int rows, int cols, int dim,
+                   int map_type, int grid_type, double radius, double scale,
+                   double eps_mass, double *D_out)
+{
+    oracle_update_kind(S, C, W, rows, cols, dim, map_type, grid_type, radius, scale, eps_mass, D_out,
+                       ORACLE_GAUSSIAN, 0);
 }
 
 /*
@@ -281,7 +307,7 @@ void oracle_update_nodes(const double *S, const double *C, const float *W, int r
             int i = nodes[t];
             memcpy(row, W + (int64_t)i * dim, sizeof(float) * (size_t)dim);
             double mass = update_node(i, S, C, row, rows, cols, dim, map_type, grid_type, radius,
-                                      scale, eps_mass, num);
+                                      scale, eps_mass, num, ORACLE_GAUSSIAN, 0);
             memcpy(W_out + (int64_t)t * dim, row, sizeof(float) * (size_t)dim);
             if (D_out) D_out[t] = mass;
         }

@@ -16,6 +16,7 @@ from . import build as _build
 PLANAR, TOROID = 0, 1
 SQUARE, HEXAGONAL = 0, 1
 LINEAR, EXPONENTIAL = 0, 1
+GAUSSIAN, BUBBLE = 0, 1
 EPS_MASS = 1e-20          # neighbourhood mass below which a node keeps its weights
 
 MAP_TYPES = {"planar": PLANAR, "toroid": TOROID}
@@ -48,9 +49,14 @@ def lib():
         L.oracle_accumulate_dense.argtypes = [f32p, C.c_int64, C.c_int, i32p, C.c_int, f64p, f64p]
         L.oracle_accumulate_csr.restype = None
         L.oracle_accumulate_csr.argtypes = [i64p, i32p, f32p, C.c_int64, C.c_int, i32p, C.c_int, f64p, f64p]
+        L.oracle_neighbourhood_kind.restype = C.c_double
+        L.oracle_neighbourhood_kind.argtypes = [C.c_int] * 6 + [C.c_double, C.c_int, C.c_int]
         L.oracle_update.restype = None
         L.oracle_update.argtypes = [f64p, f64p, f32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                     C.c_double, C.c_double, C.c_double, f64p]
+        L.oracle_update_kind.restype = None
+        L.oracle_update_kind.argtypes = [f64p, f64p, f32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                         C.c_double, C.c_double, C.c_double, f64p, C.c_int, C.c_int]
         L.oracle_update_nodes.restype = None
         L.oracle_update_nodes.argtypes = [f64p, f64p, f32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                           C.c_double, C.c_double, C.c_double, i32p, C.c_int, f32p, f64p]
@@ -164,8 +170,15 @@ def accumulate_csr(csr, dim: int, bmu, k: int):
     return S, Cn
 
 
+def neighbourhood_kind(rows, cols, map_type, grid_type, i, b, radius, function=0, compact=False) -> float:
+    """Neighbourhood weight for the Gaussian (function 0) or bubble (1) function, optionally with
+    compact support (options -n and -p)."""
+    return float(lib().oracle_neighbourhood_kind(rows, cols, map_type, grid_type, i, b, float(radius),
+                                                 int(function), int(bool(compact))))
+
+
 def update(S, Cn, W, rows: int, cols: int, map_type: int, grid_type: int, radius: float,
-           scale: float = 1.0, eps_mass: float = EPS_MASS):
+           scale: float = 1.0, eps_mass: float = EPS_MASS, function: int = 0, compact: bool = False):
     """Returns (new code book float32 [k, dim], neighbourhood mass D float64 [k])."""
     S = np.ascontiguousarray(S, dtype=np.float64)
     Cn = np.ascontiguousarray(Cn, dtype=np.float64)
@@ -173,9 +186,9 @@ def update(S, Cn, W, rows: int, cols: int, map_type: int, grid_type: int, radius
     k, dim = Wn.shape
     assert k == rows * cols and S.shape == (k, dim) and Cn.shape == (k,)
     D = np.empty(k, dtype=np.float64)
-    lib().oracle_update(_p(S, C.c_double), _p(Cn, C.c_double), _p(Wn, C.c_float), rows, cols, dim,
-                        map_type, grid_type, float(radius), float(scale), float(eps_mass),
-                        _p(D, C.c_double))
+    lib().oracle_update_kind(_p(S, C.c_double), _p(Cn, C.c_double), _p(Wn, C.c_float), rows, cols, dim,
+                             map_type, grid_type, float(radius), float(scale), float(eps_mass),
+                             _p(D, C.c_double), int(function), int(bool(compact)))
     return Wn, D
 
 
