@@ -63,6 +63,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--filter", choices=["split_f16", "fp32"], default="split_f16",
                     help="arithmetic of the dense BMU filter pass (same BMUs either way)")
+    ap.add_argument("--neighborhood", choices=["gaussian", "gaussian-compact", "bubble"], default="gaussian",
+                    help="neighbourhood of the update (the stated configurations use the plain Gaussian)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run ten plain 1 GiB device copies and exit: under rocprofv3 --pmc this gives the "
                          "reading of FETCH_SIZE / WRITE_SIZE for a kernel of known traffic")
@@ -101,6 +103,8 @@ def main() -> int:
         Xd = tuple(torch.from_numpy(a).to(dev) for a in X)
     W0d = torch.from_numpy(W0).to(dev)
     som = Som(w.rows, w.cols, w.dim, w.map_type, w.grid_type, codebook=W0d, filter=args.filter)
+    if args.neighborhood != "gaussian":
+        som.set_neighborhood("bubble" if args.neighborhood == "bubble" else "gaussian", args.neighborhood != "bubble")
     bmus = torch.empty(w.n, dtype=torch.int32, device=dev)
     # register the resident training set: its norms are then computed once, not every epoch
     if w.kind == "dense":
@@ -174,7 +178,7 @@ def main() -> int:
         "config": {"workload": f"config {w.config}: {w.name}", "kind": w.kind, "n": w.n, "dim": w.dim,
                    "map": f"{w.rows}x{w.cols} {w.map_type} {w.grid_type}",
                    "schedule": f"radius {w.radius0:g}->{w.radiusN:g} linear over {w.epochs} epochs, step s = epoch s mod {w.epochs}",
-                   "step": "som_train_epoch: BMU search + batch update"},
+                   "step": "som_train_epoch: BMU search + batch update", "neighborhood": args.neighborhood},
         "gflops_epoch": 2.0 * work / (dt / args.steps) / 1e9,
         "frac_fp32_mfma_peak_whole_epoch": 2.0 * work / (dt / args.steps) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
         "stage_ms": stage_ms,

@@ -40,6 +40,7 @@ enum { SOM_MAP_PLANAR = 0, SOM_MAP_TOROID = 1 };          /* option -m: planar (
 enum { SOM_GRID_SQUARE = 0, SOM_GRID_HEXAGONAL = 1 };     /* option -g: square (default) or hexagonal */
 enum { SOM_COOL_LINEAR = 0, SOM_COOL_EXPONENTIAL = 1 };   /* options -t / -T                          */
 enum { SOM_FILTER_FP32 = 0, SOM_FILTER_SPLIT_F16 = 1 };   /* see som_set_filter                       */
+enum { SOM_NEIGHBORHOOD_GAUSSIAN = 0, SOM_NEIGHBORHOOD_BUBBLE = 1 };   /* option -n               */
 
 /* Neighbourhood mass below which a node keeps its weights (see som_train_epoch_dense). */
 #define SOM_EPS_MASS 1e-20
@@ -174,6 +175,19 @@ int som_cool_schedule(som_ctx *ctx, int n_epochs, float radius0, float radiusN, 
  *   umatrix   device [rows][cols] fp32 out.
  */
 int som_umatrix(som_ctx *ctx, const float *codebook, float *umatrix);
+
+/*
+ * som_set_neighborhood - neighbourhood function of the batch update (options -n and -p; the
+ * paper's trainOneEpoch carries them as `gaussian` and `compact_support`).
+ *   function         SOM_NEIGHBORHOOD_GAUSSIAN (default): exp(-d^2 / (2 r^2)) of the grid distance
+ *                    d and the epoch's radius r; SOM_NEIGHBORHOOD_BUBBLE: 1 for d <= r, else 0.
+ *   compact_support  non-zero: the Gaussian is cut off to 0 beyond d > r (the bubble always is).
+ * The default (Gaussian, no cut-off) factorises over the two grid directions and is applied in
+ * two passes; the others use a one-pass kernel over a table of weights.  Takes effect from the
+ * next update on.  Errors: unknown function -> SOM_ERR_INVALID_ARG; table allocation ->
+ * SOM_ERR_ALLOC.
+ */
+int som_set_neighborhood(som_ctx *ctx, int function, int compact_support);
 
 /*
  * som_set_filter - choose the arithmetic of the dense BMU filter pass (paper, "Parallelism":

@@ -19,6 +19,7 @@ SOM_MAP_PLANAR, SOM_MAP_TOROID = 0, 1
 SOM_GRID_SQUARE, SOM_GRID_HEXAGONAL = 0, 1
 SOM_COOL_LINEAR, SOM_COOL_EXPONENTIAL = 0, 1
 SOM_FILTER_FP32, SOM_FILTER_SPLIT_F16 = 0, 1
+SOM_NEIGHBORHOOD_GAUSSIAN, SOM_NEIGHBORHOOD_BUBBLE = 0, 1
 
 EXPORTS = [
     "som_init", "som_destroy", "som_last_error",
@@ -28,7 +29,7 @@ EXPORTS = [
     "som_set_data_dense", "som_set_data_csr", "som_train",
     "som_cool_schedule", "som_umatrix", "som_get_stats",
     "som_profile_enable", "som_profile_read",
-    "som_set_filter", "som_debug_scores_dense", "som_debug_mfma_f16",
+    "som_set_filter", "som_set_neighborhood", "som_debug_scores_dense", "som_debug_mfma_f16",
 ]
 PROFILE_STAGES = ("bmu_dense_filter", "bmu_csr_filter", "bmu_exact", "node_sums", "smooth_divide", "prepare_dense")
 
@@ -87,6 +88,8 @@ def load():
     L.som_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
     L.som_set_filter.restype = i32
     L.som_set_filter.argtypes = [vp, i32]
+    L.som_set_neighborhood.restype = i32
+    L.som_set_neighborhood.argtypes = [vp, i32, i32]
     L.som_debug_scores_dense.restype = i32
     L.som_debug_scores_dense.argtypes = [vp, vp, i64, vp, vp, vp]
     L.som_debug_mfma_f16.restype = i32
@@ -240,6 +243,10 @@ def som_profile_read(ctx):
     cnt = (C.c_int64 * len(PROFILE_STAGES))()
     _check(ctx, load().som_profile_read(ctx, ms, cnt))
     return {name: (float(ms[i]), int(cnt[i])) for i, name in enumerate(PROFILE_STAGES)}
+
+
+def som_set_neighborhood(ctx, function: int, compact_support: bool) -> None:
+    _check(ctx, load().som_set_neighborhood(ctx, function, 1 if compact_support else 0))
 
 
 def som_set_filter(ctx, filter: int) -> None:

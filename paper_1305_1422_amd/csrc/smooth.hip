@@ -376,7 +376,178 @@ __global__ __launch_bounds__(256) void k_smooth_y_mat(const float *__restrict__ 
   }
 }
 
+// ---------------------------------------------------------------- neighbourhoods with compact support
+// The bubble function and the Gaussian cut off at the current radius (options -n and -p of the
+// paper's command line) are not products of a factor in x and a factor in y, so the two-pass
+// scheme above does not apply.  Their weights still depend only on the row distance a, the
+// column offset and (hexagonal grids) the parities of the two rows, so they are tabulated once
+// per epoch,
+//   H2[class][a][t],  class = parity(yi) - parity(yb) + 1 (square grids: 0),
+//   t = xi - xb + cols - 1 (planar)  or  (xi - xb) mod cols, continued cyclically past cols (toroid),
+// so that the 16 weights of 16 neighbouring destination columns and one source node are
+// contiguous: the same "lane owns a feature column, 16 outputs in registers, coefficients through
+// scalar loads" kernel as k_smooth_x_mat, now in one pass over all chosen source nodes whose row is
+// within reach, with the division at the end.  The count channel is summed in fp64 from the same table.
+__device__ __forceinline__ int direct_table_width(int cols, int toroid) {
+  return (toroid ? cols : 2 * cols - 1) + kSmoothTile;
+}
+
+__global__ __launch_bounds__(256) void k_direct_table(const EpochParams *__restrict__ params, int rows, int cols,
+                                                      int hex, int toroid, int function, int compact,
+                                                      float *__restrict__ H2) {
+  const int width = direct_table_width(cols, toroid);
+  const int classes = hex ? 3 : 1;
+  const double r = params->radius;
+  const double reach = 4.0 * r * r;               // q = 4 d^2 <= 4 r^2: inside the radius
+  const double inv = params->inv8r2;
+  const int64_t total = (int64_t)classes * rows * width;
+  for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < total; o += (int64_t)gridDim.x * blockDim.x) {
+    const int t = (int)(o % width);
+    const int a_raw = (int)((o / width) % rows);
+    const int cls = (int)(o / ((int64_t)width * rows));
+    const int dpar = hex ? cls - 1 : 0;
+    const int dx = toroid ? t % cols : t - (cols - 1);
+    long long m = 2ll * dx + dpar;
+    m = m < 0 ? -m : m;
+    long long a = a_raw;
+    if (toroid) {
+      if (2ll * cols - m < m) m = 2ll * cols - m;
+      if (rows - a < a) a = rows - a;
+    }
+    const double q = (double)(m * m + (hex ? 3 : 4) * a * a);
+    const bool inside = q <= reach;
+    float h;
+    if (function == SOM_NEIGHBORHOOD_BUBBLE) h = inside ? 1.f : 0.f;
+    else h = (compact && !inside) ? 0.f : (float)exp(-q * inv);
+    H2[o] = h;
+  }
+}
+
+__device__ __forceinline__ int direct_table_index(int xi, int xb, int cols, int toroid) {
+  if (!toroid) return xi - xb + cols - 1;
+  int d = xi - xb;
+  return d < 0 ? d + cols : d;
+}
+
+__global__ __launch_bounds__(256) void k_count_direct(const int32_t *__restrict__ counts,
+                                                      const int32_t *__restrict__ hit_x,
+                                                      const int32_t *__restrict__ hit_n,
+                                                      const int32_t *__restrict__ hit_rows,
+                                                      const float *__restrict__ H2, int rows, int cols, int hex,
+                                                      int toroid, double *__restrict__ massD) {
+  const int k = rows * cols;
+  const int width = direct_table_width(cols, toroid);
+  const int nr = hit_rows[rows];
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < k; i += gridDim.x * blockDim.x) {
+    const int yi = i / cols, xi = i - yi * cols;
+    double s = 0.0;
+    for (int r = 0; r < nr; ++r) {
+      const int yb = hit_rows[r];
+      const int a = yi > yb ? yi - yb : yb - yi;
+      const int cls = hex ? (yi & 1) - (yb & 1) + 1 : 0;
+      const float *row = H2 + ((int64_t)cls * rows + a) * width;
+      const int32_t *hx = hit_x + (int64_t)yb * cols;
+      const int nh = hit_n[yb];
+      for (int t = 0; t < nh; ++t) {
+        const int xb = hx[t];
+        s += (double)row[direct_table_index(xi, xb, cols, toroid)] * (double)counts[yb * cols + xb];
+      }
+    }
+    massD[i] = s;
+  }
+}
+
+// grid = (ceil(dim/256), rows, ceil(cols/16)).  Source rows whose distance alone puts them out of
+// reach are skipped whole (the table holds zeros there anyway).
+template <bool kHex>
+__global__ __launch_bounds__(256) void k_smooth_direct(const float *__restrict__ S, float *__restrict__ W,
+                                                       const float *__restrict__ H2,
+                                                       const int32_t *__restrict__ hit_x,
+                                                       const int32_t *__restrict__ hit_n,
+                                                       const int32_t *__restrict__ hit_rows,
+                                                       const double *__restrict__ massD,
+                                                       const EpochParams *__restrict__ params, int rows, int cols,
+                                                       int dim, int toroid, int bounded) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c = blockIdx.x * 256 + wave * 64 + lane;
+  const bool live = c < dim;
+  const int yi = blockIdx.y;
+  const int xi0 = blockIdx.z * kSmoothTile;
+  const int width = direct_table_width(cols, toroid);
+  const double reach = 4.0 * params->radius * params->radius;
+  float acc[kSmoothTile];
+#pragma unroll
+  for (int e = 0; e < kSmoothTile; ++e) acc[e] = 0.f;
+  const int nr = hit_rows[rows];
+  for (int r = 0; r < nr; ++r) {
+    const int yb = hit_rows[r];
+    int a = yi > yb ? yi - yb : yb - yi;
+    const int a_wrapped = (toroid && rows - a < a) ? rows - a : a;
+    if (bounded && (double)((kHex ? 3ll : 4ll) * a_wrapped * a_wrapped) > reach) continue;
+    const int cls = kHex ? (yi & 1) - (yb & 1) + 1 : 0;
+    const float *trow = H2 + ((int64_t)cls * rows + a) * width;
+    const float *src = S + (int64_t)yb * cols * dim + (live ? c : 0);
+    const int32_t *hx = hit_x + (int64_t)yb * cols;
+    const int nh = hit_n[yb];
+    for (int t = 0; t < nh; t += kSmoothUnroll) {
+      int xb[kSmoothUnroll];
+      float s[kSmoothUnroll];
+#pragma unroll
+      for (int u = 0; u < kSmoothUnroll; ++u) {
+        xb[u] = hx[min(t + u, nh - 1)];
+        s[u] = (live && t + u < nh) ? src[(int64_t)xb[u] * dim] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < kSmoothUnroll; ++u) {
+        const float *g = trow + direct_table_index(xi0, xb[u], cols, toroid);
+#pragma unroll
+        for (int e = 0; e < kSmoothTile; ++e) acc[e] = fmaf(g[e], s[u], acc[e]);
+      }
+    }
+  }
+  if (live) {
+#pragma unroll
+    for (int e = 0; e < kSmoothTile; ++e) {
+      const int xi = xi0 + e;
+      if (xi < cols) {
+        const int64_t i = (int64_t)yi * cols + xi;
+        const double D = massD[i];
+        if (D >= SOM_EPS_MASS) W[i * dim + c] = acc[e] / (float)D;
+      }
+    }
+  }
+}
+
+static hipError_t launch_smooth_direct(som_ctx *c, float *W) {
+  const int hex = c->grid_type == SOM_GRID_HEXAGONAL;
+  const int toroid = c->map_type == SOM_MAP_TOROID;
+  const int width = (toroid ? c->cols : 2 * c->cols - 1) + kSmoothTile;
+  const int64_t entries = (int64_t)(hex ? 3 : 1) * c->rows * width;
+  int tb = (int)((entries + 255) / 256);
+  if (tb > c->n_cu * 8) tb = c->n_cu * 8;
+  hipLaunchKernelGGL(k_direct_table, dim3(tb), dim3(256), 0, c->stream, c->params, c->rows, c->cols, hex, toroid,
+                     c->nb_function, c->nb_compact, c->H2);
+  hipLaunchKernelGGL(k_hit_lists, dim3(c->rows < 1024 ? c->rows : 1024), dim3(64), 0, c->stream, c->counts, c->rows,
+                     c->cols, c->hit_x, c->hit_n);
+  hipLaunchKernelGGL(k_hit_rows, dim3(1), dim3(64), 0, c->stream, c->hit_n, c->rows, c->hit_rows);
+  int cb = (c->k + 255) / 256;
+  hipLaunchKernelGGL(k_count_direct, dim3(cb), dim3(256), 0, c->stream, c->counts, c->hit_x, c->hit_n, c->hit_rows,
+                     c->H2, c->rows, c->cols, hex, toroid, c->massD);
+  const dim3 grid((unsigned)((c->dim + 255) / 256), (unsigned)c->rows,
+                  (unsigned)((c->cols + kSmoothTile - 1) / kSmoothTile));
+  const int bounded = c->nb_function == SOM_NEIGHBORHOOD_BUBBLE || c->nb_compact;
+  if (hex)
+    hipLaunchKernelGGL(k_smooth_direct<true>, grid, dim3(256), 0, c->stream, c->S, W, c->H2, c->hit_x, c->hit_n,
+                       c->hit_rows, c->massD, c->params, c->rows, c->cols, c->dim, toroid, bounded);
+  else
+    hipLaunchKernelGGL(k_smooth_direct<false>, grid, dim3(256), 0, c->stream, c->S, W, c->H2, c->hit_x, c->hit_n,
+                       c->hit_rows, c->massD, c->params, c->rows, c->cols, c->dim, toroid, bounded);
+  return hipGetLastError();
+}
+
 hipError_t launch_smooth_and_divide(som_ctx *c, float *W) {
+  if (c->nb_function != SOM_NEIGHBORHOOD_GAUSSIAN || c->nb_compact) return launch_smooth_direct(c, W);
   const int hex = c->grid_type == SOM_GRID_HEXAGONAL;
   const int toroid = c->map_type == SOM_MAP_TOROID;
   const int images = hex ? 2 : 1;

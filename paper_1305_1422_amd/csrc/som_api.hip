@@ -342,13 +342,13 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
             dev_alloc(&c->gy, (size_t)rows) && dev_alloc(&c->params, 1) && dev_alloc(&c->list_counts, 4) &&
             dev_alloc(&c->mu, (size_t)dim) && dev_alloc(&c->mu_partial, (size_t)64 * dim) &&
             dev_alloc(&c->zero16, 16) && dev_alloc(&c->mu_norm2, 1) && dev_alloc(&c->wscale, 1) &&
-            dev_alloc(&c->S, K * dim) && dev_alloc(&c->T, images * K * dim);
+            dev_alloc(&c->S, K * dim) && dev_alloc(&c->T, images * K * dim) &&
+            dev_alloc(&c->hit_x, K) && dev_alloc(&c->hit_n, (size_t)rows) && dev_alloc(&c->hit_rows, (size_t)rows + 1);
   if (ok && rows <= kSmoothMatMax && cols <= kSmoothMatMax) {
     const size_t par = grid_type == SOM_GRID_HEXAGONAL ? 2 : 1;
     c->xi_pad = ((cols + 15) / 16) * 16;
     c->e_pad = (int)(((((size_t)rows + par - 1) / par) + 15) / 16) * 16;
-    ok = dev_alloc(&c->GxT, par * par * cols * c->xi_pad) && dev_alloc(&c->GyT, par * rows * c->e_pad) &&
-         dev_alloc(&c->hit_x, K) && dev_alloc(&c->hit_n, (size_t)rows) && dev_alloc(&c->hit_rows, (size_t)rows + 1);
+    ok = dev_alloc(&c->GxT, par * par * cols * c->xi_pad) && dev_alloc(&c->GyT, par * rows * c->e_pad);
   }
   if (!ok) {
     som_destroy(c);
@@ -379,7 +379,7 @@ void som_destroy(som_ctx *c) {
   dev_free(c->wn32); dev_free(c->wn64); dev_free(c->wmax_bits); dev_free(c->counts); dev_free(c->seg_off);
   dev_free(c->chunk_off); dev_free(c->massD); dev_free(c->cntT); dev_free(c->gx); dev_free(c->gy);
   dev_free(c->params); dev_free(c->list_counts); dev_free(c->S); dev_free(c->T); dev_free(c->Wt);
-  dev_free(c->col_range); dev_free(c->qstep); dev_free(c->qstep_max_bits);
+  dev_free(c->col_range); dev_free(c->qstep); dev_free(c->qstep_max_bits); dev_free(c->H2);
   dev_free(c->GxT); dev_free(c->GyT); dev_free(c->hit_x); dev_free(c->hit_n); dev_free(c->hit_rows);
   dev_free(c->mu); dev_free(c->mu_partial); dev_free(c->Wc); dev_free(c->zero16); dev_free(c->mu_norm2);
   dev_free(c->Wh); dev_free(c->wscale);
@@ -552,6 +552,22 @@ int som_umatrix(som_ctx *c, const float *codebook, float *umatrix) {
   if (!c) return SOM_ERR_INVALID_ARG;
   if (!codebook || !umatrix) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
   SOM_LAUNCH(c, launch_umatrix(c, codebook, umatrix));
+  return SOM_OK;
+}
+
+int som_set_neighborhood(som_ctx *c, int function, int compact_support) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (function != SOM_NEIGHBORHOOD_GAUSSIAN && function != SOM_NEIGHBORHOOD_BUBBLE)
+    return fail(c, SOM_ERR_INVALID_ARG, "unknown neighborhood function %d", function);
+  const bool direct = function != SOM_NEIGHBORHOOD_GAUSSIAN || compact_support;
+  if (direct && !c->H2) {
+    const size_t width = (size_t)(c->map_type == SOM_MAP_TOROID ? c->cols : 2 * c->cols - 1) + 16;
+    const size_t classes = c->grid_type == SOM_GRID_HEXAGONAL ? 3 : 1;
+    if (!dev_alloc(&c->H2, classes * c->rows * width))
+      return fail(c, SOM_ERR_ALLOC, "cannot allocate the neighbourhood table");
+  }
+  c->nb_function = function;
+  c->nb_compact = compact_support ? 1 : 0;
   return SOM_OK;
 }
 

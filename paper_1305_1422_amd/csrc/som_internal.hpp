@@ -62,6 +62,9 @@ struct som_ctx {
   int xi_pad, e_pad;      // padded output extents of GxT / GyT (multiples of 16)
   int32_t *hit_x, *hit_n; // [k] columns of the chosen nodes per map row, [rows] their number
   int32_t *hit_rows;      // [rows+1] map rows with chosen nodes, last entry = their number
+  int nb_function;        // SOM_NEIGHBORHOOD_*
+  int nb_compact;         // Gaussian cut off at the current radius
+  float *H2;              // neighbourhood weights by (parity class, row distance, column offset), lazily allocated
   som::EpochParams *params;   // [1]
   float *S;               // [k][dim] per-node sums
   float *T;               // [1 or 2][k][dim] sums after the pass along x

@@ -12,6 +12,7 @@ MAP_TYPES = {"planar": capi.SOM_MAP_PLANAR, "toroid": capi.SOM_MAP_TOROID}
 GRID_TYPES = {"square": capi.SOM_GRID_SQUARE, "hexagonal": capi.SOM_GRID_HEXAGONAL}
 COOLING = {"linear": capi.SOM_COOL_LINEAR, "exponential": capi.SOM_COOL_EXPONENTIAL}
 FILTERS = {"fp32": capi.SOM_FILTER_FP32, "split_f16": capi.SOM_FILTER_SPLIT_F16}
+NEIGHBORHOODS = {"gaussian": capi.SOM_NEIGHBORHOOD_GAUSSIAN, "bubble": capi.SOM_NEIGHBORHOOD_BUBBLE}
 
 
 def _is_csr(data) -> bool:
@@ -51,6 +52,11 @@ class Som:
             filter = Som.default_filter
         if filter is not None:
             self.set_filter(filter)
+
+    def set_neighborhood(self, function: str = "gaussian", compact_support: bool = False) -> None:
+        """Neighbourhood of the batch update: "gaussian" or "bubble"; compact_support cuts the Gaussian
+        off beyond the epoch's radius."""
+        capi.som_set_neighborhood(self.ctx, NEIGHBORHOODS[function], compact_support)
 
     def set_filter(self, filter: str) -> None:
         """Arithmetic of the dense BMU filter pass: "split_f16" (default) or "fp32"; same results."""

@@ -66,14 +66,17 @@ def csr_take_rows(csr, rows):
     return out_ptr, indices[idx.astype(np.int64)], values[idx.astype(np.int64)]
 
 
-def check_codebook(oracle, S, C, W_in, W_gpu, rows, cols, map_type, grid_type, radius, nodes=None):
+def check_codebook(oracle, S, C, W_in, W_gpu, rows, cols, map_type, grid_type, radius, nodes=None,
+                   function=0, compact=False):
     """Oracle update from the given per-node sums against the GPU code book.
     Returns (number of nodes compared, number skipped as knife-edge)."""
     W_gpu = np.asarray(W_gpu)
     if nodes is None:
-        want, D = oracle.update(S, C, W_in, rows, cols, map_type, grid_type, radius)
+        want, D = oracle.update(S, C, W_in, rows, cols, map_type, grid_type, radius, function=function,
+                                compact=compact)
         got = W_gpu
     else:
+        assert function == 0 and not compact
         nodes = np.asarray(nodes, dtype=np.int32)
         want, D = oracle.update_nodes(S, C, W_in, rows, cols, map_type, grid_type, radius, nodes)
         got = W_gpu[nodes]
