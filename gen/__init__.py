@@ -10,6 +10,7 @@ from .workloads import (  # noqa: F401
     dense_uniform,
     dense_mixture,
     sparse_zipf_csr,
+    sparse_uniform_csr,
     codebook_uniform,
     make_workload,
     scaled_workload,

@@ -4,7 +4,8 @@ The paper benchmarks on random dense data (Experimental results, single-node
 performance: 50x50 and 200x200 maps, 1,000 dimensions) and on a sparse
 text-mining vector space (Visualization on real data).  None of those files
 exist here, so every input is drawn from a seeded ``numpy`` generator with the
-same shapes and structure.  Five configurations are defined; ``CONFIGS[c]``
+same shapes and structure.  The task's five configurations and two further sparse
+shapes of the paper are defined; ``CONFIGS[c]``
 describes configuration ``c`` (1-based) and ``make_workload(c)`` draws it.
 
 Only random draws live here: no distance, neighbourhood or update arithmetic.
@@ -61,6 +62,8 @@ class Workload:
             return dense_mixture(self.n, self.dim, self.data_seed, **self.params)
         if self.recipe == "zipf":
             return sparse_zipf_csr(self.n, self.dim, self.data_seed, **self.params)
+        if self.recipe == "sparse_uniform":
+            return sparse_uniform_csr(self.n, self.dim, self.data_seed, **self.params)
         raise ValueError(self.recipe)
 
     def codebook(self) -> np.ndarray:
@@ -133,10 +136,33 @@ def sparse_zipf_csr(n: int, dim: int, seed: int, mean_len: float = 100.0, max_le
     return indptr, indices, values
 
 
+def sparse_uniform_csr(n: int, dim: int, seed: int, density: float = 0.05
+                       ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Random sparse rows as in the paper's sparse-versus-dense comparison: every row has
+    round(density * dim) nonzeros at distinct uniformly drawn columns (sorted), values uniform [0, 1)."""
+    rng = np.random.default_rng(seed)
+    per = max(1, int(round(density * dim)))
+    indptr = (np.arange(n + 1, dtype=np.int64) * per)
+    indices = np.empty(n * per, dtype=np.int32)
+    chunk = max(1, (1 << 22) // dim)
+    for s in range(0, n, chunk):
+        e = min(n, s + chunk)
+        keys = rng.random((e - s, dim))
+        cols = np.sort(np.argpartition(keys, per - 1, axis=1)[:, :per], axis=1)
+        indices[s * per:e * per] = cols.reshape(-1)
+    values = rng.random(n * per).astype(np.float32)
+    return indptr, indices, values
+
+
 def codebook_uniform(k: int, dim: int, seed: int) -> np.ndarray:
     """Random initial code book: uniform [0, 1), fp32, node-major [k, dim]."""
     rng = np.random.default_rng(seed)
-    return rng.random((k, dim)).astype(np.float32)
+    out = np.empty((k, dim), dtype=np.float32)
+    chunk = max(1, (1 << 24) // max(dim, 1))          # same stream as one big draw, small fp64 intermediate
+    for s in range(0, k, chunk):
+        e = min(k, s + chunk)
+        out[s:e] = rng.random((e - s, dim)).astype(np.float32)
+    return out
 
 
 CONFIGS: Dict[int, Workload] = {
@@ -154,6 +180,15 @@ CONFIGS: Dict[int, Workload] = {
     5: Workload(5, "large-100x100-planar-hex", "dense", 1_000_000, 128, 100, 100, "planar", "hexagonal",
                 50.0, 1.0, 1.0, 0.01, 5, "mixture",
                 {"components": 256, "lo": 0.0, "hi": 1.0, "sigma": 0.03}),
+    # Two more sparse shapes from the paper's own experiments (not among the task's five):
+    # the sparse-versus-dense comparison (1,000 dimensions, five per cent nonzeros, 50 x 50 map) and
+    # the Reuters text-mining map (12,347 index terms in a space of about twenty thousand
+    # dimensions, toroid emergent map of 336 x 205 nodes, radius 100 -> 1 over ten epochs).
+    6: Workload(6, "sparse-uniform-50x50-planar-square", "csr", 100_000, 1_000, 50, 50, "planar", "square",
+                25.0, 1.0, 1.0, 0.01, 10, "sparse_uniform", {"density": 0.05}),
+    7: Workload(7, "text-esom-336x205-toroid-square", "csr", 12_347, 20_000, 205, 336, "toroid", "square",
+                100.0, 1.0, 1.0, 0.1, 10, "zipf",
+                {"mean_len": 100.0, "max_len": 400, "zipf_s": 1.1, "poisson_lam": 2.0}),
 }
 
 

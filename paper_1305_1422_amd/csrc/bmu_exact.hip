@@ -71,7 +71,7 @@ __global__ __launch_bounds__(256) void k_certify(CandView cand, int groups, cons
                                                  int32_t *__restrict__ collect_rows,
                                                  float *__restrict__ collect_thr,
                                                  int32_t *__restrict__ collect_cnt,
-                                                 int32_t *__restrict__ list_counts) {
+                                                 int32_t *__restrict__ list_counts, UnitWork work) {
   const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (j >= n) return;
   float smin = INFINITY, omin = INFINITY;
@@ -104,7 +104,30 @@ __global__ __launch_bounds__(256) void k_certify(CandView cand, int groups, cons
     float t32 = (float)thr;                     // round the threshold up: no score inside the margin is lost
     if ((double)t32 < thr) t32 = nextafterf(t32, INFINITY);
     collect_thr[slot] = cnt == 0 ? INFINITY : t32;
-    collect_cnt[slot] = 0;
+    int filled = 0;
+    if (work.sweeps > 0) {
+      // sparse search: only the node ranges whose third-best score is inside the threshold have to be
+      // swept again; the others are known completely through their two best nodes, listed here
+      const double lim = cnt == 0 ? (double)INFINITY : thr;
+      for (int q = 0; q < groups; ++q) {
+        if ((double)cand.over[(int64_t)q * n + j] <= lim) {
+          const int slice = q / work.sweeps;
+          const int pos = atomicAdd(&work.counts[slice], 1);
+          work.units[(int64_t)slice * work.cap + pos] = (int64_t)slot * work.sweeps + (q - slice * work.sweeps);
+        } else {
+          const int64_t base = ((int64_t)q * n + j) * kCand;
+#pragma unroll
+          for (int t = 0; t < kCand; ++t) {
+            const int id = cand.idx[base + t];
+            if ((unsigned)id < (unsigned)k && (double)cand.val[base + t] <= lim) {
+              if (filled < kListCap) work.list[(int64_t)slot * kListCap + filled] = id;
+              ++filled;
+            }
+          }
+        }
+      }
+    }
+    collect_cnt[slot] = filled;
   } else if (cnt == 1) {
     bmus[j] = keep[0];
   } else {
@@ -351,9 +374,11 @@ static double split_pass_roundings(int dim) {
 hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int64_t *indptr, int32_t *bmus) {
   CandView cand{c->cand_val, c->cand_idx, c->cand_over};
   MarginModel mm{2.0 * fp32_pass_roundings(c->dim) + 4.0, 0.0, nullptr, nullptr, nullptr, nullptr};
+  UnitWork work{0, 0, nullptr, nullptr, nullptr};
   if (mode == kCertifyCsr) {
     mm.indptr = indptr;
     mm.row_q = c->row_q;
+    work = UnitWork{c->csr_sweeps, c->unit_cap, c->unit_work, c->list_counts + kUnitCounts, c->collect_list};
   }
   if (mode == kCertifySplit) {
     // dot product: accumulation + 3 * 2^-22 of the split (= 12 u) ; both doubled by the factor -2;
@@ -368,7 +393,7 @@ hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int
   }
   hipLaunchKernelGGL(k_certify, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, cand, groups, c->xn32,
                      c->wmax_bits, c->mu_norm2, mm, n, c->k, bmus, c->cand_n, c->refine_list, c->collect_rows,
-                     c->collect_thr, c->collect_cnt, c->list_counts);
+                     c->collect_thr, c->collect_cnt, c->list_counts, work);
   return hipGetLastError();
 }
 

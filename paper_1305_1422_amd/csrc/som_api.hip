@@ -117,8 +117,17 @@ static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
 // The dense fp32 pass writes one candidate list per node group and instance.
 static int ensure_candidates(som_ctx *c, int64_t n, bool dense) {
   const int groups_h = dense && c->filter == SOM_FILTER_SPLIT_F16 ? bmu_dense_h_groups(c, n) : 1;
-  const int groups_f = dense ? bmu_dense_groups(c, n) : 8;      // sparse: one list per node slice
+  const int groups_f = dense ? bmu_dense_groups(c, n) : 8 * c->csr_sweeps;      // sparse: one list per node range
   const int64_t need = (int64_t)(groups_h > groups_f ? groups_h : groups_f) * n;
+  if (!dense && n * c->csr_sweeps > c->unit_cap) {
+    (void)hipStreamSynchronize(c->stream);
+    dev_free(c->unit_work);
+    c->unit_work = nullptr;
+    c->unit_cap = 0;
+    if (!dev_alloc(&c->unit_work, (size_t)8 * n * c->csr_sweeps))
+      return fail(c, SOM_ERR_ALLOC, "cannot allocate the work list of the sparse search");
+    c->unit_cap = n * c->csr_sweeps;
+  }
   if (need <= c->cand_cap) return SOM_OK;
   (void)hipStreamSynchronize(c->stream);
   dev_free(c->cand_val); dev_free(c->cand_idx); dev_free(c->cand_over);
@@ -132,8 +141,7 @@ static int ensure_candidates(som_ctx *c, int64_t n, bool dense) {
 
 static int ensure_transposed(som_ctx *c) {
   if (c->Wt) return SOM_OK;
-  // int16 entries for the sliced kernel, fp32 otherwise
-  const size_t words = bmu_csr_sliced_ok(c) ? ((size_t)c->dim * c->kpad + 1) / 2 : (size_t)c->dim * c->kpad;
+  const size_t words = ((size_t)c->dim * c->kpad + 1) / 2;      // int16 entries
   if (!(dev_alloc(&c->Wt, words) && dev_alloc(&c->col_range, (size_t)2 * 64 * c->dim) &&
         dev_alloc(&c->qstep, (size_t)c->dim) && dev_alloc(&c->qstep_max_bits, 1))) {
     dev_free(c->Wt); dev_free(c->col_range); dev_free(c->qstep); dev_free(c->qstep_max_bits);
@@ -225,8 +233,7 @@ static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *
 static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
                           int64_t n, const float *W, int32_t *bmus, bool have_xn) {
   int rc = ensure_transposed(c);
-  const bool sliced = bmu_csr_sliced_ok(c);
-  if (!rc && sliced) rc = ensure_candidates(c, n, false);
+  if (!rc) rc = ensure_candidates(c, n, false);
   if (rc) return rc;
   if (!have_xn) {
     c->d_norms_valid = 0;
@@ -235,21 +242,19 @@ static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indi
   // centring vector of the sparse search: the mean of the code-book rows (changes every epoch);
   // it overwrites the one a registered dense training set may have cached
   if (c->data_kind == 1) c->d_norms_valid = 0;
-  if (sliced) SOM_LAUNCH(c, launch_codebook_means_and_steps(c, W));      // all k <= 8192 rows: exact column ranges
-  else SOM_LAUNCH(c, launch_sample_col_means(c, W, c->k, c->dim, c->mu));
+  SOM_LAUNCH(c, launch_codebook_means_and_steps(c, W));
   SOM_LAUNCH(c, launch_vec_sqnorm(c, c->mu, c->dim, c->mu_norm2));
   SOM_LAUNCH(c, launch_center_codebook(c, W, false, true));
-  SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 3));
+  SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, kListCounts));
   {
     StageTimer t(c, 1);
     SOM_LAUNCH(c, launch_transpose_codebook(c, W));
-    if (sliced) SOM_LAUNCH(c, launch_bmu_csr_sliced(c, indptr, indices, values, n, false));
-    else SOM_LAUNCH(c, launch_bmu_csr(c, indptr, indices, values, n, bmus));
+    SOM_LAUNCH(c, launch_bmu_csr_sliced(c, indptr, indices, values, n, false));
   }
   StageTimer t(c, 2);
-  if (sliced) SOM_LAUNCH(c, launch_certify(c, n, 8, kCertifyCsr, indptr, bmus));
+  SOM_LAUNCH(c, launch_certify(c, n, 8 * c->csr_sweeps, kCertifyCsr, indptr, bmus));
   SOM_LAUNCH(c, launch_refine_csr(c, indptr, indices, values, W, bmus));
-  if (sliced) SOM_LAUNCH(c, launch_bmu_csr_sliced(c, indptr, indices, values, n, true));
+  SOM_LAUNCH(c, launch_bmu_csr_sliced(c, indptr, indices, values, n, true));
   SOM_LAUNCH(c, launch_refine_lists_csr(c, indptr, indices, values, W, bmus));
   SOM_LAUNCH(c, launch_rescan_csr(c, indptr, indices, values, W, bmus));
   return SOM_OK;
@@ -323,7 +328,7 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
   c->rows = rows; c->cols = cols; c->dim = dim; c->k = rows * cols;
   c->map_type = map_type; c->grid_type = grid_type;
   c->stream = (hipStream_t)hip_stream;
-  c->kpad = ((c->k + 511) / 512) * 512;
+  csr_slice_geometry(c->k, &c->csr_acc, &c->csr_sweeps, &c->kpad);
   c->filter = SOM_FILTER_SPLIT_F16;
 
   int dev = 0;
@@ -339,7 +344,7 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
   bool ok = dev_alloc(&c->wn32, (K + 127) / 128 * 128) && dev_alloc(&c->wn64, K) && dev_alloc(&c->wmax_bits, 2) &&
             dev_alloc(&c->counts, K + 1) && dev_alloc(&c->seg_off, K + 1) && dev_alloc(&c->chunk_off, K + 1) &&
             dev_alloc(&c->massD, K) && dev_alloc(&c->cntT, 2 * K) && dev_alloc(&c->gx, 2 * (size_t)cols + 1) &&
-            dev_alloc(&c->gy, (size_t)rows) && dev_alloc(&c->params, 1) && dev_alloc(&c->list_counts, 4) &&
+            dev_alloc(&c->gy, (size_t)rows) && dev_alloc(&c->params, 1) && dev_alloc(&c->list_counts, kListCounts) &&
             dev_alloc(&c->mu, (size_t)dim) && dev_alloc(&c->mu_partial, (size_t)64 * dim) &&
             dev_alloc(&c->zero16, 16) && dev_alloc(&c->mu_norm2, 1) && dev_alloc(&c->wscale, 1) &&
             dev_alloc(&c->S, K * dim) && dev_alloc(&c->T, images * K * dim) &&
@@ -354,7 +359,7 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
     som_destroy(c);
     return fail(nullptr, SOM_ERR_ALLOC, "cannot allocate map scratch (%d nodes x %d)", c->k, dim);
   }
-  hipError_t e = launch_fill_zero_u32(c->stream, c->list_counts, 4);
+  hipError_t e = launch_fill_zero_u32(c->stream, c->list_counts, kListCounts);
   if (e == hipSuccess) e = launch_fill_zero_u32(c->stream, c->zero16, 16);
   if (e == hipSuccess && K % 128 != 0) {       // the tail of the node constants past k stays +inf for good
     float inf[128];
@@ -378,7 +383,7 @@ void som_destroy(som_ctx *c) {
   free_row_scratch(c);
   dev_free(c->wn32); dev_free(c->wn64); dev_free(c->wmax_bits); dev_free(c->counts); dev_free(c->seg_off);
   dev_free(c->chunk_off); dev_free(c->massD); dev_free(c->cntT); dev_free(c->gx); dev_free(c->gy);
-  dev_free(c->params); dev_free(c->list_counts); dev_free(c->S); dev_free(c->T); dev_free(c->Wt);
+  dev_free(c->params); dev_free(c->list_counts); dev_free(c->unit_work); dev_free(c->S); dev_free(c->T); dev_free(c->Wt);
   dev_free(c->col_range); dev_free(c->qstep); dev_free(c->qstep_max_bits); dev_free(c->H2);
   dev_free(c->GxT); dev_free(c->GyT); dev_free(c->hit_x); dev_free(c->hit_n); dev_free(c->hit_rows);
   dev_free(c->mu); dev_free(c->mu_partial); dev_free(c->Wc); dev_free(c->zero16); dev_free(c->mu_norm2);

@@ -68,9 +68,10 @@ struct som_ctx {
   som::EpochParams *params;   // [1]
   float *S;               // [k][dim] per-node sums
   float *T;               // [1 or 2][k][dim] sums after the pass along x
-  float *Wt;              // [dim][kpad] centred transposed code book (sparse BMU only, lazily allocated): fp32, or
-                          // int16 multiples of the column steps when the sliced kernel is used
-  int kpad;
+  float *Wt;              // [dim][kpad] centred transposed code book of the sparse BMU search, int16 multiples
+                          // of the column steps (lazily allocated)
+  int kpad;               // 512 * csr_acc * csr_sweeps >= k
+  int csr_acc, csr_sweeps;    // sparse BMU kernel: scores per lane and sweep, sweeps per node slice
   float *col_range;       // [2][64][dim] slab minima and maxima of the code-book columns (with Wt)
   float *qstep;           // [dim] quantisation step of every column of Wt (with Wt)
   unsigned *qstep_max_bits;   // [1] bit pattern of the largest step
@@ -100,7 +101,9 @@ struct som_ctx {
   int32_t *collect_cnt;   // [n] nodes found under the threshold
   int32_t *collect_list;  // [n][kListCap] those nodes (dense path only, lazily allocated)
   int32_t *rescan_list;   // [n] instances that need an exact scan of all nodes
-  int32_t *list_counts;   // [3] lengths of refine_list, collect_rows, rescan_list
+  int32_t *list_counts;   // [0..2] lengths of refine_list, collect_rows, rescan_list; [4..11] of unit_work per slice
+  int64_t *unit_work;     // [8][unit_cap] sparse search: (collect slot, node range) units to sweep again
+  int64_t unit_cap;
   int32_t *sort_key[2];   // [n] each
   int32_t *sort_val[2];   // [n] each
   int32_t *radix_hist;    // [256 * sort blocks]
@@ -156,6 +159,16 @@ hipError_t launch_probe_mfma_f16(hipStream_t stream, const uint16_t *A, const ui
                                  int count);
 
 // bmu_exact.hip
+// Work list of the sparse search's second sweep: per node slice, entries slot * sweeps + range.
+struct UnitWork {
+  int sweeps;             // 0: not a sparse search, every collected instance is swept whole
+  int64_t cap;            // entries per slice
+  int64_t *units;         // [8][cap]
+  int32_t *counts;        // [8]
+  int32_t *list;          // [slots][kListCap] candidate lists, seeded with the nodes of the complete ranges
+};
+constexpr int kListCounts = 12;    // words in som_ctx::list_counts
+constexpr int kUnitCounts = 4;     // first of the eight work-list lengths in it
 enum { kCertifyFp32 = 0, kCertifySplit = 1, kCertifyCsr = 2 };      // whose rounding bound the margin uses
 hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int64_t *indptr, int32_t *bmus);
 hipError_t launch_refine_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
@@ -170,9 +183,7 @@ hipError_t launch_rescan_csr(som_ctx *c, const int64_t *indptr, const int32_t *i
 
 // bmu_csr.hip
 hipError_t launch_transpose_codebook(som_ctx *c, const float *W);
-hipError_t launch_bmu_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices,
-                          const float *values, int64_t n, int32_t *bmus);
-bool bmu_csr_sliced_ok(const som_ctx *c);          // map small enough for the one-slice-per-XCD kernel
+void csr_slice_geometry(int k, int *acc, int *sweeps, int *kpad);
 hipError_t launch_bmu_csr_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
                                  int64_t n, bool collect);
 

@@ -37,9 +37,8 @@ def test_scaled_config4(oracle, n, dim, rows, cols, epochs, mean_len):
 
 @pytest.mark.parametrize("rows,cols", [(70, 64), (64, 128), (100, 100)])
 def test_many_nodes(oracle, rows, cols):
-    """4,480 and 8,192 nodes: nine and sixteen scores per lane in the kernel that gives every XCD a
-    node slice; 10,000 nodes: past its limit, the kernel with a workgroup per instance and several
-    sweeps over the nodes takes over."""
+    """4,480 and 8,192 nodes: nine and sixteen scores per lane with one node range per XCD slice;
+    10,000 nodes: two ranges per slice."""
     from paper_1305_1422_amd import Som
     dim, n = 300, 150
     csr = sparse_zipf_csr(n, dim, 21, mean_len=12.0, max_len=40)
@@ -47,6 +46,28 @@ def test_many_nodes(oracle, rows, cols):
     som = Som(rows, cols, dim, "toroid", "hexagonal", codebook=torch.from_numpy(W))
     b = som.bmus(P.csr_to_dev(csr)).cpu().numpy()
     P.check_bmus_csr(oracle, csr, dim, W, b)
+    som.close()
+
+
+def test_smooth_map_takes_the_second_sweep_over_listed_ranges(oracle):
+    """A code book smoothed with a wide neighbourhood has neighbouring nodes closer than the 16-bit
+    filter can separate: many instances go to the second sweep, which visits only the node ranges whose
+    third-best score is inside the threshold and takes the other ranges' nodes from the first sweep.
+    10,000 nodes = two ranges per slice; the result must still be the exact argmin."""
+    from paper_1305_1422_amd import Som
+    rows, cols, dim, n = 100, 100, 400, 600
+    csr = sparse_zipf_csr(n, dim, 41, mean_len=20.0, max_len=60)
+    W0 = np.random.default_rng(42).random((rows * cols, dim)).astype(np.float32)
+    som = Som(rows, cols, dim, "toroid", "square", codebook=torch.from_numpy(W0))
+    csr_d = P.csr_to_dev(csr)
+    som.train_epoch(csr_d, 30.0)
+    collected = 0
+    for radius in (30.0, 12.0):
+        W_in = som.codebook.cpu().numpy().copy()
+        b = som.train_epoch(csr_d, radius).cpu().numpy()
+        collected += som.stats()[1]
+        P.check_bmus_csr(oracle, csr, dim, W_in, b)
+    assert collected >= 100, f"only {collected} instances took the second sweep: the test misses its case"
     som.close()
 
 
