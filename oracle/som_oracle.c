@@ -31,7 +31,9 @@
  * Parity pins (tests marked "not gpu"): brute force in numpy on tiny inputs,
  * k-means limit for radius -> 0, global-mean limit for radius -> infinity,
  * torus translation symmetry, zero-mass nodes keep their weights, closed-form
- * U-matrix of a ramp, sparse == densified dense, cooling end points.
+ * U-matrix of a ramp, sparse == densified dense, cooling end points; distances to
+ * the BMU: right triangles, agreement with the minimum the BMU search reports,
+ * scaling, numpy on tiny inputs.
  * Parity against the original tool's outputs: parity unpinned (no source, no
  * data and no printed numerical example are available).
  */
@@ -195,6 +197,40 @@ void oracle_sqdist_pairs_csr(const int64_t *indptr, const int32_t *indices, cons
         int64_t s = indptr[inst[p]], len = indptr[inst[p] + 1] - s;
         out[p] = sqdist_csr(indices + s, values + s, len, W + (int64_t)node[p] * dim, dim);
     }
+}
+
+/* ---------------------------------------------------------------------------
+ * Post-training outputs.  The paper lists the BMU of every instance, the code
+ * book and the U-matrix as results (output prefix of the command line, class
+ * variables of the Python interface) and prints no formula for a quality
+ * figure.  Reading taken here: dist[j] = Euclidean distance between instance j
+ * and the weight vector of node bmu[j]; the return value is their mean, the
+ * quantisation error in its usual sense (0 for n = 0).  dist may be NULL.
+ * ------------------------------------------------------------------------- */
+double oracle_bmu_distances_dense(const float *X, int64_t n, int dim, const float *W,
+                                  const int32_t *bmu, double *dist)
+{
+    double total = 0.0;
+    for (int64_t j = 0; j < n; ++j) {
+        double d = sqrt(sqdist_dense(X + j * (int64_t)dim, W + (int64_t)bmu[j] * dim, dim));
+        if (dist) dist[j] = d;
+        total += d;
+    }
+    return n > 0 ? total / (double)n : 0.0;
+}
+
+double oracle_bmu_distances_csr(const int64_t *indptr, const int32_t *indices, const float *values,
+                                int64_t n, int dim, const float *W, const int32_t *bmu, double *dist)
+{
+    double total = 0.0;
+    for (int64_t j = 0; j < n; ++j) {
+        int64_t s = indptr[j], len = indptr[j + 1] - s;
+        double d2 = sqdist_csr(indices + s, values + s, len, W + (int64_t)bmu[j] * dim, dim);
+        double d = sqrt(d2 > 0.0 ? d2 : 0.0);      /* the regrouped sum may round below zero */
+        if (dist) dist[j] = d;
+        total += d;
+    }
+    return n > 0 ? total / (double)n : 0.0;
 }
 
 /* ---------------------------------------------------------------------------

@@ -67,6 +67,10 @@ def lib():
         L.oracle_epoch_csr.argtypes = [i64p, i32p, f32p, C.c_int64, C.c_int, f32p, C.c_int, C.c_int,
                                        C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, i32p]
         L.oracle_cool.restype = C.c_double
+        L.oracle_bmu_distances_dense.argtypes = [f32p, C.c_int64, C.c_int, f32p, i32p, f64p]
+        L.oracle_bmu_distances_dense.restype = C.c_double
+        L.oracle_bmu_distances_csr.argtypes = [i64p, i32p, f32p, C.c_int64, C.c_int, f32p, i32p, f64p]
+        L.oracle_bmu_distances_csr.restype = C.c_double
         L.oracle_cool.argtypes = [C.c_double, C.c_double, C.c_int, C.c_int, C.c_int]
         L.oracle_umatrix.restype = None
         L.oracle_umatrix.argtypes = [f32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f64p]
@@ -234,6 +238,30 @@ def epoch_csr(csr, dim, W, rows, cols, map_type, grid_type, radius, scale=1.0, e
     if rc:
         raise MemoryError("oracle_epoch_csr")
     return bmu, Wn
+
+
+def bmu_distances_dense(X, W, bmu):
+    """(distance of every instance to node bmu[j], their mean = quantisation error)."""
+    X, W = _f32(X), _f32(W)
+    bmu = np.ascontiguousarray(bmu, dtype=np.int32)
+    n, dim = X.shape
+    assert bmu.shape == (n,) and (n == 0 or (bmu.min() >= 0 and bmu.max() < W.shape[0]))
+    dist = np.empty(n, dtype=np.float64)
+    qe = lib().oracle_bmu_distances_dense(_p(X, C.c_float), n, dim, _p(W, C.c_float), _p(bmu, C.c_int32),
+                                          _p(dist, C.c_double))
+    return dist, float(qe)
+
+
+def bmu_distances_csr(csr, dim: int, W, bmu):
+    indptr, indices, values = _csr(csr)
+    W = _f32(W)
+    bmu = np.ascontiguousarray(bmu, dtype=np.int32)
+    n = indptr.shape[0] - 1
+    assert bmu.shape == (n,) and (n == 0 or (bmu.min() >= 0 and bmu.max() < W.shape[0]))
+    dist = np.empty(n, dtype=np.float64)
+    qe = lib().oracle_bmu_distances_csr(_p(indptr, C.c_int64), _p(indices, C.c_int32), _p(values, C.c_float),
+                                        n, dim, _p(W, C.c_float), _p(bmu, C.c_int32), _p(dist, C.c_double))
+    return dist, float(qe)
 
 
 def cool(v0: float, vN: float, n_epochs: int, epoch: int, kind: int = LINEAR) -> float:
