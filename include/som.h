@@ -159,6 +159,44 @@ int som_train(som_ctx *ctx, int n_epochs, float radius0, float radiusN, float sc
               float scaleN, int cooling, float *codebook, int32_t *bmus);
 
 /*
+ * som_train_snapshots - som_train with the interim outputs of option -s.
+ *   snapshots 0: none (exactly som_train; the three pointers below are ignored).
+ *             1: the U-matrix of the code book after every epoch.
+ *             2: also the code book after every epoch and the BMUs that epoch found.
+ *   umatrices  device [n_epochs][rows][cols] fp32 out (snapshots >= 1).
+ *   codebooks  device [n_epochs][rows*cols][dim] fp32 out (snapshots == 2).
+ *   bmus_all   device [n_epochs][n] int32 out (snapshots == 2), n = registered instances.
+ * Everything is written on the context's stream in epoch order; the caller owns the buffers
+ * (for large maps `codebooks` is the big one: n_epochs code books).  Other arguments, defaults
+ * and errors as in som_train; a missing buffer or snapshots outside 0..2 -> SOM_ERR_INVALID_ARG.
+ */
+int som_train_snapshots(som_ctx *ctx, int n_epochs, float radius0, float radiusN, float scale0,
+                        float scaleN, int cooling, float *codebook, int32_t *bmus, int snapshots,
+                        float *umatrices, float *codebooks, int32_t *bmus_all);
+
+/*
+ * som_bmu_distances_dense / som_bmu_distances_csr - post-training output: how far every
+ * instance lies from the node it is mapped to.  (The paper lists the BMUs, the code book and
+ * the U-matrix as results and prints no formula for a quality figure; this is the usual
+ * quantisation error.)
+ *   data / indptr, indices, values, n, nnz   as in the epoch calls, read only.
+ *   codebook   device [rows*cols][dim] fp32, read only.
+ *   bmus       device [n] int32, read only: node of every instance, normally from som_bmus_*
+ *              against the same code book.  An index outside [0, rows*cols) gives NaN for that
+ *              instance and for the mean.
+ *   distances  device [n] fp32 out, or NULL: Euclidean distance ||x_j - w_bmus[j]||, summed in
+ *              fp64 and rounded once.
+ *   qerror     device [1] fp64 out, or NULL: the mean of the (unrounded) distances; the order
+ *              of the additions is fixed, so equal inputs give equal bits.
+ * At least one of the two outputs must be given.  Nothing is allocated.
+ */
+int som_bmu_distances_dense(som_ctx *ctx, const float *data, int64_t n, const float *codebook,
+                            const int32_t *bmus, float *distances, double *qerror);
+int som_bmu_distances_csr(som_ctx *ctx, const int64_t *indptr, const int32_t *indices,
+                          const float *values, int64_t n, int64_t nnz, const float *codebook,
+                          const int32_t *bmus, float *distances, double *qerror);
+
+/*
  * som_cool_schedule - evaluate the cooling schedule of som_train on the device.
  *   radius_out, scale_out  device [n_epochs] fp64 out (either may be NULL).
  * Defaults and formulas as in som_train.

@@ -26,7 +26,8 @@ EXPORTS = [
     "som_train_epoch_dense", "som_train_epoch_csr",
     "som_bmus_dense", "som_bmus_csr",
     "som_update_dense", "som_update_csr",
-    "som_set_data_dense", "som_set_data_csr", "som_train",
+    "som_set_data_dense", "som_set_data_csr", "som_train", "som_train_snapshots",
+    "som_bmu_distances_dense", "som_bmu_distances_csr",
     "som_cool_schedule", "som_umatrix", "som_get_stats",
     "som_profile_enable", "som_profile_read",
     "som_set_filter", "som_set_neighborhood", "som_debug_scores_dense", "som_debug_mfma_f16",
@@ -78,6 +79,12 @@ def load():
     L.som_train.argtypes = [vp, i32, f32, f32, f32, f32, i32, vp, vp]
     L.som_cool_schedule.restype = i32
     L.som_cool_schedule.argtypes = [vp, i32, f32, f32, f32, f32, i32, vp, vp]
+    L.som_train_snapshots.restype = i32
+    L.som_train_snapshots.argtypes = [vp, i32, f32, f32, f32, f32, i32, vp, vp, i32, vp, vp, vp]
+    L.som_bmu_distances_dense.restype = i32
+    L.som_bmu_distances_dense.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+    L.som_bmu_distances_csr.restype = i32
+    L.som_bmu_distances_csr.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp, vp, vp]
     L.som_umatrix.restype = i32
     L.som_umatrix.argtypes = [vp, vp, vp]
     L.som_get_stats.restype = i32
@@ -210,6 +217,37 @@ def som_train(ctx, n_epochs: int, radius0: float, radiusN: float, scale0: float,
     import torch
     _check(ctx, load().som_train(ctx, n_epochs, radius0, radiusN, scale0, scaleN, cooling,
                                  _ptr(codebook, torch.float32, "codebook"), _ptr(bmus, torch.int32, "bmus")))
+
+
+def som_train_snapshots(ctx, n_epochs: int, radius0: float, radiusN: float, scale0: float, scaleN: float,
+                        cooling: int, codebook, bmus, snapshots: int, umatrices, codebooks, bmus_all) -> None:
+    import torch
+    _check(ctx, load().som_train_snapshots(ctx, n_epochs, radius0, radiusN, scale0, scaleN, cooling,
+                                           _ptr(codebook, torch.float32, "codebook"), _ptr(bmus, torch.int32, "bmus"),
+                                           snapshots, _ptr(umatrices, torch.float32, "umatrices", True),
+                                           _ptr(codebooks, torch.float32, "codebooks", True),
+                                           _ptr(bmus_all, torch.int32, "bmus_all", True)))
+
+
+def som_bmu_distances_dense(ctx, data, codebook, bmus, distances, qerror) -> None:
+    import torch
+    _check(ctx, load().som_bmu_distances_dense(ctx, _ptr(data, torch.float32, "data"), data.shape[0],
+                                               _ptr(codebook, torch.float32, "codebook"),
+                                               _ptr(bmus, torch.int32, "bmus"),
+                                               _ptr(distances, torch.float32, "distances", True),
+                                               _ptr(qerror, torch.float64, "qerror", True)))
+
+
+def som_bmu_distances_csr(ctx, indptr, indices, values, codebook, bmus, distances, qerror) -> None:
+    import torch
+    _check(ctx, load().som_bmu_distances_csr(ctx, _ptr(indptr, torch.int64, "indptr"),
+                                             _ptr(indices, torch.int32, "indices", True),
+                                             _ptr(values, torch.float32, "values", True),
+                                             indptr.shape[0] - 1, indices.shape[0],
+                                             _ptr(codebook, torch.float32, "codebook"),
+                                             _ptr(bmus, torch.int32, "bmus"),
+                                             _ptr(distances, torch.float32, "distances", True),
+                                             _ptr(qerror, torch.float64, "qerror", True)))
 
 
 def som_cool_schedule(ctx, n_epochs: int, radius0: float, radiusN: float, scale0: float, scaleN: float,

@@ -430,6 +430,80 @@ hipError_t launch_refine_lists_csr(som_ctx *c, const int64_t *indptr, const int3
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- distances to the BMUs
+// Post-training output: Euclidean distance between every instance and the weight vector of
+// the node it is mapped to, in fp64, and the mean of those distances (quantisation error).
+// A wavefront per instance; a workgroup owns a contiguous block of instances and leaves one
+// partial sum, the partial sums are added in index order by k_mean_of_partials: the result
+// does not depend on the schedule.  A node index outside [0, k) yields NaN.
+constexpr int kDistBlocks = 1024;
+
+template <bool kCsr>
+__global__ __launch_bounds__(256) void k_bmu_distances(const float *__restrict__ X,
+                                                       const int64_t *__restrict__ indptr,
+                                                       const int32_t *__restrict__ indices,
+                                                       const float *__restrict__ values,
+                                                       const float *__restrict__ W, int64_t n, int k, int dim,
+                                                       const int32_t *__restrict__ bmus, float *__restrict__ dist,
+                                                       double *__restrict__ partial) {
+  __shared__ double wave_total[4];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const int64_t per_block = (n + gridDim.x - 1) / gridDim.x;
+  const int64_t j0 = (int64_t)blockIdx.x * per_block;
+  const int64_t j1 = j0 + per_block < n ? j0 + per_block : n;
+  double total = 0.0;
+  for (int64_t j = j0 + wave; j < j1; j += 4) {
+    const int b = bmus[j];
+    double d = NAN;
+    if ((unsigned)b < (unsigned)k) {
+      const float *w = W + (int64_t)b * dim;
+      double d2;
+      if (kCsr) {
+        double wn = 0.0;
+        for (int c = lane; c < dim; c += kWave) wn += (double)w[c] * (double)w[c];
+        wn = wave_sum(wn);
+        const int64_t rs = indptr[j];
+        d2 = sqdist_csr_wave(indices + rs, values + rs, (int)(indptr[j + 1] - rs), w, wn, dim, lane);
+        d2 = d2 > 0.0 ? d2 : 0.0;        // the regrouped sum may round below zero
+      } else {
+        d2 = sqdist_dense_wave(X + j * dim, w, dim, lane);
+      }
+      d = sqrt(d2);
+    }
+    if (dist && lane == 0) dist[j] = (float)d;
+    total += d;
+  }
+  if (lane == 0) wave_total[wave] = total;
+  __syncthreads();
+  if (threadIdx.x == 0) partial[blockIdx.x] = (wave_total[0] + wave_total[1]) + (wave_total[2] + wave_total[3]);
+}
+
+__global__ __launch_bounds__(64) void k_mean_of_partials(const double *__restrict__ partial, int count, int64_t n,
+                                                         double *__restrict__ out) {
+  double s = 0.0;
+  for (int i = threadIdx.x; i < count; i += kWave) s += partial[i];
+  s = wave_sum(s);
+  if (threadIdx.x == 0) *out = n > 0 ? s / (double)n : 0.0;
+}
+
+hipError_t launch_bmu_distances(som_ctx *c, const float *X, const int64_t *indptr, const int32_t *indices,
+                                const float *values, int64_t n, const float *W, const int32_t *bmus, float *dist,
+                                double *qerror) {
+  int blocks = (int)((n + 3) / 4);
+  if (blocks > kDistBlocks) blocks = kDistBlocks;
+  if (blocks < 1) blocks = 1;
+  if (X)
+    hipLaunchKernelGGL(k_bmu_distances<false>, dim3(blocks), dim3(256), 0, c->stream, X, nullptr, nullptr, nullptr, W,
+                       n, c->k, c->dim, bmus, dist, c->dist_partial);
+  else
+    hipLaunchKernelGGL(k_bmu_distances<true>, dim3(blocks), dim3(256), 0, c->stream, nullptr, indptr, indices, values,
+                       W, n, c->k, c->dim, bmus, dist, c->dist_partial);
+  if (qerror)
+    hipLaunchKernelGGL(k_mean_of_partials, dim3(1), dim3(64), 0, c->stream, c->dist_partial, blocks, n, qerror);
+  return hipGetLastError();
+}
+
 hipError_t launch_rescan_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
                              const float *W, int32_t *bmus) {
   hipLaunchKernelGGL(k_rescan_csr, dim3(persistent_blocks(c, 1 << 20)), dim3(256), 0, c->stream, indptr, indices,

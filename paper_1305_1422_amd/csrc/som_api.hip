@@ -343,7 +343,7 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
   const size_t images = grid_type == SOM_GRID_HEXAGONAL ? 2 : 1;
   bool ok = dev_alloc(&c->wn32, (K + 127) / 128 * 128) && dev_alloc(&c->wn64, K) && dev_alloc(&c->wmax_bits, 2) &&
             dev_alloc(&c->counts, K + 1) && dev_alloc(&c->seg_off, K + 1) && dev_alloc(&c->chunk_off, K + 1) &&
-            dev_alloc(&c->massD, K) && dev_alloc(&c->cntT, 2 * K) && dev_alloc(&c->gx, 2 * (size_t)cols + 1) &&
+            dev_alloc(&c->massD, K) && dev_alloc(&c->dist_partial, 1024) && dev_alloc(&c->cntT, 2 * K) && dev_alloc(&c->gx, 2 * (size_t)cols + 1) &&
             dev_alloc(&c->gy, (size_t)rows) && dev_alloc(&c->params, 1) && dev_alloc(&c->list_counts, kListCounts) &&
             dev_alloc(&c->mu, (size_t)dim) && dev_alloc(&c->mu_partial, (size_t)64 * dim) &&
             dev_alloc(&c->zero16, 16) && dev_alloc(&c->mu_norm2, 1) && dev_alloc(&c->wscale, 1) &&
@@ -382,7 +382,7 @@ void som_destroy(som_ctx *c) {
   (void)hipStreamSynchronize(c->stream);
   free_row_scratch(c);
   dev_free(c->wn32); dev_free(c->wn64); dev_free(c->wmax_bits); dev_free(c->counts); dev_free(c->seg_off);
-  dev_free(c->chunk_off); dev_free(c->massD); dev_free(c->cntT); dev_free(c->gx); dev_free(c->gy);
+  dev_free(c->chunk_off); dev_free(c->massD); dev_free(c->dist_partial); dev_free(c->cntT); dev_free(c->gx); dev_free(c->gy);
   dev_free(c->params); dev_free(c->list_counts); dev_free(c->unit_work); dev_free(c->S); dev_free(c->T); dev_free(c->Wt);
   dev_free(c->col_range); dev_free(c->qstep); dev_free(c->qstep_max_bits); dev_free(c->H2);
   dev_free(c->GxT); dev_free(c->GyT); dev_free(c->hit_x); dev_free(c->hit_n); dev_free(c->hit_rows);
@@ -419,6 +419,29 @@ int som_bmus_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, cons
   if (!rc && is_registered_csr(c, indptr, indices, values, n)) { rc = registered_norms(c); reg = true; }
   if (rc) return rc;
   return bmu_search_csr(c, indptr, indices, values, n, codebook, bmus, reg);
+}
+
+int som_bmu_distances_dense(som_ctx *c, const float *data, int64_t n, const float *codebook, const int32_t *bmus,
+                            float *distances, double *qerror) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (!data || !codebook || !bmus) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
+  if (!distances && !qerror) return fail(c, SOM_ERR_INVALID_ARG, "distances and qerror are both NULL");
+  const int rc = check_rows(c, n);
+  if (rc) return rc;
+  SOM_LAUNCH(c, launch_bmu_distances(c, data, nullptr, nullptr, nullptr, n, codebook, bmus, distances, qerror));
+  return SOM_OK;
+}
+
+int som_bmu_distances_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values, int64_t n,
+                          int64_t nnz, const float *codebook, const int32_t *bmus, float *distances,
+                          double *qerror) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (!codebook || !bmus) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
+  if (!distances && !qerror) return fail(c, SOM_ERR_INVALID_ARG, "distances and qerror are both NULL");
+  const int rc = check_csr(c, indptr, indices, values, n, nnz);
+  if (rc) return rc;
+  SOM_LAUNCH(c, launch_bmu_distances(c, nullptr, indptr, indices, values, n, codebook, bmus, distances, qerror));
+  return SOM_OK;
 }
 
 int som_update_dense(som_ctx *c, const float *data, int64_t n, const int32_t *bmus, float *codebook,
@@ -513,7 +536,17 @@ static void schedule_defaults(const som_ctx *c, float &r0, float &rN, float &s0,
 
 int som_train(som_ctx *c, int n_epochs, float radius0, float radiusN, float scale0, float scaleN, int cooling,
               float *codebook, int32_t *bmus) {
+  return som_train_snapshots(c, n_epochs, radius0, radiusN, scale0, scaleN, cooling, codebook, bmus, 0, nullptr,
+                             nullptr, nullptr);
+}
+
+int som_train_snapshots(som_ctx *c, int n_epochs, float radius0, float radiusN, float scale0, float scaleN,
+                        int cooling, float *codebook, int32_t *bmus, int snapshots, float *umatrices,
+                        float *codebooks, int32_t *bmus_all) {
   if (!c) return SOM_ERR_INVALID_ARG;
+  if (snapshots < 0 || snapshots > 2) return fail(c, SOM_ERR_INVALID_ARG, "snapshots must be 0, 1 or 2");
+  if (snapshots >= 1 && !umatrices) return fail(c, SOM_ERR_INVALID_ARG, "umatrices is NULL");
+  if (snapshots == 2 && (!codebooks || !bmus_all)) return fail(c, SOM_ERR_INVALID_ARG, "codebooks/bmus_all is NULL");
   if (c->data_kind == 0) return fail(c, SOM_ERR_STATE, "no training data registered (som_set_data_*)");
   if (!codebook || !bmus) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
   if (n_epochs < 1) return fail(c, SOM_ERR_INVALID_ARG, "n_epochs must be >= 1");
@@ -537,6 +570,13 @@ int som_train(som_ctx *c, int n_epochs, float radius0, float radiusN, float scal
       if (!rc) rc = update_csr(c, c->d_indptr, c->d_indices, c->d_values, c->d_n, bmus, codebook);
     }
     if (rc) return rc;
+    if (snapshots >= 1) SOM_LAUNCH(c, launch_umatrix(c, codebook, umatrices + (size_t)e * c->k));
+    if (snapshots == 2) {
+      SOM_LAUNCH(c, hipMemcpyAsync(codebooks + (size_t)e * c->k * c->dim, codebook,
+                                   (size_t)c->k * c->dim * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
+      SOM_LAUNCH(c, hipMemcpyAsync(bmus_all + (size_t)e * c->d_n, bmus, (size_t)c->d_n * sizeof(int32_t),
+                                   hipMemcpyDeviceToDevice, c->stream));
+    }
   }
   return SOM_OK;
 }

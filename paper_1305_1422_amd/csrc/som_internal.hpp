@@ -55,6 +55,7 @@ struct som_ctx {
   int32_t *seg_off;       // [k+1] exclusive scan of counts
   int32_t *chunk_off;     // [k+1] exclusive scan of chunks per node
   double *massD;          // [k] neighbourhood mass per node
+  double *dist_partial;   // [1024] per-workgroup sums of the distances to the BMUs
   double *cntT;           // [2][k] count channel after the pass along x
   float *gx;              // [2*cols+1] neighbourhood factor along x, index = twice the x offset
   float *gy;              // [rows] neighbourhood factor along y
@@ -180,6 +181,10 @@ hipError_t launch_refine_lists_csr(som_ctx *c, const int64_t *indptr, const int3
                                    const float *values, const float *W, int32_t *bmus);
 hipError_t launch_rescan_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices,
                              const float *values, const float *W, int32_t *bmus);
+
+hipError_t launch_bmu_distances(som_ctx *c, const float *X, const int64_t *indptr, const int32_t *indices,
+                                const float *values, int64_t n, const float *W, const int32_t *bmus, float *dist,
+                                double *qerror);     // X != NULL: dense rows, else CSR
 
 // bmu_csr.hip
 hipError_t launch_transpose_codebook(som_ctx *c, const float *W);

@@ -112,6 +112,35 @@ class Som:
         capi.som_train(self.ctx, n_epochs, radius0, radiusN, scale0, scaleN, COOLING[cooling], self.codebook, bmus)
         return bmus
 
+    def train_snapshots(self, data, n_epochs: int, snapshots: int = 1, radius0: float = 0.0, radiusN: float = 0.0,
+                        scale0: float = 0.0, scaleN: float = 0.0, cooling: str = "linear"):
+        """train() with the interim outputs of option -s: returns (bmus, umatrices[, codebooks, bmus_all])."""
+        bmus = self._new_bmus(data)
+        if _is_csr(data):
+            capi.som_set_data_csr(self.ctx, data[0], data[1], data[2])
+        else:
+            capi.som_set_data_dense(self.ctx, data)
+        self._data = data
+        n = bmus.shape[0]
+        um = torch.empty((n_epochs, self.rows, self.cols), dtype=torch.float32, device=self.device) \
+            if snapshots >= 1 else None
+        cbs = torch.empty((n_epochs, self.k, self.dim), dtype=torch.float32, device=self.device) \
+            if snapshots == 2 else None
+        ball = torch.empty((n_epochs, n), dtype=torch.int32, device=self.device) if snapshots == 2 else None
+        capi.som_train_snapshots(self.ctx, n_epochs, radius0, radiusN, scale0, scaleN, COOLING[cooling], self.codebook,
+                                 bmus, snapshots, um, cbs, ball)
+        return (bmus, um, cbs, ball) if snapshots == 2 else (bmus, um)
+
+    def bmu_distances(self, data, bmus: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
+        """(distance of every instance to node bmus[j] [n] fp32, their mean [1] fp64), both on the device."""
+        dist = torch.empty(bmus.shape[0], dtype=torch.float32, device=self.device)
+        qe = torch.empty(1, dtype=torch.float64, device=self.device)
+        if _is_csr(data):
+            capi.som_bmu_distances_csr(self.ctx, data[0], data[1], data[2], self.codebook, bmus, dist, qe)
+        else:
+            capi.som_bmu_distances_dense(self.ctx, data, self.codebook, bmus, dist, qe)
+        return dist, qe
+
     def cool_schedule(self, n_epochs: int, radius0: float = 0.0, radiusN: float = 0.0, scale0: float = 0.0,
                       scaleN: float = 0.0, cooling: str = "linear") -> Tuple[torch.Tensor, torch.Tensor]:
         r = torch.empty(n_epochs, dtype=torch.float64, device=self.device)
