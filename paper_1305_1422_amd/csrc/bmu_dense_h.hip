@@ -79,7 +79,7 @@ __global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__rest
                                                         const float *__restrict__ wc,
                                                         const float *__restrict__ xscale,
                                                         const float *__restrict__ wscale,
-                                                        int64_t n, int k, int nK,
+                                                        int64_t n, int k, int nK, int flush_chunks,
                                                         int groups, CandView out, float *__restrict__ dump,
                                                         const int32_t *__restrict__ rows,
                                                         const int32_t *__restrict__ n_slots,
@@ -262,9 +262,10 @@ __global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__rest
 
   // Wavefronts that share a SIMD flush their accumulators in alternate chunks, so that one's
   // additions overlap the other's MFMAs: w and w + 4 of a large workgroup, or the wavefronts of two
-  // small workgroups that sit next to each other in the launch order.  An interval is at most two
-  // chunks.
-  const int flush_phase = WI == 4 ? (wave >> 2) : (int)(slot_id & 1);
+  // small workgroups that sit next to each other in the launch order.  An interval is at most
+  // flush_chunks chunks (2 or 4, see split_flush_chunks; the exact stage's margin prices it).
+  const int flush_mask = flush_chunks - 1;
+  const int flush_phase = (WI == 4 ? (wave >> 2) : (int)(slot_id & 1)) * (flush_chunks >> 1);
   bool fresh = true;
   Operands op0, op1;
   if (kAhead) read_operands(op0, 0, 0);
@@ -286,7 +287,7 @@ __global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__rest
     multiply(op1, false);
 
     const bool last_k = (kc == nK - 1);
-    fresh = last_k || ((kc + flush_phase) & 1) == 1;
+    fresh = last_k || ((kc + flush_phase) & flush_mask) == flush_mask;
     if (fresh) {
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
@@ -346,11 +347,11 @@ hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump) {
   const float *Wh = reinterpret_cast<const float *>(c->Wh);
   if (dump)
     hipLaunchKernelGGL((k_bmu_dense_h<kHWI, kHDump>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
-                       c->wn32, c->xscale, c->wscale, n, c->k, nK, groups, out, dump, nullptr, nullptr, nullptr,
+                       c->wn32, c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, dump, nullptr, nullptr, nullptr,
                        nullptr, nullptr);
   else
     hipLaunchKernelGGL((k_bmu_dense_h<kHWI, kHFilter>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
-                       c->wn32, c->xscale, c->wscale, n, c->k, nK, groups, out, dump, nullptr, nullptr, nullptr,
+                       c->wn32, c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, dump, nullptr, nullptr, nullptr,
                        nullptr, nullptr);
   return hipGetLastError();
 }
@@ -367,7 +368,7 @@ hipError_t launch_bmu_dense_h_collect(som_ctx *c, int64_t n) {
   CandView out{nullptr, nullptr, nullptr};
   hipLaunchKernelGGL((k_bmu_dense_h<kHWI, kHCollect>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
                      reinterpret_cast<const float *>(c->Xh), reinterpret_cast<const float *>(c->Wh), c->wn32,
-                     c->xscale, c->wscale, n, c->k, nK, groups, out, nullptr, c->collect_rows, c->list_counts + 1,
+                     c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, nullptr, c->collect_rows, c->list_counts + 1,
                      c->collect_thr, c->collect_cnt, c->collect_list);
   return hipGetLastError();
 }

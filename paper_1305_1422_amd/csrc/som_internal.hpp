@@ -151,6 +151,10 @@ hipError_t launch_bmu_dense_collect(som_ctx *c, const float *X, int64_t n);
 hipError_t launch_bmu_dense_dl(som_ctx *c, const float *X, int64_t n, dim3 grid, bool collect);   // bmu_dense_dl.hip
 
 // bmu_dense_h.hip, split_f16.hip
+// Chunks of 32 features a wavefront of the split-fp16 pass multiplies into its MFMA accumulators
+// before it adds them to the running totals (a power of two; the margin prices the chain length).
+// Longer chains save additions and widen the margin: measured, four chunks pay from 256 features on.
+inline int split_flush_chunks(int dim) { return dim >= 256 ? 4 : 2; }
 int bmu_dense_h_groups(const som_ctx *c, int64_t n);
 hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump);            // Xh, Wh -> candidates (or all scores)
 hipError_t launch_bmu_dense_h_collect(som_ctx *c, int64_t n);                 // rows of collect_rows -> collect_list

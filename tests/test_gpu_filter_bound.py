@@ -3,8 +3,8 @@
 The split-fp16 filter ranks nodes by scores whose distance from the exact value is bounded by
     B = u [ coef X Wm + sqrt(dim) (sx_j Wm + sw X) + 4 Wm^2 + 6 M Wm ],      u = 2^-24,
 (X = |x_j|, Wm = max_i |w'_i|, M = |mu|, sx_j / sw = the powers of two the operands were divided
-by, coef = 2 g + 28 with g = 2.5 * 12 + 9 + ceil(dim / 64) + 2), and that bound in turn prices one
-32x32x16 fp16 matrix instruction at 9 u max|product| + 2.5 u (|C| + sum |products|).  Both
+by, coef = 2 g + 28 with g = 2.5 * 6 f + 9 + ceil(dim / (32 f)) + 2, where f = 4 from 256 features on,
+else 2), and that bound in turn prices one 32x32x16 fp16 matrix instruction at 9 u max|product| + 2.5 u (|C| + sum |products|).  Both
 statements are tested here against float64 arithmetic: the instruction on random and on
 adversarial operands (one dominant term, fifteen just below the truncation point), the scores
 of the whole filter on several value distributions.  The expected values are computed in numpy
@@ -112,7 +112,8 @@ def _score_bound_case(x, w, rows, cols):
     M = np.sqrt((mu64 ** 2).sum())
     sx = _pow2_above(np.abs(x64).max(1))
     sw = float(_pow2_above(np.abs(wc64).max()))
-    g = 2.5 * 12 + 9 + np.ceil(dim / 64) + 2
+    f = 4 if dim >= 256 else 2                                     # chunks of 32 features between two flushes
+    g = 2.5 * 6 * f + 9 + np.ceil(dim / (32 * f)) + 2
     # the rounding of w - mu is part of the library's bound but not of this comparison (the exact
     # scores above start from the rounded w'), so the bound tested here is slightly larger than needed
     B = U * ((2 * g + 28) * X * Wm + np.sqrt(dim) * (sx * Wm + sw * X) + 4 * Wm ** 2 + 6 * M * Wm)
