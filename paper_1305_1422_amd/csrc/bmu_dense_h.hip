@@ -74,17 +74,15 @@ __device__ __forceinline__ f16x8 as_halves(f32x4 v) { return __builtin_bit_cast(
 // kMode: kHFilter keeps candidates per instance; kHCollect runs over the instances listed in `rows`
 // (their number is *n_slots) and appends every node whose score is at most thr[slot] to the
 // instance's list; kHDump writes every score to dump[slot * k + node] (test hook).
+// `unit` numbers the (instance tile, node group) pairs; see the decoding below.
 template <int WI, int kMode>
-__global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__restrict__ Xh, const float *__restrict__ Wh,
-                                                        const float *__restrict__ wc,
-                                                        const float *__restrict__ xscale,
-                                                        const float *__restrict__ wscale,
-                                                        int64_t n, int k, int nK, int flush_chunks,
-                                                        int groups, CandView out, float *__restrict__ dump,
-                                                        const int32_t *__restrict__ rows,
-                                                        const int32_t *__restrict__ n_slots,
-                                                        const float *__restrict__ thr, int32_t *__restrict__ cnt,
-                                                        int32_t *__restrict__ list) {
+__device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, const float *__restrict__ Wh,
+                                                 const float *__restrict__ wc, const float *__restrict__ xscale,
+                                                 const float *__restrict__ wscale, int64_t n, int k, int nK,
+                                                 int flush_chunks, int groups, CandView out, float *__restrict__ dump,
+                                                 const int32_t *__restrict__ rows, const int32_t *__restrict__ n_slots,
+                                                 const float *__restrict__ thr, int32_t *__restrict__ cnt,
+                                                 int32_t *__restrict__ list, const int64_t unit) {
   constexpr bool kCollect = kMode == kHCollect;
   constexpr bool kDump = kMode == kHDump;
   constexpr int kHTI = 64 * WI;              // instances per tile
@@ -106,8 +104,8 @@ __global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__rest
   // workgroup -> (instance tile, node group)
   const int64_t n_inst = kCollect ? (int64_t)*n_slots : n;      // slots this launch covers
   const int64_t ntiles = (n_inst + kHTI - 1) / kHTI;
-  const int xcd = blockIdx.x & 7;
-  const int64_t slot_id = blockIdx.x >> 3;
+  const int xcd = (int)(unit & 7);
+  const int64_t slot_id = unit >> 3;
   const int group = (int)(slot_id % groups);
   const int64_t tile = (slot_id / groups) * 8 + xcd;
   if (tile >= ntiles) return;        // uniform over the workgroup
@@ -324,6 +322,34 @@ __global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__rest
                         out);
 }
 
+// Filter and dump modes: one unit per workgroup.  Collect mode: the number of live instance tiles is
+// only known on the device, so a fixed grid walks the units; its size is a multiple of 8, which keeps
+// unit mod 8 = workgroup mod 8 = the XCD the decoding assumes.
+template <int WI, int kMode>
+__global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__restrict__ Xh, const float *__restrict__ Wh,
+                                                        const float *__restrict__ wc,
+                                                        const float *__restrict__ xscale,
+                                                        const float *__restrict__ wscale,
+                                                        int64_t n, int k, int nK, int flush_chunks,
+                                                        int groups, CandView out, float *__restrict__ dump,
+                                                        const int32_t *__restrict__ rows,
+                                                        const int32_t *__restrict__ n_slots,
+                                                        const float *__restrict__ thr, int32_t *__restrict__ cnt,
+                                                        int32_t *__restrict__ list) {
+  if (kMode == kHCollect) {
+    const int64_t ntiles = ((int64_t)*n_slots + 64 * WI - 1) / (64 * WI);
+    const int64_t units = (ntiles + 7) / 8 * 8 * groups;
+    for (int64_t unit = blockIdx.x; unit < units; unit += gridDim.x) {
+      bmu_dense_h_unit<WI, kMode>(Xh, Wh, wc, xscale, wscale, n, k, nK, flush_chunks, groups, out, dump, rows, n_slots,
+                                  thr, cnt, list, unit);
+      __syncthreads();               // the next unit reuses the LDS stages
+    }
+  } else {
+    bmu_dense_h_unit<WI, kMode>(Xh, Wh, wc, xscale, wscale, n, k, nK, flush_chunks, groups, out, dump, rows, n_slots,
+                                thr, cnt, list, (int64_t)blockIdx.x);
+  }
+}
+
 // Node groups per instance tile: enough workgroups for about ten rounds over the resident slots.
 int bmu_dense_h_groups(const som_ctx *c, int64_t n) {
   const int64_t tiles = (n + 64 * kHWI - 1) / (64 * kHWI);
@@ -356,14 +382,17 @@ hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump) {
   return hipGetLastError();
 }
 
-// Repeats the sweep for the instances in c->collect_rows (their number is only known on the
-// device: the grid covers the worst case and surplus workgroups leave at once).  Usually only a
-// few instance tiles are live, so the node blocks are shared out over up to 16 workgroups.
+// Repeats the sweep for the instances in c->collect_rows.  Their number is only known on the
+// device: the grid is the worst case capped at eight workgroups per CU, and the workgroups walk
+// the live units.  Usually only a few instance tiles are live, so the node blocks are shared out
+// over up to 16 workgroups.
 hipError_t launch_bmu_dense_h_collect(som_ctx *c, int64_t n) {
   const int nNB = (c->k + kTN - 1) / kTN;
   const int groups = nNB < 16 ? nNB : 16;
   const int64_t tiles = (n + 64 * kHWI - 1) / (64 * kHWI);
-  const int64_t blocks = (tiles + 7) / 8 * 8 * groups;
+  int64_t blocks = (tiles + 7) / 8 * 8 * groups;
+  if (blocks > (int64_t)c->n_cu * 8) blocks = (int64_t)c->n_cu * 8;
+  blocks = (blocks + 7) / 8 * 8;
   const int nK = (c->dim + 31) / 32;
   CandView out{nullptr, nullptr, nullptr};
   hipLaunchKernelGGL((k_bmu_dense_h<kHWI, kHCollect>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,

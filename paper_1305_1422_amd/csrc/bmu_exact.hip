@@ -74,12 +74,17 @@ __global__ __launch_bounds__(256) void k_certify(CandView cand, int groups, cons
                                                  int32_t *__restrict__ list_counts, UnitWork work) {
   const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (j >= n) return;
+  static_assert(kCand == 4, "the candidate lists are read as 16-byte vectors");
+  const float4 *val4 = reinterpret_cast<const float4 *>(cand.val);
+  const int4 *idx4 = reinterpret_cast<const int4 *>(cand.idx);
   float smin = INFINITY, omin = INFINITY;
   for (int q = 0; q < groups; ++q) {
-    const int64_t base = ((int64_t)q * n + j) * kCand;
-#pragma unroll
-    for (int t = 0; t < kCand; ++t)
-      if ((unsigned)cand.idx[base + t] < (unsigned)k) smin = fminf(smin, cand.val[base + t]);
+    const float4 v = val4[(int64_t)q * n + j];
+    const int4 id = idx4[(int64_t)q * n + j];
+    if ((unsigned)id.x < (unsigned)k) smin = fminf(smin, v.x);
+    if ((unsigned)id.y < (unsigned)k) smin = fminf(smin, v.y);
+    if ((unsigned)id.z < (unsigned)k) smin = fminf(smin, v.z);
+    if ((unsigned)id.w < (unsigned)k) smin = fminf(smin, v.w);
     omin = fminf(omin, cand.over[(int64_t)q * n + j]);
   }
   const double margin = score_margin(mm, j, (double)xn32[j], (double)__uint_as_float(*wmax_bits), (double)*mu_norm2);
@@ -87,12 +92,14 @@ __global__ __launch_bounds__(256) void k_certify(CandView cand, int groups, cons
   int keep[kCand];
   int cnt = 0;
   for (int q = 0; q < groups; ++q) {
-    const int64_t base = ((int64_t)q * n + j) * kCand;
+    const float4 v4 = val4[(int64_t)q * n + j];
+    const int4 id4 = idx4[(int64_t)q * n + j];
+    const float v[kCand] = {v4.x, v4.y, v4.z, v4.w};
+    const int id[kCand] = {id4.x, id4.y, id4.z, id4.w};
 #pragma unroll
     for (int t = 0; t < kCand; ++t) {
-      const int id = cand.idx[base + t];
-      if ((unsigned)id < (unsigned)k && (double)cand.val[base + t] <= thr) {
-        if (cnt < kCand) keep[cnt] = id;
+      if ((unsigned)id[t] < (unsigned)k && (double)v[t] <= thr) {
+        if (cnt < kCand) keep[cnt] = id[t];
         ++cnt;
       }
     }

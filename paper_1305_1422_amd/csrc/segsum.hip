@@ -63,39 +63,68 @@ __global__ __launch_bounds__(256) void k_segment_bounds(const int32_t *__restric
   if (b == k - 1) seg_off[k] = (int32_t)n;
 }
 
-// Exclusive scan of in[0..len) into out[0..len], out[len] = total.  One workgroup of 1024.
+// Exclusive scan of in[0..len) into out[0..len], out[len] = total.  One workgroup of 1024 walks the
+// array in steps of 4096: a thread takes four consecutive elements (one 16-byte access when the
+// arrays allow it), the wavefronts scan the thread sums with shuffles and the sixteen wavefront
+// totals are combined through LDS.
 // `transform` > 0: scan ceil(in / transform) instead of in (chunks per node).
-// in and out may be the same array.
+// in and out may be the same array (a thread reads its elements before it writes them).
 __global__ __launch_bounds__(1024) void k_scan_exclusive(const int32_t *in, int32_t *out, int len, int transform) {
-  __shared__ int s_wave[16];
-  __shared__ int s_carry;
+  __shared__ int s_wave[2][16];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (tid == 0) s_carry = 0;
-  __syncthreads();
-  for (int base = 0; base < len; base += 1024) {
-    const int i = base + tid;
-    int v = 0;
-    if (i < len) {
-      v = in[i];
-      if (transform > 0) v = (v + transform - 1) / transform;
+  const bool vec = (len & 3) == 0 && (((uintptr_t)in | (uintptr_t)out) & 15) == 0;
+  int carry = 0;
+  int phase = 0;
+  for (int base = 0; base < len; base += 4096, phase ^= 1) {
+    const int i = base + 4 * tid;
+    int v[4] = {0, 0, 0, 0};
+    if (vec) {
+      if (i < len) {
+        const int4 q = *reinterpret_cast<const int4 *>(in + i);
+        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (i + e < len) v[e] = in[i + e];
     }
-    int inc = v;
+    if (transform > 0) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = (v[e] + transform - 1) / transform;
+    }
+    const int sum = (v[0] + v[1]) + (v[2] + v[3]);
+    int inc = sum;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
       const int t = __shfl_up(inc, o, 64);
       if (lane >= o) inc += t;
     }
-    if (lane == 63) s_wave[wave] = inc;
-    __syncthreads();
-    int wave_base = 0;
-    for (int w = 0; w < wave; ++w) wave_base += s_wave[w];
-    const int carry = s_carry;
-    if (i < len) out[i] = carry + wave_base + inc - v;
-    __syncthreads();
-    if (tid == 1023) s_carry = carry + wave_base + inc;
-    __syncthreads();
+    if (lane == 63) s_wave[phase][wave] = inc;
+    __syncthreads();                       // one barrier per step: the totals alternate between two rows
+    int before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+      const int t = s_wave[phase][w];
+      before += w < wave ? t : 0;
+      all += t;
+    }
+    int run = carry + before + inc - sum;
+    if (vec) {
+      if (i < len) {
+        int4 q;
+        q.x = run; q.y = run + v[0]; q.z = q.y + v[1]; q.w = q.z + v[2];
+        *reinterpret_cast<int4 *>(out + i) = q;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (i + e < len) out[i + e] = run;
+        run += v[e];
+      }
+    }
+    carry += all;
   }
-  if (tid == 0) out[len] = s_carry;
+  if (tid == 0) out[len] = carry;
 }
 
 // ---------------------------------------------------------------- stable radix sort

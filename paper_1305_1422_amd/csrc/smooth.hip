@@ -95,9 +95,18 @@ __global__ __launch_bounds__(256) void k_count_pass_y(const double *__restrict__
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < k; i += gridDim.x * blockDim.x) {
     const int yi = i / cols, x = i - yi * cols;
     const double *img = cntT + (hex ? (int64_t)(yi & 1) * k : 0);
-    double s = 0.0;
-    for (int yb = 0; yb < rows; ++yb) s += (double)gy[row_offset(yi, yb, toroid, rows)] * img[yb * cols + x];
-    massD[i] = s;
+    // four running sums: the loads of four source rows are in flight together (a single chain of
+    // dependent fp64 additions made this small kernel latency-bound)
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    int yb = 0;
+    for (; yb + 4 <= rows; yb += 4) {
+      s0 += (double)gy[row_offset(yi, yb, toroid, rows)] * img[yb * cols + x];
+      s1 += (double)gy[row_offset(yi, yb + 1, toroid, rows)] * img[(yb + 1) * cols + x];
+      s2 += (double)gy[row_offset(yi, yb + 2, toroid, rows)] * img[(yb + 2) * cols + x];
+      s3 += (double)gy[row_offset(yi, yb + 3, toroid, rows)] * img[(yb + 3) * cols + x];
+    }
+    for (; yb < rows; ++yb) s0 += (double)gy[row_offset(yi, yb, toroid, rows)] * img[yb * cols + x];
+    massD[i] = (s0 + s1) + (s2 + s3);
   }
 }
 
