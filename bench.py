@@ -150,7 +150,7 @@ def main() -> int:
                         "traffic": MEASURED_TRAFFIC_BYTES.get((w.config, args.filter)), "avg_launch_ms": dom_ms}
         else:
             # three fp16 matrix products per (instance, node, feature): hi*hi + hi*lo + lo*hi
-            roofline = {"bound": "mfma", "kernel": "k_bmu_dense_h<false> (BMU filter pass, 3 fp16 MFMAs on split fp32 operands)",
+            roofline = {"bound": "mfma", "kernel": "k_bmu_dense_h<2, 0> (BMU filter pass, 3 fp16 MFMAs on split fp32 operands)",
                         "achieved": 3.0 * fp32_equiv, "peak": PEAK_FP16_MFMA_TFLOPS, "unit": "TFLOP/s",
                         "frac": 3.0 * fp32_equiv / PEAK_FP16_MFMA_TFLOPS,
                         "traffic": MEASURED_TRAFFIC_BYTES.get((w.config, args.filter)), "avg_launch_ms": dom_ms,
