@@ -125,11 +125,21 @@ def main() -> int:
     torch.cuda.synchronize()
     capi.som_profile_enable(som.ctx, True)
     capi.som_profile_read(som.ctx)          # clear
+    # one event per step on the stream the library launches on (torch's current stream): the
+    # per-epoch figures below come from these, the headline value from the host clock around the
+    # whole timed region
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
     for s in range(args.steps):
+        marks[s].record()
         step(args.warmup + s)
+    marks[args.steps].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    per_epoch = [[] for _ in range(w.epochs)]
+    for s in range(args.steps):
+        per_epoch[(args.warmup + s) % w.epochs].append(marks[s].elapsed_time(marks[s + 1]))
+    epoch_ms_median = [float(np.median(v)) if v else None for v in per_epoch]
     prof = capi.som_profile_read(som.ctx)
     capi.som_profile_enable(som.ctx, False)
     refined, collected, rescanned = som.stats()
@@ -183,6 +193,7 @@ def main() -> int:
         "gflops_epoch": 2.0 * work / (dt / args.steps) / 1e9,
         "frac_fp32_mfma_peak_whole_epoch": 2.0 * work / (dt / args.steps) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
         "stage_ms": stage_ms,
+        "epoch_ms_median": epoch_ms_median,      # by position in the radius schedule (epoch 0 = widest radius)
         "last_step_exact_rows": {"refined": refined, "collected": collected, "rescanned": rescanned},
         "roofline": roofline,
     }

@@ -204,6 +204,7 @@ static int prepare_dense(som_ctx *c, const float *X, int64_t n, const float *W, 
     c->d_split_valid = have_xn ? 1 : 0;
   }
   SOM_LAUNCH(c, launch_center_codebook(c, W, true, false));
+  if (c->nb_function == SOM_NEIGHBORHOOD_BUBBLE) SOM_LAUNCH(c, launch_mask_duplicate_rows(c, W));
   if (split) SOM_LAUNCH(c, launch_split_rows_f16(c, c->Wc, c->k, c->wmax_bits + 1, c->Wh, c->wscale));
   SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 3));
   return SOM_OK;
@@ -245,6 +246,7 @@ static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indi
   SOM_LAUNCH(c, launch_codebook_means_and_steps(c, W));
   SOM_LAUNCH(c, launch_vec_sqnorm(c, c->mu, c->dim, c->mu_norm2));
   SOM_LAUNCH(c, launch_center_codebook(c, W, false, true));
+  if (c->nb_function == SOM_NEIGHBORHOOD_BUBBLE) SOM_LAUNCH(c, launch_mask_duplicate_rows(c, W));
   SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, kListCounts));
   {
     StageTimer t(c, 1);
@@ -382,7 +384,8 @@ void som_destroy(som_ctx *c) {
   (void)hipStreamSynchronize(c->stream);
   free_row_scratch(c);
   dev_free(c->wn32); dev_free(c->wn64); dev_free(c->wmax_bits); dev_free(c->counts); dev_free(c->seg_off);
-  dev_free(c->chunk_off); dev_free(c->massD); dev_free(c->dist_partial); dev_free(c->cntT); dev_free(c->gx); dev_free(c->gy);
+  dev_free(c->chunk_off); dev_free(c->massD); dev_free(c->dist_partial); dev_free(c->row_hash); dev_free(c->dedup_keys);
+  dev_free(c->dedup_lowest); dev_free(c->cntT); dev_free(c->gx); dev_free(c->gy);
   dev_free(c->params); dev_free(c->list_counts); dev_free(c->unit_work); dev_free(c->S); dev_free(c->T); dev_free(c->Wt);
   dev_free(c->col_range); dev_free(c->qstep); dev_free(c->qstep_max_bits); dev_free(c->H2);
   dev_free(c->GxT); dev_free(c->GyT); dev_free(c->hit_x); dev_free(c->hit_n); dev_free(c->hit_rows);
@@ -610,6 +613,17 @@ int som_set_neighborhood(som_ctx *c, int function, int compact_support) {
     const size_t classes = c->grid_type == SOM_GRID_HEXAGONAL ? 3 : 1;
     if (!dev_alloc(&c->H2, classes * c->rows * width))
       return fail(c, SOM_ERR_ALLOC, "cannot allocate the neighbourhood table");
+  }
+  if (function == SOM_NEIGHBORHOOD_BUBBLE && !c->row_hash) {
+    // a bubble makes whole classes of nodes bit-identical: the searches take the duplicates out first
+    int slots = 64;
+    while (slots < 2 * c->k) slots *= 2;
+    if (!(dev_alloc(&c->row_hash, (size_t)c->k) && dev_alloc(&c->dedup_keys, (size_t)slots) &&
+          dev_alloc(&c->dedup_lowest, (size_t)slots))) {
+      dev_free(c->row_hash); dev_free(c->dedup_keys); dev_free(c->dedup_lowest);
+      return fail(c, SOM_ERR_ALLOC, "cannot allocate the duplicate-row table");
+    }
+    c->dedup_slots = slots;
   }
   c->nb_function = function;
   c->nb_compact = compact_support ? 1 : 0;

@@ -56,6 +56,10 @@ struct som_ctx {
   int32_t *chunk_off;     // [k+1] exclusive scan of chunks per node
   double *massD;          // [k] neighbourhood mass per node
   double *dist_partial;   // [1024] per-workgroup sums of the distances to the BMUs
+  uint64_t *row_hash;     // [k] hashes of the code-book rows (bubble neighbourhood only, lazily allocated)
+  uint64_t *dedup_keys;   // [dedup_slots] open-addressing table of those hashes
+  int32_t *dedup_lowest;  // [dedup_slots] lowest node index per key
+  int dedup_slots;        // power of two >= 2 k
   double *cntT;           // [2][k] count channel after the pass along x
   float *gx;              // [2*cols+1] neighbourhood factor along x, index = twice the x offset
   float *gy;              // [rows] neighbourhood factor along y
@@ -189,6 +193,9 @@ hipError_t launch_rescan_csr(som_ctx *c, const int64_t *indptr, const int32_t *i
 hipError_t launch_bmu_distances(som_ctx *c, const float *X, const int64_t *indptr, const int32_t *indices,
                                 const float *values, int64_t n, const float *W, const int32_t *bmus, float *dist,
                                 double *qerror);     // X != NULL: dense rows, else CSR
+
+// dedup.hip
+hipError_t launch_mask_duplicate_rows(som_ctx *c, const float *W);   // wn32[i] = +inf for rows equal to a lower-indexed row
 
 // bmu_csr.hip
 hipError_t launch_transpose_codebook(som_ctx *c, const float *W);

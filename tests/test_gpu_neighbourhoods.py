@@ -91,3 +91,57 @@ def test_switching_back_to_the_gaussian(oracle):
     assert torch.equal(a.codebook, b.codebook)
     a.close()
     b.close()
+
+
+@pytest.mark.parametrize("kind", ["dense", "csr"])
+def test_bubble_plateaus_do_not_reach_the_full_rescan(oracle, kind):
+    """Several epochs with a wide bubble: whole regions of the map end up with bit-identical weight vectors.
+    The search takes the duplicates out before the filter pass, so no instance needs the exact rescan of all
+    nodes, and the BMUs are still the lowest index of the best class."""
+    from paper_1305_1422_amd import Som
+    rows, cols = 24, 25                                    # 600 nodes, far more than a collected list holds
+    if kind == "dense":
+        n, dim = 1500, 96
+        X = np.random.default_rng(36).random((n, dim)).astype(np.float32)
+        Xd = P.to_dev(X)
+    else:
+        n, dim = 900, 1200
+        X = sparse_zipf_csr(n, dim, 37, mean_len=30.0, max_len=90)
+        Xd = P.csr_to_dev(X)
+    W0 = np.random.default_rng(38).random((rows * cols, dim)).astype(np.float32)
+    som = Som(rows, cols, dim, "planar", "square", codebook=torch.from_numpy(W0))
+    som.set_neighborhood("bubble")
+    duplicates_seen = 0
+    for radius in (40.0, 12.0, 6.0, 3.0):                  # 40 covers the map: every updated node = the global mean
+        W_in = som.codebook.cpu().numpy().copy()
+        b = som.train_epoch(Xd, radius).cpu().numpy()
+        duplicates_seen = max(duplicates_seen, rows * cols - len(np.unique(W_in, axis=0)))
+        assert som.stats()[2] == 0, f"radius {radius}: {som.stats()[2]} instances fell through to the rescan"
+        if kind == "dense":
+            P.check_bmus_dense(oracle, X, W_in, b)
+        else:
+            P.check_bmus_csr(oracle, X, dim, W_in, b)
+    assert duplicates_seen > 300, "the schedule produced no large plateau: the test misses its case"
+    som.close()
+
+
+def test_duplicate_rows_with_equal_hash_slots_are_compared_bit_by_bit(oracle):
+    """Rows that differ in one bit (here: -0.0 against +0.0, equal as numbers) are not the same row to the
+    duplicate search; the result is the exact argmin with the lowest index either way."""
+    from paper_1305_1422_amd import Som
+    rng = np.random.default_rng(39)
+    rows, cols, dim, n = 6, 7, 33, 200
+    W = rng.random((rows * cols, dim)).astype(np.float32)
+    W[:, 5] = 0.0
+    W[10] = W[3]
+    W[20] = W[3]
+    W[20, 5] = -0.0                                        # bitwise different, numerically identical
+    W[30] = W[12]
+    X = (W[rng.integers(0, rows * cols, n)] + rng.normal(0, 1e-3, (n, dim))).astype(np.float32)
+    som = Som(rows, cols, dim, codebook=torch.from_numpy(W))
+    som.set_neighborhood("bubble")
+    b = som.bmus(P.to_dev(X)).cpu().numpy()
+    want = oracle.bmu_dense(X, W)
+    assert np.array_equal(b, want)
+    assert not np.isin(b, [10, 20, 30]).any()
+    som.close()
