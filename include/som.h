@@ -110,6 +110,11 @@ int som_train_epoch_csr(som_ctx *ctx, const int64_t *indptr, const int32_t *indi
 /*
  * som_bmus_dense / som_bmus_csr - BMU search only (BMU equation), code book unchanged:
  * the mapping of data onto a trained map.  Arguments as in the epoch calls.
+ * Non-finite input is not an error: an instance with a NaN or infinite component has no
+ * finite distance to any node and is mapped to node 0, as a plain scan with a strict
+ * comparison gives; a node with such a component is never chosen.  (In an epoch call such an
+ * instance then enters the sums of node 0 and the non-finite values spread through the
+ * update, as the batch equation says.)
  */
 int som_bmus_dense(som_ctx *ctx, const float *data, int64_t n, const float *codebook, int32_t *bmus);
 int som_bmus_csr(som_ctx *ctx, const int64_t *indptr, const int32_t *indices, const float *values,

@@ -191,7 +191,7 @@ __global__ __launch_bounds__(256) void k_refine_dense(const float *__restrict__ 
       const double d2 = sqdist_dense_wave(X + j * dim, W + (int64_t)i * dim, dim, lane);
       if (d2 < best || (d2 == best && i < arg)) { best = d2; arg = i; }
     }
-    if (lane == 0) bmus[j] = arg;
+    if (lane == 0) bmus[j] = arg == 0x7fffffff ? 0 : arg;      // no finite distance (non-finite input): node 0, as a plain scan gives
   }
 }
 
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(256) void k_refine_lists_dense(const float *__restr
       const double d2 = sqdist_dense_wave(X + j * dim, W + (int64_t)i * dim, dim, lane);
       if (d2 < best || (d2 == best && i < arg)) { best = d2; arg = i; }
     }
-    if (lane == 0) bmus[j] = arg;
+    if (lane == 0) bmus[j] = arg == 0x7fffffff ? 0 : arg;      // no finite distance (non-finite input): node 0, as a plain scan gives
   }
 }
 
@@ -281,7 +281,7 @@ __global__ __launch_bounds__(256) void k_refine_csr(const int64_t *__restrict__ 
       const double d2 = sqdist_csr_wave(indices + s, values + s, len, W + (int64_t)i * dim, wn64[i], dim, lane);
       if (d2 < best || (d2 == best && i < arg)) { best = d2; arg = i; }
     }
-    if (lane == 0) bmus[j] = arg;
+    if (lane == 0) bmus[j] = arg == 0x7fffffff ? 0 : arg;      // no finite distance (non-finite input): node 0, as a plain scan gives
   }
 }
 

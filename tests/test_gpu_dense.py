@@ -268,3 +268,27 @@ def test_registered_data_gives_identical_epochs(oracle):
         assert np.array_equal(a.codebook.cpu().numpy(), b.codebook.cpu().numpy())
         b.bmus(other)                                  # overwrites the cached norms; must be noticed
     a.close(); b.close()
+
+
+def test_non_finite_instances_do_not_leave_the_index_range(oracle):
+    """NaN and infinite components: such an instance has no finite distance to any node and a plain scan
+    (strict <, starting from +inf) leaves it at node 0; the other instances are unaffected."""
+    from paper_1305_1422_amd import Som
+    rng = np.random.default_rng(77)
+    n, dim, rows, cols = 700, 70, 14, 13
+    X = rng.random((n, dim)).astype(np.float32)
+    W = rng.random((rows * cols, dim)).astype(np.float32)
+    bad = {5: np.nan, 130: np.inf, 131: -np.inf, 699: np.nan}
+    for j, v in bad.items():
+        X[j, (3 * j) % dim] = v
+    X[400, :] = np.inf
+    som = Som(rows, cols, dim, codebook=torch.from_numpy(W))
+    b = som.bmus(P.to_dev(X)).cpu().numpy()
+    want = oracle.bmu_dense(X, W)
+    assert b.min() >= 0 and b.max() < rows * cols
+    assert np.array_equal(b, want)
+    assert all(b[j] == 0 for j in list(bad) + [400])
+    # a whole epoch goes through as well: the update must not fault on such rows (node 0 inherits them)
+    som.train_epoch(P.to_dev(X), 2.0)
+    torch.cuda.synchronize()
+    som.close()

@@ -133,3 +133,22 @@ def test_train_csr_schedule_runs_and_matches_last_epoch(oracle):
         b.train_epoch(csr_d, oracle.cool(4.0, 1.0, E, e, oracle.LINEAR))      # 4, 3, 2, 1: exact in fp32
     np.testing.assert_allclose(a.codebook.cpu().numpy(), b.codebook.cpu().numpy(), rtol=1e-5, atol=1e-6)
     a.close(); b.close()
+
+
+def test_non_finite_values_do_not_leave_the_index_range(oracle):
+    from paper_1305_1422_amd import Som
+    n, dim, rows, cols = 300, 400, 9, 9
+    indptr, indices, values = sparse_zipf_csr(n, dim, 78, mean_len=15.0, max_len=40)
+    values = values.copy()
+    bad_rows = [0, 17, 299]
+    for j, v in zip(bad_rows, (np.nan, np.inf, -np.inf)):
+        values[indptr[j]] = v
+    csr = (indptr, indices, values)
+    W = np.random.default_rng(79).random((rows * cols, dim)).astype(np.float32)
+    som = Som(rows, cols, dim, codebook=torch.from_numpy(W))
+    b = som.bmus(P.csr_to_dev(csr)).cpu().numpy()
+    want = oracle.bmu_csr(csr, dim, W)
+    assert b.min() >= 0 and b.max() < rows * cols
+    assert np.array_equal(b, want)
+    assert all(b[j] == 0 for j in bad_rows)
+    som.close()
