@@ -29,7 +29,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side bytes per launch of the dominant kernel (fetched + written), from the two rocprofv3 --pmc
 # runs (FETCH_SIZE, WRITE_SIZE, scaled by the copy calibration) summarised under profiles/;
 # measured once per kernel version, not during this run.  Workloads without a counter run: None.
-MEASURED_TRAFFIC_BYTES = {(2, "split_f16"): 8.846e9 + 0.025e9, (2, "fp32"): 8.49e9 + 0.025e9,
+MEASURED_TRAFFIC_BYTES = {(2, "split_f16"): 3.438e9 + 0.036e9, (2, "fp32"): 8.49e9 + 0.025e9,
                           (4, "split_f16"): 14.327e9 + 0.092e9, (4, "fp32"): 14.327e9 + 0.092e9}
 
 
