@@ -207,7 +207,7 @@ hipError_t launch_bmu_csr_sliced(som_ctx *c, const int64_t *indptr, const int32_
 hipError_t launch_sort_by_bmu(som_ctx *c, const int32_t *bmus, int64_t n);   // -> sort_val[0] = row ids
 hipError_t launch_accumulate_dense(som_ctx *c, const float *X, int64_t n);   // -> S, counts
 hipError_t launch_accumulate_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices,
-                                 const float *values, int64_t n, const int32_t *bmus);
+                                 const float *values, int64_t n, const int32_t *bmus);   // -> S, counts
 
 // smooth.hip
 hipError_t launch_epoch_params(som_ctx *c, int epoch, int n_epochs, double r0, double rN, double s0,

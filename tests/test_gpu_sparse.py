@@ -152,3 +152,23 @@ def test_non_finite_values_do_not_leave_the_index_range(oracle):
     assert np.array_equal(b, want)
     assert all(b[j] == 0 for j in bad_rows)
     som.close()
+
+
+@pytest.mark.parametrize("dim", [16384, 16385])
+def test_update_csr_at_the_row_length_where_the_accumulation_changes(oracle, dim):
+    """Rows of up to 16,384 columns are summed in LDS per node, longer ones with global atomics; both sides
+    of the switch, with one node that holds more instances than one chunk."""
+    from paper_1305_1422_amd import Som
+    n, rows, cols = 700, 3, 4
+    csr = sparse_zipf_csr(n, dim, 43, mean_len=12.0, max_len=40)
+    rng = np.random.default_rng(44)
+    W = rng.random((rows * cols, dim)).astype(np.float32)
+    bmus = rng.integers(0, rows * cols, size=n).astype(np.int32)
+    bmus[:400] = 5
+    bmus[bmus == 9] = 2                                    # node 9 is chosen by nobody
+    som = Som(rows, cols, dim, "planar", "square", codebook=torch.from_numpy(W))
+    som.update(P.csr_to_dev(csr), P.to_dev(bmus), 1.0)
+    torch.cuda.synchronize()
+    S, C = oracle.accumulate_csr(csr, dim, bmus, rows * cols)
+    P.check_codebook(oracle, S, C, W, som.codebook.cpu().numpy(), rows, cols, oracle.PLANAR, oracle.SQUARE, 1.0)
+    som.close()
