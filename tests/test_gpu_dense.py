@@ -292,3 +292,17 @@ def test_non_finite_instances_do_not_leave_the_index_range(oracle):
     som.train_epoch(P.to_dev(X), 2.0)
     torch.cuda.synchronize()
     som.close()
+
+
+@pytest.mark.parametrize("dim", [31, 32, 33, 63, 64, 65, 96, 127, 129, 255, 257, 513])
+def test_feature_counts_around_the_chunk_boundaries(oracle, dim):
+    """The filter pass walks the features in chunks of 32 and pads the last one; the per-node sums read rows
+    as 16-byte vectors when dim % 4 == 0 and element by element otherwise."""
+    from paper_1305_1422_amd import Som
+    rng = np.random.default_rng(5000 + dim)
+    n, rows, cols = 333, 6, 7
+    X = rng.normal(0.0, 1.0, (n, dim)).astype(np.float32)
+    W = rng.normal(0.0, 1.0, (rows * cols, dim)).astype(np.float32)
+    som = Som(rows, cols, dim, "toroid", "hexagonal", codebook=torch.from_numpy(W))
+    P.epoch_parity_dense(oracle, som, X, P.to_dev(X), 2.0, P.MAP["toroid"], P.GRID["hexagonal"])
+    som.close()
