@@ -2,10 +2,12 @@
 // of one epoch are enqueued.  See include/som.h for the contract of every entry point.
 //
 // One epoch (paper: "Self-organizing maps in batch mode"; API section, trainOneEpoch):
-//   node norms -> fp32 BMU filter (MFMA, or CSR gather) -> certify / exact refine / exact rescan
-//   -> counts, stable sort by BMU, chunked per-node sums -> neighbourhood smoothing in two
-//   passes with the division fused into the second.
-// Nothing in here synchronises the stream except som_destroy and som_get_stats.
+//   node norms and centring -> BMU filter pass (split-fp16 or fp32 MFMA, or the CSR sweep) ->
+//   certify / exact refine / second sweep with exact comparison of the collected lists / exact
+//   rescan -> stable sort by BMU, chunked per-node sums -> neighbourhood smoothing (two passes
+//   for the Gaussian, one over a weight table for the others) with the division fused in.
+// The stream is synchronised only where scratch has to grow (the old buffers may still be in
+// use), by som_destroy, som_get_stats and som_profile_read.
 #include "som_internal.hpp"
 
 #include <math.h>
