@@ -47,7 +47,7 @@ enum { SOM_NEIGHBORHOOD_GAUSSIAN = 0, SOM_NEIGHBORHOOD_BUBBLE = 1 };   /* option
 
 /*
  * som_init - create a context for a rows x cols map over dim-dimensional data.
- * (Paper: options -x, -y, -g, -m, -c; "The default is random initialization".)
+ * (Paper: options -x, -y, -g, -m, -c; without an initial code book the map starts from random values.)
  *   out        host pointer that receives the context.
  *   codebook   device [rows*cols][dim] fp32.  seed == 0: left as the caller filled it
  *              (option -c, initial code book).  seed != 0: overwritten with uniform [0,1)

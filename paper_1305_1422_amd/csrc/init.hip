@@ -1,4 +1,4 @@
-// Random initial code book (paper: option -c, "The default is random initialization").
+// Random initial code book (paper: option -c; without an initial code book the map starts from random values).
 // Element e of the code book gets a uniform [0,1) value from a counter-based generator:
 // a 64-bit mix (splitmix64 finaliser) of seed + e * golden-ratio increment, top 24 bits.
 #include "som_internal.hpp"
