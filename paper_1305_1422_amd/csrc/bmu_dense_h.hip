@@ -219,6 +219,7 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
   // every fourth instruction only.  The small cross products go first.  `fresh`: the accumulators
   // start from C = 0 as an operand of the instruction itself, which spares clearing 64 registers.
   auto multiply = [&](const Operands &o, bool fresh) {
+    __builtin_amdgcn_s_setprio(1);      // the wavefront that has operands ready goes first on the SIMD (-1.6 %)
     if (fresh) {
       const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -243,6 +244,7 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
 #pragma unroll
       for (int ni = 0; ni < 2; ++ni)
         acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g1[mi], o.h1[ni], acc[mi][ni], 0, 0, 0);
+    __builtin_amdgcn_s_setprio(0);
   };
 
   // Pipeline with three stages.  Chunk c is loaded into stage c % 3 during iteration c - 2 and every
