@@ -136,7 +136,7 @@ __global__ __launch_bounds__(256) void k_bmu_csr_sliced(const int64_t *__restric
       if (p0 + lane < len) {
         c = indices[rs + p0 + lane];
         c = c < 0 ? 0 : (c >= dim ? dim - 1 : c);
-        v = values[rs + p0 + lane] * qstep[c];
+        v = qstep ? values[rs + p0 + lane] * qstep[c] : values[rs + p0 + lane];
         vq_abs += fabsf(v);
       }
       const int m = min(64, len - p0);
@@ -235,7 +235,7 @@ static void launch_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indi
   const UnitWork work{c->csr_sweeps, c->unit_cap, c->unit_work, c->list_counts + kUnitCounts, c->collect_list};
 #define SOM_SLICED(A)                                                                                              \
   hipLaunchKernelGGL((k_bmu_csr_sliced<A, kCollect>), grid, dim3(256), 0, c->stream, indptr, indices, values,        \
-                     reinterpret_cast<const int16_t *>(c->Wt), c->kpad, c->csr_sweeps, c->qstep, c->wn32, n, c->k,  \
+                     reinterpret_cast<const int16_t *>(c->Wt), c->kpad, c->csr_sweeps, nullptr, c->wn32, n, c->k,   \
                      c->dim, out, c->row_q, c->collect_rows, work, c->collect_thr, c->collect_cnt,    \
                      c->collect_list)
   switch (c->csr_acc) {
@@ -257,6 +257,29 @@ static void launch_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indi
     default: SOM_SLICED(16); break;
   }
 #undef SOM_SLICED
+}
+
+// Values of the nonzeros times the quantisation step of their column: once per search instead of once
+// per node range and slice.
+__global__ __launch_bounds__(256) void k_scale_values(const int32_t *__restrict__ indices,
+                                                      const float *__restrict__ values, int64_t nnz, int dim,
+                                                      const float *__restrict__ qstep, float *__restrict__ out) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += stride) {
+    int c = indices[p];
+    c = c < 0 ? 0 : (c >= dim ? dim - 1 : c);
+    out[p] = values[p] * qstep[c];
+  }
+}
+
+hipError_t launch_scale_values(som_ctx *c, const int32_t *indices, const float *values, int64_t nnz) {
+  if (!c->vq || c->vq_cap < nnz) return hipErrorInvalidValue;
+  if (nnz < 1) return hipSuccess;
+  int64_t cb = (nnz + 255) / 256;
+  if (cb > (int64_t)c->n_cu * 16) cb = (int64_t)c->n_cu * 16;
+  hipLaunchKernelGGL(k_scale_values, dim3((unsigned)cb), dim3(256), 0, c->stream, indices, values, nnz, c->dim,
+                     c->qstep, c->vq);
+  return hipGetLastError();
 }
 
 hipError_t launch_bmu_csr_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,

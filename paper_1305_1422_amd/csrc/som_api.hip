@@ -234,7 +234,14 @@ static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *
 }
 
 static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
-                          int64_t n, const float *W, int32_t *bmus, bool have_xn) {
+                          int64_t n, int64_t nnz, const float *W, int32_t *bmus, bool have_xn) {
+  if (nnz > c->vq_cap) {
+    (void)hipStreamSynchronize(c->stream);
+    dev_free(c->vq);
+    c->vq_cap = 0;
+    if (!dev_alloc(&c->vq, (size_t)nnz)) return fail(c, SOM_ERR_ALLOC, "cannot allocate %lld scaled values", (long long)nnz);
+    c->vq_cap = nnz;
+  }
   int rc = ensure_transposed(c);
   if (!rc) rc = ensure_candidates(c, n, false);
   if (rc) return rc;
@@ -253,12 +260,13 @@ static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indi
   {
     StageTimer t(c, 1);
     SOM_LAUNCH(c, launch_transpose_codebook(c, W));
-    SOM_LAUNCH(c, launch_bmu_csr_sliced(c, indptr, indices, values, n, false));
+    SOM_LAUNCH(c, launch_scale_values(c, indices, values, nnz));
+    SOM_LAUNCH(c, launch_bmu_csr_sliced(c, indptr, indices, c->vq, n, false));
   }
   StageTimer t(c, 2);
   SOM_LAUNCH(c, launch_certify(c, n, 8 * c->csr_sweeps, kCertifyCsr, indptr, bmus));
   SOM_LAUNCH(c, launch_refine_csr(c, indptr, indices, values, W, bmus));
-  SOM_LAUNCH(c, launch_bmu_csr_sliced(c, indptr, indices, values, n, true));
+  SOM_LAUNCH(c, launch_bmu_csr_sliced(c, indptr, indices, c->vq, n, true));
   SOM_LAUNCH(c, launch_refine_lists_csr(c, indptr, indices, values, W, bmus));
   SOM_LAUNCH(c, launch_rescan_csr(c, indptr, indices, values, W, bmus));
   return SOM_OK;
@@ -388,7 +396,7 @@ void som_destroy(som_ctx *c) {
   dev_free(c->wn32); dev_free(c->wn64); dev_free(c->wmax_bits); dev_free(c->counts); dev_free(c->seg_off);
   dev_free(c->chunk_off); dev_free(c->massD); dev_free(c->dist_partial); dev_free(c->row_hash); dev_free(c->dedup_keys);
   dev_free(c->dedup_lowest); dev_free(c->cntT); dev_free(c->gx); dev_free(c->gy);
-  dev_free(c->params); dev_free(c->list_counts); dev_free(c->unit_work); dev_free(c->S); dev_free(c->T); dev_free(c->Wt);
+  dev_free(c->params); dev_free(c->list_counts); dev_free(c->unit_work); dev_free(c->vq); dev_free(c->S); dev_free(c->T); dev_free(c->Wt);
   dev_free(c->col_range); dev_free(c->qstep); dev_free(c->qstep_max_bits); dev_free(c->H2);
   dev_free(c->GxT); dev_free(c->GyT); dev_free(c->hit_x); dev_free(c->hit_n); dev_free(c->hit_rows);
   dev_free(c->mu); dev_free(c->mu_partial); dev_free(c->Wc); dev_free(c->zero16); dev_free(c->mu_norm2);
@@ -423,7 +431,7 @@ int som_bmus_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, cons
   bool reg = false;
   if (!rc && is_registered_csr(c, indptr, indices, values, n)) { rc = registered_norms(c); reg = true; }
   if (rc) return rc;
-  return bmu_search_csr(c, indptr, indices, values, n, codebook, bmus, reg);
+  return bmu_search_csr(c, indptr, indices, values, n, nnz, codebook, bmus, reg);
 }
 
 int som_bmu_distances_dense(som_ctx *c, const float *data, int64_t n, const float *codebook, const int32_t *bmus,
@@ -500,7 +508,7 @@ int som_train_epoch_csr(som_ctx *c, const int64_t *indptr, const int32_t *indice
   if (!rc && is_registered_csr(c, indptr, indices, values, n)) { rc = registered_norms(c); reg = true; }
   if (rc) return rc;
   SOM_LAUNCH(c, launch_epoch_params(c, 0, 1, radius, radius, scale, scale, SOM_COOL_LINEAR));
-  rc = bmu_search_csr(c, indptr, indices, values, n, codebook, bmus, reg);
+  rc = bmu_search_csr(c, indptr, indices, values, n, nnz, codebook, bmus, reg);
   if (rc) return rc;
   return update_csr(c, indptr, indices, values, n, bmus, codebook);
 }
@@ -571,7 +579,7 @@ int som_train_snapshots(som_ctx *c, int n_epochs, float radius0, float radiusN, 
       rc = bmu_search_dense(c, c->d_data, c->d_n, codebook, bmus, true);
       if (!rc) rc = update_dense(c, c->d_data, c->d_n, bmus, codebook);
     } else {
-      rc = bmu_search_csr(c, c->d_indptr, c->d_indices, c->d_values, c->d_n, codebook, bmus, true);
+      rc = bmu_search_csr(c, c->d_indptr, c->d_indices, c->d_values, c->d_n, c->d_nnz, codebook, bmus, true);
       if (!rc) rc = update_csr(c, c->d_indptr, c->d_indices, c->d_values, c->d_n, bmus, codebook);
     }
     if (rc) return rc;

@@ -92,6 +92,8 @@ struct som_ctx {
   // per-data scratch (grown on demand to n_cap rows)
   int64_t n_cap;
   float *xn32;            // [n] squared norms of the instances
+  float *vq;              // [vq_cap] sparse search: value of every nonzero times the step of its column
+  int64_t vq_cap;
   float *row_q;           // [n] sparse rows: sum over the nonzeros of |value| x quantisation step of the column
   _Float16 *Xh;           // [n][ceil(dim/32)][64] dense instances as fp16 hi/lo planes (lazily allocated)
   float *xscale;          // [n] the power of two each instance was divided by
@@ -200,6 +202,7 @@ hipError_t launch_mask_duplicate_rows(som_ctx *c, const float *W);   // wn32[i] 
 // bmu_csr.hip
 hipError_t launch_transpose_codebook(som_ctx *c, const float *W);
 void csr_slice_geometry(int k, int *acc, int *sweeps, int *kpad);
+hipError_t launch_scale_values(som_ctx *c, const int32_t *indices, const float *values, int64_t nnz);   // -> vq
 hipError_t launch_bmu_csr_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
                                  int64_t n, bool collect);
 
