@@ -306,3 +306,19 @@ def test_feature_counts_around_the_chunk_boundaries(oracle, dim):
     som = Som(rows, cols, dim, "toroid", "hexagonal", codebook=torch.from_numpy(W))
     P.epoch_parity_dense(oracle, som, X, P.to_dev(X), 2.0, P.MAP["toroid"], P.GRID["hexagonal"])
     som.close()
+
+
+@pytest.mark.parametrize("rows,cols", [(2, 1100), (1030, 3)])
+@pytest.mark.parametrize("map_type,grid", [("planar", "square"), ("toroid", "hexagonal")])
+def test_map_side_above_the_coefficient_matrix_limit(oracle, rows, cols, map_type, grid):
+    """A side of more than 1,024 nodes: the smoothing runs on the filter vectors directly instead of the
+    stored coefficient matrices."""
+    from paper_1305_1422_amd import Som
+    rng = np.random.default_rng(rows * 7 + cols)
+    n, dim = 400, 12
+    X = rng.random((n, dim)).astype(np.float32)
+    W = rng.random((rows * cols, dim)).astype(np.float32)
+    som = Som(rows, cols, dim, map_type, grid, codebook=torch.from_numpy(W))
+    for radius in (40.0, 3.0):
+        P.epoch_parity_dense(oracle, som, X, P.to_dev(X), radius, P.MAP[map_type], P.GRID[grid])
+    som.close()

@@ -172,3 +172,17 @@ def test_update_csr_at_the_row_length_where_the_accumulation_changes(oracle, dim
     S, C = oracle.accumulate_csr(csr, dim, bmus, rows * cols)
     P.check_codebook(oracle, S, C, W, som.codebook.cpu().numpy(), rows, cols, oracle.PLANAR, oracle.SQUARE, 1.0)
     som.close()
+
+
+def test_sparse_update_on_a_map_side_above_the_coefficient_matrix_limit(oracle):
+    """With a side of more than 1,024 nodes the smoothing reads every row of the per-node sums, chosen or
+    not: the rows nobody chose have to be zero."""
+    from paper_1305_1422_amd import Som
+    rows, cols, dim, n = 2, 1040, 60, 500
+    csr = sparse_zipf_csr(n, dim, 45, mean_len=8.0, max_len=25)
+    W = np.random.default_rng(46).random((rows * cols, dim)).astype(np.float32)
+    som = Som(rows, cols, dim, "toroid", "square", codebook=torch.from_numpy(W))
+    csr_d = P.csr_to_dev(csr)
+    for radius in (25.0, 2.0):
+        P.epoch_parity_csr(oracle, som, csr, csr_d, dim, radius, oracle.TOROID, oracle.SQUARE)
+    som.close()
