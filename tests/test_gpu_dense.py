@@ -322,3 +322,15 @@ def test_map_side_above_the_coefficient_matrix_limit(oracle, rows, cols, map_typ
     for radius in (40.0, 3.0):
         P.epoch_parity_dense(oracle, som, X, P.to_dev(X), radius, P.MAP[map_type], P.GRID[grid])
     som.close()
+
+
+def test_long_instances_take_the_workgroup_per_row_split(oracle):
+    """More than 2,048 features: the fp16 planes are written by a workgroup per row instead of a wavefront."""
+    from paper_1305_1422_amd import Som
+    rng = np.random.default_rng(91)
+    n, dim, rows, cols = 150, 2100, 5, 6
+    X = rng.normal(0.0, 1.0, (n, dim)).astype(np.float32)
+    W = rng.normal(0.0, 1.0, (rows * cols, dim)).astype(np.float32)
+    som = Som(rows, cols, dim, codebook=torch.from_numpy(W))
+    P.epoch_parity_dense(oracle, som, X, P.to_dev(X), 1.5, P.MAP["planar"], P.GRID["square"])
+    som.close()

@@ -186,3 +186,20 @@ def test_sparse_update_on_a_map_side_above_the_coefficient_matrix_limit(oracle):
     for radius in (25.0, 2.0):
         P.epoch_parity_csr(oracle, som, csr, csr_d, dim, radius, oracle.TOROID, oracle.SQUARE)
     som.close()
+
+
+@pytest.mark.parametrize("acc", list(range(1, 17)))
+def test_every_number_of_scores_per_lane(oracle, acc):
+    """512 acc - 7 nodes: acc scores per lane and node range in the sparse sweep (one range per slice), the
+    last slice ragged; both sweeps, since the code book rows are nearly alike."""
+    from paper_1305_1422_amd import Som
+    k = 512 * acc - 7
+    rows, cols = 1, k
+    dim, n = 120, 70
+    csr = sparse_zipf_csr(n, dim, 47 + acc, mean_len=9.0, max_len=30)
+    rng = np.random.default_rng(48 + acc)
+    W = (rng.random((1, dim)) + 1e-4 * rng.random((k, dim))).astype(np.float32)
+    som = Som(rows, cols, dim, "planar", "square", codebook=torch.from_numpy(W))
+    b = som.bmus(P.csr_to_dev(csr)).cpu().numpy()
+    P.check_bmus_csr(oracle, csr, dim, W, b)
+    som.close()
