@@ -334,3 +334,20 @@ def test_long_instances_take_the_workgroup_per_row_split(oracle):
     som = Som(rows, cols, dim, codebook=torch.from_numpy(W))
     P.epoch_parity_dense(oracle, som, X, P.to_dev(X), 1.5, P.MAP["planar"], P.GRID["square"])
     som.close()
+
+
+def test_one_context_serves_growing_and_shrinking_data_and_both_filters(oracle):
+    """The per-data scratch grows on demand and is reused for smaller sets; changing the filter variant in
+    between must not leave stale planes or candidate arrays behind."""
+    from paper_1305_1422_amd import Som
+    rng = np.random.default_rng(92)
+    dim, rows, cols = 70, 15, 14
+    W = rng.random((rows * cols, dim)).astype(np.float32)
+    som = Som(rows, cols, dim, codebook=torch.from_numpy(W))
+    for n, filt in [(100, "split_f16"), (5000, "split_f16"), (300, "fp32"), (7000, "fp32"), (64, "split_f16"),
+                    (7000, "split_f16")]:
+        som.set_filter(filt)
+        X = rng.random((n, dim)).astype(np.float32)
+        b = som.bmus(P.to_dev(X)).cpu().numpy()
+        P.check_bmus_dense(oracle, X, W, b)
+    som.close()

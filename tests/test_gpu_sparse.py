@@ -203,3 +203,16 @@ def test_every_number_of_scores_per_lane(oracle, acc):
     b = som.bmus(P.csr_to_dev(csr)).cpu().numpy()
     P.check_bmus_csr(oracle, csr, dim, W, b)
     som.close()
+
+
+def test_one_context_serves_growing_and_shrinking_sparse_data(oracle):
+    from paper_1305_1422_amd import Som
+    rng = np.random.default_rng(93)
+    dim, rows, cols = 900, 11, 12
+    W = (rng.random((rows * cols, dim)) * 0.1).astype(np.float32)
+    som = Som(rows, cols, dim, codebook=torch.from_numpy(W))
+    for t, n in enumerate([50, 3000, 200, 4000, 10]):
+        csr = sparse_zipf_csr(n, dim, 94 + t, mean_len=20.0 + 10 * t, max_len=200)
+        b = som.bmus(P.csr_to_dev(csr)).cpu().numpy()
+        P.check_bmus_csr(oracle, csr, dim, W, b)
+    som.close()
