@@ -16,7 +16,10 @@
  *     inside `som_ctx`, which it allocates with hipMalloc and grows on demand.
  *   - All work is enqueued on the HIP stream given to som_init (NULL = the default
  *     stream) and is asynchronous: outputs are valid once that stream has been
- *     synchronised.  No call synchronises unless its description says so.
+ *     synchronised.  No call synchronises unless its description says so, with one
+ *     exception: a call that has to grow the context's scratch (more instances, or more
+ *     nonzeros, than any call before it on this context) waits for the stream first, because
+ *     work already enqueued may still use the old buffers.
  *   - Node index i = y * cols + x, x = column in 0..cols-1, y = row in 0..rows-1
  *     (options -x/-y of the paper's command line).  The code book is node-major
  *     [rows*cols][dim], fp32, as in the paper's API (`float *codebook`).
