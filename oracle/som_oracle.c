@@ -124,19 +124,23 @@ static double sqdist_dense(const float *x, const float *w, int dim)
     return s;
 }
 
-/* Same distance for a sparse instance whose unlisted coordinates are zero:
- * sum_c w_c^2 + sum_nz ((v - w_c)^2 - w_c^2).  Identical in exact arithmetic
- * to the dense sum over all dim coordinates. */
+/* Same distance for a sparse instance, by the same definition: the sum runs over
+ * all dim coordinates in ascending order, a coordinate the row does not list
+ * counts as zero.  idx holds the row's columns, zero-based and strictly
+ * increasing (the sparse file format of the command-line interface), so one
+ * cursor into the row tells for every coordinate whether it is listed.  No
+ * regrouping: the result has the bits sqdist_dense gives on the densified row,
+ * and it is exactly 0 when the instance coincides with the weight vector. */
 static double sqdist_csr(const int32_t *idx, const float *val, int64_t len,
                          const float *w, int dim)
 {
     double s = 0.0;
-    for (int c = 0; c < dim; ++c)
-        s += (double)w[c] * (double)w[c];
-    for (int64_t p = 0; p < len; ++p) {
-        double wc = (double)w[idx[p]];
-        double d = (double)val[p] - wc;
-        s += d * d - wc * wc;
+    int64_t p = 0;
+    for (int c = 0; c < dim; ++c) {
+        double x = 0.0;
+        if (p < len && idx[p] == c) { x = (double)val[p]; ++p; }
+        double d = x - (double)w[c];
+        s += d * d;
     }
     return s;
 }
@@ -225,8 +229,7 @@ double oracle_bmu_distances_csr(const int64_t *indptr, const int32_t *indices, c
     double total = 0.0;
     for (int64_t j = 0; j < n; ++j) {
         int64_t s = indptr[j], len = indptr[j + 1] - s;
-        double d2 = sqdist_csr(indices + s, values + s, len, W + (int64_t)bmu[j] * dim, dim);
-        double d = sqrt(d2 > 0.0 ? d2 : 0.0);      /* the regrouped sum may round below zero */
+        double d = sqrt(sqdist_csr(indices + s, values + s, len, W + (int64_t)bmu[j] * dim, dim));
         if (dist) dist[j] = d;
         total += d;
     }

@@ -127,6 +127,46 @@ def test_sparse_equals_densified(oracle, seed):
                                oracle.sqdist_pairs_dense(X, W, inst, node), rtol=1e-10, atol=1e-12)
 
 
+def test_sparse_distance_has_the_bits_of_the_dense_distance(oracle):
+    """The sparse distance is the BMU equation's plain sum over all coordinates: bit for bit what
+    the dense routine gives on the densified row, also with a large common offset in the weights
+    (where a regrouped |w|^2 - 2 x.w + ... form would lose digits)."""
+    dim, n, k = 700, 60, 20
+    csr = sparse_zipf_csr(n, dim, 11, mean_len=15.0, max_len=50)
+    rng = np.random.default_rng(12)
+    W = (rng.random((k, dim)) * 0.3 + 40.0).astype(np.float32)
+    X = densify(csr, dim)
+    inst = np.arange(n).repeat(k)
+    node = np.tile(np.arange(k), n)
+    a = oracle.sqdist_pairs_csr(csr, dim, W, inst, node)
+    b = oracle.sqdist_pairs_dense(X, W, inst, node)
+    assert np.array_equal(a, b)
+    b_s, d_s = oracle.bmu_csr(csr, dim, W, want_d2=True)
+    b_d, d_d = oracle.bmu_dense(X, W, want_d2=True)
+    assert np.array_equal(b_s, b_d) and np.array_equal(d_s, d_d)
+
+
+def test_sparse_instance_on_a_node_is_at_distance_zero(oracle):
+    """An instance that coincides with a weight vector is at distance exactly 0 (not at the rounding
+    noise of a cancelling sum), and near-copies of it are told apart at any offset of the map."""
+    dim, n = 5000, 40
+    csr = sparse_zipf_csr(n, dim, 21, mean_len=80.0, max_len=160)
+    X = densify(csr, dim)
+    rng = np.random.default_rng(22)
+    W = rng.random((3 * n, dim)).astype(np.float32)
+    W[n:2 * n] = X                                   # node n + j is instance j itself
+    W[:n] = X
+    W[:n, 0] = np.nextafter(X[:, 0], np.float32(9.0))          # node j: one ulp off in one coordinate
+    bmu, d2 = oracle.bmu_csr(csr, dim, W, want_d2=True)
+    assert np.array_equal(bmu, np.arange(n, 2 * n).astype(np.int32))
+    assert np.all(d2 == 0.0)
+    near = oracle.sqdist_pairs_csr(csr, dim, W, np.arange(n), np.arange(n).astype(np.int32))
+    ulp = (W[:n, 0].astype(np.float64) - X[:, 0].astype(np.float64)) ** 2
+    assert np.array_equal(near, ulp) and np.all(near > 0.0)
+    dist, qe = oracle.bmu_distances_csr(csr, dim, W, bmu)
+    assert np.all(dist == 0.0) and qe == 0.0
+
+
 def test_empty_sparse_row_goes_to_smallest_norm_node(oracle):
     csr = (np.array([0, 0, 1], dtype=np.int64), np.array([2], dtype=np.int32),
            np.array([5.0], dtype=np.float32))
