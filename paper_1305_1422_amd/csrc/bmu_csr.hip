@@ -273,8 +273,8 @@ __global__ __launch_bounds__(256) void k_scale_values(const int32_t *__restrict_
 }
 
 hipError_t launch_scale_values(som_ctx *c, const int32_t *indices, const float *values, int64_t nnz) {
+  if (nnz < 1) return hipSuccess;                       // every row empty: nothing to scale (and no buffer yet)
   if (!c->vq || c->vq_cap < nnz) return hipErrorInvalidValue;
-  if (nnz < 1) return hipSuccess;
   int64_t cb = (nnz + 255) / 256;
   if (cb > (int64_t)c->n_cu * 16) cb = (int64_t)c->n_cu * 16;
   hipLaunchKernelGGL(k_scale_values, dim3((unsigned)cb), dim3(256), 0, c->stream, indices, values, nnz, c->dim,

@@ -6,7 +6,8 @@
 //              everything else by more than twice the bound is decided on the spot;
 //   refine   - otherwise the candidates inside the bound are compared by their squared
 //              distances sum_c (x_c - w_c)^2 evaluated in fp64 on the original (uncentred)
-//              vectors, lowest node index on exact ties;
+//              vectors, lowest node index on exact ties (sparse rows: a regrouped sum over the
+//              nonzeros, and the plain sum over all coordinates where that one would cancel);
 //   collect  - if a dropped score lies inside the bound too, the fp32 sweep is repeated for
 //              that instance and every node under the threshold is listed (bmu_dense.hip),
 //              then the list is compared exactly;
@@ -156,10 +157,14 @@ __device__ __forceinline__ double sqdist_dense_wave(const float *__restrict__ x,
   return wave_sum(s);
 }
 
-// The same distance for a sparse row with implicit zeros: |w|^2 + sum_nz ((v - w_c)^2 - w_c^2).
-__device__ __forceinline__ double sqdist_csr_wave(const int32_t *__restrict__ idx, const float *__restrict__ val,
-                                                  int len, const float *__restrict__ w, double wn, int dim,
-                                                  int lane) {
+// The same distance for a sparse row with implicit zeros, regrouped so that only the nonzeros are
+// visited: |w|^2 + sum_nz ((v - w_c)^2 - w_c^2).  Equal to the plain sum in exact arithmetic; in fp64
+// its absolute error is about (dim + len) 2^-53 (|w|^2 + |x|^2), which is harmless unless the
+// distance itself is that small (sqdist_csr_wave below).
+__device__ __forceinline__ double sqdist_csr_regrouped_wave(const int32_t *__restrict__ idx,
+                                                            const float *__restrict__ val, int len,
+                                                            const float *__restrict__ w, double wn, int dim,
+                                                            int lane) {
   double s = 0.0;
   for (int p = lane; p < len; p += kWave) {
     int c = idx[p];
@@ -169,6 +174,45 @@ __device__ __forceinline__ double sqdist_csr_wave(const int32_t *__restrict__ id
     s += d * d - wc * wc;
   }
   return wn + wave_sum(s);
+}
+
+// The BMU equation's sum as it is printed: every coordinate once, an unlisted one as zero, all
+// terms non-negative, so nothing cancels and an instance that coincides with the weight vector
+// is at distance exactly 0.  Lanes take the coordinates round-robin; each keeps a cursor into the
+// row's (sorted) column list, which only ever moves forward.  dim loads: the rare path.
+__device__ __forceinline__ double sqdist_csr_plain_wave(const int32_t *__restrict__ idx,
+                                                        const float *__restrict__ val, int len,
+                                                        const float *__restrict__ w, int dim, int lane) {
+  double s = 0.0;
+  int p = 0;
+  for (int c = lane; c < dim; c += kWave) {
+    while (p < len && idx[p] < c) ++p;
+    const double x = (p < len && idx[p] == c) ? (double)val[p] : 0.0;
+    const double d = x - (double)w[c];
+    s += d * d;
+  }
+  return wave_sum(s);
+}
+
+// Squared norm of a sparse row in fp64 (every lane gets the sum).
+__device__ __forceinline__ double csr_row_sqnorm_wave(const float *__restrict__ val, int len, int lane) {
+  double s = 0.0;
+  for (int p = lane; p < len; p += kWave) s += (double)val[p] * (double)val[p];
+  return wave_sum(s);
+}
+
+// Exact distance of a sparse row: the regrouped sum wherever its rounding is at least 2^23 times
+// smaller than the result (relative error below 1.2e-7, a hundredth of the tolerance band of the
+// decision), the plain sum otherwise.  wn = |w|^2, xn = |x|^2.  Every lane holds the same bits of
+// the regrouped value, so the branch is uniform over the wavefront; bit-identical weight vectors
+// take the same branch and get the same bits.
+__device__ __forceinline__ double sqdist_csr_wave(const int32_t *__restrict__ idx, const float *__restrict__ val,
+                                                  int len, const float *__restrict__ w, double wn, double xn,
+                                                  int dim, int lane) {
+  const double d2 = sqdist_csr_regrouped_wave(idx, val, len, w, wn, dim, lane);
+  const double noise = ((double)dim + (double)len + 2.0) * 1.862645149230957e-09 * (wn + xn);   // 2^-29 = 2^-52 * 2^23
+  if (d2 < noise) return sqdist_csr_plain_wave(idx, val, len, w, dim, lane);
+  return d2;
 }
 
 __global__ __launch_bounds__(256) void k_refine_dense(const float *__restrict__ X, const float *__restrict__ W,
@@ -274,11 +318,12 @@ __global__ __launch_bounds__(256) void k_refine_csr(const int64_t *__restrict__ 
     const int64_t s = indptr[j];
     const int len = (int)(indptr[j + 1] - s);
     const int cn = cand_n[j];
+    const double xn = csr_row_sqnorm_wave(values + s, len, lane);
     double best = INFINITY;
     int arg = 0x7fffffff;
     for (int t = 0; t < cn; ++t) {
       const int i = cand_idx[j * kCand + t];
-      const double d2 = sqdist_csr_wave(indices + s, values + s, len, W + (int64_t)i * dim, wn64[i], dim, lane);
+      const double d2 = sqdist_csr_wave(indices + s, values + s, len, W + (int64_t)i * dim, wn64[i], xn, dim, lane);
       if (d2 < best || (d2 == best && i < arg)) { best = d2; arg = i; }
     }
     if (lane == 0) bmus[j] = arg == 0x7fffffff ? 0 : arg;      // no finite distance (non-finite input): node 0, as a plain scan gives
@@ -310,11 +355,12 @@ __global__ __launch_bounds__(256) void k_refine_lists_csr(const int64_t *__restr
     }
     const int cn = min(collect_cnt[e], kListCap);
     const int32_t *lst = collect_list + (int64_t)e * kListCap;
+    const double xn = csr_row_sqnorm_wave(values + s, len, lane);
     double best = INFINITY;
     int arg = 0x7fffffff;
     for (int t = 0; t < cn; ++t) {
       const int i = min(max(lst[t], 0), k - 1);
-      const double d2 = sqdist_csr_wave(indices + s, values + s, len, W + (int64_t)i * dim, wn64[i], dim, lane);
+      const double d2 = sqdist_csr_wave(indices + s, values + s, len, W + (int64_t)i * dim, wn64[i], xn, dim, lane);
       if (d2 < best || (d2 == best && i < arg)) { best = d2; arg = i; }
     }
     if (lane == 0) bmus[j] = arg == 0x7fffffff ? 0 : arg;
@@ -337,10 +383,11 @@ __global__ __launch_bounds__(256) void k_rescan_csr(const int64_t *__restrict__ 
     const int64_t j = rescan_list[e];
     const int64_t s = indptr[j];
     const int len = (int)(indptr[j + 1] - s);
+    const double xn = csr_row_sqnorm_wave(values + s, len, lane);
     double best = INFINITY;
     int arg = 0x7fffffff;
     for (int i = wave; i < k; i += 4) {
-      const double d2 = sqdist_csr_wave(indices + s, values + s, len, W + (int64_t)i * dim, wn64[i], dim, lane);
+      const double d2 = sqdist_csr_wave(indices + s, values + s, len, W + (int64_t)i * dim, wn64[i], xn, dim, lane);
       if (d2 < best) { best = d2; arg = i; }
     }
     if (lane == 0) { s_best[wave] = best; s_arg[wave] = arg; }
@@ -472,8 +519,9 @@ __global__ __launch_bounds__(256) void k_bmu_distances(const float *__restrict__
         for (int c = lane; c < dim; c += kWave) wn += (double)w[c] * (double)w[c];
         wn = wave_sum(wn);
         const int64_t rs = indptr[j];
-        d2 = sqdist_csr_wave(indices + rs, values + rs, (int)(indptr[j + 1] - rs), w, wn, dim, lane);
-        d2 = d2 > 0.0 ? d2 : 0.0;        // the regrouped sum may round below zero
+        const int len = (int)(indptr[j + 1] - rs);
+        d2 = sqdist_csr_wave(indices + rs, values + rs, len, w, wn, csr_row_sqnorm_wave(values + rs, len, lane), dim,
+                             lane);
       } else {
         d2 = sqdist_dense_wave(X + j * dim, w, dim, lane);
       }

@@ -46,7 +46,7 @@ def test_distances_csr(oracle, n, dim, rows, cols, mean_len):
     b = som.bmus(csr_d)
     dist, qe = som.bmu_distances(csr_d, b)
     want, want_qe = oracle.bmu_distances_csr(csr, dim, W, b.cpu().numpy())
-    # the regrouped sparse sum cancels |w|^2: absolute error of the squared distance ~ 2^-52 |w|^2
+    # the library regroups the sparse sum only where its rounding is below 1.2e-7 of the result
     np.testing.assert_allclose(dist.cpu().numpy(), want, rtol=DIST_RTOL, atol=1e-9)
     np.testing.assert_allclose(qe.item(), want_qe, rtol=1e-10)
     som.close()

@@ -216,3 +216,72 @@ def test_one_context_serves_growing_and_shrinking_sparse_data(oracle):
         b = som.bmus(P.csr_to_dev(csr)).cpu().numpy()
         P.check_bmus_csr(oracle, csr, dim, W, b)
     som.close()
+
+
+def test_all_rows_empty(oracle):
+    """nnz = 0 is legal: every instance is the zero vector and maps to the node of smallest norm
+    (lowest index among equals); the update then gives every reachable node the zero vector."""
+    from paper_1305_1422_amd import Som
+    dim, rows, cols, n = 70, 5, 6, 33
+    rng = np.random.default_rng(95)
+    W = rng.random((rows * cols, dim)).astype(np.float32) + np.float32(0.25)
+    W[19] = W[8] = W[3] * np.float32(0.05)
+    csr = (np.zeros(n + 1, dtype=np.int64), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.float32))
+    som = Som(rows, cols, dim, codebook=torch.from_numpy(W))
+    csr_d = P.csr_to_dev(csr)
+    b = som.bmus(csr_d).cpu().numpy()
+    assert np.array_equal(b, oracle.bmu_csr(csr, dim, W)) and np.all(b == 8)
+    P.epoch_parity_csr(oracle, som, csr, csr_d, dim, 1.5, oracle.PLANAR, oracle.SQUARE)
+    som.close()
+
+
+def test_instances_that_coincide_with_nodes(oracle):
+    """Weight vectors equal to instances, with one-ulp near-copies at lower and higher node indices and a
+    long feature space: a distance evaluated as |w|^2 - 2 x.w + ... cancels to its own rounding here and
+    cannot tell the copies apart; the search must still return the coincident node, at distance exactly 0."""
+    from paper_1305_1422_amd import Som, capi
+    dim, n, rows, cols = 12000, 96, 12, 24
+    csr = sparse_zipf_csr(n, dim, 96, mean_len=90.0, max_len=300)
+    X = densify(csr, dim)
+    rng = np.random.default_rng(97)
+    W = (rng.random((rows * cols, dim)) * 0.05).astype(np.float32)
+    first = csr[1][csr[0][:-1]]                                   # first listed column of every row
+    W[n:2 * n] = X                                                # node n + j is instance j
+    W[:n] = X
+    W[np.arange(n), first] = np.nextafter(X[np.arange(n), first], np.float32(9.0))       # one ulp up
+    W[2 * n:3 * n] = X
+    W[2 * n + np.arange(n), first] = np.nextafter(X[np.arange(n), first], np.float32(-9.0))   # one ulp down
+    som = Som(rows, cols, dim, codebook=torch.from_numpy(W))
+    csr_d = P.csr_to_dev(csr)
+    b = som.bmus(csr_d).cpu().numpy()
+    assert np.array_equal(b, np.arange(n, 2 * n))
+    P.check_bmus_csr(oracle, csr, dim, W, b)
+    dist, qe = som.bmu_distances(csr_d, P.to_dev(b.astype(np.int32)))
+    assert float(qe) == 0.0 and np.all(dist.cpu().numpy() == 0.0)
+    som.close()
+
+
+@pytest.mark.parametrize("nb,compact,radius", [("gaussian", True, 1.0), ("bubble", False, 1.0), ("gaussian", True, 0.5)])
+def test_nodes_updated_by_a_single_instance(oracle, nb, compact, radius):
+    """More nodes than instances under a neighbourhood of compact support: after an epoch many nodes are the
+    weighted mean of ONE instance, i.e. that instance up to an ulp, and so are their neighbours.  The next
+    searches meet instances that (nearly) coincide with several nodes; BMUs and code book must keep matching
+    the oracle under the plain rule (a best distance of 0 admits only answers at distance 0)."""
+    from paper_1305_1422_amd import Som
+    dim, n, rows, cols = 6000, 150, 30, 28
+    csr = sparse_zipf_csr(n, dim, 98, mean_len=40.0, max_len=160)
+    W0 = (np.random.default_rng(99).random((rows * cols, dim)) * 0.02).astype(np.float32)
+    som = Som(rows, cols, dim, "toroid", "hexagonal", codebook=torch.from_numpy(W0))
+    som.set_neighborhood(nb, compact)
+    csr_d = P.csr_to_dev(csr)
+    zero_best = 0
+    for e in range(4):
+        W_in = som.codebook.cpu().numpy().copy()
+        b = som.train_epoch(csr_d, radius).cpu().numpy()
+        P.check_bmus_csr(oracle, csr, dim, W_in, b)
+        zero_best += int(np.count_nonzero(oracle.sqdist_pairs_csr(csr, dim, W_in, np.arange(n), b) < 1e-12))
+        S, C = oracle.accumulate_csr(csr, dim, b, rows * cols)
+        P.check_codebook(oracle, S, C, W_in, som.codebook.cpu().numpy(), rows, cols, oracle.TOROID, oracle.HEXAGONAL,
+                         radius, function=1 if nb == "bubble" else 0, compact=compact)
+    assert zero_best >= n // 2, "hardly any instance ever sat on a node: the test misses its case"
+    som.close()
