@@ -65,7 +65,8 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
 /* Release the context and its scratch memory (synchronises the stream first). */
 void som_destroy(som_ctx *ctx);
 
-/* Message of the last failing call on ctx; ctx == NULL: of the last failing som_init. */
+/* Message of the last failing call on ctx; ctx == NULL: of the last failing call that takes no
+ * context (som_init, som_bmu_distances_dense_static). */
 const char *som_last_error(const som_ctx *ctx);
 
 /*
@@ -203,6 +204,31 @@ int som_bmu_distances_dense(som_ctx *ctx, const float *data, int64_t n, const fl
 int som_bmu_distances_csr(som_ctx *ctx, const int64_t *indptr, const int32_t *indices,
                           const float *values, int64_t n, int64_t nnz, const float *codebook,
                           const int32_t *bmus, float *distances, double *qerror);
+
+/*
+ * som_bmu_distances_dense_static - som_bmu_distances_dense for callers that cannot allocate device
+ * memory or create a context at the point of the call: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  It takes no context and calls no allocating routine;
+ * its only scratch (one fp64 partial sum per workgroup, 1,024 of them = 8 KB) is a fixed array in
+ * the library's device image, which every GPU the library is used on holds until the process ends.
+ *   data       device [n][dim] fp32, read only.
+ *   codebook   device [n_nodes][dim] fp32, read only.
+ *   bmus, distances, qerror   as in som_bmu_distances_dense (same kernels, same bits).
+ *   hip_stream hipStream_t cast to void*, or NULL for the default stream; the work is enqueued
+ *              there, asynchronously.
+ * The scratch never limits n (the instances are dealt to at most 1,024 workgroups), so the size
+ * limits are those of the other calls: n outside [1, 2^31), dim < 1, n_nodes outside [1, 2^24],
+ * n_nodes * dim >= 2^40, a NULL input or both outputs NULL -> SOM_ERR_INVALID_ARG, nothing
+ * enqueued (message: som_last_error(NULL)).
+ * All calls on one GPU share that GPU's array: two calls whose work may overlap on the same GPU
+ * (different streams, or different threads) race on it and must be ordered by the caller; calls
+ * on one stream are ordered already.  Nothing has to be cleared between calls: a call overwrites
+ * every partial sum it later reads.  The array's address is looked up once per device, by som_init
+ * or else by the first call of this function on that device; make that first call outside a
+ * graph capture.
+ */
+int som_bmu_distances_dense_static(const float *data, int64_t n, int dim, const float *codebook, int n_nodes,
+                                   const int32_t *bmus, float *distances, double *qerror, void *hip_stream);
 
 /*
  * som_cool_schedule - evaluate the cooling schedule of som_train on the device.

@@ -27,7 +27,7 @@ EXPORTS = [
     "som_bmus_dense", "som_bmus_csr",
     "som_update_dense", "som_update_csr",
     "som_set_data_dense", "som_set_data_csr", "som_train", "som_train_snapshots",
-    "som_bmu_distances_dense", "som_bmu_distances_csr",
+    "som_bmu_distances_dense", "som_bmu_distances_csr", "som_bmu_distances_dense_static",
     "som_cool_schedule", "som_umatrix", "som_get_stats",
     "som_profile_enable", "som_profile_read",
     "som_set_filter", "som_set_neighborhood", "som_debug_scores_dense", "som_debug_mfma_f16",
@@ -85,6 +85,8 @@ def load():
     L.som_bmu_distances_dense.argtypes = [vp, vp, i64, vp, vp, vp, vp]
     L.som_bmu_distances_csr.restype = i32
     L.som_bmu_distances_csr.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp, vp, vp]
+    L.som_bmu_distances_dense_static.restype = i32
+    L.som_bmu_distances_dense_static.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, vp]
     L.som_umatrix.restype = i32
     L.som_umatrix.argtypes = [vp, vp, vp]
     L.som_get_stats.restype = i32
@@ -236,6 +238,17 @@ def som_bmu_distances_dense(ctx, data, codebook, bmus, distances, qerror) -> Non
                                                _ptr(bmus, torch.int32, "bmus"),
                                                _ptr(distances, torch.float32, "distances", True),
                                                _ptr(qerror, torch.float64, "qerror", True)))
+
+
+def som_bmu_distances_dense_static(data, codebook, bmus, distances, qerror, stream: Optional[int] = None) -> None:
+    """The variant without context and without allocations; ``stream``: a hipStream_t as int, None = default."""
+    import torch
+    _check(None, load().som_bmu_distances_dense_static(_ptr(data, torch.float32, "data"), data.shape[0], data.shape[1],
+                                                      _ptr(codebook, torch.float32, "codebook"), codebook.shape[0],
+                                                      _ptr(bmus, torch.int32, "bmus"),
+                                                      _ptr(distances, torch.float32, "distances", True),
+                                                      _ptr(qerror, torch.float64, "qerror", True),
+                                                      C.c_void_p(stream or 0)))
 
 
 def som_bmu_distances_csr(ctx, indptr, indices, values, codebook, bmus, distances, qerror) -> None:

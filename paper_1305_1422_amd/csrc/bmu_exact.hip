@@ -491,7 +491,6 @@ hipError_t launch_refine_lists_csr(som_ctx *c, const int64_t *indptr, const int3
 // A wavefront per instance; a workgroup owns a contiguous block of instances and leaves one
 // partial sum, the partial sums are added in index order by k_mean_of_partials: the result
 // does not depend on the schedule.  A node index outside [0, k) yields NaN.
-constexpr int kDistBlocks = 1024;
 
 template <bool kCsr>
 __global__ __launch_bounds__(256) void k_bmu_distances(const float *__restrict__ X,
@@ -543,21 +542,28 @@ __global__ __launch_bounds__(64) void k_mean_of_partials(const double *__restric
   if (threadIdx.x == 0) *out = n > 0 ? s / (double)n : 0.0;
 }
 
-hipError_t launch_bmu_distances(som_ctx *c, const float *X, const int64_t *indptr, const int32_t *indices,
-                                const float *values, int64_t n, const float *W, const int32_t *bmus, float *dist,
-                                double *qerror) {
+hipError_t launch_bmu_distances_on(hipStream_t stream, const float *X, const int64_t *indptr, const int32_t *indices,
+                                   const float *values, int64_t n, const float *W, int k, int dim,
+                                   const int32_t *bmus, float *dist, double *qerror, double *partial) {
   int blocks = (int)((n + 3) / 4);
   if (blocks > kDistBlocks) blocks = kDistBlocks;
   if (blocks < 1) blocks = 1;
   if (X)
-    hipLaunchKernelGGL(k_bmu_distances<false>, dim3(blocks), dim3(256), 0, c->stream, X, nullptr, nullptr, nullptr, W,
-                       n, c->k, c->dim, bmus, dist, c->dist_partial);
+    hipLaunchKernelGGL(k_bmu_distances<false>, dim3(blocks), dim3(256), 0, stream, X, nullptr, nullptr, nullptr, W,
+                       n, k, dim, bmus, dist, partial);
   else
-    hipLaunchKernelGGL(k_bmu_distances<true>, dim3(blocks), dim3(256), 0, c->stream, nullptr, indptr, indices, values,
-                       W, n, c->k, c->dim, bmus, dist, c->dist_partial);
+    hipLaunchKernelGGL(k_bmu_distances<true>, dim3(blocks), dim3(256), 0, stream, nullptr, indptr, indices, values,
+                       W, n, k, dim, bmus, dist, partial);
   if (qerror)
-    hipLaunchKernelGGL(k_mean_of_partials, dim3(1), dim3(64), 0, c->stream, c->dist_partial, blocks, n, qerror);
+    hipLaunchKernelGGL(k_mean_of_partials, dim3(1), dim3(64), 0, stream, partial, blocks, n, qerror);
   return hipGetLastError();
+}
+
+hipError_t launch_bmu_distances(som_ctx *c, const float *X, const int64_t *indptr, const int32_t *indices,
+                                const float *values, int64_t n, const float *W, const int32_t *bmus, float *dist,
+                                double *qerror) {
+  return launch_bmu_distances_on(c->stream, X, indptr, indices, values, n, W, c->k, c->dim, bmus, dist, qerror,
+                                 c->dist_partial);
 }
 
 hipError_t launch_rescan_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,

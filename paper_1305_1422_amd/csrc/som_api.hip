@@ -16,9 +16,39 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
+
 using namespace som;
 
 static char g_init_error[256] = "";
+
+// Scratch of the entry point that must not allocate (som_bmu_distances_dense_static): one partial sum per
+// workgroup of the distance kernel.  Every GPU the library runs on holds its own copy of this array
+// for the life of the process, at its own address; the name below is only a host-side handle of the
+// symbol, so host code resolves the address once per device and passes that pointer to the kernels.
+static __device__ __align__(256) double scratch[kDistBlocks];      // 8 KB
+constexpr int kMaxDevices = 64;
+static double *g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+// Address of `scratch` on the current device (resolved on first use, then cached); null on failure.
+static double *static_scratch(hipError_t *err) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices)) e = hipErrorInvalidDevice;
+  double *p = nullptr;
+  if (e == hipSuccess) {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+      void *sym = nullptr;
+      e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+      if (e == hipSuccess) g_scratch_ptr[dev] = static_cast<double *>(sym);
+    }
+    p = g_scratch_ptr[dev];
+  }
+  if (err) *err = e;
+  return e == hipSuccess ? p : nullptr;
+}
 
 static int fail(som_ctx *c, int code, const char *fmt, ...) {
   char *dst = c ? c->err : g_init_error;
@@ -350,12 +380,13 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
     return fail(nullptr, SOM_ERR_DEVICE, "no HIP device");
   }
   c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  (void)static_scratch(nullptr);      // so that a later som_bmu_distances_dense_static on this device has nothing left to set up
 
   const size_t K = (size_t)c->k;
   const size_t images = grid_type == SOM_GRID_HEXAGONAL ? 2 : 1;
   bool ok = dev_alloc(&c->wn32, (K + 127) / 128 * 128) && dev_alloc(&c->wn64, K) && dev_alloc(&c->wmax_bits, 2) &&
             dev_alloc(&c->counts, K + 1) && dev_alloc(&c->seg_off, K + 1) && dev_alloc(&c->chunk_off, K + 1) &&
-            dev_alloc(&c->massD, K) && dev_alloc(&c->dist_partial, 1024) && dev_alloc(&c->cntT, 2 * K) && dev_alloc(&c->gx, 2 * (size_t)cols + 1) &&
+            dev_alloc(&c->massD, K) && dev_alloc(&c->dist_partial, kDistBlocks) && dev_alloc(&c->cntT, 2 * K) && dev_alloc(&c->gx, 2 * (size_t)cols + 1) &&
             dev_alloc(&c->gy, (size_t)rows) && dev_alloc(&c->params, 1) && dev_alloc(&c->list_counts, kListCounts) &&
             dev_alloc(&c->mu, (size_t)dim) && dev_alloc(&c->mu_partial, (size_t)64 * dim) &&
             dev_alloc(&c->zero16, 16) && dev_alloc(&c->mu_norm2, 1) && dev_alloc(&c->wscale, 1) &&
@@ -454,6 +485,22 @@ int som_bmu_distances_csr(som_ctx *c, const int64_t *indptr, const int32_t *indi
   const int rc = check_csr(c, indptr, indices, values, n, nnz);
   if (rc) return rc;
   SOM_LAUNCH(c, launch_bmu_distances(c, nullptr, indptr, indices, values, n, codebook, bmus, distances, qerror));
+  return SOM_OK;
+}
+
+int som_bmu_distances_dense_static(const float *data, int64_t n, int dim, const float *codebook, int n_nodes,
+                                   const int32_t *bmus, float *distances, double *qerror, void *hip_stream) {
+  if (!data || !codebook || !bmus) return fail(nullptr, SOM_ERR_INVALID_ARG, "NULL pointer argument");
+  if (!distances && !qerror) return fail(nullptr, SOM_ERR_INVALID_ARG, "distances and qerror are both NULL");
+  if (n < 1 || n >= (1ll << 31)) return fail(nullptr, SOM_ERR_INVALID_ARG, "n must be in [1, 2^31)");
+  if (dim < 1 || n_nodes < 1 || n_nodes > (1 << 24) || (int64_t)n_nodes * dim >= (1ll << 40))
+    return fail(nullptr, SOM_ERR_INVALID_ARG, "dim and n_nodes must be >= 1, n_nodes <= 2^24, n_nodes * dim < 2^40");
+  hipError_t e = hipSuccess;
+  double *partial = static_scratch(&e);
+  if (!partial) return dev_fail(nullptr, e, "address of the static scratch");
+  e = launch_bmu_distances_on((hipStream_t)hip_stream, data, nullptr, nullptr, nullptr, n, codebook, n_nodes, dim,
+                              bmus, distances, qerror, partial);
+  if (e != hipSuccess) return dev_fail(nullptr, e, "som_bmu_distances_dense_static");
   return SOM_OK;
 }
 

@@ -192,6 +192,12 @@ hipError_t launch_refine_lists_csr(som_ctx *c, const int64_t *indptr, const int3
 hipError_t launch_rescan_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices,
                              const float *values, const float *W, int32_t *bmus);
 
+// Workgroups of the distance kernel = partial sums it leaves (and the capacity of every buffer for them).
+constexpr int kDistBlocks = 1024;
+hipError_t launch_bmu_distances_on(hipStream_t stream, const float *X, const int64_t *indptr, const int32_t *indices,
+                                   const float *values, int64_t n, const float *W, int k, int dim,
+                                   const int32_t *bmus, float *dist, double *qerror,
+                                   double *partial /* [kDistBlocks] device scratch */);
 hipError_t launch_bmu_distances(som_ctx *c, const float *X, const int64_t *indptr, const int32_t *indices,
                                 const float *values, int64_t n, const float *W, const int32_t *bmus, float *dist,
                                 double *qerror);     // X != NULL: dense rows, else CSR
