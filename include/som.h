@@ -41,7 +41,7 @@ typedef struct som_ctx som_ctx;
 enum { SOM_OK = 0, SOM_ERR_INVALID_ARG = 1, SOM_ERR_ALLOC = 2, SOM_ERR_DEVICE = 3, SOM_ERR_STATE = 4 };
 enum { SOM_MAP_PLANAR = 0, SOM_MAP_TOROID = 1 };          /* option -m: planar (default) or toroid   */
 enum { SOM_GRID_SQUARE = 0, SOM_GRID_HEXAGONAL = 1 };     /* option -g: square (default) or hexagonal */
-enum { SOM_COOL_LINEAR = 0, SOM_COOL_EXPONENTIAL = 1 };   /* options -t / -T                          */
+enum { SOM_COOL_AS_RADIUS = -1, SOM_COOL_LINEAR = 0, SOM_COOL_EXPONENTIAL = 1 };   /* options -t / -T */
 enum { SOM_FILTER_FP32 = 0, SOM_FILTER_SPLIT_F16 = 1 };   /* see som_set_filter                       */
 enum { SOM_NEIGHBORHOOD_GAUSSIAN = 0, SOM_NEIGHBORHOOD_BUBBLE = 1 };   /* option -n               */
 
@@ -100,9 +100,10 @@ int som_train_epoch_dense(som_ctx *ctx, const float *data, int64_t n, float *cod
  *             increasing within a row.
  *   values    device [nnz] fp32.
  * Unlisted coordinates are zero; an empty row is legal (its BMU is the node of smallest
- * norm).  The code book stays dense.  CSR structure is NOT validated on the device: rows
- * that violate the contract give undefined results (indices are still clamped so that no
- * access leaves the code book).  Other arguments, outputs and errors as for the dense call;
+ * norm).  The code book stays dense.  The epoch and search calls do not check the CSR
+ * structure: rows that violate the contract give undefined results (indices are still clamped
+ * so that no access leaves the code book); som_validate_csr checks it on request.  Other
+ * arguments, outputs and errors as for the dense call;
  * nnz < 0 or nnz >= 2^31 -> SOM_ERR_INVALID_ARG.
  * The per-node sums of this call are accumulated with fp32 atomic adds, so the last bits
  * of the new code book may vary from run to run; the BMUs do not.
@@ -110,6 +111,16 @@ int som_train_epoch_dense(som_ctx *ctx, const float *data, int64_t n, float *cod
 int som_train_epoch_csr(som_ctx *ctx, const int64_t *indptr, const int32_t *indices,
                         const float *values, int64_t n, int64_t nnz, float *codebook,
                         float radius, float scale, int32_t *bmus);
+
+/*
+ * som_validate_csr - debug pass over a CSR data set (paper: sparse file format, zero-based
+ * index:value pairs).  Checks indptr[0] = 0, indptr non-decreasing, indptr[n] = nnz, every column
+ * index in [0, dim) and strictly increasing within its row.  Arguments as in som_train_epoch_csr.
+ * Synchronises the stream.  Returns SOM_OK, or SOM_ERR_INVALID_ARG with the kind of violation in
+ * som_last_error (a row whose bounds leave [0, nnz] is reported, not read).
+ */
+int som_validate_csr(som_ctx *ctx, const int64_t *indptr, const int32_t *indices, const float *values,
+                     int64_t n, int64_t nnz);
 
 /*
  * som_bmus_dense / som_bmus_csr - BMU search only (BMU equation), code book unchanged:
@@ -158,7 +169,8 @@ int som_set_data_csr(som_ctx *ctx, const int64_t *indptr, const int32_t *indices
  *   v_e = v0 (vN / v0)^(e / (n_epochs-1)) (exponential); one epoch uses v0.
  *   radius0 <= 0: default, half the smaller map side (at least 1); radiusN <= 0: 1.
  *   scale0 <= 0: 1.0; scaleN <= 0: 0.01 (the paper's defaults).
- *   cooling   SOM_COOL_*, applied to radius and scale alike.
+ *   cooling   SOM_COOL_LINEAR or SOM_COOL_EXPONENTIAL for the radius (option -t), and for the
+ *             learning rate too unless som_set_scale_cooling chose another kind for it (option -T).
  *   codebook  device, in/out as in the epoch calls.
  *   bmus      device [n] int32 out: BMUs found in the LAST epoch (against the code book
  *             that entered it).
@@ -237,6 +249,15 @@ int som_bmu_distances_dense_static(const float *data, int64_t n, int dim, const 
  */
 int som_cool_schedule(som_ctx *ctx, int n_epochs, float radius0, float radiusN, float scale0,
                       float scaleN, int cooling, double *radius_out, double *scale_out);
+
+/*
+ * som_set_scale_cooling - cooling kind of the learning rate (option -T) where it differs from the
+ * radius' (option -t): SOM_COOL_LINEAR, SOM_COOL_EXPONENTIAL, or SOM_COOL_AS_RADIUS (default) =
+ * whatever kind som_train / som_train_snapshots / som_cool_schedule are given for the radius.  The
+ * learning rate cancels in the batch equation, so this changes what som_cool_schedule reports, not the
+ * code book.  Errors: unknown value -> SOM_ERR_INVALID_ARG.
+ */
+int som_set_scale_cooling(som_ctx *ctx, int cooling);
 
 /*
  * som_umatrix - U-matrix of a code book (U-matrix equation): for every node the mean

@@ -17,7 +17,7 @@ LIB_PATH = os.environ.get("SOM_LIB_PATH", os.path.join(HERE, "libsom.so"))
 SOM_OK, SOM_ERR_INVALID_ARG, SOM_ERR_ALLOC, SOM_ERR_DEVICE, SOM_ERR_STATE = 0, 1, 2, 3, 4
 SOM_MAP_PLANAR, SOM_MAP_TOROID = 0, 1
 SOM_GRID_SQUARE, SOM_GRID_HEXAGONAL = 0, 1
-SOM_COOL_LINEAR, SOM_COOL_EXPONENTIAL = 0, 1
+SOM_COOL_AS_RADIUS, SOM_COOL_LINEAR, SOM_COOL_EXPONENTIAL = -1, 0, 1
 SOM_FILTER_FP32, SOM_FILTER_SPLIT_F16 = 0, 1
 SOM_NEIGHBORHOOD_GAUSSIAN, SOM_NEIGHBORHOOD_BUBBLE = 0, 1
 
@@ -30,7 +30,7 @@ EXPORTS = [
     "som_bmu_distances_dense", "som_bmu_distances_csr", "som_bmu_distances_dense_static",
     "som_cool_schedule", "som_umatrix", "som_get_stats",
     "som_profile_enable", "som_profile_read",
-    "som_set_filter", "som_set_neighborhood", "som_debug_scores_dense", "som_debug_mfma_f16",
+    "som_set_filter", "som_set_neighborhood", "som_set_scale_cooling", "som_validate_csr", "som_debug_scores_dense", "som_debug_mfma_f16",
 ]
 PROFILE_STAGES = ("bmu_dense_filter", "bmu_csr_filter", "bmu_exact", "node_sums", "smooth_divide", "prepare_dense")
 
@@ -95,6 +95,10 @@ def load():
     L.som_profile_enable.argtypes = [vp, i32]
     L.som_profile_read.restype = i32
     L.som_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
+    L.som_set_scale_cooling.restype = i32
+    L.som_set_scale_cooling.argtypes = [vp, i32]
+    L.som_validate_csr.restype = i32
+    L.som_validate_csr.argtypes = [vp, vp, vp, vp, i64, i64]
     L.som_set_filter.restype = i32
     L.som_set_filter.argtypes = [vp, i32]
     L.som_set_neighborhood.restype = i32
@@ -298,6 +302,19 @@ def som_profile_read(ctx):
 
 def som_set_neighborhood(ctx, function: int, compact_support: bool) -> None:
     _check(ctx, load().som_set_neighborhood(ctx, function, 1 if compact_support else 0))
+
+
+def som_set_scale_cooling(ctx, cooling: int) -> None:
+    _check(ctx, load().som_set_scale_cooling(ctx, cooling))
+
+
+def som_validate_csr(ctx, indptr, indices, values) -> None:
+    """Raises SomError(SOM_ERR_INVALID_ARG) naming the violation if the CSR structure is not well formed."""
+    import torch
+    _check(ctx, load().som_validate_csr(ctx, _ptr(indptr, torch.int64, "indptr"),
+                                        _ptr(indices, torch.int32, "indices", True),
+                                        _ptr(values, torch.float32, "values", True), indptr.shape[0] - 1,
+                                        0 if indices is None else indices.shape[0]))
 
 
 def som_set_filter(ctx, filter: int) -> None:

@@ -282,6 +282,46 @@ hipError_t launch_scale_values(som_ctx *c, const int32_t *indices, const float *
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- structure check (debug pass)
+// The sparse format of the paper's command line: per row, zero-based index:value pairs.  The searches
+// assume indptr[0] = 0, indptr non-decreasing up to indptr[n] = nnz, and within a row strictly
+// increasing column indices in [0, dim).  One wavefront per row; the largest violation code found is
+// left in *flag (0 = none).  A row whose bounds are not inside [0, nnz] is reported and not read.
+__global__ __launch_bounds__(256) void k_validate_csr(const int64_t *__restrict__ indptr,
+                                                      const int32_t *__restrict__ indices, int64_t n, int64_t nnz,
+                                                      int dim, int32_t *__restrict__ flag) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  int bad = 0;
+  if (wave == 0 && lane == 0) {
+    if (indptr[n] != nnz) bad = kCsrBadLast;
+    if (indptr[0] != 0) bad = kCsrBadFirst;
+  }
+  for (int64_t j = wave; j < n; j += nwaves) {
+    const int64_t s = indptr[j], e = indptr[j + 1];
+    if (s > e || s < 0 || e > nnz) {
+      bad = max(bad, (int)kCsrBadOrder);
+      continue;
+    }
+    for (int64_t p = s + lane; p < e; p += 64) {
+      const int c = indices[p];
+      if (c < 0 || c >= dim) bad = max(bad, (int)kCsrBadIndex);
+      else if (p > s && indices[p - 1] >= c) bad = max(bad, (int)kCsrBadSorted);
+    }
+  }
+  if (bad) atomicMax(flag, bad);
+}
+
+hipError_t launch_validate_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, int64_t n, int64_t nnz,
+                               int32_t *flag) {
+  int64_t blocks = (n + 3) / 4;
+  if (blocks > (int64_t)c->n_cu * 16) blocks = (int64_t)c->n_cu * 16;
+  hipLaunchKernelGGL(k_validate_csr, dim3((unsigned)blocks), dim3(256), 0, c->stream, indptr, indices, n, nnz, c->dim,
+                     flag);
+  return hipGetLastError();
+}
+
 hipError_t launch_bmu_csr_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
                                  int64_t n, bool collect) {
   if (collect) launch_sliced<true>(c, indptr, indices, values, n);

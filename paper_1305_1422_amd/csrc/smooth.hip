@@ -33,12 +33,12 @@ __device__ __forceinline__ double cooled(double v0, double vN, int n_epochs, int
 __global__ __launch_bounds__(256) void k_epoch_params(EpochParams *__restrict__ params, float *__restrict__ gx,
                                                       float *__restrict__ gy, int rows, int cols, int hex,
                                                       int epoch, int n_epochs, double r0, double rN, double s0,
-                                                      double sN, int cooling) {
+                                                      double sN, int cooling, int scale_cooling) {
   const double radius = cooled(r0, rN, n_epochs, epoch, cooling);
   const double inv = 1.0 / (8.0 * radius * radius);
   if (threadIdx.x == 0) {
     params->radius = radius;
-    params->scale = cooled(s0, sN, n_epochs, epoch, cooling);
+    params->scale = cooled(s0, sN, n_epochs, epoch, scale_cooling);
     params->inv8r2 = inv;
   }
   for (int m = threadIdx.x; m <= 2 * cols; m += blockDim.x) gx[m] = (float)exp(-(double)m * (double)m * inv);
@@ -47,11 +47,12 @@ __global__ __launch_bounds__(256) void k_epoch_params(EpochParams *__restrict__ 
 }
 
 __global__ __launch_bounds__(256) void k_cool_schedule(int n_epochs, double r0, double rN, double s0, double sN,
-                                                       int cooling, double *__restrict__ radius_out,
+                                                       int cooling, int scale_cooling,
+                                                       double *__restrict__ radius_out,
                                                        double *__restrict__ scale_out) {
   for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < n_epochs; e += gridDim.x * blockDim.x) {
     if (radius_out) radius_out[e] = cooled(r0, rN, n_epochs, e, cooling);
-    if (scale_out) scale_out[e] = cooled(s0, sN, n_epochs, e, cooling);
+    if (scale_out) scale_out[e] = cooled(s0, sN, n_epochs, e, scale_cooling);
   }
 }
 
@@ -183,17 +184,21 @@ __global__ __launch_bounds__(256) void k_smooth_y_divide(const float *__restrict
   }
 }
 
+// The learning rate follows its own cooling kind if one was set (som_set_scale_cooling), else the radius' kind.
+static int scale_cooling_of(const som_ctx *c, int cooling) { return c->scale_cooling >= 0 ? c->scale_cooling : cooling; }
+
 hipError_t launch_epoch_params(som_ctx *c, int epoch, int n_epochs, double r0, double rN, double s0, double sN,
                                int cooling) {
   hipLaunchKernelGGL(k_epoch_params, dim3(1), dim3(256), 0, c->stream, c->params, c->gx, c->gy, c->rows, c->cols,
-                     c->grid_type == SOM_GRID_HEXAGONAL, epoch, n_epochs, r0, rN, s0, sN, cooling);
+                     c->grid_type == SOM_GRID_HEXAGONAL, epoch, n_epochs, r0, rN, s0, sN, cooling,
+                     scale_cooling_of(c, cooling));
   return hipGetLastError();
 }
 
 hipError_t launch_cool_schedule(som_ctx *c, int n_epochs, double r0, double rN, double s0, double sN,
                                 int cooling, double *radius_out, double *scale_out) {
   hipLaunchKernelGGL(k_cool_schedule, dim3((n_epochs + 255) / 256), dim3(256), 0, c->stream, n_epochs, r0, rN, s0,
-                     sN, cooling, radius_out, scale_out);
+                     sN, cooling, scale_cooling_of(c, cooling), radius_out, scale_out);
   return hipGetLastError();
 }
 

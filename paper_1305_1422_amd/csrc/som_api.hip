@@ -372,6 +372,7 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
   c->stream = (hipStream_t)hip_stream;
   csr_slice_geometry(c->k, &c->csr_acc, &c->csr_sweeps, &c->kpad);
   c->filter = SOM_FILTER_SPLIT_F16;
+  c->scale_cooling = -1;
 
   int dev = 0;
   hipDeviceProp_t prop;
@@ -685,6 +686,35 @@ int som_set_neighborhood(som_ctx *c, int function, int compact_support) {
   c->nb_function = function;
   c->nb_compact = compact_support ? 1 : 0;
   return SOM_OK;
+}
+
+int som_set_scale_cooling(som_ctx *c, int cooling) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (cooling != SOM_COOL_AS_RADIUS && cooling != SOM_COOL_LINEAR && cooling != SOM_COOL_EXPONENTIAL)
+    return fail(c, SOM_ERR_INVALID_ARG, "unknown cooling %d", cooling);
+  c->scale_cooling = cooling;
+  return SOM_OK;
+}
+
+int som_validate_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values, int64_t n,
+                     int64_t nnz) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  int rc = check_csr(c, indptr, indices, values, n, nnz);
+  if (rc) return rc;
+  int32_t *flag = c->list_counts + 3;
+  int32_t bad = 0;
+  SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, flag, 1));
+  SOM_LAUNCH(c, launch_validate_csr(c, indptr, indices, n, nnz, flag));
+  SOM_LAUNCH(c, hipMemcpyAsync(&bad, flag, sizeof(bad), hipMemcpyDeviceToHost, c->stream));
+  SOM_LAUNCH(c, hipStreamSynchronize(c->stream));
+  switch (bad) {
+    case 0: return SOM_OK;
+    case kCsrBadFirst: return fail(c, SOM_ERR_INVALID_ARG, "CSR: indptr[0] is not 0");
+    case kCsrBadLast: return fail(c, SOM_ERR_INVALID_ARG, "CSR: indptr[n] is not nnz");
+    case kCsrBadOrder: return fail(c, SOM_ERR_INVALID_ARG, "CSR: indptr decreases or leaves [0, nnz]");
+    case kCsrBadIndex: return fail(c, SOM_ERR_INVALID_ARG, "CSR: a column index is outside [0, dim)");
+    default: return fail(c, SOM_ERR_INVALID_ARG, "CSR: column indices of a row are not strictly increasing");
+  }
 }
 
 int som_set_filter(som_ctx *c, int filter) {

@@ -69,6 +69,7 @@ struct som_ctx {
   int32_t *hit_rows;      // [rows+1] map rows with chosen nodes, last entry = their number
   int nb_function;        // SOM_NEIGHBORHOOD_*
   int nb_compact;         // Gaussian cut off at the current radius
+  int scale_cooling;      // SOM_COOL_* of the learning rate, or -1: the kind the call gives for the radius
   float *H2;              // neighbourhood weights by (parity class, row distance, column offset), lazily allocated
   som::EpochParams *params;   // [1]
   float *S;               // [k][dim] per-node sums
@@ -108,7 +109,8 @@ struct som_ctx {
   int32_t *collect_cnt;   // [n] nodes found under the threshold
   int32_t *collect_list;  // [n][kListCap] those nodes (dense path only, lazily allocated)
   int32_t *rescan_list;   // [n] instances that need an exact scan of all nodes
-  int32_t *list_counts;   // [0..2] lengths of refine_list, collect_rows, rescan_list; [4..11] of unit_work per slice
+  int32_t *list_counts;   // [0..2] lengths of refine_list, collect_rows, rescan_list; [3] flag of som_validate_csr;
+                          // [4..11] lengths of unit_work per slice
   int64_t *unit_work;     // [8][unit_cap] sparse search: (collect slot, node range) units to sweep again
   int64_t unit_cap;
   int32_t *sort_key[2];   // [n] each
@@ -209,6 +211,9 @@ hipError_t launch_mask_duplicate_rows(som_ctx *c, const float *W);   // wn32[i] 
 hipError_t launch_transpose_codebook(som_ctx *c, const float *W);
 void csr_slice_geometry(int k, int *acc, int *sweeps, int *kpad);
 hipError_t launch_scale_values(som_ctx *c, const int32_t *indices, const float *values, int64_t nnz);   // -> vq
+enum { kCsrBadSorted = 1, kCsrBadIndex = 2, kCsrBadOrder = 3, kCsrBadLast = 4, kCsrBadFirst = 5 };   // k_validate_csr: the largest is reported
+hipError_t launch_validate_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, int64_t n, int64_t nnz,
+                               int32_t *flag);
 hipError_t launch_bmu_csr_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
                                  int64_t n, bool collect);
 

@@ -58,6 +58,15 @@ class Som:
         off beyond the epoch's radius."""
         capi.som_set_neighborhood(self.ctx, NEIGHBORHOODS[function], compact_support)
 
+    def set_scale_cooling(self, cooling: Optional[str]) -> None:
+        """Cooling kind of the learning rate where it differs from the radius' ("linear", "exponential");
+        None = the same as the radius."""
+        capi.som_set_scale_cooling(self.ctx, capi.SOM_COOL_AS_RADIUS if cooling is None else COOLING[cooling])
+
+    def validate_csr(self, csr) -> None:
+        """Debug pass: raises capi.SomError if the CSR triple (indptr, indices, values) is malformed."""
+        capi.som_validate_csr(self.ctx, csr[0], csr[1], csr[2])
+
     def set_filter(self, filter: str) -> None:
         """Arithmetic of the dense BMU filter pass: "split_f16" (default) or "fp32"; same results."""
         capi.som_set_filter(self.ctx, FILTERS[filter])

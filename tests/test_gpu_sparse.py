@@ -285,3 +285,37 @@ def test_nodes_updated_by_a_single_instance(oracle, nb, compact, radius):
                          radius, function=1 if nb == "bubble" else 0, compact=compact)
     assert zero_best >= n // 2, "hardly any instance ever sat on a node: the test misses its case"
     som.close()
+
+
+def test_validate_csr_names_every_kind_of_violation():
+    from paper_1305_1422_amd import Som, capi
+    dim, n = 300, 500
+    indptr, indices, values = sparse_zipf_csr(n, dim, 61, mean_len=12.0, max_len=40)
+    som = Som(3, 3, dim, seed=5)
+    som.validate_csr(P.csr_to_dev((indptr, indices, values)))
+
+    def expect(ip, ix, what):
+        with pytest.raises(capi.SomError) as err:
+            som.validate_csr(P.csr_to_dev((ip, ix, values[: ix.size])))
+        assert err.value.code == capi.SOM_ERR_INVALID_ARG and what in str(err.value)
+
+    ip = indptr.copy(); ip[0] = 1
+    expect(ip, indices, "indptr[0]")
+    ip = indptr.copy(); ip[-1] -= 1
+    expect(ip, indices, "indptr[n]")
+    ip = indptr.copy(); ip[200] = ip[201] + 3
+    expect(ip, indices, "indptr decreases")
+    ip = indptr.copy(); ip[77] = -5
+    expect(ip, indices, "indptr decreases")
+    ix = indices.copy(); ix[indptr[123]] = dim
+    expect(indptr, ix, "outside [0, dim)")
+    ix = indices.copy(); ix[indptr[400] + 1] = -1
+    expect(indptr, ix, "outside [0, dim)")
+    j = int(np.argmax(np.diff(indptr) >= 3))
+    ix = indices.copy(); ix[indptr[j] + 1], ix[indptr[j] + 2] = ix[indptr[j] + 2], ix[indptr[j] + 1]
+    expect(indptr, ix, "strictly increasing")
+    ix = indices.copy(); ix[indptr[j] + 1] = ix[indptr[j]]            # a duplicate column
+    expect(indptr, ix, "strictly increasing")
+    # all rows empty, and a row that ends the array, are well formed
+    som.validate_csr(P.csr_to_dev((np.zeros(n + 1, np.int64), indices[:0], values[:0])))
+    som.close()

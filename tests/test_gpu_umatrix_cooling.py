@@ -47,3 +47,20 @@ def test_cooling_defaults_follow_the_papers_command_line(oracle):
     np.testing.assert_allclose(r.cpu().numpy(), [15.0, 15.0 - 14.0 / 3, 15.0 - 28.0 / 3, 1.0], rtol=1e-13)
     np.testing.assert_allclose(s.cpu().numpy()[[0, -1]], [1.0, float(np.float32(0.01))], rtol=1e-13)
     som.close()
+
+
+@pytest.mark.parametrize("radius_kind,scale_kind", [("linear", "exponential"), ("exponential", "linear"),
+                                                    ("exponential", None)])
+def test_radius_and_learning_rate_cool_by_their_own_kinds(oracle, radius_kind, scale_kind):
+    """Options -t and -T of the command line are separate: the radius may cool linearly while the
+    learning rate cools exponentially, and the other way round."""
+    from paper_1305_1422_amd import Som
+    E, r0, rN, s0, sN = 9, 20.0, 2.0, 0.5, 0.0625
+    som = Som(4, 4, 2, seed=3)
+    som.set_scale_cooling(scale_kind)
+    r, s = som.cool_schedule(E, r0, rN, s0, sN, radius_kind)
+    want_r = [oracle.cool(r0, rN, E, e, oracle.COOLING[radius_kind]) for e in range(E)]
+    want_s = [oracle.cool(s0, sN, E, e, oracle.COOLING[scale_kind or radius_kind]) for e in range(E)]
+    np.testing.assert_allclose(r.cpu().numpy(), want_r, rtol=1e-13)
+    np.testing.assert_allclose(s.cpu().numpy(), want_s, rtol=1e-13)
+    som.close()
