@@ -21,8 +21,12 @@
 #include "som_internal.hpp"
 
 #include <math.h>
+#include <stdlib.h>
 
 namespace som {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ double cooled(double v0, double vN, int n_epochs, int epoch, int kind) {
   if (n_epochs <= 1) return v0;
@@ -390,6 +394,232 @@ __global__ __launch_bounds__(256) void k_smooth_y_mat(const float *__restrict__ 
   }
 }
 
+// ---------------------------------------------------------------- feature channels, matrix cores
+// On a map with a side of a hundred nodes or more, a pass of the separable filter is a real matrix
+// product: out[m][c] = sum_t G[m][src_t] In[src_t][c] over the sources of one map line (pass x: the
+// chosen nodes of a map row; pass y: the map rows that hold chosen nodes), m = the outputs along the
+// line, c = the feature channels.  k_smooth_mfma runs it on v_mfma_f32_32x32x2_f32 - fp32 operands as
+// they are, fp32 accumulation, the same arithmetic class as the vector kernels above.  MFMA rows =
+// outputs m (A operand = coefficients from the transposed coefficient matrices), MFMA columns = 32
+// consecutive channels (B operand = the source rows as they lie in memory), so a lane ends up with one
+// channel and 16 outputs per block and every store instruction writes whole 128-byte runs.  A
+// wavefront owns 32 channels and MB blocks of 32 outputs (all outputs of the line when they fit into
+// seven blocks: the sources are then read exactly once), a workgroup 256 channels.  Both operands go
+// through LDS in chunks of 16 sources, double-buffered: the coefficients because all wavefronts of
+// the workgroup multiply with the same ones, the source rows because the workgroup can then fetch each
+// of them as one contiguous kilobyte (one wavefront instruction) instead of eight separate 128-byte
+// pieces at different times - the rows of one line are megabytes apart, and what the memory system
+// sees of this kernel is a stream of such row visits.
+constexpr int kMfmaChunk = 16;      // sources per LDS stage (8 MFMA k-steps of 2)
+constexpr int kMfmaMaxBlocks = 7;   // 32-output blocks per wavefront: 7 x 16 accumulator registers
+constexpr int kMfmaWaves = 8;       // wavefronts (32-channel slices) per workgroup
+
+template <int MB, bool kPassY, bool kHex, bool kVec4>
+__global__ __launch_bounds__(64 * kMfmaWaves) void k_smooth_mfma(const float *__restrict__ In, float *__restrict__ Out,
+                                                     const float *__restrict__ Gt,
+                                                     const int32_t *__restrict__ hit_x,
+                                                     const int32_t *__restrict__ hit_n,
+                                                     const int32_t *__restrict__ hit_rows,
+                                                     const double *__restrict__ massD, int rows, int cols, int dim,
+                                                     int g_pad, int groups) {
+  constexpr int kM = 32 * MB;                        // outputs per workgroup
+  constexpr int kCh = 32 * kMfmaWaves;               // channels per workgroup
+  constexpr int kThreads = 64 * kMfmaWaves;
+  constexpr int kVecs = kMfmaChunk * (kM / 4);       // 16-byte pieces of one coefficient chunk
+  constexpr int kPer = (kVecs + kThreads - 1) / kThreads;
+  constexpr int kBPer = kMfmaChunk * (kCh / 4) / kThreads;      // 16-byte pieces of a source chunk per thread
+  static_assert(kMfmaChunk * (kCh / 4) % kThreads == 0, "source chunk must divide evenly among the threads");
+  __shared__ __attribute__((aligned(16))) float sG[2][kMfmaChunk][kM];
+  __shared__ __attribute__((aligned(16))) float sB[2][kMfmaChunk][kCh];
+  __shared__ int sSrc[kSmoothMatMax + kMfmaChunk];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int cb0 = blockIdx.x * kCh;                  // first channel of the workgroup
+  const int c = cb0 + wave * 32 + l32;
+  const bool live = c < dim;
+  const int line = blockIdx.y;                       // pass x: map row y; pass y: map column x
+  const int part = blockIdx.z / groups;              // pass x: image (parity of the destination rows); pass y: class
+  const int m0 = (blockIdx.z - part * groups) * kM;
+  const int classes = kHex ? 2 : 1;
+
+  int ns;                                            // sources of this line
+  const int32_t *src;
+  const float *G;                                    // coefficient rows: G[source * g_pad + m]
+  const float *in;                                   // In[source * in_stride + channel]
+  int64_t in_stride;
+  if (kPassY) {
+    ns = hit_rows[rows];
+    if (ns <= 0) return;                             // nothing was chosen: every node keeps its weights
+    src = hit_rows;
+    G = Gt + (int64_t)part * rows * g_pad;
+    in = In + (kHex ? (int64_t)part * rows * cols * dim : 0) + (int64_t)line * dim;
+    in_stride = (int64_t)cols * dim;
+  } else {
+    ns = hit_n[line];
+    if (ns == 0) return;                             // pass y skips this map row
+    src = hit_x + (int64_t)line * cols;
+    G = Gt + ((int64_t)(part * classes + (kHex ? (line & 1) : 0)) * cols) * g_pad;
+    in = In + (int64_t)line * cols * dim;
+    in_stride = dim;
+  }
+
+  // The source list of the line goes into LDS once, padded with its last entry to a whole chunk, so
+  // that the loads below need neither an index fetch from memory nor a bounds branch: a source past
+  // the end repeats the last one, and its values are replaced by zeros before they are multiplied.
+  for (int i = tid; i < ns + kMfmaChunk; i += kThreads) sSrc[i] = src[i < ns ? i : ns - 1];
+  __syncthreads();
+
+  // Coefficients of a chunk, [source][output]: thread t fetches the 16-byte pieces t, t + kThreads, ...
+  // Outputs past the padded row are read from its last piece; they are never stored.
+  f32x4 greg[kPer];
+  auto fetch_coefficients = [&](int t0) {
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      const int e = min(tid + i * kThreads, kVecs - 1);
+      const int r = e / (kM / 4), q = e - r * (kM / 4);
+      greg[i] = *reinterpret_cast<const f32x4 *>(G + (int64_t)sSrc[t0 + r] * g_pad + min(m0 + 4 * q, g_pad - 4));
+    }
+  };
+  // Source rows of a chunk, [source][channel]: a wavefront fetches one row of kCh channels per
+  // instruction.  Channels past dim repeat the last ones (their outputs are not stored).
+  f32x4 breg[kBPer];
+  auto fetch_sources = [&](int t0) {
+#pragma unroll
+    for (int i = 0; i < kBPer; ++i) {
+      const int e = tid + i * kThreads;
+      const int r = e / (kCh / 4), q = e - r * (kCh / 4);
+      const float *row = in + (int64_t)sSrc[t0 + r] * in_stride;
+      const int ch = cb0 + 4 * q;
+      if (kVec4) {
+        breg[i] = *reinterpret_cast<const f32x4 *>(row + min(ch, dim - 4));
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) breg[i][j] = row[min(ch + j, dim - 1)];
+      }
+    }
+  };
+  auto stash = [&](int stage, int t0) {
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      const int e = tid + i * kThreads;
+      if (e < kVecs) *reinterpret_cast<f32x4 *>(&sG[stage][0][0] + 4 * e) = greg[i];
+    }
+#pragma unroll
+    for (int i = 0; i < kBPer; ++i) {
+      const int e = tid + i * kThreads;
+      const bool on = t0 + e / (kCh / 4) < ns;
+      *reinterpret_cast<f32x4 *>(&sB[stage][0][0] + 4 * e) = on ? breg[i] : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+  };
+
+  f32x16 acc[MB];
+#pragma unroll
+  for (int b = 0; b < MB; ++b)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
+
+  fetch_coefficients(0);
+  fetch_sources(0);
+  stash(0, 0);
+  __syncthreads();
+  int stage = 0;
+  for (int t0 = 0; t0 < ns; t0 += kMfmaChunk) {
+    const bool more = t0 + kMfmaChunk < ns;
+    if (more) {
+      fetch_coefficients(t0 + kMfmaChunk);
+      fetch_sources(t0 + kMfmaChunk);
+    }
+    // operands of pair u + 1 are read from LDS while the matrix instructions of pair u run
+    float a[2][MB], bv[2];
+#pragma unroll
+    for (int b = 0; b < MB; ++b) a[0][b] = sG[stage][lhi][32 * b + l32];
+    bv[0] = sB[stage][lhi][wave * 32 + l32];
+#pragma unroll
+    for (int u = 0; u < kMfmaChunk / 2; ++u) {
+      if (u + 1 < kMfmaChunk / 2) {
+#pragma unroll
+        for (int b = 0; b < MB; ++b) a[(u + 1) & 1][b] = sG[stage][2 * (u + 1) + lhi][32 * b + l32];
+        bv[(u + 1) & 1] = sB[stage][2 * (u + 1) + lhi][wave * 32 + l32];
+      }
+      __builtin_amdgcn_sched_barrier(0);             // keep those reads ahead of the multiplications they overlap with
+#pragma unroll
+      for (int b = 0; b < MB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u & 1][b], bv[u & 1], acc[b], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (more) stash(stage ^ 1, t0 + kMfmaChunk);     // that stage was last read before the previous barrier
+    __syncthreads();
+    stage ^= 1;
+  }
+
+  const int mtot = kPassY ? (rows - part + classes - 1) / classes : cols;     // outputs of this line (and class)
+  // pass y divides by the neighbourhood mass: the masses of the line's outputs are fetched by the
+  // workgroup once (0 stands for "below the floor: keep the weights"), so that the stores below are
+  // not interleaved with dependent loads
+  float *sD = &sG[0][0][0];                          // every wavefront has left the loop: the stages are free
+  if (kPassY) {
+    for (int ml = tid; ml < kM; ml += kThreads) {
+      const int m = m0 + ml;
+      double D = 0.0;
+      if (m < mtot) D = massD[(int64_t)(classes * m + part) * cols + line];
+      sD[ml] = D >= SOM_EPS_MASS ? (float)D : 0.f;
+    }
+    __syncthreads();
+  }
+  if (!live) return;
+#pragma unroll
+  for (int b = 0; b < MB; ++b)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int ml = 32 * b + 8 * (v >> 2) + 4 * lhi + (v & 3);
+      const int m = m0 + ml;
+      if (m >= mtot) continue;
+      if (kPassY) {
+        const float D = sD[ml];
+        if (D > 0.f) Out[((int64_t)(classes * m + part) * cols + line) * dim + c] = acc[b][v] / D;
+      } else {
+        Out[(((int64_t)part * rows + line) * cols + m) * (int64_t)dim + c] = acc[b][v];
+      }
+    }
+}
+
+// Blocks of 32 outputs per wavefront and groups of such wavefront tiles for a line of `outputs` outputs.
+static void mfma_tiling(int outputs, int *mb, int *groups) {
+  const int nb = (outputs + 31) / 32;
+  *groups = (nb + kMfmaMaxBlocks - 1) / kMfmaMaxBlocks;
+  *mb = (nb + *groups - 1) / *groups;
+}
+
+template <bool kPassY, bool kHex>
+static void launch_smooth_mfma(som_ctx *c, const float *In, float *Out, const float *Gt, int g_pad, int outputs,
+                               int lines, int parts) {
+  int mb, groups;
+  mfma_tiling(outputs, &mb, &groups);
+  const dim3 grid((unsigned)((c->dim + 32 * kMfmaWaves - 1) / (32 * kMfmaWaves)), (unsigned)lines, (unsigned)(parts * groups));
+  // 16-byte loads of the source rows need rows that start and stay on 16-byte boundaries
+  const bool vec4 = c->dim % 4 == 0 && c->dim >= 4 && (reinterpret_cast<uintptr_t>(In) & 15) == 0;
+#define SOM_SMOOTH_MFMA(B)                                                                                          \
+  do {                                                                                                              \
+    if (vec4)                                                                                                       \
+      hipLaunchKernelGGL((k_smooth_mfma<B, kPassY, kHex, true>), grid, dim3(64 * kMfmaWaves), 0, c->stream, In, Out, \
+                         Gt, c->hit_x, c->hit_n, c->hit_rows, c->massD, c->rows, c->cols, c->dim, g_pad, groups);    \
+    else                                                                                                            \
+      hipLaunchKernelGGL((k_smooth_mfma<B, kPassY, kHex, false>), grid, dim3(64 * kMfmaWaves), 0, c->stream, In,     \
+                         Out, Gt, c->hit_x, c->hit_n, c->hit_rows, c->massD, c->rows, c->cols, c->dim, g_pad, groups); \
+  } while (0)
+  switch (mb) {
+    case 1: SOM_SMOOTH_MFMA(1); break;
+    case 2: SOM_SMOOTH_MFMA(2); break;
+    case 3: SOM_SMOOTH_MFMA(3); break;
+    case 4: SOM_SMOOTH_MFMA(4); break;
+    case 5: SOM_SMOOTH_MFMA(5); break;
+    case 6: SOM_SMOOTH_MFMA(6); break;
+    default: SOM_SMOOTH_MFMA(7); break;
+  }
+#undef SOM_SMOOTH_MFMA
+}
+
 // ---------------------------------------------------------------- neighbourhoods with compact support
 // The bubble function and the Gaussian cut off at the current radius (options -n and -p of the
 // paper's command line) are not products of a factor in x and a factor in y, so the two-pass
@@ -587,16 +817,23 @@ hipError_t launch_smooth_and_divide(som_ctx *c, float *W) {
     const unsigned cb8 = (cb256 + 7) / 8 * 8;
     const dim3 gx = fold ? dim3(cb8 * xt, c->rows, 1) : dim3(cb256, c->rows, xt);
     const dim3 gy = fold ? dim3(cb8 * yt, c->cols, 1) : dim3(cb256, c->cols, yt);
+    // a pass runs on the matrix cores when its line is long enough to fill their 32-output blocks
+    const bool mfma_x = c->smooth_mfma_min > 0 && c->cols >= c->smooth_mfma_min;
+    const bool mfma_y = c->smooth_mfma_min > 0 && c->rows >= c->smooth_mfma_min;
     if (hex) {
-      hipLaunchKernelGGL(k_smooth_x_mat<true>, gx, dim3(256), 0, c->stream, c->S, c->T, c->GxT,
-                         c->hit_x, c->hit_n, c->rows, c->cols, c->dim, c->xi_pad);
-      hipLaunchKernelGGL(k_smooth_y_mat<true>, gy, dim3(256), 0, c->stream, c->T, W, c->GyT,
-                         c->hit_rows, c->massD, c->rows, c->cols, c->dim, c->e_pad);
+      if (mfma_x) launch_smooth_mfma<false, true>(c, c->S, c->T, c->GxT, c->xi_pad, c->cols, c->rows, 2);
+      else hipLaunchKernelGGL(k_smooth_x_mat<true>, gx, dim3(256), 0, c->stream, c->S, c->T, c->GxT,
+                              c->hit_x, c->hit_n, c->rows, c->cols, c->dim, c->xi_pad);
+      if (mfma_y) launch_smooth_mfma<true, true>(c, c->T, W, c->GyT, c->e_pad, (c->rows + 1) / 2, c->cols, 2);
+      else hipLaunchKernelGGL(k_smooth_y_mat<true>, gy, dim3(256), 0, c->stream, c->T, W, c->GyT,
+                              c->hit_rows, c->massD, c->rows, c->cols, c->dim, c->e_pad);
     } else {
-      hipLaunchKernelGGL(k_smooth_x_mat<false>, gx, dim3(256), 0, c->stream, c->S, c->T, c->GxT,
-                         c->hit_x, c->hit_n, c->rows, c->cols, c->dim, c->xi_pad);
-      hipLaunchKernelGGL(k_smooth_y_mat<false>, gy, dim3(256), 0, c->stream, c->T, W, c->GyT,
-                         c->hit_rows, c->massD, c->rows, c->cols, c->dim, c->e_pad);
+      if (mfma_x) launch_smooth_mfma<false, false>(c, c->S, c->T, c->GxT, c->xi_pad, c->cols, c->rows, 1);
+      else hipLaunchKernelGGL(k_smooth_x_mat<false>, gx, dim3(256), 0, c->stream, c->S, c->T, c->GxT,
+                              c->hit_x, c->hit_n, c->rows, c->cols, c->dim, c->xi_pad);
+      if (mfma_y) launch_smooth_mfma<true, false>(c, c->T, W, c->GyT, c->e_pad, c->rows, c->cols, 1);
+      else hipLaunchKernelGGL(k_smooth_y_mat<false>, gy, dim3(256), 0, c->stream, c->T, W, c->GyT,
+                              c->hit_rows, c->massD, c->rows, c->cols, c->dim, c->e_pad);
     }
     return hipGetLastError();
   }

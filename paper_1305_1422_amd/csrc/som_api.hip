@@ -373,6 +373,8 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
   csr_slice_geometry(c->k, &c->csr_acc, &c->csr_sweeps, &c->kpad);
   c->filter = SOM_FILTER_SPLIT_F16;
   c->scale_cooling = -1;
+  c->smooth_mfma_min = 128;
+  if (const char *v = getenv("SOM_SMOOTH_MFMA_MIN")) c->smooth_mfma_min = atoi(v);      // timing experiments only
 
   int dev = 0;
   hipDeviceProp_t prop;
@@ -395,8 +397,8 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
             dev_alloc(&c->hit_x, K) && dev_alloc(&c->hit_n, (size_t)rows) && dev_alloc(&c->hit_rows, (size_t)rows + 1);
   if (ok && rows <= kSmoothMatMax && cols <= kSmoothMatMax) {
     const size_t par = grid_type == SOM_GRID_HEXAGONAL ? 2 : 1;
-    c->xi_pad = ((cols + 15) / 16) * 16;
-    c->e_pad = (int)(((((size_t)rows + par - 1) / par) + 15) / 16) * 16;
+    c->xi_pad = ((cols + 31) / 32) * 32;
+    c->e_pad = (int)(((((size_t)rows + par - 1) / par) + 31) / 32) * 32;
     ok = dev_alloc(&c->GxT, par * par * cols * c->xi_pad) && dev_alloc(&c->GyT, par * rows * c->e_pad);
   }
   if (!ok) {

@@ -64,7 +64,8 @@ struct som_ctx {
   float *gx;              // [2*cols+1] neighbourhood factor along x, index = twice the x offset
   float *gy;              // [rows] neighbourhood factor along y
   float *GxT, *GyT;       // the two filters as transposed coefficient matrices (maps with sides <= kSmoothMatMax)
-  int xi_pad, e_pad;      // padded output extents of GxT / GyT (multiples of 16)
+  int xi_pad, e_pad;      // padded output extents of GxT / GyT (multiples of 32)
+  int smooth_mfma_min;    // a smoothing pass over lines of at least this many nodes runs on the matrix cores (0: never)
   int32_t *hit_x, *hit_n; // [k] columns of the chosen nodes per map row, [rows] their number
   int32_t *hit_rows;      // [rows+1] map rows with chosen nodes, last entry = their number
   int nb_function;        // SOM_NEIGHBORHOOD_*
