@@ -297,17 +297,24 @@ int som_set_neighborhood(som_ctx *ctx, int function, int compact_support);
 int som_set_filter(som_ctx *ctx, int filter);
 
 /*
- * som_debug_scores_dense - test hook (not an operation of the paper): runs the split-fp16
- * filter on data [n][dim] against codebook and writes EVERY score, not just the candidates:
- * scores[j * rows*cols + i] = c_i - 2 x_j . w'_i as the filter computed it, w' = fl(w - mu),
- * c_i = |w'_i|^2 + 2 mu . w'_i; mu_out [dim] receives the centring vector mu that was used.
- * All pointers are device pointers; scores must hold n * rows*cols floats.  A test compares
- * the scores with their exact values and the rounding bound the exact stage relies on.
- * Errors: NULL pointers, n out of range -> SOM_ERR_INVALID_ARG; filter is not
- * SOM_FILTER_SPLIT_F16 -> SOM_ERR_STATE.
+ * som_debug_scores_dense / som_debug_scores_csr - test hooks (not operations of the paper): run the
+ * filter pass of the BMU search (the dense one selected by som_set_filter, or the sparse sweep) on
+ * the given data against codebook and write EVERY score, not just the candidates:
+ *   scores[j * rows*cols + i] = c_i - 2 x_j . w'_i as the filter computed it, w' = fl(w - mu),
+ *   c_i = |w'_i|^2 + 2 mu . w'_i  (the sparse sweep multiplies with a 16-bit quantisation of w');
+ *   mu_out [dim]    the centring vector mu that was used;
+ *   margin_out [n]  fp64: the margin the exact stage applies to instance j - two scores of j whose
+ *                   difference exceeds it are taken as decided - evaluated by the same device
+ *                   function on the same inputs.  It is meant to cover the error of both scores.
+ * All pointers are device pointers; scores must hold n * rows*cols floats.  A test compares the
+ * scores with their exact values and checks that no error exceeds half the margin.
+ * Errors: NULL pointers, n / nnz out of range -> SOM_ERR_INVALID_ARG.
  */
 int som_debug_scores_dense(som_ctx *ctx, const float *data, int64_t n, const float *codebook, float *scores,
-                           float *mu_out);
+                           float *mu_out, double *margin_out);
+int som_debug_scores_csr(som_ctx *ctx, const int64_t *indptr, const int32_t *indices, const float *values,
+                         int64_t n, int64_t nnz, const float *codebook, float *scores, float *mu_out,
+                         double *margin_out);
 
 /*
  * som_debug_mfma_f16 - test hook (not an operation of the paper): `count` independent

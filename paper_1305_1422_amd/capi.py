@@ -30,7 +30,7 @@ EXPORTS = [
     "som_bmu_distances_dense", "som_bmu_distances_csr", "som_bmu_distances_dense_static",
     "som_cool_schedule", "som_umatrix", "som_get_stats",
     "som_profile_enable", "som_profile_read",
-    "som_set_filter", "som_set_neighborhood", "som_set_scale_cooling", "som_validate_csr", "som_debug_scores_dense", "som_debug_mfma_f16",
+    "som_set_filter", "som_set_neighborhood", "som_set_scale_cooling", "som_validate_csr", "som_debug_scores_dense", "som_debug_scores_csr", "som_debug_mfma_f16",
 ]
 PROFILE_STAGES = ("bmu_dense_filter", "bmu_csr_filter", "bmu_exact", "node_sums", "smooth_divide", "prepare_dense")
 
@@ -104,7 +104,9 @@ def load():
     L.som_set_neighborhood.restype = i32
     L.som_set_neighborhood.argtypes = [vp, i32, i32]
     L.som_debug_scores_dense.restype = i32
-    L.som_debug_scores_dense.argtypes = [vp, vp, i64, vp, vp, vp]
+    L.som_debug_scores_dense.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+    L.som_debug_scores_csr.restype = i32
+    L.som_debug_scores_csr.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp, vp, vp]
     L.som_debug_mfma_f16.restype = i32
     L.som_debug_mfma_f16.argtypes = [vp, vp, vp, vp, i32, vp]
     _lib = L
@@ -321,13 +323,28 @@ def som_set_filter(ctx, filter: int) -> None:
     _check(ctx, load().som_set_filter(ctx, filter))
 
 
-def som_debug_scores_dense(ctx, data, codebook, scores, mu_out) -> None:
-    """Test hook: every score of the split-fp16 filter, scores [n][k], and the centring vector used."""
+def som_debug_scores_dense(ctx, data, codebook, scores, mu_out, margin_out) -> None:
+    """Test hook: every score of the dense filter in use, scores [n][k], the centring vector used and the
+    margin [n] (float64) the exact stage applies per instance."""
     import torch
     _check(ctx, load().som_debug_scores_dense(ctx, _ptr(data, torch.float32, "data"), data.shape[0],
                                               _ptr(codebook, torch.float32, "codebook"),
                                               _ptr(scores, torch.float32, "scores"),
-                                              _ptr(mu_out, torch.float32, "mu_out")))
+                                              _ptr(mu_out, torch.float32, "mu_out"),
+                                              _ptr(margin_out, torch.float64, "margin_out")))
+
+
+def som_debug_scores_csr(ctx, indptr, indices, values, codebook, scores, mu_out, margin_out) -> None:
+    """Test hook: the same for the sparse sweep."""
+    import torch
+    _check(ctx, load().som_debug_scores_csr(ctx, _ptr(indptr, torch.int64, "indptr"),
+                                            _ptr(indices, torch.int32, "indices", True),
+                                            _ptr(values, torch.float32, "values", True), indptr.shape[0] - 1,
+                                            0 if indices is None else indices.shape[0],
+                                            _ptr(codebook, torch.float32, "codebook"),
+                                            _ptr(scores, torch.float32, "scores"),
+                                            _ptr(mu_out, torch.float32, "mu_out"),
+                                            _ptr(margin_out, torch.float64, "margin_out")))
 
 
 def som_debug_mfma_f16(a, b, c_in, d_out) -> None:

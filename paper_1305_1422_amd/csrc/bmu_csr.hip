@@ -101,7 +101,7 @@ __global__ __launch_bounds__(256) void k_bmu_csr_sliced(const int64_t *__restric
                                                         const int32_t *__restrict__ rows,
                                                         UnitWork work,
                                                         const float *__restrict__ thr, int32_t *__restrict__ cnt,
-                                                        int32_t *__restrict__ list) {
+                                                        int32_t *__restrict__ list, float *__restrict__ dump) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int slice = blockIdx.x & 7;
@@ -184,6 +184,11 @@ __global__ __launch_bounds__(256) void k_bmu_csr_sliced(const int64_t *__restric
         }
       }
     } else {
+      if (dump) {                                        // test hook: every score of the unit
+#pragma unroll
+        for (int a = 0; a < ACC; ++a)
+          if (base + 64 * a < k) dump[j * k + base + 64 * a] = sc[a];
+      }
       // two best nodes of the range and the smallest score after them
       float best[3];
       int arg[2];
@@ -226,7 +231,8 @@ __global__ __launch_bounds__(256) void k_bmu_csr_sliced(const int64_t *__restric
 }
 
 template <bool kCollect>
-static void launch_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values, int64_t n) {
+static void launch_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values, int64_t n,
+                          float *dump) {
   int64_t groups = (n * c->csr_sweeps + 3) / 4;                   // workgroups per slice
   const int64_t cap = (int64_t)c->n_cu;                           // 8 slices x n_cu = 8 workgroups per CU
   if (groups > cap) groups = cap;
@@ -237,7 +243,7 @@ static void launch_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indi
   hipLaunchKernelGGL((k_bmu_csr_sliced<A, kCollect>), grid, dim3(256), 0, c->stream, indptr, indices, values,        \
                      reinterpret_cast<const int16_t *>(c->Wt), c->kpad, c->csr_sweeps, nullptr, c->wn32, n, c->k,   \
                      c->dim, out, c->row_q, c->collect_rows, work, c->collect_thr, c->collect_cnt,    \
-                     c->collect_list)
+                     c->collect_list, dump)
   switch (c->csr_acc) {
     case 1: SOM_SLICED(1); break;
     case 2: SOM_SLICED(2); break;
@@ -323,9 +329,9 @@ hipError_t launch_validate_csr(som_ctx *c, const int64_t *indptr, const int32_t 
 }
 
 hipError_t launch_bmu_csr_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
-                                 int64_t n, bool collect) {
-  if (collect) launch_sliced<true>(c, indptr, indices, values, n);
-  else launch_sliced<false>(c, indptr, indices, values, n);
+                                 int64_t n, bool collect, float *dump) {
+  if (collect) launch_sliced<true>(c, indptr, indices, values, n, nullptr);
+  else launch_sliced<false>(c, indptr, indices, values, n, dump);
   return hipGetLastError();
 }
 

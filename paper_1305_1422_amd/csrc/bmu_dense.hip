@@ -59,7 +59,7 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense(const float *__restrict__ 
                                                       CandView out, const int32_t *__restrict__ rows,
                                                       const int32_t *__restrict__ n_slots,
                                                       const float *__restrict__ thr, int32_t *__restrict__ cnt,
-                                                      int32_t *__restrict__ list) {
+                                                      int32_t *__restrict__ list, float *__restrict__ dump) {
   __shared__ __attribute__((aligned(16))) float sW[2][kTN * kLS];
   __shared__ __attribute__((aligned(16))) float sX[2][kTI * kLS];
   __shared__ float sWn[2][kTN];
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense(const float *__restrict__ 
 #pragma unroll
           for (int v = 0; v < 16; ++v) { tot[mi][ni][v] += acc[mi][ni][v]; acc[mi][ni][v] = 0.f; }
     }
-    if (last_k) consume_scores<kCollect>(tot, sWn[nb & 1], nb * kTN, k, wm, lhi, kMinusTwo, top, lim, slot_of, cnt, list);
+    if (last_k) consume_scores<kCollect>(tot, sWn[nb & 1], nb * kTN, k, wm, lhi, kMinusTwo, top, lim, slot_of, cnt, list, dump, n);
 
     if (t + 1 < total) stage(t + 1);
     __syncthreads();
@@ -207,12 +207,12 @@ int bmu_dense_groups(const som_ctx *c, int64_t n) {
   return (nNB + nb_per - 1) / nb_per;
 }
 
-hipError_t launch_bmu_dense(som_ctx *c, const float *X, int64_t n) {
+hipError_t launch_bmu_dense(som_ctx *c, const float *X, int64_t n, float *dump) {
   CandView out{c->cand_val, c->cand_idx, c->cand_over};
   const dim3 grid((unsigned)((n + kTI - 1) / kTI), (unsigned)bmu_dense_groups(c, n));
-  if (direct_loads_ok(c, X)) return launch_bmu_dense_dl(c, X, n, grid, false);
+  if (direct_loads_ok(c, X)) return launch_bmu_dense_dl(c, X, n, grid, false, dump);
   hipLaunchKernelGGL((k_bmu_dense<false>), grid, dim3(256), 0, c->stream, X, c->Wc, c->wn32, n, c->k, c->dim, out,
-                     nullptr, nullptr, nullptr, nullptr, nullptr);
+                     nullptr, nullptr, nullptr, nullptr, nullptr, dump);
   return hipGetLastError();
 }
 
@@ -223,9 +223,9 @@ hipError_t launch_bmu_dense_collect(som_ctx *c, const float *X, int64_t n) {
   CandView out{nullptr, nullptr, nullptr};
   const int nNB = (c->k + kTN - 1) / kTN;
   const dim3 grid((unsigned)((n + kTI - 1) / kTI), (unsigned)(nNB < 16 ? nNB : 16));
-  if (direct_loads_ok(c, X)) return launch_bmu_dense_dl(c, X, n, grid, true);
+  if (direct_loads_ok(c, X)) return launch_bmu_dense_dl(c, X, n, grid, true, nullptr);
   hipLaunchKernelGGL((k_bmu_dense<true>), grid, dim3(256), 0, c->stream, X, c->Wc, c->wn32, n, c->k, c->dim, out,
-                     c->collect_rows, c->list_counts + 1, c->collect_thr, c->collect_cnt, c->collect_list);
+                     c->collect_rows, c->list_counts + 1, c->collect_thr, c->collect_cnt, c->collect_list, nullptr);
   return hipGetLastError();
 }
 

@@ -54,13 +54,28 @@ __device__ __forceinline__ int mfma_row(int mi, int v, int lhi) { return mi * 32
 
 // Scores of one node block, s = c_i + factor * dot (factor = -2, times the operand scales where
 // the operands were scaled): push into the running lists (filter mode) or append the nodes under
-// the per-instance threshold to the collected lists (collect mode).  `tot` is cleared.
+// the per-instance threshold to the collected lists (collect mode).  `tot` is cleared.  With `dump`
+// (filter mode, test hook) the scores of the first n_dump instances are also written out.
 template <bool kCollect>
 __device__ __forceinline__ void consume_scores(f32x16 (&tot)[2][2], const float *__restrict__ swn, int node0, int k,
                                                int wm, int lhi, const float (&factor)[2], Top2 (&top)[2],
                                                const float (&lim)[2],
                                                const int64_t (&slot_of)[2], int32_t *__restrict__ cnt,
-                                               int32_t *__restrict__ list) {
+                                               int32_t *__restrict__ list, float *__restrict__ dump = nullptr,
+                                               int64_t n_dump = 0) {
+  if (!kCollect && dump) {
+    // test hook: every score of the block goes to dump[instance][node] as well (tot is read, not cleared)
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int nl = wm * 64 + mfma_row(mi, v, lhi);
+        const int node = node0 + nl;
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+          if (node < k && slot_of[ni] < n_dump) dump[slot_of[ni] * k + node] = fmaf(factor[ni], tot[mi][ni][v], swn[nl]);
+      }
+  }
   if (kCollect) {
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)

@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense_dl(const float *__restrict
                                                          int dim, CandView out, const int32_t *__restrict__ rows,
                                                          const int32_t *__restrict__ n_slots,
                                                          const float *__restrict__ thr, int32_t *__restrict__ cnt,
-                                                         int32_t *__restrict__ list) {
+                                                         int32_t *__restrict__ list, float *__restrict__ dump) {
   __shared__ __attribute__((aligned(16))) float sW[2][kTileFloats];
   __shared__ __attribute__((aligned(16))) float sX[2][kTileFloats];
   __shared__ float sWn[2][kTN];
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense_dl(const float *__restrict
 #pragma unroll
           for (int v = 0; v < 16; ++v) { tot[mi][ni][v] += acc[mi][ni][v]; acc[mi][ni][v] = 0.f; }
     }
-    if (last_k) consume_scores<kCollect>(tot, sWn[nb & 1], nb * kTN, k, wm, lhi, kMinusTwo, top, lim, slot_of, cnt, list);
+    if (last_k) consume_scores<kCollect>(tot, sWn[nb & 1], nb * kTN, k, wm, lhi, kMinusTwo, top, lim, slot_of, cnt, list, dump, n);
 
     wait_vector_memory();
     __syncthreads();
@@ -201,16 +201,16 @@ __global__ __launch_bounds__(256, 2) void k_bmu_dense_dl(const float *__restrict
                   out);
 }
 
-hipError_t launch_bmu_dense_dl(som_ctx *c, const float *X, int64_t n, dim3 grid, bool collect) {
+hipError_t launch_bmu_dense_dl(som_ctx *c, const float *X, int64_t n, dim3 grid, bool collect, float *dump) {
   if (collect) {
     CandView out{nullptr, nullptr, nullptr};
     hipLaunchKernelGGL((k_bmu_dense_dl<true>), grid, dim3(256), 0, c->stream, X, c->Wc, c->wn32, c->zero16, n, c->k,
                        c->dim, out, c->collect_rows, c->list_counts + 1, c->collect_thr, c->collect_cnt,
-                       c->collect_list);
+                       c->collect_list, nullptr);
   } else {
     CandView out{c->cand_val, c->cand_idx, c->cand_over};
     hipLaunchKernelGGL((k_bmu_dense_dl<false>), grid, dim3(256), 0, c->stream, X, c->Wc, c->wn32, c->zero16, n, c->k,
-                       c->dim, out, nullptr, nullptr, nullptr, nullptr, nullptr);
+                       c->dim, out, nullptr, nullptr, nullptr, nullptr, nullptr, dump);
   }
   return hipGetLastError();
 }

@@ -426,14 +426,12 @@ static double split_pass_roundings(int dim) {
   return 2.5 * 6.0 * chunks + 9.0 + (double)((dim + 32 * chunks - 1) / (32 * chunks)) + 2.0;
 }
 
-hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int64_t *indptr, int32_t *bmus) {
-  CandView cand{c->cand_val, c->cand_idx, c->cand_over};
+// The rounding model of the filter that produced the scores (mode = kCertify*).
+static MarginModel margin_model(const som_ctx *c, int mode, const int64_t *indptr) {
   MarginModel mm{2.0 * fp32_pass_roundings(c->dim) + 4.0, 0.0, nullptr, nullptr, nullptr, nullptr};
-  UnitWork work{0, 0, nullptr, nullptr, nullptr};
   if (mode == kCertifyCsr) {
     mm.indptr = indptr;
     mm.row_q = c->row_q;
-    work = UnitWork{c->csr_sweeps, c->unit_cap, c->unit_work, c->list_counts + kUnitCounts, c->collect_list};
   }
   if (mode == kCertifySplit) {
     // dot product: accumulation + 3 * 2^-22 of the split (= 12 u) ; both doubled by the factor -2;
@@ -446,9 +444,32 @@ hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int
     mm.xscale = c->xscale;
     mm.wscale = c->wscale;
   }
+  return mm;
+}
+
+hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int64_t *indptr, int32_t *bmus) {
+  CandView cand{c->cand_val, c->cand_idx, c->cand_over};
+  const MarginModel mm = margin_model(c, mode, indptr);
+  UnitWork work{0, 0, nullptr, nullptr, nullptr};
+  if (mode == kCertifyCsr)
+    work = UnitWork{c->csr_sweeps, c->unit_cap, c->unit_work, c->list_counts + kUnitCounts, c->collect_list};
   hipLaunchKernelGGL(k_certify, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, cand, groups, c->xn32,
                      c->wmax_bits, c->mu_norm2, mm, n, c->k, bmus, c->cand_n, c->refine_list, c->collect_rows,
                      c->collect_thr, c->collect_cnt, c->list_counts, work);
+  return hipGetLastError();
+}
+
+// Test hook: the margin k_certify applies to every instance (the same function, the same inputs).
+__global__ __launch_bounds__(256) void k_margins(const float *__restrict__ xn32, const unsigned *__restrict__ wmax_bits,
+                                                 const float *__restrict__ mu_norm2, MarginModel mm, int64_t n,
+                                                 double *__restrict__ out) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j < n) out[j] = score_margin(mm, j, (double)xn32[j], (double)__uint_as_float(*wmax_bits), (double)*mu_norm2);
+}
+
+hipError_t launch_margins(som_ctx *c, int64_t n, int mode, const int64_t *indptr, double *out) {
+  hipLaunchKernelGGL(k_margins, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, c->xn32, c->wmax_bits,
+                     c->mu_norm2, margin_model(c, mode, indptr), n, out);
   return hipGetLastError();
 }
 

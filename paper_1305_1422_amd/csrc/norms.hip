@@ -231,7 +231,8 @@ __global__ __launch_bounds__(64) void k_finish_col_means(const double *__restric
       }
       const double amax = fmax((double)hi - (double)m, (double)m - (double)lo);
       step = amax > 0.0 && amax < 1e300 ? (float)(amax * (1.0 + 1e-6) / 32767.0) : 0.f;
-      if (!(step > 0.f)) step = 1.f;             // constant column (or no rows): every quotient is 0
+      if (!(step > 0.f)) step = 1e-30f;          // constant column (or no rows): every quotient is 0, and the
+                                                 // column must not weigh on the quantisation term of the margin
       qstep[c] = step;
     }
   }

@@ -250,7 +250,7 @@ static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *
   {
     StageTimer t(c, 0);
     if (split) SOM_LAUNCH(c, launch_bmu_dense_h(c, n, nullptr));
-    else SOM_LAUNCH(c, launch_bmu_dense(c, X, n));
+    else SOM_LAUNCH(c, launch_bmu_dense(c, X, n, nullptr));
   }
   StageTimer t(c, 2);
   SOM_LAUNCH(c, launch_certify(c, n, split ? bmu_dense_h_groups(c, n) : bmu_dense_groups(c, n),
@@ -263,8 +263,11 @@ static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *
   return SOM_OK;
 }
 
-static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
-                          int64_t n, int64_t nnz, const float *W, int32_t *bmus, bool have_xn) {
+// Everything the sparse sweep needs: scratch, norms of the instances (unless registered), the centring
+// vector (mean of the code-book rows) with the quantisation steps, node constants, the transposed 16-bit
+// code book and the scaled values.
+static int prepare_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values, int64_t n,
+                       int64_t nnz, const float *W, bool have_xn) {
   if (nnz > c->vq_cap) {
     (void)hipStreamSynchronize(c->stream);
     dev_free(c->vq);
@@ -287,6 +290,13 @@ static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indi
   SOM_LAUNCH(c, launch_center_codebook(c, W, false, true));
   if (c->nb_function == SOM_NEIGHBORHOOD_BUBBLE) SOM_LAUNCH(c, launch_mask_duplicate_rows(c, W));
   SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, kListCounts));
+  return SOM_OK;
+}
+
+static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
+                          int64_t n, int64_t nnz, const float *W, int32_t *bmus, bool have_xn) {
+  int rc = prepare_csr(c, indptr, indices, values, n, nnz, W, have_xn);
+  if (rc) return rc;
   {
     StageTimer t(c, 1);
     SOM_LAUNCH(c, launch_transpose_codebook(c, W));
@@ -728,16 +738,34 @@ int som_set_filter(som_ctx *c, int filter) {
 }
 
 int som_debug_scores_dense(som_ctx *c, const float *data, int64_t n, const float *codebook, float *scores,
-                           float *mu_out) {
+                           float *mu_out, double *margin_out) {
   if (!c) return SOM_ERR_INVALID_ARG;
-  if (!data || !codebook || !scores || !mu_out) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
-  if (c->filter != SOM_FILTER_SPLIT_F16) return fail(c, SOM_ERR_STATE, "only the split-fp16 filter can dump its scores");
+  if (!data || !codebook || !scores || !mu_out || !margin_out) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
   int rc = check_rows(c, n);
   if (!rc) rc = ensure_rows(c, n, true);
   if (!rc) rc = ensure_candidates(c, n, true);
   if (!rc) rc = prepare_dense(c, data, n, codebook, false);
   if (rc) return rc;
-  SOM_LAUNCH(c, launch_bmu_dense_h(c, n, scores));
+  const bool split = c->filter == SOM_FILTER_SPLIT_F16;
+  if (split) SOM_LAUNCH(c, launch_bmu_dense_h(c, n, scores));
+  else SOM_LAUNCH(c, launch_bmu_dense(c, data, n, scores));
+  SOM_LAUNCH(c, launch_margins(c, n, split ? kCertifySplit : kCertifyFp32, nullptr, margin_out));
+  SOM_LAUNCH(c, hipMemcpyAsync(mu_out, c->mu, (size_t)c->dim * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
+  return SOM_OK;
+}
+
+int som_debug_scores_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values, int64_t n,
+                         int64_t nnz, const float *codebook, float *scores, float *mu_out, double *margin_out) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (!codebook || !scores || !mu_out || !margin_out) return fail(c, SOM_ERR_INVALID_ARG, "NULL pointer argument");
+  int rc = check_csr(c, indptr, indices, values, n, nnz);
+  if (!rc) rc = ensure_rows(c, n, false);
+  if (!rc) rc = prepare_csr(c, indptr, indices, values, n, nnz, codebook, false);
+  if (rc) return rc;
+  SOM_LAUNCH(c, launch_transpose_codebook(c, codebook));
+  SOM_LAUNCH(c, launch_scale_values(c, indices, values, nnz));
+  SOM_LAUNCH(c, launch_bmu_csr_sliced(c, indptr, indices, c->vq, n, false, scores));
+  SOM_LAUNCH(c, launch_margins(c, n, kCertifyCsr, indptr, margin_out));
   SOM_LAUNCH(c, hipMemcpyAsync(mu_out, c->mu, (size_t)c->dim * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
   return SOM_OK;
 }

@@ -155,9 +155,9 @@ hipError_t launch_csr_row_sqnorms(som_ctx *c, const int64_t *indptr, const float
 
 // bmu_dense.hip
 int bmu_dense_groups(const som_ctx *c, int64_t n);
-hipError_t launch_bmu_dense(som_ctx *c, const float *X, int64_t n);
+hipError_t launch_bmu_dense(som_ctx *c, const float *X, int64_t n, float *dump);   // dump: test hook, all scores [n][k], or null
 hipError_t launch_bmu_dense_collect(som_ctx *c, const float *X, int64_t n);
-hipError_t launch_bmu_dense_dl(som_ctx *c, const float *X, int64_t n, dim3 grid, bool collect);   // bmu_dense_dl.hip
+hipError_t launch_bmu_dense_dl(som_ctx *c, const float *X, int64_t n, dim3 grid, bool collect, float *dump);   // bmu_dense_dl.hip
 
 // bmu_dense_h.hip, split_f16.hip
 // Chunks of 32 features a wavefront of the split-fp16 pass multiplies into its MFMA accumulators
@@ -185,6 +185,7 @@ constexpr int kListCounts = 12;    // words in som_ctx::list_counts
 constexpr int kUnitCounts = 4;     // first of the eight work-list lengths in it
 enum { kCertifyFp32 = 0, kCertifySplit = 1, kCertifyCsr = 2 };      // whose rounding bound the margin uses
 hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int64_t *indptr, int32_t *bmus);
+hipError_t launch_margins(som_ctx *c, int64_t n, int mode, const int64_t *indptr, double *out);   // test hook: the margin per instance
 hipError_t launch_refine_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
 hipError_t launch_refine_lists_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
 hipError_t launch_rescan_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
@@ -216,7 +217,7 @@ enum { kCsrBadSorted = 1, kCsrBadIndex = 2, kCsrBadOrder = 3, kCsrBadLast = 4, k
 hipError_t launch_validate_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, int64_t n, int64_t nnz,
                                int32_t *flag);
 hipError_t launch_bmu_csr_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
-                                 int64_t n, bool collect);
+                                 int64_t n, bool collect, float *dump = nullptr);   // dump: test hook, all scores [n][k]
 
 // segsum.hip
 hipError_t launch_sort_by_bmu(som_ctx *c, const int32_t *bmus, int64_t n);   // -> sort_val[0] = row ids

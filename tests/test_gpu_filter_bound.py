@@ -1,4 +1,10 @@
-"""The rounding bound that the exact BMU stage relies on, checked where it is assumed.
+"""The rounding bounds that the exact BMU stage relies on, checked where they are assumed: every score of
+each of the three filters (split-fp16 MFMA, fp32 MFMA in both of its kernels, the 16-bit sparse sweep) is
+dumped and compared with its exact value in float64; no error may exceed half the margin the exact stage
+applies to that instance (the library reports the margin it uses: same device function, same inputs), and for
+the two dense filters the documented closed form of the bound is evaluated here from the inputs alone as well.
+
+Split-fp16 filter:
 
 The split-fp16 filter ranks nodes by scores whose distance from the exact value is bounded by
     B = u [ coef X Wm + sqrt(dim) (sx_j Wm + sw X) + 4 Wm^2 + 6 M Wm ],      u = 2^-24,
@@ -88,18 +94,20 @@ def _pow2_above(m):
     return 2.0 ** e
 
 
-def _score_bound_case(x, w, rows, cols):
+def _score_bound_case(x, w, rows, cols, filter="split_f16"):
     from paper_1305_1422_amd import Som, capi
     n, dim = x.shape
     k = rows * cols
-    som = Som(rows, cols, dim, codebook=torch.from_numpy(w), filter="split_f16")
+    som = Som(rows, cols, dim, codebook=torch.from_numpy(w), filter=filter)
     xd = torch.from_numpy(x).cuda()
     scores = torch.empty((n, k), dtype=torch.float32, device="cuda")
     mu = torch.empty(dim, dtype=torch.float32, device="cuda")
-    capi.som_debug_scores_dense(som.ctx, xd, som.codebook, scores, mu)
+    margin = torch.empty(n, dtype=torch.float64, device="cuda")
+    capi.som_debug_scores_dense(som.ctx, xd, som.codebook, scores, mu, margin)
     torch.cuda.synchronize()
     s_gpu = scores.cpu().numpy().astype(np.float64)
     mu32 = mu.cpu().numpy()
+    margin = margin.cpu().numpy()
     som.close()
 
     wc = (w - mu32[None, :]).astype(np.float32)                   # w' = fl(w - mu), one fp32 rounding
@@ -110,23 +118,28 @@ def _score_bound_case(x, w, rows, cols):
     X = np.sqrt((x64 ** 2).sum(1))
     Wm = np.sqrt((wc64 ** 2).sum(1).max())
     M = np.sqrt((mu64 ** 2).sum())
-    sx = _pow2_above(np.abs(x64).max(1))
-    sw = float(_pow2_above(np.abs(wc64).max()))
-    f = 4 if dim >= 256 else 2                                     # chunks of 32 features between two flushes
-    g = 2.5 * 6 * f + 9 + np.ceil(dim / (32 * f)) + 2
     # the rounding of w - mu is part of the library's bound but not of this comparison (the exact
     # scores above start from the rounded w'), so the bound tested here is slightly larger than needed
-    B = U * ((2 * g + 28) * X * Wm + np.sqrt(dim) * (sx * Wm + sw * X) + 4 * Wm ** 2 + 6 * M * Wm)
+    if filter == "split_f16":
+        sx = _pow2_above(np.abs(x64).max(1))
+        sw = float(_pow2_above(np.abs(wc64).max()))
+        f = 4 if dim >= 256 else 2                                 # chunks of 32 features between two flushes
+        g = 2.5 * 6 * f + 9 + np.ceil(dim / (32 * f)) + 2
+        B = U * ((2 * g + 28) * X * Wm + np.sqrt(dim) * (sx * Wm + sw * X) + 4 * Wm ** 2 + 6 * M * Wm)
+    else:
+        g = 32 + np.ceil(dim / 32) + 2                             # accumulator flushed every 32 features
+        B = U * ((2 * g + 4) * X * Wm + 4 * Wm ** 2 + 6 * M * Wm)
     err = np.abs(s_gpu - s_exact)
     ratio = (err / B[:, None]).max()
     assert ratio <= 1.0, f"filter score error exceeds the bound: {ratio:.3f} x"
+    # what the exact stage really uses: two scores of an instance are told apart by `margin`, so each may
+    # be off by half of it; and the margin is the documented 2.125 B (never less)
+    assert np.all(err <= 0.5 * margin[:, None]), f"score error above half the margin: {(err / margin[:, None]).max():.3f}"
+    assert np.all(margin >= 2.125 * B * (1 - 1e-6))
     return ratio
 
 
-@pytest.mark.parametrize("case", ["uniform", "offset_mixture", "heavy_tail", "tiny_and_huge_rows", "ragged_dim"])
-def test_filter_scores_stay_within_the_bound(case):
-    rng = np.random.default_rng(11)
-    rows, cols = 12, 25                                            # 300 nodes: three node blocks, ragged
+def _dense_case(case, rng, rows, cols):
     n, dim = 700, 200
     if case == "uniform":
         x = rng.uniform(0, 1, (n, dim))
@@ -141,10 +154,104 @@ def test_filter_scores_stay_within_the_bound(case):
     elif case == "tiny_and_huge_rows":
         x = rng.standard_normal((n, dim)) * (10.0 ** rng.integers(-12, 6, size=(n, 1)))
         w = rng.standard_normal((rows * cols, dim)) * (10.0 ** rng.integers(-3, 2, size=(rows * cols, 1)))
-    else:
+    elif case == "ragged_dim":
         dim = 1000                                                 # not a multiple of 32 chunks of 64: 16 flushes
         n = 300
         x = rng.uniform(-1, 1, (n, dim))
         w = rng.uniform(-1, 1, (rows * cols, dim))
-    ratio = _score_bound_case(x.astype(np.float32), w.astype(np.float32), rows, cols)
-    print(f"{case}: worst error / bound = {ratio:.4f}")
+    else:                                                          # "odd_dim": the register-staged fp32 kernel
+        dim = 333
+        n = 300
+        x = rng.uniform(-1, 1, (n, dim)) + 3.0
+        w = rng.uniform(-1, 1, (rows * cols, dim)) + 3.0
+    return x.astype(np.float32), w.astype(np.float32)
+
+
+@pytest.mark.parametrize("filter", ["split_f16", "fp32"])
+@pytest.mark.parametrize("case", ["uniform", "offset_mixture", "heavy_tail", "tiny_and_huge_rows", "ragged_dim",
+                                  "odd_dim"])
+def test_filter_scores_stay_within_the_bound(case, filter):
+    rng = np.random.default_rng(11)
+    rows, cols = 12, 25                                            # 300 nodes: three node blocks, ragged
+    x, w = _dense_case(case, rng, rows, cols)
+    ratio = _score_bound_case(x, w, rows, cols, filter)
+    print(f"{filter} {case}: worst error / bound = {ratio:.4f}")
+
+
+# ---------------------------------------------------------------- sparse sweep
+def _csr_rows(rng, n, dim, lengths, value_kind):
+    indptr = np.zeros(n + 1, np.int64)
+    np.cumsum(lengths, out=indptr[1:])
+    indices = np.concatenate([np.sort(rng.choice(dim, size=int(l), replace=False)) for l in lengths] or
+                             [np.zeros(0)]).astype(np.int32)
+    nnz = int(indptr[-1])
+    if value_kind == "tf":
+        values = np.log(2.0 + rng.poisson(2.0, nnz))
+    elif value_kind == "signed_wide":
+        values = rng.standard_normal(nnz) * 10.0 ** rng.integers(-4, 4, nnz)
+    else:
+        values = rng.uniform(0.5, 1.5, nnz)
+    return indptr, indices, values.astype(np.float32)
+
+
+@pytest.mark.parametrize("case", ["text_like", "heavy_tailed_columns", "one_huge_column", "constant_columns",
+                                  "short_and_long_rows", "signed_wide_values"])
+def test_sparse_sweep_scores_stay_within_the_margin(case):
+    """Scores of the sparse sweep (code book quantised to 16 bits per column step, values times step, one FMA
+    chain per row) against float64: the margin carries 0.51 sum |v_c| step_c for the quantisation plus the fp32
+    chain; the error of every score must stay below half of it."""
+    from paper_1305_1422_amd import Som, capi
+    rng = np.random.default_rng(23)
+    rows, cols, dim, n = 20, 35, 3000, 260                         # 700 nodes: eight slices, the last ragged
+    k = rows * cols
+    w = rng.uniform(0, 1, (k, dim))
+    lengths = np.clip(rng.poisson(60, n), 1, 400)
+    kind = "tf"
+    if case == "heavy_tailed_columns":
+        w = w * 10.0 ** rng.uniform(-3, 3, (1, dim))               # column scales over six decades
+        w[rng.integers(k, size=40), rng.integers(dim, size=40)] *= 50.0      # and single outliers that set a step
+    elif case == "one_huge_column":
+        w[:, 7] = rng.standard_normal(k) * 1e6
+        lengths[:] = 30
+    elif case == "constant_columns":
+        w[:, ::3] = 0.25                                           # centred to exactly 0: step falls back to 1
+        w[:, 1::3] = rng.uniform(0, 1, (1, len(range(1, dim, 3)))) # constant per column, different values
+    elif case == "short_and_long_rows":
+        lengths = np.where(np.arange(n) % 3 == 0, 1, np.where(np.arange(n) % 3 == 1, 400, 0))
+    elif case == "signed_wide_values":
+        kind = "signed_wide"
+        w = w - 0.5
+    w = w.astype(np.float32)
+    csr = _csr_rows(rng, n, dim, lengths, kind)
+    if case == "one_huge_column":                                  # every row lists the huge column
+        for j in range(n):
+            row = csr[1][csr[0][j]:csr[0][j + 1]]
+            if 7 not in row:
+                row[0] = 7 if row[0] > 7 or row.size == 1 else row[0]
+        # keep rows sorted and unique after the edit
+        for j in range(n):
+            seg = slice(csr[0][j], csr[0][j + 1])
+            assert np.all(np.diff(csr[1][seg]) > 0)
+    som = Som(rows, cols, dim, codebook=torch.from_numpy(w))
+    dev = tuple(torch.from_numpy(a).cuda() for a in csr)
+    scores = torch.empty((n, k), dtype=torch.float32, device="cuda")
+    mu = torch.empty(dim, dtype=torch.float32, device="cuda")
+    margin = torch.empty(n, dtype=torch.float64, device="cuda")
+    capi.som_debug_scores_csr(som.ctx, dev[0], dev[1], dev[2], som.codebook, scores, mu, margin)
+    torch.cuda.synchronize()
+    s_gpu = scores.cpu().numpy().astype(np.float64)
+    mu32 = mu.cpu().numpy()
+    margin = margin.cpu().numpy()
+    som.close()
+    wc64 = (w - mu32[None, :]).astype(np.float32).astype(np.float64)
+    c_i = (wc64 ** 2).sum(1) + 2.0 * wc64 @ mu32.astype(np.float64)
+    worst = 0.0
+    for j in range(n):
+        seg = slice(csr[0][j], csr[0][j + 1])
+        dot = wc64[:, csr[1][seg]] @ csr[2][seg].astype(np.float64)
+        err = np.abs(s_gpu[j] - (c_i - 2.0 * dot))
+        assert np.all(err <= 0.5 * margin[j]), (f"row {j} (length {seg.stop - seg.start}): score error "
+                                                f"{err.max():.3e} above half the margin {margin[j]:.3e}")
+        worst = max(worst, float(err.max() / (margin[j] / 2.125)))
+    print(f"{case}: worst error / bound = {worst:.4f}")
+    assert worst > 1e-4                                            # the comparison is not vacuous
