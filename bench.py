@@ -26,12 +26,16 @@ METRIC = "epoch throughput (instance*node*dim/s)"
 PEAK_FP32_MFMA_TFLOPS = 157.3
 PEAK_FP16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
-# HBM-side bytes per launch of the dominant kernel (fetched + written), from the two rocprofv3 --pmc
-# runs (FETCH_SIZE, WRITE_SIZE, scaled by the copy calibration) summarised under profiles/;
-# measured once per kernel version, not during this run (the dense figure varies between 3.4 and 4.0 GB from
-# run to run: it depends on how long the workgroups that share an instance tile stay in step).  Workloads without a counter run: None.
-MEASURED_TRAFFIC_BYTES = {(2, "split_f16"): 4.023e9 + 0.036e9, (2, "fp32"): 8.49e9 + 0.025e9,
-                          (4, "split_f16"): 13.836e9 + 0.090e9, (4, "fp32"): 13.836e9 + 0.090e9}
+# HBM-side bytes per launch of the dominant kernel (fetched + written), from the rocprofv3 --pmc passes
+# (FETCH_SIZE, WRITE_SIZE, scaled by the copy calibration) summarised in profiles/epoch_config*.md;
+# measured once per kernel version, not during this run (the dense figures vary by some ten percent from
+# run to run: they depend on how long the workgroups that share an instance tile stay in step).
+MEASURED_TRAFFIC_BYTES = {(2, "split_f16"): 3.978e9 + 0.036e9, (2, "fp32"): 8.49e9 + 0.025e9,
+                          (3, "split_f16"): 14.445e9 + 0.025e9, (5, "split_f16"): 15.021e9 + 0.072e9,
+                          (4, "split_f16"): 13.842e9 + 0.091e9, (4, "fp32"): 13.842e9 + 0.091e9,
+                          (6, "split_f16"): 0.340e9 + 0.030e9, (6, "fp32"): 0.340e9 + 0.030e9,
+                          (7, "split_f16"): 87.195e9 + 0.095e9, (7, "fp32"): 87.195e9 + 0.095e9}
+PEAK_FP32_VALU_TFLOPS = 157.3
 
 
 def cpu_baseline(w, X, W0, seconds_budget: float = 20.0):
@@ -67,6 +71,8 @@ def main() -> int:
                     help="arithmetic of the dense BMU filter pass (same BMUs either way)")
     ap.add_argument("--neighborhood", choices=["gaussian", "gaussian-compact", "bubble"], default="gaussian",
                     help="neighbourhood of the update (the stated configurations use the plain Gaussian)")
+    ap.add_argument("--smoothing", choices=["auto", "vector", "matrix"], default="auto",
+                    help="units that run the Gaussian smoothing passes (same results)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run ten plain 1 GiB device copies and exit: under rocprofv3 --pmc this gives the "
                          "reading of FETCH_SIZE / WRITE_SIZE for a kernel of known traffic")
@@ -107,6 +113,7 @@ def main() -> int:
     som = Som(w.rows, w.cols, w.dim, w.map_type, w.grid_type, codebook=W0d, filter=args.filter)
     if args.neighborhood != "gaussian":
         som.set_neighborhood("bubble" if args.neighborhood == "bubble" else "gaussian", args.neighborhood != "bubble")
+    som.set_smoothing(args.smoothing)
     bmus = torch.empty(w.n, dtype=torch.int32, device=dev)
     # register the resident training set: its norms are then computed once, not every epoch
     if w.kind == "dense":
@@ -177,11 +184,20 @@ def main() -> int:
         # compulsory bytes: CSR once (8 B per nonzero + 8 B per row), code book once, BMUs out
         alg_bytes = nnz * 8.0 + (w.n + 1) * 8.0 + w.k * w.dim * 4.0 + w.n * 4.0
         achieved = alg_bytes / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
+        traffic = MEASURED_TRAFFIC_BYTES.get((w.config, args.filter))
+        valu_bound_ms = 2.0 * nnz * w.k / (PEAK_FP32_VALU_TFLOPS * 1e12) * 1e3
         roofline = {"bound": "hbm", "kernel": "k_transpose_centered_q16 + k_bmu_csr_sliced (sparse BMU filter pass)",
                     "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((w.config, args.filter)), "avg_launch_ms": dom_ms,
-                    "traffic_rate_gbs": (MEASURED_TRAFFIC_BYTES[(w.config, args.filter)] / (dom_ms * 1e-3) / 1e9
-                                         if (w.config, args.filter) in MEASURED_TRAFFIC_BYTES and dom_ms > 0 else None)}
+                    "traffic": traffic, "avg_launch_ms": dom_ms,
+                    # the three views of this kernel: (i) against the plain fp32 vector ALUs, on which 2 nnz k
+                    # flop cannot take less than valu_bound_ms; (ii) `frac` above: compulsory bytes (CSR once,
+                    # code book once, BMUs) against the HBM peak; (iii) the traffic the gathers really send past
+                    # L2 (counter reading of the sweep kernel) against the HBM peak
+                    "valu_bound_ms": valu_bound_ms, "frac_of_valu_bound": valu_bound_ms / dom_ms if dom_ms > 0 else None,
+                    "compulsory_bytes": alg_bytes,
+                    "traffic_rate_gbs": traffic / (dom_ms * 1e-3) / 1e9 if traffic and dom_ms > 0 else None,
+                    "traffic_frac_of_hbm_peak": (traffic / (dom_ms * 1e-3) / 1e9 / PEAK_HBM_GBS
+                                                 if traffic and dom_ms > 0 else None)}
 
     out = {
         "metric": METRIC, "value": value, "unit": "instance*node*dim/s", "n_gpus": 1, "steps": args.steps,
@@ -197,7 +213,7 @@ def main() -> int:
                             "depends on the code book included; outside the step, once per registered data set: "
                             + ("squared norms of the instances, their fp16 hi/lo planes, sampled column means"
                                if w.kind == "dense" else "squared norms of the instances")),
-                   "neighborhood": args.neighborhood},
+                   "neighborhood": args.neighborhood, "smoothing": args.smoothing},
         "gflops_epoch": 2.0 * work / (dt / args.steps) / 1e9,
         "frac_fp32_mfma_peak_whole_epoch": 2.0 * work / (dt / args.steps) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
         "stage_ms": stage_ms,

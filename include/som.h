@@ -44,6 +44,7 @@ enum { SOM_GRID_SQUARE = 0, SOM_GRID_HEXAGONAL = 1 };     /* option -g: square (
 enum { SOM_COOL_AS_RADIUS = -1, SOM_COOL_LINEAR = 0, SOM_COOL_EXPONENTIAL = 1 };   /* options -t / -T */
 enum { SOM_FILTER_FP32 = 0, SOM_FILTER_SPLIT_F16 = 1 };   /* see som_set_filter                       */
 enum { SOM_NEIGHBORHOOD_GAUSSIAN = 0, SOM_NEIGHBORHOOD_BUBBLE = 1 };   /* option -n               */
+enum { SOM_SMOOTH_AUTO = 0, SOM_SMOOTH_VECTOR = 1, SOM_SMOOTH_MATRIX = 2 };   /* see som_set_smoothing   */
 
 /* Neighbourhood mass below which a node keeps its weights (see som_train_epoch_dense). */
 #define SOM_EPS_MASS 1e-20
@@ -281,6 +282,17 @@ int som_umatrix(som_ctx *ctx, const float *codebook, float *umatrix);
  * SOM_ERR_ALLOC.
  */
 int som_set_neighborhood(som_ctx *ctx, int function, int compact_support);
+
+/*
+ * som_set_smoothing - which units run the two passes of the Gaussian neighbourhood smoothing (batch
+ * equation; neighbourhood equation).  The result is the same up to the order of the fp32 additions.
+ *   SOM_SMOOTH_AUTO (default)  a pass over map lines of at least 128 nodes runs as a matrix product on
+ *                  the fp32 matrix cores, a shorter one on the vector units;
+ *   SOM_SMOOTH_VECTOR  always the vector units;  SOM_SMOOTH_MATRIX  the matrix cores for any line length
+ *                  (maps with a side above 1,024 nodes always use the vector units).
+ * Errors: unknown value -> SOM_ERR_INVALID_ARG.
+ */
+int som_set_smoothing(som_ctx *ctx, int form);
 
 /*
  * som_set_filter - choose the arithmetic of the dense BMU filter pass (paper, "Parallelism":

@@ -20,6 +20,7 @@ SOM_GRID_SQUARE, SOM_GRID_HEXAGONAL = 0, 1
 SOM_COOL_AS_RADIUS, SOM_COOL_LINEAR, SOM_COOL_EXPONENTIAL = -1, 0, 1
 SOM_FILTER_FP32, SOM_FILTER_SPLIT_F16 = 0, 1
 SOM_NEIGHBORHOOD_GAUSSIAN, SOM_NEIGHBORHOOD_BUBBLE = 0, 1
+SOM_SMOOTH_AUTO, SOM_SMOOTH_VECTOR, SOM_SMOOTH_MATRIX = 0, 1, 2
 
 EXPORTS = [
     "som_init", "som_destroy", "som_last_error",
@@ -30,7 +31,7 @@ EXPORTS = [
     "som_bmu_distances_dense", "som_bmu_distances_csr", "som_bmu_distances_dense_static",
     "som_cool_schedule", "som_umatrix", "som_get_stats",
     "som_profile_enable", "som_profile_read",
-    "som_set_filter", "som_set_neighborhood", "som_set_scale_cooling", "som_validate_csr", "som_debug_scores_dense", "som_debug_scores_csr", "som_debug_mfma_f16",
+    "som_set_filter", "som_set_smoothing", "som_set_neighborhood", "som_set_scale_cooling", "som_validate_csr", "som_debug_scores_dense", "som_debug_scores_csr", "som_debug_mfma_f16",
 ]
 PROFILE_STAGES = ("bmu_dense_filter", "bmu_csr_filter", "bmu_exact", "node_sums", "smooth_divide", "prepare_dense")
 
@@ -99,6 +100,8 @@ def load():
     L.som_set_scale_cooling.argtypes = [vp, i32]
     L.som_validate_csr.restype = i32
     L.som_validate_csr.argtypes = [vp, vp, vp, vp, i64, i64]
+    L.som_set_smoothing.restype = i32
+    L.som_set_smoothing.argtypes = [vp, i32]
     L.som_set_filter.restype = i32
     L.som_set_filter.argtypes = [vp, i32]
     L.som_set_neighborhood.restype = i32
@@ -317,6 +320,10 @@ def som_validate_csr(ctx, indptr, indices, values) -> None:
                                         _ptr(indices, torch.int32, "indices", True),
                                         _ptr(values, torch.float32, "values", True), indptr.shape[0] - 1,
                                         0 if indices is None else indices.shape[0]))
+
+
+def som_set_smoothing(ctx, form: int) -> None:
+    _check(ctx, load().som_set_smoothing(ctx, form))
 
 
 def som_set_filter(ctx, filter: int) -> None:

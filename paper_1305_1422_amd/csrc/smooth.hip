@@ -21,7 +21,6 @@
 #include "som_internal.hpp"
 
 #include <math.h>
-#include <stdlib.h>
 
 namespace som {
 

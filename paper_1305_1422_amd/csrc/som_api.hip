@@ -383,8 +383,7 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
   csr_slice_geometry(c->k, &c->csr_acc, &c->csr_sweeps, &c->kpad);
   c->filter = SOM_FILTER_SPLIT_F16;
   c->scale_cooling = -1;
-  c->smooth_mfma_min = 128;
-  if (const char *v = getenv("SOM_SMOOTH_MFMA_MIN")) c->smooth_mfma_min = atoi(v);      // timing experiments only
+  c->smooth_mfma_min = kSmoothMfmaMin;
 
   int dev = 0;
   hipDeviceProp_t prop;
@@ -727,6 +726,14 @@ int som_validate_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, 
     case kCsrBadIndex: return fail(c, SOM_ERR_INVALID_ARG, "CSR: a column index is outside [0, dim)");
     default: return fail(c, SOM_ERR_INVALID_ARG, "CSR: column indices of a row are not strictly increasing");
   }
+}
+
+int som_set_smoothing(som_ctx *c, int form) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (form != SOM_SMOOTH_AUTO && form != SOM_SMOOTH_VECTOR && form != SOM_SMOOTH_MATRIX)
+    return fail(c, SOM_ERR_INVALID_ARG, "unknown smoothing form %d", form);
+  c->smooth_mfma_min = form == SOM_SMOOTH_AUTO ? kSmoothMfmaMin : (form == SOM_SMOOTH_VECTOR ? 0 : 1);
+  return SOM_OK;
 }
 
 int som_set_filter(som_ctx *c, int filter) {

@@ -67,6 +67,11 @@ class Som:
         """Debug pass: raises capi.SomError if the CSR triple (indptr, indices, values) is malformed."""
         capi.som_validate_csr(self.ctx, csr[0], csr[1], csr[2])
 
+    def set_smoothing(self, form: str) -> None:
+        """Units that run the Gaussian smoothing passes: "auto" (default), "vector" or "matrix"; same results."""
+        capi.som_set_smoothing(self.ctx, {"auto": capi.SOM_SMOOTH_AUTO, "vector": capi.SOM_SMOOTH_VECTOR,
+                                          "matrix": capi.SOM_SMOOTH_MATRIX}[form])
+
     def set_filter(self, filter: str) -> None:
         """Arithmetic of the dense BMU filter pass: "split_f16" (default) or "fp32"; same results."""
         capi.som_set_filter(self.ctx, FILTERS[filter])

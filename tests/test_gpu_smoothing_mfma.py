@@ -43,25 +43,23 @@ def test_update_matches_oracle(oracle, map_type, grid, rows, cols, dim, n, radiu
     som.close()
 
 
-def test_both_forms_agree_on_a_whole_map(oracle):
-    """The vector and the matrix-core form of the passes differ only in the order of their fp32 sums."""
-    import os
+@pytest.mark.parametrize("rows,cols", [(140, 150), (30, 50)])
+def test_both_forms_agree_on_a_whole_map(oracle, rows, cols):
+    """The vector and the matrix-core form of the passes differ only in the order of their fp32 sums; the
+    small map takes the matrix cores only when they are asked for."""
     from paper_1305_1422_amd import Som
-    rows, cols, dim, n = 140, 150, 64, 5000
+    dim, n = 64, 5000
     rng = np.random.default_rng(77)
     X = rng.standard_normal((n, dim)).astype(np.float32)
     W = rng.random((rows * cols, dim)).astype(np.float32)
     bmus = rng.integers(0, rows * cols, size=n).astype(np.int32)
     out = []
-    for setting in ("0", None):
-        if setting is None:
-            os.environ.pop("SOM_SMOOTH_MFMA_MIN", None)
-        else:
-            os.environ["SOM_SMOOTH_MFMA_MIN"] = setting
+    for form in ("vector", "matrix", "auto"):
         som = Som(rows, cols, dim, "toroid", "hexagonal", codebook=torch.from_numpy(W))
+        som.set_smoothing(form)
         som.update(P.to_dev(X), P.to_dev(bmus), 12.0)
         torch.cuda.synchronize()
         out.append(som.codebook.cpu().numpy())
         som.close()
-    os.environ.pop("SOM_SMOOTH_MFMA_MIN", None)
     np.testing.assert_allclose(out[0], out[1], rtol=2e-5, atol=1e-6)
+    assert np.array_equal(out[2], out[1] if rows >= 128 else out[0])
