@@ -286,7 +286,7 @@ int som_set_neighborhood(som_ctx *ctx, int function, int compact_support);
 /*
  * som_set_smoothing - which units run the two passes of the Gaussian neighbourhood smoothing (batch
  * equation; neighbourhood equation).  The result is the same up to the order of the fp32 additions.
- *   SOM_SMOOTH_AUTO (default)  a pass over map lines of at least 128 nodes runs as a matrix product on
+ *   SOM_SMOOTH_AUTO (default)  a pass over map lines of at least 32 nodes runs as a matrix product on
  *                  the fp32 matrix cores, a shorter one on the vector units;
  *   SOM_SMOOTH_VECTOR  always the vector units;  SOM_SMOOTH_MATRIX  the matrix cores for any line length
  *                  (maps with a side above 1,024 nodes always use the vector units).

@@ -17,7 +17,7 @@ constexpr int kListCap = 256;             // nodes a collected candidate list ca
 constexpr int kChunkRows = 32;            // instances summed by one block of the segmented accumulation
 constexpr int kSortTile = 1024;           // fewest keys ranked by one wave of the radix scatter
 constexpr int kSmoothMatMax = 1024;        // largest map side for which the smoothing filters are stored as matrices
-constexpr int kSmoothMfmaMin = 128;        // shortest map line whose smoothing pass runs on the matrix cores by default
+constexpr int kSmoothMfmaMin = 32;         // shortest map line whose smoothing pass runs on the matrix cores by default
 constexpr int kProfMax = 512;              // event brackets kept per stage between two reads
 #ifndef SOM_FLUSH_BLOCK
 #define SOM_FLUSH_BLOCK 32
