@@ -1,7 +1,9 @@
 // Dense best-matching-unit search, filter pass on the fp16 matrix cores with split operands
 // (paper: BMU equation; "Parallelism": distances through linear algebra).
 //
-// Same scores as the fp32 pass (bmu_dense_dl.hip): s = c_i - 2 x.w'_i with w' = fl(w - mu), but the
+// Same ranking as the fp32 pass (bmu_dense_dl.hip), from scores s = |w'_i|^2 - 2 x'.w'_i with w' = fl(w - mu)
+// and x' = fl(x - mu) (the planes of the instances are the library's own, so they hold centred rows;
+// the score differs from the fp32 pass's c_i - 2 x.w'_i by the rounding of x - mu only).  The
 // dot product is evaluated as three fp16 MFMAs on the hi/lo planes written by split_f16.hip:
 //     x.w' = sx sw (hi_x.hi_w + hi_x.lo_w + lo_x.hi_w) (1 + O(2^-22)),
 // accumulated in fp32 by v_mfma_f32_32x32x16_f16.  On gfx950 that instruction issues in 8 passes
@@ -9,13 +11,12 @@
 // the fp32 rate.  The exact stage (bmu_exact.hip) decides as before; only its margin differs.
 //
 // Each wavefront owns 64 nodes x 64 instances (2 x 2 MFMA blocks) and sweeps the workgroup's group
-// of node blocks of 128.  Two workgroup shapes are compiled (template parameter WI).  The one in
-// use has 4 wavefronts, 128 instances and two LDS stages of (128 + 128) rows x 128 bytes (64 KB),
-// two workgroups per CU: at this MFMA rate a chunk is multiplied in about half a microsecond, so
-// the gap every barrier leaves in the matrix pipe matters, and a second workgroup with barriers of
-// its own fills it.  The other (8 wavefronts, 256 instances, three stages = 144 KB, one workgroup
-// per CU, first operands of the next chunk read before the barrier) moves a quarter less data
-// through L2 but measured 3-12 % slower on the three dense configurations.  The 128
+// of node blocks of 128.  A workgroup has 4 wavefronts, 128 instances and two LDS stages of
+// (128 + 128) rows x 128 bytes (64 KB), two workgroups per CU: at this MFMA rate a chunk is
+// multiplied in about half a microsecond, so the gap every barrier leaves in the matrix pipe
+// matters, and a second workgroup with barriers of its own fills it.  (A shape with 8 wavefronts,
+// 256 instances and three stages, one workgroup per CU, moves a quarter less data through L2 but
+// measured 3-12 % slower on the three dense configurations and is no longer compiled.)  The 128
 // bytes of a tile row are one chunk of the split layout: 32 hi halves, 32 lo halves.  Tiles are
 // loaded straight into LDS with the XOR swizzle of the fp32 pass (the two passes share the row
 // geometry, so the same swizzle makes the ds_read_b128 operand reads conflict-free): 16-byte
@@ -35,7 +36,7 @@ typedef __attribute__((address_space(3))) void *lptr_h_t;
 
 constexpr int kHRow = 32;                  // floats per tile row (= 64 halves = one chunk of 32 columns)
 constexpr int kHWTile = kTN * kHRow;       // floats
-constexpr int kHWI = 2;                    // tile shape in use (see the template parameter WI): measured faster
+constexpr int kHWI = 2;                    // 64-instance columns of wavefronts in a workgroup
 
 __device__ __forceinline__ unsigned lds_address_h(const float *p) { return (unsigned)(size_t)(lptr_h_t)p; }
 
@@ -68,14 +69,11 @@ enum { kHFilter = 0, kHCollect = 1, kHDump = 2 };
 
 __device__ __forceinline__ f16x8 as_halves(f32x4 v) { return __builtin_bit_cast(f16x8, v); }
 
-// WI: 64-instance columns of wavefronts in a workgroup.  WI = 4: 8 wavefronts, 256 instances, three
-// LDS stages (144 KB), one workgroup per CU.  WI = 2: 4 wavefronts, 128 instances, two LDS stages
-// (64 KB), two workgroups per CU whose barriers are independent.
 // kMode: kHFilter keeps candidates per instance; kHCollect runs over the instances listed in `rows`
 // (their number is *n_slots) and appends every node whose score is at most thr[slot] to the
 // instance's list; kHDump writes every score to dump[slot * k + node] (test hook).
 // `unit` numbers the (instance tile, node group) pairs; see the decoding below.
-template <int WI, int kMode>
+template <int kMode>
 __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, const float *__restrict__ Wh,
                                                  const float *__restrict__ wc, const float *__restrict__ xscale,
                                                  const float *__restrict__ wscale, int64_t n, int k, int nK,
@@ -85,13 +83,14 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
                                                  int32_t *__restrict__ list, const int64_t unit) {
   constexpr bool kCollect = kMode == kHCollect;
   constexpr bool kDump = kMode == kHDump;
+  constexpr int WI = kHWI;
   constexpr int kHTI = 64 * WI;              // instances per tile
   constexpr int kHXTile = kHTI * kHRow;      // floats
-  constexpr int kHStages = WI == 4 ? 3 : 2;
+  constexpr int kHStages = 2;
   constexpr int kWSlots = 16 / (2 * WI);     // W-tile load instructions per wavefront and chunk
   __shared__ __attribute__((aligned(16))) float sW[kHStages][kHWTile];
   __shared__ __attribute__((aligned(16))) float sX[kHStages][kHXTile];
-  __shared__ float sWn[4][kTN];      // node constants of the node blocks in flight (at most three)
+  __shared__ float sWn[4][kTN];      // node constants of the node blocks in flight
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -247,43 +246,30 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
     __builtin_amdgcn_s_setprio(0);
   };
 
-  // Pipeline with three stages.  Chunk c is loaded into stage c % 3 during iteration c - 2 and every
-  // wavefront waits for all its loads before the barrier that ends an iteration, so at the start of
-  // iteration t the chunks t and t + 1 are both complete in LDS.  That is what the third stage
-  // buys: the operands of the first k-step of chunk t + 1 are read into registers during iteration
-  // t, BEFORE the barrier, and the MFMAs of iteration t + 1 start right after it instead of waiting
-  // for LDS.  With two stages chunk t + 1 is loaded during iteration t and every operand is read
-  // after the barrier; there a second workgroup on the CU fills the gap.
-  constexpr bool kAhead = kHStages == 3;
+  // Two stages: chunk t + 1 is loaded during iteration t, every wavefront waits for its own loads
+  // before the barrier that ends the iteration, and every operand is read after that barrier; the
+  // second workgroup on the CU fills the gap.
   issue_loads(0);
-  if (kAhead && total > 1) issue_loads(1);
   __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wavefront's direct-to-LDS loads have landed
   __syncthreads();
 
   // Wavefronts that share a SIMD flush their accumulators in alternate chunks, so that one's
-  // additions overlap the other's MFMAs: w and w + 4 of a large workgroup, or the wavefronts of two
-  // small workgroups that sit next to each other in the launch order.  An interval is at most
+  // additions overlap the other's MFMAs: the wavefronts of two workgroups that sit next to each
+  // other in the launch order.  An interval is at most
   // flush_chunks chunks (2 or 4, see split_flush_chunks; the exact stage's margin prices it).
   const int flush_mask = flush_chunks - 1;
-  const int flush_phase = (WI == 4 ? (wave >> 2) : (int)(slot_id & 1)) * (flush_chunks >> 1);
+  const int flush_phase = (int)(slot_id & 1) * (flush_chunks >> 1);
   bool fresh = true;
   Operands op0, op1;
-  if (kAhead) read_operands(op0, 0, 0);
   int stage = 0;                                 // t % kHStages
   for (int t = 0; t < total; ++t) {
     const int nb = nb_first + t / nK, kc = t % nK;
-    const int next_stage = stage == kHStages - 1 ? 0 : stage + 1;
+    const int next_stage = stage ^ 1;
     // the stage that is loaded now held chunk t - 1, which every wavefront has left
-    if (kAhead) {
-      if (t + 2 < total) issue_loads(stage == 0 ? 2 : stage - 1);
-    } else {
-      if (t + 1 < total) issue_loads(next_stage);
-      read_operands(op0, stage, 0);
-    }
-
+    if (t + 1 < total) issue_loads(next_stage);
+    read_operands(op0, stage, 0);
     read_operands(op1, stage, 1);
     multiply(op0, fresh);
-    if (kAhead && t + 1 < total) read_operands(op0, next_stage, 0);
     multiply(op1, false);
 
     const bool last_k = (kc == nK - 1);
@@ -327,8 +313,8 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
 // Filter and dump modes: one unit per workgroup.  Collect mode: the number of live instance tiles is
 // only known on the device, so a fixed grid walks the units; its size is a multiple of 8, which keeps
 // unit mod 8 = workgroup mod 8 = the XCD the decoding assumes.
-template <int WI, int kMode>
-__global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__restrict__ Xh, const float *__restrict__ Wh,
+template <int kMode>
+__global__ __launch_bounds__(128 * kHWI, 2) void k_bmu_dense_h(const float *__restrict__ Xh, const float *__restrict__ Wh,
                                                         const float *__restrict__ wc,
                                                         const float *__restrict__ xscale,
                                                         const float *__restrict__ wscale,
@@ -339,15 +325,15 @@ __global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__rest
                                                         const float *__restrict__ thr, int32_t *__restrict__ cnt,
                                                         int32_t *__restrict__ list) {
   if (kMode == kHCollect) {
-    const int64_t ntiles = ((int64_t)*n_slots + 64 * WI - 1) / (64 * WI);
+    const int64_t ntiles = ((int64_t)*n_slots + 64 * kHWI - 1) / (64 * kHWI);
     const int64_t units = (ntiles + 7) / 8 * 8 * groups;
     for (int64_t unit = blockIdx.x; unit < units; unit += gridDim.x) {
-      bmu_dense_h_unit<WI, kMode>(Xh, Wh, wc, xscale, wscale, n, k, nK, flush_chunks, groups, out, dump, rows, n_slots,
+      bmu_dense_h_unit<kMode>(Xh, Wh, wc, xscale, wscale, n, k, nK, flush_chunks, groups, out, dump, rows, n_slots,
                                   thr, cnt, list, unit);
       __syncthreads();               // the next unit reuses the LDS stages
     }
   } else {
-    bmu_dense_h_unit<WI, kMode>(Xh, Wh, wc, xscale, wscale, n, k, nK, flush_chunks, groups, out, dump, rows, n_slots,
+    bmu_dense_h_unit<kMode>(Xh, Wh, wc, xscale, wscale, n, k, nK, flush_chunks, groups, out, dump, rows, n_slots,
                                 thr, cnt, list, (int64_t)blockIdx.x);
   }
 }
@@ -359,7 +345,7 @@ __global__ __launch_bounds__(128 * WI, 2) void k_bmu_dense_h(const float *__rest
 int bmu_dense_h_groups(const som_ctx *c, int64_t n) {
   const int64_t tiles = (n + 64 * kHWI - 1) / (64 * kHWI);
   const int nNB = (c->k + kTN - 1) / kTN;
-  const int64_t slots = (int64_t)c->n_cu * (kHWI == 4 ? 1 : 2);
+  const int64_t slots = (int64_t)c->n_cu * 2;      // two workgroups per CU
   int64_t want = (10 * slots + tiles - 1) / tiles;
   if (want < 2 && nNB >= 16) want = 2;
   if (want > nNB) want = nNB;
@@ -386,11 +372,11 @@ hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump) {
   const float *Xh = reinterpret_cast<const float *>(c->Xh);
   const float *Wh = reinterpret_cast<const float *>(c->Wh);
   if (dump)
-    hipLaunchKernelGGL((k_bmu_dense_h<kHWI, kHDump>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
+    hipLaunchKernelGGL((k_bmu_dense_h<kHDump>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
                        c->wn32, c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, dump, nullptr, nullptr, nullptr,
                        nullptr, nullptr);
   else
-    hipLaunchKernelGGL((k_bmu_dense_h<kHWI, kHFilter>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
+    hipLaunchKernelGGL((k_bmu_dense_h<kHFilter>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
                        c->wn32, c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, dump, nullptr, nullptr, nullptr,
                        nullptr, nullptr);
   return hipGetLastError();
@@ -409,7 +395,7 @@ hipError_t launch_bmu_dense_h_collect(som_ctx *c, int64_t n) {
   blocks = (blocks + 7) / 8 * 8;
   const int nK = (c->dim + 31) / 32;
   CandView out{nullptr, nullptr, nullptr};
-  hipLaunchKernelGGL((k_bmu_dense_h<kHWI, kHCollect>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
+  hipLaunchKernelGGL((k_bmu_dense_h<kHCollect>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
                      reinterpret_cast<const float *>(c->Xh), reinterpret_cast<const float *>(c->Wh), c->wn32,
                      c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, nullptr, c->collect_rows, c->list_counts + 1,
                      c->collect_thr, c->collect_cnt, c->collect_list);

@@ -15,6 +15,8 @@
 // The instance lists are built with atomic counters, so their order varies between runs;
 // every instance is decided independently, so the BMUs do not.
 //
+// (The split-fp16 pass multiplies centred instances x' = fl(x - mu): there X = |x'| and the terms in M
+// fall away.)
 // Error bound of one dense fp32 score s = c_i - 2 x.w'_i (u = 2^-24, g = roundings a product term
 // can suffer, X = |x|, M = |mu|, Wm = max |w'| over the nodes, w' = fl(w - mu)):
 //   |s_fp32 - s_exact| <= u [ (2 g + 4) X Wm + 4 Wm^2 + 6 M Wm ]
@@ -37,6 +39,7 @@ struct MarginModel {
   double coef_floor;         // 0 for the fp32 pass
   const float *xscale;       // [n] power-of-two scale of every instance (split-fp16 pass), else null
   const float *wscale;       // [1] power-of-two scale of the centred code book, else null
+  int x_centered;            // the instances were centred too (split-fp16 pass): X = |x - mu|, no term in M
   const int64_t *indptr;     // sparse rows: coef_xw = 2 max(row length, 1) + 6 (one FMA chain over the row)
   const float *row_q;        // [n] sparse rows scored against the 16-bit code book: sum_nz |v_c| step_c
 };
@@ -46,7 +49,7 @@ __device__ __forceinline__ double score_margin(const MarginModel &mm, int64_t j,
   const double u = 5.9604644775390625e-08;   // 2^-24
   const double xn = sqrt(xnorm2 * (1.0 + 1.2e-7));
   const double wm = sqrt(wmax2 * (1.0 + 1.2e-7));
-  const double mn = sqrt(munorm2 * (1.0 + 1.2e-7));
+  const double mn = mm.x_centered ? 0.0 : sqrt(munorm2 * (1.0 + 1.2e-7));
   double coef = mm.coef_xw;
   double absolute = 0.0;
   if (mm.indptr) {
@@ -428,21 +431,22 @@ static double split_pass_roundings(int dim) {
 
 // The rounding model of the filter that produced the scores (mode = kCertify*).
 static MarginModel margin_model(const som_ctx *c, int mode, const int64_t *indptr) {
-  MarginModel mm{2.0 * fp32_pass_roundings(c->dim) + 4.0, 0.0, nullptr, nullptr, nullptr, nullptr};
+  MarginModel mm{2.0 * fp32_pass_roundings(c->dim) + 4.0, 0.0, nullptr, nullptr, 0, nullptr, nullptr};
   if (mode == kCertifyCsr) {
     mm.indptr = indptr;
     mm.row_q = c->row_q;
   }
   if (mode == kCertifySplit) {
     // dot product: accumulation + 3 * 2^-22 of the split (= 12 u) ; both doubled by the factor -2;
-    // + 4 for the stored c_i, the final multiply-add and the rounding of w - mu.  The collect pass
-    // runs on the fp32 kernel with the threshold computed here, so the margin must cover that
-    // pass's own bound as well: never below the fp32 coefficient.
-    const double split = 2.0 * split_pass_roundings(c->dim) + 24.0 + 4.0;
+    // + 4 for the stored c_i, the final multiply-add and the rounding of w - mu, + 2 for the rounding
+    // of x - mu (its part that does not depend on the node cancels in every comparison).  Never
+    // below the fp32 coefficient.
+    const double split = 2.0 * split_pass_roundings(c->dim) + 24.0 + 4.0 + 2.0;
     if (split > mm.coef_xw) mm.coef_xw = split;
     mm.coef_floor = sqrt((double)c->dim);        // 2 * 2^-25 per element = u, |v|_1 <= sqrt(dim) |v|_2
     mm.xscale = c->xscale;
     mm.wscale = c->wscale;
+    mm.x_centered = 1;
   }
   return mm;
 }

@@ -9,6 +9,8 @@
 // error of the fp32 scores then scales with |x| |w - mu| instead of |x| |w|.  mu is the mean
 // of a sample of the instances.  Every epoch k_center_codebook writes w' = fl(w - mu) and the
 // per-node constants c_i = |w'_i|^2 + 2 mu.w'_i (of the rounded w', in fp64, rounded once).
+// The split-fp16 filter reads the instances from planes of the library's own, which hold
+// x' = fl(x - mu): there the scores are |w'_i|^2 - 2 x'.w'_i and their error scales with |x - mu|.
 // |x|^2 and |mu|^2 only bound the rounding error.  One wavefront per row, fp64 accumulation.
 #include "som_internal.hpp"
 
@@ -70,7 +72,7 @@ __global__ __launch_bounds__(256) void k_center_codebook(const float *__restrict
                                                          const float *__restrict__ mu, float *__restrict__ Wc,
                                                          float *__restrict__ cn, unsigned *__restrict__ max_bits,
                                                          double *__restrict__ wn64,
-                                                         unsigned *__restrict__ wabs_bits) {
+                                                         unsigned *__restrict__ wabs_bits, int x_centered) {
   __shared__ double scratch[4][3];
   constexpr int kTeams = 256 / kTeam;
   const int tl = threadIdx.x % kTeam, team = threadIdx.x / kTeam;
@@ -113,7 +115,7 @@ __global__ __launch_bounds__(256) void k_center_codebook(const float *__restrict
       sw = wave_sum(sw);
     }
     if (tl == 0) {
-      cn[i] = (float)(s2 + 2.0 * sm);
+      cn[i] = (float)(x_centered ? s2 : s2 + 2.0 * sm);      // instances centred too: |w'|^2 - 2 x'.w' ranks alike
       vmax = fmaxf(vmax, (float)s2);
       if (wn64) wn64[i] = sw;
     }
@@ -293,7 +295,7 @@ hipError_t launch_vec_sqnorm(som_ctx *c, const float *v, int dim, float *out) {
   return hipGetLastError();
 }
 
-hipError_t launch_center_codebook(som_ctx *c, const float *W, bool store_centered, bool want_wn64) {
+hipError_t launch_center_codebook(som_ctx *c, const float *W, bool store_centered, bool want_wn64, bool x_centered) {
   hipError_t e = launch_fill_zero_u32(c->stream, c->wmax_bits, 2);     // wmax_bits and wabs_bits are neighbours
   if (e != hipSuccess) return e;
   float *wc = store_centered ? c->Wc : nullptr;
@@ -303,11 +305,11 @@ hipError_t launch_center_codebook(som_ctx *c, const float *W, bool store_centere
   if (c->dim <= 2048) {
     const int need = (c->k + 3) / 4;
     hipLaunchKernelGGL(k_center_codebook<64>, dim3(need < cap ? need : cap), dim3(256), 0, c->stream, W, c->k, c->dim,
-                       c->mu, wc, c->wn32, c->wmax_bits, wn64, wabs);
+                       c->mu, wc, c->wn32, c->wmax_bits, wn64, wabs, x_centered ? 1 : 0);
   } else {
     const int cap_long = c->n_cu * 8;       // long rows: more workgroups in flight, still few atomics
     hipLaunchKernelGGL(k_center_codebook<256>, dim3(c->k < cap_long ? c->k : cap_long), dim3(256), 0, c->stream, W, c->k, c->dim,
-                       c->mu, wc, c->wn32, c->wmax_bits, wn64, wabs);
+                       c->mu, wc, c->wn32, c->wmax_bits, wn64, wabs, x_centered ? 1 : 0);
   }
   return hipGetLastError();
 }

@@ -229,15 +229,15 @@ static int prepare_dense(som_ctx *c, const float *X, int64_t n, const float *W, 
     c->d_split_valid = 0;
     SOM_LAUNCH(c, launch_sample_col_means(c, X, n, c->dim, c->mu));
     SOM_LAUNCH(c, launch_vec_sqnorm(c, c->mu, c->dim, c->mu_norm2));
-    SOM_LAUNCH(c, launch_row_sqnorms(c, X, n, c->dim, nullptr, c->xn32, nullptr, nullptr));
+    SOM_LAUNCH(c, launch_row_sqnorms(c, X, n, c->dim, split ? c->mu : nullptr, c->xn32, nullptr, nullptr));
   }
   if (split && !(have_xn && c->d_split_valid)) {
-    SOM_LAUNCH(c, launch_split_rows_f16(c, X, n, nullptr, c->Xh, c->xscale));
+    SOM_LAUNCH(c, launch_split_rows_f16(c, X, n, nullptr, c->mu, c->Xh, c->xscale));
     c->d_split_valid = have_xn ? 1 : 0;
   }
-  SOM_LAUNCH(c, launch_center_codebook(c, W, true, false));
+  SOM_LAUNCH(c, launch_center_codebook(c, W, true, false, split));
   if (c->nb_function == SOM_NEIGHBORHOOD_BUBBLE) SOM_LAUNCH(c, launch_mask_duplicate_rows(c, W));
-  if (split) SOM_LAUNCH(c, launch_split_rows_f16(c, c->Wc, c->k, c->wmax_bits + 1, c->Wh, c->wscale));
+  if (split) SOM_LAUNCH(c, launch_split_rows_f16(c, c->Wc, c->k, c->wmax_bits + 1, nullptr, c->Wh, c->wscale));
   SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 3));
   return SOM_OK;
 }
@@ -284,10 +284,10 @@ static int prepare_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices
   }
   // centring vector of the sparse search: the mean of the code-book rows (changes every epoch);
   // it overwrites the one a registered dense training set may have cached
-  if (c->data_kind == 1) c->d_norms_valid = 0;
+  if (c->data_kind == 1) { c->d_norms_valid = 0; c->d_split_valid = 0; }
   SOM_LAUNCH(c, launch_codebook_means_and_steps(c, W));
   SOM_LAUNCH(c, launch_vec_sqnorm(c, c->mu, c->dim, c->mu_norm2));
-  SOM_LAUNCH(c, launch_center_codebook(c, W, false, true));
+  SOM_LAUNCH(c, launch_center_codebook(c, W, false, true, false));
   if (c->nb_function == SOM_NEIGHBORHOOD_BUBBLE) SOM_LAUNCH(c, launch_mask_duplicate_rows(c, W));
   SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, kListCounts));
   return SOM_OK;
@@ -340,7 +340,9 @@ static int registered_norms(som_ctx *c) {
   if (c->data_kind == 1) {
     SOM_LAUNCH(c, launch_sample_col_means(c, c->d_data, c->d_n, c->dim, c->mu));
     SOM_LAUNCH(c, launch_vec_sqnorm(c, c->mu, c->dim, c->mu_norm2));
-    SOM_LAUNCH(c, launch_row_sqnorms(c, c->d_data, c->d_n, c->dim, nullptr, c->xn32, nullptr, nullptr));
+    // the split-fp16 filter works on centred instances, and its margin on their norms
+    SOM_LAUNCH(c, launch_row_sqnorms(c, c->d_data, c->d_n, c->dim, c->filter == SOM_FILTER_SPLIT_F16 ? c->mu : nullptr,
+                                     c->xn32, nullptr, nullptr));
   } else {
     SOM_LAUNCH(c, launch_csr_row_sqnorms(c, c->d_indptr, c->d_values, c->d_n, c->xn32));
   }
@@ -740,6 +742,10 @@ int som_set_filter(som_ctx *c, int filter) {
   if (!c) return SOM_ERR_INVALID_ARG;
   if (filter != SOM_FILTER_FP32 && filter != SOM_FILTER_SPLIT_F16)
     return fail(c, SOM_ERR_INVALID_ARG, "unknown filter %d", filter);
+  if (filter != c->filter) {           // norms and planes of a registered set belong to the filter they were made for
+    c->d_norms_valid = 0;
+    c->d_split_valid = 0;
+  }
   c->filter = filter;
   return SOM_OK;
 }

@@ -94,7 +94,7 @@ struct som_ctx {
 
   // per-data scratch (grown on demand to n_cap rows)
   int64_t n_cap;
-  float *xn32;            // [n] squared norms of the instances
+  float *xn32;            // [n] squared norms of the instances (split-fp16 filter: of the centred instances x - mu)
   float *vq;              // [vq_cap] sparse search: value of every nonzero times the step of its column
   int64_t vq_cap;
   float *row_q;           // [n] sparse rows: sum over the nonzeros of |value| x quantisation step of the column
@@ -148,7 +148,8 @@ namespace som {
 hipError_t launch_sample_col_means(som_ctx *c, const float *A, int64_t nrows, int dim, float *mu);
 hipError_t launch_codebook_means_and_steps(som_ctx *c, const float *W);      // -> mu, qstep, qstep_max_bits
 hipError_t launch_vec_sqnorm(som_ctx *c, const float *v, int dim, float *out);
-hipError_t launch_center_codebook(som_ctx *c, const float *W, bool store_centered, bool want_wn64);   // -> Wc, wn32 (= c_i), wmax_bits, wn64
+hipError_t launch_center_codebook(som_ctx *c, const float *W, bool store_centered, bool want_wn64,
+                                  bool x_centered);   // -> Wc, wn32 (= c_i; without the 2 mu.w' term if the instances are centred too), wmax_bits, wn64
 hipError_t launch_row_sqnorms(som_ctx *c, const float *A, int64_t nrows, int dim, const float *mu,
                               float *out32, double *out64, unsigned *max_bits);
 hipError_t launch_csr_row_sqnorms(som_ctx *c, const int64_t *indptr, const float *values, int64_t n,
@@ -169,7 +170,7 @@ int bmu_dense_h_groups(const som_ctx *c, int64_t n);
 hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump);            // Xh, Wh -> candidates (or all scores)
 hipError_t launch_bmu_dense_h_collect(som_ctx *c, int64_t n);                 // rows of collect_rows -> collect_list
 hipError_t launch_split_rows_f16(som_ctx *c, const float *A, int64_t nrows, const unsigned *global_max_bits,
-                                 _Float16 *out, float *scale_out);
+                                 const float *mu /* subtracted first, or null */, _Float16 *out, float *scale_out);
 hipError_t launch_probe_mfma_f16(hipStream_t stream, const uint16_t *A, const uint16_t *B, const float *C, float *D,
                                  int count);
 

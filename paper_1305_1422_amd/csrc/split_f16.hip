@@ -33,9 +33,12 @@ __device__ __forceinline__ float pow2_above(float m, float *inverse) {
 // `global_max_bits` every row uses the same scale (the code book: one factor for all nodes, so
 // that the scores of an instance stay comparable without a per-node multiplication) and the
 // scale is also written to *scale_out; without it each row gets its own scale in scale_out[row].
+// With `mu` the rows are centred first, a_c - mu_c in fp32 (the instances of the dense search: their
+// scores then carry |x - mu| instead of |x| in the rounding bound).
 template <int kTeam>
 __global__ __launch_bounds__(256) void k_split_rows_f16(const float *__restrict__ A, int64_t nrows, int dim, int nK,
                                                         const unsigned *__restrict__ global_max_bits,
+                                                        const float *__restrict__ mu,
                                                         _Float16 *__restrict__ out, float *__restrict__ scale_out) {
   __shared__ float smax[4];
   constexpr int kTeams = 256 / kTeam;
@@ -48,7 +51,7 @@ __global__ __launch_bounds__(256) void k_split_rows_f16(const float *__restrict_
       m = __uint_as_float(*global_max_bits);
     } else {
       m = 0.f;
-      for (int c = tl; c < dim; c += kTeam) m = fmaxf(m, fabsf(a[c]));
+      for (int c = tl; c < dim; c += kTeam) m = fmaxf(m, fabsf(mu ? a[c] - mu[c] : a[c]));
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
       if (kTeam == 256) {          // r depends on the block only: every thread gets here
@@ -66,7 +69,7 @@ __global__ __launch_bounds__(256) void k_split_rows_f16(const float *__restrict_
     }
     _Float16 *o = out + r * (int64_t)nK * 64;
     for (int c = tl; c < padded; c += kTeam) {
-      const float v = c < dim ? a[c] * inv : 0.f;
+      const float v = c < dim ? (mu ? a[c] - mu[c] : a[c]) * inv : 0.f;
       const _Float16 hi = (_Float16)v;
       const _Float16 lo = (_Float16)(v - (float)hi);
       const int at = (c >> 5) * 64 + (c & 31);
@@ -77,18 +80,18 @@ __global__ __launch_bounds__(256) void k_split_rows_f16(const float *__restrict_
 }
 
 hipError_t launch_split_rows_f16(som_ctx *c, const float *A, int64_t nrows, const unsigned *global_max_bits,
-                                 _Float16 *out, float *scale_out) {
+                                 const float *mu, _Float16 *out, float *scale_out) {
   const int nK = (c->dim + 31) / 32;
   const int64_t cap = (int64_t)c->n_cu * 16;
   if (c->dim <= 2048) {
     int64_t blocks = (nrows + 3) / 4;
     if (blocks > cap) blocks = cap;
     hipLaunchKernelGGL(k_split_rows_f16<64>, dim3((unsigned)blocks), dim3(256), 0, c->stream, A, nrows, c->dim, nK,
-                       global_max_bits, out, scale_out);
+                       global_max_bits, mu, out, scale_out);
   } else {
     int64_t blocks = nrows < cap ? nrows : cap;
     hipLaunchKernelGGL(k_split_rows_f16<256>, dim3((unsigned)blocks), dim3(256), 0, c->stream, A, nrows, c->dim, nK,
-                       global_max_bits, out, scale_out);
+                       global_max_bits, mu, out, scale_out);
   }
   return hipGetLastError();
 }

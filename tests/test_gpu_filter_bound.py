@@ -4,7 +4,8 @@ dumped and compared with its exact value in float64; no error may exceed half th
 applies to that instance (the library reports the margin it uses: same device function, same inputs), and for
 the two dense filters the documented closed form of the bound is evaluated here from the inputs alone as well.
 
-Split-fp16 filter:
+Split-fp16 filter (it multiplies centred instances x' = fl(x - mu), so X below is |x'_j| and the term in M
+falls away; the closed form evaluated in the test is the centred one, with coef = 2 g + 30):
 
 The split-fp16 filter ranks nodes by scores whose distance from the exact value is bounded by
     B = u [ coef X Wm + sqrt(dim) (sx_j Wm + sw X) + 4 Wm^2 + 6 M Wm ],      u = 2^-24,
@@ -121,11 +122,18 @@ def _score_bound_case(x, w, rows, cols, filter="split_f16"):
     # the rounding of w - mu is part of the library's bound but not of this comparison (the exact
     # scores above start from the rounded w'), so the bound tested here is slightly larger than needed
     if filter == "split_f16":
-        sx = _pow2_above(np.abs(x64).max(1))
+        # this filter multiplies centred instances x' = fl(x - mu): their norms and scales enter the bound,
+        # |mu| does not (what the rounding of x - mu adds for all nodes alike cancels in every comparison)
+        xc64 = (x - mu32[None, :]).astype(np.float32).astype(np.float64)
+        Xc = np.sqrt((xc64 ** 2).sum(1))
+        sx = _pow2_above(np.abs(xc64).max(1))
         sw = float(_pow2_above(np.abs(wc64).max()))
         f = 4 if dim >= 256 else 2                                 # chunks of 32 features between two flushes
         g = 2.5 * 6 * f + 9 + np.ceil(dim / (32 * f)) + 2
-        B = U * ((2 * g + 28) * X * Wm + np.sqrt(dim) * (sx * Wm + sw * X) + 4 * Wm ** 2 + 6 * M * Wm)
+        B = U * ((2 * g + 30) * Xc * Wm + np.sqrt(dim) * (sx * Wm + sw * Xc) + 4 * Wm ** 2)
+        # the constant 2 delta.x' that the rounding delta of x - mu adds to every score of an instance is no
+        # error of the ranking: compare after removing each instance's mean difference
+        s_exact = s_exact + np.mean(s_gpu - s_exact, axis=1, keepdims=True)
     else:
         g = 32 + np.ceil(dim / 32) + 2                             # accumulator flushed every 32 features
         B = U * ((2 * g + 4) * X * Wm + 4 * Wm ** 2 + 6 * M * Wm)
