@@ -73,6 +73,8 @@ def main() -> int:
                     help="neighbourhood of the update (the stated configurations use the plain Gaussian)")
     ap.add_argument("--smoothing", choices=["auto", "vector", "matrix"], default="auto",
                     help="units that run the Gaussian smoothing passes (same results)")
+    ap.add_argument("--no-hot-block", action="store_true",
+                    help="sparse workloads: keep all columns in the gather sweep (no dense block of frequent columns)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run ten plain 1 GiB device copies and exit: under rocprofv3 --pmc this gives the "
                          "reading of FETCH_SIZE / WRITE_SIZE for a kernel of known traffic")
@@ -114,6 +116,8 @@ def main() -> int:
     if args.neighborhood != "gaussian":
         som.set_neighborhood("bubble" if args.neighborhood == "bubble" else "gaussian", args.neighborhood != "bubble")
     som.set_smoothing(args.smoothing)
+    if args.no_hot_block:
+        som.set_sparse_hot_block(False)
     bmus = torch.empty(w.n, dtype=torch.int32, device=dev)
     # register the resident training set: its norms are then computed once, not every epoch
     if w.kind == "dense":
@@ -213,7 +217,8 @@ def main() -> int:
                             "depends on the code book included; outside the step, once per registered data set: "
                             + ("squared norms of the instances, their fp16 hi/lo planes, sampled column means"
                                if w.kind == "dense" else "squared norms of the instances")),
-                   "neighborhood": args.neighborhood, "smoothing": args.smoothing},
+                   "neighborhood": args.neighborhood, "smoothing": args.smoothing,
+                   "sparse_hot_block": bool(w.kind != "dense" and capi.som_sparse_hot_block_active(som.ctx))},
         "gflops_epoch": 2.0 * work / (dt / args.steps) / 1e9,
         "frac_fp32_mfma_peak_whole_epoch": 2.0 * work / (dt / args.steps) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
         "stage_ms": stage_ms,

@@ -284,6 +284,20 @@ int som_umatrix(som_ctx *ctx, const float *codebook, float *umatrix);
 int som_set_neighborhood(som_ctx *ctx, int function, int compact_support);
 
 /*
+ * som_set_sparse_hot_block - whether a REGISTERED sparse training set may be split into a dense block of
+ * its 256 most frequent columns, multiplied with the code book on the matrix cores, and a sparse rest
+ * (paper: sparse kernel).  On by default; the split is used only when those columns hold at least 30 % of
+ * the nonzeros, dim >= 1,024 and the table of partial sums (4 bytes per instance and node) stays under
+ * 8 GiB.  The BMUs do not depend on it (the exact stage decides on the caller's full rows).  It is
+ * prepared at the first epoch or search after registration, which waits for the stream once, and costs
+ * about 1 KB of device memory per instance plus a copy of the remaining nonzeros.
+ */
+int som_set_sparse_hot_block(som_ctx *ctx, int enable);
+
+/* 1 if the registered sparse set has been examined and its hot-column block is in use, else 0. */
+int som_sparse_hot_block_active(const som_ctx *ctx);
+
+/*
  * som_set_smoothing - which units run the two passes of the Gaussian neighbourhood smoothing (batch
  * equation; neighbourhood equation).  The result is the same up to the order of the fp32 additions.
  *   SOM_SMOOTH_AUTO (default)  a pass over map lines of at least 32 nodes runs as a matrix product on

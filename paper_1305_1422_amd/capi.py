@@ -31,7 +31,7 @@ EXPORTS = [
     "som_bmu_distances_dense", "som_bmu_distances_csr", "som_bmu_distances_dense_static",
     "som_cool_schedule", "som_umatrix", "som_get_stats",
     "som_profile_enable", "som_profile_read",
-    "som_set_filter", "som_set_smoothing", "som_set_neighborhood", "som_set_scale_cooling", "som_validate_csr", "som_debug_scores_dense", "som_debug_scores_csr", "som_debug_mfma_f16",
+    "som_set_filter", "som_set_smoothing", "som_set_sparse_hot_block", "som_sparse_hot_block_active", "som_set_neighborhood", "som_set_scale_cooling", "som_validate_csr", "som_debug_scores_dense", "som_debug_scores_csr", "som_debug_mfma_f16",
 ]
 PROFILE_STAGES = ("bmu_dense_filter", "bmu_csr_filter", "bmu_exact", "node_sums", "smooth_divide", "prepare_dense")
 
@@ -100,6 +100,10 @@ def load():
     L.som_set_scale_cooling.argtypes = [vp, i32]
     L.som_validate_csr.restype = i32
     L.som_validate_csr.argtypes = [vp, vp, vp, vp, i64, i64]
+    L.som_set_sparse_hot_block.restype = i32
+    L.som_set_sparse_hot_block.argtypes = [vp, i32]
+    L.som_sparse_hot_block_active.restype = i32
+    L.som_sparse_hot_block_active.argtypes = [vp]
     L.som_set_smoothing.restype = i32
     L.som_set_smoothing.argtypes = [vp, i32]
     L.som_set_filter.restype = i32
@@ -320,6 +324,14 @@ def som_validate_csr(ctx, indptr, indices, values) -> None:
                                         _ptr(indices, torch.int32, "indices", True),
                                         _ptr(values, torch.float32, "values", True), indptr.shape[0] - 1,
                                         0 if indices is None else indices.shape[0]))
+
+
+def som_set_sparse_hot_block(ctx, enable: bool) -> None:
+    _check(ctx, load().som_set_sparse_hot_block(ctx, 1 if enable else 0))
+
+
+def som_sparse_hot_block_active(ctx) -> bool:
+    return bool(load().som_sparse_hot_block_active(ctx))
 
 
 def som_set_smoothing(ctx, form: int) -> None:

@@ -101,7 +101,9 @@ __global__ __launch_bounds__(256) void k_bmu_csr_sliced(const int64_t *__restric
                                                         const int32_t *__restrict__ rows,
                                                         UnitWork work,
                                                         const float *__restrict__ thr, int32_t *__restrict__ cnt,
-                                                        int32_t *__restrict__ list, float *__restrict__ dump) {
+                                                        int32_t *__restrict__ list, float *__restrict__ dump,
+                                                        const float *__restrict__ phot,
+                                                        const float *__restrict__ hot_xscale) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int slice = blockIdx.x & 7;
@@ -128,8 +130,20 @@ __global__ __launch_bounds__(256) void k_bmu_csr_sliced(const int64_t *__restric
     const int base = slice0 + sw * (64 * ACC) + lane;    // this lane's first node
     float vq_abs = 0.f;                                  // this lane's share of sum |v_c| step_c
     float acc[ACC];
+    if (phot) {
+      // the rows are the tail of a registered set: the dot products of its frequent columns come from the
+      // matrix-core pass (csr_hot.hip), 64 consecutive nodes = 256 contiguous bytes per load
+      // (the table is [block of 128 nodes][instance][128]: a lane set of 64 nodes never straddles a block)
+      const float xs = hot_xscale[j];
 #pragma unroll
-    for (int a = 0; a < ACC; ++a) acc[a] = 0.f;
+      for (int a = 0; a < ACC; ++a) {
+        const int node = base + 64 * a;
+        acc[a] = node < k ? xs * phot[((int64_t)(node >> 7) * n + j) * 128 + (node & 127)] : 0.f;
+      }
+    } else {
+#pragma unroll
+      for (int a = 0; a < ACC; ++a) acc[a] = 0.f;
+    }
     for (int p0 = 0; p0 < len; p0 += 64) {
       int c = 0;
       float v = 0.f;
@@ -232,7 +246,8 @@ __global__ __launch_bounds__(256) void k_bmu_csr_sliced(const int64_t *__restric
 
 template <bool kCollect>
 static void launch_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values, int64_t n,
-                          float *dump) {
+                          float *dump, bool hot) {
+  const float *phot = hot ? c->hot_P : nullptr;
   int64_t groups = (n * c->csr_sweeps + 3) / 4;                   // workgroups per slice
   const int64_t cap = (int64_t)c->n_cu;                           // 8 slices x n_cu = 8 workgroups per CU
   if (groups > cap) groups = cap;
@@ -243,7 +258,7 @@ static void launch_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indi
   hipLaunchKernelGGL((k_bmu_csr_sliced<A, kCollect>), grid, dim3(256), 0, c->stream, indptr, indices, values,        \
                      reinterpret_cast<const int16_t *>(c->Wt), c->kpad, c->csr_sweeps, nullptr, c->wn32, n, c->k,   \
                      c->dim, out, c->row_q, c->collect_rows, work, c->collect_thr, c->collect_cnt,    \
-                     c->collect_list, dump)
+                     c->collect_list, dump, phot, c->hot_xscale)
   switch (c->csr_acc) {
     case 1: SOM_SLICED(1); break;
     case 2: SOM_SLICED(2); break;
@@ -329,9 +344,9 @@ hipError_t launch_validate_csr(som_ctx *c, const int64_t *indptr, const int32_t 
 }
 
 hipError_t launch_bmu_csr_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
-                                 int64_t n, bool collect, float *dump) {
-  if (collect) launch_sliced<true>(c, indptr, indices, values, n, nullptr);
-  else launch_sliced<false>(c, indptr, indices, values, n, dump);
+                                 int64_t n, bool collect, float *dump, bool hot) {
+  if (collect) launch_sliced<true>(c, indptr, indices, values, n, nullptr, hot);
+  else launch_sliced<false>(c, indptr, indices, values, n, dump, hot);
   return hipGetLastError();
 }
 

@@ -65,13 +65,17 @@ __device__ __forceinline__ void load16_to_lds_v(const void *lane_address, unsign
 }
 #pragma clang diagnostic pop
 
-enum { kHFilter = 0, kHCollect = 1, kHDump = 2 };
+enum { kHFilter = 0, kHCollect = 1, kHDump = 2, kHPartial = 3 };
 
 __device__ __forceinline__ f16x8 as_halves(f32x4 v) { return __builtin_bit_cast(f16x8, v); }
 
 // kMode: kHFilter keeps candidates per instance; kHCollect runs over the instances listed in `rows`
 // (their number is *n_slots) and appends every node whose score is at most thr[slot] to the
-// instance's list; kHDump writes every score to dump[slot * k + node] (test hook).
+// instance's list; kHDump writes every score to dump[slot * k + node] (test hook); kHPartial is the
+// hot-column block of the sparse search (csr_hot.hip): the two operands swap places in the matrix
+// instruction, so a lane holds one NODE and 16 instances per block, and the plain dot products times
+// the code book's scale go to dump[(node block * n + instance) * 128 + node within the block] - 128
+// contiguous bytes per store and half-wavefront.  No candidates, no constants.
 // `unit` numbers the (instance tile, node group) pairs; see the decoding below.
 template <int kMode>
 __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, const float *__restrict__ Wh,
@@ -83,6 +87,7 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
                                                  int32_t *__restrict__ list, const int64_t unit) {
   constexpr bool kCollect = kMode == kHCollect;
   constexpr bool kDump = kMode == kHDump;
+  constexpr bool kPartial = kMode == kHPartial;
   constexpr int WI = kHWI;
   constexpr int kHTI = 64 * WI;              // instances per tile
   constexpr int kHXTile = kHTI * kHRow;      // floats
@@ -156,7 +161,7 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
       for (int i = 0; i < kWSlots; ++i) woff[i] = (unsigned)(wrow[i] < last_node ? wrow[i] : last_node) * row_bytes + wq[i];
       // node constants of the block: wc is padded to whole blocks with +inf (such nodes can never
       // win), so the 128 values are loaded like the tiles, as the oldest operation of the batch
-      if (wave < 2) load4_to_lds_h(wc + (int64_t)ld_nb * kTN, wn_off, lds_wn + (ld_nb & 3) * (kTN * 4) + wave * 256);
+      if (!kPartial && wave < 2) load4_to_lds_h(wc + (int64_t)ld_nb * kTN, wn_off, lds_wn + (ld_nb & 3) * (kTN * 4) + wave * 256);
     }
     const unsigned off = (unsigned)ld_kc * (kHRow * 4);
 #pragma unroll
@@ -188,7 +193,7 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
     slot_of[ni] = inst0 + wi * 64 + ni * 32 + l32;
     const bool live = slot_of[ni] < n_inst;
     const int64_t inst = live ? (kCollect ? (int64_t)rows[slot_of[ni]] : slot_of[ni]) : 0;
-    factor[ni] = live ? -2.f * xscale[inst] * sw : 0.f;
+    factor[ni] = (live && !kPartial) ? -2.f * xscale[inst] * sw : 0.f;
     lim[ni] = (kCollect && live) ? thr[slot_of[ni]] : -INFINITY;
   }
 
@@ -225,24 +230,28 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g2[mi], o.h1[ni], zero, 0, 0, 0);
+          acc[mi][ni] = kPartial ? __builtin_amdgcn_mfma_f32_32x32x16_f16(o.h1[ni], o.g2[mi], zero, 0, 0, 0)
+                                 : __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g2[mi], o.h1[ni], zero, 0, 0, 0);
     } else {
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g2[mi], o.h1[ni], acc[mi][ni], 0, 0, 0);
+          acc[mi][ni] = kPartial ? __builtin_amdgcn_mfma_f32_32x32x16_f16(o.h1[ni], o.g2[mi], acc[mi][ni], 0, 0, 0)
+                                 : __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g2[mi], o.h1[ni], acc[mi][ni], 0, 0, 0);
     }
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
       for (int ni = 0; ni < 2; ++ni)
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g1[mi], o.h2[ni], acc[mi][ni], 0, 0, 0);
+        acc[mi][ni] = kPartial ? __builtin_amdgcn_mfma_f32_32x32x16_f16(o.h2[ni], o.g1[mi], acc[mi][ni], 0, 0, 0)
+                               : __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g1[mi], o.h2[ni], acc[mi][ni], 0, 0, 0);
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
       for (int ni = 0; ni < 2; ++ni)
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g1[mi], o.h1[ni], acc[mi][ni], 0, 0, 0);
+        acc[mi][ni] = kPartial ? __builtin_amdgcn_mfma_f32_32x32x16_f16(o.h1[ni], o.g1[mi], acc[mi][ni], 0, 0, 0)
+                               : __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g1[mi], o.h1[ni], acc[mi][ni], 0, 0, 0);
     __builtin_amdgcn_s_setprio(0);
   };
 
@@ -283,7 +292,22 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
           for (int v = 0; v < 16; ++v) tot[mi][ni][v] += acc[mi][ni][v];
     }
     if (last_k) {
-      if (kDump) {
+      if (kPartial) {
+        // lane = node wm 64 + mi 32 + l32 of the block, register v = instance wi 64 + ni 32 + mfma_row;
+        // the table is laid out [node block][instance][128 nodes], so the 128 x 128 results of a workgroup
+        // and node block fill one contiguous 64 KB run
+        float *pblk = dump + ((int64_t)nb * n + inst0) * kTN + wm * 64 + l32;
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int il = wi * 64 + ni * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
+              if (inst0 + il < n) pblk[il * kTN + mi * 32] = sw * tot[mi][ni][v];
+              tot[mi][ni][v] = 0.f;
+            }
+      } else if (kDump) {
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -305,7 +329,7 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
     __syncthreads();
     stage = next_stage;
   }
-  if (kDump || kCollect) return;
+  if (kDump || kCollect || kPartial) return;
   merge_and_store<kHTI>(top, &sW[0][0], reinterpret_cast<int *>(&sX[0][0]), tid, wm, wi, l32, lhi, inst0, n, group,
                         out);
 }
@@ -379,6 +403,20 @@ hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump) {
     hipLaunchKernelGGL((k_bmu_dense_h<kHFilter>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
                        c->wn32, c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, dump, nullptr, nullptr, nullptr,
                        nullptr, nullptr);
+  return hipGetLastError();
+}
+
+// Hot-column block of the sparse search: P[node block][n][128] = (x_hot . w'_hot) / (scale of the instance), from the
+// planes c->hot_Xh [n][kHot] and c->hot_Wh [k][kHot]; the same tiling and launch shape as the filter.
+hipError_t launch_hot_partial(som_ctx *c, int64_t n) {
+  const int groups = bmu_dense_h_groups(c, n);
+  const int64_t tiles = (n + 64 * kHWI - 1) / (64 * kHWI);
+  const int64_t blocks = (tiles + 7) / 8 * 8 * groups;
+  CandView out{nullptr, nullptr, nullptr};
+  hipLaunchKernelGGL((k_bmu_dense_h<kHPartial>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
+                     reinterpret_cast<const float *>(c->hot_Xh), reinterpret_cast<const float *>(c->hot_Wh), nullptr,
+                     nullptr, c->hot_wscale, n, c->k, kHot / 32, split_flush_chunks(kHot), groups, out, c->hot_P,
+                     nullptr, nullptr, nullptr, nullptr, nullptr);
   return hipGetLastError();
 }
 

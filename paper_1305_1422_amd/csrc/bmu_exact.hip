@@ -42,6 +42,12 @@ struct MarginModel {
   int x_centered;            // the instances were centred too (split-fp16 pass): X = |x - mu|, no term in M
   const int64_t *indptr;     // sparse rows: coef_xw = 2 max(row length, 1) + 6 (one FMA chain over the row)
   const float *row_q;        // [n] sparse rows scored against the 16-bit code book: sum_nz |v_c| step_c
+  // sparse rows whose frequent columns went through the matrix cores (csr_hot.hip): the split-fp16 bound
+  // of that block, coef_hot |x_hot| Wm + sqrt(kHot) (hot_xscale_j Wm + hot_wscale |x_hot|), in units of u
+  double coef_hot;           // 0: no hot block
+  const float *hot_xn;       // [n] |x_hot|^2
+  const float *hot_xscale;   // [n]
+  const float *hot_wscale;   // [1]
 };
 
 __device__ __forceinline__ double score_margin(const MarginModel &mm, int64_t j, double xnorm2, double wmax2,
@@ -61,6 +67,10 @@ __device__ __forceinline__ double score_margin(const MarginModel &mm, int64_t j,
     if (mm.row_q) absolute = 2.0 * 0.51 * (1.0 + 1e-5) * (double)mm.row_q[j];
   }
   double bound = coef * xn * wm + 4.0 * wm * wm + 6.0 * mn * wm;
+  if (mm.coef_hot > 0.0) {
+    const double xh = sqrt((double)mm.hot_xn[j] * (1.0 + 1.2e-7));
+    bound += mm.coef_hot * xh * wm + sqrt((double)kHot) * ((double)mm.hot_xscale[j] * wm + (double)*mm.hot_wscale * xh);
+  }
   if (mm.xscale) bound += mm.coef_floor * ((double)mm.xscale[j] * wm + (double)*mm.wscale * xn);
   return 2.125 * (u * bound + absolute);          // both scores of a pair may err, plus slack for higher-order terms
 }
@@ -430,11 +440,25 @@ static double split_pass_roundings(int dim) {
 }
 
 // The rounding model of the filter that produced the scores (mode = kCertify*).
-static MarginModel margin_model(const som_ctx *c, int mode, const int64_t *indptr) {
-  MarginModel mm{2.0 * fp32_pass_roundings(c->dim) + 4.0, 0.0, nullptr, nullptr, 0, nullptr, nullptr};
+// Roundings of the split-fp16 pass over `dim` features (see split_pass_roundings).
+static double split_roundings_for(int dim) {
+  const int chunks = split_flush_chunks(dim);
+  return 2.5 * 6.0 * chunks + 9.0 + (double)((dim + 32 * chunks - 1) / (32 * chunks)) + 2.0;
+}
+
+static MarginModel margin_model(const som_ctx *c, int mode, const int64_t *indptr, bool hot = false) {
+  MarginModel mm{2.0 * fp32_pass_roundings(c->dim) + 4.0, 0.0, nullptr, nullptr, 0, nullptr, nullptr, 0.0, nullptr, nullptr, nullptr};
   if (mode == kCertifyCsr) {
     mm.indptr = indptr;
     mm.row_q = c->row_q;
+    if (hot) {
+      // the hot block's dot product: accumulation + 12 u of the split, doubled by the factor -2 of the score;
+      // its product then joins the chain of the tail (one more rounding, inside the tail's own + 6)
+      mm.coef_hot = 2.0 * split_roundings_for(kHot) + 24.0;
+      mm.hot_xn = c->hot_xn;
+      mm.hot_xscale = c->hot_xscale;
+      mm.hot_wscale = c->hot_wscale;
+    }
   }
   if (mode == kCertifySplit) {
     // dot product: accumulation + 3 * 2^-22 of the split (= 12 u) ; both doubled by the factor -2;
@@ -451,9 +475,9 @@ static MarginModel margin_model(const som_ctx *c, int mode, const int64_t *indpt
   return mm;
 }
 
-hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int64_t *indptr, int32_t *bmus) {
+hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int64_t *indptr, int32_t *bmus, bool hot) {
   CandView cand{c->cand_val, c->cand_idx, c->cand_over};
-  const MarginModel mm = margin_model(c, mode, indptr);
+  const MarginModel mm = margin_model(c, mode, indptr, hot);
   UnitWork work{0, 0, nullptr, nullptr, nullptr};
   if (mode == kCertifyCsr)
     work = UnitWork{c->csr_sweeps, c->unit_cap, c->unit_work, c->list_counts + kUnitCounts, c->collect_list};
@@ -471,9 +495,9 @@ __global__ __launch_bounds__(256) void k_margins(const float *__restrict__ xn32,
   if (j < n) out[j] = score_margin(mm, j, (double)xn32[j], (double)__uint_as_float(*wmax_bits), (double)*mu_norm2);
 }
 
-hipError_t launch_margins(som_ctx *c, int64_t n, int mode, const int64_t *indptr, double *out) {
+hipError_t launch_margins(som_ctx *c, int64_t n, int mode, const int64_t *indptr, double *out, bool hot) {
   hipLaunchKernelGGL(k_margins, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, c->xn32, c->wmax_bits,
-                     c->mu_norm2, margin_model(c, mode, indptr), n, out);
+                     c->mu_norm2, margin_model(c, mode, indptr, hot), n, out);
   return hipGetLastError();
 }
 

@@ -372,6 +372,11 @@ hipError_t launch_sort_by_bmu(som_ctx *c, const int32_t *bmus, int64_t n) {
   return hipGetLastError();
 }
 
+hipError_t launch_scan_exclusive_i32(som_ctx *c, const int32_t *in, int32_t *out, int len) {
+  hipLaunchKernelGGL(k_scan_exclusive, dim3(1), dim3(1024), 0, c->stream, in, out, len, 0);
+  return hipGetLastError();
+}
+
 hipError_t launch_accumulate_dense(som_ctx *c, const float *X, int64_t n) {
   hipLaunchKernelGGL(k_scan_exclusive, dim3(1), dim3(1024), 0, c->stream, c->counts, c->chunk_off, c->k,
                      kChunkRows);

@@ -17,6 +17,7 @@
 #include <string.h>
 
 #include <mutex>
+#include <vector>
 
 using namespace som;
 
@@ -297,16 +298,28 @@ static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indi
                           int64_t n, int64_t nnz, const float *W, int32_t *bmus, bool have_xn) {
   int rc = prepare_csr(c, indptr, indices, values, n, nnz, W, have_xn);
   if (rc) return rc;
+  // registered rows whose frequent columns were split off: the sweeps walk the tail and start from the
+  // matrix-core pass over the hot block; the exact kernels keep the caller's full rows
+  const bool hot = have_xn && c->hot_on;
+  const int64_t *sw_indptr = hot ? c->tail_indptr : indptr;
+  const int32_t *sw_indices = hot ? c->tail_indices : indices;
+  const float *sw_values = hot ? c->tail_values : values;
+  const int64_t sw_nnz = hot ? c->tail_nnz : nnz;
   {
     StageTimer t(c, 1);
     SOM_LAUNCH(c, launch_transpose_codebook(c, W));
-    SOM_LAUNCH(c, launch_scale_values(c, indices, values, nnz));
-    SOM_LAUNCH(c, launch_bmu_csr_sliced(c, indptr, indices, c->vq, n, false));
+    if (hot) {
+      SOM_LAUNCH(c, launch_gather_hot_codebook(c, W));
+      SOM_LAUNCH(c, launch_split_rows_f16(c, c->hot_Wc, c->k, c->hot_wmax_bits, nullptr, c->hot_Wh, c->hot_wscale, kHot));
+      SOM_LAUNCH(c, launch_hot_partial(c, n));
+    }
+    SOM_LAUNCH(c, launch_scale_values(c, sw_indices, sw_values, sw_nnz));
+    SOM_LAUNCH(c, launch_bmu_csr_sliced(c, sw_indptr, sw_indices, c->vq, n, false, nullptr, hot));
   }
   StageTimer t(c, 2);
-  SOM_LAUNCH(c, launch_certify(c, n, 8 * c->csr_sweeps, kCertifyCsr, indptr, bmus));
+  SOM_LAUNCH(c, launch_certify(c, n, 8 * c->csr_sweeps, kCertifyCsr, sw_indptr, bmus, hot));
   SOM_LAUNCH(c, launch_refine_csr(c, indptr, indices, values, W, bmus));
-  SOM_LAUNCH(c, launch_bmu_csr_sliced(c, indptr, indices, c->vq, n, true));
+  SOM_LAUNCH(c, launch_bmu_csr_sliced(c, sw_indptr, sw_indices, c->vq, n, true, nullptr, hot));
   SOM_LAUNCH(c, launch_refine_lists_csr(c, indptr, indices, values, W, bmus));
   SOM_LAUNCH(c, launch_rescan_csr(c, indptr, indices, values, W, bmus));
   return SOM_OK;
@@ -350,6 +363,74 @@ static int registered_norms(som_ctx *c) {
   return SOM_OK;
 }
 
+namespace som { int64_t choose_hot_columns(const std::vector<int32_t> &counts, std::vector<int32_t> &cols); }
+
+static void free_hot(som_ctx *c) {
+  dev_free(c->tail_start); dev_free(c->tail_indptr); dev_free(c->tail_indices); dev_free(c->tail_values);
+  dev_free(c->hot_Xh); dev_free(c->hot_xscale); dev_free(c->hot_xn); dev_free(c->hot_P);
+  c->hot_n_cap = 0;
+  c->hot_nnz_cap = 0;
+}
+
+// Hot-column split of the registered sparse set (csr_hot.hip), examined once per registration: the column
+// histogram, the choice of the columns (on the host: it waits for the stream), the tail as a CSR set of its
+// own and the hot block as fp16 planes.  Leaves hot_on = 0 when the split is switched off, the columns are
+// too few or too evenly used, or the table of partial sums would not be worth its memory.
+static int registered_hot(som_ctx *c) {
+  if (c->hot_valid) return SOM_OK;
+  c->hot_valid = 1;
+  c->hot_on = 0;
+  const int64_t n = c->d_n, nnz = c->d_nnz;
+  const int64_t kP = ((int64_t)c->k + 127) / 128 * 128;
+  if (!c->hot_enabled || c->data_kind != 2 || c->dim < 4 * kHot || nnz < 1) return SOM_OK;
+  if (n * kP * 4 > (8ll << 30)) return SOM_OK;
+  if (!c->hot_counts) {
+    const size_t halves = (size_t)kHot * 2;
+    if (!(dev_alloc(&c->hot_counts, (size_t)c->dim) && dev_alloc(&c->hot_rank, (size_t)c->dim) &&
+          dev_alloc(&c->hot_cols, (size_t)kHot) && dev_alloc(&c->hot_Wc, (size_t)c->k * kHot) &&
+          dev_alloc(&c->hot_Wh, (size_t)c->k * halves) && dev_alloc(&c->hot_wscale, 1) &&
+          dev_alloc(&c->hot_wmax_bits, 1))) {
+      dev_free(c->hot_counts); dev_free(c->hot_rank); dev_free(c->hot_cols); dev_free(c->hot_Wc); dev_free(c->hot_Wh);
+      dev_free(c->hot_wscale); dev_free(c->hot_wmax_bits);
+      return fail(c, SOM_ERR_ALLOC, "cannot allocate the hot-column tables");
+    }
+  }
+  SOM_LAUNCH(c, launch_hot_histogram(c, c->d_indices, nnz, c->hot_counts));
+  std::vector<int32_t> counts((size_t)c->dim), cols, rank((size_t)c->dim, -1);
+  SOM_LAUNCH(c, hipMemcpyAsync(counts.data(), c->hot_counts, counts.size() * sizeof(int32_t), hipMemcpyDeviceToHost,
+                               c->stream));
+  SOM_LAUNCH(c, hipStreamSynchronize(c->stream));
+  const int64_t held = choose_hot_columns(counts, cols);
+  if ((int)cols.size() < kHot || (double)held < kHotMinShare * (double)nnz) return SOM_OK;
+  for (int h = 0; h < kHot; ++h) rank[(size_t)cols[h]] = h;
+  SOM_LAUNCH(c, hipMemcpyAsync(c->hot_rank, rank.data(), rank.size() * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+  SOM_LAUNCH(c, hipMemcpyAsync(c->hot_cols, cols.data(), cols.size() * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+  SOM_LAUNCH(c, hipStreamSynchronize(c->stream));          // the host vectors go out of scope
+  const int64_t tail_cap = nnz;                            // the counters may include out-of-range indices the kernels clamp
+  if (n > c->hot_n_cap || tail_cap > c->hot_nnz_cap) {
+    free_hot(c);
+    if (!(dev_alloc(&c->tail_start, (size_t)n + 1) && dev_alloc(&c->tail_indptr, (size_t)n + 1) &&
+          dev_alloc(&c->tail_indices, (size_t)tail_cap) && dev_alloc(&c->tail_values, (size_t)tail_cap) &&
+          dev_alloc(&c->hot_Xh, (size_t)n * kHot * 2) && dev_alloc(&c->hot_xscale, (size_t)n) &&
+          dev_alloc(&c->hot_xn, (size_t)n) && dev_alloc(&c->hot_P, (size_t)(n * kP)))) {
+      free_hot(c);
+      return fail(c, SOM_ERR_ALLOC, "cannot allocate the hot-column split of %lld rows", (long long)n);
+    }
+    c->hot_n_cap = n;
+    c->hot_nnz_cap = tail_cap;
+  }
+  SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->tail_start + n, 1));
+  SOM_LAUNCH(c, launch_tail_lengths(c, c->d_indptr, c->d_indices, n, c->tail_start));
+  SOM_LAUNCH(c, launch_scan_exclusive_i32(c, c->tail_start, c->tail_start, (int)(n + 1)));
+  SOM_LAUNCH(c, launch_split_hot_tail(c, c->d_indptr, c->d_indices, c->d_values, n));
+  int32_t total = 0;
+  SOM_LAUNCH(c, hipMemcpyAsync(&total, c->tail_start + n, sizeof(total), hipMemcpyDeviceToHost, c->stream));
+  SOM_LAUNCH(c, hipStreamSynchronize(c->stream));
+  c->tail_nnz = total;
+  c->hot_on = 1;
+  return SOM_OK;
+}
+
 static bool is_registered_dense(const som_ctx *c, const float *data, int64_t n) {
   return c->data_kind == 1 && data == c->d_data && n == c->d_n;
 }
@@ -385,6 +466,7 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
   csr_slice_geometry(c->k, &c->csr_acc, &c->csr_sweeps, &c->kpad);
   c->filter = SOM_FILTER_SPLIT_F16;
   c->scale_cooling = -1;
+  c->hot_enabled = 1;
   c->smooth_mfma_min = kSmoothMfmaMin;
 
   int dev = 0;
@@ -446,6 +528,9 @@ void som_destroy(som_ctx *c) {
   dev_free(c->GxT); dev_free(c->GyT); dev_free(c->hit_x); dev_free(c->hit_n); dev_free(c->hit_rows);
   dev_free(c->mu); dev_free(c->mu_partial); dev_free(c->Wc); dev_free(c->zero16); dev_free(c->mu_norm2);
   dev_free(c->Wh); dev_free(c->wscale);
+  free_hot(c);
+  dev_free(c->hot_counts); dev_free(c->hot_rank); dev_free(c->hot_cols); dev_free(c->hot_Wc); dev_free(c->hot_Wh);
+  dev_free(c->hot_wscale); dev_free(c->hot_wmax_bits);
   for (int s = 0; s < SOM_PROFILE_STAGES; ++s) {
     if (!c->prof_ev[s]) continue;
     for (int e = 0; e < 2 * kProfMax; ++e) (void)hipEventDestroy(c->prof_ev[s][e]);
@@ -474,7 +559,11 @@ int som_bmus_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, cons
   int rc = check_csr(c, indptr, indices, values, n, nnz);
   if (!rc) rc = ensure_rows(c, n, false);
   bool reg = false;
-  if (!rc && is_registered_csr(c, indptr, indices, values, n)) { rc = registered_norms(c); reg = true; }
+  if (!rc && is_registered_csr(c, indptr, indices, values, n)) {
+    rc = registered_norms(c);
+    if (!rc) rc = registered_hot(c);
+    reg = true;
+  }
   if (rc) return rc;
   return bmu_search_csr(c, indptr, indices, values, n, nnz, codebook, bmus, reg);
 }
@@ -566,7 +655,11 @@ int som_train_epoch_csr(som_ctx *c, const int64_t *indptr, const int32_t *indice
   if (!rc) rc = check_epoch_scalars(c, radius, scale);
   if (!rc) rc = ensure_rows(c, n, false);
   bool reg = false;
-  if (!rc && is_registered_csr(c, indptr, indices, values, n)) { rc = registered_norms(c); reg = true; }
+  if (!rc && is_registered_csr(c, indptr, indices, values, n)) {
+    rc = registered_norms(c);
+    if (!rc) rc = registered_hot(c);
+    reg = true;
+  }
   if (rc) return rc;
   SOM_LAUNCH(c, launch_epoch_params(c, 0, 1, radius, radius, scale, scale, SOM_COOL_LINEAR));
   rc = bmu_search_csr(c, indptr, indices, values, n, nnz, codebook, bmus, reg);
@@ -583,6 +676,8 @@ int som_set_data_dense(som_ctx *c, const float *data, int64_t n) {
   c->d_indptr = nullptr; c->d_indices = nullptr; c->d_values = nullptr;
   c->d_norms_valid = 0;
   c->d_split_valid = 0;
+  c->hot_valid = 0;
+  c->hot_on = 0;
   return SOM_OK;
 }
 
@@ -595,6 +690,8 @@ int som_set_data_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, 
   c->d_indptr = indptr; c->d_indices = indices; c->d_values = values;
   c->d_norms_valid = 0;
   c->d_split_valid = 0;
+  c->hot_valid = 0;
+  c->hot_on = 0;
   return SOM_OK;
 }
 
@@ -633,6 +730,7 @@ int som_train_snapshots(som_ctx *c, int n_epochs, float radius0, float radiusN, 
   int rc = ensure_rows(c, c->d_n, dense);
   if (rc) return rc;
   rc = registered_norms(c);
+  if (!rc && !dense) rc = registered_hot(c);
   if (rc) return rc;
   for (int e = 0; e < n_epochs; ++e) {
     SOM_LAUNCH(c, launch_epoch_params(c, e, n_epochs, radius0, radiusN, scale0, scaleN, cooling));
@@ -729,6 +827,16 @@ int som_validate_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, 
     default: return fail(c, SOM_ERR_INVALID_ARG, "CSR: column indices of a row are not strictly increasing");
   }
 }
+
+int som_set_sparse_hot_block(som_ctx *c, int enable) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  c->hot_enabled = enable ? 1 : 0;
+  c->hot_valid = 0;          // examined again at the next use of the registered set
+  c->hot_on = 0;
+  return SOM_OK;
+}
+
+int som_sparse_hot_block_active(const som_ctx *c) { return c && c->hot_valid && c->hot_on ? 1 : 0; }
 
 int som_set_smoothing(som_ctx *c, int form) {
   if (!c) return SOM_ERR_INVALID_ARG;

@@ -18,6 +18,8 @@ constexpr int kChunkRows = 32;            // instances summed by one block of th
 constexpr int kSortTile = 1024;           // fewest keys ranked by one wave of the radix scatter
 constexpr int kSmoothMatMax = 1024;        // largest map side for which the smoothing filters are stored as matrices
 constexpr int kSmoothMfmaMin = 32;         // shortest map line whose smoothing pass runs on the matrix cores by default
+constexpr int kHot = 256;                  // columns of the dense hot block of a registered sparse training set
+constexpr double kHotMinShare = 0.3;       // share of the nonzeros those columns must hold for the split to be used
 constexpr int kProfMax = 512;              // event brackets kept per stage between two reads
 #ifndef SOM_FLUSH_BLOCK
 #define SOM_FLUSH_BLOCK 32
@@ -122,6 +124,28 @@ struct som_ctx {
   float *partial;         // [n/kChunkRows + k][dim]
   int64_t max_chunks;
 
+  // hot-column split of the registered sparse training set (csr_hot.hip); built on first use
+  int hot_valid;          // 0: not examined yet; 1: examined (hot_on says whether the split is in use)
+  int hot_on;
+  int hot_enabled;        // som_set_sparse_hot_block
+  int64_t hot_n_cap, hot_nnz_cap;
+  int32_t *hot_counts;    // [dim] nonzeros per column
+  int32_t *hot_rank;      // [dim] position of a column in the hot block, or -1
+  int32_t *hot_cols;      // [kHot] the hot columns, ascending
+  int32_t *tail_start;    // [n+1] nonzeros of the rows outside the hot columns, then their exclusive scan
+  int64_t *tail_indptr;   // [n+1] the tail as a CSR set of its own
+  int32_t *tail_indices;  // [tail nonzeros]
+  float *tail_values;
+  int64_t tail_nnz;
+  _Float16 *hot_Xh;       // [n][kHot/32][64] hot part of the instances as fp16 hi/lo planes
+  float *hot_xscale;      // [n] their power-of-two scales
+  float *hot_xn;          // [n] |x_hot|^2
+  float *hot_Wc;          // [k][kHot] hot columns of the centred code book
+  _Float16 *hot_Wh;       // [k][kHot/32][64] the same as planes
+  float *hot_wscale;      // [1]
+  unsigned *hot_wmax_bits;    // [1]
+  float *hot_P;           // [ceil(k/128)][n][128] dot products of the hot parts divided by the instance scale
+
   // registered training set for som_train
   int data_kind;          // 0 none, 1 dense, 2 csr
   const float *d_data;
@@ -170,7 +194,8 @@ int bmu_dense_h_groups(const som_ctx *c, int64_t n);
 hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump);            // Xh, Wh -> candidates (or all scores)
 hipError_t launch_bmu_dense_h_collect(som_ctx *c, int64_t n);                 // rows of collect_rows -> collect_list
 hipError_t launch_split_rows_f16(som_ctx *c, const float *A, int64_t nrows, const unsigned *global_max_bits,
-                                 const float *mu /* subtracted first, or null */, _Float16 *out, float *scale_out);
+                                 const float *mu /* subtracted first, or null */, _Float16 *out, float *scale_out,
+                                 int dim = 0 /* row length; 0: the context's */);
 hipError_t launch_probe_mfma_f16(hipStream_t stream, const uint16_t *A, const uint16_t *B, const float *C, float *D,
                                  int count);
 
@@ -186,8 +211,10 @@ struct UnitWork {
 constexpr int kListCounts = 12;    // words in som_ctx::list_counts
 constexpr int kUnitCounts = 4;     // first of the eight work-list lengths in it
 enum { kCertifyFp32 = 0, kCertifySplit = 1, kCertifyCsr = 2 };      // whose rounding bound the margin uses
-hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int64_t *indptr, int32_t *bmus);
-hipError_t launch_margins(som_ctx *c, int64_t n, int mode, const int64_t *indptr, double *out);   // test hook: the margin per instance
+hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int64_t *indptr, int32_t *bmus,
+                          bool hot = false);
+hipError_t launch_margins(som_ctx *c, int64_t n, int mode, const int64_t *indptr, double *out,
+                          bool hot = false);   // test hook: the margin per instance
 hipError_t launch_refine_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
 hipError_t launch_refine_lists_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
 hipError_t launch_rescan_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
@@ -208,6 +235,15 @@ hipError_t launch_bmu_distances(som_ctx *c, const float *X, const int64_t *indpt
                                 const float *values, int64_t n, const float *W, const int32_t *bmus, float *dist,
                                 double *qerror);     // X != NULL: dense rows, else CSR
 
+// csr_hot.hip
+hipError_t launch_hot_histogram(som_ctx *c, const int32_t *indices, int64_t nnz, int32_t *counts);
+hipError_t launch_tail_lengths(som_ctx *c, const int64_t *indptr, const int32_t *indices, int64_t n, int32_t *len);
+hipError_t launch_split_hot_tail(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
+                                 int64_t n);
+hipError_t launch_gather_hot_codebook(som_ctx *c, const float *W);   // -> hot_Wc, hot_wmax_bits
+hipError_t launch_hot_partial(som_ctx *c, int64_t n);                // bmu_dense_h.hip: hot_Xh, hot_Wh -> hot_P
+hipError_t launch_scan_exclusive_i32(som_ctx *c, const int32_t *in, int32_t *out, int len);   // segsum.hip
+
 // dedup.hip
 hipError_t launch_mask_duplicate_rows(som_ctx *c, const float *W);   // wn32[i] = +inf for rows equal to a lower-indexed row
 
@@ -219,7 +255,8 @@ enum { kCsrBadSorted = 1, kCsrBadIndex = 2, kCsrBadOrder = 3, kCsrBadLast = 4, k
 hipError_t launch_validate_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, int64_t n, int64_t nnz,
                                int32_t *flag);
 hipError_t launch_bmu_csr_sliced(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
-                                 int64_t n, bool collect, float *dump = nullptr);   // dump: test hook, all scores [n][k]
+                                 int64_t n, bool collect, float *dump = nullptr,   // dump: test hook, all scores [n][k]
+                                 bool hot = false);   // the rows are the tail of the registered set: sums start from hot_P
 
 // segsum.hip
 hipError_t launch_sort_by_bmu(som_ctx *c, const int32_t *bmus, int64_t n);   // -> sort_val[0] = row ids

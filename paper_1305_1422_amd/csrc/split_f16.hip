@@ -80,17 +80,18 @@ __global__ __launch_bounds__(256) void k_split_rows_f16(const float *__restrict_
 }
 
 hipError_t launch_split_rows_f16(som_ctx *c, const float *A, int64_t nrows, const unsigned *global_max_bits,
-                                 const float *mu, _Float16 *out, float *scale_out) {
-  const int nK = (c->dim + 31) / 32;
+                                 const float *mu, _Float16 *out, float *scale_out, int dim) {
+  if (dim <= 0) dim = c->dim;
+  const int nK = (dim + 31) / 32;
   const int64_t cap = (int64_t)c->n_cu * 16;
-  if (c->dim <= 2048) {
+  if (dim <= 2048) {
     int64_t blocks = (nrows + 3) / 4;
     if (blocks > cap) blocks = cap;
-    hipLaunchKernelGGL(k_split_rows_f16<64>, dim3((unsigned)blocks), dim3(256), 0, c->stream, A, nrows, c->dim, nK,
+    hipLaunchKernelGGL(k_split_rows_f16<64>, dim3((unsigned)blocks), dim3(256), 0, c->stream, A, nrows, dim, nK,
                        global_max_bits, mu, out, scale_out);
   } else {
     int64_t blocks = nrows < cap ? nrows : cap;
-    hipLaunchKernelGGL(k_split_rows_f16<256>, dim3((unsigned)blocks), dim3(256), 0, c->stream, A, nrows, c->dim, nK,
+    hipLaunchKernelGGL(k_split_rows_f16<256>, dim3((unsigned)blocks), dim3(256), 0, c->stream, A, nrows, dim, nK,
                        global_max_bits, mu, out, scale_out);
   }
   return hipGetLastError();

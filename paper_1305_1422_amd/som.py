@@ -67,6 +67,10 @@ class Som:
         """Debug pass: raises capi.SomError if the CSR triple (indptr, indices, values) is malformed."""
         capi.som_validate_csr(self.ctx, csr[0], csr[1], csr[2])
 
+    def set_sparse_hot_block(self, enable: bool) -> None:
+        """Allow (default) or forbid the dense block of frequent columns of a registered sparse set."""
+        capi.som_set_sparse_hot_block(self.ctx, enable)
+
     def set_smoothing(self, form: str) -> None:
         """Units that run the Gaussian smoothing passes: "auto" (default), "vector" or "matrix"; same results."""
         capi.som_set_smoothing(self.ctx, {"auto": capi.SOM_SMOOTH_AUTO, "vector": capi.SOM_SMOOTH_VECTOR,

@@ -319,3 +319,63 @@ def test_validate_csr_names_every_kind_of_violation():
     # all rows empty, and a row that ends the array, are well formed
     som.validate_csr(P.csr_to_dev((np.zeros(n + 1, np.int64), indices[:0], values[:0])))
     som.close()
+
+
+@pytest.mark.parametrize("n,dim,rows,cols,mean_len", [(3000, 4000, 12, 10, 60.0), (700, 1500, 24, 22, 25.0)])
+def test_hot_column_block_of_a_registered_set(oracle, n, dim, rows, cols, mean_len):
+    """A registered sparse set with skewed column frequencies: its 256 most frequent columns go through the
+    matrix cores, the rest through the gather sweep.  BMUs are the exact argmin either way, so they must be
+    the same with the split on and off, epoch by epoch, and match the oracle; instances 0 / 1 have no nonzero
+    at all / none outside the frequent columns."""
+    from paper_1305_1422_amd import Som, capi
+    indptr, indices, values = sparse_zipf_csr(n, dim, 71, mean_len=mean_len, max_len=int(4 * mean_len))
+    freq = np.bincount(indices, minlength=dim)
+    hot = np.sort(np.argsort(-freq, kind="stable")[:256])
+    keep = np.ones(indices.size, bool)
+    keep[indptr[0]:indptr[1]] = False                                             # row 0: empty
+    keep[indptr[1]:indptr[2]] = np.isin(indices[indptr[1]:indptr[2]], hot)        # row 1: frequent columns only
+    lens = np.add.reduceat(keep, indptr[:-1]) * (np.diff(indptr) > 0)
+    indptr2 = np.zeros(n + 1, np.int64)
+    np.cumsum(lens, out=indptr2[1:])
+    csr = (indptr2, indices[keep], values[keep])
+    assert indptr2[1] == 0 and indptr2[2] > indptr2[1]
+    csr_d = P.csr_to_dev(csr)
+    W0 = (np.random.default_rng(72).random((rows * cols, dim)) * 0.1).astype(np.float32)
+    out = {}
+    for on in (True, False):
+        som = Som(rows, cols, dim, "toroid", "square", codebook=torch.from_numpy(W0))
+        som.set_sparse_hot_block(on)
+        capi.som_set_data_csr(som.ctx, *csr_d)
+        seq = []
+        for radius in (4.0, 2.0, 1.0):
+            W_in = som.codebook.cpu().numpy().copy()
+            b = som.train_epoch(csr_d, radius).cpu().numpy()
+            assert capi.som_sparse_hot_block_active(som.ctx) == on
+            P.check_bmus_csr(oracle, csr, dim, W_in, b)
+            seq.append(b)
+        b = som.bmus(csr_d).cpu().numpy()                      # search only, on the final map
+        P.check_bmus_csr(oracle, csr, dim, som.codebook.cpu().numpy(), b)
+        seq.append(b)
+        out[on] = seq
+        som.close()
+    assert np.array_equal(out[True][0], out[False][0])         # same input code book: same BMUs, bit for bit
+
+
+def test_hot_column_block_is_declined_for_evenly_used_columns(oracle):
+    from paper_1305_1422_amd import Som, capi
+    rng = np.random.default_rng(73)
+    n, dim, rows, cols = 400, 2048, 6, 7
+    lens = rng.integers(5, 40, n)
+    indptr = np.zeros(n + 1, np.int64)
+    np.cumsum(lens, out=indptr[1:])
+    indices = np.concatenate([np.sort(rng.choice(dim, size=int(l), replace=False)) for l in lens]).astype(np.int32)
+    values = rng.random(indices.size).astype(np.float32)
+    csr = (indptr, indices, values)
+    W = rng.random((rows * cols, dim)).astype(np.float32)
+    som = Som(rows, cols, dim, codebook=torch.from_numpy(W))
+    csr_d = P.csr_to_dev(csr)
+    capi.som_set_data_csr(som.ctx, *csr_d)
+    b = som.bmus(csr_d).cpu().numpy()
+    assert not capi.som_sparse_hot_block_active(som.ctx)       # 256 of 2,048 evenly used columns hold an eighth
+    P.check_bmus_csr(oracle, csr, dim, W, b)
+    som.close()
