@@ -52,31 +52,121 @@ void csr_slice_geometry(int k, int *acc, int *sweeps, int *kpad) {
   *kpad = 64 * kCsrSlices * a * ns;
 }
 
-// ---------------------------------------------------------------- transpose with centring
-// Entries as int16 multiples of the column's quantisation step, q = round((w - mu_c) / step_c),
-// |q| <= 32767 by the choice of the step; nodes past k are zeros.
-__global__ __launch_bounds__(256) void k_transpose_centered_q16(const float *__restrict__ W,
-                                                                const float *__restrict__ mu,
-                                                                const float *__restrict__ qstep, int k, int dim,
-                                                                int kpad, int16_t *__restrict__ Wt) {
-  __shared__ float tile[32][33];
-  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;       // 32 x 8
-  const unsigned col_tiles = (unsigned)(dim + 31) / 32;         // one-dimensional grid: column tile fastest
-  const int c0 = (int)(blockIdx.x % col_tiles) * 32, i0 = (int)(blockIdx.x / col_tiles) * 32;
-  for (int r = ty; r < 32; r += 8) {
-    const int i = i0 + r, c = c0 + tx;
-    float q = 0.f;
-    if (i < k && c < dim) {
-      q = rintf((W[(int64_t)i * dim + c] - mu[c]) / qstep[c]);
-      q = fminf(fmaxf(q, -32767.f), 32767.f);
+// ---------------------------------------------------------------- centring, node constants and transpose in one pass
+// One pass over the code book does what the sparse search needs of it every epoch: w' = fl(w - mu), the
+// node constants c_i = |w'_i|^2 + 2 mu.w'_i and |w_i|^2 (fp64 sums in a fixed order: the exact stage
+// relies on bit-identical rows having bit-identical norms), the largest |w'_i|^2, and the transposed
+// 16-bit code book: entries q = round(w' / step_c) as int16, |q| <= 32767 by the choice of the step; nodes
+// past k are zeros.  A workgroup owns 64 nodes and a slab of the columns, which it walks in tiles of 64:
+// a thread reads four nodes x four columns per tile (16-byte loads along the rows), the quantised tile
+// turns in LDS, and every column leaves as 128 contiguous bytes.  The row sums of a slab go to
+// `partial` [slab][node][3]; k_finish_node_constants adds the slabs in order.
+constexpr int kCtNodes = 64;
+constexpr int kCtCols = 64;
+
+__global__ __launch_bounds__(256) void k_center_transpose_q16(const float *__restrict__ W, const float *__restrict__ mu,
+                                                              const float *__restrict__ qstep, int k, int dim,
+                                                              int kpad, int cols_per_slab, int16_t *__restrict__ Wt,
+                                                              double *__restrict__ partial) {
+  __shared__ int16_t tile[kCtNodes][kCtCols + 2];
+  const int tid = threadIdx.x;
+  const int q4 = tid & 15;                      // column quad within the tile
+  const int r0 = tid >> 4;                      // first of this thread's four rows (r0 + 16 j)
+  const int i0 = blockIdx.x * kCtNodes;
+  const int slab = blockIdx.y;
+  const int c_begin = slab * cols_per_slab;
+  const int c_end = min(dim, c_begin + cols_per_slab);
+  const bool vec = (dim & 3) == 0 && (reinterpret_cast<uintptr_t>(W) & 15) == 0;
+  double s2[4] = {0, 0, 0, 0}, sm[4] = {0, 0, 0, 0}, sw[4] = {0, 0, 0, 0};
+  for (int c0 = c_begin; c0 < c_end; c0 += kCtCols) {
+    const int c = c0 + 4 * q4;
+    float m[4], st[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const bool on = c + e < c_end;
+      m[e] = on ? mu[c + e] : 0.f;
+      st[e] = on ? qstep[c + e] : 1.f;
     }
-    tile[r][tx] = q;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int r = r0 + 16 * j;
+      const int i = i0 + r;
+      float x[4] = {0.f, 0.f, 0.f, 0.f};
+      if (i < k) {
+        const float *row = W + (int64_t)i * dim;
+        if (vec && c + 3 < c_end) {
+          const float4 v = *reinterpret_cast<const float4 *>(row + c);
+          x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) x[e] = c + e < c_end ? row[c + e] : m[e];      // past the slab: w' = 0
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = m[e];                                       // past the map: w' = 0
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float t = x[e] - m[e];
+        if (i < k && c + e < c_end) {
+          s2[j] += (double)t * (double)t;
+          sm[j] += (double)m[e] * (double)t;
+          sw[j] += (double)x[e] * (double)x[e];
+        }
+        float q = rintf(t / st[e]);
+        q = fminf(fmaxf(q, -32767.f), 32767.f);
+        tile[r][4 * q4 + e] = (int16_t)q;
+      }
+    }
+    __syncthreads();
+    {   // column tid / 4 of the tile, nodes 16 (tid % 4) .. + 15: 32 contiguous bytes of one row of Wt
+      const int col = tid >> 2, g = tid & 3;
+      if (c0 + col < c_end && i0 + 16 * g < kpad) {
+        __attribute__((aligned(16))) int16_t out[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) out[e] = tile[16 * g + e][col];
+        int16_t *dst = Wt + (int64_t)(c0 + col) * kpad + i0 + 16 * g;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) *reinterpret_cast<uint4 *>(dst + 8 * h) = *reinterpret_cast<const uint4 *>(out + 8 * h);
+      }
+    }
+    __syncthreads();
   }
-  __syncthreads();
-  for (int r = ty; r < 32; r += 8) {
-    const int c = c0 + r, i = i0 + tx;
-    if (c < dim && i < kpad) Wt[(int64_t)c * kpad + i] = (int16_t)tile[tx][r];
+  // the four rows' sums over this slab: the 16 threads of a row sit in consecutive lanes
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) {
+      s2[j] += __shfl_xor(s2[j], o, 64);
+      sm[j] += __shfl_xor(sm[j], o, 64);
+      sw[j] += __shfl_xor(sw[j], o, 64);
+    }
+    const int i = i0 + r0 + 16 * j;
+    if (q4 == 0 && i < k) {
+      double *dst = partial + ((int64_t)slab * k + i) * 3;
+      dst[0] = s2[j]; dst[1] = sm[j]; dst[2] = sw[j];
+    }
   }
+}
+
+__global__ __launch_bounds__(256) void k_finish_node_constants(const double *__restrict__ partial, int slabs, int k,
+                                                               float *__restrict__ cn, double *__restrict__ wn64,
+                                                               unsigned *__restrict__ max_bits) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  float vmax = 0.f;
+  if (i < k) {
+    double s2 = 0.0, sm = 0.0, sw = 0.0;
+    for (int s = 0; s < slabs; ++s) {
+      const double *p = partial + ((int64_t)s * k + i) * 3;
+      s2 += p[0]; sm += p[1]; sw += p[2];
+    }
+    cn[i] = (float)(s2 + 2.0 * sm);
+    wn64[i] = sw;
+    vmax = (float)s2;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) vmax = fmaxf(vmax, __shfl_xor(vmax, o, 64));
+  if ((threadIdx.x & 63) == 0 && vmax > 0.f) atomicMax(max_bits, __float_as_uint(vmax));
 }
 
 __device__ __forceinline__ void wave_argmin(float &v, int &i) {
@@ -350,10 +440,24 @@ hipError_t launch_bmu_csr_sliced(som_ctx *c, const int64_t *indptr, const int32_
   return hipGetLastError();
 }
 
-hipError_t launch_transpose_codebook(som_ctx *c, const float *W) {
-  const dim3 grid((unsigned)(((int64_t)(c->dim + 31) / 32) * ((c->kpad + 31) / 32)));
-  hipLaunchKernelGGL(k_transpose_centered_q16, grid, dim3(256), 0, c->stream, W, c->mu, c->qstep, c->k, c->dim,
-                     c->kpad, reinterpret_cast<int16_t *>(c->Wt));
+// Centred transposed 16-bit code book, node constants (wn32 = c_i), |w_i|^2 (wn64) and the largest |w'_i|^2
+// (wmax_bits), from mu and qstep: one pass over W.
+hipError_t launch_center_transpose_codebook(som_ctx *c, const float *W) {
+  hipError_t e = launch_fill_zero_u32(c->stream, c->wmax_bits, 2);
+  if (e != hipSuccess) return e;
+  const int tiles = c->kpad / kCtNodes;                       // kpad is a multiple of 512
+  int slabs = (2 * c->n_cu + tiles - 1) / tiles;              // enough workgroups for two per CU
+  const int max_slabs = (c->dim + kCtCols - 1) / kCtCols;
+  if (slabs > max_slabs) slabs = max_slabs;
+  if (slabs > kCtMaxSlabs) slabs = kCtMaxSlabs;
+  if (slabs < 1) slabs = 1;
+  int cols_per_slab = (c->dim + slabs - 1) / slabs;
+  cols_per_slab = (cols_per_slab + kCtCols - 1) / kCtCols * kCtCols;
+  slabs = (c->dim + cols_per_slab - 1) / cols_per_slab;
+  hipLaunchKernelGGL(k_center_transpose_q16, dim3((unsigned)tiles, (unsigned)slabs), dim3(256), 0, c->stream, W, c->mu,
+                     c->qstep, c->k, c->dim, c->kpad, cols_per_slab, reinterpret_cast<int16_t *>(c->Wt), c->ct_partial);
+  hipLaunchKernelGGL(k_finish_node_constants, dim3((c->k + 255) / 256), dim3(256), 0, c->stream, c->ct_partial, slabs,
+                     c->k, c->wn32, c->wn64, c->wmax_bits);
   return hipGetLastError();
 }
 

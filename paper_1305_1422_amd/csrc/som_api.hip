@@ -176,8 +176,9 @@ static int ensure_transposed(som_ctx *c) {
   if (c->Wt) return SOM_OK;
   const size_t words = ((size_t)c->dim * c->kpad + 1) / 2;      // int16 entries
   if (!(dev_alloc(&c->Wt, words) && dev_alloc(&c->col_range, (size_t)2 * 64 * c->dim) &&
-        dev_alloc(&c->qstep, (size_t)c->dim) && dev_alloc(&c->qstep_max_bits, 1))) {
-    dev_free(c->Wt); dev_free(c->col_range); dev_free(c->qstep); dev_free(c->qstep_max_bits);
+        dev_alloc(&c->qstep, (size_t)c->dim) && dev_alloc(&c->qstep_max_bits, 1) &&
+        dev_alloc(&c->ct_partial, (size_t)kCtMaxSlabs * c->k * 3))) {
+    dev_free(c->Wt); dev_free(c->col_range); dev_free(c->qstep); dev_free(c->qstep_max_bits); dev_free(c->ct_partial);
     return fail(c, SOM_ERR_ALLOC, "cannot allocate the transposed code book (%d x %d)", c->dim, c->kpad);
   }
   SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->Wt, (int64_t)words));
@@ -288,9 +289,15 @@ static int prepare_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices
   if (c->data_kind == 1) { c->d_norms_valid = 0; c->d_split_valid = 0; }
   SOM_LAUNCH(c, launch_codebook_means_and_steps(c, W));
   SOM_LAUNCH(c, launch_vec_sqnorm(c, c->mu, c->dim, c->mu_norm2));
-  SOM_LAUNCH(c, launch_center_codebook(c, W, false, true, false));
-  if (c->nb_function == SOM_NEIGHBORHOOD_BUBBLE) SOM_LAUNCH(c, launch_mask_duplicate_rows(c, W));
   SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, kListCounts));
+  return SOM_OK;
+}
+
+// First part of the sparse filter pass: the code book read once - centred, quantised, transposed, its node
+// constants and norms taken on the way - and, under a bubble neighbourhood, its duplicate rows masked.
+static int codebook_for_sweep(som_ctx *c, const float *W) {
+  SOM_LAUNCH(c, launch_center_transpose_codebook(c, W));
+  if (c->nb_function == SOM_NEIGHBORHOOD_BUBBLE) SOM_LAUNCH(c, launch_mask_duplicate_rows(c, W));
   return SOM_OK;
 }
 
@@ -307,7 +314,8 @@ static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indi
   const int64_t sw_nnz = hot ? c->tail_nnz : nnz;
   {
     StageTimer t(c, 1);
-    SOM_LAUNCH(c, launch_transpose_codebook(c, W));
+    rc = codebook_for_sweep(c, W);
+    if (rc) return rc;
     if (hot) {
       SOM_LAUNCH(c, launch_gather_hot_codebook(c, W));
       SOM_LAUNCH(c, launch_split_rows_f16(c, c->hot_Wc, c->k, c->hot_wmax_bits, nullptr, c->hot_Wh, c->hot_wscale, kHot));
@@ -524,7 +532,7 @@ void som_destroy(som_ctx *c) {
   dev_free(c->chunk_off); dev_free(c->massD); dev_free(c->dist_partial); dev_free(c->row_hash); dev_free(c->dedup_keys);
   dev_free(c->dedup_lowest); dev_free(c->cntT); dev_free(c->gx); dev_free(c->gy);
   dev_free(c->params); dev_free(c->list_counts); dev_free(c->unit_work); dev_free(c->vq); dev_free(c->S); dev_free(c->T); dev_free(c->Wt);
-  dev_free(c->col_range); dev_free(c->qstep); dev_free(c->qstep_max_bits); dev_free(c->H2);
+  dev_free(c->col_range); dev_free(c->qstep); dev_free(c->qstep_max_bits); dev_free(c->ct_partial); dev_free(c->H2);
   dev_free(c->GxT); dev_free(c->GyT); dev_free(c->hit_x); dev_free(c->hit_n); dev_free(c->hit_rows);
   dev_free(c->mu); dev_free(c->mu_partial); dev_free(c->Wc); dev_free(c->zero16); dev_free(c->mu_norm2);
   dev_free(c->Wh); dev_free(c->wscale);
@@ -883,7 +891,8 @@ int som_debug_scores_csr(som_ctx *c, const int64_t *indptr, const int32_t *indic
   if (!rc) rc = ensure_rows(c, n, false);
   if (!rc) rc = prepare_csr(c, indptr, indices, values, n, nnz, codebook, false);
   if (rc) return rc;
-  SOM_LAUNCH(c, launch_transpose_codebook(c, codebook));
+  rc = codebook_for_sweep(c, codebook);
+  if (rc) return rc;
   SOM_LAUNCH(c, launch_scale_values(c, indices, values, nnz));
   SOM_LAUNCH(c, launch_bmu_csr_sliced(c, indptr, indices, c->vq, n, false, scores));
   SOM_LAUNCH(c, launch_margins(c, n, kCertifyCsr, indptr, margin_out));

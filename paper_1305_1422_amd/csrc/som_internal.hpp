@@ -84,6 +84,7 @@ struct som_ctx {
   int csr_acc, csr_sweeps;    // sparse BMU kernel: scores per lane and sweep, sweeps per node slice
   float *col_range;       // [2][64][dim] slab minima and maxima of the code-book columns (with Wt)
   float *qstep;           // [dim] quantisation step of every column of Wt (with Wt)
+  double *ct_partial;     // [kCtMaxSlabs][k][3] row sums per column slab of the fused centring / transpose pass (with Wt)
   unsigned *qstep_max_bits;   // [1] bit pattern of the largest step
   float *Wc;              // [k][dim] centred code book w' = fl(w - mu) of the dense BMU search (lazily allocated)
   _Float16 *Wh;           // [k][ceil(dim/32)][64] centred code book as fp16 hi/lo planes (lazily allocated)
@@ -248,7 +249,8 @@ hipError_t launch_scan_exclusive_i32(som_ctx *c, const int32_t *in, int32_t *out
 hipError_t launch_mask_duplicate_rows(som_ctx *c, const float *W);   // wn32[i] = +inf for rows equal to a lower-indexed row
 
 // bmu_csr.hip
-hipError_t launch_transpose_codebook(som_ctx *c, const float *W);
+constexpr int kCtMaxSlabs = 16;            // column slabs of the fused centring / transpose pass
+hipError_t launch_center_transpose_codebook(som_ctx *c, const float *W);   // mu, qstep -> Wt, wn32, wn64, wmax_bits
 void csr_slice_geometry(int k, int *acc, int *sweeps, int *kpad);
 hipError_t launch_scale_values(som_ctx *c, const int32_t *indices, const float *values, int64_t nnz);   // -> vq
 enum { kCsrBadSorted = 1, kCsrBadIndex = 2, kCsrBadOrder = 3, kCsrBadLast = 4, kCsrBadFirst = 5 };   // k_validate_csr: the largest is reported
