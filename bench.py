@@ -73,6 +73,10 @@ def main() -> int:
                     help="neighbourhood of the update (the stated configurations use the plain Gaussian)")
     ap.add_argument("--smoothing", choices=["auto", "vector", "matrix"], default="auto",
                     help="units that run the Gaussian smoothing passes (same results)")
+    ap.add_argument("--mode", choices=["epoch", "map"], default="epoch",
+                    help="epoch (default): a step is one training epoch of the schedule.  map: the schedule is "
+                         "trained once, untimed, and a step is one BMU search (som_bmus_*) of the whole data set "
+                         "against that trained map - the post-training mapping, a slow corner of the exact stage")
     ap.add_argument("--no-hot-block", action="store_true",
                     help="sparse workloads: keep all columns in the gather sweep (no dense block of frequent columns)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -126,7 +130,14 @@ def main() -> int:
         capi.som_set_data_csr(som.ctx, *Xd)
     radii = [w.radius0 + (w.radiusN - w.radius0) * e / max(1, w.epochs - 1) for e in range(w.epochs)]
 
+    if args.mode == "map":
+        for e in range(w.epochs):
+            som.train_epoch(Xd, radii[e], 1.0, bmus)
+
     def step(s: int):
+        if args.mode == "map":
+            som.bmus(Xd, bmus)
+            return
         e = s % w.epochs
         if e == 0:
             som.codebook.copy_(W0d)
@@ -213,7 +224,10 @@ def main() -> int:
         "config": {"workload": f"config {w.config}: {w.name}", "kind": w.kind, "n": w.n, "dim": w.dim,
                    "map": f"{w.rows}x{w.cols} {w.map_type} {w.grid_type}",
                    "schedule": f"radius {w.radius0:g}->{w.radiusN:g} linear over {w.epochs} epochs, step s = epoch s mod {w.epochs}",
-                   "step": ("som_train_epoch on the registered data set: BMU search + batch update, everything that "
+                   "mode": args.mode,
+                   "step": ("som_bmus on the registered data set against the map the schedule has trained: BMU search alone"
+                            if args.mode == "map" else
+                            "som_train_epoch on the registered data set: BMU search + batch update, everything that "
                             "depends on the code book included; outside the step, once per registered data set: "
                             + ("squared norms of the instances, their fp16 hi/lo planes, sampled column means"
                                if w.kind == "dense" else "squared norms of the instances")),

@@ -170,6 +170,27 @@ __device__ __forceinline__ double sqdist_dense_wave(const float *__restrict__ x,
   return wave_sum(s);
 }
 
+// Four such distances at once, each with the summation order of sqdist_dense_wave (same bits).
+__device__ __forceinline__ void sqdist_dense_wave4(const float *__restrict__ x, const float *__restrict__ W,
+                                                   const int (&id)[4], int dim, int lane, double (&out)[4]) {
+  const float *w0 = W + (int64_t)id[0] * dim, *w1 = W + (int64_t)id[1] * dim;
+  const float *w2 = W + (int64_t)id[2] * dim, *w3 = W + (int64_t)id[3] * dim;
+  double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+  for (int c = lane; c < dim; c += kWave) {
+    const double xv = (double)x[c];
+    const double d0 = xv - (double)w0[c], d1 = xv - (double)w1[c];
+    const double d2 = xv - (double)w2[c], d3 = xv - (double)w3[c];
+    s0 += d0 * d0;
+    s1 += d1 * d1;
+    s2 += d2 * d2;
+    s3 += d3 * d3;
+  }
+  out[0] = wave_sum(s0);
+  out[1] = wave_sum(s1);
+  out[2] = wave_sum(s2);
+  out[3] = wave_sum(s3);
+}
+
 // The same distance for a sparse row with implicit zeros, regrouped so that only the nonzeros are
 // visited: |w|^2 + sum_nz ((v - w_c)^2 - w_c^2).  Equal to the plain sum in exact arithmetic; in fp64
 // its absolute error is about (dim + len) 2^-53 (|w|^2 + |x|^2), which is harmless unless the
@@ -275,8 +296,22 @@ __global__ __launch_bounds__(256) void k_refine_lists_dense(const float *__restr
     const int32_t *lst = collect_list + (int64_t)e * kListCap;
     double best = INFINITY;
     int arg = 0x7fffffff;
-    for (int t = 0; t < cn; ++t) {
-      const int i = min(max(lst[t], 0), k - 1);        // lists only ever hold valid nodes; never trust memory
+    // four listed nodes at a time: their rows stream together and the instance is read once for the four
+    // (a list can be long, and one distance at a time left the kernel waiting on its own loads); every
+    // distance is still summed in the order of sqdist_dense_wave
+    int t = 0;
+    for (; t + 4 <= cn; t += 4) {
+      int id[4];
+      double d2[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) id[u] = min(max(lst[t + u], 0), k - 1);   // lists only ever hold valid nodes; never trust memory
+      sqdist_dense_wave4(X + j * dim, W, id, dim, lane, d2);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (d2[u] < best || (d2[u] == best && id[u] < arg)) { best = d2[u]; arg = id[u]; }
+    }
+    for (; t < cn; ++t) {
+      const int i = min(max(lst[t], 0), k - 1);
       const double d2 = sqdist_dense_wave(X + j * dim, W + (int64_t)i * dim, dim, lane);
       if (d2 < best || (d2 == best && i < arg)) { best = d2; arg = i; }
     }
