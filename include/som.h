@@ -353,6 +353,15 @@ int som_debug_mfma_f16(const uint16_t *a, const uint16_t *b, const float *c_in, 
                        void *hip_stream);
 
 /*
+ * som_debug_xcc_ids - test hook (not an operation of the paper): launches n_blocks one-wavefront
+ * workgroups and writes the id of the XCD (accelerator complex) each of them ran on to out[0..n_blocks)
+ * (device pointer).  The dense filter and the sparse sweep put workgroups that share operands 8 apart
+ * in a launch, expecting consecutive workgroups to be dealt round-robin to the eight XCDs so that those
+ * land on one L2; only speed depends on it, and a test checks it through this call.
+ */
+int som_debug_xcc_ids(int32_t *out, int n_blocks, void *hip_stream);
+
+/*
  * som_get_stats - counters of the most recent BMU search on ctx (synchronises the stream).
  *   rows_refined   instances whose fp32 scores left two to four candidate nodes, decided by
  *                  the exact fp64 distances of those candidates;

@@ -31,7 +31,7 @@ EXPORTS = [
     "som_bmu_distances_dense", "som_bmu_distances_csr", "som_bmu_distances_dense_static",
     "som_cool_schedule", "som_umatrix", "som_get_stats",
     "som_profile_enable", "som_profile_read",
-    "som_set_filter", "som_set_smoothing", "som_set_sparse_hot_block", "som_sparse_hot_block_active", "som_set_neighborhood", "som_set_scale_cooling", "som_validate_csr", "som_debug_scores_dense", "som_debug_scores_csr", "som_debug_mfma_f16",
+    "som_set_filter", "som_set_smoothing", "som_set_sparse_hot_block", "som_sparse_hot_block_active", "som_set_neighborhood", "som_set_scale_cooling", "som_validate_csr", "som_debug_scores_dense", "som_debug_scores_csr", "som_debug_mfma_f16", "som_debug_xcc_ids",
 ]
 PROFILE_STAGES = ("bmu_dense_filter", "bmu_csr_filter", "bmu_exact", "node_sums", "smooth_divide", "prepare_dense")
 
@@ -114,6 +114,8 @@ def load():
     L.som_debug_scores_dense.argtypes = [vp, vp, i64, vp, vp, vp, vp]
     L.som_debug_scores_csr.restype = i32
     L.som_debug_scores_csr.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp, vp, vp]
+    L.som_debug_xcc_ids.restype = i32
+    L.som_debug_xcc_ids.argtypes = [vp, i32, vp]
     L.som_debug_mfma_f16.restype = i32
     L.som_debug_mfma_f16.argtypes = [vp, vp, vp, vp, i32, vp]
     _lib = L
@@ -364,6 +366,14 @@ def som_debug_scores_csr(ctx, indptr, indices, values, codebook, scores, mu_out,
                                             _ptr(scores, torch.float32, "scores"),
                                             _ptr(mu_out, torch.float32, "mu_out"),
                                             _ptr(margin_out, torch.float64, "margin_out")))
+
+
+def som_debug_xcc_ids(out) -> None:
+    """Test hook: out[b] = id of the XCD that workgroup b of a launch of out.numel() workgroups ran on."""
+    import torch
+    rc = load().som_debug_xcc_ids(_ptr(out, torch.int32, "out"), out.numel(), C.c_void_p(0))
+    if rc != SOM_OK:
+        raise SomError(rc, "som_debug_xcc_ids")
 
 
 def som_debug_mfma_f16(a, b, c_in, d_out) -> None:

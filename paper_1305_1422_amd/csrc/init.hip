@@ -27,4 +27,22 @@ hipError_t launch_fill_uniform(som_ctx *c, float *W, int64_t count, uint64_t see
   return hipGetLastError();
 }
 
+// Which XCD (accelerator complex, each with an L2 of its own) every workgroup of a one-dimensional launch
+// runs on.  The dense filter and the sparse sweep place the workgroups that share data 8 apart on the
+// assumption that the dispatcher deals consecutive workgroups round-robin to the eight XCDs; that is a
+// property of the hardware scheduler, not of the programming model, so a test reads it back.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__global__ __launch_bounds__(64) void k_probe_xcc(int32_t *__restrict__ out) {
+  unsigned id;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(id));
+  if (threadIdx.x == 0) out[blockIdx.x] = (int32_t)(id & 0xf);
+}
+#pragma clang diagnostic pop
+
+hipError_t launch_probe_xcc(hipStream_t stream, int32_t *out, int n_blocks) {
+  hipLaunchKernelGGL(k_probe_xcc, dim3((unsigned)n_blocks), dim3(64), 0, stream, out);
+  return hipGetLastError();
+}
+
 }  // namespace som

@@ -907,6 +907,11 @@ int som_debug_mfma_f16(const uint16_t *a, const uint16_t *b, const float *c_in, 
                                                                                                 : SOM_ERR_DEVICE;
 }
 
+int som_debug_xcc_ids(int32_t *out, int n_blocks, void *hip_stream) {
+  if (!out || n_blocks < 1 || n_blocks > (1 << 20)) return SOM_ERR_INVALID_ARG;
+  return launch_probe_xcc((hipStream_t)hip_stream, out, n_blocks) == hipSuccess ? SOM_OK : SOM_ERR_DEVICE;
+}
+
 int som_get_stats(som_ctx *c, int64_t *out) {
   if (!c) return SOM_ERR_INVALID_ARG;
   if (!out) return fail(c, SOM_ERR_INVALID_ARG, "out is NULL");

@@ -279,6 +279,7 @@ hipError_t launch_umatrix(som_ctx *c, const float *W, float *U);
 // init.hip
 hipError_t launch_fill_uniform(som_ctx *c, float *W, int64_t count, uint64_t seed);
 hipError_t launch_fill_zero_u32(hipStream_t s, void *p, int64_t count_u32);
+hipError_t launch_probe_xcc(hipStream_t stream, int32_t *out, int n_blocks);
 
 // ---------------------------------------------------------------- device helpers
 __device__ __forceinline__ double wave_sum(double v) {

@@ -263,3 +263,16 @@ def test_sparse_sweep_scores_stay_within_the_margin(case):
         worst = max(worst, float(err.max() / (margin[j] / 2.125)))
     print(f"{case}: worst error / bound = {worst:.4f}")
     assert worst > 1e-4                                            # the comparison is not vacuous
+
+
+def test_consecutive_workgroups_go_round_the_eight_xcds():
+    """What the launch geometry of the dense filter and of the sparse sweep assumes of the dispatcher (it affects
+    their L2 hit rates, not their results): workgroup b of a launch runs on the same XCD as workgroup b + 8, and
+    eight consecutive workgroups are on eight different XCDs."""
+    from paper_1305_1422_amd import capi
+    out = torch.full((1024,), -1, dtype=torch.int32, device="cuda")
+    capi.som_debug_xcc_ids(out)
+    torch.cuda.synchronize()
+    ids = out.cpu().numpy()
+    assert ids.min() >= 0 and len(set(ids[:8].tolist())) == 8, f"first eight workgroups on XCDs {ids[:8]}"
+    assert np.array_equal(ids, np.tile(ids[:8], 128)), "workgroups 8 apart do not share an XCD"
