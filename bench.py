@@ -30,11 +30,12 @@ PEAK_HBM_GBS = 8000.0
 # (FETCH_SIZE, WRITE_SIZE, scaled by the copy calibration) summarised in profiles/epoch_config*.md;
 # measured once per kernel version, not during this run (the dense figures vary by some ten percent from
 # run to run: they depend on how long the workgroups that share an instance tile stay in step).
-MEASURED_TRAFFIC_BYTES = {(2, "split_f16"): 3.978e9 + 0.036e9, (2, "fp32"): 8.49e9 + 0.025e9,
-                          (3, "split_f16"): 14.445e9 + 0.025e9, (5, "split_f16"): 15.021e9 + 0.072e9,
-                          (4, "split_f16"): 13.842e9 + 0.091e9, (4, "fp32"): 13.842e9 + 0.091e9,
-                          (6, "split_f16"): 0.340e9 + 0.030e9, (6, "fp32"): 0.340e9 + 0.030e9,
-                          (7, "split_f16"): 87.195e9 + 0.095e9, (7, "fp32"): 87.195e9 + 0.095e9}
+MEASURED_TRAFFIC_BYTES = {(2, "split_f16"): 3.841e9 + 0.036e9, (2, "fp32"): 8.49e9 + 0.025e9,
+                          (3, "split_f16"): 14.283e9 + 0.025e9, (5, "split_f16"): 13.917e9 + 0.072e9,
+                          # sparse: all kernels of the filter stage (code-book pass, hot-column block, sweep)
+                          (4, "split_f16"): 16.012e9 + 1.613e9, (4, "fp32"): 16.012e9 + 1.613e9,
+                          (6, "split_f16"): 0.390e9 + 0.056e9, (6, "fp32"): 0.390e9 + 0.056e9,
+                          (7, "split_f16"): 82.536e9 + 6.542e9, (7, "fp32"): 82.536e9 + 6.542e9}
 PEAK_FP32_VALU_TFLOPS = 157.3
 
 
@@ -201,13 +202,14 @@ def main() -> int:
         achieved = alg_bytes / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
         traffic = MEASURED_TRAFFIC_BYTES.get((w.config, args.filter))
         valu_bound_ms = 2.0 * nnz * w.k / (PEAK_FP32_VALU_TFLOPS * 1e12) * 1e3
-        roofline = {"bound": "hbm", "kernel": "k_transpose_centered_q16 + k_bmu_csr_sliced (sparse BMU filter pass)",
+        roofline = {"bound": "hbm", "kernel": "sparse BMU filter pass: k_center_transpose_q16 + hot-column block "
+                                              "(k_bmu_dense_h<partial>) + k_bmu_csr_sliced",
                     "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
                     "traffic": traffic, "avg_launch_ms": dom_ms,
                     # the three views of this kernel: (i) against the plain fp32 vector ALUs, on which 2 nnz k
                     # flop cannot take less than valu_bound_ms; (ii) `frac` above: compulsory bytes (CSR once,
                     # code book once, BMUs) against the HBM peak; (iii) the traffic the gathers really send past
-                    # L2 (counter reading of the sweep kernel) against the HBM peak
+                    # L2 (counter readings of the stage's kernels, with the hot-column block on) against the HBM peak
                     "valu_bound_ms": valu_bound_ms, "frac_of_valu_bound": valu_bound_ms / dom_ms if dom_ms > 0 else None,
                     "compulsory_bytes": alg_bytes,
                     "traffic_rate_gbs": traffic / (dom_ms * 1e-3) / 1e9 if traffic and dom_ms > 0 else None,
