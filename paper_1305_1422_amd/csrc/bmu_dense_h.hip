@@ -72,10 +72,9 @@ __device__ __forceinline__ f16x8 as_halves(f32x4 v) { return __builtin_bit_cast(
 // kMode: kHFilter keeps candidates per instance; kHCollect runs over the instances listed in `rows`
 // (their number is *n_slots) and appends every node whose score is at most thr[slot] to the
 // instance's list; kHDump writes every score to dump[slot * k + node] (test hook); kHPartial is the
-// hot-column block of the sparse search (csr_hot.hip): the two operands swap places in the matrix
-// instruction, so a lane holds one NODE and 16 instances per block, and the plain dot products times
-// the code book's scale go to dump[(node block * n + instance) * 128 + node within the block] - 128
-// contiguous bytes per store and half-wavefront.  No candidates, no constants.
+// hot-column block of the sparse search (csr_hot.hip): the plain dot products times the code book's
+// scale go to dump[(node block * n + instance) * 128 + node within the block], four neighbouring nodes
+// of one instance per 16-byte store.  No candidates, no constants.
 // `unit` numbers the (instance tile, node group) pairs; see the decoding below.
 template <int kMode>
 __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, const float *__restrict__ Wh,
@@ -230,28 +229,24 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni)
-          acc[mi][ni] = kPartial ? __builtin_amdgcn_mfma_f32_32x32x16_f16(o.h1[ni], o.g2[mi], zero, 0, 0, 0)
-                                 : __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g2[mi], o.h1[ni], zero, 0, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g2[mi], o.h1[ni], zero, 0, 0, 0);
     } else {
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni)
-          acc[mi][ni] = kPartial ? __builtin_amdgcn_mfma_f32_32x32x16_f16(o.h1[ni], o.g2[mi], acc[mi][ni], 0, 0, 0)
-                                 : __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g2[mi], o.h1[ni], acc[mi][ni], 0, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g2[mi], o.h1[ni], acc[mi][ni], 0, 0, 0);
     }
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
       for (int ni = 0; ni < 2; ++ni)
-        acc[mi][ni] = kPartial ? __builtin_amdgcn_mfma_f32_32x32x16_f16(o.h2[ni], o.g1[mi], acc[mi][ni], 0, 0, 0)
-                               : __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g1[mi], o.h2[ni], acc[mi][ni], 0, 0, 0);
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g1[mi], o.h2[ni], acc[mi][ni], 0, 0, 0);
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
       for (int ni = 0; ni < 2; ++ni)
-        acc[mi][ni] = kPartial ? __builtin_amdgcn_mfma_f32_32x32x16_f16(o.h1[ni], o.g1[mi], acc[mi][ni], 0, 0, 0)
-                               : __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g1[mi], o.h1[ni], acc[mi][ni], 0, 0, 0);
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g1[mi], o.h1[ni], acc[mi][ni], 0, 0, 0);
     __builtin_amdgcn_s_setprio(0);
   };
 
@@ -293,20 +288,25 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
     }
     if (last_k) {
       if (kPartial) {
-        // lane = node wm 64 + mi 32 + l32 of the block, register v = instance wi 64 + ni 32 + mfma_row;
-        // the table is laid out [node block][instance][128 nodes], so the 128 x 128 results of a workgroup
-        // and node block fill one contiguous 64 KB run
-        float *pblk = dump + ((int64_t)nb * n + inst0) * kTN + wm * 64 + l32;
+        // lane = instance wi 64 + ni 32 + l32 of the tile; registers 4 g .. 4 g + 3 of an output block are
+        // nodes wm 64 + mi 32 + 8 g + 4 lhi .. + 3 of the node block, which lie side by side in the table
+        // [node block][instance][128 nodes]: one 16-byte store each, and the 128 x 128 results of a
+        // workgroup and node block fill one contiguous 64 KB run
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
+        for (int ni = 0; ni < 2; ++ni) {
+          const int64_t inst = inst0 + wi * 64 + ni * 32 + l32;
+          float *prow = dump + ((int64_t)nb * n + inst) * kTN + wm * 64 + 4 * lhi;
 #pragma unroll
-          for (int ni = 0; ni < 2; ++ni)
+          for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int il = wi * 64 + ni * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
-              if (inst0 + il < n) pblk[il * kTN + mi * 32] = sw * tot[mi][ni][v];
-              tot[mi][ni][v] = 0.f;
+            for (int g = 0; g < 4; ++g) {
+              const f32x4 val = {sw * tot[mi][ni][4 * g], sw * tot[mi][ni][4 * g + 1], sw * tot[mi][ni][4 * g + 2],
+                                 sw * tot[mi][ni][4 * g + 3]};
+              if (inst < n) *reinterpret_cast<f32x4 *>(prow + mi * 32 + 8 * g) = val;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) tot[mi][ni][4 * g + e] = 0.f;
             }
+        }
       } else if (kDump) {
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi)
