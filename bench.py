@@ -68,7 +68,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 4, 5, 6, 7])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--filter", choices=["split_f16", "fp32"], default="split_f16",
+    ap.add_argument("--filter", choices=["auto", "two_level", "split_f16", "fp32"], default="auto",
                     help="arithmetic of the dense BMU filter pass (same BMUs either way)")
     ap.add_argument("--neighborhood", choices=["gaussian", "gaussian-compact", "bubble"], default="gaussian",
                     help="neighbourhood of the update (the stated configurations use the plain Gaussian)")

@@ -42,7 +42,7 @@ enum { SOM_OK = 0, SOM_ERR_INVALID_ARG = 1, SOM_ERR_ALLOC = 2, SOM_ERR_DEVICE = 
 enum { SOM_MAP_PLANAR = 0, SOM_MAP_TOROID = 1 };          /* option -m: planar (default) or toroid   */
 enum { SOM_GRID_SQUARE = 0, SOM_GRID_HEXAGONAL = 1 };     /* option -g: square (default) or hexagonal */
 enum { SOM_COOL_AS_RADIUS = -1, SOM_COOL_LINEAR = 0, SOM_COOL_EXPONENTIAL = 1 };   /* options -t / -T */
-enum { SOM_FILTER_FP32 = 0, SOM_FILTER_SPLIT_F16 = 1 };   /* see som_set_filter                       */
+enum { SOM_FILTER_FP32 = 0, SOM_FILTER_SPLIT_F16 = 1, SOM_FILTER_TWO_LEVEL = 2, SOM_FILTER_AUTO = 3 };   /* see som_set_filter */
 enum { SOM_NEIGHBORHOOD_GAUSSIAN = 0, SOM_NEIGHBORHOOD_BUBBLE = 1 };   /* option -n               */
 enum { SOM_SMOOTH_AUTO = 0, SOM_SMOOTH_VECTOR = 1, SOM_SMOOTH_MATRIX = 2 };   /* see som_set_smoothing   */
 
@@ -313,10 +313,19 @@ int som_set_smoothing(som_ctx *ctx, int form);
  * the GPU variant obtains the distances through linear algebra).  The result of a BMU search
  * does not depend on it: every filter only shortlists nodes within a proven rounding bound,
  * and exact fp64 distances decide.
- *   SOM_FILTER_SPLIT_F16 (default)  every fp32 operand is split into two fp16 numbers and the
+ *   SOM_FILTER_SPLIT_F16  every fp32 operand is split into two fp16 numbers and the
  *                  dot products run as three fp16 matrix instructions with fp32 accumulation:
  *                  fp32-grade scores at several times the fp32 matrix rate; needs 4 bytes per
  *                  element of extra device memory for instances and code book.
+ *   SOM_FILTER_TWO_LEVEL  a coarse pass with ONE fp16 product per feature (the hi halves alone) finds, per
+ *                  instance and block of 128 nodes, the smallest coarse score; the blocks that cannot
+ *                  hold the BMU by the proven bound of those scores are dropped, the instances are
+ *                  ordered by their best block, and the split-fp16 pass runs over the remaining
+ *                  (128 instances, block) pairs only.  Needs 6 bytes per element of extra device memory
+ *                  and 4 bytes per instance and node block.
+ *   SOM_FILTER_AUTO (default)  SOM_FILTER_TWO_LEVEL for maps of 1,024 nodes or more whose table of
+ *                  block minima (4 bytes x instances x nodes / 128) stays under 8 GiB, else
+ *                  SOM_FILTER_SPLIT_F16.
  *   SOM_FILTER_FP32  fp32 matrix instructions on the operands as they are.
  * Errors: unknown value -> SOM_ERR_INVALID_ARG.
  */

@@ -18,7 +18,7 @@ SOM_OK, SOM_ERR_INVALID_ARG, SOM_ERR_ALLOC, SOM_ERR_DEVICE, SOM_ERR_STATE = 0, 1
 SOM_MAP_PLANAR, SOM_MAP_TOROID = 0, 1
 SOM_GRID_SQUARE, SOM_GRID_HEXAGONAL = 0, 1
 SOM_COOL_AS_RADIUS, SOM_COOL_LINEAR, SOM_COOL_EXPONENTIAL = -1, 0, 1
-SOM_FILTER_FP32, SOM_FILTER_SPLIT_F16 = 0, 1
+SOM_FILTER_FP32, SOM_FILTER_SPLIT_F16, SOM_FILTER_TWO_LEVEL, SOM_FILTER_AUTO = 0, 1, 2, 3
 SOM_NEIGHBORHOOD_GAUSSIAN, SOM_NEIGHBORHOOD_BUBBLE = 0, 1
 SOM_SMOOTH_AUTO, SOM_SMOOTH_VECTOR, SOM_SMOOTH_MATRIX = 0, 1, 2
 

@@ -133,10 +133,12 @@ __device__ __forceinline__ void consume_scores(f32x16 (&tot)[2][2], const float 
 // Merge the four partial lists of every instance of the tile (two node halves x two lane halves)
 // into kCand candidates plus the smallest dropped score, and store them.  TI = instances per
 // tile; mval/midx: LDS scratch of TI*4*3 floats and TI*4*2 ints that no wavefront reads any more.
+// With `rows` the tile is positions inst0 .. of that index list and the lists are stored under the
+// instances' own numbers.
 template <int TI>
 __device__ __forceinline__ void merge_and_store(const Top2 (&top)[2], float *mval, int *midx, int tid, int wm, int wi,
                                                 int l32, int lhi, int64_t inst0, int64_t n, int64_t group,
-                                                CandView out) {
+                                                CandView out, const int32_t *__restrict__ rows = nullptr) {
 #pragma unroll
   for (int ni = 0; ni < 2; ++ni) {
     const int il = wi * 64 + ni * 32 + l32;
@@ -176,7 +178,7 @@ __device__ __forceinline__ void merge_and_store(const Top2 (&top)[2], float *mva
         if (c[0]) { v[0] = x; id[0] = xi; }
       }
     }
-    const int64_t j = group * n + inst0 + tid;      // lists are stored [node group][instance]
+    const int64_t j = group * n + (rows ? (int64_t)rows[inst0 + tid] : inst0 + tid);      // lists are stored [node group][instance]
 #pragma unroll
     for (int t = 0; t < kCand; ++t) {
       out.val[j * kCand + t] = v[t];

@@ -65,7 +65,7 @@ __device__ __forceinline__ void load16_to_lds_v(const void *lane_address, unsign
 }
 #pragma clang diagnostic pop
 
-enum { kHFilter = 0, kHCollect = 1, kHDump = 2, kHPartial = 3 };
+enum { kHFilter = 0, kHCollect = 1, kHDump = 2, kHPartial = 3, kHBlockMin = 4, kHFine = 5 };
 
 __device__ __forceinline__ f16x8 as_halves(f32x4 v) { return __builtin_bit_cast(f16x8, v); }
 
@@ -75,8 +75,16 @@ __device__ __forceinline__ f16x8 as_halves(f32x4 v) { return __builtin_bit_cast(
 // hot-column block of the sparse search (csr_hot.hip): the plain dot products times the code book's
 // scale go to dump[(node block * n + instance) * 128 + node within the block], four neighbouring nodes
 // of one instance per 16-byte store.  No candidates, no constants.
+// The two-level search (bmu_two_level.hip) adds two modes.  kHBlockMin is its coarse pass: the smallest
+// score of every (instance, node block) pair goes to dump[node block * n + instance], nothing else is
+// kept.  kHFine is its second pass: the instance tiles are taken through the index list `rows` (all n
+// instances, ordered so that neighbours in the list have their best nodes in the same block), and the
+// workgroups of tile t share out the cnt[t] node blocks listed, ascending, in list[t * blocks of the
+// map ..] instead of all of them; candidates are stored under the instances' own numbers.
+// kCoarse: the operands are hi-only planes (chunks of 64 features, see split_f16.hip) and a k-step is
+// one product instead of three: 11-bit operands, a third of the matrix work per feature.
 // `unit` numbers the (instance tile, node group) pairs; see the decoding below.
-template <int kMode>
+template <int kMode, bool kCoarse>
 __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, const float *__restrict__ Wh,
                                                  const float *__restrict__ wc, const float *__restrict__ xscale,
                                                  const float *__restrict__ wscale, int64_t n, int k, int nK,
@@ -87,6 +95,9 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
   constexpr bool kCollect = kMode == kHCollect;
   constexpr bool kDump = kMode == kHDump;
   constexpr bool kPartial = kMode == kHPartial;
+  constexpr bool kBlockMin = kMode == kHBlockMin;
+  constexpr bool kFine = kMode == kHFine;
+  constexpr bool kGather = kCollect || kFine;        // instance tiles through the index list `rows`
   constexpr int WI = kHWI;
   constexpr int kHTI = 64 * WI;              // instances per tile
   constexpr int kHXTile = kHTI * kHRow;      // floats
@@ -95,6 +106,7 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
   __shared__ __attribute__((aligned(16))) float sW[kHStages][kHWTile];
   __shared__ __attribute__((aligned(16))) float sX[kHStages][kHXTile];
   __shared__ float sWn[4][kTN];      // node constants of the node blocks in flight
+  __shared__ float sMin[2][kHTI];    // block-minimum mode: the upper node half's minima, two blocks in flight
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -114,11 +126,23 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
   if (tile >= ntiles) return;        // uniform over the workgroup
   const int64_t inst0 = tile * kHTI;
 
+  // the node blocks of this workgroup: positions nb_first .. nb_first + nNB - 1 of the map's blocks, or
+  // (fine mode) of the tile's own ascending list
   const int nNB_all = (k + kTN - 1) / kTN;
-  const int nb_per = (nNB_all + groups - 1) / groups;
+  const int32_t *blist = kFine ? list + tile * (int64_t)nNB_all : nullptr;
+  const int nNB_avail = kFine ? min(cnt[tile], nNB_all) : nNB_all;
+  const int nb_per = (nNB_avail + groups - 1) / groups;
   const int nb_first = group * nb_per;
-  const int nNB = min(nb_per, nNB_all - nb_first);
-  if (nNB <= 0) return;              // uniform over the workgroup
+  const int nNB = min(nb_per, nNB_avail - nb_first);
+  if (nNB <= 0) {                    // uniform over the workgroup
+    if (kFine && tid < kHTI && inst0 + tid < n) {      // certify reads a list per (instance, group): an empty one
+      const int64_t j = (int64_t)group * n + rows[inst0 + tid];
+#pragma unroll
+      for (int t = 0; t < kCand; ++t) { out.val[j * kCand + t] = INFINITY; out.idx[j * kCand + t] = -1; }
+      out.over[j] = INFINITY;
+    }
+    return;
+  }
   const int total = nK * nNB;
 
   // ---- loader: one instruction fills 8 tile rows (64 lanes x 16 bytes); wavefront w issues W slots
@@ -139,7 +163,7 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
     const int q = ld_pos ^ ((row & 7) ^ ((row >> 3) & 1));
     const int rclamped = row < last_inst ? row : (int)last_inst;
     xoff[i] = (unsigned)rclamped * row_bytes + 16u * q;
-    xptr[i] = kCollect ? reinterpret_cast<const char *>(Xh) + (int64_t)rows[inst0 + rclamped] * row_bytes + 16 * q : nullptr;
+    xptr[i] = kGather ? reinterpret_cast<const char *>(Xh) + (int64_t)rows[inst0 + rclamped] * row_bytes + 16 * q : nullptr;
   }
 #pragma unroll
   for (int i = 0; i < kWSlots; ++i) {
@@ -151,7 +175,8 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
   const unsigned lds_x = lds_address_h(&sX[0][1024 * wave]);    // 4 slots
   const unsigned lds_wn = lds_address_h(&sWn[0][0]);
   const unsigned wn_off = (unsigned)(wave * 64 + lane) * 4u;
-  int ld_nb = nb_first, ld_kc = 0;
+  int ld_ord = 0, ld_kc = 0;        // ordinal of the node block being loaded within this workgroup's run
+  int ld_nb = kFine ? blist[nb_first] : nb_first;
   auto issue_loads = [&](int buf) {
     const char *wbase = reinterpret_cast<const char *>(Wh) + (int64_t)ld_nb * kTN * row_bytes;
     if (ld_kc == 0) {                                           // entering a node block
@@ -160,17 +185,23 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
       for (int i = 0; i < kWSlots; ++i) woff[i] = (unsigned)(wrow[i] < last_node ? wrow[i] : last_node) * row_bytes + wq[i];
       // node constants of the block: wc is padded to whole blocks with +inf (such nodes can never
       // win), so the 128 values are loaded like the tiles, as the oldest operation of the batch
-      if (!kPartial && wave < 2) load4_to_lds_h(wc + (int64_t)ld_nb * kTN, wn_off, lds_wn + (ld_nb & 3) * (kTN * 4) + wave * 256);
+      if (!kPartial && wave < 2)
+        load4_to_lds_h(wc + (int64_t)ld_nb * kTN, wn_off,
+                       lds_wn + __builtin_amdgcn_readfirstlane(ld_ord & 3) * (kTN * 4) + wave * 256);
     }
     const unsigned off = (unsigned)ld_kc * (kHRow * 4);
 #pragma unroll
     for (int i = 0; i < kWSlots; ++i) load16_to_lds_h(wbase + off, woff[i], lds_w + buf * (kHWTile * 4) + i * 1024);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      if (kCollect) load16_to_lds_v(xptr[i] + off, lds_x + buf * (kHXTile * 4) + i * 1024);
+      if (kGather) load16_to_lds_v(xptr[i] + off, lds_x + buf * (kHXTile * 4) + i * 1024);
       else load16_to_lds_h(xbase + off, xoff[i], lds_x + buf * (kHXTile * 4) + i * 1024);
     }
-    if (++ld_kc == nK) { ld_kc = 0; ++ld_nb; }
+    if (++ld_kc == nK) {
+      ld_kc = 0;
+      ++ld_ord;
+      ld_nb = kFine ? (ld_ord < nNB ? blist[nb_first + ld_ord] : 0) : ld_nb + 1;
+    }
   };
 
   // ---- reader
@@ -191,12 +222,13 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
     top2_init(top[ni]);
     slot_of[ni] = inst0 + wi * 64 + ni * 32 + l32;
     const bool live = slot_of[ni] < n_inst;
-    const int64_t inst = live ? (kCollect ? (int64_t)rows[slot_of[ni]] : slot_of[ni]) : 0;
+    const int64_t inst = live ? (kGather ? (int64_t)rows[slot_of[ni]] : slot_of[ni]) : 0;
     factor[ni] = (live && !kPartial) ? -2.f * xscale[inst] * sw : 0.f;
     lim[ni] = (kCollect && live) ? thr[slot_of[ni]] : -INFINITY;
   }
 
   f32x16 acc[2][2], tot[2][2];
+  float block_min[2] = {INFINITY, INFINITY};
 #pragma unroll
   for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -205,7 +237,8 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
       for (int v = 0; v < 16; ++v) tot[mi][ni][v] = 0.f;
 
   // Operands of one k-step (16 features): the hi and lo planes of this wavefront's two 32-node and
-  // two 32-instance row blocks, eight 16-byte LDS reads per lane.
+  // two 32-instance row blocks, eight 16-byte LDS reads per lane.  (Hi-only planes: the same eight reads
+  // are the hi halves of the 16-feature steps ks and ks + 2 of a 64-feature chunk.)
   struct Operands { f16x8 g1[2], g2[2], h1[2], h2[2]; };
   auto read_operands = [&](Operands &o, int st, int ks) {
     const float *pw = &sW[st][a_base];
@@ -218,30 +251,34 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
       o.h2[b] = as_halves(*reinterpret_cast<const f32x4 *>(px + b * 32 * kHRow + rd_off[2 + ks]));
     }
   };
-  // Twelve MFMAs of one k-step; the four output blocks take turns, so that an accumulator is reused
+  // Twelve MFMAs of one k-step (eight on hi-only planes, where the operand pairs 1 and 2 are two different
+  // 16-feature steps of the chunk); the four output blocks take turns, so that an accumulator is reused
   // every fourth instruction only.  The small cross products go first.  `fresh`: the accumulators
   // start from C = 0 as an operand of the instruction itself, which spares clearing 64 registers.
   auto multiply = [&](const Operands &o, bool fresh) {
     __builtin_amdgcn_s_setprio(1);      // the wavefront that has operands ready goes first on the SIMD (-1.6 %)
+    // first product: hi_w(k-step ks + 2) . hi_x(same) on hi-only planes, lo_w . hi_x on split planes
     if (fresh) {
       const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g2[mi], o.h1[ni], zero, 0, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g2[mi], kCoarse ? o.h2[ni] : o.h1[ni], zero, 0, 0, 0);
     } else {
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g2[mi], o.h1[ni], acc[mi][ni], 0, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g2[mi], kCoarse ? o.h2[ni] : o.h1[ni], acc[mi][ni], 0, 0, 0);
     }
+    if (!kCoarse) {
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+      for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-      for (int ni = 0; ni < 2; ++ni)
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g1[mi], o.h2[ni], acc[mi][ni], 0, 0, 0);
+        for (int ni = 0; ni < 2; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g1[mi], o.h2[ni], acc[mi][ni], 0, 0, 0);
+    }
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -267,7 +304,7 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
   Operands op0, op1;
   int stage = 0;                                 // t % kHStages
   for (int t = 0; t < total; ++t) {
-    const int nb = nb_first + t / nK, kc = t % nK;
+    const int ord = t / nK, kc = t % nK;           // ordinal of the node block in this workgroup's run
     const int next_stage = stage ^ 1;
     // the stage that is loaded now held chunk t - 1, which every wavefront has left
     if (t + 1 < total) issue_loads(next_stage);
@@ -287,7 +324,25 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
           for (int v = 0; v < 16; ++v) tot[mi][ni][v] += acc[mi][ni][v];
     }
     if (last_k) {
-      if (kPartial) {
+      const int nb = kFine ? blist[nb_first + ord] : nb_first + ord;
+      if (kBlockMin) {
+        // smallest score of the block per instance: over this lane's 32 nodes, the other lane half, and
+        // (through LDS, after the barrier below) the other node half
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+          float m = INFINITY;
+#pragma unroll
+          for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              m = fminf(m, fmaf(factor[ni], tot[mi][ni][v], sWn[ord & 3][wm * 64 + mfma_row(mi, v, lhi)]));
+              tot[mi][ni][v] = 0.f;
+            }
+          m = fminf(m, __shfl_xor(m, 32, 64));
+          block_min[ni] = m;
+          if (wm == 1 && lhi == 0) sMin[ord & 1][wi * 64 + ni * 32 + l32] = m;
+        }
+      } else if (kPartial) {
         // lane = instance wi 64 + ni 32 + l32 of the tile; registers 4 g .. 4 g + 3 of an output block are
         // nodes wm 64 + mi 32 + 8 g + 4 lhi .. + 3 of the node block, which lie side by side in the table
         // [node block][instance][128 nodes]: one 16-byte store each, and the 128 x 128 results of a
@@ -316,28 +371,38 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
             const int node = nb * kTN + nl;
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni) {
-              if (node < k && slot_of[ni] < n) dump[slot_of[ni] * k + node] = fmaf(factor[ni], tot[mi][ni][v], sWn[nb & 3][nl]);
+              if (node < k && slot_of[ni] < n) dump[slot_of[ni] * k + node] = fmaf(factor[ni], tot[mi][ni][v], sWn[ord & 3][nl]);
               tot[mi][ni][v] = 0.f;
             }
           }
       } else {
-        consume_scores<kCollect>(tot, sWn[nb & 3], nb * kTN, k, wm, lhi, factor, top, lim, slot_of, cnt, list);
+        consume_scores<kCollect>(tot, sWn[ord & 3], nb * kTN, k, wm, lhi, factor, top, lim, slot_of, cnt, list);
       }
     }
 
     __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
     __syncthreads();
+    if (kBlockMin && last_k && wm == 0 && lhi == 0) {
+      // the upper node half wrote its minima before the barrier; the buffer of this parity is written again
+      // two node blocks later, i.e. after the next barrier at the earliest
+      const int nb = nb_first + ord;
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni) {
+        const int il = wi * 64 + ni * 32 + l32;
+        if (inst0 + il < n) dump[(int64_t)nb * n + inst0 + il] = fminf(block_min[ni], sMin[ord & 1][il]);
+      }
+    }
     stage = next_stage;
   }
-  if (kDump || kCollect || kPartial) return;
+  if (kDump || kCollect || kPartial || kBlockMin) return;
   merge_and_store<kHTI>(top, &sW[0][0], reinterpret_cast<int *>(&sX[0][0]), tid, wm, wi, l32, lhi, inst0, n, group,
-                        out);
+                        out, kFine ? rows : nullptr);
 }
 
-// Filter and dump modes: one unit per workgroup.  Collect mode: the number of live instance tiles is
-// only known on the device, so a fixed grid walks the units; its size is a multiple of 8, which keeps
-// unit mod 8 = workgroup mod 8 = the XCD the decoding assumes.
-template <int kMode>
+// Filter, dump, partial, block-minimum and fine modes: one unit per workgroup.  Collect mode: the number
+// of live instance tiles is only known on the device, so a fixed grid walks the units; its size is a
+// multiple of 8, which keeps unit mod 8 = workgroup mod 8 = the XCD the decoding assumes.
+template <int kMode, bool kCoarse>
 __global__ __launch_bounds__(128 * kHWI, 2) void k_bmu_dense_h(const float *__restrict__ Xh, const float *__restrict__ Wh,
                                                         const float *__restrict__ wc,
                                                         const float *__restrict__ xscale,
@@ -352,13 +417,13 @@ __global__ __launch_bounds__(128 * kHWI, 2) void k_bmu_dense_h(const float *__re
     const int64_t ntiles = ((int64_t)*n_slots + 64 * kHWI - 1) / (64 * kHWI);
     const int64_t units = (ntiles + 7) / 8 * 8 * groups;
     for (int64_t unit = blockIdx.x; unit < units; unit += gridDim.x) {
-      bmu_dense_h_unit<kMode>(Xh, Wh, wc, xscale, wscale, n, k, nK, flush_chunks, groups, out, dump, rows, n_slots,
-                                  thr, cnt, list, unit);
+      bmu_dense_h_unit<kMode, kCoarse>(Xh, Wh, wc, xscale, wscale, n, k, nK, flush_chunks, groups, out, dump, rows,
+                                       n_slots, thr, cnt, list, unit);
       __syncthreads();               // the next unit reuses the LDS stages
     }
   } else {
-    bmu_dense_h_unit<kMode>(Xh, Wh, wc, xscale, wscale, n, k, nK, flush_chunks, groups, out, dump, rows, n_slots,
-                                thr, cnt, list, (int64_t)blockIdx.x);
+    bmu_dense_h_unit<kMode, kCoarse>(Xh, Wh, wc, xscale, wscale, n, k, nK, flush_chunks, groups, out, dump, rows,
+                                     n_slots, thr, cnt, list, (int64_t)blockIdx.x);
   }
 }
 
@@ -387,7 +452,21 @@ int bmu_dense_h_groups(const som_ctx *c, int64_t n) {
   return (nNB + best - 1) / best;
 }
 
-hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump) {
+// Workgroups per instance tile in the second pass of the two-level search: a tile usually lists a few
+// node blocks only, so the tiles themselves fill the chip unless there are few of them.
+int bmu_dense_h_fine_groups(const som_ctx *c, int64_t n) {
+  const int64_t tiles = (n + 64 * kHWI - 1) / (64 * kHWI);
+  const int nNB = (c->k + kTN - 1) / kTN;
+  const int64_t slots = (int64_t)c->n_cu * 2;
+  int64_t want = (4 * slots + tiles - 1) / tiles;
+  if (want > 8) want = 8;
+  if (want > nNB) want = nNB;
+  if (want < 1) want = 1;
+  return (int)want;
+}
+
+// coarse: the scores of the coarse pass of the two-level search (hi-only planes), dump mode only.
+hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump, bool coarse) {
   const int groups = bmu_dense_h_groups(c, n);
   const int64_t tiles = (n + 64 * kHWI - 1) / (64 * kHWI);
   const int64_t blocks = (tiles + 7) / 8 * 8 * groups;
@@ -395,14 +474,48 @@ hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump) {
   CandView out{c->cand_val, c->cand_idx, c->cand_over};
   const float *Xh = reinterpret_cast<const float *>(c->Xh);
   const float *Wh = reinterpret_cast<const float *>(c->Wh);
-  if (dump)
-    hipLaunchKernelGGL((k_bmu_dense_h<kHDump>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
+  if (dump && coarse)
+    hipLaunchKernelGGL((k_bmu_dense_h<kHDump, true>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
+                       reinterpret_cast<const float *>(c->Xh1), reinterpret_cast<const float *>(c->Wh1), c->wn32,
+                       c->xscale, c->wscale, n, c->k, (c->dim + 63) / 64, split_flush_chunks(c->dim), groups, out, dump,
+                       nullptr, nullptr, nullptr, nullptr, nullptr);
+  else if (dump)
+    hipLaunchKernelGGL((k_bmu_dense_h<kHDump, false>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
                        c->wn32, c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, dump, nullptr, nullptr, nullptr,
                        nullptr, nullptr);
   else
-    hipLaunchKernelGGL((k_bmu_dense_h<kHFilter>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
+    hipLaunchKernelGGL((k_bmu_dense_h<kHFilter, false>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
                        c->wn32, c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, dump, nullptr, nullptr, nullptr,
                        nullptr, nullptr);
+  return hipGetLastError();
+}
+
+// Coarse pass of the two-level search: c->coarse_min[node block][instance] = smallest one-product score
+// of the pair, from the hi-only planes c->Xh1 and c->Wh1; the tiling and launch shape of the filter.
+hipError_t launch_bmu_block_min(som_ctx *c, int64_t n) {
+  const int groups = bmu_dense_h_groups(c, n);
+  const int64_t tiles = (n + 64 * kHWI - 1) / (64 * kHWI);
+  const int64_t blocks = (tiles + 7) / 8 * 8 * groups;
+  CandView out{nullptr, nullptr, nullptr};
+  hipLaunchKernelGGL((k_bmu_dense_h<kHBlockMin, true>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
+                     reinterpret_cast<const float *>(c->Xh1), reinterpret_cast<const float *>(c->Wh1), c->wn32,
+                     c->xscale, c->wscale, n, c->k, (c->dim + 63) / 64, split_flush_chunks(c->dim), groups, out,
+                     c->coarse_min, nullptr, nullptr, nullptr, nullptr, nullptr);
+  return hipGetLastError();
+}
+
+// Second pass of the two-level search: the split-fp16 filter over the instance tiles of the order
+// c->sort_val[0] and the node blocks c->tile_list lists for each (c->tile_cnt of them).
+hipError_t launch_bmu_dense_h_fine(som_ctx *c, int64_t n) {
+  const int groups = bmu_dense_h_fine_groups(c, n);
+  const int64_t tiles = (n + 64 * kHWI - 1) / (64 * kHWI);
+  const int64_t blocks = (tiles + 7) / 8 * 8 * groups;
+  const int nK = (c->dim + 31) / 32;
+  CandView out{c->cand_val, c->cand_idx, c->cand_over};
+  hipLaunchKernelGGL((k_bmu_dense_h<kHFine, false>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
+                     reinterpret_cast<const float *>(c->Xh), reinterpret_cast<const float *>(c->Wh), c->wn32,
+                     c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, nullptr, c->sort_val[0],
+                     nullptr, nullptr, c->tile_cnt, c->tile_list);
   return hipGetLastError();
 }
 
@@ -413,7 +526,7 @@ hipError_t launch_hot_partial(som_ctx *c, int64_t n) {
   const int64_t tiles = (n + 64 * kHWI - 1) / (64 * kHWI);
   const int64_t blocks = (tiles + 7) / 8 * 8 * groups;
   CandView out{nullptr, nullptr, nullptr};
-  hipLaunchKernelGGL((k_bmu_dense_h<kHPartial>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
+  hipLaunchKernelGGL((k_bmu_dense_h<kHPartial, false>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
                      reinterpret_cast<const float *>(c->hot_Xh), reinterpret_cast<const float *>(c->hot_Wh), nullptr,
                      nullptr, c->hot_wscale, n, c->k, kHot / 32, split_flush_chunks(kHot), groups, out, c->hot_P,
                      nullptr, nullptr, nullptr, nullptr, nullptr);
@@ -433,7 +546,7 @@ hipError_t launch_bmu_dense_h_collect(som_ctx *c, int64_t n) {
   blocks = (blocks + 7) / 8 * 8;
   const int nK = (c->dim + 31) / 32;
   CandView out{nullptr, nullptr, nullptr};
-  hipLaunchKernelGGL((k_bmu_dense_h<kHCollect>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
+  hipLaunchKernelGGL((k_bmu_dense_h<kHCollect, false>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
                      reinterpret_cast<const float *>(c->Xh), reinterpret_cast<const float *>(c->Wh), c->wn32,
                      c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, nullptr, c->collect_rows, c->list_counts + 1,
                      c->collect_thr, c->collect_cnt, c->collect_list);

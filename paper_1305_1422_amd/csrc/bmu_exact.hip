@@ -26,54 +26,9 @@
 // MFMA pass with two-level accumulation: g = block + ceil(dim / block) + 2.
 // Sparse scores |w|^2 - 2 x.w from an FMA chain of len terms, no centring: g = len,
 //   |s_fp32 - s_exact| <= u [ (2 g + 2) X Wm + 2 Wm^2 ].
-#include "som_internal.hpp"
-
-#include <math.h>
+#include "margin.hpp"
 
 namespace som {
-
-// Coefficients of the bound for one filter variant: |s_filter - s_exact| <=
-//   u [ coef_xw X Wm + coef_floor (xscale_j Wm + wscale X) + 4 Wm^2 + 6 M Wm ].
-struct MarginModel {
-  double coef_xw;
-  double coef_floor;         // 0 for the fp32 pass
-  const float *xscale;       // [n] power-of-two scale of every instance (split-fp16 pass), else null
-  const float *wscale;       // [1] power-of-two scale of the centred code book, else null
-  int x_centered;            // the instances were centred too (split-fp16 pass): X = |x - mu|, no term in M
-  const int64_t *indptr;     // sparse rows: coef_xw = 2 max(row length, 1) + 6 (one FMA chain over the row)
-  const float *row_q;        // [n] sparse rows scored against the 16-bit code book: sum_nz |v_c| step_c
-  // sparse rows whose frequent columns went through the matrix cores (csr_hot.hip): the split-fp16 bound
-  // of that block, coef_hot |x_hot| Wm + sqrt(kHot) (hot_xscale_j Wm + hot_wscale |x_hot|), in units of u
-  double coef_hot;           // 0: no hot block
-  const float *hot_xn;       // [n] |x_hot|^2
-  const float *hot_xscale;   // [n]
-  const float *hot_wscale;   // [1]
-};
-
-__device__ __forceinline__ double score_margin(const MarginModel &mm, int64_t j, double xnorm2, double wmax2,
-                                               double munorm2) {
-  const double u = 5.9604644775390625e-08;   // 2^-24
-  const double xn = sqrt(xnorm2 * (1.0 + 1.2e-7));
-  const double wm = sqrt(wmax2 * (1.0 + 1.2e-7));
-  const double mn = mm.x_centered ? 0.0 : sqrt(munorm2 * (1.0 + 1.2e-7));
-  double coef = mm.coef_xw;
-  double absolute = 0.0;
-  if (mm.indptr) {
-    const double len = (double)(mm.indptr[j + 1] - mm.indptr[j]);
-    coef = 2.0 * (len < 1.0 ? 1.0 : len) + 6.0;     // + 2: the product of value and column step is rounded
-    // a quantised entry is within 0.51 steps of w' (0.5 from rounding, the rest from the fp32
-    // division), so the dot product moves by at most 0.51 sum |v_c| step_c (the sum itself carries
-    // fp32 rounding: 1e-5 relative is ample), the score by twice that
-    if (mm.row_q) absolute = 2.0 * 0.51 * (1.0 + 1e-5) * (double)mm.row_q[j];
-  }
-  double bound = coef * xn * wm + 4.0 * wm * wm + 6.0 * mn * wm;
-  if (mm.coef_hot > 0.0) {
-    const double xh = sqrt((double)mm.hot_xn[j] * (1.0 + 1.2e-7));
-    bound += mm.coef_hot * xh * wm + sqrt((double)kHot) * ((double)mm.hot_xscale[j] * wm + (double)*mm.hot_wscale * xh);
-  }
-  if (mm.xscale) bound += mm.coef_floor * ((double)mm.xscale[j] * wm + (double)*mm.wscale * xn);
-  return 2.125 * (u * bound + absolute);          // both scores of a pair may err, plus slack for higher-order terms
-}
 
 // `groups` candidate lists per instance (one per node group of the fp32 pass), stored
 // [group][instance][kCand]; the kept candidates are written back into group 0's slots.
@@ -481,7 +436,7 @@ static double split_roundings_for(int dim) {
   return 2.5 * 6.0 * chunks + 9.0 + (double)((dim + 32 * chunks - 1) / (32 * chunks)) + 2.0;
 }
 
-static MarginModel margin_model(const som_ctx *c, int mode, const int64_t *indptr, bool hot = false) {
+MarginModel margin_model(const som_ctx *c, int mode, const int64_t *indptr, bool hot) {
   MarginModel mm{2.0 * fp32_pass_roundings(c->dim) + 4.0, 0.0, nullptr, nullptr, 0, nullptr, nullptr, 0.0, nullptr, nullptr, nullptr};
   if (mode == kCertifyCsr) {
     mm.indptr = indptr;
@@ -494,6 +449,20 @@ static MarginModel margin_model(const som_ctx *c, int mode, const int64_t *indpt
       mm.hot_xscale = c->hot_xscale;
       mm.hot_wscale = c->hot_wscale;
     }
+  }
+  if (mode == kCertifyCoarse) {
+    // One fp16 product per feature pair on the hi halves alone (coarse pass of the two-level search).  An
+    // operand element v / scale is rounded to 11 significant bits, |dv| <= 2^-11 |v| + 2^-25 scale, so by
+    // Cauchy-Schwarz the dot product of the rounded rows is off by at most
+    //   |dx| |w'| + |hi_x| |dw| <= (2 + 2^-11) 2^-11 X Wm + floor terms = (2^14 + 8) u X Wm + ...,
+    // doubled by the factor -2 of the score.  Accumulation (fewer instructions per flush interval than the
+    // split pass, priced like it), the stored c_i, the final multiply-add and the roundings of w - mu and
+    // x - mu as in the split model.
+    mm.coef_xw = 2.0 * (16384.0 + 8.0) + 2.0 * split_pass_roundings(c->dim) + 4.0 + 2.0;
+    mm.coef_floor = sqrt((double)c->dim);        // 2^-25 per element and operand, doubled = u
+    mm.xscale = c->xscale;
+    mm.wscale = c->wscale;
+    mm.x_centered = 1;
   }
   if (mode == kCertifySplit) {
     // dot product: accumulation + 3 * 2^-22 of the split (= 12 u) ; both doubled by the factor -2;

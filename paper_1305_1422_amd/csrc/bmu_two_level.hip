@@ -1,0 +1,102 @@
+// Dense best-matching-unit search in two levels (paper: BMU equation; "Parallelism": distances
+// through linear algebra).
+//
+// The split-fp16 filter (bmu_dense_h.hip) spends three matrix products per feature on EVERY
+// (instance, node) pair to get fp32-grade scores, although all it needs of most pairs is the
+// knowledge that the node is not the best one.  One product on the hi halves alone gives scores with
+// 11-bit operands at a third of the work, and a proven bound e_j on their error (margin.hpp).  So:
+//   1. coarse pass (k_bmu_dense_h, block-minimum mode): m[b][j] = the smallest coarse score of instance
+//      j among the 128 nodes of block b;
+//   2. k_select_blocks: with m_j = min_b m[b][j], the BMU of j lies in a block with
+//      m[b][j] <= m_j + 2 e_j - a node of any other block has an exact score above that of the node
+//      that gave m_j, strictly, so it is not the BMU and does not tie with it.  The kernel writes that
+//      block set as a bit mask and the block of m_j as a sort key;
+//   3. the instances are put in the order of their keys (segsum.hip's radix sort): neighbours in that
+//      order have their best nodes in the same block and, on a map that has begun to order itself,
+//      nearly the same block sets;
+//   4. k_tile_lists: the union of the masks over every 128 consecutive instances of that order, as an
+//      ascending list of blocks;
+//   5. fine pass (k_bmu_dense_h, fine mode): the split-fp16 filter over those (tile, block) pairs only.
+// Its candidates go through the exact stage like those of the one-level filter: the nodes it never saw
+// are out by the argument of step 2, whatever the exact stage decides about the others.
+// The price is steps 2-4 and the table m (4 bytes per instance and node block, written once and read
+// twice); when every block of every tile is listed (a code book of equal rows) the fine pass is the
+// whole one-level filter and the coarse pass is lost: a third more work in that worst case.
+#include "margin.hpp"
+
+namespace som {
+
+// One thread per instance; the table is read twice (the second time from L2: a workgroup's slice
+// is a few tens of KB), coalesced over the instances.
+__global__ __launch_bounds__(256) void k_select_blocks(const float *__restrict__ m, int64_t n, int blocks,
+                                                       const float *__restrict__ xn32,
+                                                       const unsigned *__restrict__ wmax_bits,
+                                                       const float *__restrict__ mu_norm2, MarginModel mm,
+                                                       int32_t *__restrict__ key, uint32_t *__restrict__ mask) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  float best = INFINITY;
+  int arg = 0;
+  for (int b = 0; b < blocks; ++b) {
+    const float v = m[(int64_t)b * n + j];
+    if (v < best) { best = v; arg = b; }
+  }
+  // score_margin is the bound for a PAIR of scores (2 e_j and slack): exactly the window of step 2
+  const double thr = (double)best + score_margin(mm, j, (double)xn32[j], (double)__uint_as_float(*wmax_bits), (double)*mu_norm2);
+  float t32 = (float)thr;                       // rounded up: no block inside the window is lost
+  if ((double)t32 < thr) t32 = nextafterf(t32, INFINITY);
+  if (!(best < INFINITY)) t32 = INFINITY;       // no finite score at all: every block stays in
+  key[j] = arg;
+  for (int w0 = 0; w0 < blocks; w0 += 32) {
+    uint32_t bits = 0;
+    const int top = blocks - w0 < 32 ? blocks - w0 : 32;
+    for (int b = 0; b < top; ++b) {
+      const float v = m[(int64_t)(w0 + b) * n + j];
+      bits |= (!(v > t32) ? 1u : 0u) << b;      // a NaN keeps its block in
+    }
+    mask[(int64_t)(w0 >> 5) * n + j] = bits;
+  }
+}
+
+// One wavefront per tile of 128 consecutive entries of `rows`: OR of their masks, expanded to a list.
+__global__ __launch_bounds__(256) void k_tile_lists(const uint32_t *__restrict__ mask, const int32_t *__restrict__ rows,
+                                                    int64_t n, int blocks, int64_t tiles,
+                                                    int32_t *__restrict__ tile_cnt, int32_t *__restrict__ tile_list) {
+  const int lane = threadIdx.x & 63;
+  const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (tile >= tiles) return;                    // uniform over the wavefront
+  const int64_t p0 = tile * 128 + lane, p1 = p0 + 64;
+  const int64_t r0 = p0 < n ? rows[p0] : -1, r1 = p1 < n ? rows[p1] : -1;
+  int32_t *out = tile_list + tile * blocks;
+  int count = 0;
+  for (int w0 = 0; w0 < blocks; w0 += 32) {
+    uint32_t bits = 0;
+    if (r0 >= 0) bits |= mask[(int64_t)(w0 >> 5) * n + r0];
+    if (r1 >= 0) bits |= mask[(int64_t)(w0 >> 5) * n + r1];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) bits |= __shfl_xor(bits, o, 64);
+    const bool set = lane < 32 && w0 + lane < blocks && ((bits >> lane) & 1u);
+    const unsigned long long bal = __ballot(set);
+    if (set) out[count + __popcll(bal & ((1ull << lane) - 1ull))] = w0 + lane;
+    count += __popcll(bal);
+  }
+  if (lane == 0) tile_cnt[tile] = count;
+}
+
+hipError_t launch_select_blocks(som_ctx *c, int64_t n) {
+  const int blocks = (c->k + 127) / 128;
+  hipLaunchKernelGGL(k_select_blocks, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, c->coarse_min, n,
+                     blocks, c->xn32, c->wmax_bits, c->mu_norm2, margin_model(c, kCertifyCoarse, nullptr),
+                     c->coarse_key, c->coarse_mask);
+  return hipGetLastError();
+}
+
+hipError_t launch_tile_lists(som_ctx *c, int64_t n) {
+  const int blocks = (c->k + 127) / 128;
+  const int64_t tiles = (n + 127) / 128;
+  hipLaunchKernelGGL(k_tile_lists, dim3((unsigned)((tiles + 3) / 4)), dim3(256), 0, c->stream, c->coarse_mask,
+                     c->sort_val[0], n, blocks, tiles, c->tile_cnt, c->tile_list);
+  return hipGetLastError();
+}
+
+}  // namespace som

@@ -342,31 +342,39 @@ static int radix_passes(int k) {
   return (bits + 7) / 8;
 }
 
-// Stable permutation of instance ids by BMU, segment offsets and counts.
-// On return c->sort_val[0] holds the permutation (c->sort_key[0] the sorted BMUs).
-hipError_t launch_sort_by_bmu(som_ctx *c, const int32_t *bmus, int64_t n) {
+// Stable permutation of the ids 0 .. n - 1 by integer keys in [0, key_range) (larger keys are clamped).
+// On return c->sort_val[0] holds the permutation, c->sort_key[0] the sorted keys.
+hipError_t launch_sort_keys(som_ctx *c, const int32_t *bmus, int64_t n, int key_range) {
   // Keys per wavefront of the scatter: small tiles give more parallelism, but the histogram of
   // 256 counters per tile is scanned by one workgroup, so their number is kept near 256.
   int64_t tile64 = ((n + 255) / 256 + 63) / 64 * 64;
   if (tile64 < kSortTile) tile64 = kSortTile;
   const int tile = (int)tile64;
   const int nblk = (int)((n + tile - 1) / tile);
-  const int passes = radix_passes(c->k);
+  const int passes = radix_passes(key_range);
   const int32_t *kin = bmus;
   const int32_t *vin = nullptr;
   // an even number of hops ends in buffer 0: start in buffer 1 when the pass count is even
   int dst = (passes % 2 == 0) ? 1 : 0;
   for (int p = 0; p < passes; ++p) {
-    hipLaunchKernelGGL(k_radix_hist, dim3(nblk), dim3(256), 0, c->stream, kin, n, 8 * p, nblk, tile, c->k,
+    hipLaunchKernelGGL(k_radix_hist, dim3(nblk), dim3(256), 0, c->stream, kin, n, 8 * p, nblk, tile, key_range,
                        c->radix_hist);
     hipLaunchKernelGGL(k_scan_exclusive, dim3(1), dim3(1024), 0, c->stream, c->radix_hist, c->radix_hist,
                        256 * nblk, 0);
     hipLaunchKernelGGL(k_radix_scatter, dim3(nblk), dim3(64), 0, c->stream, kin, vin, c->sort_key[dst],
-                       c->sort_val[dst], n, 8 * p, nblk, tile, c->k, c->radix_hist);
+                       c->sort_val[dst], n, 8 * p, nblk, tile, key_range, c->radix_hist);
     kin = c->sort_key[dst];
     vin = c->sort_val[dst];
     dst ^= 1;
   }
+  return hipGetLastError();
+}
+
+// Stable permutation of instance ids by BMU, segment offsets and counts.
+// On return c->sort_val[0] holds the permutation (c->sort_key[0] the sorted BMUs).
+hipError_t launch_sort_by_bmu(som_ctx *c, const int32_t *bmus, int64_t n) {
+  hipError_t e = launch_sort_keys(c, bmus, n, c->k);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_segment_bounds, dim3((c->k + 255) / 256), dim3(256), 0, c->stream, c->sort_key[0], n, c->k,
                      c->seg_off, c->counts);
   return hipGetLastError();

@@ -83,6 +83,25 @@ static void dev_free(T *&p) {
   p = nullptr;
 }
 
+// The dense filter runs on fp16 planes (one-level split pass or the two-level search).
+static bool uses_planes(const som_ctx *c) { return c->filter != SOM_FILTER_FP32; }
+
+// Two-level search for n instances?  Asked for outright, or by default when the map has enough node
+// blocks for the coarse pass to leave most of them out; never when its table of block minima would
+// not be a modest share of the device memory.
+static bool two_level(const som_ctx *c, int64_t n) {
+  if (c->filter != SOM_FILTER_TWO_LEVEL && c->filter != SOM_FILTER_AUTO) return false;
+  const int64_t blocks = (c->k + 127) / 128;
+  if (c->filter == SOM_FILTER_AUTO && blocks < kTwoLevelMinBlocks) return false;
+  return blocks * n * 4 <= kTwoLevelMaxTable;
+}
+
+// ... and its scratch is there (ensure_rows sizes it for the largest row count seen, whose table may not fit
+// when that of a smaller n would: then the one-level pass serves)
+static bool two_level_ready(const som_ctx *c, int64_t n) {
+  return two_level(c, n) && c->Xh1 != nullptr && c->Wh1 != nullptr && n <= c->n_cap;
+}
+
 static void free_row_scratch(som_ctx *c) {
   dev_free(c->xn32); dev_free(c->row_q); dev_free(c->cand_val); dev_free(c->cand_idx); dev_free(c->cand_over);
   dev_free(c->cand_n); dev_free(c->refine_list); dev_free(c->rescan_list);
@@ -90,6 +109,8 @@ static void free_row_scratch(som_ctx *c) {
   dev_free(c->sort_key[0]); dev_free(c->sort_key[1]); dev_free(c->sort_val[0]); dev_free(c->sort_val[1]);
   dev_free(c->radix_hist); dev_free(c->chunk_node); dev_free(c->partial);
   dev_free(c->Xh); dev_free(c->xscale);
+  dev_free(c->Xh1); dev_free(c->coarse_min); dev_free(c->coarse_key); dev_free(c->coarse_mask);
+  dev_free(c->tile_cnt); dev_free(c->tile_list);
   c->n_cap = 0;
   c->cand_cap = 0;
   c->d_norms_valid = 0;
@@ -98,9 +119,12 @@ static void free_row_scratch(som_ctx *c) {
 
 // Scratch that scales with the number of instances; grown (never shrunk) on demand.
 static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
-  const bool split = dense && c->filter == SOM_FILTER_SPLIT_F16;
+  const bool split = dense && uses_planes(c);
+  // sized for the rows the scratch is (or will be) allocated for, so that it serves every n up to n_cap
+  const bool coarse = split && two_level(c, n > c->n_cap ? n : c->n_cap);
   const bool need_partial = (dense && (c->partial == nullptr || c->Wc == nullptr)) || c->collect_list == nullptr ||
-                            (split && (c->Xh == nullptr || c->Wh == nullptr));
+                            (split && (c->Xh == nullptr || c->Wh == nullptr)) ||
+                            (coarse && (c->Xh1 == nullptr || c->Wh1 == nullptr));
   if (n <= c->n_cap && !need_partial) return SOM_OK;
   if (n > c->n_cap) {
     (void)hipStreamSynchronize(c->stream);
@@ -144,12 +168,29 @@ static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
         return fail(c, SOM_ERR_ALLOC, "cannot allocate the fp16 planes of %lld instances", (long long)c->n_cap);
     }
   }
+  if (coarse) {
+    const size_t row_halves = (size_t)((c->dim + 63) / 64) * 64;
+    const size_t blocks = (size_t)(c->k + 127) / 128, tiles = ((size_t)c->n_cap + 127) / 128;
+    if (c->Wh1 == nullptr && !dev_alloc(&c->Wh1, (size_t)c->k * row_halves))
+      return fail(c, SOM_ERR_ALLOC, "cannot allocate the fp16 plane of the code book");
+    if (c->Xh1 == nullptr) {
+      c->d_split_valid = 0;
+      if (!(dev_alloc(&c->Xh1, (size_t)c->n_cap * row_halves) && dev_alloc(&c->coarse_min, blocks * (size_t)c->n_cap) &&
+            dev_alloc(&c->coarse_key, (size_t)c->n_cap) && dev_alloc(&c->coarse_mask, (blocks + 31) / 32 * (size_t)c->n_cap) &&
+            dev_alloc(&c->tile_cnt, tiles) && dev_alloc(&c->tile_list, tiles * blocks))) {
+        dev_free(c->Xh1); dev_free(c->coarse_min); dev_free(c->coarse_key); dev_free(c->coarse_mask);
+        dev_free(c->tile_cnt); dev_free(c->tile_list);
+        return fail(c, SOM_ERR_ALLOC, "cannot allocate the two-level search's scratch for %lld instances", (long long)c->n_cap);
+      }
+    }
+  }
   return SOM_OK;
 }
 
 // The dense fp32 pass writes one candidate list per node group and instance.
 static int ensure_candidates(som_ctx *c, int64_t n, bool dense) {
-  const int groups_h = dense && c->filter == SOM_FILTER_SPLIT_F16 ? bmu_dense_h_groups(c, n) : 1;
+  int groups_h = dense && uses_planes(c) ? bmu_dense_h_groups(c, n) : 1;
+  if (dense && two_level_ready(c, n) && bmu_dense_h_fine_groups(c, n) > groups_h) groups_h = bmu_dense_h_fine_groups(c, n);
   const int groups_f = dense ? bmu_dense_groups(c, n) : 8 * c->csr_sweeps;      // sparse: one list per node range
   const int64_t need = (int64_t)(groups_h > groups_f ? groups_h : groups_f) * n;
   if (!dense && n * c->csr_sweeps > c->unit_cap) {
@@ -225,7 +266,8 @@ struct StageTimer {
 // for the split-fp16 filter the fp16 planes of both operands.
 static int prepare_dense(som_ctx *c, const float *X, int64_t n, const float *W, bool have_xn) {
   StageTimer t(c, 5);
-  const bool split = c->filter == SOM_FILTER_SPLIT_F16;
+  const bool split = uses_planes(c);
+  const bool coarse = two_level_ready(c, n);
   if (!have_xn) {
     c->d_norms_valid = 0;
     c->d_split_valid = 0;
@@ -234,12 +276,14 @@ static int prepare_dense(som_ctx *c, const float *X, int64_t n, const float *W, 
     SOM_LAUNCH(c, launch_row_sqnorms(c, X, n, c->dim, split ? c->mu : nullptr, c->xn32, nullptr, nullptr));
   }
   if (split && !(have_xn && c->d_split_valid)) {
-    SOM_LAUNCH(c, launch_split_rows_f16(c, X, n, nullptr, c->mu, c->Xh, c->xscale));
+    SOM_LAUNCH(c, launch_split_rows_f16(c, X, n, nullptr, c->mu, c->Xh, c->xscale, 0, coarse ? c->Xh1 : nullptr));
     c->d_split_valid = have_xn ? 1 : 0;
   }
   SOM_LAUNCH(c, launch_center_codebook(c, W, true, false, split));
   if (c->nb_function == SOM_NEIGHBORHOOD_BUBBLE) SOM_LAUNCH(c, launch_mask_duplicate_rows(c, W));
-  if (split) SOM_LAUNCH(c, launch_split_rows_f16(c, c->Wc, c->k, c->wmax_bits + 1, nullptr, c->Wh, c->wscale));
+  if (split)
+    SOM_LAUNCH(c, launch_split_rows_f16(c, c->Wc, c->k, c->wmax_bits + 1, nullptr, c->Wh, c->wscale, 0,
+                                        coarse ? c->Wh1 : nullptr));
   SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 3));
   return SOM_OK;
 }
@@ -248,14 +292,24 @@ static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *
   int rc = ensure_candidates(c, n, true);
   if (!rc) rc = prepare_dense(c, X, n, W, have_xn);
   if (rc) return rc;
-  const bool split = c->filter == SOM_FILTER_SPLIT_F16;
+  const bool split = uses_planes(c);
+  const bool coarse = two_level_ready(c, n);
   {
     StageTimer t(c, 0);
-    if (split) SOM_LAUNCH(c, launch_bmu_dense_h(c, n, nullptr));
-    else SOM_LAUNCH(c, launch_bmu_dense(c, X, n, nullptr));
+    if (coarse) {
+      SOM_LAUNCH(c, launch_bmu_block_min(c, n));
+      SOM_LAUNCH(c, launch_select_blocks(c, n));
+      SOM_LAUNCH(c, launch_sort_keys(c, c->coarse_key, n, (c->k + 127) / 128));
+      SOM_LAUNCH(c, launch_tile_lists(c, n));
+      SOM_LAUNCH(c, launch_bmu_dense_h_fine(c, n));
+    } else if (split) {
+      SOM_LAUNCH(c, launch_bmu_dense_h(c, n, nullptr));
+    } else {
+      SOM_LAUNCH(c, launch_bmu_dense(c, X, n, nullptr));
+    }
   }
   StageTimer t(c, 2);
-  SOM_LAUNCH(c, launch_certify(c, n, split ? bmu_dense_h_groups(c, n) : bmu_dense_groups(c, n),
+  SOM_LAUNCH(c, launch_certify(c, n, coarse ? bmu_dense_h_fine_groups(c, n) : split ? bmu_dense_h_groups(c, n) : bmu_dense_groups(c, n),
                                split ? kCertifySplit : kCertifyFp32, nullptr, bmus));
   SOM_LAUNCH(c, launch_refine_dense(c, X, W, bmus));
   if (split) SOM_LAUNCH(c, launch_bmu_dense_h_collect(c, n));
@@ -362,7 +416,7 @@ static int registered_norms(som_ctx *c) {
     SOM_LAUNCH(c, launch_sample_col_means(c, c->d_data, c->d_n, c->dim, c->mu));
     SOM_LAUNCH(c, launch_vec_sqnorm(c, c->mu, c->dim, c->mu_norm2));
     // the split-fp16 filter works on centred instances, and its margin on their norms
-    SOM_LAUNCH(c, launch_row_sqnorms(c, c->d_data, c->d_n, c->dim, c->filter == SOM_FILTER_SPLIT_F16 ? c->mu : nullptr,
+    SOM_LAUNCH(c, launch_row_sqnorms(c, c->d_data, c->d_n, c->dim, uses_planes(c) ? c->mu : nullptr,
                                      c->xn32, nullptr, nullptr));
   } else {
     SOM_LAUNCH(c, launch_csr_row_sqnorms(c, c->d_indptr, c->d_values, c->d_n, c->xn32));
@@ -472,7 +526,7 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
   c->map_type = map_type; c->grid_type = grid_type;
   c->stream = (hipStream_t)hip_stream;
   csr_slice_geometry(c->k, &c->csr_acc, &c->csr_sweeps, &c->kpad);
-  c->filter = SOM_FILTER_SPLIT_F16;
+  c->filter = SOM_FILTER_AUTO;
   c->scale_cooling = -1;
   c->hot_enabled = 1;
   c->smooth_mfma_min = kSmoothMfmaMin;
@@ -535,7 +589,7 @@ void som_destroy(som_ctx *c) {
   dev_free(c->col_range); dev_free(c->qstep); dev_free(c->qstep_max_bits); dev_free(c->ct_partial); dev_free(c->H2);
   dev_free(c->GxT); dev_free(c->GyT); dev_free(c->hit_x); dev_free(c->hit_n); dev_free(c->hit_rows);
   dev_free(c->mu); dev_free(c->mu_partial); dev_free(c->Wc); dev_free(c->zero16); dev_free(c->mu_norm2);
-  dev_free(c->Wh); dev_free(c->wscale);
+  dev_free(c->Wh); dev_free(c->Wh1); dev_free(c->wscale);
   free_hot(c);
   dev_free(c->hot_counts); dev_free(c->hot_rank); dev_free(c->hot_cols); dev_free(c->hot_Wc); dev_free(c->hot_Wh);
   dev_free(c->hot_wscale); dev_free(c->hot_wmax_bits);
@@ -856,7 +910,8 @@ int som_set_smoothing(som_ctx *c, int form) {
 
 int som_set_filter(som_ctx *c, int filter) {
   if (!c) return SOM_ERR_INVALID_ARG;
-  if (filter != SOM_FILTER_FP32 && filter != SOM_FILTER_SPLIT_F16)
+  if (filter != SOM_FILTER_FP32 && filter != SOM_FILTER_SPLIT_F16 && filter != SOM_FILTER_TWO_LEVEL &&
+      filter != SOM_FILTER_AUTO)
     return fail(c, SOM_ERR_INVALID_ARG, "unknown filter %d", filter);
   if (filter != c->filter) {           // norms and planes of a registered set belong to the filter they were made for
     c->d_norms_valid = 0;
@@ -875,10 +930,11 @@ int som_debug_scores_dense(som_ctx *c, const float *data, int64_t n, const float
   if (!rc) rc = ensure_candidates(c, n, true);
   if (!rc) rc = prepare_dense(c, data, n, codebook, false);
   if (rc) return rc;
-  const bool split = c->filter == SOM_FILTER_SPLIT_F16;
-  if (split) SOM_LAUNCH(c, launch_bmu_dense_h(c, n, scores));
+  const bool split = uses_planes(c);
+  const bool coarse = c->filter == SOM_FILTER_TWO_LEVEL && two_level_ready(c, n);    // asked for by name: its coarse scores
+  if (split) SOM_LAUNCH(c, launch_bmu_dense_h(c, n, scores, coarse));
   else SOM_LAUNCH(c, launch_bmu_dense(c, data, n, scores));
-  SOM_LAUNCH(c, launch_margins(c, n, split ? kCertifySplit : kCertifyFp32, nullptr, margin_out));
+  SOM_LAUNCH(c, launch_margins(c, n, coarse ? kCertifyCoarse : split ? kCertifySplit : kCertifyFp32, nullptr, margin_out));
   SOM_LAUNCH(c, hipMemcpyAsync(mu_out, c->mu, (size_t)c->dim * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
   return SOM_OK;
 }

@@ -88,6 +88,7 @@ struct som_ctx {
   unsigned *qstep_max_bits;   // [1] bit pattern of the largest step
   float *Wc;              // [k][dim] centred code book w' = fl(w - mu) of the dense BMU search (lazily allocated)
   _Float16 *Wh;           // [k][ceil(dim/32)][64] centred code book as fp16 hi/lo planes (lazily allocated)
+  _Float16 *Wh1;          // [k][ceil(dim/64)][64] its hi halves alone (two-level search)
   float *wscale;          // [1] the power of two the centred code book was divided by
   int filter;             // SOM_FILTER_*: which matrix format the dense BMU filter runs on
   float *zero16;          // 64 bytes of zeros: source of out-of-range direct-to-LDS loads
@@ -103,6 +104,13 @@ struct som_ctx {
   float *row_q;           // [n] sparse rows: sum over the nonzeros of |value| x quantisation step of the column
   _Float16 *Xh;           // [n][ceil(dim/32)][64] dense instances as fp16 hi/lo planes (lazily allocated)
   float *xscale;          // [n] the power of two each instance was divided by
+  // two-level dense search (bmu_two_level.hip), lazily allocated with Xh
+  _Float16 *Xh1;          // [n][ceil(dim/64)][64] the hi halves alone
+  float *coarse_min;      // [ceil(k/128)][n] smallest coarse score per node block and instance
+  int32_t *coarse_key;    // [n] node block of every instance's smallest coarse score
+  uint32_t *coarse_mask;  // [ceil(blocks/32)][n] node blocks an instance's BMU may lie in
+  int32_t *tile_cnt;      // [ceil(n/128)] node blocks listed per instance tile of the sorted order
+  int32_t *tile_list;     // [ceil(n/128)][ceil(k/128)] those blocks, ascending
   int64_t cand_cap;       // instance slots in the three candidate arrays (node groups x instances)
   float *cand_val;        // [groups][n][kCand]
   int32_t *cand_idx;      // [groups][n][kCand]
@@ -191,12 +199,23 @@ hipError_t launch_bmu_dense_dl(som_ctx *c, const float *X, int64_t n, dim3 grid,
 // before it adds them to the running totals (a power of two; the margin prices the chain length).
 // Longer chains save additions and widen the margin: measured, four chunks pay from 256 features on.
 inline int split_flush_chunks(int dim) { return dim >= 256 ? 4 : 2; }
+// Two-level search (bmu_two_level.hip): by default from this many node blocks of 128 on, and only
+// while its table of block minima stays under this many bytes.
+constexpr int kTwoLevelMinBlocks = 8;
+constexpr int64_t kTwoLevelMaxTable = 8ll << 30;
 int bmu_dense_h_groups(const som_ctx *c, int64_t n);
-hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump);            // Xh, Wh -> candidates (or all scores)
+hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump, bool coarse = false);   // Xh, Wh -> candidates (or all scores)
+int bmu_dense_h_fine_groups(const som_ctx *c, int64_t n);
+hipError_t launch_bmu_block_min(som_ctx *c, int64_t n);                        // Xh1, Wh1 -> coarse_min
+hipError_t launch_bmu_dense_h_fine(som_ctx *c, int64_t n);                     // sort_val[0], tile_cnt, tile_list -> candidates
+// bmu_two_level.hip
+hipError_t launch_select_blocks(som_ctx *c, int64_t n);                        // coarse_min -> coarse_key, coarse_mask
+hipError_t launch_tile_lists(som_ctx *c, int64_t n);                           // coarse_mask, sort_val[0] -> tile_cnt, tile_list
 hipError_t launch_bmu_dense_h_collect(som_ctx *c, int64_t n);                 // rows of collect_rows -> collect_list
 hipError_t launch_split_rows_f16(som_ctx *c, const float *A, int64_t nrows, const unsigned *global_max_bits,
                                  const float *mu /* subtracted first, or null */, _Float16 *out, float *scale_out,
-                                 int dim = 0 /* row length; 0: the context's */);
+                                 int dim = 0 /* row length; 0: the context's */,
+                                 _Float16 *out_hi = nullptr /* the hi halves alone, rows padded to 64 columns */);
 hipError_t launch_probe_mfma_f16(hipStream_t stream, const uint16_t *A, const uint16_t *B, const float *C, float *D,
                                  int count);
 
@@ -211,7 +230,7 @@ struct UnitWork {
 };
 constexpr int kListCounts = 12;    // words in som_ctx::list_counts
 constexpr int kUnitCounts = 4;     // first of the eight work-list lengths in it
-enum { kCertifyFp32 = 0, kCertifySplit = 1, kCertifyCsr = 2 };      // whose rounding bound the margin uses
+enum { kCertifyFp32 = 0, kCertifySplit = 1, kCertifyCsr = 2, kCertifyCoarse = 3 };      // whose rounding bound the margin uses
 hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int64_t *indptr, int32_t *bmus,
                           bool hot = false);
 hipError_t launch_margins(som_ctx *c, int64_t n, int mode, const int64_t *indptr, double *out,
@@ -262,6 +281,7 @@ hipError_t launch_bmu_csr_sliced(som_ctx *c, const int64_t *indptr, const int32_
 
 // segsum.hip
 hipError_t launch_sort_by_bmu(som_ctx *c, const int32_t *bmus, int64_t n);   // -> sort_val[0] = row ids
+hipError_t launch_sort_keys(som_ctx *c, const int32_t *keys, int64_t n, int key_range);   // the permutation alone
 hipError_t launch_accumulate_dense(som_ctx *c, const float *X, int64_t n);   // -> S, counts
 hipError_t launch_accumulate_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices,
                                  const float *values, int64_t n, const int32_t *bmus);   // -> S, counts

@@ -12,6 +12,8 @@
 // Storage: rows are padded to whole chunks of 32 columns, and chunk t of a row is 128 bytes:
 // the 32 hi halves of columns 32 t .. 32 t + 31, then their 32 lo halves.  That is exactly the
 // shape of one LDS tile row of the filter kernel (bmu_dense_h.hip).  Padding columns are zero.
+// The coarse pass of the two-level search reads the hi halves alone: a second copy, rows padded to
+// whole chunks of 64 columns, 128 bytes per chunk again.
 #include "som_internal.hpp"
 
 #include <math.h>
@@ -39,11 +41,13 @@ template <int kTeam>
 __global__ __launch_bounds__(256) void k_split_rows_f16(const float *__restrict__ A, int64_t nrows, int dim, int nK,
                                                         const unsigned *__restrict__ global_max_bits,
                                                         const float *__restrict__ mu,
-                                                        _Float16 *__restrict__ out, float *__restrict__ scale_out) {
+                                                        _Float16 *__restrict__ out, float *__restrict__ scale_out,
+                                                        _Float16 *__restrict__ out_hi) {
   __shared__ float smax[4];
   constexpr int kTeams = 256 / kTeam;
   const int tl = threadIdx.x % kTeam, team = threadIdx.x / kTeam;
   const int padded = nK * 32;
+  const int padded_hi = (nK + 1) / 2 * 64;
   for (int64_t r = (int64_t)blockIdx.x * kTeams + team; r < nrows; r += (int64_t)gridDim.x * kTeams) {
     const float *a = A + r * dim;
     float m;
@@ -75,12 +79,16 @@ __global__ __launch_bounds__(256) void k_split_rows_f16(const float *__restrict_
       const int at = (c >> 5) * 64 + (c & 31);
       o[at] = hi;
       o[at + 32] = lo;
+      if (out_hi) out_hi[r * (int64_t)padded_hi + c] = hi;
+    }
+    if (out_hi && padded_hi > padded) {
+      for (int c = padded + tl; c < padded_hi; c += kTeam) out_hi[r * (int64_t)padded_hi + c] = (_Float16)0.f;
     }
   }
 }
 
 hipError_t launch_split_rows_f16(som_ctx *c, const float *A, int64_t nrows, const unsigned *global_max_bits,
-                                 const float *mu, _Float16 *out, float *scale_out, int dim) {
+                                 const float *mu, _Float16 *out, float *scale_out, int dim, _Float16 *out_hi) {
   if (dim <= 0) dim = c->dim;
   const int nK = (dim + 31) / 32;
   const int64_t cap = (int64_t)c->n_cu * 16;
@@ -88,11 +96,11 @@ hipError_t launch_split_rows_f16(som_ctx *c, const float *A, int64_t nrows, cons
     int64_t blocks = (nrows + 3) / 4;
     if (blocks > cap) blocks = cap;
     hipLaunchKernelGGL(k_split_rows_f16<64>, dim3((unsigned)blocks), dim3(256), 0, c->stream, A, nrows, dim, nK,
-                       global_max_bits, mu, out, scale_out);
+                       global_max_bits, mu, out, scale_out, out_hi);
   } else {
     int64_t blocks = nrows < cap ? nrows : cap;
     hipLaunchKernelGGL(k_split_rows_f16<256>, dim3((unsigned)blocks), dim3(256), 0, c->stream, A, nrows, dim, nK,
-                       global_max_bits, mu, out, scale_out);
+                       global_max_bits, mu, out, scale_out, out_hi);
   }
   return hipGetLastError();
 }

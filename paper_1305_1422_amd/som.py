@@ -11,7 +11,8 @@ from . import capi
 MAP_TYPES = {"planar": capi.SOM_MAP_PLANAR, "toroid": capi.SOM_MAP_TOROID}
 GRID_TYPES = {"square": capi.SOM_GRID_SQUARE, "hexagonal": capi.SOM_GRID_HEXAGONAL}
 COOLING = {"linear": capi.SOM_COOL_LINEAR, "exponential": capi.SOM_COOL_EXPONENTIAL}
-FILTERS = {"fp32": capi.SOM_FILTER_FP32, "split_f16": capi.SOM_FILTER_SPLIT_F16}
+FILTERS = {"fp32": capi.SOM_FILTER_FP32, "split_f16": capi.SOM_FILTER_SPLIT_F16,
+           "two_level": capi.SOM_FILTER_TWO_LEVEL, "auto": capi.SOM_FILTER_AUTO}
 NEIGHBORHOODS = {"gaussian": capi.SOM_NEIGHBORHOOD_GAUSSIAN, "bubble": capi.SOM_NEIGHBORHOOD_BUBBLE}
 
 

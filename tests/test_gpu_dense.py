@@ -14,9 +14,9 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 
-@pytest.fixture(autouse=True, params=["split_f16", "fp32"])
+@pytest.fixture(autouse=True, params=["split_f16", "fp32", "two_level"])
 def dense_filter(request):
-    """Every test of this module runs with both arithmetic variants of the dense BMU filter."""
+    """Every test of this module runs with every variant of the dense BMU filter."""
     from paper_1305_1422_amd import Som
     old = Som.default_filter
     Som.default_filter = request.param
@@ -336,7 +336,7 @@ def test_long_instances_take_the_workgroup_per_row_split(oracle):
     som.close()
 
 
-def test_one_context_serves_growing_and_shrinking_data_and_both_filters(oracle):
+def test_one_context_serves_growing_and_shrinking_data_and_every_filter(oracle):
     """The per-data scratch grows on demand and is reused for smaller sets; changing the filter variant in
     between must not leave stale planes or candidate arrays behind."""
     from paper_1305_1422_amd import Som
@@ -344,8 +344,8 @@ def test_one_context_serves_growing_and_shrinking_data_and_both_filters(oracle):
     dim, rows, cols = 70, 15, 14
     W = rng.random((rows * cols, dim)).astype(np.float32)
     som = Som(rows, cols, dim, codebook=torch.from_numpy(W))
-    for n, filt in [(100, "split_f16"), (5000, "split_f16"), (300, "fp32"), (7000, "fp32"), (64, "split_f16"),
-                    (7000, "split_f16")]:
+    for n, filt in [(100, "split_f16"), (5000, "two_level"), (300, "fp32"), (7000, "fp32"), (64, "two_level"),
+                    (7000, "split_f16"), (9000, "two_level"), (6000, "auto")]:
         som.set_filter(filt)
         X = rng.random((n, dim)).astype(np.float32)
         b = som.bmus(P.to_dev(X)).cpu().numpy()

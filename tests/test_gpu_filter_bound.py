@@ -121,7 +121,7 @@ def _score_bound_case(x, w, rows, cols, filter="split_f16"):
     M = np.sqrt((mu64 ** 2).sum())
     # the rounding of w - mu is part of the library's bound but not of this comparison (the exact
     # scores above start from the rounded w'), so the bound tested here is slightly larger than needed
-    if filter == "split_f16":
+    if filter in ("split_f16", "two_level"):
         # this filter multiplies centred instances x' = fl(x - mu): their norms and scales enter the bound,
         # |mu| does not (what the rounding of x - mu adds for all nodes alike cancels in every comparison)
         xc64 = (x - mu32[None, :]).astype(np.float32).astype(np.float64)
@@ -130,7 +130,10 @@ def _score_bound_case(x, w, rows, cols, filter="split_f16"):
         sw = float(_pow2_above(np.abs(wc64).max()))
         f = 4 if dim >= 256 else 2                                 # chunks of 32 features between two flushes
         g = 2.5 * 6 * f + 9 + np.ceil(dim / (32 * f)) + 2
-        B = U * ((2 * g + 30) * Xc * Wm + np.sqrt(dim) * (sx * Wm + sw * Xc) + 4 * Wm ** 2)
+        # two_level: the scores of its coarse pass, one product of operands rounded to 11 bits
+        # (2 (2^14 + 8) u X Wm for the roundings of the two rows, doubled by the factor -2)
+        split = 30 if filter == "split_f16" else 2 * (16384 + 8) + 6
+        B = U * ((2 * g + split) * Xc * Wm + np.sqrt(dim) * (sx * Wm + sw * Xc) + 4 * Wm ** 2)
         # the constant 2 delta.x' that the rounding delta of x - mu adds to every score of an instance is no
         # error of the ranking: compare after removing each instance's mean difference
         s_exact = s_exact + np.mean(s_gpu - s_exact, axis=1, keepdims=True)
@@ -175,7 +178,7 @@ def _dense_case(case, rng, rows, cols):
     return x.astype(np.float32), w.astype(np.float32)
 
 
-@pytest.mark.parametrize("filter", ["split_f16", "fp32"])
+@pytest.mark.parametrize("filter", ["split_f16", "fp32", "two_level"])
 @pytest.mark.parametrize("case", ["uniform", "offset_mixture", "heavy_tail", "tiny_and_huge_rows", "ragged_dim",
                                   "odd_dim"])
 def test_filter_scores_stay_within_the_bound(case, filter):

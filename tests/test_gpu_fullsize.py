@@ -15,9 +15,9 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 
-@pytest.fixture(autouse=True, params=["split_f16", "fp32"])
+@pytest.fixture(autouse=True, params=["split_f16", "fp32", "two_level"])
 def dense_filter(request):
-    """Every test of this module runs with both arithmetic variants of the dense BMU filter."""
+    """Every test of this module runs with every variant of the dense BMU filter."""
     from paper_1305_1422_amd import Som
     old = Som.default_filter
     Som.default_filter = request.param
@@ -28,7 +28,7 @@ def dense_filter(request):
 def _epochs(oracle, cfg, radii, n_rows=48, n_nodes=32):
     from paper_1305_1422_amd import Som, capi
     w = make_workload(cfg)
-    if w.kind == "csr" and Som.default_filter == "fp32":
+    if w.kind == "csr" and Som.default_filter != "split_f16":
         pytest.skip("the sparse path has a single filter; covered by the other parametrisation")
     rng = np.random.default_rng(1000 + cfg)
     X = w.data()

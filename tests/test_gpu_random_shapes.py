@@ -1,4 +1,4 @@
-"""Seeded sweep over random valid shapes: dense and sparse data, both filters, every map and grid type,
+"""Seeded sweep over random valid shapes: dense and sparse data, every filter, every map and grid type,
 every neighbourhood, ragged sizes of all kinds, two epochs each, compared with the oracle element by
 element (gpu tests, through the C ABI)."""
 import numpy as np
@@ -26,7 +26,7 @@ def test_random_shape(oracle, case):
     grid = ["square", "hexagonal"][int(rng.integers(0, 2))]
     radius = float(np.float32(rng.uniform(0.3, max(rows, cols))))
     name, compact, function = NEIGHBOURHOODS[case % 3]
-    filt = ["split_f16", "fp32"][(case // 2) % 2]
+    filt = ["split_f16", "fp32", "two_level"][(case // 2) % 3]
     W = (rng.random((rows * cols, dim)) * rng.choice([1.0, 0.05, 20.0])).astype(np.float32)
     if dense:
         X = (rng.random((n, dim)) * rng.choice([1.0, 0.05, 20.0])).astype(np.float32)
