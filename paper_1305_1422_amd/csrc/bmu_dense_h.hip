@@ -314,14 +314,16 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
     multiply(op1, false);
 
     const bool last_k = (kc == nK - 1);
-    fresh = last_k || ((kc + flush_phase) & flush_mask) == flush_mask;
+    // (hi-only planes: the products carry 11 bits, so the fp32 accumulators run through the whole node
+    // block and are the totals)
+    fresh = last_k || (!kCoarse && ((kc + flush_phase) & flush_mask) == flush_mask);
     if (fresh) {
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) tot[mi][ni][v] += acc[mi][ni][v];
+          for (int v = 0; v < 16; ++v) tot[mi][ni][v] = kCoarse ? acc[mi][ni][v] : tot[mi][ni][v] + acc[mi][ni][v];
     }
     if (last_k) {
       const int nb = kFine ? blist[nb_first + ord] : nb_first + ord;
@@ -334,9 +336,11 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
 #pragma unroll
           for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              m = fminf(m, fmaf(factor[ni], tot[mi][ni][v], sWn[ord & 3][wm * 64 + mfma_row(mi, v, lhi)]));
-              tot[mi][ni][v] = 0.f;
+            for (int v = 0; v < 16; v += 2) {          // pairs: one three-way minimum per two scores
+              const float s0 = fmaf(factor[ni], tot[mi][ni][v], sWn[ord & 3][wm * 64 + mfma_row(mi, v, lhi)]);
+              const float s1 = fmaf(factor[ni], tot[mi][ni][v + 1], sWn[ord & 3][wm * 64 + mfma_row(mi, v + 1, lhi)]);
+              m = fminf(fminf(m, s0), s1);
+              tot[mi][ni][v] = tot[mi][ni][v + 1] = 0.f;
             }
           m = fminf(m, __shfl_xor(m, 32, 64));
           block_min[ni] = m;

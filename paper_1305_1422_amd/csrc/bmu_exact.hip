@@ -455,10 +455,12 @@ MarginModel margin_model(const som_ctx *c, int mode, const int64_t *indptr, bool
     // operand element v / scale is rounded to 11 significant bits, |dv| <= 2^-11 |v| + 2^-25 scale, so by
     // Cauchy-Schwarz the dot product of the rounded rows is off by at most
     //   |dx| |w'| + |hi_x| |dw| <= (2 + 2^-11) 2^-11 X Wm + floor terms = (2^14 + 8) u X Wm + ...,
-    // doubled by the factor -2 of the score.  Accumulation (fewer instructions per flush interval than the
-    // split pass, priced like it), the stored c_i, the final multiply-add and the roundings of w - mu and
-    // x - mu as in the split model.
-    mm.coef_xw = 2.0 * (16384.0 + 8.0) + 2.0 * split_pass_roundings(c->dim) + 4.0 + 2.0;
+    // doubled by the factor -2 of the score.  Accumulation: one chain of ceil(dim / 16) matrix instructions
+    // per score, never flushed, priced per instruction like the split pass (2.5 u of the running sum each,
+    // 9 u of the largest product once, + 2).  The stored c_i, the final multiply-add and the roundings of
+    // w - mu and x - mu as in the split model.
+    const double chain = 2.5 * (double)((c->dim + 15) / 16) + 9.0 + 2.0;
+    mm.coef_xw = 2.0 * (16384.0 + 8.0) + 2.0 * chain + 4.0 + 2.0;
     mm.coef_floor = sqrt((double)c->dim);        // 2^-25 per element and operand, doubled = u
     mm.xscale = c->xscale;
     mm.wscale = c->wscale;

@@ -10,10 +10,13 @@
 //   2. k_select_blocks: with m_j = min_b m[b][j], the BMU of j lies in a block with
 //      m[b][j] <= m_j + 2 e_j - a node of any other block has an exact score above that of the node
 //      that gave m_j, strictly, so it is not the BMU and does not tie with it.  The kernel writes that
-//      block set as a bit mask and the block of m_j as a sort key;
-//   3. the instances are put in the order of their keys (segsum.hip's radix sort): neighbours in that
-//      order have their best nodes in the same block and, on a map that has begun to order itself,
-//      nearly the same block sets;
+//      block set as a bit mask, and a sort key made of the size class of the set (1, 2, 3-4, 5-8, ...
+//      blocks) and its lowest block;
+//   3. the instances are put in the order of their keys (segsum.hip's radix sort).  A fine-pass tile
+//      works on the union of its 128 instances' sets, so one instance with a wide set (one that lies
+//      between clusters, say) makes its whole tile expensive: the size class keeps such instances among
+//      themselves, and within a class the lowest block puts instances with nearly the same sets side
+//      by side (on a map that has begun to order itself the sets are runs of neighbouring blocks);
 //   4. k_tile_lists: the union of the masks over every 128 consecutive instances of that order, as an
 //      ascending list of blocks;
 //   5. fine pass (k_bmu_dense_h, fine mode): the split-fp16 filter over those (tile, block) pairs only.
@@ -26,36 +29,63 @@
 
 namespace som {
 
-// One thread per instance; the table is read twice (the second time from L2: a workgroup's slice
-// is a few tens of KB), coalesced over the instances.
+// Four threads per instance (one per wavefront of the workgroup, so that a wavefront reads 64 consecutive
+// instances of a table row); they share out the blocks for the minimum and the 32-block words of the mask
+// and combine through LDS.  The table is read twice, the second time from L2 (a workgroup's slice is a few
+// tens of KB).
 __global__ __launch_bounds__(256) void k_select_blocks(const float *__restrict__ m, int64_t n, int blocks,
                                                        const float *__restrict__ xn32,
                                                        const unsigned *__restrict__ wmax_bits,
                                                        const float *__restrict__ mu_norm2, MarginModel mm,
                                                        int32_t *__restrict__ key, uint32_t *__restrict__ mask) {
-  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= n) return;
+  __shared__ float s_best[4][64];
+  __shared__ int s_listed[4][64], s_lowest[4][64];
+  const int lane = threadIdx.x & 63, part = threadIdx.x >> 6;
+  const int64_t j = (int64_t)blockIdx.x * 64 + lane;
+  const bool live = j < n;
   float best = INFINITY;
-  int arg = 0;
-  for (int b = 0; b < blocks; ++b) {
-    const float v = m[(int64_t)b * n + j];
-    if (v < best) { best = v; arg = b; }
+  if (live)
+    for (int b = part; b < blocks; b += 4) best = fminf(best, m[(int64_t)b * n + j]);
+  s_best[part][lane] = best;
+  __syncthreads();
+  best = fminf(fminf(s_best[0][lane], s_best[1][lane]), fminf(s_best[2][lane], s_best[3][lane]));
+  float t32 = INFINITY;                         // no finite score at all: every block stays in
+  if (live && best < INFINITY) {
+    // score_margin is the bound for a PAIR of scores (2 e_j and slack): exactly the window of step 2
+    const double thr = (double)best + score_margin(mm, j, (double)xn32[j], (double)__uint_as_float(*wmax_bits), (double)*mu_norm2);
+    t32 = (float)thr;                           // rounded up: no block inside the window is lost
+    if ((double)t32 < thr) t32 = nextafterf(t32, INFINITY);
   }
-  // score_margin is the bound for a PAIR of scores (2 e_j and slack): exactly the window of step 2
-  const double thr = (double)best + score_margin(mm, j, (double)xn32[j], (double)__uint_as_float(*wmax_bits), (double)*mu_norm2);
-  float t32 = (float)thr;                       // rounded up: no block inside the window is lost
-  if ((double)t32 < thr) t32 = nextafterf(t32, INFINITY);
-  if (!(best < INFINITY)) t32 = INFINITY;       // no finite score at all: every block stays in
-  key[j] = arg;
-  for (int w0 = 0; w0 < blocks; w0 += 32) {
-    uint32_t bits = 0;
-    const int top = blocks - w0 < 32 ? blocks - w0 : 32;
-    for (int b = 0; b < top; ++b) {
-      const float v = m[(int64_t)(w0 + b) * n + j];
-      bits |= (!(v > t32) ? 1u : 0u) << b;      // a NaN keeps its block in
+  int listed = 0, lowest = 0x7fffffff;
+  if (live) {
+    for (int w0 = 32 * part; w0 < blocks; w0 += 128) {
+      uint32_t bits = 0;
+      const int top = blocks - w0 < 32 ? blocks - w0 : 32;
+      for (int b = 0; b < top; ++b) {
+        const float v = m[(int64_t)(w0 + b) * n + j];
+        bits |= (!(v > t32) ? 1u : 0u) << b;    // a NaN keeps its block in
+      }
+      mask[(int64_t)(w0 >> 5) * n + j] = bits;
+      if (bits && lowest == 0x7fffffff) lowest = w0 + __ffs((int)bits) - 1;
+      listed += __popc(bits);
     }
-    mask[(int64_t)(w0 >> 5) * n + j] = bits;
   }
+  s_listed[part][lane] = listed;
+  s_lowest[part][lane] = lowest;
+  __syncthreads();
+  if (part == 0 && live) {
+    listed = s_listed[0][lane] + s_listed[1][lane] + s_listed[2][lane] + s_listed[3][lane];
+    lowest = min(min(s_lowest[0][lane], s_lowest[1][lane]), min(s_lowest[2][lane], s_lowest[3][lane]));
+    const int size_class = listed <= 1 ? 0 : 32 - __clz(listed - 1);      // ceil(log2(listed))
+    key[j] = size_class * blocks + (lowest == 0x7fffffff ? 0 : lowest);
+  }
+}
+
+// Keys of k_select_blocks are below this.
+int two_level_key_range(int blocks) {
+  int classes = 1;
+  while ((1 << (classes - 1)) < blocks) ++classes;      // size classes 0 .. ceil(log2(blocks))
+  return classes * blocks;
 }
 
 // One wavefront per tile of 128 consecutive entries of `rows`: OR of their masks, expanded to a list.
@@ -85,7 +115,7 @@ __global__ __launch_bounds__(256) void k_tile_lists(const uint32_t *__restrict__
 
 hipError_t launch_select_blocks(som_ctx *c, int64_t n) {
   const int blocks = (c->k + 127) / 128;
-  hipLaunchKernelGGL(k_select_blocks, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, c->coarse_min, n,
+  hipLaunchKernelGGL(k_select_blocks, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, c->stream, c->coarse_min, n,
                      blocks, c->xn32, c->wmax_bits, c->mu_norm2, margin_model(c, kCertifyCoarse, nullptr),
                      c->coarse_key, c->coarse_mask);
   return hipGetLastError();

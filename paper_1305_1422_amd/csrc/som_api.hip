@@ -299,7 +299,7 @@ static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *
     if (coarse) {
       SOM_LAUNCH(c, launch_bmu_block_min(c, n));
       SOM_LAUNCH(c, launch_select_blocks(c, n));
-      SOM_LAUNCH(c, launch_sort_keys(c, c->coarse_key, n, (c->k + 127) / 128));
+      SOM_LAUNCH(c, launch_sort_keys(c, c->coarse_key, n, two_level_key_range((c->k + 127) / 128)));
       SOM_LAUNCH(c, launch_tile_lists(c, n));
       SOM_LAUNCH(c, launch_bmu_dense_h_fine(c, n));
     } else if (split) {

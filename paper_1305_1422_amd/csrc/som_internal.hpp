@@ -107,7 +107,7 @@ struct som_ctx {
   // two-level dense search (bmu_two_level.hip), lazily allocated with Xh
   _Float16 *Xh1;          // [n][ceil(dim/64)][64] the hi halves alone
   float *coarse_min;      // [ceil(k/128)][n] smallest coarse score per node block and instance
-  int32_t *coarse_key;    // [n] node block of every instance's smallest coarse score
+  int32_t *coarse_key;    // [n] sort key of every instance: size class of its block set, lowest block of the set
   uint32_t *coarse_mask;  // [ceil(blocks/32)][n] node blocks an instance's BMU may lie in
   int32_t *tile_cnt;      // [ceil(n/128)] node blocks listed per instance tile of the sorted order
   int32_t *tile_list;     // [ceil(n/128)][ceil(k/128)] those blocks, ascending
@@ -210,6 +210,7 @@ hipError_t launch_bmu_block_min(som_ctx *c, int64_t n);                        /
 hipError_t launch_bmu_dense_h_fine(som_ctx *c, int64_t n);                     // sort_val[0], tile_cnt, tile_list -> candidates
 // bmu_two_level.hip
 hipError_t launch_select_blocks(som_ctx *c, int64_t n);                        // coarse_min -> coarse_key, coarse_mask
+int two_level_key_range(int blocks);                                           // keys of coarse_key are below this
 hipError_t launch_tile_lists(som_ctx *c, int64_t n);                           // coarse_mask, sort_val[0] -> tile_cnt, tile_list
 hipError_t launch_bmu_dense_h_collect(som_ctx *c, int64_t n);                 // rows of collect_rows -> collect_list
 hipError_t launch_split_rows_f16(som_ctx *c, const float *A, int64_t nrows, const unsigned *global_max_bits,

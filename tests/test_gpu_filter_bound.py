@@ -133,6 +133,8 @@ def _score_bound_case(x, w, rows, cols, filter="split_f16"):
         # two_level: the scores of its coarse pass, one product of operands rounded to 11 bits
         # (2 (2^14 + 8) u X Wm for the roundings of the two rows, doubled by the factor -2)
         split = 30 if filter == "split_f16" else 2 * (16384 + 8) + 6
+        if filter == "two_level":
+            g = 2.5 * np.ceil(dim / 16) + 9 + 2                    # one unflushed chain of ceil(dim / 16) instructions
         B = U * ((2 * g + split) * Xc * Wm + np.sqrt(dim) * (sx * Wm + sw * Xc) + 4 * Wm ** 2)
         # the constant 2 delta.x' that the rounding delta of x - mu adds to every score of an instance is no
         # error of the ranking: compare after removing each instance's mean difference
