@@ -168,6 +168,19 @@ def main() -> int:
     capi.som_profile_enable(som.ctx, False)
     refined, collected, rescanned = som.stats()
 
+    # two-level dense search: share of the (instance tile, node block) pairs its second pass works on, from one
+    # more, untimed, run through the schedule (the call that reads it synchronises)
+    fine_share = None
+    if w.kind == "dense" and args.mode == "epoch":
+        shares = []
+        for e in range(w.epochs):
+            step(e)
+            listed, pairs = som.two_level_stats()
+            if pairs:
+                shares.append(listed / pairs)
+        if shares:
+            fine_share = {"mean": float(np.mean(shares)), "per_epoch": [round(v, 4) for v in shares]}
+
     ms_per_step = 1e3 * dt / args.steps
     work = float(w.n) * w.k * w.dim
     value = work / (dt / args.steps)
@@ -184,6 +197,21 @@ def main() -> int:
                         "achieved": fp32_equiv, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                         "frac": fp32_equiv / PEAK_FP32_MFMA_TFLOPS,
                         "traffic": MEASURED_TRAFFIC_BYTES.get((w.config, args.filter)), "avg_launch_ms": dom_ms}
+        elif fine_share is not None:
+            # two-level search: one fp16 product per (instance, node, feature) in the coarse pass and three
+            # more on the share of the pairs the second pass works on: mfma_issue_frac counts those (how busy
+            # the matrix pipe is), frac counts the method's one multiply-add per triple.  avg_launch_ms is the
+            # whole filter stage (coarse pass, block selection, ordering, lists, second pass)
+            products = 1.0 + 3.0 * fine_share["mean"]
+            roofline = {"bound": "mfma", "kernel": "two-level BMU filter stage: k_bmu_dense_h<block minima, 1 fp16 product> + "
+                                                   "k_select_blocks + radix sort + k_tile_lists + k_bmu_dense_h<fine, 3 fp16 "
+                                                   "products on the listed pairs>",
+                        "achieved": fp32_equiv, "peak": PEAK_FP16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                        "frac": fp32_equiv / PEAK_FP16_MFMA_TFLOPS,
+                        "traffic": MEASURED_TRAFFIC_BYTES.get((w.config, "two_level")), "avg_launch_ms": dom_ms,
+                        "second_pass_share_of_pairs": fine_share,
+                        "mfma_issue_frac": products * fp32_equiv / PEAK_FP16_MFMA_TFLOPS,
+                        "vs_fp32_mfma_peak": fp32_equiv / PEAK_FP32_MFMA_TFLOPS}
         else:
             # the kernel issues three fp16 matrix products per (instance, node, feature), hi*hi + hi*lo + lo*hi:
             # mfma_issue_frac counts those (how busy the matrix pipe is), frac does not

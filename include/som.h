@@ -383,6 +383,14 @@ int som_debug_xcc_ids(int32_t *out, int n_blocks, void *hip_stream);
 int som_get_stats(som_ctx *ctx, int64_t *out);
 
 /*
+ * som_two_level_stats - how selective the coarse pass of the most recent dense BMU search on ctx was
+ * (see som_set_filter, SOM_FILTER_TWO_LEVEL; synchronises the stream).  out is a HOST pointer to two
+ * int64 values: the (tile of 128 instances, block of 128 nodes) pairs the second pass worked on, and all
+ * such pairs.  Both are 0 when that search ran in one level (or no dense search has run yet).
+ */
+int som_two_level_stats(som_ctx *ctx, int64_t *out);
+
+/*
  * som_profile_enable / som_profile_read - measurement support (not an operation of the paper).
  * While enabled, the library brackets the stages of every epoch with HIP events recorded on
  * the context's stream, so a benchmark can report per-stage device time without a profiler:

@@ -29,7 +29,7 @@ EXPORTS = [
     "som_update_dense", "som_update_csr",
     "som_set_data_dense", "som_set_data_csr", "som_train", "som_train_snapshots",
     "som_bmu_distances_dense", "som_bmu_distances_csr", "som_bmu_distances_dense_static",
-    "som_cool_schedule", "som_umatrix", "som_get_stats",
+    "som_cool_schedule", "som_umatrix", "som_get_stats", "som_two_level_stats",
     "som_profile_enable", "som_profile_read",
     "som_set_filter", "som_set_smoothing", "som_set_sparse_hot_block", "som_sparse_hot_block_active", "som_set_neighborhood", "som_set_scale_cooling", "som_validate_csr", "som_debug_scores_dense", "som_debug_scores_csr", "som_debug_mfma_f16", "som_debug_xcc_ids",
 ]
@@ -92,6 +92,8 @@ def load():
     L.som_umatrix.argtypes = [vp, vp, vp]
     L.som_get_stats.restype = i32
     L.som_get_stats.argtypes = [vp, C.POINTER(i64)]
+    L.som_two_level_stats.restype = i32
+    L.som_two_level_stats.argtypes = [vp, C.POINTER(i64)]
     L.som_profile_enable.restype = i32
     L.som_profile_enable.argtypes = [vp, i32]
     L.som_profile_read.restype = i32
@@ -297,6 +299,14 @@ def som_get_stats(ctx):
     out = (C.c_int64 * 3)()
     _check(ctx, load().som_get_stats(ctx, out))
     return int(out[0]), int(out[1]), int(out[2])
+
+
+def som_two_level_stats(ctx):
+    """(listed, all) pairs of (128 instances, 128 nodes) of the most recent dense BMU search's second pass;
+    (0, 0) if it ran in one level.  Synchronises."""
+    out = (C.c_int64 * 2)()
+    _check(ctx, load().som_two_level_stats(ctx, out))
+    return int(out[0]), int(out[1])
 
 
 def som_profile_enable(ctx, on: bool) -> None:

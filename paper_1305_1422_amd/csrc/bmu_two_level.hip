@@ -11,7 +11,7 @@
 //      m[b][j] <= m_j + 2 e_j - a node of any other block has an exact score above that of the node
 //      that gave m_j, strictly, so it is not the BMU and does not tie with it.  The kernel writes that
 //      block set as a bit mask, and a sort key made of the size class of the set (1, 2, 3-4, 5-8, ...
-//      blocks) and its lowest block;
+//      blocks; the widest class first) and its lowest block;
 //   3. the instances are put in the order of their keys (segsum.hip's radix sort).  A fine-pass tile
 //      works on the union of its 128 instances' sets, so one instance with a wide set (one that lies
 //      between clusters, say) makes its whole tile expensive: the size class keeps such instances among
@@ -37,7 +37,8 @@ __global__ __launch_bounds__(256) void k_select_blocks(const float *__restrict__
                                                        const float *__restrict__ xn32,
                                                        const unsigned *__restrict__ wmax_bits,
                                                        const float *__restrict__ mu_norm2, MarginModel mm,
-                                                       int32_t *__restrict__ key, uint32_t *__restrict__ mask) {
+                                                       int classes, int32_t *__restrict__ key,
+                                                       uint32_t *__restrict__ mask) {
   __shared__ float s_best[4][64];
   __shared__ int s_listed[4][64], s_lowest[4][64];
   const int lane = threadIdx.x & 63, part = threadIdx.x >> 6;
@@ -77,16 +78,20 @@ __global__ __launch_bounds__(256) void k_select_blocks(const float *__restrict__
     listed = s_listed[0][lane] + s_listed[1][lane] + s_listed[2][lane] + s_listed[3][lane];
     lowest = min(min(s_lowest[0][lane], s_lowest[1][lane]), min(s_lowest[2][lane], s_lowest[3][lane]));
     const int size_class = listed <= 1 ? 0 : 32 - __clz(listed - 1);      // ceil(log2(listed))
-    key[j] = size_class * blocks + (lowest == 0x7fffffff ? 0 : lowest);
+    // widest sets first: their tiles are the longest workgroups of the fine pass and should not start last
+    key[j] = (classes - 1 - size_class) * blocks + (lowest == 0x7fffffff ? 0 : lowest);
   }
 }
 
-// Keys of k_select_blocks are below this.
-int two_level_key_range(int blocks) {
+// Size classes 0 .. ceil(log2(blocks)) of a block set.
+static int size_classes(int blocks) {
   int classes = 1;
-  while ((1 << (classes - 1)) < blocks) ++classes;      // size classes 0 .. ceil(log2(blocks))
-  return classes * blocks;
+  while ((1 << (classes - 1)) < blocks) ++classes;
+  return classes;
 }
+
+// Keys of k_select_blocks are below this.
+int two_level_key_range(int blocks) { return size_classes(blocks) * blocks; }
 
 // One wavefront per tile of 128 consecutive entries of `rows`: OR of their masks, expanded to a list.
 __global__ __launch_bounds__(256) void k_tile_lists(const uint32_t *__restrict__ mask, const int32_t *__restrict__ rows,
@@ -117,7 +122,7 @@ hipError_t launch_select_blocks(som_ctx *c, int64_t n) {
   const int blocks = (c->k + 127) / 128;
   hipLaunchKernelGGL(k_select_blocks, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, c->stream, c->coarse_min, n,
                      blocks, c->xn32, c->wmax_bits, c->mu_norm2, margin_model(c, kCertifyCoarse, nullptr),
-                     c->coarse_key, c->coarse_mask);
+                     size_classes(blocks), c->coarse_key, c->coarse_mask);
   return hipGetLastError();
 }
 

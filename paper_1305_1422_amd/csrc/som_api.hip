@@ -111,6 +111,7 @@ static void free_row_scratch(som_ctx *c) {
   dev_free(c->Xh); dev_free(c->xscale);
   dev_free(c->Xh1); dev_free(c->coarse_min); dev_free(c->coarse_key); dev_free(c->coarse_mask);
   dev_free(c->tile_cnt); dev_free(c->tile_list);
+  c->two_level_n = 0;
   c->n_cap = 0;
   c->cand_cap = 0;
   c->d_norms_valid = 0;
@@ -294,6 +295,7 @@ static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *
   if (rc) return rc;
   const bool split = uses_planes(c);
   const bool coarse = two_level_ready(c, n);
+  c->two_level_n = coarse ? n : 0;
   {
     StageTimer t(c, 0);
     if (coarse) {
@@ -978,6 +980,21 @@ int som_get_stats(som_ctx *c, int64_t *out) {
   out[0] = h[0];
   out[1] = h[1];
   out[2] = h[2];
+  return SOM_OK;
+}
+
+int som_two_level_stats(som_ctx *c, int64_t *out) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  if (!out) return fail(c, SOM_ERR_INVALID_ARG, "out is NULL");
+  out[0] = out[1] = 0;
+  if (c->two_level_n <= 0) return SOM_OK;
+  const int64_t tiles = (c->two_level_n + 127) / 128;
+  std::vector<int32_t> h((size_t)tiles);
+  hipError_t e = hipMemcpyAsync(h.data(), c->tile_cnt, (size_t)tiles * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return dev_fail(c, e, "som_two_level_stats");
+  for (int32_t v : h) out[0] += v;
+  out[1] = tiles * (int64_t)((c->k + 127) / 128);
   return SOM_OK;
 }
 

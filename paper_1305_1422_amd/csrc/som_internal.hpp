@@ -111,6 +111,7 @@ struct som_ctx {
   uint32_t *coarse_mask;  // [ceil(blocks/32)][n] node blocks an instance's BMU may lie in
   int32_t *tile_cnt;      // [ceil(n/128)] node blocks listed per instance tile of the sorted order
   int32_t *tile_list;     // [ceil(n/128)][ceil(k/128)] those blocks, ascending
+  int64_t two_level_n;    // instances of the most recent dense search if it ran in two levels, else 0
   int64_t cand_cap;       // instance slots in the three candidate arrays (node groups x instances)
   float *cand_val;        // [groups][n][kCand]
   int32_t *cand_idx;      // [groups][n][kCand]

@@ -174,3 +174,7 @@ class Som:
 
     def stats(self):
         return capi.som_get_stats(self.ctx)
+
+    def two_level_stats(self):
+        """(listed, all) node-block/instance-tile pairs of the last dense search's second pass; (0, 0) if one-level."""
+        return capi.som_two_level_stats(self.ctx)
