@@ -65,7 +65,7 @@ __device__ __forceinline__ void load16_to_lds_v(const void *lane_address, unsign
 }
 #pragma clang diagnostic pop
 
-enum { kHFilter = 0, kHCollect = 1, kHDump = 2, kHPartial = 3, kHBlockMin = 4, kHFine = 5 };
+enum { kHFilter = 0, kHCollect = 1, kHDump = 2, kHPartial = 3, kHFine = 4 };
 
 __device__ __forceinline__ f16x8 as_halves(f32x4 v) { return __builtin_bit_cast(f16x8, v); }
 
@@ -75,16 +75,13 @@ __device__ __forceinline__ f16x8 as_halves(f32x4 v) { return __builtin_bit_cast(
 // hot-column block of the sparse search (csr_hot.hip): the plain dot products times the code book's
 // scale go to dump[(node block * n + instance) * 128 + node within the block], four neighbouring nodes
 // of one instance per 16-byte store.  No candidates, no constants.
-// The two-level search (bmu_two_level.hip) adds two modes.  kHBlockMin is its coarse pass: the smallest
-// score of every (instance, node block) pair goes to dump[node block * n + instance], nothing else is
-// kept.  kHFine is its second pass: the instance tiles are taken through the index list `rows` (all n
-// instances, ordered so that neighbours in the list have their best nodes in the same block), and the
-// workgroups of tile t share out the cnt[t] node blocks listed, ascending, in list[t * blocks of the
-// map ..] instead of all of them; candidates are stored under the instances' own numbers.
-// kCoarse: the operands are hi-only planes (chunks of 64 features, see split_f16.hip) and a k-step is
-// one product instead of three: 11-bit operands, a third of the matrix work per feature.
+// kHFine is the second pass of the two-level search (bmu_two_level.hip): the instance tiles are taken
+// through the index list `rows` (all n instances, ordered so that neighbours in the list have nearly the
+// same sets of candidate blocks), and the workgroups of tile t share out the cnt[t] node blocks listed,
+// ascending, in list[t * blocks of the map ..] instead of all of them; candidates are stored under the
+// instances' own numbers.
 // `unit` numbers the (instance tile, node group) pairs; see the decoding below.
-template <int kMode, bool kCoarse>
+template <int kMode>
 __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, const float *__restrict__ Wh,
                                                  const float *__restrict__ wc, const float *__restrict__ xscale,
                                                  const float *__restrict__ wscale, int64_t n, int k, int nK,
@@ -95,7 +92,6 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
   constexpr bool kCollect = kMode == kHCollect;
   constexpr bool kDump = kMode == kHDump;
   constexpr bool kPartial = kMode == kHPartial;
-  constexpr bool kBlockMin = kMode == kHBlockMin;
   constexpr bool kFine = kMode == kHFine;
   constexpr bool kGather = kCollect || kFine;        // instance tiles through the index list `rows`
   constexpr int WI = kHWI;
@@ -106,7 +102,6 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
   __shared__ __attribute__((aligned(16))) float sW[kHStages][kHWTile];
   __shared__ __attribute__((aligned(16))) float sX[kHStages][kHXTile];
   __shared__ float sWn[4][kTN];      // node constants of the node blocks in flight
-  __shared__ float sMin[2][kHTI];    // block-minimum mode: the upper node half's minima, two blocks in flight
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -228,7 +223,6 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
   }
 
   f32x16 acc[2][2], tot[2][2];
-  float block_min[2] = {INFINITY, INFINITY};
 #pragma unroll
   for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -237,8 +231,7 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
       for (int v = 0; v < 16; ++v) tot[mi][ni][v] = 0.f;
 
   // Operands of one k-step (16 features): the hi and lo planes of this wavefront's two 32-node and
-  // two 32-instance row blocks, eight 16-byte LDS reads per lane.  (Hi-only planes: the same eight reads
-  // are the hi halves of the 16-feature steps ks and ks + 2 of a 64-feature chunk.)
+  // two 32-instance row blocks, eight 16-byte LDS reads per lane.
   struct Operands { f16x8 g1[2], g2[2], h1[2], h2[2]; };
   auto read_operands = [&](Operands &o, int st, int ks) {
     const float *pw = &sW[st][a_base];
@@ -251,34 +244,30 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
       o.h2[b] = as_halves(*reinterpret_cast<const f32x4 *>(px + b * 32 * kHRow + rd_off[2 + ks]));
     }
   };
-  // Twelve MFMAs of one k-step (eight on hi-only planes, where the operand pairs 1 and 2 are two different
-  // 16-feature steps of the chunk); the four output blocks take turns, so that an accumulator is reused
+  // Twelve MFMAs of one k-step; the four output blocks take turns, so that an accumulator is reused
   // every fourth instruction only.  The small cross products go first.  `fresh`: the accumulators
   // start from C = 0 as an operand of the instruction itself, which spares clearing 64 registers.
   auto multiply = [&](const Operands &o, bool fresh) {
     __builtin_amdgcn_s_setprio(1);      // the wavefront that has operands ready goes first on the SIMD (-1.6 %)
-    // first product: hi_w(k-step ks + 2) . hi_x(same) on hi-only planes, lo_w . hi_x on split planes
     if (fresh) {
       const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g2[mi], kCoarse ? o.h2[ni] : o.h1[ni], zero, 0, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g2[mi], o.h1[ni], zero, 0, 0, 0);
     } else {
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g2[mi], kCoarse ? o.h2[ni] : o.h1[ni], acc[mi][ni], 0, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g2[mi], o.h1[ni], acc[mi][ni], 0, 0, 0);
     }
-    if (!kCoarse) {
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g1[mi], o.h2[ni], acc[mi][ni], 0, 0, 0);
-    }
+      for (int ni = 0; ni < 2; ++ni)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(o.g1[mi], o.h2[ni], acc[mi][ni], 0, 0, 0);
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -314,39 +303,18 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
     multiply(op1, false);
 
     const bool last_k = (kc == nK - 1);
-    // (hi-only planes: the products carry 11 bits, so the fp32 accumulators run through the whole node
-    // block and are the totals)
-    fresh = last_k || (!kCoarse && ((kc + flush_phase) & flush_mask) == flush_mask);
+    fresh = last_k || ((kc + flush_phase) & flush_mask) == flush_mask;
     if (fresh) {
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) tot[mi][ni][v] = kCoarse ? acc[mi][ni][v] : tot[mi][ni][v] + acc[mi][ni][v];
+          for (int v = 0; v < 16; ++v) tot[mi][ni][v] += acc[mi][ni][v];
     }
     if (last_k) {
       const int nb = kFine ? blist[nb_first + ord] : nb_first + ord;
-      if (kBlockMin) {
-        // smallest score of the block per instance: over this lane's 32 nodes, the other lane half, and
-        // (through LDS, after the barrier below) the other node half
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni) {
-          float m = INFINITY;
-#pragma unroll
-          for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-            for (int v = 0; v < 16; v += 2) {          // pairs: one three-way minimum per two scores
-              const float s0 = fmaf(factor[ni], tot[mi][ni][v], sWn[ord & 3][wm * 64 + mfma_row(mi, v, lhi)]);
-              const float s1 = fmaf(factor[ni], tot[mi][ni][v + 1], sWn[ord & 3][wm * 64 + mfma_row(mi, v + 1, lhi)]);
-              m = fminf(fminf(m, s0), s1);
-              tot[mi][ni][v] = tot[mi][ni][v + 1] = 0.f;
-            }
-          m = fminf(m, __shfl_xor(m, 32, 64));
-          block_min[ni] = m;
-          if (wm == 1 && lhi == 0) sMin[ord & 1][wi * 64 + ni * 32 + l32] = m;
-        }
-      } else if (kPartial) {
+      if (kPartial) {
         // lane = instance wi 64 + ni 32 + l32 of the tile; registers 4 g .. 4 g + 3 of an output block are
         // nodes wm 64 + mi 32 + 8 g + 4 lhi .. + 3 of the node block, which lie side by side in the table
         // [node block][instance][128 nodes]: one 16-byte store each, and the 128 x 128 results of a
@@ -386,27 +354,17 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
 
     __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
     __syncthreads();
-    if (kBlockMin && last_k && wm == 0 && lhi == 0) {
-      // the upper node half wrote its minima before the barrier; the buffer of this parity is written again
-      // two node blocks later, i.e. after the next barrier at the earliest
-      const int nb = nb_first + ord;
-#pragma unroll
-      for (int ni = 0; ni < 2; ++ni) {
-        const int il = wi * 64 + ni * 32 + l32;
-        if (inst0 + il < n) dump[(int64_t)nb * n + inst0 + il] = fminf(block_min[ni], sMin[ord & 1][il]);
-      }
-    }
     stage = next_stage;
   }
-  if (kDump || kCollect || kPartial || kBlockMin) return;
+  if (kDump || kCollect || kPartial) return;
   merge_and_store<kHTI>(top, &sW[0][0], reinterpret_cast<int *>(&sX[0][0]), tid, wm, wi, l32, lhi, inst0, n, group,
                         out, kFine ? rows : nullptr);
 }
 
-// Filter, dump, partial, block-minimum and fine modes: one unit per workgroup.  Collect mode: the number
+// Filter, dump, partial and fine modes: one unit per workgroup.  Collect mode: the number
 // of live instance tiles is only known on the device, so a fixed grid walks the units; its size is a
 // multiple of 8, which keeps unit mod 8 = workgroup mod 8 = the XCD the decoding assumes.
-template <int kMode, bool kCoarse>
+template <int kMode>
 __global__ __launch_bounds__(128 * kHWI, 2) void k_bmu_dense_h(const float *__restrict__ Xh, const float *__restrict__ Wh,
                                                         const float *__restrict__ wc,
                                                         const float *__restrict__ xscale,
@@ -421,12 +379,12 @@ __global__ __launch_bounds__(128 * kHWI, 2) void k_bmu_dense_h(const float *__re
     const int64_t ntiles = ((int64_t)*n_slots + 64 * kHWI - 1) / (64 * kHWI);
     const int64_t units = (ntiles + 7) / 8 * 8 * groups;
     for (int64_t unit = blockIdx.x; unit < units; unit += gridDim.x) {
-      bmu_dense_h_unit<kMode, kCoarse>(Xh, Wh, wc, xscale, wscale, n, k, nK, flush_chunks, groups, out, dump, rows,
+      bmu_dense_h_unit<kMode>(Xh, Wh, wc, xscale, wscale, n, k, nK, flush_chunks, groups, out, dump, rows,
                                        n_slots, thr, cnt, list, unit);
       __syncthreads();               // the next unit reuses the LDS stages
     }
   } else {
-    bmu_dense_h_unit<kMode, kCoarse>(Xh, Wh, wc, xscale, wscale, n, k, nK, flush_chunks, groups, out, dump, rows,
+    bmu_dense_h_unit<kMode>(Xh, Wh, wc, xscale, wscale, n, k, nK, flush_chunks, groups, out, dump, rows,
                                      n_slots, thr, cnt, list, (int64_t)blockIdx.x);
   }
 }
@@ -469,8 +427,7 @@ int bmu_dense_h_fine_groups(const som_ctx *c, int64_t n) {
   return (int)want;
 }
 
-// coarse: the scores of the coarse pass of the two-level search (hi-only planes), dump mode only.
-hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump, bool coarse) {
+hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump) {
   const int groups = bmu_dense_h_groups(c, n);
   const int64_t tiles = (n + 64 * kHWI - 1) / (64 * kHWI);
   const int64_t blocks = (tiles + 7) / 8 * 8 * groups;
@@ -478,33 +435,14 @@ hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump, bool coarse) {
   CandView out{c->cand_val, c->cand_idx, c->cand_over};
   const float *Xh = reinterpret_cast<const float *>(c->Xh);
   const float *Wh = reinterpret_cast<const float *>(c->Wh);
-  if (dump && coarse)
-    hipLaunchKernelGGL((k_bmu_dense_h<kHDump, true>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
-                       reinterpret_cast<const float *>(c->Xh1), reinterpret_cast<const float *>(c->Wh1), c->wn32,
-                       c->xscale, c->wscale, n, c->k, (c->dim + 63) / 64, split_flush_chunks(c->dim), groups, out, dump,
-                       nullptr, nullptr, nullptr, nullptr, nullptr);
-  else if (dump)
-    hipLaunchKernelGGL((k_bmu_dense_h<kHDump, false>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
+  if (dump)
+    hipLaunchKernelGGL((k_bmu_dense_h<kHDump>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
                        c->wn32, c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, dump, nullptr, nullptr, nullptr,
                        nullptr, nullptr);
   else
-    hipLaunchKernelGGL((k_bmu_dense_h<kHFilter, false>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
+    hipLaunchKernelGGL((k_bmu_dense_h<kHFilter>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
                        c->wn32, c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, dump, nullptr, nullptr, nullptr,
                        nullptr, nullptr);
-  return hipGetLastError();
-}
-
-// Coarse pass of the two-level search: c->coarse_min[node block][instance] = smallest one-product score
-// of the pair, from the hi-only planes c->Xh1 and c->Wh1; the tiling and launch shape of the filter.
-hipError_t launch_bmu_block_min(som_ctx *c, int64_t n) {
-  const int groups = bmu_dense_h_groups(c, n);
-  const int64_t tiles = (n + 64 * kHWI - 1) / (64 * kHWI);
-  const int64_t blocks = (tiles + 7) / 8 * 8 * groups;
-  CandView out{nullptr, nullptr, nullptr};
-  hipLaunchKernelGGL((k_bmu_dense_h<kHBlockMin, true>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
-                     reinterpret_cast<const float *>(c->Xh1), reinterpret_cast<const float *>(c->Wh1), c->wn32,
-                     c->xscale, c->wscale, n, c->k, (c->dim + 63) / 64, split_flush_chunks(c->dim), groups, out,
-                     c->coarse_min, nullptr, nullptr, nullptr, nullptr, nullptr);
   return hipGetLastError();
 }
 
@@ -516,7 +454,7 @@ hipError_t launch_bmu_dense_h_fine(som_ctx *c, int64_t n) {
   const int64_t blocks = (tiles + 7) / 8 * 8 * groups;
   const int nK = (c->dim + 31) / 32;
   CandView out{c->cand_val, c->cand_idx, c->cand_over};
-  hipLaunchKernelGGL((k_bmu_dense_h<kHFine, false>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
+  hipLaunchKernelGGL((k_bmu_dense_h<kHFine>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
                      reinterpret_cast<const float *>(c->Xh), reinterpret_cast<const float *>(c->Wh), c->wn32,
                      c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, nullptr, c->sort_val[0],
                      nullptr, nullptr, c->tile_cnt, c->tile_list);
@@ -530,7 +468,7 @@ hipError_t launch_hot_partial(som_ctx *c, int64_t n) {
   const int64_t tiles = (n + 64 * kHWI - 1) / (64 * kHWI);
   const int64_t blocks = (tiles + 7) / 8 * 8 * groups;
   CandView out{nullptr, nullptr, nullptr};
-  hipLaunchKernelGGL((k_bmu_dense_h<kHPartial, false>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
+  hipLaunchKernelGGL((k_bmu_dense_h<kHPartial>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
                      reinterpret_cast<const float *>(c->hot_Xh), reinterpret_cast<const float *>(c->hot_Wh), nullptr,
                      nullptr, c->hot_wscale, n, c->k, kHot / 32, split_flush_chunks(kHot), groups, out, c->hot_P,
                      nullptr, nullptr, nullptr, nullptr, nullptr);
@@ -550,7 +488,7 @@ hipError_t launch_bmu_dense_h_collect(som_ctx *c, int64_t n) {
   blocks = (blocks + 7) / 8 * 8;
   const int nK = (c->dim + 31) / 32;
   CandView out{nullptr, nullptr, nullptr};
-  hipLaunchKernelGGL((k_bmu_dense_h<kHCollect, false>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
+  hipLaunchKernelGGL((k_bmu_dense_h<kHCollect>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
                      reinterpret_cast<const float *>(c->Xh), reinterpret_cast<const float *>(c->Wh), c->wn32,
                      c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, nullptr, c->collect_rows, c->list_counts + 1,
                      c->collect_thr, c->collect_cnt, c->collect_list);

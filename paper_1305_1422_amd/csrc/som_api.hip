@@ -299,7 +299,7 @@ static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *
   {
     StageTimer t(c, 0);
     if (coarse) {
-      SOM_LAUNCH(c, launch_bmu_block_min(c, n));
+      SOM_LAUNCH(c, launch_bmu_coarse(c, n, nullptr));
       SOM_LAUNCH(c, launch_select_blocks(c, n));
       SOM_LAUNCH(c, launch_sort_keys(c, c->coarse_key, n, two_level_key_range((c->k + 127) / 128)));
       SOM_LAUNCH(c, launch_tile_lists(c, n));
@@ -934,7 +934,8 @@ int som_debug_scores_dense(som_ctx *c, const float *data, int64_t n, const float
   if (rc) return rc;
   const bool split = uses_planes(c);
   const bool coarse = c->filter == SOM_FILTER_TWO_LEVEL && two_level_ready(c, n);    // asked for by name: its coarse scores
-  if (split) SOM_LAUNCH(c, launch_bmu_dense_h(c, n, scores, coarse));
+  if (coarse) SOM_LAUNCH(c, launch_bmu_coarse(c, n, scores));
+  else if (split) SOM_LAUNCH(c, launch_bmu_dense_h(c, n, scores));
   else SOM_LAUNCH(c, launch_bmu_dense(c, data, n, scores));
   SOM_LAUNCH(c, launch_margins(c, n, coarse ? kCertifyCoarse : split ? kCertifySplit : kCertifyFp32, nullptr, margin_out));
   SOM_LAUNCH(c, hipMemcpyAsync(mu_out, c->mu, (size_t)c->dim * sizeof(float), hipMemcpyDeviceToDevice, c->stream));

@@ -205,9 +205,9 @@ inline int split_flush_chunks(int dim) { return dim >= 256 ? 4 : 2; }
 constexpr int kTwoLevelMinBlocks = 8;
 constexpr int64_t kTwoLevelMaxTable = 8ll << 30;
 int bmu_dense_h_groups(const som_ctx *c, int64_t n);
-hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump, bool coarse = false);   // Xh, Wh -> candidates (or all scores)
+hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump);            // Xh, Wh -> candidates (or all scores)
 int bmu_dense_h_fine_groups(const som_ctx *c, int64_t n);
-hipError_t launch_bmu_block_min(som_ctx *c, int64_t n);                        // Xh1, Wh1 -> coarse_min
+hipError_t launch_bmu_coarse(som_ctx *c, int64_t n, float *dump);              // bmu_coarse.hip: Xh1, Wh1 -> coarse_min (or all scores)
 hipError_t launch_bmu_dense_h_fine(som_ctx *c, int64_t n);                     // sort_val[0], tile_cnt, tile_list -> candidates
 // bmu_two_level.hip
 hipError_t launch_select_blocks(som_ctx *c, int64_t n);                        // coarse_min -> coarse_key, coarse_mask
