@@ -30,12 +30,14 @@ PEAK_HBM_GBS = 8000.0
 # (FETCH_SIZE, WRITE_SIZE, scaled by the copy calibration) summarised in profiles/epoch_config*.md;
 # measured once per kernel version, not during this run (the dense figures vary by some ten percent from
 # run to run: they depend on how long the workgroups that share an instance tile stay in step).
-MEASURED_TRAFFIC_BYTES = {(2, "split_f16"): 3.841e9 + 0.036e9, (2, "fp32"): 8.49e9 + 0.025e9,
+MEASURED_TRAFFIC_BYTES = {(2, "two_level"): 1.388e9 + 0.034e9, (3, "two_level"): 2.990e9 + 0.094e9,
+                          (5, "two_level"): 10.347e9 + 0.424e9,
+                          # one-level split-fp16 filter and fp32 filter (earlier counter runs; those kernels are unchanged)
+                          (2, "split_f16"): 3.841e9 + 0.036e9, (2, "fp32"): 8.49e9 + 0.025e9,
                           (3, "split_f16"): 14.283e9 + 0.025e9, (5, "split_f16"): 13.917e9 + 0.072e9,
                           # sparse: all kernels of the filter stage (code-book pass, hot-column block, sweep)
-                          (4, "split_f16"): 16.012e9 + 1.613e9, (4, "fp32"): 16.012e9 + 1.613e9,
-                          (6, "split_f16"): 0.390e9 + 0.056e9, (6, "fp32"): 0.390e9 + 0.056e9,
-                          (7, "split_f16"): 82.536e9 + 6.542e9, (7, "fp32"): 82.536e9 + 6.542e9}
+                          (4, "sparse"): 16.365e9 + 1.450e9, (6, "sparse"): 0.415e9 + 0.058e9,
+                          (7, "sparse"): 87.461e9 + 6.471e9}
 PEAK_FP32_VALU_TFLOPS = 157.3
 
 
@@ -228,7 +230,7 @@ def main() -> int:
         # compulsory bytes: CSR once (8 B per nonzero + 8 B per row), code book once, BMUs out
         alg_bytes = nnz * 8.0 + (w.n + 1) * 8.0 + w.k * w.dim * 4.0 + w.n * 4.0
         achieved = alg_bytes / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
-        traffic = MEASURED_TRAFFIC_BYTES.get((w.config, args.filter))
+        traffic = MEASURED_TRAFFIC_BYTES.get((w.config, "sparse"))
         valu_bound_ms = 2.0 * nnz * w.k / (PEAK_FP32_VALU_TFLOPS * 1e12) * 1e3
         roofline = {"bound": "hbm", "kernel": "sparse BMU filter pass: k_center_transpose_q16 + hot-column block "
                                               "(k_bmu_dense_h<partial>) + k_bmu_csr_sliced",

@@ -29,27 +29,39 @@
 
 namespace som {
 
-// Four threads per instance (one per wavefront of the workgroup, so that a wavefront reads 64 consecutive
-// instances of a table row); they share out the blocks for the minimum and the 32-block words of the mask
-// and combine through LDS.  The table is read twice, the second time from L2 (a workgroup's slice is a few
-// tens of KB).
-__global__ __launch_bounds__(256) void k_select_blocks(const float *__restrict__ m, int64_t n, int blocks,
-                                                       const float *__restrict__ xn32,
-                                                       const unsigned *__restrict__ wmax_bits,
-                                                       const float *__restrict__ mu_norm2, MarginModel mm,
-                                                       int classes, int32_t *__restrict__ key,
-                                                       uint32_t *__restrict__ mask) {
-  __shared__ float s_best[4][64];
-  __shared__ int s_listed[4][64], s_lowest[4][64];
+// kParts threads per instance (one per wavefront of the workgroup, so that a wavefront reads 64 consecutive
+// instances of a table row); thread p of an instance takes the blocks p, p + kParts, ... and keeps the first
+// 32 of them in registers, so that the table is read once for maps of up to 32 kParts blocks (beyond that the
+// rest is read again for the comparison); minima, mask words and the key are combined through LDS.
+template <int kParts>
+__global__ __launch_bounds__(64 * kParts) void k_select_blocks(const float *__restrict__ m, int64_t n, int blocks,
+                                                              const float *__restrict__ xn32,
+                                                              const unsigned *__restrict__ wmax_bits,
+                                                              const float *__restrict__ mu_norm2, MarginModel mm,
+                                                              int classes, int32_t *__restrict__ key,
+                                                              uint32_t *__restrict__ mask) {
+  constexpr int kHold = 32;
+  constexpr int kWordsAtOnce = 8;               // mask words combined per round: 256 blocks
+  __shared__ float s_best[kParts][64];
+  __shared__ uint32_t s_bits[kParts][kWordsAtOnce][64];
   const int lane = threadIdx.x & 63, part = threadIdx.x >> 6;
   const int64_t j = (int64_t)blockIdx.x * 64 + lane;
   const bool live = j < n;
+  float held[kHold];
   float best = INFINITY;
+#pragma unroll
+  for (int i = 0; i < kHold; ++i) {
+    const int b = part + i * kParts;
+    held[i] = (live && b < blocks) ? m[(int64_t)b * n + j] : INFINITY;
+    best = fminf(best, held[i]);
+  }
   if (live)
-    for (int b = part; b < blocks; b += 4) best = fminf(best, m[(int64_t)b * n + j]);
+    for (int b = part + kHold * kParts; b < blocks; b += kParts) best = fminf(best, m[(int64_t)b * n + j]);
   s_best[part][lane] = best;
   __syncthreads();
-  best = fminf(fminf(s_best[0][lane], s_best[1][lane]), fminf(s_best[2][lane], s_best[3][lane]));
+  best = s_best[0][lane];
+#pragma unroll
+  for (int p = 1; p < kParts; ++p) best = fminf(best, s_best[p][lane]);
   float t32 = INFINITY;                         // no finite score at all: every block stays in
   if (live && best < INFINITY) {
     // score_margin is the bound for a PAIR of scores (2 e_j and slack): exactly the window of step 2
@@ -57,26 +69,45 @@ __global__ __launch_bounds__(256) void k_select_blocks(const float *__restrict__
     t32 = (float)thr;                           // rounded up: no block inside the window is lost
     if ((double)t32 < thr) t32 = nextafterf(t32, INFINITY);
   }
-  int listed = 0, lowest = 0x7fffffff;
-  if (live) {
-    for (int w0 = 32 * part; w0 < blocks; w0 += 128) {
-      uint32_t bits = 0;
-      const int top = blocks - w0 < 32 ? blocks - w0 : 32;
-      for (int b = 0; b < top; ++b) {
-        const float v = m[(int64_t)(w0 + b) * n + j];
-        bits |= (!(v > t32) ? 1u : 0u) << b;    // a NaN keeps its block in
+  int listed = 0, lowest = 0x7fffffff;          // kept by part 0
+  for (int w0 = 0; w0 < blocks; w0 += 32 * kWordsAtOnce) {
+    uint32_t bits[kWordsAtOnce];
+#pragma unroll
+    for (int w = 0; w < kWordsAtOnce; ++w) bits[w] = 0;
+    if (w0 == 0) {                              // the blocks held in registers: 32 kParts <= 256 of them
+#pragma unroll
+      for (int i = 0; i < kHold; ++i) {
+        const int b = part + i * kParts;        // compile-time word and bit position up to `part`
+        if (b < blocks && !(held[i] > t32)) bits[(i * kParts) >> 5] |= 1u << ((part + i * kParts) & 31);   // a NaN keeps its block in
       }
-      mask[(int64_t)(w0 >> 5) * n + j] = bits;
-      if (bits && lowest == 0x7fffffff) lowest = w0 + __ffs((int)bits) - 1;
-      listed += __popc(bits);
     }
+    if (w0 > 0 && live) {                       // (the launcher picks kParts so that the first round is all held)
+#pragma unroll
+      for (int w = 0; w < kWordsAtOnce; ++w)
+#pragma unroll
+        for (int t = 0; t < 32 / kParts; ++t) {
+          const int b = w0 + 32 * w + part + kParts * t;
+          if (b < blocks && !(m[(int64_t)b * n + j] > t32)) bits[w] |= 1u << (part + kParts * t);
+        }
+    }
+#pragma unroll
+    for (int w = 0; w < kWordsAtOnce; ++w) s_bits[part][w][lane] = bits[w];
+    __syncthreads();
+    if (part == 0 && live) {
+#pragma unroll
+      for (int w = 0; w < kWordsAtOnce; ++w) {
+        if (w0 + 32 * w >= blocks) break;
+        uint32_t all = 0;
+#pragma unroll
+        for (int p = 0; p < kParts; ++p) all |= s_bits[p][w][lane];
+        mask[(int64_t)((w0 >> 5) + w) * n + j] = all;
+        if (all && lowest == 0x7fffffff) lowest = w0 + 32 * w + __ffs((int)all) - 1;
+        listed += __popc(all);
+      }
+    }
+    __syncthreads();
   }
-  s_listed[part][lane] = listed;
-  s_lowest[part][lane] = lowest;
-  __syncthreads();
   if (part == 0 && live) {
-    listed = s_listed[0][lane] + s_listed[1][lane] + s_listed[2][lane] + s_listed[3][lane];
-    lowest = min(min(s_lowest[0][lane], s_lowest[1][lane]), min(s_lowest[2][lane], s_lowest[3][lane]));
     const int size_class = listed <= 1 ? 0 : 32 - __clz(listed - 1);      // ceil(log2(listed))
     // widest sets first: their tiles are the longest workgroups of the fine pass and should not start last
     key[j] = (classes - 1 - size_class) * blocks + (lowest == 0x7fffffff ? 0 : lowest);
@@ -120,9 +151,14 @@ __global__ __launch_bounds__(256) void k_tile_lists(const uint32_t *__restrict__
 
 hipError_t launch_select_blocks(som_ctx *c, int64_t n) {
   const int blocks = (c->k + 127) / 128;
-  hipLaunchKernelGGL(k_select_blocks, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, c->stream, c->coarse_min, n,
-                     blocks, c->xn32, c->wmax_bits, c->mu_norm2, margin_model(c, kCertifyCoarse, nullptr),
-                     size_classes(blocks), c->coarse_key, c->coarse_mask);
+  if (blocks <= 128)      // 32 blocks held per thread: all of them
+    hipLaunchKernelGGL(k_select_blocks<4>, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, c->stream, c->coarse_min, n,
+                       blocks, c->xn32, c->wmax_bits, c->mu_norm2, margin_model(c, kCertifyCoarse, nullptr),
+                       size_classes(blocks), c->coarse_key, c->coarse_mask);
+  else
+    hipLaunchKernelGGL(k_select_blocks<8>, dim3((unsigned)((n + 63) / 64)), dim3(512), 0, c->stream, c->coarse_min, n,
+                       blocks, c->xn32, c->wmax_bits, c->mu_norm2, margin_model(c, kCertifyCoarse, nullptr),
+                       size_classes(blocks), c->coarse_key, c->coarse_mask);
   return hipGetLastError();
 }
 

@@ -131,3 +131,27 @@ def test_default_filter_is_two_level_on_large_maps_only(oracle):
         b_split, _ = _bmus(W, X, rows, cols, "split_f16")
         assert np.array_equal(b_auto, b_split)
         P.check_bmus_dense(oracle, X, W, b_auto)
+
+
+def test_statistics_of_the_second_pass(oracle):
+    """som_two_level_stats: the pairs the second pass worked on, out of all (tile, block) pairs; an ordered map
+    lists a small share, a code book of equal rows all of them, a one-level search reports (0, 0)."""
+    from paper_1305_1422_amd import Som
+    rng = np.random.default_rng(4800)
+    rows, cols, dim, n = 48, 48, 40, 3000                        # 2,304 nodes = 18 blocks, 24 tiles
+    W, anchors = _ordered_map(rng, rows, cols, dim, 10)
+    X = (anchors[rng.integers(10, size=n)] + 0.02 * rng.standard_normal((n, dim))).astype(np.float32)
+    som = Som(rows, cols, dim, codebook=torch.from_numpy(W), filter="two_level")
+    assert som.two_level_stats() == (0, 0)                       # no search yet
+    som.bmus(P.to_dev(X))
+    listed, pairs = som.two_level_stats()
+    assert pairs == 24 * 18 and 24 <= listed < pairs // 2, (listed, pairs)
+    som.set_filter("split_f16")
+    som.bmus(P.to_dev(X))
+    assert som.two_level_stats() == (0, 0)
+    som.close()
+    W_eq = np.tile(W[:1], (rows * cols, 1))
+    som = Som(rows, cols, dim, codebook=torch.from_numpy(W_eq), filter="two_level")
+    som.bmus(P.to_dev(X))
+    assert som.two_level_stats() == (pairs, pairs)
+    som.close()
