@@ -205,7 +205,7 @@ def main() -> int:
             # the matrix pipe is), frac counts the method's one multiply-add per triple.  avg_launch_ms is the
             # whole filter stage (coarse pass, block selection, ordering, lists, second pass)
             products = 1.0 + 3.0 * fine_share["mean"]
-            roofline = {"bound": "mfma", "kernel": "two-level BMU filter stage: k_bmu_dense_h<block minima, 1 fp16 product> + "
+            roofline = {"bound": "mfma", "kernel": "two-level BMU filter stage: k_bmu_coarse (block minima, 1 fp16 product) + "
                                                    "k_select_blocks + radix sort + k_tile_lists + k_bmu_dense_h<fine, 3 fp16 "
                                                    "products on the listed pairs>",
                         "achieved": fp32_equiv, "peak": PEAK_FP16_MFMA_TFLOPS, "unit": "TFLOP/s",

@@ -77,9 +77,10 @@ __device__ __forceinline__ f16x8 as_halves(f32x4 v) { return __builtin_bit_cast(
 // of one instance per 16-byte store.  No candidates, no constants.
 // kHFine is the second pass of the two-level search (bmu_two_level.hip): the instance tiles are taken
 // through the index list `rows` (all n instances, ordered so that neighbours in the list have nearly the
-// same sets of candidate blocks), and the workgroups of tile t share out the cnt[t] node blocks listed,
-// ascending, in list[t * blocks of the map ..] instead of all of them; candidates are stored under the
-// instances' own numbers.
+// same sets of candidate blocks), and the workgroups of tile t share out the tcnt[t] node blocks listed,
+// ascending, in tlist[t * blocks of the map ..] instead of all of them; candidates are stored under the
+// instances' own numbers.  Collect mode takes such lists too (for the tiles of ITS index list) when the
+// search ran in two levels: a node outside the blocks listed for an instance cannot be its BMU.
 // `unit` numbers the (instance tile, node group) pairs; see the decoding below.
 template <int kMode>
 __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, const float *__restrict__ Wh,
@@ -88,7 +89,8 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
                                                  int flush_chunks, int groups, CandView out, float *__restrict__ dump,
                                                  const int32_t *__restrict__ rows, const int32_t *__restrict__ n_slots,
                                                  const float *__restrict__ thr, int32_t *__restrict__ cnt,
-                                                 int32_t *__restrict__ list, const int64_t unit) {
+                                                 int32_t *__restrict__ list, const int32_t *__restrict__ tcnt,
+                                                 const int32_t *__restrict__ tlist, const int64_t unit) {
   constexpr bool kCollect = kMode == kHCollect;
   constexpr bool kDump = kMode == kHDump;
   constexpr bool kPartial = kMode == kHPartial;
@@ -124,8 +126,9 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
   // the node blocks of this workgroup: positions nb_first .. nb_first + nNB - 1 of the map's blocks, or
   // (fine mode) of the tile's own ascending list
   const int nNB_all = (k + kTN - 1) / kTN;
-  const int32_t *blist = kFine ? list + tile * (int64_t)nNB_all : nullptr;
-  const int nNB_avail = kFine ? min(cnt[tile], nNB_all) : nNB_all;
+  const bool listed = kFine || (kCollect && tlist != nullptr);   // (collect mode: the lists are optional)
+  const int32_t *blist = listed ? tlist + tile * (int64_t)nNB_all : nullptr;
+  const int nNB_avail = listed ? min(tcnt[tile], nNB_all) : nNB_all;
   const int nb_per = (nNB_avail + groups - 1) / groups;
   const int nb_first = group * nb_per;
   const int nNB = min(nb_per, nNB_avail - nb_first);
@@ -171,7 +174,7 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
   const unsigned lds_wn = lds_address_h(&sWn[0][0]);
   const unsigned wn_off = (unsigned)(wave * 64 + lane) * 4u;
   int ld_ord = 0, ld_kc = 0;        // ordinal of the node block being loaded within this workgroup's run
-  int ld_nb = kFine ? blist[nb_first] : nb_first;
+  int ld_nb = listed ? blist[nb_first] : nb_first;
   auto issue_loads = [&](int buf) {
     const char *wbase = reinterpret_cast<const char *>(Wh) + (int64_t)ld_nb * kTN * row_bytes;
     if (ld_kc == 0) {                                           // entering a node block
@@ -195,7 +198,7 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
     if (++ld_kc == nK) {
       ld_kc = 0;
       ++ld_ord;
-      ld_nb = kFine ? (ld_ord < nNB ? blist[nb_first + ld_ord] : 0) : ld_nb + 1;
+      ld_nb = listed ? (ld_ord < nNB ? blist[nb_first + ld_ord] : 0) : ld_nb + 1;
     }
   };
 
@@ -313,7 +316,7 @@ __device__ __forceinline__ void bmu_dense_h_unit(const float *__restrict__ Xh, c
           for (int v = 0; v < 16; ++v) tot[mi][ni][v] += acc[mi][ni][v];
     }
     if (last_k) {
-      const int nb = kFine ? blist[nb_first + ord] : nb_first + ord;
+      const int nb = listed ? blist[nb_first + ord] : nb_first + ord;
       if (kPartial) {
         // lane = instance wi 64 + ni 32 + l32 of the tile; registers 4 g .. 4 g + 3 of an output block are
         // nodes wm 64 + mi 32 + 8 g + 4 lhi .. + 3 of the node block, which lie side by side in the table
@@ -374,18 +377,19 @@ __global__ __launch_bounds__(128 * kHWI, 2) void k_bmu_dense_h(const float *__re
                                                         const int32_t *__restrict__ rows,
                                                         const int32_t *__restrict__ n_slots,
                                                         const float *__restrict__ thr, int32_t *__restrict__ cnt,
-                                                        int32_t *__restrict__ list) {
+                                                        int32_t *__restrict__ list, const int32_t *__restrict__ tcnt,
+                                                        const int32_t *__restrict__ tlist) {
   if (kMode == kHCollect) {
     const int64_t ntiles = ((int64_t)*n_slots + 64 * kHWI - 1) / (64 * kHWI);
     const int64_t units = (ntiles + 7) / 8 * 8 * groups;
     for (int64_t unit = blockIdx.x; unit < units; unit += gridDim.x) {
       bmu_dense_h_unit<kMode>(Xh, Wh, wc, xscale, wscale, n, k, nK, flush_chunks, groups, out, dump, rows,
-                                       n_slots, thr, cnt, list, unit);
+                              n_slots, thr, cnt, list, tcnt, tlist, unit);
       __syncthreads();               // the next unit reuses the LDS stages
     }
   } else {
     bmu_dense_h_unit<kMode>(Xh, Wh, wc, xscale, wscale, n, k, nK, flush_chunks, groups, out, dump, rows,
-                                     n_slots, thr, cnt, list, (int64_t)blockIdx.x);
+                            n_slots, thr, cnt, list, tcnt, tlist, (int64_t)blockIdx.x);
   }
 }
 
@@ -438,11 +442,11 @@ hipError_t launch_bmu_dense_h(som_ctx *c, int64_t n, float *dump) {
   if (dump)
     hipLaunchKernelGGL((k_bmu_dense_h<kHDump>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
                        c->wn32, c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, dump, nullptr, nullptr, nullptr,
-                       nullptr, nullptr);
+                       nullptr, nullptr, nullptr, nullptr);
   else
     hipLaunchKernelGGL((k_bmu_dense_h<kHFilter>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream, Xh, Wh,
                        c->wn32, c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, dump, nullptr, nullptr, nullptr,
-                       nullptr, nullptr);
+                       nullptr, nullptr, nullptr, nullptr);
   return hipGetLastError();
 }
 
@@ -457,7 +461,7 @@ hipError_t launch_bmu_dense_h_fine(som_ctx *c, int64_t n) {
   hipLaunchKernelGGL((k_bmu_dense_h<kHFine>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
                      reinterpret_cast<const float *>(c->Xh), reinterpret_cast<const float *>(c->Wh), c->wn32,
                      c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, nullptr, c->sort_val[0],
-                     nullptr, nullptr, c->tile_cnt, c->tile_list);
+                     nullptr, nullptr, nullptr, nullptr, c->tile_cnt, c->tile_list);
   return hipGetLastError();
 }
 
@@ -471,7 +475,7 @@ hipError_t launch_hot_partial(som_ctx *c, int64_t n) {
   hipLaunchKernelGGL((k_bmu_dense_h<kHPartial>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
                      reinterpret_cast<const float *>(c->hot_Xh), reinterpret_cast<const float *>(c->hot_Wh), nullptr,
                      nullptr, c->hot_wscale, n, c->k, kHot / 32, split_flush_chunks(kHot), groups, out, c->hot_P,
-                     nullptr, nullptr, nullptr, nullptr, nullptr);
+                     nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
   return hipGetLastError();
 }
 
@@ -479,7 +483,8 @@ hipError_t launch_hot_partial(som_ctx *c, int64_t n) {
 // device: the grid is the worst case capped at eight workgroups per CU, and the workgroups walk
 // the live units.  Usually only a few instance tiles are live, so the node blocks are shared out
 // over up to 16 workgroups.
-hipError_t launch_bmu_dense_h_collect(som_ctx *c, int64_t n) {
+// lists: the node blocks of every tile of 128 collect slots are given in c->ctile_cnt / c->ctile_list.
+hipError_t launch_bmu_dense_h_collect(som_ctx *c, int64_t n, bool lists) {
   const int nNB = (c->k + kTN - 1) / kTN;
   const int groups = nNB < 16 ? nNB : 16;
   const int64_t tiles = (n + 64 * kHWI - 1) / (64 * kHWI);
@@ -491,7 +496,8 @@ hipError_t launch_bmu_dense_h_collect(som_ctx *c, int64_t n) {
   hipLaunchKernelGGL((k_bmu_dense_h<kHCollect>), dim3((unsigned)blocks), dim3(128 * kHWI), 0, c->stream,
                      reinterpret_cast<const float *>(c->Xh), reinterpret_cast<const float *>(c->Wh), c->wn32,
                      c->xscale, c->wscale, n, c->k, nK, split_flush_chunks(c->dim), groups, out, nullptr, c->collect_rows, c->list_counts + 1,
-                     c->collect_thr, c->collect_cnt, c->collect_list);
+                     c->collect_thr, c->collect_cnt, c->collect_list, lists ? c->ctile_cnt : nullptr,
+                     lists ? c->ctile_list : nullptr);
   return hipGetLastError();
 }
 

@@ -40,9 +40,14 @@ __global__ __launch_bounds__(256) void k_certify(CandView cand, int groups, cons
                                                  int32_t *__restrict__ collect_rows,
                                                  float *__restrict__ collect_thr,
                                                  int32_t *__restrict__ collect_cnt,
-                                                 int32_t *__restrict__ list_counts, UnitWork work) {
-  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= n) return;
+                                                 int32_t *__restrict__ list_counts, UnitWork work,
+                                                 const int32_t *__restrict__ order) {
+  // with `order` the instances are visited in that order, so that neighbours in it are appended to the
+  // lists together (the wavefront's appends are one atomic): the second sweep's tiles then hold instances
+  // with similar block sets (two-level search)
+  const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= n) return;
+  const int64_t j = order ? (int64_t)order[p] : p;
   static_assert(kCand == 4, "the candidate lists are read as 16-byte vectors");
   const float4 *val4 = reinterpret_cast<const float4 *>(cand.val);
   const int4 *idx4 = reinterpret_cast<const int4 *>(cand.idx);
@@ -481,7 +486,8 @@ MarginModel margin_model(const som_ctx *c, int mode, const int64_t *indptr, bool
   return mm;
 }
 
-hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int64_t *indptr, int32_t *bmus, bool hot) {
+hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int64_t *indptr, int32_t *bmus, bool hot,
+                          const int32_t *order) {
   CandView cand{c->cand_val, c->cand_idx, c->cand_over};
   const MarginModel mm = margin_model(c, mode, indptr, hot);
   UnitWork work{0, 0, nullptr, nullptr, nullptr};
@@ -489,7 +495,7 @@ hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int
     work = UnitWork{c->csr_sweeps, c->unit_cap, c->unit_work, c->list_counts + kUnitCounts, c->collect_list};
   hipLaunchKernelGGL(k_certify, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, cand, groups, c->xn32,
                      c->wmax_bits, c->mu_norm2, mm, n, c->k, bmus, c->cand_n, c->refine_list, c->collect_rows,
-                     c->collect_thr, c->collect_cnt, c->list_counts, work);
+                     c->collect_thr, c->collect_cnt, c->list_counts, work, order);
   return hipGetLastError();
 }
 

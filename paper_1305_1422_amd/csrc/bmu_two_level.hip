@@ -125,14 +125,16 @@ static int size_classes(int blocks) {
 int two_level_key_range(int blocks) { return size_classes(blocks) * blocks; }
 
 // One wavefront per tile of 128 consecutive entries of `rows`: OR of their masks, expanded to a list.
+// The masks are stored with stride n; `rows` has n entries, or *n_rows of them if n_rows is given.
 __global__ __launch_bounds__(256) void k_tile_lists(const uint32_t *__restrict__ mask, const int32_t *__restrict__ rows,
-                                                    int64_t n, int blocks, int64_t tiles,
+                                                    int64_t n, const int32_t *__restrict__ n_rows, int blocks,
                                                     int32_t *__restrict__ tile_cnt, int32_t *__restrict__ tile_list) {
   const int lane = threadIdx.x & 63;
   const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (tile >= tiles) return;                    // uniform over the wavefront
+  const int64_t entries = n_rows ? (int64_t)*n_rows : n;
+  if (tile * 128 >= entries) return;            // uniform over the wavefront
   const int64_t p0 = tile * 128 + lane, p1 = p0 + 64;
-  const int64_t r0 = p0 < n ? rows[p0] : -1, r1 = p1 < n ? rows[p1] : -1;
+  const int64_t r0 = p0 < entries ? rows[p0] : -1, r1 = p1 < entries ? rows[p1] : -1;
   int32_t *out = tile_list + tile * blocks;
   int count = 0;
   for (int w0 = 0; w0 < blocks; w0 += 32) {
@@ -166,7 +168,16 @@ hipError_t launch_tile_lists(som_ctx *c, int64_t n) {
   const int blocks = (c->k + 127) / 128;
   const int64_t tiles = (n + 127) / 128;
   hipLaunchKernelGGL(k_tile_lists, dim3((unsigned)((tiles + 3) / 4)), dim3(256), 0, c->stream, c->coarse_mask,
-                     c->sort_val[0], n, blocks, tiles, c->tile_cnt, c->tile_list);
+                     c->sort_val[0], n, nullptr, blocks, c->tile_cnt, c->tile_list);
+  return hipGetLastError();
+}
+
+// The same for the instances the exact stage sweeps again (c->collect_rows, their number on the device).
+hipError_t launch_collect_tile_lists(som_ctx *c, int64_t n) {
+  const int blocks = (c->k + 127) / 128;
+  const int64_t tiles = (n + 127) / 128;
+  hipLaunchKernelGGL(k_tile_lists, dim3((unsigned)((tiles + 3) / 4)), dim3(256), 0, c->stream, c->coarse_mask,
+                     c->collect_rows, n, c->list_counts + 1, blocks, c->ctile_cnt, c->ctile_list);
   return hipGetLastError();
 }
 

@@ -110,7 +110,7 @@ static void free_row_scratch(som_ctx *c) {
   dev_free(c->radix_hist); dev_free(c->chunk_node); dev_free(c->partial);
   dev_free(c->Xh); dev_free(c->xscale);
   dev_free(c->Xh1); dev_free(c->coarse_min); dev_free(c->coarse_key); dev_free(c->coarse_mask);
-  dev_free(c->tile_cnt); dev_free(c->tile_list);
+  dev_free(c->tile_cnt); dev_free(c->tile_list); dev_free(c->ctile_cnt); dev_free(c->ctile_list);
   c->two_level_n = 0;
   c->n_cap = 0;
   c->cand_cap = 0;
@@ -178,9 +178,10 @@ static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
       c->d_split_valid = 0;
       if (!(dev_alloc(&c->Xh1, (size_t)c->n_cap * row_halves) && dev_alloc(&c->coarse_min, blocks * (size_t)c->n_cap) &&
             dev_alloc(&c->coarse_key, (size_t)c->n_cap) && dev_alloc(&c->coarse_mask, (blocks + 31) / 32 * (size_t)c->n_cap) &&
-            dev_alloc(&c->tile_cnt, tiles) && dev_alloc(&c->tile_list, tiles * blocks))) {
+            dev_alloc(&c->tile_cnt, tiles) && dev_alloc(&c->tile_list, tiles * blocks) &&
+            dev_alloc(&c->ctile_cnt, tiles) && dev_alloc(&c->ctile_list, tiles * blocks))) {
         dev_free(c->Xh1); dev_free(c->coarse_min); dev_free(c->coarse_key); dev_free(c->coarse_mask);
-        dev_free(c->tile_cnt); dev_free(c->tile_list);
+        dev_free(c->tile_cnt); dev_free(c->tile_list); dev_free(c->ctile_cnt); dev_free(c->ctile_list);
         return fail(c, SOM_ERR_ALLOC, "cannot allocate the two-level search's scratch for %lld instances", (long long)c->n_cap);
       }
     }
@@ -312,9 +313,10 @@ static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *
   }
   StageTimer t(c, 2);
   SOM_LAUNCH(c, launch_certify(c, n, coarse ? bmu_dense_h_fine_groups(c, n) : split ? bmu_dense_h_groups(c, n) : bmu_dense_groups(c, n),
-                               split ? kCertifySplit : kCertifyFp32, nullptr, bmus));
+                               split ? kCertifySplit : kCertifyFp32, nullptr, bmus, false, coarse ? c->sort_val[0] : nullptr));
   SOM_LAUNCH(c, launch_refine_dense(c, X, W, bmus));
-  if (split) SOM_LAUNCH(c, launch_bmu_dense_h_collect(c, n));
+  if (coarse) SOM_LAUNCH(c, launch_collect_tile_lists(c, n));
+  if (split) SOM_LAUNCH(c, launch_bmu_dense_h_collect(c, n, coarse));
   else SOM_LAUNCH(c, launch_bmu_dense_collect(c, X, n));
   SOM_LAUNCH(c, launch_refine_lists_dense(c, X, W, bmus));
   SOM_LAUNCH(c, launch_rescan_dense(c, X, W, bmus));

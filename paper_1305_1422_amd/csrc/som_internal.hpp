@@ -111,6 +111,7 @@ struct som_ctx {
   uint32_t *coarse_mask;  // [ceil(blocks/32)][n] node blocks an instance's BMU may lie in
   int32_t *tile_cnt;      // [ceil(n/128)] node blocks listed per instance tile of the sorted order
   int32_t *tile_list;     // [ceil(n/128)][ceil(k/128)] those blocks, ascending
+  int32_t *ctile_cnt, *ctile_list;   // the same for the tiles of collect_rows (second sweep of the exact stage)
   int64_t two_level_n;    // instances of the most recent dense search if it ran in two levels, else 0
   int64_t cand_cap;       // instance slots in the three candidate arrays (node groups x instances)
   float *cand_val;        // [groups][n][kCand]
@@ -213,7 +214,8 @@ hipError_t launch_bmu_dense_h_fine(som_ctx *c, int64_t n);                     /
 hipError_t launch_select_blocks(som_ctx *c, int64_t n);                        // coarse_min -> coarse_key, coarse_mask
 int two_level_key_range(int blocks);                                           // keys of coarse_key are below this
 hipError_t launch_tile_lists(som_ctx *c, int64_t n);                           // coarse_mask, sort_val[0] -> tile_cnt, tile_list
-hipError_t launch_bmu_dense_h_collect(som_ctx *c, int64_t n);                 // rows of collect_rows -> collect_list
+hipError_t launch_collect_tile_lists(som_ctx *c, int64_t n);                   // coarse_mask, collect_rows -> ctile_cnt, ctile_list
+hipError_t launch_bmu_dense_h_collect(som_ctx *c, int64_t n, bool lists = false);   // rows of collect_rows -> collect_list
 hipError_t launch_split_rows_f16(som_ctx *c, const float *A, int64_t nrows, const unsigned *global_max_bits,
                                  const float *mu /* subtracted first, or null */, _Float16 *out, float *scale_out,
                                  int dim = 0 /* row length; 0: the context's */,
@@ -234,7 +236,7 @@ constexpr int kListCounts = 12;    // words in som_ctx::list_counts
 constexpr int kUnitCounts = 4;     // first of the eight work-list lengths in it
 enum { kCertifyFp32 = 0, kCertifySplit = 1, kCertifyCsr = 2, kCertifyCoarse = 3 };      // whose rounding bound the margin uses
 hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int64_t *indptr, int32_t *bmus,
-                          bool hot = false);
+                          bool hot = false, const int32_t *order = nullptr /* visit the instances in this order */);
 hipError_t launch_margins(som_ctx *c, int64_t n, int mode, const int64_t *indptr, double *out,
                           bool hot = false);   // test hook: the margin per instance
 hipError_t launch_refine_dense(som_ctx *c, const float *X, const float *W, int32_t *bmus);
