@@ -206,24 +206,56 @@ __global__ __launch_bounds__(256) void k_accumulate_dense(const float *__restric
   }
 }
 
-// Empty node: zero row.  One chunk: already written.  Several: add the partial rows, eight
-// interleaved running sums (chunk t goes to sum t mod 8) combined pairwise at the end: a fixed
-// order, with eight loads in flight instead of one.
+// Nodes with many chunks (early in training a few nodes hold most of the instances, thousands of chunks
+// each; one workgroup adding them one after the other took three times as long as computing them): every
+// group of kCombineGroup consecutive chunks of such a node is first added up, in place, into the group's
+// first chunk.  One workgroup per chunk slot; only the group leaders of large nodes do anything.
+constexpr int kCombineGroup = 32;
+
+__global__ __launch_bounds__(256) void k_combine_groups(const int32_t *__restrict__ chunk_off,
+                                                        const int32_t *__restrict__ chunk_node, int k, int dim,
+                                                        float *__restrict__ partial) {
+  const int chunk = blockIdx.x;
+  if (chunk >= chunk_off[k]) return;
+  const int b = chunk_node[chunk];
+  const int c0 = chunk_off[b], nc = chunk_off[b + 1] - c0;
+  const int at = chunk - c0;
+  if (nc <= kCombineGroup || at % kCombineGroup != 0) return;
+  const int len = min(kCombineGroup, nc - at);
+  float *dst = partial + (int64_t)chunk * dim;
+  for (int c = blockIdx.y * blockDim.x + threadIdx.x; c < dim; c += gridDim.y * blockDim.x) {
+    double a[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    int t = 0;
+    for (; t + 8 <= len; t += 8)
+#pragma unroll
+      for (int u = 0; u < 8; ++u) a[u] += (double)dst[(int64_t)(t + u) * dim + c];
+    for (int u = 0; t < len; ++t, ++u) a[u] += (double)dst[(int64_t)t * dim + c];
+    dst[c] = (float)(((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7])));
+  }
+}
+
+// Empty node: zero row.  One chunk: already written.  Several: add the partial rows (of a node with more
+// than kCombineGroup chunks: the group sums k_combine_groups left in every kCombineGroup-th row), eight
+// interleaved running sums (term t goes to sum t mod 8) combined pairwise at the end: a fixed order, with
+// eight loads in flight instead of one.
 __global__ __launch_bounds__(256) void k_combine_chunks(const int32_t *__restrict__ chunk_off, int dim,
                                                         const float *__restrict__ partial, float *__restrict__ S) {
   const int b = blockIdx.x;
   const int c0 = chunk_off[b], nc = chunk_off[b + 1] - c0;
   if (nc == 1) return;
   float *dst = S + (int64_t)b * dim;
+  const bool grouped = nc > kCombineGroup;
+  const int terms = grouped ? (nc + kCombineGroup - 1) / kCombineGroup : nc;
+  const int64_t step = (int64_t)(grouped ? kCombineGroup : 1) * dim;
   const float *src = partial + (int64_t)c0 * dim;
   // grid.y splits the columns: late in training a few dozen nodes hold all the chunks
   for (int c = blockIdx.y * blockDim.x + threadIdx.x; c < dim; c += gridDim.y * blockDim.x) {
     double a[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     int t = 0;
-    for (; t + 8 <= nc; t += 8)
+    for (; t + 8 <= terms; t += 8)
 #pragma unroll
-      for (int u = 0; u < 8; ++u) a[u] += (double)src[(int64_t)(t + u) * dim + c];
-    for (int u = 0; t < nc; ++t, ++u) a[u] += (double)src[(int64_t)t * dim + c];
+      for (int u = 0; u < 8; ++u) a[u] += (double)src[(t + u) * step + c];
+    for (int u = 0; t < terms; ++t, ++u) a[u] += (double)src[t * step + c];
     dst[c] = (float)(((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7])));
   }
 }
@@ -405,6 +437,10 @@ hipError_t launch_accumulate_dense(som_ctx *c, const float *X, int64_t n) {
                        c->dim, c->sort_val[0], c->seg_off, c->chunk_off, c->chunk_node, c->k, c->S, c->partial);
   int ysplit = (c->dim + 255) / 256;
   if (ysplit > 16) ysplit = 16;
+  const int cthreads = c->dim >= 256 ? 256 : (c->dim + 63) / 64 * 64;
+  if (max_chunks > kCombineGroup)
+    hipLaunchKernelGGL(k_combine_groups, dim3((unsigned)max_chunks, ysplit), dim3(cthreads), 0, c->stream, c->chunk_off,
+                       c->chunk_node, c->k, c->dim, c->partial);
   hipLaunchKernelGGL(k_combine_chunks, dim3(c->k, ysplit), dim3(256), 0, c->stream, c->chunk_off, c->dim, c->partial,
                      c->S);
   return hipGetLastError();
