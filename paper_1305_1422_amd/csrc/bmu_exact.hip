@@ -43,44 +43,72 @@ __global__ __launch_bounds__(256) void k_certify(CandView cand, int groups, cons
                                                  int32_t *__restrict__ list_counts, UnitWork work,
                                                  const int32_t *__restrict__ order) {
   // with `order` the instances are visited in that order, so that neighbours in it are appended to the
-  // lists together (the wavefront's appends are one atomic): the second sweep's tiles then hold instances
-  // with similar block sets (two-level search)
+  // lists together: the second sweep's tiles then hold instances with similar block sets (two-level
+  // search).  List slots are reserved per workgroup - one atomic per list and workgroup, the positions
+  // inside from ballots - because a million instances' worth of wavefront-wide atomics on one counter
+  // (16,000 of them) were what this kernel spent its time on.
+  __shared__ int s_wave_cnt[2][4], s_base[2];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (p >= n) return;
-  const int64_t j = order ? (int64_t)order[p] : p;
+  const bool live = p < n;
+  const int64_t j = live ? (order ? (int64_t)order[p] : p) : 0;
   static_assert(kCand == 4, "the candidate lists are read as 16-byte vectors");
   const float4 *val4 = reinterpret_cast<const float4 *>(cand.val);
   const int4 *idx4 = reinterpret_cast<const int4 *>(cand.idx);
   float smin = INFINITY, omin = INFINITY;
-  for (int q = 0; q < groups; ++q) {
-    const float4 v = val4[(int64_t)q * n + j];
-    const int4 id = idx4[(int64_t)q * n + j];
-    if ((unsigned)id.x < (unsigned)k) smin = fminf(smin, v.x);
-    if ((unsigned)id.y < (unsigned)k) smin = fminf(smin, v.y);
-    if ((unsigned)id.z < (unsigned)k) smin = fminf(smin, v.z);
-    if ((unsigned)id.w < (unsigned)k) smin = fminf(smin, v.w);
-    omin = fminf(omin, cand.over[(int64_t)q * n + j]);
-  }
-  const double margin = score_margin(mm, j, (double)xn32[j], (double)__uint_as_float(*wmax_bits), (double)*mu_norm2);
-  const double thr = (double)smin + margin;
-  int keep[kCand];
+  double thr = 0.0;
+  int keep[kCand] = {0, 0, 0, 0};
   int cnt = 0;
-  for (int q = 0; q < groups; ++q) {
-    const float4 v4 = val4[(int64_t)q * n + j];
-    const int4 id4 = idx4[(int64_t)q * n + j];
-    const float v[kCand] = {v4.x, v4.y, v4.z, v4.w};
-    const int id[kCand] = {id4.x, id4.y, id4.z, id4.w};
+  if (live) {
+    for (int q = 0; q < groups; ++q) {
+      const float4 v = val4[(int64_t)q * n + j];
+      const int4 id = idx4[(int64_t)q * n + j];
+      if ((unsigned)id.x < (unsigned)k) smin = fminf(smin, v.x);
+      if ((unsigned)id.y < (unsigned)k) smin = fminf(smin, v.y);
+      if ((unsigned)id.z < (unsigned)k) smin = fminf(smin, v.z);
+      if ((unsigned)id.w < (unsigned)k) smin = fminf(smin, v.w);
+      omin = fminf(omin, cand.over[(int64_t)q * n + j]);
+    }
+    const double margin = score_margin(mm, j, (double)xn32[j], (double)__uint_as_float(*wmax_bits), (double)*mu_norm2);
+    thr = (double)smin + margin;
+    for (int q = 0; q < groups; ++q) {
+      const float4 v4 = val4[(int64_t)q * n + j];
+      const int4 id4 = idx4[(int64_t)q * n + j];
+      const float v[kCand] = {v4.x, v4.y, v4.z, v4.w};
+      const int id[kCand] = {id4.x, id4.y, id4.z, id4.w};
 #pragma unroll
-    for (int t = 0; t < kCand; ++t) {
-      if ((unsigned)id[t] < (unsigned)k && (double)v[t] <= thr) {
-        if (cnt < kCand) keep[cnt] = id[t];
-        ++cnt;
+      for (int t = 0; t < kCand; ++t) {
+        if ((unsigned)id[t] < (unsigned)k && (double)v[t] <= thr) {
+          if (cnt < kCand) keep[cnt] = id[t];
+          ++cnt;
+        }
       }
     }
   }
   const bool overflow = (double)omin <= thr || cnt > kCand;
-  if (overflow || cnt == 0) {
-    const int slot = atomicAdd(&list_counts[1], 1);
+  const bool to_collect = live && (overflow || cnt == 0);
+  const bool to_refine = live && !to_collect && cnt > 1;
+  // slots: [0] refine list, [1] collect list
+  const unsigned long long bal_r = __ballot(to_refine), bal_c = __ballot(to_collect);
+  if (lane == 0) {
+    s_wave_cnt[0][wave] = __popcll(bal_r);
+    s_wave_cnt[1][wave] = __popcll(bal_c);
+  }
+  __syncthreads();
+  if (threadIdx.x < 2) {
+    const int total = s_wave_cnt[threadIdx.x][0] + s_wave_cnt[threadIdx.x][1] + s_wave_cnt[threadIdx.x][2] +
+                      s_wave_cnt[threadIdx.x][3];
+    s_base[threadIdx.x] = total ? atomicAdd(&list_counts[threadIdx.x], total) : 0;
+  }
+  __syncthreads();
+  const unsigned long long below = (1ull << lane) - 1ull;
+  int before_r = s_base[0], before_c = s_base[1];
+  for (int w = 0; w < wave; ++w) {
+    before_r += s_wave_cnt[0][w];
+    before_c += s_wave_cnt[1][w];
+  }
+  if (to_collect) {
+    const int slot = before_c + __popcll(bal_c & below);
     collect_rows[slot] = (int32_t)j;
     float t32 = (float)thr;                     // round the threshold up: no score inside the margin is lost
     if ((double)t32 < thr) t32 = nextafterf(t32, INFINITY);
@@ -109,12 +137,12 @@ __global__ __launch_bounds__(256) void k_certify(CandView cand, int groups, cons
       }
     }
     collect_cnt[slot] = filled;
-  } else if (cnt == 1) {
-    bmus[j] = keep[0];
-  } else {
+  } else if (to_refine) {
     for (int t = 0; t < cnt; ++t) cand.idx[j * kCand + t] = keep[t];
     cand_n[j] = cnt;
-    refine_list[atomicAdd(&list_counts[0], 1)] = (int32_t)j;
+    refine_list[before_r + __popcll(bal_r & below)] = (int32_t)j;
+  } else if (live) {
+    bmus[j] = keep[0];
   }
 }
 

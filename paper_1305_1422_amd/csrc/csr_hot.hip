@@ -144,21 +144,22 @@ __global__ __launch_bounds__(256) void k_split_hot_tail(const int64_t *__restric
 __global__ __launch_bounds__(256) void k_gather_hot_codebook(const float *__restrict__ W, const float *__restrict__ mu,
                                                              const int32_t *__restrict__ hot_cols, int k, int dim,
                                                              float *__restrict__ out, unsigned *__restrict__ max_bits) {
-  const int h = threadIdx.x;               // kHot == blockDim.x
-  const int c = hot_cols[h];
-  const float m = mu[c];
   float amax = 0.f;
-  for (int i = blockIdx.x; i < k; i += gridDim.x) {
-    const float t = W[(int64_t)i * dim + c] - m;
-    out[(int64_t)i * kHot + h] = t;
-    amax = fmaxf(amax, fabsf(t));
+  for (int h = threadIdx.x; h < kHot; h += 256) {
+    const int c = hot_cols[h];
+    const float m = mu[c];
+    for (int i = blockIdx.x; i < k; i += gridDim.x) {
+      const float t = W[(int64_t)i * dim + c] - m;
+      out[(int64_t)i * kHot + h] = t;
+      amax = fmaxf(amax, fabsf(t));
+    }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
   if ((threadIdx.x & 63) == 0 && amax > 0.f) atomicMax(max_bits, __float_as_uint(amax));
 }
 
-static_assert(kHot == 256, "k_gather_hot_codebook runs one thread per hot column");
+static_assert(kHot % 256 == 0, "k_gather_hot_codebook deals the hot columns to 256 threads");
 
 hipError_t launch_hot_histogram(som_ctx *c, const int32_t *indices, int64_t nnz, int32_t *counts) {
   hipError_t e = launch_fill_zero_u32(c->stream, counts, c->dim);
@@ -208,7 +209,7 @@ hipError_t launch_gather_hot_codebook(som_ctx *c, const float *W) {
   hipError_t e = launch_fill_zero_u32(c->stream, c->hot_wmax_bits, 1);
   if (e != hipSuccess) return e;
   const int blocks = c->k < c->n_cu * 4 ? c->k : c->n_cu * 4;
-  hipLaunchKernelGGL(k_gather_hot_codebook, dim3(blocks), dim3(kHot), 0, c->stream, W, c->mu, c->hot_cols, c->k,
+  hipLaunchKernelGGL(k_gather_hot_codebook, dim3(blocks), dim3(256), 0, c->stream, W, c->mu, c->hot_cols, c->k,
                      c->dim, c->hot_Wc, c->hot_wmax_bits);
   return hipGetLastError();
 }
