@@ -82,6 +82,8 @@ def main() -> int:
                          "against that trained map - the post-training mapping, a slow corner of the exact stage")
     ap.add_argument("--no-hot-block", action="store_true",
                     help="sparse workloads: keep all columns in the gather sweep (no dense block of frequent columns)")
+    ap.add_argument("--no-dense-planes", action="store_true",
+                    help="sparse workloads of modest dimension: keep the gather sweep (no dense filter pass on planes)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run ten plain 1 GiB device copies and exit: under rocprofv3 --pmc this gives the "
                          "reading of FETCH_SIZE / WRITE_SIZE for a kernel of known traffic")
@@ -125,6 +127,8 @@ def main() -> int:
     som.set_smoothing(args.smoothing)
     if args.no_hot_block:
         som.set_sparse_hot_block(False)
+    if args.no_dense_planes:
+        som.set_sparse_dense_filter(False)
     bmus = torch.empty(w.n, dtype=torch.int32, device=dev)
     # register the resident training set: its norms are then computed once, not every epoch
     if w.kind == "dense":
@@ -173,7 +177,8 @@ def main() -> int:
     # two-level dense search: share of the (instance tile, node block) pairs its second pass works on, from one
     # more, untimed, run through the schedule (the call that reads it synchronises)
     fine_share = None
-    if w.kind == "dense" and args.mode == "epoch":
+    planes = w.kind != "dense" and capi.som_sparse_dense_filter_active(som.ctx)    # sparse rows, dense filter pass
+    if (w.kind == "dense" or planes) and args.mode == "epoch":
         shares = []
         for e in range(w.epochs):
             step(e)
@@ -188,8 +193,8 @@ def main() -> int:
     value = work / (dt / args.steps)
 
     stage_ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in prof.items()}
-    if w.kind == "dense":
-        dom_ms = stage_ms["bmu_dense_filter"]
+    if w.kind == "dense" or planes:
+        dom_ms = stage_ms["bmu_csr_filter" if planes else "bmu_dense_filter"]
         flops = 2.0 * work                               # one multiply-add per (instance, node, feature)
         fp32_equiv = flops / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
         # achieved = the method's own work, one multiply-add per (instance, node, feature) = 2 n k dim flop,
@@ -223,6 +228,10 @@ def main() -> int:
                         "traffic": MEASURED_TRAFFIC_BYTES.get((w.config, args.filter)), "avg_launch_ms": dom_ms,
                         "mfma_issue_frac": 3.0 * fp32_equiv / PEAK_FP16_MFMA_TFLOPS,
                         "vs_fp32_mfma_peak": fp32_equiv / PEAK_FP32_MFMA_TFLOPS}
+        if planes:
+            roofline["note"] = ("sparse rows of modest dimension: the filter pass runs on dense fp16 planes of the centred rows "
+                                "(som_set_sparse_dense_filter), priced as n*k*dim multiply-adds like the dense workloads; "
+                                "the exact stage and the update work on the sparse rows")
     else:
         indptr = X[0]
         nnz = int(indptr[-1])
@@ -250,7 +259,7 @@ def main() -> int:
         "metric": METRIC, "value": value, "unit": "instance*node*dim/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None,
-        "dtype": ("f32" if w.kind != "dense" or args.filter == "fp32" else
+        "dtype": ("f32" if (w.kind != "dense" and not planes) or args.filter == "fp32" else
                   "f32 operands split into 2 x f16, f32 accumulation (filter); f64 (decision)"),
         "data": "synthetic",
         "config": {"workload": f"config {w.config}: {w.name}", "kind": w.kind, "n": w.n, "dim": w.dim,
@@ -262,9 +271,12 @@ def main() -> int:
                             "som_train_epoch on the registered data set: BMU search + batch update, everything that "
                             "depends on the code book included; outside the step, once per registered data set: "
                             + ("squared norms of the instances, their fp16 hi/lo planes, sampled column means"
-                               if w.kind == "dense" else "squared norms of the instances")),
+                               if w.kind == "dense" else
+                               "column means, squared norms and fp16 hi/lo planes of the centred rows" if planes else
+                               "squared norms of the instances, hot-column split")),
                    "neighborhood": args.neighborhood, "smoothing": args.smoothing,
-                   "sparse_hot_block": bool(w.kind != "dense" and capi.som_sparse_hot_block_active(som.ctx))},
+                   "sparse_hot_block": bool(w.kind != "dense" and capi.som_sparse_hot_block_active(som.ctx)),
+                   "sparse_dense_planes": bool(w.kind != "dense" and capi.som_sparse_dense_filter_active(som.ctx))},
         "gflops_epoch": 2.0 * work / (dt / args.steps) / 1e9,
         "frac_fp32_mfma_peak_whole_epoch": 2.0 * work / (dt / args.steps) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
         "stage_ms": stage_ms,

@@ -298,6 +298,22 @@ int som_set_sparse_hot_block(som_ctx *ctx, int enable);
 int som_sparse_hot_block_active(const som_ctx *ctx);
 
 /*
+ * som_set_sparse_dense_filter - whether the BMU search over a REGISTERED sparse training set of modest
+ * dimension may run the DENSE filter pass (som_set_filter) on fp16 planes of the centred rows instead of
+ * the gather sweep (paper: sparse kernel; its comparison of sparse and dense runs on the same 5 % dense
+ * data).  A centred sparse row is dense anyway, and the matrix cores do n x nodes x dim multiply-adds
+ * faster than the vector units do nnz x nodes when the rows are short and well filled.  On by default;
+ * used when dim <= 4,096, at least 3 % of the entries are nonzero and the filter is not SOM_FILTER_FP32.
+ * The exact stage and the update keep working on the caller's sparse rows, so BMUs and code book do not
+ * depend on it.  Prepared at the first epoch or search after registration; costs 4 to 6 bytes of device
+ * memory per entry of the dense matrix.
+ */
+int som_set_sparse_dense_filter(som_ctx *ctx, int enable);
+
+/* 1 if the registered sparse set has been examined and is searched through dense planes, else 0. */
+int som_sparse_dense_filter_active(const som_ctx *ctx);
+
+/*
  * som_set_smoothing - which units run the two passes of the Gaussian neighbourhood smoothing (batch
  * equation; neighbourhood equation).  The result is the same up to the order of the fp32 additions.
  *   SOM_SMOOTH_AUTO (default)  a pass over map lines of at least 32 nodes runs as a matrix product on

@@ -31,7 +31,7 @@ EXPORTS = [
     "som_bmu_distances_dense", "som_bmu_distances_csr", "som_bmu_distances_dense_static",
     "som_cool_schedule", "som_umatrix", "som_get_stats", "som_two_level_stats",
     "som_profile_enable", "som_profile_read",
-    "som_set_filter", "som_set_smoothing", "som_set_sparse_hot_block", "som_sparse_hot_block_active", "som_set_neighborhood", "som_set_scale_cooling", "som_validate_csr", "som_debug_scores_dense", "som_debug_scores_csr", "som_debug_mfma_f16", "som_debug_xcc_ids",
+    "som_set_filter", "som_set_smoothing", "som_set_sparse_hot_block", "som_sparse_hot_block_active", "som_set_sparse_dense_filter", "som_sparse_dense_filter_active", "som_set_neighborhood", "som_set_scale_cooling", "som_validate_csr", "som_debug_scores_dense", "som_debug_scores_csr", "som_debug_mfma_f16", "som_debug_xcc_ids",
 ]
 PROFILE_STAGES = ("bmu_dense_filter", "bmu_csr_filter", "bmu_exact", "node_sums", "smooth_divide", "prepare_dense")
 
@@ -106,6 +106,10 @@ def load():
     L.som_set_sparse_hot_block.argtypes = [vp, i32]
     L.som_sparse_hot_block_active.restype = i32
     L.som_sparse_hot_block_active.argtypes = [vp]
+    L.som_set_sparse_dense_filter.restype = i32
+    L.som_set_sparse_dense_filter.argtypes = [vp, i32]
+    L.som_sparse_dense_filter_active.restype = i32
+    L.som_sparse_dense_filter_active.argtypes = [vp]
     L.som_set_smoothing.restype = i32
     L.som_set_smoothing.argtypes = [vp, i32]
     L.som_set_filter.restype = i32
@@ -344,6 +348,14 @@ def som_set_sparse_hot_block(ctx, enable: bool) -> None:
 
 def som_sparse_hot_block_active(ctx) -> bool:
     return bool(load().som_sparse_hot_block_active(ctx))
+
+
+def som_set_sparse_dense_filter(ctx, enable: bool) -> None:
+    _check(ctx, load().som_set_sparse_dense_filter(ctx, 1 if enable else 0))
+
+
+def som_sparse_dense_filter_active(ctx) -> bool:
+    return bool(load().som_sparse_dense_filter_active(ctx))
 
 
 def som_set_smoothing(ctx, form: int) -> None:

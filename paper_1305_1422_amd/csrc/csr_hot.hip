@@ -159,6 +159,64 @@ __global__ __launch_bounds__(256) void k_gather_hot_codebook(const float *__rest
   if ((threadIdx.x & 63) == 0 && amax > 0.f) atomicMax(max_bits, __float_as_uint(amax));
 }
 
+// ---- dense planes of a registered sparse set of modest dimension (som_set_sparse_dense_filter)
+// Column sums of the nonzeros (fp32 atomics: the result is only used as a centring vector, any vector
+// serves) and rows written out densely, zeros included, for the kernels that split dense rows into planes.
+__global__ __launch_bounds__(256) void k_csr_col_sums(const int32_t *__restrict__ indices, const float *__restrict__ values,
+                                                      int64_t nnz, int dim, float *__restrict__ sums) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += stride) {
+    const int c = indices[p];
+    if (c >= 0 && c < dim) unsafeAtomicAdd(&sums[c], values[p]);
+  }
+}
+
+__global__ __launch_bounds__(256) void k_scale_vector(float *__restrict__ v, int len, float factor) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < len) v[i] *= factor;
+}
+
+// One workgroup per row: clear, then add the nonzeros in (indices outside [0, dim) are clamped as everywhere;
+// a column listed twice counts twice, as in the sweep).
+__global__ __launch_bounds__(256) void k_csr_densify(const int64_t *__restrict__ indptr, const int32_t *__restrict__ indices,
+                                                     const float *__restrict__ values, int64_t row0, int64_t nrows,
+                                                     int dim, float *__restrict__ out) {
+  for (int64_t r = blockIdx.x; r < nrows; r += gridDim.x) {
+    float *o = out + r * dim;
+    for (int c = threadIdx.x; c < dim; c += 256) o[c] = 0.f;
+    __syncthreads();
+    for (int64_t p = indptr[row0 + r] + threadIdx.x; p < indptr[row0 + r + 1]; p += 256) {
+      int c = indices[p];
+      c = c < 0 ? 0 : (c >= dim ? dim - 1 : c);
+      unsafeAtomicAdd(&o[c], values[p]);
+    }
+    __syncthreads();
+  }
+}
+
+hipError_t launch_csr_col_sums(som_ctx *c, const int32_t *indices, const float *values, int64_t nnz, float *sums) {
+  hipError_t e = launch_fill_zero_u32(c->stream, sums, c->dim);
+  if (e != hipSuccess || nnz < 1) return e;
+  int64_t blocks = (nnz + 255) / 256;
+  if (blocks > (int64_t)c->n_cu * 8) blocks = (int64_t)c->n_cu * 8;
+  hipLaunchKernelGGL(k_csr_col_sums, dim3((unsigned)blocks), dim3(256), 0, c->stream, indices, values, nnz, c->dim, sums);
+  return hipGetLastError();
+}
+
+hipError_t launch_scale_vector(som_ctx *c, float *v, int len, float factor) {
+  hipLaunchKernelGGL(k_scale_vector, dim3((len + 255) / 256), dim3(256), 0, c->stream, v, len, factor);
+  return hipGetLastError();
+}
+
+hipError_t launch_csr_densify(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
+                              int64_t row0, int64_t nrows, float *out) {
+  int64_t blocks = nrows < (int64_t)c->n_cu * 16 ? nrows : (int64_t)c->n_cu * 16;
+  if (blocks < 1) return hipSuccess;
+  hipLaunchKernelGGL(k_csr_densify, dim3((unsigned)blocks), dim3(256), 0, c->stream, indptr, indices, values, row0,
+                     nrows, c->dim, out);
+  return hipGetLastError();
+}
+
 static_assert(kHot % 256 == 0, "k_gather_hot_codebook deals the hot columns to 256 threads");
 
 hipError_t launch_hot_histogram(som_ctx *c, const int32_t *indices, int64_t nnz, int32_t *counts) {

@@ -116,6 +116,8 @@ static void free_row_scratch(som_ctx *c) {
   c->cand_cap = 0;
   c->d_norms_valid = 0;
   c->d_split_valid = 0;
+  c->csrd_valid = 0;
+  c->csrd_on = 0;
 }
 
 // Scratch that scales with the number of instances; grown (never shrunk) on demand.
@@ -165,6 +167,7 @@ static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
       return fail(c, SOM_ERR_ALLOC, "cannot allocate the fp16 planes of the code book");
     if (c->Xh == nullptr) {
       c->d_split_valid = 0;
+      c->csrd_valid = 0;
       if (!(dev_alloc(&c->Xh, (size_t)c->n_cap * row_halves) && dev_alloc(&c->xscale, (size_t)c->n_cap)))
         return fail(c, SOM_ERR_ALLOC, "cannot allocate the fp16 planes of %lld instances", (long long)c->n_cap);
     }
@@ -176,6 +179,7 @@ static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
       return fail(c, SOM_ERR_ALLOC, "cannot allocate the fp16 plane of the code book");
     if (c->Xh1 == nullptr) {
       c->d_split_valid = 0;
+      c->csrd_valid = 0;
       if (!(dev_alloc(&c->Xh1, (size_t)c->n_cap * row_halves) && dev_alloc(&c->coarse_min, blocks * (size_t)c->n_cap) &&
             dev_alloc(&c->coarse_key, (size_t)c->n_cap) && dev_alloc(&c->coarse_mask, (blocks + 31) / 32 * (size_t)c->n_cap) &&
             dev_alloc(&c->tile_cnt, tiles) && dev_alloc(&c->tile_list, tiles * blocks) &&
@@ -273,6 +277,7 @@ static int prepare_dense(som_ctx *c, const float *X, int64_t n, const float *W, 
   if (!have_xn) {
     c->d_norms_valid = 0;
     c->d_split_valid = 0;
+    c->csrd_valid = 0;          // the planes are about to hold other rows
     SOM_LAUNCH(c, launch_sample_col_means(c, X, n, c->dim, c->mu));
     SOM_LAUNCH(c, launch_vec_sqnorm(c, c->mu, c->dim, c->mu_norm2));
     SOM_LAUNCH(c, launch_row_sqnorms(c, X, n, c->dim, split ? c->mu : nullptr, c->xn32, nullptr, nullptr));
@@ -290,6 +295,22 @@ static int prepare_dense(som_ctx *c, const float *X, int64_t n, const float *W, 
   return SOM_OK;
 }
 
+// The filter pass over the planes (or, with the fp32 filter, over X itself): candidates per instance.
+static int dense_filter_stage(som_ctx *c, const float *X, int64_t n, bool split, bool coarse) {
+  if (coarse) {
+    SOM_LAUNCH(c, launch_bmu_coarse(c, n, nullptr));
+    SOM_LAUNCH(c, launch_select_blocks(c, n));
+    SOM_LAUNCH(c, launch_sort_keys(c, c->coarse_key, n, two_level_key_range((c->k + 127) / 128)));
+    SOM_LAUNCH(c, launch_tile_lists(c, n));
+    SOM_LAUNCH(c, launch_bmu_dense_h_fine(c, n));
+  } else if (split) {
+    SOM_LAUNCH(c, launch_bmu_dense_h(c, n, nullptr));
+  } else {
+    SOM_LAUNCH(c, launch_bmu_dense(c, X, n, nullptr));
+  }
+  return SOM_OK;
+}
+
 static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *W, int32_t *bmus, bool have_xn) {
   int rc = ensure_candidates(c, n, true);
   if (!rc) rc = prepare_dense(c, X, n, W, have_xn);
@@ -299,17 +320,8 @@ static int bmu_search_dense(som_ctx *c, const float *X, int64_t n, const float *
   c->two_level_n = coarse ? n : 0;
   {
     StageTimer t(c, 0);
-    if (coarse) {
-      SOM_LAUNCH(c, launch_bmu_coarse(c, n, nullptr));
-      SOM_LAUNCH(c, launch_select_blocks(c, n));
-      SOM_LAUNCH(c, launch_sort_keys(c, c->coarse_key, n, two_level_key_range((c->k + 127) / 128)));
-      SOM_LAUNCH(c, launch_tile_lists(c, n));
-      SOM_LAUNCH(c, launch_bmu_dense_h_fine(c, n));
-    } else if (split) {
-      SOM_LAUNCH(c, launch_bmu_dense_h(c, n, nullptr));
-    } else {
-      SOM_LAUNCH(c, launch_bmu_dense(c, X, n, nullptr));
-    }
+    rc = dense_filter_stage(c, X, n, split, coarse);
+    if (rc) return rc;
   }
   StageTimer t(c, 2);
   SOM_LAUNCH(c, launch_certify(c, n, coarse ? bmu_dense_h_fine_groups(c, n) : split ? bmu_dense_h_groups(c, n) : bmu_dense_groups(c, n),
@@ -359,8 +371,54 @@ static int codebook_for_sweep(som_ctx *c, const float *W) {
   return SOM_OK;
 }
 
+// Sparse rows searched through their dense planes: the dense filter stage against the data-centred code
+// book, then the exact stage on the sparse rows themselves.  The centring vector and the norms of the
+// centred rows are the registration's own copies, put in place of the context's for the launches.
+struct PlaneOperands {
+  som_ctx *c;
+  float *mu, *mu_norm2, *xn32;
+  explicit PlaneOperands(som_ctx *ctx) : c(ctx), mu(ctx->mu), mu_norm2(ctx->mu_norm2), xn32(ctx->xn32) {
+    c->mu = c->csrd_mu; c->mu_norm2 = c->csrd_mu_norm2; c->xn32 = c->csrd_xn;
+  }
+  ~PlaneOperands() { c->mu = mu; c->mu_norm2 = mu_norm2; c->xn32 = xn32; }
+};
+
+static int dense_filter_stage(som_ctx *c, const float *X, int64_t n, bool split, bool coarse);
+
+static int bmu_search_csr_planes(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
+                                 int64_t n, const float *W, int32_t *bmus) {
+  int rc = ensure_candidates(c, n, true);
+  if (rc) return rc;
+  PlaneOperands swap(c);
+  const bool coarse = two_level_ready(c, n);
+  c->two_level_n = coarse ? n : 0;
+  {
+    StageTimer t(c, 5);
+    SOM_LAUNCH(c, launch_center_codebook(c, W, true, true /* |w|^2 in fp64 for the sparse exact kernels */, true));
+    if (c->nb_function == SOM_NEIGHBORHOOD_BUBBLE) SOM_LAUNCH(c, launch_mask_duplicate_rows(c, W));
+    SOM_LAUNCH(c, launch_split_rows_f16(c, c->Wc, c->k, c->wmax_bits + 1, nullptr, c->Wh, c->wscale, 0,
+                                        coarse ? c->Wh1 : nullptr));
+    SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, kListCounts));
+  }
+  {
+    StageTimer t(c, 1);
+    rc = dense_filter_stage(c, nullptr, n, true, coarse);
+    if (rc) return rc;
+  }
+  StageTimer t(c, 2);
+  SOM_LAUNCH(c, launch_certify(c, n, coarse ? bmu_dense_h_fine_groups(c, n) : bmu_dense_h_groups(c, n), kCertifySplit,
+                               nullptr, bmus, false, coarse ? c->sort_val[0] : nullptr));
+  SOM_LAUNCH(c, launch_refine_csr(c, indptr, indices, values, W, bmus));
+  if (coarse) SOM_LAUNCH(c, launch_collect_tile_lists(c, n));
+  SOM_LAUNCH(c, launch_bmu_dense_h_collect(c, n, coarse));
+  SOM_LAUNCH(c, launch_refine_lists_csr(c, indptr, indices, values, W, bmus));
+  SOM_LAUNCH(c, launch_rescan_csr(c, indptr, indices, values, W, bmus));
+  return SOM_OK;
+}
+
 static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
                           int64_t n, int64_t nnz, const float *W, int32_t *bmus, bool have_xn) {
+  if (have_xn && c->csrd_valid && c->csrd_on) return bmu_search_csr_planes(c, indptr, indices, values, n, W, bmus);
   int rc = prepare_csr(c, indptr, indices, values, n, nnz, W, have_xn);
   if (rc) return rc;
   // registered rows whose frequent columns were split off: the sweeps walk the tail and start from the
@@ -497,6 +555,60 @@ static int registered_hot(som_ctx *c) {
   return SOM_OK;
 }
 
+// Dense planes of the registered sparse set (som_set_sparse_dense_filter), examined once per registration:
+// column means of the rows as the centring vector, then the rows are written out densely a batch at a time
+// and go through the kernels that give dense data their norms and fp16 planes.  Leaves csrd_on = 0 when the
+// mode is switched off, the filter does not use planes, or the rows are too long or too empty for the
+// matrix cores to beat the gather sweep.
+static int registered_csr_dense(som_ctx *c) {
+  if (c->csrd_valid) return SOM_OK;
+  c->csrd_valid = 1;
+  c->csrd_on = 0;
+  const int64_t n = c->d_n, nnz = c->d_nnz;
+  if (!c->csrd_enabled || c->data_kind != 2 || !uses_planes(c) || c->dim > kCsrDenseMaxDim || nnz < 1) return SOM_OK;
+  if ((double)nnz < kCsrDenseMinDensity * (double)n * (double)c->dim) return SOM_OK;
+  int rc = ensure_rows(c, n, true);          // planes, centred code book (may reset csrd_valid: set again below)
+  if (rc) return rc;
+  c->csrd_valid = 1;
+  if (n > c->csrd_n_cap || !c->csrd_mu) {
+    dev_free(c->csrd_xn); dev_free(c->csrd_mu); dev_free(c->csrd_mu_norm2);
+    c->csrd_n_cap = 0;
+    if (!(dev_alloc(&c->csrd_xn, (size_t)n) && dev_alloc(&c->csrd_mu, (size_t)c->dim) && dev_alloc(&c->csrd_mu_norm2, 1))) {
+      dev_free(c->csrd_xn); dev_free(c->csrd_mu); dev_free(c->csrd_mu_norm2);
+      return fail(c, SOM_ERR_ALLOC, "cannot allocate the norms of %lld centred rows", (long long)n);
+    }
+    c->csrd_n_cap = n;
+  }
+  SOM_LAUNCH(c, launch_csr_col_sums(c, c->d_indices, c->d_values, nnz, c->csrd_mu));
+  SOM_LAUNCH(c, launch_scale_vector(c, c->csrd_mu, c->dim, 1.0f / (float)n));
+  SOM_LAUNCH(c, launch_vec_sqnorm(c, c->csrd_mu, c->dim, c->csrd_mu_norm2));
+  // batches of rows through a dense buffer of at most 1 GiB
+  int64_t batch = (1ll << 28) / c->dim;
+  if (batch > n) batch = n;
+  if (batch < 1) batch = 1;
+  float *dense = nullptr;
+  if (!dev_alloc(&dense, (size_t)batch * c->dim)) return fail(c, SOM_ERR_ALLOC, "cannot allocate a batch of dense rows");
+  const bool coarse = two_level_ready(c, n);
+  const size_t row_halves = (size_t)((c->dim + 31) / 32) * 64, row_halves1 = (size_t)((c->dim + 63) / 64) * 64;
+  int rcl = SOM_OK;
+  for (int64_t r0 = 0; r0 < n && rcl == SOM_OK; r0 += batch) {
+    const int64_t rows = n - r0 < batch ? n - r0 : batch;
+    hipError_t e = launch_csr_densify(c, c->d_indptr, c->d_indices, c->d_values, r0, rows, dense);
+    if (e == hipSuccess) e = launch_row_sqnorms(c, dense, rows, c->dim, c->csrd_mu, c->csrd_xn + r0, nullptr, nullptr);
+    if (e == hipSuccess)
+      e = launch_split_rows_f16(c, dense, rows, nullptr, c->csrd_mu, c->Xh + (size_t)r0 * row_halves, c->xscale + r0, 0,
+                                coarse ? c->Xh1 + (size_t)r0 * row_halves1 : nullptr);
+    if (e != hipSuccess) rcl = dev_fail(c, e, "dense planes of the sparse rows");
+  }
+  hipError_t es = hipStreamSynchronize(c->stream);     // the batch buffer is freed below
+  dev_free(dense);
+  if (rcl != SOM_OK) return rcl;
+  if (es != hipSuccess) return dev_fail(c, es, "dense planes of the sparse rows");
+  c->d_split_valid = 0;       // the planes do not belong to a registered dense set
+  c->csrd_on = 1;
+  return SOM_OK;
+}
+
 static bool is_registered_dense(const som_ctx *c, const float *data, int64_t n) {
   return c->data_kind == 1 && data == c->d_data && n == c->d_n;
 }
@@ -533,6 +645,7 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
   c->filter = SOM_FILTER_AUTO;
   c->scale_cooling = -1;
   c->hot_enabled = 1;
+  c->csrd_enabled = 1;
   c->smooth_mfma_min = kSmoothMfmaMin;
 
   int dev = 0;
@@ -595,6 +708,7 @@ void som_destroy(som_ctx *c) {
   dev_free(c->mu); dev_free(c->mu_partial); dev_free(c->Wc); dev_free(c->zero16); dev_free(c->mu_norm2);
   dev_free(c->Wh); dev_free(c->Wh1); dev_free(c->wscale);
   free_hot(c);
+  dev_free(c->csrd_mu); dev_free(c->csrd_mu_norm2); dev_free(c->csrd_xn);
   dev_free(c->hot_counts); dev_free(c->hot_rank); dev_free(c->hot_cols); dev_free(c->hot_Wc); dev_free(c->hot_Wh);
   dev_free(c->hot_wscale); dev_free(c->hot_wmax_bits);
   for (int s = 0; s < SOM_PROFILE_STAGES; ++s) {
@@ -627,7 +741,8 @@ int som_bmus_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, cons
   bool reg = false;
   if (!rc && is_registered_csr(c, indptr, indices, values, n)) {
     rc = registered_norms(c);
-    if (!rc) rc = registered_hot(c);
+    if (!rc) rc = registered_csr_dense(c);
+    if (!rc && !c->csrd_on) rc = registered_hot(c);
     reg = true;
   }
   if (rc) return rc;
@@ -723,7 +838,8 @@ int som_train_epoch_csr(som_ctx *c, const int64_t *indptr, const int32_t *indice
   bool reg = false;
   if (!rc && is_registered_csr(c, indptr, indices, values, n)) {
     rc = registered_norms(c);
-    if (!rc) rc = registered_hot(c);
+    if (!rc) rc = registered_csr_dense(c);
+    if (!rc && !c->csrd_on) rc = registered_hot(c);
     reg = true;
   }
   if (rc) return rc;
@@ -744,6 +860,8 @@ int som_set_data_dense(som_ctx *c, const float *data, int64_t n) {
   c->d_split_valid = 0;
   c->hot_valid = 0;
   c->hot_on = 0;
+  c->csrd_valid = 0;
+  c->csrd_on = 0;
   return SOM_OK;
 }
 
@@ -758,6 +876,8 @@ int som_set_data_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, 
   c->d_split_valid = 0;
   c->hot_valid = 0;
   c->hot_on = 0;
+  c->csrd_valid = 0;
+  c->csrd_on = 0;
   return SOM_OK;
 }
 
@@ -796,7 +916,8 @@ int som_train_snapshots(som_ctx *c, int n_epochs, float radius0, float radiusN, 
   int rc = ensure_rows(c, c->d_n, dense);
   if (rc) return rc;
   rc = registered_norms(c);
-  if (!rc && !dense) rc = registered_hot(c);
+  if (!rc && !dense) rc = registered_csr_dense(c);
+  if (!rc && !dense && !c->csrd_on) rc = registered_hot(c);
   if (rc) return rc;
   for (int e = 0; e < n_epochs; ++e) {
     SOM_LAUNCH(c, launch_epoch_params(c, e, n_epochs, radius0, radiusN, scale0, scaleN, cooling));
@@ -904,6 +1025,16 @@ int som_set_sparse_hot_block(som_ctx *c, int enable) {
 
 int som_sparse_hot_block_active(const som_ctx *c) { return c && c->hot_valid && c->hot_on ? 1 : 0; }
 
+int som_set_sparse_dense_filter(som_ctx *c, int enable) {
+  if (!c) return SOM_ERR_INVALID_ARG;
+  c->csrd_enabled = enable ? 1 : 0;
+  c->csrd_valid = 0;         // examined again at the next use of the registered set
+  c->csrd_on = 0;
+  return SOM_OK;
+}
+
+int som_sparse_dense_filter_active(const som_ctx *c) { return c && c->csrd_valid && c->csrd_on ? 1 : 0; }
+
 int som_set_smoothing(som_ctx *c, int form) {
   if (!c) return SOM_ERR_INVALID_ARG;
   if (form != SOM_SMOOTH_AUTO && form != SOM_SMOOTH_VECTOR && form != SOM_SMOOTH_MATRIX)
@@ -920,6 +1051,7 @@ int som_set_filter(som_ctx *c, int filter) {
   if (filter != c->filter) {           // norms and planes of a registered set belong to the filter they were made for
     c->d_norms_valid = 0;
     c->d_split_valid = 0;
+    c->csrd_valid = 0;
   }
   c->filter = filter;
   return SOM_OK;

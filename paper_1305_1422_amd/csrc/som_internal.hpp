@@ -18,6 +18,8 @@ constexpr int kChunkRows = 32;            // instances summed by one block of th
 constexpr int kSortTile = 1024;           // fewest keys ranked by one wave of the radix scatter
 constexpr int kSmoothMatMax = 1024;        // largest map side for which the smoothing filters are stored as matrices
 constexpr int kSmoothMfmaMin = 32;         // shortest map line whose smoothing pass runs on the matrix cores by default
+constexpr int kCsrDenseMaxDim = 4096;      // registered sparse sets up to this many columns may be searched through dense planes
+constexpr double kCsrDenseMinDensity = 0.03;   // ... if at least this share of their entries is nonzero
 constexpr int kHot = 256;                  // columns of the dense hot block of a registered sparse training set
 constexpr double kHotMinShare = 0.3;       // share of the nonzeros those columns must hold for the split to be used
 constexpr int kProfMax = 512;              // event brackets kept per stage between two reads
@@ -157,6 +159,15 @@ struct som_ctx {
   unsigned *hot_wmax_bits;    // [1]
   float *hot_P;           // [ceil(k/128)][n][128] dot products of the hot parts divided by the instance scale
 
+  // dense planes of the registered sparse training set (som_set_sparse_dense_filter); built on first use
+  int csrd_valid;         // 0: not examined yet; 1: examined (csrd_on says whether the planes are in use)
+  int csrd_on;
+  int csrd_enabled;
+  float *csrd_mu;         // [dim] column means of the sparse set: the centring vector of its planes
+  float *csrd_mu_norm2;   // [1]
+  float *csrd_xn;         // [n] squared norms of the centred rows
+  int64_t csrd_n_cap;
+
   // registered training set for som_train
   int data_kind;          // 0 none, 1 dense, 2 csr
   const float *d_data;
@@ -260,6 +271,10 @@ hipError_t launch_bmu_distances(som_ctx *c, const float *X, const int64_t *indpt
                                 double *qerror);     // X != NULL: dense rows, else CSR
 
 // csr_hot.hip
+hipError_t launch_csr_col_sums(som_ctx *c, const int32_t *indices, const float *values, int64_t nnz, float *sums);
+hipError_t launch_csr_densify(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
+                              int64_t row0, int64_t nrows, float *out /* [nrows][dim] */);
+hipError_t launch_scale_vector(som_ctx *c, float *v, int len, float factor);
 hipError_t launch_hot_histogram(som_ctx *c, const int32_t *indices, int64_t nnz, int32_t *counts);
 hipError_t launch_tail_lengths(som_ctx *c, const int64_t *indptr, const int32_t *indices, int64_t n, int32_t *len);
 hipError_t launch_split_hot_tail(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,

@@ -72,6 +72,11 @@ class Som:
         """Allow (default) or forbid the dense block of frequent columns of a registered sparse set."""
         capi.som_set_sparse_hot_block(self.ctx, enable)
 
+    def set_sparse_dense_filter(self, enable: bool) -> None:
+        """Allow (default) or forbid the dense filter pass on fp16 planes for a registered sparse set of modest
+        dimension."""
+        capi.som_set_sparse_dense_filter(self.ctx, enable)
+
     def set_smoothing(self, form: str) -> None:
         """Units that run the Gaussian smoothing passes: "auto" (default), "vector" or "matrix"; same results."""
         capi.som_set_smoothing(self.ctx, {"auto": capi.SOM_SMOOTH_AUTO, "vector": capi.SOM_SMOOTH_VECTOR,

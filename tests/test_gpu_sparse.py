@@ -2,7 +2,7 @@
 import numpy as np
 import pytest
 
-from gen import scaled_workload, sparse_zipf_csr
+from gen import scaled_workload, sparse_uniform_csr, sparse_zipf_csr
 from tests import parity as P
 
 pytestmark = pytest.mark.gpu
@@ -378,4 +378,76 @@ def test_hot_column_block_is_declined_for_evenly_used_columns(oracle):
     b = som.bmus(csr_d).cpu().numpy()
     assert not capi.som_sparse_hot_block_active(som.ctx)       # 256 of 2,048 evenly used columns hold an eighth
     P.check_bmus_csr(oracle, csr, dim, W, b)
+    som.close()
+
+
+@pytest.mark.parametrize("n,dim,rows,cols,density,filt", [(1500, 600, 30, 40, 0.05, None), (700, 333, 9, 11, 0.2, "split_f16"),
+                                                           (2000, 96, 36, 36, 0.5, "two_level")])
+def test_dense_planes_of_a_registered_set(oracle, n, dim, rows, cols, density, filt):
+    """A registered sparse set of modest dimension and at least 3 % nonzeros is searched through the dense
+    filter on fp16 planes of its centred rows; the exact stage and the update stay on the sparse rows.  BMUs
+    are the exact argmin either way: the same with the planes on and off, epoch by epoch, equal to the
+    oracle's; row 0 is empty, row 1 has a single nonzero."""
+    from paper_1305_1422_amd import Som, capi
+    indptr, indices, values = sparse_uniform_csr(n, dim, 81, density=density)
+    keep = np.ones(indices.size, bool)
+    keep[indptr[0]:indptr[1]] = False
+    keep[indptr[1] + 1:indptr[2]] = False
+    lens = np.add.reduceat(keep, indptr[:-1]) * (np.diff(indptr) > 0)
+    indptr2 = np.zeros(n + 1, np.int64)
+    np.cumsum(lens, out=indptr2[1:])
+    csr = (indptr2, indices[keep], values[keep])
+    assert indptr2[1] == 0 and indptr2[2] == 1
+    csr_d = P.csr_to_dev(csr)
+    W0 = np.random.default_rng(82).random((rows * cols, dim)).astype(np.float32)
+    out = {}
+    for on in (True, False):
+        som = Som(rows, cols, dim, "planar", "hexagonal", codebook=torch.from_numpy(W0), filter=filt)
+        som.set_sparse_dense_filter(on)
+        capi.som_set_data_csr(som.ctx, *csr_d)
+        seq = []
+        for radius in (5.0, 2.0, 1.0):
+            W_in = som.codebook.cpu().numpy().copy()
+            b = som.train_epoch(csr_d, radius).cpu().numpy()
+            assert capi.som_sparse_dense_filter_active(som.ctx) == on
+            P.check_bmus_csr(oracle, csr, dim, W_in, b)
+            seq.append(b)
+        b = som.bmus(csr_d).cpu().numpy()                      # search only, on the final map
+        P.check_bmus_csr(oracle, csr, dim, som.codebook.cpu().numpy(), b)
+        out[on] = seq
+        som.close()
+    assert np.array_equal(out[True][0], out[False][0])         # same input code book: same BMUs, bit for bit
+
+
+def test_dense_planes_are_declined_or_dropped(oracle):
+    """Not used for long or nearly empty rows, nor with the fp32 filter; and a search over other data on the same
+    context (which reuses the plane buffers) makes the next epoch on the registered set build them again."""
+    from paper_1305_1422_amd import Som, capi
+    rng = np.random.default_rng(83)
+    rows, cols = 8, 9
+    for n, dim, density, filt in [(300, 5000, 0.05, None), (300, 800, 0.01, None), (300, 800, 0.1, "fp32")]:
+        csr = sparse_uniform_csr(n, dim, 84, density=density)
+        W = rng.random((rows * cols, dim)).astype(np.float32)
+        som = Som(rows, cols, dim, codebook=torch.from_numpy(W), filter=filt)
+        csr_d = P.csr_to_dev(csr)
+        capi.som_set_data_csr(som.ctx, *csr_d)
+        b = som.bmus(csr_d).cpu().numpy()
+        assert not capi.som_sparse_dense_filter_active(som.ctx)
+        P.check_bmus_csr(oracle, csr, dim, W, b)
+        som.close()
+    n, dim = 900, 400
+    csr = sparse_uniform_csr(n, dim, 85, density=0.08)
+    other = rng.random((1300, dim)).astype(np.float32)          # more rows than the registered set: the scratch grows
+    W = rng.random((rows * cols, dim)).astype(np.float32)
+    som = Som(rows, cols, dim, codebook=torch.from_numpy(W))
+    csr_d = P.csr_to_dev(csr)
+    capi.som_set_data_csr(som.ctx, *csr_d)
+    b1 = som.bmus(csr_d).cpu().numpy()
+    assert capi.som_sparse_dense_filter_active(som.ctx)
+    bo = som.bmus(P.to_dev(other)).cpu().numpy()
+    P.check_bmus_dense(oracle, other, W, bo)
+    b2 = som.bmus(csr_d).cpu().numpy()
+    assert capi.som_sparse_dense_filter_active(som.ctx)
+    assert np.array_equal(b1, b2)
+    P.check_bmus_csr(oracle, csr, dim, W, b2)
     som.close()
