@@ -303,7 +303,7 @@ int som_sparse_hot_block_active(const som_ctx *ctx);
  * the gather sweep (paper: sparse kernel; its comparison of sparse and dense runs on the same 5 % dense
  * data).  A centred sparse row is dense anyway, and the matrix cores do n x nodes x dim multiply-adds
  * faster than the vector units do nnz x nodes when the rows are short and well filled.  On by default;
- * used when dim <= 4,096, at least 3 % of the entries are nonzero and the filter is not SOM_FILTER_FP32.
+ * used when dim <= 4,096, at least 4 % of the entries are nonzero and the filter is not SOM_FILTER_FP32.
  * The exact stage and the update keep working on the caller's sparse rows, so BMUs and code book do not
  * depend on it.  Prepared at the first epoch or search after registration; costs 4 to 6 bytes of device
  * memory per entry of the dense matrix.

@@ -19,7 +19,7 @@ constexpr int kSortTile = 1024;           // fewest keys ranked by one wave of t
 constexpr int kSmoothMatMax = 1024;        // largest map side for which the smoothing filters are stored as matrices
 constexpr int kSmoothMfmaMin = 32;         // shortest map line whose smoothing pass runs on the matrix cores by default
 constexpr int kCsrDenseMaxDim = 4096;      // registered sparse sets up to this many columns may be searched through dense planes
-constexpr double kCsrDenseMinDensity = 0.03;   // ... if at least this share of their entries is nonzero
+constexpr double kCsrDenseMinDensity = 0.04;   // ... if at least this share of their entries is nonzero
 constexpr int kHot = 256;                  // columns of the dense hot block of a registered sparse training set
 constexpr double kHotMinShare = 0.3;       // share of the nonzeros those columns must hold for the split to be used
 constexpr int kProfMax = 512;              // event brackets kept per stage between two reads

@@ -384,7 +384,7 @@ def test_hot_column_block_is_declined_for_evenly_used_columns(oracle):
 @pytest.mark.parametrize("n,dim,rows,cols,density,filt", [(1500, 600, 30, 40, 0.05, None), (700, 333, 9, 11, 0.2, "split_f16"),
                                                            (2000, 96, 36, 36, 0.5, "two_level")])
 def test_dense_planes_of_a_registered_set(oracle, n, dim, rows, cols, density, filt):
-    """A registered sparse set of modest dimension and at least 3 % nonzeros is searched through the dense
+    """A registered sparse set of modest dimension and at least 4 % nonzeros is searched through the dense
     filter on fp16 planes of its centred rows; the exact stage and the update stay on the sparse rows.  BMUs
     are the exact argmin either way: the same with the planes on and off, epoch by epoch, equal to the
     oracle's; row 0 is empty, row 1 has a single nonzero."""
