@@ -58,8 +58,8 @@ void csr_slice_geometry(int k, int *acc, int *sweeps, int *kpad) {
 // relies on bit-identical rows having bit-identical norms), the largest |w'_i|^2, and the transposed
 // 16-bit code book: entries q = round(w' / step_c) as int16, |q| <= 32767 by the choice of the step; nodes
 // past k are zeros.  A workgroup owns 64 nodes and a slab of the columns, which it walks in tiles of 64:
-// a thread reads four nodes x four columns per tile (16-byte loads along the rows), the quantised tile
-// turns in LDS, and every column leaves as 128 contiguous bytes.  The row sums of a slab go to
+// a thread reads four nodes (two pairs of neighbours) x four columns per tile (16-byte loads along the
+// rows), the quantised tile turns in LDS, and every column leaves as 128 contiguous bytes.  The row sums of a slab go to
 // `partial` [slab][node][3]; k_finish_node_constants adds the slabs in order.
 constexpr int kCtNodes = 64;
 constexpr int kCtCols = 64;
@@ -68,83 +68,106 @@ __global__ __launch_bounds__(256) void k_center_transpose_q16(const float *__res
                                                               const float *__restrict__ qstep, int k, int dim,
                                                               int kpad, int cols_per_slab, int16_t *__restrict__ Wt,
                                                               double *__restrict__ partial) {
-  __shared__ int16_t tile[kCtNodes][kCtCols + 2];
+  // the tile turned: [column][pair of neighbouring nodes] as 32-bit words (two int16), so that a thread
+  // writes one word per two entries and the columns leave through 16-byte reads; 33 words per row keep
+  // the column-wise writes of a wavefront on different banks
+  __shared__ uint32_t tile[kCtCols][kCtNodes / 2 + 1];
   const int tid = threadIdx.x;
   const int q4 = tid & 15;                      // column quad within the tile
-  const int r0 = tid >> 4;                      // first of this thread's four rows (r0 + 16 j)
+  const int p0 = tid >> 4;                      // first of this thread's two node pairs (p0 + 16 j): rows 2 p, 2 p + 1
   const int i0 = blockIdx.x * kCtNodes;
   const int slab = blockIdx.y;
   const int c_begin = slab * cols_per_slab;
   const int c_end = min(dim, c_begin + cols_per_slab);
   const bool vec = (dim & 3) == 0 && (reinterpret_cast<uintptr_t>(W) & 15) == 0;
-  double s2[4] = {0, 0, 0, 0}, sm[4] = {0, 0, 0, 0}, sw[4] = {0, 0, 0, 0};
+  double s2[4] = {0, 0, 0, 0}, sm[4] = {0, 0, 0, 0}, sw[4] = {0, 0, 0, 0};      // rows 2 (p0 + 16 j) + h at [2 j + h]
+  // this thread's four rows x four columns of a tile; entries past the slab or the map come out as mu (w' = 0).
+  // The next tile is loaded while the current one goes through LDS.
+  auto load_tile = [&](int c0, float (&x)[4][4]) {
+    const int c = c0 + 4 * q4;
+#pragma unroll
+    for (int jh = 0; jh < 4; ++jh) {
+      const int i = i0 + 2 * (p0 + 16 * (jh >> 1)) + (jh & 1);
+      if (i < k && vec && c + 3 < c_end) {
+        const float4 v = *reinterpret_cast<const float4 *>(W + (int64_t)i * dim + c);
+        x[jh][0] = v.x; x[jh][1] = v.y; x[jh][2] = v.z; x[jh][3] = v.w;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const bool on = i < k && c + e < c_end;
+          x[jh][e] = on ? W[(int64_t)i * dim + c + e] : (c + e < c_end ? mu[c + e] : 0.f);
+        }
+      }
+    }
+  };
+  float xn[4][4];
+  load_tile(c_begin, xn);
   for (int c0 = c_begin; c0 < c_end; c0 += kCtCols) {
     const int c = c0 + 4 * q4;
-    float m[4], st[4];
+    float xc[4][4];
+#pragma unroll
+    for (int jh = 0; jh < 4; ++jh)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) xc[jh][e] = xn[jh][e];
+    if (c0 + kCtCols < c_end) load_tile(c0 + kCtCols, xn);
+    float m[4], inv[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const bool on = c + e < c_end;
       m[e] = on ? mu[c + e] : 0.f;
-      st[e] = on ? qstep[c + e] : 1.f;
+      inv[e] = on ? qstep[c + e] : 1.f;
     }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int r = r0 + 16 * j;
-      const int i = i0 + r;
-      float x[4] = {0.f, 0.f, 0.f, 0.f};
-      if (i < k) {
-        const float *row = W + (int64_t)i * dim;
-        if (vec && c + 3 < c_end) {
-          const float4 v = *reinterpret_cast<const float4 *>(row + c);
-          x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
-        } else {
+    for (int j = 0; j < 2; ++j) {
+      const int pr = p0 + 16 * j;
+      uint32_t word[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-          for (int e = 0; e < 4; ++e) x[e] = c + e < c_end ? row[c + e] : m[e];      // past the slab: w' = 0
+      for (int h = 0; h < 2; ++h) {
+        const int i = i0 + 2 * pr + h;
+        const float (&x)[4] = xc[2 * j + h];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float t = x[e] - m[e];
+          if (i < k && c + e < c_end) {
+            s2[2 * j + h] += (double)t * (double)t;
+            sm[2 * j + h] += (double)m[e] * (double)t;
+            sw[2 * j + h] += (double)x[e] * (double)x[e];
+          }
+          float q = rintf(t / inv[e]);
+          q = fminf(fmaxf(q, -32767.f), 32767.f);
+          word[e] |= ((uint32_t)(uint16_t)(int16_t)q) << (16 * h);
         }
-      } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) x[e] = m[e];                                       // past the map: w' = 0
       }
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float t = x[e] - m[e];
-        if (i < k && c + e < c_end) {
-          s2[j] += (double)t * (double)t;
-          sm[j] += (double)m[e] * (double)t;
-          sw[j] += (double)x[e] * (double)x[e];
-        }
-        float q = rintf(t / st[e]);
-        q = fminf(fmaxf(q, -32767.f), 32767.f);
-        tile[r][4 * q4 + e] = (int16_t)q;
-      }
+      for (int e = 0; e < 4; ++e) tile[4 * q4 + e][pr] = word[e];
     }
     __syncthreads();
     {   // column tid / 4 of the tile, nodes 16 (tid % 4) .. + 15: 32 contiguous bytes of one row of Wt
       const int col = tid >> 2, g = tid & 3;
       if (c0 + col < c_end && i0 + 16 * g < kpad) {
-        __attribute__((aligned(16))) int16_t out[16];
+        uint32_t out[8];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) out[e] = tile[16 * g + e][col];
-        int16_t *dst = Wt + (int64_t)(c0 + col) * kpad + i0 + 16 * g;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) *reinterpret_cast<uint4 *>(dst + 8 * h) = *reinterpret_cast<const uint4 *>(out + 8 * h);
+        for (int e = 0; e < 8; ++e) out[e] = tile[col][8 * g + e];
+        uint4 *dst = reinterpret_cast<uint4 *>(Wt + (int64_t)(c0 + col) * kpad + i0 + 16 * g);
+        dst[0] = make_uint4(out[0], out[1], out[2], out[3]);
+        dst[1] = make_uint4(out[4], out[5], out[6], out[7]);
       }
     }
     __syncthreads();
   }
-  // the four rows' sums over this slab: the 16 threads of a row sit in consecutive lanes
+  // the four rows' sums over this slab: the 16 threads of a row pair sit in consecutive lanes
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int jh = 0; jh < 4; ++jh) {
 #pragma unroll
     for (int o = 1; o < 16; o <<= 1) {
-      s2[j] += __shfl_xor(s2[j], o, 64);
-      sm[j] += __shfl_xor(sm[j], o, 64);
-      sw[j] += __shfl_xor(sw[j], o, 64);
+      s2[jh] += __shfl_xor(s2[jh], o, 64);
+      sm[jh] += __shfl_xor(sm[jh], o, 64);
+      sw[jh] += __shfl_xor(sw[jh], o, 64);
     }
-    const int i = i0 + r0 + 16 * j;
+    const int i = i0 + 2 * (p0 + 16 * (jh >> 1)) + (jh & 1);
     if (q4 == 0 && i < k) {
       double *dst = partial + ((int64_t)slab * k + i) * 3;
-      dst[0] = s2[j]; dst[1] = sm[j]; dst[2] = sw[j];
+      dst[0] = s2[jh]; dst[1] = sm[jh]; dst[2] = sw[jh];
     }
   }
 }
@@ -446,7 +469,9 @@ hipError_t launch_center_transpose_codebook(som_ctx *c, const float *W) {
   hipError_t e = launch_fill_zero_u32(c->stream, c->wmax_bits, 2);
   if (e != hipSuccess) return e;
   const int tiles = c->kpad / kCtNodes;                       // kpad is a multiple of 512
-  int slabs = (2 * c->n_cu + tiles - 1) / tiles;              // enough workgroups for two per CU
+  // enough workgroups for twelve per CU: a workgroup walks its slab one tile after the other and waits for
+  // every tile's loads, so the memory system is kept busy by their number (two per CU: 2.3 TB/s)
+  int slabs = (12 * c->n_cu + tiles - 1) / tiles;
   const int max_slabs = (c->dim + kCtCols - 1) / kCtCols;
   if (slabs > max_slabs) slabs = max_slabs;
   if (slabs > kCtMaxSlabs) slabs = kCtMaxSlabs;

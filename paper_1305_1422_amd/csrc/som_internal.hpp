@@ -287,7 +287,7 @@ hipError_t launch_scan_exclusive_i32(som_ctx *c, const int32_t *in, int32_t *out
 hipError_t launch_mask_duplicate_rows(som_ctx *c, const float *W);   // wn32[i] = +inf for rows equal to a lower-indexed row
 
 // bmu_csr.hip
-constexpr int kCtMaxSlabs = 16;            // column slabs of the fused centring / transpose pass
+constexpr int kCtMaxSlabs = 64;            // column slabs of the fused centring / transpose pass
 hipError_t launch_center_transpose_codebook(som_ctx *c, const float *W);   // mu, qstep -> Wt, wn32, wn64, wmax_bits
 void csr_slice_geometry(int k, int *acc, int *sweeps, int *kpad);
 hipError_t launch_scale_values(som_ctx *c, const int32_t *indices, const float *values, int64_t nnz);   // -> vq
