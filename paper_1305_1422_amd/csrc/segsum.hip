@@ -328,6 +328,49 @@ __global__ __launch_bounds__(256) void k_accumulate_csr(const int64_t *__restric
   }
 }
 
+// Long rows of a context that holds a split into frequent columns and the rest (csr_hot.hip; the tables
+// describe the registered set, but any table gives correct sums): the instances are sorted by BMU and cut
+// into chunks as above, the nonzeros of the kHot frequent columns - about half of all, and the ones whose
+// atomics collide - are added up in LDS per chunk and leave as at most kHot atomics, the others go straight
+// into S.  The rows of the chosen nodes are cleared beforehand.
+__global__ __launch_bounds__(256) void k_accumulate_csr_hot(const int64_t *__restrict__ indptr,
+                                                            const int32_t *__restrict__ indices,
+                                                            const float *__restrict__ values, int dim,
+                                                            const int32_t *__restrict__ perm,
+                                                            const int32_t *__restrict__ seg_off,
+                                                            const int32_t *__restrict__ chunk_off,
+                                                            const int32_t *__restrict__ chunk_node, int k,
+                                                            const int32_t *__restrict__ rank,
+                                                            const int32_t *__restrict__ hot_cols,
+                                                            float *__restrict__ S) {
+  __shared__ float s_hot[kHot];
+  const int chunk = blockIdx.x;
+  if (chunk >= chunk_off[k]) return;          // uniform over the workgroup
+  const int b = chunk_node[chunk];
+  const int first_chunk = chunk_off[b];
+  const int lo = seg_off[b] + (chunk - first_chunk) * kCsrChunkRows;
+  const int hi = min(lo + kCsrChunkRows, seg_off[b + 1]);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float *dst = S + (int64_t)b * dim;
+  for (int h = threadIdx.x; h < kHot; h += 256) s_hot[h] = 0.f;
+  __syncthreads();
+  for (int r = lo + wave; r < hi; r += 4) {
+    const int64_t j = perm[r];
+    for (int64_t p = indptr[j] + lane; p < indptr[j + 1]; p += 64) {
+      int c = indices[p];
+      c = c < 0 ? 0 : (c >= dim ? dim - 1 : c);
+      const int h = rank[c];
+      if (h >= 0) atomicAdd(&s_hot[h], values[p]);
+      else unsafeAtomicAdd(dst + c, values[p]);
+    }
+  }
+  __syncthreads();
+  for (int h = threadIdx.x; h < kHot; h += 256) {
+    const float v = s_hot[h];
+    if (v != 0.f) unsafeAtomicAdd(dst + hot_cols[h], v);
+  }
+}
+
 // C_b for the sparse path.  Trained maps send most instances to few nodes, so the lanes of a
 // wavefront that hold the same node are merged into one atomic add.
 __global__ __launch_bounds__(256) void k_count_bmus(const int32_t *__restrict__ bmus, int64_t n, int k,
@@ -469,6 +512,28 @@ hipError_t launch_accumulate_csr(som_ctx *c, const int64_t *indptr, const int32_
     hipLaunchKernelGGL(k_accumulate_csr, dim3((unsigned)max_chunks), dim3(256), (size_t)c->dim * sizeof(float),
                        c->stream, indptr, indices, values, c->dim, c->sort_val[0], c->seg_off, c->chunk_off,
                        c->chunk_node, c->k, c->S);
+    return hipGetLastError();
+  }
+  // (worth the sort only with several instances per node: with 12,347 instances on 68,880 nodes it cost 0.09 ms
+  // more than the plain scatter, with 100,000 on 2,500 it saves 0.14)
+  if (c->hot_valid && c->hot_on && n >= 8 * (int64_t)c->k) {
+    hipError_t e = launch_sort_by_bmu(c, bmus, n);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_scan_exclusive, dim3(1), dim3(1024), 0, c->stream, c->counts, c->chunk_off, c->k,
+                       kCsrChunkRows);
+    hipLaunchKernelGGL(k_fill_chunk_nodes, dim3(c->n_cu * 2), dim3(256), 0, c->stream, c->chunk_off, c->k,
+                       c->chunk_node);
+    if (c->GxT) {
+      hipLaunchKernelGGL(k_zero_rows_if, dim3(c->k, ysplit), dim3(256), 0, c->stream, c->counts, 0, c->dim, c->S);
+    } else {
+      e = launch_fill_zero_u32(c->stream, c->S, (int64_t)c->k * c->dim);
+      if (e != hipSuccess) return e;
+    }
+    int64_t max_chunks = n / kCsrChunkRows + (n < c->k ? n : c->k);
+    if (max_chunks < 1) max_chunks = 1;
+    hipLaunchKernelGGL(k_accumulate_csr_hot, dim3((unsigned)max_chunks), dim3(256), 0, c->stream, indptr, indices,
+                       values, c->dim, c->sort_val[0], c->seg_off, c->chunk_off, c->chunk_node, c->k, c->hot_rank,
+                       c->hot_cols, c->S);
     return hipGetLastError();
   }
   hipError_t e = launch_fill_zero_u32(c->stream, c->counts, c->k);
