@@ -451,3 +451,25 @@ def test_dense_planes_are_declined_or_dropped(oracle):
     assert np.array_equal(b1, b2)
     P.check_bmus_csr(oracle, csr, dim, W, b2)
     som.close()
+
+
+def test_long_rows_with_hot_column_tables_whole_epochs(oracle):
+    """Rows longer than an LDS tile of columns (17,000 > 16,384) on a context that holds the hot-column tables, with
+    more than eight instances per node: the per-node sums go through the BMU-sorted chunks with the frequent
+    columns in LDS.  Whole epochs against the oracle, registered and - same tables, other rows - unregistered data;
+    one node takes half of the instances (many chunks), most nodes none."""
+    from paper_1305_1422_amd import Som, capi
+    n, dim, rows, cols = 1500, 17000, 5, 6
+    csr = sparse_zipf_csr(n, dim, 91, mean_len=50.0, max_len=150)
+    csr_d = P.csr_to_dev(csr)
+    W0 = (np.random.default_rng(92).random((rows * cols, dim)) * 0.05).astype(np.float32)
+    W0[7] += 0.02                                              # a node close to everything at the start
+    som = Som(rows, cols, dim, "planar", "square", codebook=torch.from_numpy(W0))
+    capi.som_set_data_csr(som.ctx, *csr_d)
+    for radius in (2.0, 1.0, 0.6):
+        P.epoch_parity_csr(oracle, som, csr, csr_d, dim, radius, P.MAP["planar"], P.GRID["square"])
+    assert capi.som_sparse_hot_block_active(som.ctx)
+    other = sparse_zipf_csr(900, dim, 93, mean_len=30.0, max_len=90)
+    other_d = P.csr_to_dev(other)
+    P.epoch_parity_csr(oracle, som, other, other_d, dim, 1.0, P.MAP["planar"], P.GRID["square"])
+    som.close()
