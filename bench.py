@@ -37,8 +37,8 @@ MEASURED_TRAFFIC_BYTES = {(2, "two_level"): 1.389e9 + 0.034e9, (3, "two_level"):
                           (2, "split_f16"): 3.841e9 + 0.036e9, (2, "fp32"): 8.49e9 + 0.025e9,
                           (3, "split_f16"): 14.283e9 + 0.025e9, (5, "split_f16"): 13.917e9 + 0.072e9,
                           # sparse: all kernels of the filter stage (code-book pass, hot-column block, sweep)
-                          (4, "sparse"): 16.409e9 + 1.452e9, (6, "sparse"): 0.415e9 + 0.058e9,
-                          (7, "sparse"): 87.522e9 + 6.476e9}
+                          (4, "sparse"): 16.395e9 + 1.453e9, (6, "sparse"): 0.415e9 + 0.058e9,
+                          (7, "sparse"): 87.540e9 + 6.474e9}
 PEAK_FP32_VALU_TFLOPS = 157.3
 
 
