@@ -1,5 +1,6 @@
 """The rounding bounds that the exact BMU stage relies on, checked where they are assumed: every score of
-each of the three filters (split-fp16 MFMA, fp32 MFMA in both of its kernels, the 16-bit sparse sweep) is
+each of the filter passes (split-fp16 MFMA, fp32 MFMA in both of its kernels, the one-product coarse pass of the
+two-level search, the 16-bit sparse sweep) is
 dumped and compared with its exact value in float64; no error may exceed half the margin the exact stage
 applies to that instance (the library reports the margin it uses: same device function, same inputs), and for
 the two dense filters the documented closed form of the bound is evaluated here from the inputs alone as well.
