@@ -261,6 +261,20 @@ __global__ __launch_bounds__(256) void k_refine_dense(const float *__restrict__ 
   }
 }
 
+// Next entry of a work list for this wavefront.  The lists differ in length by two orders of magnitude (2 to
+// 256 nodes), and a fixed assignment of entries to wavefronts left most of the chip idle behind the wavefronts
+// that had drawn the long ones (5 resident wavefronts per CU on average, out of 32); so entries are handed out
+// from counters that the search zeroes with the list lengths.  One counter serialises: an atomic on one address
+// takes about 10 ns whoever issues it, more than the comparison of a list of 128-feature rows.  Hence eight
+// counters in different memory channels: workgroup b draws from counter b mod 8, which hands out the entries
+// e = b mod 8 (mod 8).
+__device__ inline int next_entry(int32_t *list_counts, int lane) {
+  const int slice = blockIdx.x & (kListTickets - 1);
+  int t = 0;
+  if (lane == 0) t = atomicAdd(list_counts + kListCounts + slice * kListTicketStride, 1);
+  return __builtin_amdgcn_readfirstlane(t) * kListTickets + slice;
+}
+
 // Exact comparison of the collected lists: one wavefront per listed instance.  A list that
 // overflowed its capacity sends the instance on to the full rescan.
 __global__ __launch_bounds__(256) void k_refine_lists_dense(const float *__restrict__ X, const float *__restrict__ W,
@@ -271,10 +285,8 @@ __global__ __launch_bounds__(256) void k_refine_lists_dense(const float *__restr
                                                             int32_t *__restrict__ list_counts,
                                                             int32_t *__restrict__ bmus) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int wave = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-  const int nwaves = gridDim.x * (blockDim.x / kWave);
   const int count = list_counts[1];
-  for (int e = wave; e < count; e += nwaves) {
+  for (int e = next_entry(list_counts, lane); e < count; e = next_entry(list_counts, lane)) {
     const int64_t j = collect_rows[e];
     const int cn = collect_cnt[e];
     if (cn > kListCap || cn == 0) {
@@ -378,10 +390,8 @@ __global__ __launch_bounds__(256) void k_refine_lists_csr(const int64_t *__restr
                                                           int32_t *__restrict__ list_counts,
                                                           int32_t *__restrict__ bmus) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int wave = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-  const int nwaves = gridDim.x * (blockDim.x / kWave);
   const int count = list_counts[1];
-  for (int e = wave; e < count; e += nwaves) {
+  for (int e = next_entry(list_counts, lane); e < count; e = next_entry(list_counts, lane)) {
     const int64_t j = collect_rows[e];
     const int64_t s = indptr[j];
     const int len = (int)(indptr[j + 1] - s);

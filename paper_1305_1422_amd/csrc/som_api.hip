@@ -291,7 +291,7 @@ static int prepare_dense(som_ctx *c, const float *X, int64_t n, const float *W, 
   if (split)
     SOM_LAUNCH(c, launch_split_rows_f16(c, c->Wc, c->k, c->wmax_bits + 1, nullptr, c->Wh, c->wscale, 0,
                                         coarse ? c->Wh1 : nullptr));
-  SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, 3));
+  SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, kListWords));
   return SOM_OK;
 }
 
@@ -359,7 +359,7 @@ static int prepare_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices
   if (c->data_kind == 1) { c->d_norms_valid = 0; c->d_split_valid = 0; }
   SOM_LAUNCH(c, launch_codebook_means_and_steps(c, W));
   SOM_LAUNCH(c, launch_vec_sqnorm(c, c->mu, c->dim, c->mu_norm2));
-  SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, kListCounts));
+  SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, kListWords));
   return SOM_OK;
 }
 
@@ -398,7 +398,7 @@ static int bmu_search_csr_planes(som_ctx *c, const int64_t *indptr, const int32_
     if (c->nb_function == SOM_NEIGHBORHOOD_BUBBLE) SOM_LAUNCH(c, launch_mask_duplicate_rows(c, W));
     SOM_LAUNCH(c, launch_split_rows_f16(c, c->Wc, c->k, c->wmax_bits + 1, nullptr, c->Wh, c->wscale, 0,
                                         coarse ? c->Wh1 : nullptr));
-    SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, kListCounts));
+    SOM_LAUNCH(c, launch_fill_zero_u32(c->stream, c->list_counts, kListWords));
   }
   {
     StageTimer t(c, 1);
@@ -662,7 +662,7 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
   bool ok = dev_alloc(&c->wn32, (K + 127) / 128 * 128) && dev_alloc(&c->wn64, K) && dev_alloc(&c->wmax_bits, 2) &&
             dev_alloc(&c->counts, K + 1) && dev_alloc(&c->seg_off, K + 1) && dev_alloc(&c->chunk_off, K + 1) &&
             dev_alloc(&c->massD, K) && dev_alloc(&c->dist_partial, kDistBlocks) && dev_alloc(&c->cntT, 2 * K) && dev_alloc(&c->gx, 2 * (size_t)cols + 1) &&
-            dev_alloc(&c->gy, (size_t)rows) && dev_alloc(&c->params, 1) && dev_alloc(&c->list_counts, kListCounts) &&
+            dev_alloc(&c->gy, (size_t)rows) && dev_alloc(&c->params, 1) && dev_alloc(&c->list_counts, kListWords) &&
             dev_alloc(&c->mu, (size_t)dim) && dev_alloc(&c->mu_partial, (size_t)64 * dim) &&
             dev_alloc(&c->zero16, 16) && dev_alloc(&c->mu_norm2, 1) && dev_alloc(&c->wscale, 1) &&
             dev_alloc(&c->S, K * dim) && dev_alloc(&c->T, images * K * dim) &&
@@ -677,7 +677,7 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
     som_destroy(c);
     return fail(nullptr, SOM_ERR_ALLOC, "cannot allocate map scratch (%d nodes x %d)", c->k, dim);
   }
-  hipError_t e = launch_fill_zero_u32(c->stream, c->list_counts, kListCounts);
+  hipError_t e = launch_fill_zero_u32(c->stream, c->list_counts, kListWords);
   if (e == hipSuccess) e = launch_fill_zero_u32(c->stream, c->zero16, 16);
   if (e == hipSuccess && K % 128 != 0) {       // the tail of the node constants past k stays +inf for good
     float inf[128];

@@ -127,7 +127,8 @@ struct som_ctx {
   int32_t *collect_list;  // [n][kListCap] those nodes (dense path only, lazily allocated)
   int32_t *rescan_list;   // [n] instances that need an exact scan of all nodes
   int32_t *list_counts;   // [0..2] lengths of refine_list, collect_rows, rescan_list; [3] flag of som_validate_csr;
-                          // [4..11] lengths of unit_work per slice
+                          // [4..11] lengths of unit_work per slice; behind these kListCounts words the
+                          // list comparison's entry counters, kListTicketStride words apart
   int64_t *unit_work;     // [8][unit_cap] sparse search: (collect slot, node range) units to sweep again
   int64_t unit_cap;
   int32_t *sort_key[2];   // [n] each
@@ -243,7 +244,10 @@ struct UnitWork {
   int32_t *counts;        // [8]
   int32_t *list;          // [slots][kListCap] candidate lists, seeded with the nodes of the complete ranges
 };
-constexpr int kListCounts = 12;    // words in som_ctx::list_counts
+constexpr int kListCounts = 16;    // words of lengths and flags at the head of som_ctx::list_counts
+constexpr int kListTickets = 8;    // entry counters of the list comparison behind them ...
+constexpr int kListTicketStride = 1088;      // ... 4 KB + 256 B apart: another memory channel each
+constexpr int kListWords = kListCounts + kListTickets * kListTicketStride;
 constexpr int kUnitCounts = 4;     // first of the eight work-list lengths in it
 enum { kCertifyFp32 = 0, kCertifySplit = 1, kCertifyCsr = 2, kCertifyCoarse = 3 };      // whose rounding bound the margin uses
 hipError_t launch_certify(som_ctx *c, int64_t n, int groups, int mode, const int64_t *indptr, int32_t *bmus,
