@@ -108,6 +108,10 @@ int som_train_epoch_dense(som_ctx *ctx, const float *data, int64_t n, float *cod
  * nnz < 0 or nnz >= 2^31 -> SOM_ERR_INVALID_ARG.
  * The per-node sums of this call are accumulated with fp32 atomic adds, so the last bits
  * of the new code book may vary from run to run; the BMUs do not.
+ * Scratch of the sparse search, allocated with the first sparse call on the context: a
+ * transposed code book of 2 bytes per weight, and, if it takes no more than 16 GiB, a
+ * transposed fp32 copy (4 bytes per weight) for the instances that have to be compared with
+ * every node exactly.
  */
 int som_train_epoch_csr(som_ctx *ctx, const int64_t *indptr, const int32_t *indices,
                         const float *values, int64_t n, int64_t nnz, float *codebook,

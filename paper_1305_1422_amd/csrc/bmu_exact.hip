@@ -387,7 +387,7 @@ __global__ __launch_bounds__(256) void k_refine_lists_csr(const int64_t *__restr
                                                           const int32_t *__restrict__ collect_cnt,
                                                           const int32_t *__restrict__ collect_list,
                                                           int32_t *__restrict__ rescan_list,
-                                                          int32_t *__restrict__ list_counts,
+                                                          int32_t *__restrict__ list_counts, int scan_above,
                                                           int32_t *__restrict__ bmus) {
   const int lane = threadIdx.x & (kWave - 1);
   const int count = list_counts[1];
@@ -395,7 +395,9 @@ __global__ __launch_bounds__(256) void k_refine_lists_csr(const int64_t *__restr
     const int64_t j = collect_rows[e];
     const int64_t s = indptr[j];
     const int len = (int)(indptr[j + 1] - s);
-    if (collect_cnt[e] > kListCap || collect_cnt[e] < 1) {      // overflowed (or empty) list: exact scan of all nodes
+    // overflowed (or empty) list: exact scan of all nodes; so is a list longer than scan_above, for which that scan
+    // is the cheaper of the two
+    if (collect_cnt[e] > min(kListCap, scan_above) || collect_cnt[e] < 1) {
       if (lane == 0) rescan_list[atomicAdd(&list_counts[2], 1)] = (int32_t)j;
       continue;
     }
@@ -410,6 +412,20 @@ __global__ __launch_bounds__(256) void k_refine_lists_csr(const int64_t *__restr
       if (d2 < best || (d2 == best && i < arg)) { best = d2; arg = i; }
     }
     if (lane == 0) bmus[j] = arg == 0x7fffffff ? 0 : arg;
+  }
+}
+
+// Exact scan of all nodes for one sparse row from the row-major code book: wavefront w takes the nodes
+// w, w + 4, ...; (best, arg) of this wavefront, ties to the lowest index.
+__device__ __forceinline__ void rescan_row_major(const int32_t *__restrict__ idx, const float *__restrict__ val,
+                                                 int len, const float *__restrict__ W,
+                                                 const double *__restrict__ wn64, double xn, int dim, int k,
+                                                 int lane, int wave, double &best, int &arg) {
+  best = INFINITY;
+  arg = 0x7fffffff;
+  for (int i = wave; i < k; i += 4) {             // ascending within a wave: strict < keeps the lowest index
+    const double d2 = sqdist_csr_wave(idx, val, len, W + (int64_t)i * dim, wn64[i], xn, dim, lane);
+    if (d2 < best) { best = d2; arg = i; }
   }
 }
 
@@ -430,15 +446,143 @@ __global__ __launch_bounds__(256) void k_rescan_csr(const int64_t *__restrict__ 
     const int64_t s = indptr[j];
     const int len = (int)(indptr[j + 1] - s);
     const double xn = csr_row_sqnorm_wave(values + s, len, lane);
-    double best = INFINITY;
-    int arg = 0x7fffffff;
-    for (int i = wave; i < k; i += 4) {
-      const double d2 = sqdist_csr_wave(indices + s, values + s, len, W + (int64_t)i * dim, wn64[i], xn, dim, lane);
-      if (d2 < best) { best = d2; arg = i; }
-    }
+    double best;
+    int arg;
+    rescan_row_major(indices + s, values + s, len, W, wn64, xn, dim, k, lane, wave, best, arg);
     if (lane == 0) { s_best[wave] = best; s_arg[wave] = arg; }
     __syncthreads();
     if (threadIdx.x == 0) {
+      for (int w = 1; w < 4; ++w)
+        if (s_best[w] < best || (s_best[w] == best && s_arg[w] < arg)) { best = s_best[w]; arg = s_arg[w]; }
+      bmus[j] = arg == 0x7fffffff ? 0 : arg;
+    }
+    __syncthreads();
+  }
+}
+
+// The same scan from a transposed fp32 copy of the code book, Wt[c][i] with row stride kt.  A scan from the
+// row-major code book reads one 4-byte weight per node and nonzero, each from a row of its own: a memory
+// transaction per weight.  From the transposed copy the weights of one column and 64 consecutive nodes are
+// one 256-byte read, and a thread adds up one node's terms over the row's nonzeros:
+//     d2_i = |w_i|^2 + sum_nz ((v - w_ic)^2 - w_ic^2)
+// (the regrouped sum of sqdist_csr_regrouped_wave, its terms added in the order of the row instead of
+// across a wavefront).  A node for which that sum is all rounding noise needs the plain sum over every
+// coordinate, which has to walk the node's row of W: if any node of the scan is that close to the instance,
+// the whole scan is done again from the row-major code book, as k_rescan_csr does it (an instance that
+// coincides with a weight vector: rare).
+// The copy is written by k_transpose_for_rescan, and only when the list of instances to scan is not empty.
+constexpr int kRescanChunk = 512;        // nonzeros staged in LDS at a time
+constexpr int kRescanNodes = 2;          // nodes per thread and round
+
+__global__ __launch_bounds__(256) void k_transpose_for_rescan(const float *__restrict__ W, int k, int dim, int64_t kt,
+                                                              const int32_t *__restrict__ list_counts,
+                                                              float *__restrict__ Wt) {
+  if (list_counts[2] == 0) return;
+  __shared__ float tile[64][65];
+  const int tc = (dim + 63) / 64, ti = (k + 63) / 64;
+  const int x = threadIdx.x & 63, y = threadIdx.x >> 6;
+  for (int64_t t = blockIdx.x; t < (int64_t)tc * ti; t += gridDim.x) {
+    const int i0 = (int)(t / tc) * 64, c0 = (int)(t % tc) * 64;
+    for (int r = y; r < 64; r += 4) {
+      const int i = i0 + r, c = c0 + x;
+      tile[r][x] = (i < k && c < dim) ? W[(int64_t)i * dim + c] : 0.f;
+    }
+    __syncthreads();
+    for (int r = y; r < 64; r += 4) {
+      const int c = c0 + r, i = i0 + x;
+      if (c < dim && i < kt) Wt[(int64_t)c * kt + i] = tile[x][r];
+    }
+    __syncthreads();
+  }
+}
+
+__global__ __launch_bounds__(256) void k_rescan_csr_t(const int64_t *__restrict__ indptr,
+                                                      const int32_t *__restrict__ indices,
+                                                      const float *__restrict__ values,
+                                                      const float *__restrict__ W, const float *__restrict__ Wt,
+                                                      int64_t kt, const double *__restrict__ wn64, int dim, int k,
+                                                      const int32_t *__restrict__ rescan_list,
+                                                      const int32_t *__restrict__ list_counts,
+                                                      int32_t *__restrict__ bmus) {
+  __shared__ int32_t s_col[kRescanChunk];
+  __shared__ float s_val[kRescanChunk];
+  __shared__ double s_best[4];
+  __shared__ int s_arg[4];
+  const int tid = threadIdx.x;
+  const int lane = tid & (kWave - 1);
+  const int wave = tid / kWave;
+  const int count = list_counts[2];
+  for (int e = blockIdx.x; e < count; e += gridDim.x) {
+    const int64_t j = rescan_list[e];
+    const int64_t s = indptr[j];
+    const int len = (int)(indptr[j + 1] - s);
+    const double xn = csr_row_sqnorm_wave(values + s, len, lane);
+    const double noise_scale = ((double)dim + (double)len + 2.0) * 1.862645149230957e-09;      // as in sqdist_csr_wave
+    const bool fits = len <= kRescanChunk;
+    if (fits) {
+      for (int p = tid; p < len; p += 256) {
+        s_col[p] = min(max(indices[s + p], 0), dim - 1);
+        s_val[p] = values[s + p];
+      }
+      __syncthreads();
+    }
+    double best = INFINITY;
+    int arg = 0x7fffffff;
+    bool in_noise = false;
+    for (int i0 = 0; i0 < k; i0 += 256 * kRescanNodes) {
+      double acc[kRescanNodes];
+      int node[kRescanNodes];
+#pragma unroll
+      for (int r = 0; r < kRescanNodes; ++r) {
+        acc[r] = 0.0;
+        node[r] = min(i0 + r * 256 + tid, k - 1);       // a thread beyond the last node reads node k - 1 and drops the result
+      }
+      for (int p0 = 0; p0 < len; p0 += kRescanChunk) {
+        const int cn = min(kRescanChunk, len - p0);
+        if (!fits) {
+          __syncthreads();
+          for (int p = tid; p < cn; p += 256) {
+            s_col[p] = min(max(indices[s + p0 + p], 0), dim - 1);
+            s_val[p] = values[s + p0 + p];
+          }
+          __syncthreads();
+        }
+#pragma unroll 4
+        for (int p = 0; p < cn; ++p) {
+          const float *row = Wt + (int64_t)s_col[p] * kt;
+          const double v = (double)s_val[p];
+#pragma unroll
+          for (int r = 0; r < kRescanNodes; ++r) {
+            const double wc = (double)row[node[r]];
+            const double d = v - wc;
+            acc[r] += d * d - wc * wc;
+          }
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < kRescanNodes; ++r) {
+        const int i = i0 + r * 256 + tid;
+        if (i < k) {                                    // ascending per thread: strict < keeps the lowest index
+          const double wn = wn64[i];
+          const double d2 = wn + acc[r];
+          if (d2 < noise_scale * (wn + xn)) in_noise = true;
+          if (d2 < best) { best = d2; arg = i; }
+        }
+      }
+    }
+    if (__syncthreads_or(in_noise)) {
+      rescan_row_major(indices + s, values + s, len, W, wn64, xn, dim, k, lane, wave, best, arg);
+    } else {
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) {
+        const double ob = __shfl_xor(best, o, kWave);
+        const int oa = __shfl_xor(arg, o, kWave);
+        if (ob < best || (ob == best && oa < arg)) { best = ob; arg = oa; }
+      }
+    }
+    if (lane == 0) { s_best[wave] = best; s_arg[wave] = arg; }
+    __syncthreads();
+    if (tid == 0) {
       for (int w = 1; w < 4; ++w)
         if (s_best[w] < best || (s_best[w] == best && s_arg[w] < arg)) { best = s_best[w]; arg = s_arg[w]; }
       bmus[j] = arg == 0x7fffffff ? 0 : arg;
@@ -578,9 +722,13 @@ hipError_t launch_refine_csr(som_ctx *c, const int64_t *indptr, const int32_t *i
 
 hipError_t launch_refine_lists_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
                                    const float *W, int32_t *bmus) {
+  // A listed node costs a memory transaction per nonzero (its weights lie in a row of their own); the scan of all
+  // nodes from the transposed copy reads the same weights 16 to a transaction, and measured 24 times cheaper per
+  // (instance, node) pair on a 50 x 50 map: beyond k / 24 listed nodes the scan of everything wins.
+  const int scan_above = c->Wt32 ? (c->k / 24 > 16 ? c->k / 24 : 16) : kListCap;
   hipLaunchKernelGGL(k_refine_lists_csr, dim3(persistent_blocks(c, 1 << 20)), dim3(256), 0, c->stream, indptr,
                      indices, values, W, c->wn64, c->dim, c->k, c->collect_rows, c->collect_cnt, c->collect_list,
-                     c->rescan_list, c->list_counts, bmus);
+                     c->rescan_list, c->list_counts, scan_above, bmus);
   return hipGetLastError();
 }
 
@@ -667,6 +815,13 @@ hipError_t launch_bmu_distances(som_ctx *c, const float *X, const int64_t *indpt
 
 hipError_t launch_rescan_csr(som_ctx *c, const int64_t *indptr, const int32_t *indices, const float *values,
                              const float *W, int32_t *bmus) {
+  if (c->Wt32) {
+    hipLaunchKernelGGL(k_transpose_for_rescan, dim3(persistent_blocks(c, 1 << 20)), dim3(256), 0, c->stream, W, c->k,
+                       c->dim, c->kt32, c->list_counts, c->Wt32);
+    hipLaunchKernelGGL(k_rescan_csr_t, dim3(persistent_blocks(c, 1 << 20)), dim3(256), 0, c->stream, indptr, indices,
+                       values, W, c->Wt32, c->kt32, c->wn64, c->dim, c->k, c->rescan_list, c->list_counts, bmus);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(k_rescan_csr, dim3(persistent_blocks(c, 1 << 20)), dim3(256), 0, c->stream, indptr, indices,
                      values, W, c->wn64, c->dim, c->k, c->rescan_list, c->list_counts, bmus);
   return hipGetLastError();

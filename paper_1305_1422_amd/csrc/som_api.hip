@@ -232,6 +232,20 @@ static int ensure_transposed(som_ctx *c) {
   return SOM_OK;
 }
 
+// The transposed copy the full sparse rescan reads (bmu_exact.hip).  Optional: without it the rescan walks the
+// row-major code book.
+static void ensure_rescan_copy(som_ctx *c) {
+  if (c->Wt32 || c->Wt32_tried) return;
+  c->Wt32_tried = 1;
+  c->kt32 = ((int64_t)c->k + 63) / 64 * 64;
+  const size_t words = (size_t)c->dim * (size_t)c->kt32;
+  if (words * sizeof(float) > kRescanCopyMax) return;
+  if (!dev_alloc(&c->Wt32, words)) {
+    (void)hipGetLastError();      // not an error of the search: it goes on without the copy
+    c->Wt32 = nullptr;
+  }
+}
+
 static int check_epoch_scalars(som_ctx *c, float radius, float scale) {
   if (!(radius > 0.f) || !isfinite(radius)) return fail(c, SOM_ERR_INVALID_ARG, "radius must be finite and > 0");
   if (!(scale > 0.f) || !(scale <= 1.f)) return fail(c, SOM_ERR_INVALID_ARG, "scale must be in (0, 1]");
@@ -389,6 +403,7 @@ static int bmu_search_csr_planes(som_ctx *c, const int64_t *indptr, const int32_
                                  int64_t n, const float *W, int32_t *bmus) {
   int rc = ensure_candidates(c, n, true);
   if (rc) return rc;
+  ensure_rescan_copy(c);
   PlaneOperands swap(c);
   const bool coarse = two_level_ready(c, n);
   c->two_level_n = coarse ? n : 0;
@@ -421,6 +436,7 @@ static int bmu_search_csr(som_ctx *c, const int64_t *indptr, const int32_t *indi
   if (have_xn && c->csrd_valid && c->csrd_on) return bmu_search_csr_planes(c, indptr, indices, values, n, W, bmus);
   int rc = prepare_csr(c, indptr, indices, values, n, nnz, W, have_xn);
   if (rc) return rc;
+  ensure_rescan_copy(c);
   // registered rows whose frequent columns were split off: the sweeps walk the tail and start from the
   // matrix-core pass over the hot block; the exact kernels keep the caller's full rows
   const bool hot = have_xn && c->hot_on;
@@ -702,7 +718,7 @@ void som_destroy(som_ctx *c) {
   dev_free(c->wn32); dev_free(c->wn64); dev_free(c->wmax_bits); dev_free(c->counts); dev_free(c->seg_off);
   dev_free(c->chunk_off); dev_free(c->massD); dev_free(c->dist_partial); dev_free(c->row_hash); dev_free(c->dedup_keys);
   dev_free(c->dedup_lowest); dev_free(c->cntT); dev_free(c->gx); dev_free(c->gy);
-  dev_free(c->params); dev_free(c->list_counts); dev_free(c->unit_work); dev_free(c->vq); dev_free(c->S); dev_free(c->T); dev_free(c->Wt);
+  dev_free(c->params); dev_free(c->list_counts); dev_free(c->unit_work); dev_free(c->vq); dev_free(c->S); dev_free(c->T); dev_free(c->Wt); dev_free(c->Wt32);
   dev_free(c->col_range); dev_free(c->qstep); dev_free(c->qstep_max_bits); dev_free(c->ct_partial); dev_free(c->H2);
   dev_free(c->GxT); dev_free(c->GyT); dev_free(c->hit_x); dev_free(c->hit_n); dev_free(c->hit_rows);
   dev_free(c->mu); dev_free(c->mu_partial); dev_free(c->Wc); dev_free(c->zero16); dev_free(c->mu_norm2);

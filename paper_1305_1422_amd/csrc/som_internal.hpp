@@ -83,6 +83,9 @@ struct som_ctx {
   float *Wt;              // [dim][kpad] centred transposed code book of the sparse BMU search, int16 multiples
                           // of the column steps (lazily allocated)
   int kpad;               // 512 * csr_acc * csr_sweeps >= k
+  float *Wt32;            // [dim][kt32] transposed fp32 copy of the code book for the sparse full rescan (allocated with
+  int64_t kt32;           // the first sparse search if it fits kRescanCopyMax; written only in searches that rescan)
+  int Wt32_tried;
   int csr_acc, csr_sweeps;    // sparse BMU kernel: scores per lane and sweep, sweeps per node slice
   float *col_range;       // [2][64][dim] slab minima and maxima of the code-book columns (with Wt)
   float *qstep;           // [dim] quantisation step of every column of Wt (with Wt)
@@ -244,6 +247,7 @@ struct UnitWork {
   int32_t *counts;        // [8]
   int32_t *list;          // [slots][kListCap] candidate lists, seeded with the nodes of the complete ranges
 };
+constexpr size_t kRescanCopyMax = (size_t)16 << 30;      // bytes: no transposed copy for the full rescan beyond this
 constexpr int kListCounts = 16;    // words of lengths and flags at the head of som_ctx::list_counts
 constexpr int kListTickets = 8;    // entry counters of the list comparison behind them ...
 constexpr int kListTicketStride = 1088;      // ... 4 KB + 256 B apart: another memory channel each

@@ -473,3 +473,43 @@ def test_long_rows_with_hot_column_tables_whole_epochs(oracle):
     other_d = P.csr_to_dev(other)
     P.epoch_parity_csr(oracle, som, other, other_d, dim, 1.0, P.MAP["planar"], P.GRID["square"])
     som.close()
+
+
+def _csr_with_row_lengths(lengths, dim, seed):
+    rng = np.random.default_rng(seed)
+    indptr = np.zeros(len(lengths) + 1, dtype=np.int64)
+    np.cumsum(lengths, out=indptr[1:])
+    indices = np.concatenate([np.sort(rng.choice(dim, size=m, replace=False)) for m in lengths]).astype(np.int32)
+    values = (rng.random(indptr[-1]) + 0.1).astype(np.float32)
+    return indptr, indices, values
+
+
+@pytest.mark.parametrize("copies,rows,cols", [(400, 25, 30), (100, 40, 40), (700, 40, 40)])
+def test_full_scan_of_instances_with_hundreds_of_near_copies(oracle, copies, rows, cols):
+    """Hundreds of nodes that differ from one another by a few ulps: the candidate lists overflow (or, at 100
+    copies on 1,600 nodes, are long enough for the scan of everything to be the cheaper way), and the exact scan of
+    all nodes decides.  It reads a transposed copy of the code book; rows of 0, 1, 511, 512, 513 and 1,100
+    nonzeros cross its staging buffer of 512, the 750 and 1,600 nodes leave its last round of 512 nodes ragged,
+    and instance 6 coincides with three of the nodes (the others are its near-copies), which sends its scan back to
+    the row-major code book for the plain sum."""
+    from paper_1305_1422_amd import Som
+    dim = 3000
+    k = rows * cols
+    lengths = [0, 1, 40, 511, 512, 513, 1100] * 6 + [60] * 30
+    csr = _csr_with_row_lengths(lengths, dim, 7100 + copies)
+    X = densify(csr, dim)
+    rng = np.random.default_rng(7200 + copies)
+    base = X[6]                                                              # a row of 1,100 nonzeros
+    W = (rng.random((k, dim)) * 0.3 + 0.5).astype(np.float32)              # the other nodes: far from everything
+    near = rng.choice(k, size=copies, replace=False)
+    W[near] = base
+    W[near] += (rng.integers(-2, 3, size=(copies, dim)) * np.float32(2.0 ** -24)).astype(np.float32)
+    exact = np.sort(rng.choice(near, size=3, replace=False))
+    W[exact] = base                                                          # instance 6 is these three nodes
+    som = Som(rows, cols, dim, codebook=torch.from_numpy(W))
+    b = som.bmus(P.csr_to_dev(csr)).cpu().numpy()
+    refined, collected, rescanned = som.stats()
+    som.close()
+    assert rescanned >= 24, (refined, collected, rescanned)                 # the rows of 511 nonzeros and more, at least
+    P.check_bmus_csr(oracle, csr, dim, W, b)
+    assert b[6] == exact[0]                                                  # exact zero distance: no band, the lowest copy
