@@ -700,8 +700,30 @@ __global__ __launch_bounds__(256) void k_count_direct(const int32_t *__restrict_
   }
 }
 
+// Positions in the ascending list a[0..n) of the first entries that are >= v0, >= v1 and >= v2: every
+// wavefront counts the smaller entries 64 at a time (one load per 64 entries, all in flight together;
+// a bisection would be a chain of dependent loads per row).
+__device__ __forceinline__ void first_not_below3(const int32_t *__restrict__ a, int n, int lane, int v0, int v1, int v2,
+                                                 int &p0, int &p1, int &p2) {
+  p0 = p1 = p2 = 0;
+  for (int t0 = 0; t0 < n; t0 += 64) {
+    const int t = t0 + lane;
+    const int x = t < n ? a[t] : 0x7fffffff;
+    p0 += __popcll(__ballot(x < v0));
+    p1 += __popcll(__ballot(x < v1));
+    p2 += __popcll(__ballot(x < v2));
+  }
+  p0 = __builtin_amdgcn_readfirstlane(p0);      // the same in every lane: keep the loops over them scalar
+  p1 = __builtin_amdgcn_readfirstlane(p1);
+  p2 = __builtin_amdgcn_readfirstlane(p2);
+}
+
 // grid = (ceil(dim/256), rows, ceil(cols/16)).  Source rows whose distance alone puts them out of
-// reach are skipped whole (the table holds zeros there anyway).
+// reach are skipped whole, and of the others only the source nodes whose column can be within reach of
+// one of the tile's 16 destination columns are visited: at row distance a that is |dx| <=
+// (sqrt(4 r^2 - (4 or 3) a^2) + 1) / 2, a stretch of the row's ascending hit list (two stretches
+// where it wraps round a toroid map).  The table holds zeros for everything
+// skipped, so the sums are the same; on a 336-column map at r = 30 the stretch is a seventh of the row.
 template <bool kHex>
 __global__ __launch_bounds__(256) void k_smooth_direct(const float *__restrict__ S, float *__restrict__ W,
                                                        const float *__restrict__ H2,
@@ -727,25 +749,49 @@ __global__ __launch_bounds__(256) void k_smooth_direct(const float *__restrict__
     const int yb = hit_rows[r];
     int a = yi > yb ? yi - yb : yb - yi;
     const int a_wrapped = (toroid && rows - a < a) ? rows - a : a;
-    if (bounded && (double)((kHex ? 3ll : 4ll) * a_wrapped * a_wrapped) > reach) continue;
+    const double left = reach - (double)((kHex ? 3ll : 4ll) * a_wrapped * a_wrapped);
+    if (bounded && left < 0.0) continue;
     const int cls = kHex ? (yi & 1) - (yb & 1) + 1 : 0;
     const float *trow = H2 + ((int64_t)cls * rows + a) * width;
     const float *src = S + (int64_t)yb * cols * dim + (live ? c : 0);
     const int32_t *hx = hit_x + (int64_t)yb * cols;
     const int nh = hit_n[yb];
-    for (int t = 0; t < nh; t += kSmoothUnroll) {
-      int xb[kSmoothUnroll];
-      float s[kSmoothUnroll];
-#pragma unroll
-      for (int u = 0; u < kSmoothUnroll; ++u) {
-        xb[u] = hx[min(t + u, nh - 1)];
-        s[u] = (live && t + u < nh) ? src[(int64_t)xb[u] * dim] : 0.f;
+    // stretches [seg_lo[s], seg_hi[s]) of the hit list
+    int seg_lo[2] = {0, 0}, seg_hi[2] = {nh, 0};
+    if (bounded && nh >= 8) {
+      const int half = (int)(0.5 * sqrt(left)) + 2;        // |dx| of a node within reach is below this
+      if (2 * half + kSmoothTile < cols) {
+        int lo = xi0 - half, hi = xi0 + kSmoothTile - 1 + half;
+        if (toroid) {
+          const int span = hi - lo;                         // < cols - 1
+          lo %= cols;
+          if (lo < 0) lo += cols;
+          hi = lo + span;
+        }
+        int p_lo, p_hi, p_wrap;                             // hi >= cols (toroid only): lo .. cols - 1, then 0 .. hi - cols
+        first_not_below3(hx, nh, lane, lo, hi + 1, hi - cols + 1, p_lo, p_hi, p_wrap);
+        seg_lo[0] = p_lo;
+        seg_hi[0] = p_hi;
+        if (toroid && hi >= cols) seg_hi[1] = p_wrap;
       }
+    }
 #pragma unroll
-      for (int u = 0; u < kSmoothUnroll; ++u) {
-        const float *g = trow + direct_table_index(xi0, xb[u], cols, toroid);
+    for (int sgm = 0; sgm < 2; ++sgm) {
+      const int t_end = seg_hi[sgm];
+      for (int t = seg_lo[sgm]; t < t_end; t += kSmoothUnroll) {
+        int xb[kSmoothUnroll];
+        float s[kSmoothUnroll];
 #pragma unroll
-        for (int e = 0; e < kSmoothTile; ++e) acc[e] = fmaf(g[e], s[u], acc[e]);
+        for (int u = 0; u < kSmoothUnroll; ++u) {
+          xb[u] = hx[min(t + u, t_end - 1)];
+          s[u] = (live && t + u < t_end) ? src[(int64_t)xb[u] * dim] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < kSmoothUnroll; ++u) {
+          const float *g = trow + direct_table_index(xi0, xb[u], cols, toroid);
+#pragma unroll
+          for (int e = 0; e < kSmoothTile; ++e) acc[e] = fmaf(g[e], s[u], acc[e]);
+        }
       }
     }
   }

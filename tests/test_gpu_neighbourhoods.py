@@ -39,6 +39,35 @@ def test_update_matches_oracle(oracle, map_type, grid_type, name, compact, funct
         som.close()
 
 
+@pytest.mark.parametrize("map_type", ["planar", "toroid"])
+@pytest.mark.parametrize("grid_type", ["square", "hexagonal"])
+@pytest.mark.parametrize("name,compact,function", VARIANTS)
+def test_update_on_a_map_wider_than_the_neighbourhood(oracle, map_type, grid_type, name, compact, function):
+    """73 columns and radii of 1 to 13: the kernel visits only the stretch of each row's source nodes whose columns
+    can be within reach of its 16 destination columns, one that wraps round the seam on a toroid map (first and last
+    tiles), is cut at the border on a planar one, and widens to the whole row at the largest radius; sources are
+    sparse in some rows (stretches that are empty) and dense in others."""
+    from paper_1305_1422_amd import Som
+    rng = np.random.default_rng(37)
+    rows, cols, dim, n = 22, 73, 40, 2500
+    k = rows * cols
+    X = rng.standard_normal((n, dim)).astype(np.float32)
+    W = rng.random((k, dim)).astype(np.float32)
+    bmu = rng.integers(0, k, size=n).astype(np.int32)
+    y = bmu // cols
+    bmu[(y % 5 == 2) & (bmu % 11 != 0)] = 3                # rows with few sources, and one crowded node
+    S, C = oracle.accumulate_dense(X, bmu, k)
+    Xd, bd = P.to_dev(X), torch.from_numpy(bmu).cuda()
+    for radius in (1.0, 2.5, 6.0, 13.0, 30.0):
+        som = Som(rows, cols, dim, map_type, grid_type, codebook=torch.from_numpy(W))
+        som.set_neighborhood(name, compact)
+        som.update(Xd, bd, radius)
+        torch.cuda.synchronize()
+        kept, knife = P.check_codebook(oracle, S, C, W, som.codebook.cpu().numpy(), rows, cols, P.MAP[map_type],
+                                       P.GRID[grid_type], radius, function=function, compact=compact)
+        som.close()
+
+
 def test_bubble_below_one_is_kmeans_on_the_gpu(oracle):
     from paper_1305_1422_amd import Som
     rng = np.random.default_rng(32)
