@@ -75,7 +75,7 @@ def main() -> int:
                     help="arithmetic of the dense BMU filter pass (same BMUs either way)")
     ap.add_argument("--neighborhood", choices=["gaussian", "gaussian-compact", "bubble"], default="gaussian",
                     help="neighbourhood of the update (the stated configurations use the plain Gaussian)")
-    ap.add_argument("--smoothing", choices=["auto", "vector", "matrix"], default="auto",
+    ap.add_argument("--smoothing", choices=["auto", "vector", "matrix", "matrix_split"], default="auto",
                     help="units that run the Gaussian smoothing passes (same results)")
     ap.add_argument("--mode", choices=["epoch", "map"], default="epoch",
                     help="epoch (default): a step is one training epoch of the schedule.  map: the schedule is "

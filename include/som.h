@@ -44,7 +44,7 @@ enum { SOM_GRID_SQUARE = 0, SOM_GRID_HEXAGONAL = 1 };     /* option -g: square (
 enum { SOM_COOL_AS_RADIUS = -1, SOM_COOL_LINEAR = 0, SOM_COOL_EXPONENTIAL = 1 };   /* options -t / -T */
 enum { SOM_FILTER_FP32 = 0, SOM_FILTER_SPLIT_F16 = 1, SOM_FILTER_TWO_LEVEL = 2, SOM_FILTER_AUTO = 3 };   /* see som_set_filter */
 enum { SOM_NEIGHBORHOOD_GAUSSIAN = 0, SOM_NEIGHBORHOOD_BUBBLE = 1 };   /* option -n               */
-enum { SOM_SMOOTH_AUTO = 0, SOM_SMOOTH_VECTOR = 1, SOM_SMOOTH_MATRIX = 2 };   /* see som_set_smoothing   */
+enum { SOM_SMOOTH_AUTO = 0, SOM_SMOOTH_VECTOR = 1, SOM_SMOOTH_MATRIX = 2, SOM_SMOOTH_MATRIX_SPLIT = 3 };   /* see som_set_smoothing */
 
 /* Neighbourhood mass below which a node keeps its weights (see som_train_epoch_dense). */
 #define SOM_EPS_MASS 1e-20
@@ -321,9 +321,13 @@ int som_sparse_dense_filter_active(const som_ctx *ctx);
  * som_set_smoothing - which units run the two passes of the Gaussian neighbourhood smoothing (batch
  * equation; neighbourhood equation).  The result is the same up to the order of the fp32 additions.
  *   SOM_SMOOTH_AUTO (default)  a pass over map lines of at least 32 nodes runs as a matrix product on
- *                  the fp32 matrix cores, a shorter one on the vector units;
- *   SOM_SMOOTH_VECTOR  always the vector units;  SOM_SMOOTH_MATRIX  the matrix cores for any line length
- *                  (maps with a side above 1,024 nodes always use the vector units).
+ *                  the matrix cores, a shorter one on the vector units; from 96 nodes on the product
+ *                  runs on the bf16 matrix cores with every fp32 operand carried as three bf16 parts
+ *                  (six part products, fp32 accumulation: what is dropped is below 2^-23 of a term),
+ *                  below that on the fp32 ones;
+ *   SOM_SMOOTH_VECTOR  always the vector units;  SOM_SMOOTH_MATRIX  the fp32 matrix cores for any line
+ *                  length;  SOM_SMOOTH_MATRIX_SPLIT  the bf16 ones with three-part operands for any
+ *                  line length (maps with a side above 1,024 nodes always use the vector units).
  * Errors: unknown value -> SOM_ERR_INVALID_ARG.
  */
 int som_set_smoothing(som_ctx *ctx, int form);

@@ -20,7 +20,7 @@ SOM_GRID_SQUARE, SOM_GRID_HEXAGONAL = 0, 1
 SOM_COOL_AS_RADIUS, SOM_COOL_LINEAR, SOM_COOL_EXPONENTIAL = -1, 0, 1
 SOM_FILTER_FP32, SOM_FILTER_SPLIT_F16, SOM_FILTER_TWO_LEVEL, SOM_FILTER_AUTO = 0, 1, 2, 3
 SOM_NEIGHBORHOOD_GAUSSIAN, SOM_NEIGHBORHOOD_BUBBLE = 0, 1
-SOM_SMOOTH_AUTO, SOM_SMOOTH_VECTOR, SOM_SMOOTH_MATRIX = 0, 1, 2
+SOM_SMOOTH_AUTO, SOM_SMOOTH_VECTOR, SOM_SMOOTH_MATRIX, SOM_SMOOTH_MATRIX_SPLIT = 0, 1, 2, 3
 
 EXPORTS = [
     "som_init", "som_destroy", "som_last_error",

@@ -583,6 +583,229 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_smooth_mfma(const float *__
     }
 }
 
+// The same product on the bf16 matrix cores, which run sixteen times the fp32 ones' rate: every fp32
+// operand is carried as three bf16 parts, x = hi + mid + lo exactly up to 2^-25 |x| (each part is the
+// rounding of what the parts before it leave), and a product a b as the six part products of order down
+// to 2^-16: hi hi, hi mid, mid hi, mid mid, hi lo, lo hi.  What is dropped is below 2^-23 |a b|, the
+// accumulation is fp32 as before: the same arithmetic class as the fp32 instruction, at three eighths of
+// its matrix-pipe time (6 x 8 passes against 8 x 16 per 16 sources).  bf16 has the exponent range of
+// fp32, so no operand needs a scale (fp16 parts would: coefficients of far nodes reach 1e-20).
+// The parts are made once per workgroup and chunk, when the chunk goes into LDS: a thread fetches the
+// values of eight consecutive sources for one output (coefficients) or one channel (source rows) -
+// neighbouring lanes read neighbouring addresses - and writes their three times eight parts as three
+// 16-byte pieces, which is exactly what a lane of v_mfma_f32_32x32x16_bf16 takes as its A or B operand.
+// LDS rows of 32 bytes (16 sources); the two halves of a row swap places in every second group of
+// eight rows, which spreads the 16-byte reads of 16 lanes over all banks.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// Two values at a time: one packed conversion gives both bf16 parts, and their fp32 values are the two
+// halves of that word shifted into place.
+__device__ __forceinline__ uint32_t bf16_pair(float a, float b, float &a_back, float &b_back) {
+  const bf16x2 h = __builtin_convertvector(f32x2{a, b}, bf16x2);
+  const uint32_t u = __builtin_bit_cast(uint32_t, h);
+  a_back = __uint_as_float(u << 16);
+  b_back = __uint_as_float(u & 0xffff0000u);
+  return u;
+}
+
+__device__ __forceinline__ void split_bf16x3(const float (&v)[8], bf16x8 &hi, bf16x8 &mid, bf16x8 &lo) {
+  uint32_t h[4], m[4], l[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float a, b, c, d;
+    h[i] = bf16_pair(v[2 * i], v[2 * i + 1], a, b);
+    const float ra = v[2 * i] - a, rb = v[2 * i + 1] - b;       // exact
+    m[i] = bf16_pair(ra, rb, c, d);
+    float e, f;
+    l[i] = bf16_pair(ra - c, rb - d, e, f);
+  }
+  hi = __builtin_bit_cast(bf16x8, uint4{h[0], h[1], h[2], h[3]});
+  mid = __builtin_bit_cast(bf16x8, uint4{m[0], m[1], m[2], m[3]});
+  lo = __builtin_bit_cast(bf16x8, uint4{l[0], l[1], l[2], l[3]});
+}
+
+template <int MB, bool kPassY, bool kHex, int kWaves>
+__global__ __launch_bounds__(64 * kWaves) void k_smooth_mfma_split(const float *__restrict__ In, float *__restrict__ Out,
+                                                       const float *__restrict__ Gt,
+                                                       const int32_t *__restrict__ hit_x,
+                                                       const int32_t *__restrict__ hit_n,
+                                                       const int32_t *__restrict__ hit_rows,
+                                                       const double *__restrict__ massD, int rows, int cols,
+                                                       int dim, int g_pad, int groups) {
+  constexpr int kM = 32 * MB;                        // outputs per workgroup
+  constexpr int kMp = (kM + 63) / 64 * 64;           // ... rounded up to whole wavefronts of staging tasks
+  constexpr int kCh = 32 * kWaves;                   // channels per workgroup
+  constexpr int kThreads = 64 * kWaves;
+  constexpr int kGPer = (2 * kMp + kThreads - 1) / kThreads;      // coefficient staging tasks per thread
+  static_assert(kMfmaChunk == 16, "one matrix instruction takes 16 sources");
+  static_assert(kWaves >= 2 && 2 * kCh == kThreads, "one source staging task per thread, its half the same for a wavefront");
+  __shared__ __attribute__((aligned(16))) bf16x8 sG[2][3][kM][2];      // [stage][part][output][half of the 16 sources]
+  __shared__ __attribute__((aligned(16))) bf16x8 sB[2][3][kCh][2];     // [stage][part][channel][half]
+  __shared__ __attribute__((aligned(16))) int sSrc[kSmoothMatMax + kMfmaChunk];
+  __shared__ float sD[kM];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int cb0 = blockIdx.x * kCh;
+  const int c = cb0 + wave * 32 + l32;
+  const bool live = c < dim;
+  const int line = blockIdx.y;
+  const int part = blockIdx.z / groups;
+  const int m0 = (blockIdx.z - part * groups) * kM;
+  const int classes = kHex ? 2 : 1;
+
+  int ns;
+  const int32_t *src;
+  const float *G;
+  const float *in;
+  int64_t in_stride;
+  if (kPassY) {
+    ns = hit_rows[rows];
+    if (ns <= 0) return;
+    src = hit_rows;
+    G = Gt + (int64_t)part * rows * g_pad;
+    in = In + (kHex ? (int64_t)part * rows * cols * dim : 0) + (int64_t)line * dim;
+    in_stride = (int64_t)cols * dim;
+  } else {
+    ns = hit_n[line];
+    if (ns == 0) return;
+    src = hit_x + (int64_t)line * cols;
+    G = Gt + ((int64_t)(part * classes + (kHex ? (line & 1) : 0)) * cols) * g_pad;
+    in = In + (int64_t)line * cols * dim;
+    in_stride = dim;
+  }
+  for (int i = tid; i < ns + kMfmaChunk; i += kThreads) sSrc[i] = src[i < ns ? i : ns - 1];
+  __syncthreads();
+
+  // Staging tasks.  Source values: channel b_chl, the sources 8 b_half .. + 7 of the chunk (one task per thread).
+  // Coefficients: task g = tid + i kThreads is output g % kMp, sources 8 (g / kMp) .. + 7.  Either half is the same
+  // for a whole wavefront, so a source's row offset is a scalar and the loads need no per-lane address arithmetic.
+  const int b_half = __builtin_amdgcn_readfirstlane(tid / kCh);
+  const int b_chl = tid % kCh;
+  const float *b_lane = in + min(cb0 + b_chl, dim - 1);     // channels past dim repeat the last one; never stored
+  int g_half[kGPer], g_m[kGPer];
+  bool g_task[kGPer];
+  const float *g_lane[kGPer];
+#pragma unroll
+  for (int i = 0; i < kGPer; ++i) {
+    const int g = tid + i * kThreads;
+    g_half[i] = __builtin_amdgcn_readfirstlane(g / kMp);
+    g_m[i] = g % kMp;
+    g_task[i] = g_half[i] < 2 && g_m[i] < kM;
+    g_lane[i] = G + min(m0 + g_m[i], g_pad - 1);            // outputs past the padded row repeat its last one; never stored
+  }
+  float gval[kGPer][8], bval[8];
+  // the eight source indices of a task come out of LDS in two 16-byte reads (every lane the same address)
+  auto source_rows = [&](int first, int64_t (&row)[8]) {
+    const int4 lo4 = *reinterpret_cast<const int4 *>(&sSrc[first]), hi4 = *reinterpret_cast<const int4 *>(&sSrc[first + 4]);
+    row[0] = __builtin_amdgcn_readfirstlane(lo4.x); row[1] = __builtin_amdgcn_readfirstlane(lo4.y);
+    row[2] = __builtin_amdgcn_readfirstlane(lo4.z); row[3] = __builtin_amdgcn_readfirstlane(lo4.w);
+    row[4] = __builtin_amdgcn_readfirstlane(hi4.x); row[5] = __builtin_amdgcn_readfirstlane(hi4.y);
+    row[6] = __builtin_amdgcn_readfirstlane(hi4.z); row[7] = __builtin_amdgcn_readfirstlane(hi4.w);
+  };
+  auto fetch = [&](int t0) {
+    int64_t row[8];
+    source_rows(t0 + 8 * b_half, row);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) bval[u] = b_lane[row[u] * in_stride];
+#pragma unroll
+    for (int i = 0; i < kGPer; ++i)
+      if (g_task[i]) {
+        source_rows(t0 + 8 * (g_half[i] & 1), row);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) gval[i][u] = g_lane[i][row[u] * g_pad];
+      }
+  };
+  auto stash = [&](int stage, int t0) {
+    bf16x8 hi, mid, lo;
+#pragma unroll
+    for (int i = 0; i < kGPer; ++i)
+      if (g_task[i]) {
+        split_bf16x3(gval[i], hi, mid, lo);
+        const int h = g_half[i] ^ ((g_m[i] >> 3) & 1);
+        sG[stage][0][g_m[i]][h] = hi;
+        sG[stage][1][g_m[i]][h] = mid;
+        sG[stage][2][g_m[i]][h] = lo;
+      }
+    float bz[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) bz[u] = t0 + 8 * b_half + u < ns ? bval[u] : 0.f;     // sources past the end count as zero
+    split_bf16x3(bz, hi, mid, lo);
+    const int h = b_half ^ ((b_chl >> 3) & 1);
+    sB[stage][0][b_chl][h] = hi;
+    sB[stage][1][b_chl][h] = mid;
+    sB[stage][2][b_chl][h] = lo;
+  };
+
+  f32x16 acc[MB];
+#pragma unroll
+  for (int b = 0; b < MB; ++b)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
+
+  // The loads of the next chunk are issued before this chunk's matrix instructions and used after them.  (Loads
+  // of two or three chunks ahead, in more register buffers, measured slower: 6.7 against 6.1 ms for both passes on
+  // a 336 x 205 map of 12,347 features - the passes are bound by how the memory system takes these visits of
+  // rows a map line apart, and more of them in flight at once only scatter them further.)
+  fetch(0);
+  stash(0, 0);
+  __syncthreads();
+  int stage = 0;
+  const int b_row = wave * 32 + l32;
+  const int b_sel = lhi ^ ((b_row >> 3) & 1);
+  for (int t0 = 0; t0 < ns; t0 += kMfmaChunk) {
+    const bool more = t0 + kMfmaChunk < ns;
+    if (more) fetch(t0 + kMfmaChunk);
+    const bf16x8 bh = sB[stage][0][b_row][b_sel], bm = sB[stage][1][b_row][b_sel], bl = sB[stage][2][b_row][b_sel];
+#pragma unroll
+    for (int b = 0; b < MB; ++b) {
+      const int a_row = 32 * b + l32;
+      const int a_sel = lhi ^ ((a_row >> 3) & 1);
+      const bf16x8 ah = sG[stage][0][a_row][a_sel], am = sG[stage][1][a_row][a_sel], al = sG[stage][2][a_row][a_sel];
+      // the small products first
+      acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, acc[b], 0, 0, 0);
+      acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, acc[b], 0, 0, 0);
+      acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bm, acc[b], 0, 0, 0);
+      acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bh, acc[b], 0, 0, 0);
+      acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bm, acc[b], 0, 0, 0);
+      acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc[b], 0, 0, 0);
+    }
+    if (more) stash(stage ^ 1, t0 + kMfmaChunk);     // that stage was last read before the previous barrier
+    __syncthreads();
+    stage ^= 1;
+  }
+
+  const int mtot = kPassY ? (rows - part + classes - 1) / classes : cols;
+  if (kPassY) {
+    for (int ml = tid; ml < kM; ml += kThreads) {
+      const int m = m0 + ml;
+      double D = 0.0;
+      if (m < mtot) D = massD[(int64_t)(classes * m + part) * cols + line];
+      sD[ml] = D >= SOM_EPS_MASS ? (float)D : 0.f;
+    }
+    __syncthreads();
+  }
+  if (!live) return;
+#pragma unroll
+  for (int b = 0; b < MB; ++b)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int ml = 32 * b + 8 * (v >> 2) + 4 * lhi + (v & 3);
+      const int m = m0 + ml;
+      if (m >= mtot) continue;
+      if (kPassY) {
+        const float D = sD[ml];
+        if (D > 0.f) Out[((int64_t)(classes * m + part) * cols + line) * dim + c] = acc[b][v] / D;
+      } else {
+        Out[(((int64_t)part * rows + line) * cols + m) * (int64_t)dim + c] = acc[b][v];
+      }
+    }
+}
+
 // Blocks of 32 outputs per wavefront and groups of such wavefront tiles for a line of `outputs` outputs.
 static void mfma_tiling(int outputs, int *mb, int *groups) {
   const int nb = (outputs + 31) / 32;
@@ -590,17 +813,25 @@ static void mfma_tiling(int outputs, int *mb, int *groups) {
   *mb = (nb + *groups - 1) / *groups;
 }
 
+constexpr int kSplitWaves = 8;      // wavefronts of a k_smooth_mfma_split workgroup
+
+
 template <bool kPassY, bool kHex>
 static void launch_smooth_mfma(som_ctx *c, const float *In, float *Out, const float *Gt, int g_pad, int outputs,
-                               int lines, int parts) {
+                               int lines, int parts, bool split) {
   int mb, groups;
   mfma_tiling(outputs, &mb, &groups);
   const dim3 grid((unsigned)((c->dim + 32 * kMfmaWaves - 1) / (32 * kMfmaWaves)), (unsigned)lines, (unsigned)(parts * groups));
+  const dim3 split_grid((unsigned)((c->dim + 32 * kSplitWaves - 1) / (32 * kSplitWaves)), (unsigned)lines, (unsigned)(parts * groups));
   // 16-byte loads of the source rows need rows that start and stay on 16-byte boundaries
   const bool vec4 = c->dim % 4 == 0 && c->dim >= 4 && (reinterpret_cast<uintptr_t>(In) & 15) == 0;
 #define SOM_SMOOTH_MFMA(B)                                                                                          \
   do {                                                                                                              \
-    if (vec4)                                                                                                       \
+    if (split)                                                                                                      \
+      hipLaunchKernelGGL((k_smooth_mfma_split<B, kPassY, kHex, kSplitWaves>), split_grid, dim3(64 * kSplitWaves), 0, \
+                         c->stream, In, Out, Gt, c->hit_x, c->hit_n, c->hit_rows, c->massD, c->rows, c->cols, c->dim, \
+                         g_pad, groups);                                                                            \
+    else if (vec4)                                                                                                  \
       hipLaunchKernelGGL((k_smooth_mfma<B, kPassY, kHex, true>), grid, dim3(64 * kMfmaWaves), 0, c->stream, In, Out, \
                          Gt, c->hit_x, c->hit_n, c->hit_rows, c->massD, c->rows, c->cols, c->dim, g_pad, groups);    \
     else                                                                                                            \
@@ -865,18 +1096,21 @@ hipError_t launch_smooth_and_divide(som_ctx *c, float *W) {
     // a pass runs on the matrix cores when its line is long enough to fill their 32-output blocks
     const bool mfma_x = c->smooth_mfma_min > 0 && c->cols >= c->smooth_mfma_min;
     const bool mfma_y = c->smooth_mfma_min > 0 && c->rows >= c->smooth_mfma_min;
+    // ... and on the bf16 ones, operands in three parts, when the line is long enough for the matrix pipe to be the limit
+    const bool split_x = mfma_x && c->smooth_split_min > 0 && c->cols >= c->smooth_split_min;
+    const bool split_y = mfma_y && c->smooth_split_min > 0 && c->rows >= c->smooth_split_min;
     if (hex) {
-      if (mfma_x) launch_smooth_mfma<false, true>(c, c->S, c->T, c->GxT, c->xi_pad, c->cols, c->rows, 2);
+      if (mfma_x) launch_smooth_mfma<false, true>(c, c->S, c->T, c->GxT, c->xi_pad, c->cols, c->rows, 2, split_x);
       else hipLaunchKernelGGL(k_smooth_x_mat<true>, gx, dim3(256), 0, c->stream, c->S, c->T, c->GxT,
                               c->hit_x, c->hit_n, c->rows, c->cols, c->dim, c->xi_pad);
-      if (mfma_y) launch_smooth_mfma<true, true>(c, c->T, W, c->GyT, c->e_pad, (c->rows + 1) / 2, c->cols, 2);
+      if (mfma_y) launch_smooth_mfma<true, true>(c, c->T, W, c->GyT, c->e_pad, (c->rows + 1) / 2, c->cols, 2, split_y);
       else hipLaunchKernelGGL(k_smooth_y_mat<true>, gy, dim3(256), 0, c->stream, c->T, W, c->GyT,
                               c->hit_rows, c->massD, c->rows, c->cols, c->dim, c->e_pad);
     } else {
-      if (mfma_x) launch_smooth_mfma<false, false>(c, c->S, c->T, c->GxT, c->xi_pad, c->cols, c->rows, 1);
+      if (mfma_x) launch_smooth_mfma<false, false>(c, c->S, c->T, c->GxT, c->xi_pad, c->cols, c->rows, 1, split_x);
       else hipLaunchKernelGGL(k_smooth_x_mat<false>, gx, dim3(256), 0, c->stream, c->S, c->T, c->GxT,
                               c->hit_x, c->hit_n, c->rows, c->cols, c->dim, c->xi_pad);
-      if (mfma_y) launch_smooth_mfma<true, false>(c, c->T, W, c->GyT, c->e_pad, c->rows, c->cols, 1);
+      if (mfma_y) launch_smooth_mfma<true, false>(c, c->T, W, c->GyT, c->e_pad, c->rows, c->cols, 1, split_y);
       else hipLaunchKernelGGL(k_smooth_y_mat<false>, gy, dim3(256), 0, c->stream, c->T, W, c->GyT,
                               c->hit_rows, c->massD, c->rows, c->cols, c->dim, c->e_pad);
     }

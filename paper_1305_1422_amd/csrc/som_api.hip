@@ -663,6 +663,7 @@ int som_init(som_ctx **out, int rows, int cols, int dim, int map_type, int grid_
   c->hot_enabled = 1;
   c->csrd_enabled = 1;
   c->smooth_mfma_min = kSmoothMfmaMin;
+  c->smooth_split_min = kSmoothSplitMin;
 
   int dev = 0;
   hipDeviceProp_t prop;
@@ -1053,9 +1054,10 @@ int som_sparse_dense_filter_active(const som_ctx *c) { return c && c->csrd_valid
 
 int som_set_smoothing(som_ctx *c, int form) {
   if (!c) return SOM_ERR_INVALID_ARG;
-  if (form != SOM_SMOOTH_AUTO && form != SOM_SMOOTH_VECTOR && form != SOM_SMOOTH_MATRIX)
+  if (form != SOM_SMOOTH_AUTO && form != SOM_SMOOTH_VECTOR && form != SOM_SMOOTH_MATRIX && form != SOM_SMOOTH_MATRIX_SPLIT)
     return fail(c, SOM_ERR_INVALID_ARG, "unknown smoothing form %d", form);
   c->smooth_mfma_min = form == SOM_SMOOTH_AUTO ? kSmoothMfmaMin : (form == SOM_SMOOTH_VECTOR ? 0 : 1);
+  c->smooth_split_min = form == SOM_SMOOTH_AUTO ? kSmoothSplitMin : (form == SOM_SMOOTH_MATRIX_SPLIT ? 1 : 0);
   return SOM_OK;
 }
 

@@ -18,6 +18,7 @@ constexpr int kChunkRows = 32;            // instances summed by one block of th
 constexpr int kSortTile = 1024;           // fewest keys ranked by one wave of the radix scatter
 constexpr int kSmoothMatMax = 1024;        // largest map side for which the smoothing filters are stored as matrices
 constexpr int kSmoothMfmaMin = 32;         // shortest map line whose smoothing pass runs on the matrix cores by default
+constexpr int kSmoothSplitMin = 96;        // ... and on the bf16 ones with three-part operands
 constexpr int kCsrDenseMaxDim = 4096;      // registered sparse sets up to this many columns may be searched through dense planes
 constexpr double kCsrDenseMinDensity = 0.04;   // ... if at least this share of their entries is nonzero
 constexpr int kHot = 256;                  // columns of the dense hot block of a registered sparse training set
@@ -71,6 +72,7 @@ struct som_ctx {
   float *GxT, *GyT;       // the two filters as transposed coefficient matrices (maps with sides <= kSmoothMatMax)
   int xi_pad, e_pad;      // padded output extents of GxT / GyT (multiples of 32)
   int smooth_mfma_min;    // a smoothing pass over lines of at least this many nodes runs on the matrix cores (0: never)
+  int smooth_split_min;   // ... and from this many nodes on with bf16 operands in three parts (0: never)
   int32_t *hit_x, *hit_n; // [k] columns of the chosen nodes per map row, [rows] their number
   int32_t *hit_rows;      // [rows+1] map rows with chosen nodes, last entry = their number
   int nb_function;        // SOM_NEIGHBORHOOD_*

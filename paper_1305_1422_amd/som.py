@@ -80,7 +80,7 @@ class Som:
     def set_smoothing(self, form: str) -> None:
         """Units that run the Gaussian smoothing passes: "auto" (default), "vector" or "matrix"; same results."""
         capi.som_set_smoothing(self.ctx, {"auto": capi.SOM_SMOOTH_AUTO, "vector": capi.SOM_SMOOTH_VECTOR,
-                                          "matrix": capi.SOM_SMOOTH_MATRIX}[form])
+                                          "matrix": capi.SOM_SMOOTH_MATRIX, "matrix_split": capi.SOM_SMOOTH_MATRIX_SPLIT}[form])
 
     def set_filter(self, filter: str) -> None:
         """Arithmetic of the dense BMU filter pass: "split_f16" (default) or "fp32"; same results."""
