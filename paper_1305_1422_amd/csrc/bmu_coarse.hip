@@ -108,6 +108,10 @@ __global__ __launch_bounds__(kCThreads, 1) void k_bmu_coarse(const float *__rest
   const unsigned lds_w = lds_address_c(&sW[0][1024 * wave]);     // 4 slots of 256 floats
   const unsigned lds_x = lds_address_c(&sX[0][1024 * wave]);
   const unsigned lds_wn = lds_address_c(&sWn[0][0]);
+  // Up to 128 features the whole instance tile fits the two X stages: it is loaded once, with the first node tile,
+  // and only the node tiles stream (half the traffic from L2 into LDS, which is what bounds the pass at so few
+  // features per tile).
+  const bool x_stays = nK <= 2;
   int ld_nb = nb_first, ld_kc = 0;
   auto issue_loads = [&](int buf) {
     const char *wbase = reinterpret_cast<const char *>(Wh) + (int64_t)ld_nb * kCTN * row_bytes;
@@ -125,8 +129,13 @@ __global__ __launch_bounds__(kCThreads, 1) void k_bmu_coarse(const float *__rest
     const unsigned off = (unsigned)ld_kc * (kCRow * 4);
 #pragma unroll
     for (int i = 0; i < 4; ++i) load16_to_lds_c(wbase + off, woff[i], lds_w + buf * (kCTN * kCRow * 4) + i * 1024);
+    if (!x_stays) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) load16_to_lds_c(xbase + off, xoff[i], lds_x + buf * (kCTI * kCRow * 4) + i * 1024);
+      for (int i = 0; i < 4; ++i) load16_to_lds_c(xbase + off, xoff[i], lds_x + buf * (kCTI * kCRow * 4) + i * 1024);
+    } else if (ld_nb == nb_first) {                               // chunk kc of the instance tile lives in sX[kc]
+#pragma unroll
+      for (int i = 0; i < 4; ++i) load16_to_lds_c(xbase + off, xoff[i], lds_x + ld_kc * (kCTI * kCRow * 4) + i * 1024);
+    }
     if (++ld_kc == nK) { ld_kc = 0; ++ld_nb; }
   };
 
@@ -149,9 +158,9 @@ __global__ __launch_bounds__(kCThreads, 1) void k_bmu_coarse(const float *__rest
   f32x16 acc[4][2];
   // Operands of two k-steps (ks and ks + 2 of the chunk's four): 12 LDS reads of 16 bytes for 16 MFMAs.
   struct Operands { f16x8 g1[4], g2[4], h1[2], h2[2]; };
-  auto read_operands = [&](Operands &o, int st, int ks) {
+  auto read_operands = [&](Operands &o, int st, int xst, int ks) {
     const float *pw = &sW[st][a_base];
-    const float *px = &sX[st][b_base];
+    const float *px = &sX[xst][b_base];
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
       o.g1[b] = as_halves_c(*reinterpret_cast<const f32x4 *>(pw + b * 32 * kCRow + rd_off[ks]));
@@ -200,8 +209,9 @@ __global__ __launch_bounds__(kCThreads, 1) void k_bmu_coarse(const float *__rest
   for (int t = 0; t < total; ++t) {
     const int ord = t / nK, kc = t % nK;         // ordinal of the node tile in this workgroup's run
     if (t + 1 < total) issue_loads(stage ^ 1);   // that stage held chunk t - 1, which every wavefront has left
-    read_operands(op0, stage, 0);
-    read_operands(op1, stage, 1);
+    const int xstage = x_stays ? kc : stage;
+    read_operands(op0, stage, xstage, 0);
+    read_operands(op1, stage, xstage, 1);
     multiply(op0, fresh);
     multiply(op1, false);
     fresh = (kc == nK - 1);
