@@ -106,31 +106,34 @@ __global__ __launch_bounds__(1024) void k_scan_exclusive(const int32_t *in, int3
 }
 
 // ---------------------------------------------------------------- stable radix sort
-__global__ __launch_bounds__(256) void k_radix_hist(const int32_t *__restrict__ keys, int64_t n, int shift,
+// Digits of `bits` bits (at most 8) at `shift`; hist[digit][tile].
+__global__ __launch_bounds__(256) void k_radix_hist(const int32_t *__restrict__ keys, int64_t n, int shift, int bits,
                                                     int nblk, int tile, int k, int32_t *__restrict__ hist) {
   __shared__ int s_hist[256];
+  const int mask = (1 << bits) - 1;
   s_hist[threadIdx.x] = 0;
   __syncthreads();
   const int64_t base = (int64_t)blockIdx.x * tile;
   for (int e = threadIdx.x; e < tile; e += 256) {
     const int64_t j = base + e;
-    if (j < n) atomicAdd(&s_hist[(clamp_node(keys[j], k) >> shift) & 255], 1);
+    if (j < n) atomicAdd(&s_hist[(clamp_node(keys[j], k) >> shift) & mask], 1);
   }
   __syncthreads();
-  hist[(int64_t)threadIdx.x * nblk + blockIdx.x] = s_hist[threadIdx.x];
+  if ((int)threadIdx.x <= mask) hist[(int64_t)threadIdx.x * nblk + blockIdx.x] = s_hist[threadIdx.x];
 }
 
 // One wavefront ranks its tile 64 keys at a time, in order: a key's position is the running
-// count of its digit plus the number of lower lanes holding the same digit (eight ballots).
+// count of its digit plus the number of lower lanes holding the same digit (a ballot per digit bit).
 __global__ __launch_bounds__(64) void k_radix_scatter(const int32_t *__restrict__ keys_in,
                                                       const int32_t *__restrict__ vals_in,
                                                       int32_t *__restrict__ keys_out,
-                                                      int32_t *__restrict__ vals_out, int64_t n, int shift,
+                                                      int32_t *__restrict__ vals_out, int64_t n, int shift, int bits,
                                                       int nblk, int tile, int k,
                                                       const int32_t *__restrict__ hist_scanned) {
   __shared__ int s_cnt[256];
   const int lane = threadIdx.x;
-  for (int d = lane; d < 256; d += 64) s_cnt[d] = hist_scanned[(int64_t)d * nblk + blockIdx.x];
+  const int mask = (1 << bits) - 1;
+  for (int d = lane; d <= mask; d += 64) s_cnt[d] = hist_scanned[(int64_t)d * nblk + blockIdx.x];
   __syncthreads();
   const int64_t base = (int64_t)blockIdx.x * tile;
   for (int step = 0; step < tile / 64; ++step) {
@@ -138,13 +141,15 @@ __global__ __launch_bounds__(64) void k_radix_scatter(const int32_t *__restrict_
     const bool valid = j < n;
     const int key = valid ? clamp_node(keys_in[j], k) : 0;
     const int val = valid ? (vals_in ? vals_in[j] : (int32_t)j) : 0;
-    const int d = (key >> shift) & 255;
+    const int d = (key >> shift) & mask;
     unsigned long long same = __ballot(valid);
 #pragma unroll
     for (int b = 0; b < 8; ++b) {
-      const bool bit = (d >> b) & 1;
-      const unsigned long long bal = __ballot(bit);
-      same &= bit ? bal : ~bal;
+      if (b < bits) {                              // uniform
+        const bool bit = (d >> b) & 1;
+        const unsigned long long bal = __ballot(bit);
+        same &= bit ? bal : ~bal;
+      }
     }
     const int rank = __popcll(same & ((1ull << lane) - 1ull));
     const int before = valid ? s_cnt[d] : 0;
@@ -411,33 +416,23 @@ __global__ __launch_bounds__(256) void k_scatter_csr(const int64_t *__restrict__
   }
 }
 
-static int radix_passes(int k) {
-  int bits = 1;
-  while ((1ll << bits) < (long long)k) ++bits;
-  return (bits + 7) / 8;
-}
-
 // Stable permutation of the ids 0 .. n - 1 by integer keys in [0, key_range) (larger keys are clamped).
 // On return c->sort_val[0] holds the permutation, c->sort_key[0] the sorted keys.
 hipError_t launch_sort_keys(som_ctx *c, const int32_t *bmus, int64_t n, int key_range) {
-  // Keys per wavefront of the scatter: small tiles give more parallelism, but the histogram of
-  // 256 counters per tile is scanned by one workgroup, so their number is kept near 256.
-  int64_t tile64 = ((n + 255) / 256 + 63) / 64 * 64;
-  if (tile64 < kSortTile) tile64 = kSortTile;
-  const int tile = (int)tile64;
-  const int nblk = (int)((n + tile - 1) / tile);
-  const int passes = radix_passes(key_range);
+  const RadixPlan plan = radix_plan(n, key_range);
+  const int bins = 1 << plan.digit_bits;
   const int32_t *kin = bmus;
   const int32_t *vin = nullptr;
   // an even number of hops ends in buffer 0: start in buffer 1 when the pass count is even
-  int dst = (passes % 2 == 0) ? 1 : 0;
-  for (int p = 0; p < passes; ++p) {
-    hipLaunchKernelGGL(k_radix_hist, dim3(nblk), dim3(256), 0, c->stream, kin, n, 8 * p, nblk, tile, key_range,
-                       c->radix_hist);
+  int dst = (plan.passes % 2 == 0) ? 1 : 0;
+  for (int p = 0; p < plan.passes; ++p) {
+    hipLaunchKernelGGL(k_radix_hist, dim3(plan.nblk), dim3(256), 0, c->stream, kin, n, plan.digit_bits * p,
+                       plan.digit_bits, plan.nblk, plan.tile, key_range, c->radix_hist);
     hipLaunchKernelGGL(k_scan_exclusive, dim3(1), dim3(1024), 0, c->stream, c->radix_hist, c->radix_hist,
-                       256 * nblk, 0);
-    hipLaunchKernelGGL(k_radix_scatter, dim3(nblk), dim3(64), 0, c->stream, kin, vin, c->sort_key[dst],
-                       c->sort_val[dst], n, 8 * p, nblk, tile, key_range, c->radix_hist);
+                       bins * plan.nblk, 0);
+    hipLaunchKernelGGL(k_radix_scatter, dim3(plan.nblk), dim3(64), 0, c->stream, kin, vin, c->sort_key[dst],
+                       c->sort_val[dst], n, plan.digit_bits * p, plan.digit_bits, plan.nblk, plan.tile, key_range,
+                       c->radix_hist);
     kin = c->sort_key[dst];
     vin = c->sort_val[dst];
     dst ^= 1;

@@ -133,13 +133,12 @@ static int ensure_rows(som_ctx *c, int64_t n, bool dense) {
     (void)hipStreamSynchronize(c->stream);
     free_row_scratch(c);
     const size_t N = (size_t)n;
-    const size_t nblk = (N + kSortTile - 1) / kSortTile;
     bool ok = dev_alloc(&c->xn32, N) && dev_alloc(&c->row_q, N) && dev_alloc(&c->cand_val, N * kCand) && dev_alloc(&c->cand_idx, N * kCand) &&
               dev_alloc(&c->cand_over, N) && dev_alloc(&c->cand_n, N) && dev_alloc(&c->refine_list, N) &&
               dev_alloc(&c->rescan_list, N) && dev_alloc(&c->collect_rows, N) && dev_alloc(&c->collect_thr, N) &&
               dev_alloc(&c->collect_cnt, N) && dev_alloc(&c->sort_key[0], N) && dev_alloc(&c->sort_key[1], N) &&
               dev_alloc(&c->sort_val[0], N) && dev_alloc(&c->sort_val[1], N) &&
-              dev_alloc(&c->radix_hist, 256 * nblk + 1);
+              dev_alloc(&c->radix_hist, radix_table_entries(n));
     c->max_chunks = (int64_t)(N / kChunkRows) + c->k;
     ok = ok && dev_alloc(&c->chunk_node, (size_t)c->max_chunks);
     if (!ok) {

@@ -15,7 +15,47 @@ constexpr int kWave = 64;                 // CDNA wavefront width
 constexpr int kCand = 4;                  // candidate nodes kept per instance by the fp32 pass
 constexpr int kListCap = 256;             // nodes a collected candidate list can hold per instance
 constexpr int kChunkRows = 32;            // instances summed by one block of the segmented accumulation
-constexpr int kSortTile = 1024;           // fewest keys ranked by one wave of the radix scatter
+// Stable radix sort of n keys below key_range (segsum.hip): passes of at most 8 bits, the bits spread evenly over
+// the passes (12 bits: two passes of 6, not 8 + 4 - the table of digit counts per tile, which one workgroup has to
+// scan, shrinks with the digit), and tiles of `tile` keys, one wavefront each.  The scan takes a step per 4,096
+// table entries, the scatter a step per 64 keys of a tile, and the two cost about the same per step: the number
+// of tiles that balances them is 8 sqrt(n / bins).
+struct RadixPlan {
+  int passes, digit_bits, tile, nblk;
+};
+inline RadixPlan radix_plan_for_digits(int64_t n, int passes, int digit_bits) {
+  RadixPlan p;
+  p.passes = passes;
+  p.digit_bits = digit_bits;
+  const double bins = (double)(1 << digit_bits);
+  int64_t want = (int64_t)(8.0 * __builtin_sqrt((double)(n < 1 ? 1 : n) / bins));
+  if (want < 64) want = 64;
+  int64_t tile = ((n + want - 1) / want + 63) / 64 * 64;
+  if (tile < 64) tile = 64;
+  p.tile = (int)tile;
+  p.nblk = (int)((n + tile - 1) / tile);
+  if (p.nblk < 1) p.nblk = 1;
+  return p;
+}
+inline RadixPlan radix_plan(int64_t n, int key_range) {
+  int bits = 1;
+  while ((1ll << bits) < (long long)key_range) ++bits;
+  const int passes = (bits + 7) / 8;
+  return radix_plan_for_digits(n, passes, (bits + passes - 1) / passes);
+}
+// Entries of the digit-count table that serve any number of keys up to n and any key range: a plan never has
+// more tiles than the number it aims for (at least 64), and that number grows with the key count.
+inline size_t radix_table_entries(int64_t n) {
+  size_t most = 0;
+  for (int db = 1; db <= 8; ++db) {
+    const double bins = (double)(1 << db);
+    double want = 8.0 * __builtin_sqrt((double)(n < 1 ? 1 : n) / bins);
+    if (want < 64.0) want = 64.0;
+    const size_t e = ((size_t)1 << db) * ((size_t)want + 2);
+    if (e > most) most = e;
+  }
+  return most + 1;
+}
 constexpr int kSmoothMatMax = 1024;        // largest map side for which the smoothing filters are stored as matrices
 constexpr int kSmoothMfmaMin = 32;         // shortest map line whose smoothing pass runs on the matrix cores by default
 constexpr int kSmoothSplitMin = 96;        // ... and on the bf16 ones with three-part operands
@@ -138,7 +178,7 @@ struct som_ctx {
   int64_t unit_cap;
   int32_t *sort_key[2];   // [n] each
   int32_t *sort_val[2];   // [n] each
-  int32_t *radix_hist;    // [256 * sort blocks]
+  int32_t *radix_hist;    // [bins * sort tiles], radix_table_entries(n_cap)
   int32_t *chunk_node;    // [n/kChunkRows + k]
   float *partial;         // [n/kChunkRows + k][dim]
   int64_t max_chunks;
