@@ -30,15 +30,15 @@ PEAK_HBM_GBS = 8000.0
 # (FETCH_SIZE, WRITE_SIZE, scaled by the copy calibration) summarised in profiles/epoch_config*.md;
 # measured once per kernel version, not during this run (the dense figures vary by some ten percent from
 # run to run: they depend on how long the workgroups that share an instance tile stay in step).
-MEASURED_TRAFFIC_BYTES = {(2, "two_level"): 1.389e9 + 0.034e9, (3, "two_level"): 2.904e9 + 0.094e9,
-                          (5, "two_level"): 10.027e9 + 0.424e9,
-                          (6, "two_level"): 2.989e9 + 0.035e9,      # sparse rows searched through dense planes
+MEASURED_TRAFFIC_BYTES = {(2, "two_level"): 1.388e9 + 0.034e9, (3, "two_level"): 2.906e9 + 0.094e9,
+                          (5, "two_level"): 4.446e9 + 0.424e9,
+                          (6, "two_level"): 2.977e9 + 0.035e9,      # sparse rows searched through dense planes
                           # one-level split-fp16 filter and fp32 filter (earlier counter runs; those kernels are unchanged)
                           (2, "split_f16"): 3.841e9 + 0.036e9, (2, "fp32"): 8.49e9 + 0.025e9,
                           (3, "split_f16"): 14.283e9 + 0.025e9, (5, "split_f16"): 13.917e9 + 0.072e9,
                           # sparse: all kernels of the filter stage (code-book pass, hot-column block, sweep)
-                          (4, "sparse"): 16.395e9 + 1.453e9, (6, "sparse"): 0.415e9 + 0.058e9,
-                          (7, "sparse"): 87.540e9 + 6.474e9}
+                          (4, "sparse"): 16.393e9 + 1.453e9, (6, "sparse"): 0.415e9 + 0.058e9,
+                          (7, "sparse"): 87.465e9 + 6.475e9}
 PEAK_FP32_VALU_TFLOPS = 157.3
 
 
