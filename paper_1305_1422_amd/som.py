@@ -78,7 +78,8 @@ class Som:
         capi.som_set_sparse_dense_filter(self.ctx, enable)
 
     def set_smoothing(self, form: str) -> None:
-        """Units that run the Gaussian smoothing passes: "auto" (default), "vector" or "matrix"; same results."""
+        """Units that run the Gaussian smoothing passes: "auto" (default), "vector", "matrix" (fp32 matrix instructions)
+        or "matrix_split" (bf16 matrix instructions, operands in three parts); same results to fp32 rounding."""
         capi.som_set_smoothing(self.ctx, {"auto": capi.SOM_SMOOTH_AUTO, "vector": capi.SOM_SMOOTH_VECTOR,
                                           "matrix": capi.SOM_SMOOTH_MATRIX, "matrix_split": capi.SOM_SMOOTH_MATRIX_SPLIT}[form])
 
