@@ -748,7 +748,7 @@ __global__ __launch_bounds__(64 * kWaves) void k_smooth_mfma_split(const float *
     for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
 
   // The loads of the next chunk are issued before this chunk's matrix instructions and used after them.  (Loads
-  // of two or three chunks ahead, in more register buffers, measured slower: 6.7 against 6.1 ms for both passes on
+  // of two or three chunks ahead, in more register buffers, measured slower: 6.2 and 6.7 against 6.1 ms for both passes on
   // a 336 x 205 map of 20,000 features - the passes are bound by how the memory system takes these visits of
   // rows a map line apart, and more of them in flight at once only scatter them further.)
   fetch(0);
